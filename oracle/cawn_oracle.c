@@ -1,0 +1,388 @@
+/*
+ * CAWN Resonance-Layer hot path -- reference oracle.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain fp64 statement of what the
+ * path computes.  Only the test-suite, the smoke check and the benchmark's CPU-baseline
+ * leg may build or call it; the GPU library shares no code, header, table or constant
+ * with it and never calls it.
+ *
+ * What is computed (paper sections):
+ *   - Temporal Syntax Cache (Sec. 3.2): causal depth-wise conv over time, hard clamp,
+ *     SiLU.
+ *   - Gated phasor push (Sec. 3.3 hard-threshold gate with straight-through estimator;
+ *     Sec. 3.4 gated-push equations): p = g * a * (cos phi, sin phi).
+ *   - Causal phase accumulation (Sec. 3.4 accumulation equations, real form):
+ *       S_r[t] = p_r[t] + gamma (S_r[t-1] cos th - S_i[t-1] sin th)
+ *       S_i[t] = p_i[t] + gamma (S_r[t-1] sin th + S_i[t-1] cos th),  S[-1] = state_in or 0.
+ *   - Output clamp (Sec. 3.4 clamp equation), Concat layout (Sec. 3.5).
+ *   - State passing (Sec. 3.7 / Sec. 5 chunked prefill): the phase state plus the last
+ *     conv_k-1 pre-conv rows.
+ *   - Backward (Sec. 3.4 last paragraph, Sec. 3.5): reverse-time adjoint; clamp passes the
+ *     gradient; returned per-element gradients clamped.
+ *
+ * Readings taken where the paper is silent (each is also listed in the design notes):
+ *   - conv is a cross-correlation, last tap on the current token, optional bias;
+ *   - the gate thresholds the per-lane amplitude |a| >= tau (keep when >=);
+ *   - the output clamp is NOT fed back into the recurrence unless clamp_feedback=1
+ *     (forward only, for quantifying the difference);
+ *   - the gate DECISION is taken in fp32 (the kernel's precision): with the conv
+ *     front-end the fp32 pre-activation z32 = fmaf-chain(bias, taps in order) is formed,
+ *     and the decision is |A(SiLU(clamp(z32)))| >= tau evaluated in fp64 on that fp32
+ *     value; without the conv it is evaluated on the fp32 input itself.  Everything else
+ *     is fp64;
+ *   - grad clamp applies to the returned per-element dp (= adjoint G_t) before the chain
+ *     to d(amplitude), d(phase), and to each per-(b,t) term of dgamma / dtheta before the
+ *     sum; the carried adjoint is not clamped.
+ *
+ * All arrays are dense, lane index j = h*F + k fastest.  Inputs are the same fp32 arrays the
+ * GPU receives, widened to double.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+    int32_t B, L, H, F;
+    int32_t conv_k;          /* 0 = no conv front-end: inputs are already magnitude/angle */
+    int32_t amp_mode;        /* 0: a = m;  1: a = min(softplus(m), 10) (Sec. 3.3 item 1)   */
+    int32_t clamp_feedback;  /* 0: clamp only what is emitted; 1: carry the clamped value  */
+    int32_t nthreads;        /* <=0: leave the OpenMP default                              */
+    float gate_tau;          /* threshold, same fp32 value the GPU gets; 0 = open           */
+    float pad_;
+    double conv_clamp;       /* 50 in the paper; +inf disables                              */
+    double out_clamp;        /* 100; +inf disables                                          */
+    double grad_clamp;       /* 100; +inf disables                                          */
+} oracle_cfg;
+
+static double clampd(double v, double c) { return v < -c ? -c : (v > c ? c : v); }
+static double sigmoid(double v) { return 1.0 / (1.0 + exp(-v)); }
+static double silu(double v) { return v / (1.0 + exp(-v)); }
+static double dsilu(double v)
+{
+    double s = sigmoid(v);
+    return s * (1.0 + v * (1.0 - s));
+}
+static double softplus(double v) { return v > 30.0 ? v + log1p(exp(-v)) : log1p(exp(v)); }
+static double amp(int mode, double m) { return mode == 1 ? fmin(softplus(m), 10.0) : m; }
+static double damp(int mode, double m)
+{
+    if (mode != 1) return 1.0;
+    return softplus(m) < 10.0 ? sigmoid(m) : 0.0;
+}
+
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Pre-conv input of stream s (0 magnitude, 1 angle) at time t (may be negative: history). */
+static double u_at(const float *x, const float *tail_in, int L, int J, int Kc, int b, int s,
+                   int j, int t)
+{
+    if (t >= 0) return (double)x[((size_t)b * L + t) * J + j];
+    if (!tail_in) return 0.0;
+    int row = t + (Kc - 1); /* oldest row first */
+    return (double)tail_in[(((size_t)b * (Kc - 1) + row) * 2 + s) * J + j];
+}
+static float u_at_f(const float *x, const float *tail_in, int L, int J, int Kc, int b, int s,
+                    int j, int t)
+{
+    if (t >= 0) return x[((size_t)b * L + t) * J + j];
+    if (!tail_in) return 0.0f;
+    int row = t + (Kc - 1);
+    return tail_in[(((size_t)b * (Kc - 1) + row) * 2 + s) * J + j];
+}
+
+/*
+ * Stand-alone Temporal Syntax Cache on C channels (Sec. 3.2).
+ *   x [B][L][C] fp32, w [C][Kc], bias [C] or NULL, hist_in [B][Kc-1][C] or NULL (zeros),
+ *   y [B][L][C] fp64, hist_out [B][Kc-1][C] fp32 or NULL.
+ */
+int oracle_syntax_conv(int B, int L, int C, int Kc, double conv_clamp, const float *x,
+                       const float *w, const float *bias, const float *hist_in, double *y,
+                       float *hist_out)
+{
+    if (B <= 0 || L < 0 || C <= 0 || Kc < 1) return -1;
+    for (int b = 0; b < B; ++b)
+        for (int t = 0; t < L; ++t)
+            for (int c = 0; c < C; ++c) {
+                double z = bias ? (double)bias[c] : 0.0;
+                for (int i = 0; i < Kc; ++i) {
+                    int tt = t - (Kc - 1) + i;
+                    double u;
+                    if (tt >= 0)
+                        u = (double)x[((size_t)b * L + tt) * C + c];
+                    else if (hist_in)
+                        u = (double)hist_in[((size_t)b * (Kc - 1) + (tt + Kc - 1)) * C + c];
+                    else
+                        u = 0.0;
+                    z += (double)w[(size_t)c * Kc + i] * u;
+                }
+                y[((size_t)b * L + t) * C + c] = silu(clampd(z, conv_clamp));
+            }
+    if (hist_out)
+        for (int b = 0; b < B; ++b)
+            for (int r = 0; r < Kc - 1; ++r)
+                for (int c = 0; c < C; ++c) {
+                    int tt = L - (Kc - 1) + r;
+                    float v;
+                    if (tt >= 0)
+                        v = x[((size_t)b * L + tt) * C + c];
+                    else if (hist_in)
+                        v = hist_in[((size_t)b * (Kc - 1) + (tt + Kc - 1)) * C + c];
+                    else
+                        v = 0.0f;
+                    hist_out[((size_t)b * (Kc - 1) + r) * C + c] = v;
+                }
+    return 0;
+}
+
+/* Everything the front-end produces for one (b, t, j). */
+typedef struct {
+    double zm, za;   /* conv pre-activations (fp64); the raw inputs when conv_k = 0 */
+    double m, phi;   /* magnitude-stream and angle-stream values after the front-end */
+    double a;        /* amplitude */
+    int g;           /* gate */
+} front_t;
+
+static front_t front_end(const oracle_cfg *c, const float *mag, const float *ang,
+                         const float *conv_w, const float *conv_b, const float *tail_in, int b,
+                         int t, int j)
+{
+    const int J = c->H * c->F, L = c->L, Kc = c->conv_k;
+    front_t f;
+    double gate_arg; /* fp32-representable quantity the gate decision is taken on */
+    if (Kc > 0) {
+        double z[2];
+        float z32 = 0.0f;
+        for (int s = 0; s < 2; ++s) {
+            const float *x = s ? ang : mag;
+            const float *w = conv_w + ((size_t)s * J + j) * Kc;
+            double acc = conv_b ? (double)conv_b[(size_t)s * J + j] : 0.0;
+            float acc32 = conv_b ? conv_b[(size_t)s * J + j] : 0.0f;
+            for (int i = 0; i < Kc; ++i) {
+                int tt = t - (Kc - 1) + i;
+                acc += (double)w[i] * u_at(x, tail_in, L, J, Kc, b, s, j, tt);
+                if (s == 0) acc32 = fmaf(w[i], u_at_f(x, tail_in, L, J, Kc, b, s, j, tt), acc32);
+            }
+            z[s] = acc;
+            if (s == 0) z32 = acc32;
+        }
+        f.zm = z[0];
+        f.za = z[1];
+        f.m = silu(clampd(f.zm, c->conv_clamp));
+        f.phi = silu(clampd(f.za, c->conv_clamp));
+        gate_arg = silu(clampd((double)z32, c->conv_clamp));
+    } else {
+        f.zm = (double)mag[((size_t)b * L + t) * J + j];
+        f.za = (double)ang[((size_t)b * L + t) * J + j];
+        f.m = f.zm;
+        f.phi = f.za;
+        gate_arg = f.zm;
+    }
+    f.a = amp(c->amp_mode, f.m);
+    f.g = fabs(amp(c->amp_mode, gate_arg)) >= (double)c->gate_tau ? 1 : 0;
+    return f;
+}
+
+/*
+ * Forward: front-end, gate, phasor, accumulation, clamp.
+ *   mag, ang   [B][L][J] fp32          gamma, theta [J] fp32
+ *   conv_w     [2][J][Kc] fp32         conv_b [2][J] fp32 or NULL   (unused when conv_k = 0)
+ *   scan_in    [B][2][J] fp64 or NULL  tail_in [B][Kc-1][2][J] fp32 or NULL
+ *   z_re, z_im [B][L][J] fp64          scan_out [B][2][J] fp64 or NULL (unclamped S[L-1])
+ *   tail_out   [B][Kc-1][2][J] fp32 or NULL      gate [B][L][J] bytes (0/1) or NULL
+ */
+int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, const float *gamma,
+                     const float *theta, const float *conv_w, const float *conv_b,
+                     const double *scan_in, const float *tail_in, double *z_re, double *z_im,
+                     double *scan_out, float *tail_out, uint8_t *gate)
+{
+    if (!c || c->B <= 0 || c->L < 0 || c->H <= 0 || c->F <= 0 || c->conv_k < 0) return -1;
+    const int B = c->B, L = c->L, J = c->H * c->F, Kc = c->conv_k;
+#ifdef _OPENMP
+    if (c->nthreads > 0) omp_set_num_threads(c->nthreads);
+#endif
+#pragma omp parallel for schedule(static)
+    for (int bj = 0; bj < B * J; ++bj) {
+        const int b = bj / J, j = bj % J;
+        const double ga = (double)gamma[j], ct = cos((double)theta[j]), st = sin((double)theta[j]);
+        double Sr = scan_in ? scan_in[((size_t)b * 2 + 0) * J + j] : 0.0;
+        double Si = scan_in ? scan_in[((size_t)b * 2 + 1) * J + j] : 0.0;
+        for (int t = 0; t < L; ++t) {
+            front_t f = front_end(c, mag, ang, conv_w, conv_b, tail_in, b, t, j);
+            double pr = f.g ? f.a * cos(f.phi) : 0.0;
+            double pi = f.g ? f.a * sin(f.phi) : 0.0;
+            double nr = pr + ga * (Sr * ct - Si * st);
+            double ni = pi + ga * (Sr * st + Si * ct);
+            double zr = clampd(nr, c->out_clamp), zi = clampd(ni, c->out_clamp);
+            if (c->clamp_feedback) {
+                nr = zr;
+                ni = zi;
+            }
+            Sr = nr;
+            Si = ni;
+            size_t o = ((size_t)b * L + t) * J + j;
+            z_re[o] = zr;
+            z_im[o] = zi;
+            if (gate) gate[o] = (uint8_t)f.g;
+        }
+        if (scan_out) {
+            scan_out[((size_t)b * 2 + 0) * J + j] = Sr;
+            scan_out[((size_t)b * 2 + 1) * J + j] = Si;
+        }
+        if (tail_out && Kc > 1)
+            for (int r = 0; r < Kc - 1; ++r)
+                for (int s = 0; s < 2; ++s)
+                    tail_out[(((size_t)b * (Kc - 1) + r) * 2 + s) * J + j] =
+                        u_at_f(s ? ang : mag, tail_in, L, J, Kc, b, s, j, L - (Kc - 1) + r);
+    }
+    return 0;
+}
+
+/*
+ * Backward of oracle_phase_fwd (clamp_feedback must be 0).
+ *   dz_re, dz_im [B][L][J] fp32 upstream gradients of the emitted (clamped) outputs
+ *   dscan_out    [B][2][J] fp64 or NULL     gradient w.r.t. scan_out
+ *   dtail_out    [B][Kc-1][2][J] fp64 or NULL gradient w.r.t. tail_out
+ * Outputs (fp64, any may be NULL except dmag, dang):
+ *   dmag, dang [B][L][J]; dgamma, dtheta [J]; dconv_w [2][J][Kc]; dconv_b [2][J];
+ *   dscan_in [B][2][J]; dtail_in [B][Kc-1][2][J].
+ * Parameter gradients are overwritten (summed over b and t).
+ */
+int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, const float *gamma,
+                     const float *theta, const float *conv_w, const float *conv_b,
+                     const double *scan_in, const float *tail_in, const float *dz_re,
+                     const float *dz_im, const double *dscan_out, const double *dtail_out,
+                     double *dmag, double *dang, double *dgamma, double *dtheta, double *dconv_w,
+                     double *dconv_b, double *dscan_in, double *dtail_in)
+{
+    if (!c || c->B <= 0 || c->L < 0 || c->H <= 0 || c->F <= 0 || c->conv_k < 0 || c->conv_k > 16)
+        return -1;
+    if (c->clamp_feedback) return -2;
+    const int B = c->B, L = c->L, J = c->H * c->F, Kc = c->conv_k;
+    const double gc = c->grad_clamp;
+#ifdef _OPENMP
+    if (c->nthreads > 0) omp_set_num_threads(c->nthreads);
+#endif
+#pragma omp parallel for schedule(static)
+    for (int j = 0; j < J; ++j) {
+        const double ga = (double)gamma[j], ct = cos((double)theta[j]), st = sin((double)theta[j]);
+        double acc_g = 0.0, acc_t = 0.0;
+        double acc_w[2][16], acc_b[2] = {0.0, 0.0};
+        for (int s = 0; s < 2; ++s)
+            for (int i = 0; i < 16; ++i) acc_w[s][i] = 0.0;
+        /* per-sequence scratch */
+        double *Sr = (double *)malloc(sizeof(double) * (size_t)(L + 1) * 2);
+        double *Si = Sr + (L + 1);
+        front_t *fr = (front_t *)malloc(sizeof(front_t) * (size_t)(L > 0 ? L : 1));
+        double *dzc = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1) * 2);
+        for (int b = 0; b < B; ++b) {
+            /* forward recompute; Sr[t+1] holds S[t], Sr[0] holds S[-1] */
+            Sr[0] = scan_in ? scan_in[((size_t)b * 2 + 0) * J + j] : 0.0;
+            Si[0] = scan_in ? scan_in[((size_t)b * 2 + 1) * J + j] : 0.0;
+            for (int t = 0; t < L; ++t) {
+                fr[t] = front_end(c, mag, ang, conv_w, conv_b, tail_in, b, t, j);
+                double pr = fr[t].g ? fr[t].a * cos(fr[t].phi) : 0.0;
+                double pi = fr[t].g ? fr[t].a * sin(fr[t].phi) : 0.0;
+                Sr[t + 1] = pr + ga * (Sr[t] * ct - Si[t] * st);
+                Si[t + 1] = pi + ga * (Sr[t] * st + Si[t] * ct);
+            }
+            /* reverse-time adjoint */
+            double Gr = 0.0, Gi = 0.0; /* conj(lambda) * G[t+1] enters below */
+            for (int t = L - 1; t >= 0; --t) {
+                size_t o = ((size_t)b * L + t) * J + j;
+                double dSr = (double)dz_re[o], dSi = (double)dz_im[o]; /* clamp passes gradient */
+                if (t == L - 1 && dscan_out) {
+                    dSr += dscan_out[((size_t)b * 2 + 0) * J + j];
+                    dSi += dscan_out[((size_t)b * 2 + 1) * J + j];
+                }
+                /* G[t] = dS[t] + conj(lambda) G[t+1] */
+                double nGr = dSr + ga * (Gr * ct + Gi * st);
+                double nGi = dSi + ga * (-Gr * st + Gi * ct);
+                Gr = nGr;
+                Gi = nGi;
+                /* parameter terms use S[t-1] and the unclamped adjoint */
+                double rr = Sr[t] * ct - Si[t] * st, ri = Sr[t] * st + Si[t] * ct; /* e^{i th} S[t-1] */
+                acc_g += clampd(Gr * rr + Gi * ri, gc);
+                acc_t += clampd(ga * (Gr * (-ri) + Gi * rr), gc);
+                /* returned dp, clamped, then chained to amplitude and phase */
+                double hr = clampd(Gr, gc), hi = clampd(Gi, gc);
+                double cph = cos(fr[t].phi), sph = sin(fr[t].phi);
+                double da = hr * cph + hi * sph;                 /* straight-through: no gate */
+                double dphi = fr[t].g ? fr[t].a * (-hr * sph + hi * cph) : 0.0;
+                double dm = da * damp(c->amp_mode, fr[t].m);
+                if (Kc > 0) {
+                    double km = fabs(fr[t].zm) <= c->conv_clamp ? dsilu(fr[t].zm) : 0.0;
+                    double ka = fabs(fr[t].za) <= c->conv_clamp ? dsilu(fr[t].za) : 0.0;
+                    dzc[t] = dm * km;
+                    dzc[L + t] = dphi * ka;
+                } else {
+                    dmag[o] = dm;
+                    dang[o] = dphi;
+                }
+            }
+            if (dscan_in) {
+                dscan_in[((size_t)b * 2 + 0) * J + j] = ga * (Gr * ct + Gi * st);
+                dscan_in[((size_t)b * 2 + 1) * J + j] = ga * (-Gr * st + Gi * ct);
+            }
+            if (Kc > 0) {
+                /* transposed conv, weight and bias gradients, history gradient */
+                for (int s = 0; s < 2; ++s) {
+                    const float *x = s ? ang : mag;
+                    double *dx = s ? dang : dmag;
+                    const float *w = conv_w + ((size_t)s * J + j) * Kc;
+                    for (int t = 0; t < L; ++t) dx[((size_t)b * L + t) * J + j] = 0.0;
+                    if (dtail_in)
+                        for (int r = 0; r < Kc - 1; ++r)
+                            dtail_in[(((size_t)b * (Kc - 1) + r) * 2 + s) * J + j] = 0.0;
+                    for (int t = 0; t < L; ++t) {
+                        double d = dzc[(size_t)s * L + t];
+                        acc_b[s] += d;
+                        for (int i = 0; i < Kc; ++i) {
+                            int tt = t - (Kc - 1) + i;
+                            acc_w[s][i] += d * u_at(x, tail_in, L, J, Kc, b, s, j, tt);
+                            if (tt >= 0)
+                                dx[((size_t)b * L + tt) * J + j] += (double)w[i] * d;
+                            else if (dtail_in)
+                                dtail_in[(((size_t)b * (Kc - 1) + (tt + Kc - 1)) * 2 + s) * J + j] +=
+                                    (double)w[i] * d;
+                        }
+                    }
+                    /* tail_out rows are copies of input rows (or of tail_in rows when L < Kc-1) */
+                    if (dtail_out)
+                        for (int r = 0; r < Kc - 1; ++r) {
+                            int tt = L - (Kc - 1) + r;
+                            double d = dtail_out[(((size_t)b * (Kc - 1) + r) * 2 + s) * J + j];
+                            if (tt >= 0)
+                                dx[((size_t)b * L + tt) * J + j] += d;
+                            else if (dtail_in)
+                                dtail_in[(((size_t)b * (Kc - 1) + (tt + Kc - 1)) * 2 + s) * J + j] += d;
+                        }
+                }
+            }
+        }
+        if (dgamma) dgamma[j] = acc_g;
+        if (dtheta) dtheta[j] = acc_t;
+        if (Kc > 0) {
+            for (int s = 0; s < 2; ++s) {
+                if (dconv_b) dconv_b[(size_t)s * J + j] = acc_b[s];
+                if (dconv_w)
+                    for (int i = 0; i < Kc; ++i) dconv_w[((size_t)s * J + j) * Kc + i] = acc_w[s][i];
+            }
+        }
+        free(Sr);
+        free(fr);
+        free(dzc);
+    }
+    return 0;
+}

@@ -1,0 +1,513 @@
+"""Pins for the fp64 oracle: what the paper and the mathematics fix, written with numpy complex
+arithmetic / library routines that share nothing with the oracle's real-form loop.
+
+Each test is chosen so that a plausible slip in the oracle (a dropped term, a sign, a transposed
+tap, an off-by-one in time) fails it.  CPU only.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import cawn_oracle as O
+
+INF = float("inf")
+
+
+def rng_(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def lam(gamma, theta):
+    return gamma.astype(np.float64) * np.exp(1j * theta.astype(np.float64))
+
+
+def np_silu(v):
+    return v / (1.0 + np.exp(-v))
+
+
+def np_dsilu(v):
+    s = 1.0 / (1.0 + np.exp(-v))
+    return s * (1.0 + v * (1.0 - s))
+
+
+def brute_scan(p, lmb, s_in=None):
+    """O(L^2): S_t = lambda^(t+1) S_in + sum_{tau<=t} lambda^(t-tau) p_tau  (Sec. 3.4: a push
+    injected at tau is rotated by (t-tau) theta and decayed by gamma^(t-tau))."""
+    B, L, J = p.shape
+    S = np.zeros((B, L, J), dtype=np.complex128)
+    for t in range(L):
+        for tau in range(t + 1):
+            S[:, t] += np.power(lmb, t - tau)[None] * p[:, tau]
+        if s_in is not None:
+            S[:, t] += np.power(lmb, t + 1)[None] * s_in
+    return S
+
+
+def brute_adjoint(dS, lmb):
+    """G_t = sum_{s>=t} conj(lambda)^(s-t) dS_s."""
+    B, L, J = dS.shape
+    G = np.zeros((B, L, J), dtype=np.complex128)
+    for t in range(L):
+        for s in range(t, L):
+            G[:, t] += np.power(np.conj(lmb), s - t)[None] * dS[:, s]
+    return G
+
+
+def small(seed, B=2, L=24, H=2, F=3, Kc=0):
+    r = rng_(seed)
+    J = H * F
+    d = dict(mag=r.standard_normal((B, L, J)).astype(np.float32),
+             ang=(2.0 * r.standard_normal((B, L, J))).astype(np.float32),
+             gamma=r.uniform(0.5, 0.999, J).astype(np.float32),
+             theta=r.uniform(0, np.pi, J).astype(np.float32))
+    if Kc:
+        d["conv_w"] = (r.standard_normal((2, J, Kc)) / math.sqrt(Kc)).astype(np.float32)
+        d["conv_b"] = (0.1 * r.standard_normal((2, J))).astype(np.float32)
+    return d
+
+
+# ----------------------------------------------------------------------------------- recurrence
+def test_brute_force_sum_of_decayed_rotated_pushes():
+    B, L, H, F = 2, 40, 2, 4
+    d = small(1, B, L, H, F)
+    tau = 0.3
+    cfg = O.Cfg(B, L, H, F, gate_tau=tau, out_clamp=INF)
+    s_in = rng_(2).standard_normal((B, 2, H * F))
+    out = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], scan_in=s_in)
+    a = d["mag"].astype(np.float64)
+    g = np.abs(d["mag"]) >= np.float32(tau)
+    p = g * a * np.exp(1j * d["ang"].astype(np.float64))
+    S = brute_scan(p, lam(d["gamma"], d["theta"]), s_in[:, 0] + 1j * s_in[:, 1])
+    np.testing.assert_allclose(out["z_re"], S.real, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["z_im"], S.imag, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(out["gate"], g.astype(np.uint8))
+    np.testing.assert_allclose(out["scan_out"][:, 0], S[:, -1].real, atol=1e-12)
+    np.testing.assert_allclose(out["scan_out"][:, 1], S[:, -1].imag, atol=1e-12)
+
+
+def test_single_impulse_modulus_and_counter_clockwise_phase():
+    # one push at t0: |S_t| = gamma^(t-t0) |p|, arg S_t = phi + (t-t0) theta  (Sec. 3.4)
+    L, t0 = 30, 4
+    gamma = np.array([0.97], np.float32)
+    theta = np.array([0.11], np.float32)
+    mag = np.zeros((1, L, 1), np.float32)
+    ang = np.zeros((1, L, 1), np.float32)
+    mag[0, t0, 0] = 1.5
+    ang[0, t0, 0] = 0.4
+    out = O.phase_fwd(O.Cfg(1, L, 1, 1), mag, ang, gamma, theta)
+    S = out["z_re"][0, :, 0] + 1j * out["z_im"][0, :, 0]
+    assert np.all(S[:t0] == 0)
+    n = np.arange(L - t0)
+    np.testing.assert_allclose(np.abs(S[t0:]), 1.5 * float(gamma[0]) ** n, rtol=1e-13)
+    expect = float(ang[0, t0, 0]) + n * float(theta[0])
+    np.testing.assert_allclose(np.angle(S[t0:] * np.exp(-1j * expect)), 0.0, atol=1e-13)
+
+
+def test_constant_input_geometric_series():
+    L, H, F = 200, 1, 5
+    J = H * F
+    gamma = np.array([0.9, 0.99, 0.999, 1.0, 0.5], np.float32)
+    theta = np.array([0.0, 0.3, 1.0, 0.0, 3.0], np.float32)
+    mag = np.full((1, L, J), 0.75, np.float32)
+    ang = np.full((1, L, J), -0.6, np.float32)
+    out = O.phase_fwd(O.Cfg(1, L, H, F, out_clamp=INF), mag, ang, gamma, theta)
+    lmb = lam(gamma, theta)
+    p = 0.75 * np.exp(1j * float(np.float32(-0.6)))
+    t = np.arange(L)[:, None]
+    with np.errstate(invalid="ignore", divide="ignore"):
+        S = p * (1 - lmb[None] ** (t + 1)) / (1 - lmb[None])
+    S[:, 3] = (t[:, 0] + 1) * p  # lambda = 1
+    got = out["z_re"][0] + 1j * out["z_im"][0]
+    np.testing.assert_allclose(got, S, rtol=1e-11, atol=1e-12)
+
+
+def test_reduces_to_prefix_sum():
+    B, L, H, F = 2, 100, 1, 4
+    d = small(3, B, L, H, F)
+    one = np.ones(H * F, np.float32)
+    zero = np.zeros(H * F, np.float32)
+    out = O.phase_fwd(O.Cfg(B, L, H, F, gate_tau=0.0, out_clamp=INF), d["mag"], d["ang"], one, zero)
+    p = d["mag"].astype(np.float64) * np.exp(1j * d["ang"].astype(np.float64))
+    np.testing.assert_allclose(out["z_re"], np.cumsum(p.real, axis=1), atol=1e-12)
+    np.testing.assert_allclose(out["z_im"], np.cumsum(p.imag, axis=1), atol=1e-12)
+    assert out["gate"].all()
+
+
+@pytest.mark.parametrize("Kc", [0, 3, 4])
+def test_chunked_equals_unchunked_bitwise(Kc):
+    B, L, H, F = 2, 37, 2, 3
+    d = small(4, B, L, H, F, Kc)
+    kw = dict(conv_w=d.get("conv_w"), conv_b=d.get("conv_b"))
+    full = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=0.1), d["mag"], d["ang"], d["gamma"],
+                       d["theta"], **kw)
+    for splits in ([1] * L, [2, 1, 1, 3, 30], [36, 1], [5, 32], [17, 20]):
+        assert sum(splits) == L
+        scan, tail, t0 = None, None, 0
+        zr, zi, gt = [], [], []
+        for n in splits:
+            o = O.phase_fwd(O.Cfg(B, n, H, F, conv_k=Kc, gate_tau=0.1), d["mag"][:, t0:t0 + n],
+                            d["ang"][:, t0:t0 + n], d["gamma"], d["theta"], scan_in=scan,
+                            tail_in=tail, **kw)
+            scan, tail = o["scan_out"], o["tail_out"]
+            zr.append(o["z_re"]); zi.append(o["z_im"]); gt.append(o["gate"])
+            t0 += n
+        assert np.array_equal(np.concatenate(zr, 1), full["z_re"])
+        assert np.array_equal(np.concatenate(zi, 1), full["z_im"])
+        assert np.array_equal(np.concatenate(gt, 1), full["gate"])
+        assert np.array_equal(scan, full["scan_out"])
+        if Kc > 1:
+            assert np.array_equal(tail, full["tail_out"])
+            assert np.array_equal(tail[:, :, 0], d["mag"][:, L - (Kc - 1):])
+            assert np.array_equal(tail[:, :, 1], d["ang"][:, L - (Kc - 1):])
+
+
+# ----------------------------------------------------------------------------------------- conv
+def test_conv_kernel1_is_silu():
+    x = rng_(5).standard_normal((2, 9, 4)).astype(np.float32)
+    y, _ = O.syntax_conv(x, np.ones((4, 1), np.float32))
+    np.testing.assert_allclose(y, np_silu(x.astype(np.float64)), rtol=1e-14)
+
+
+def test_conv_impulse_reads_taps_back_last_tap_on_current_token():
+    Kc, L, t0 = 4, 12, 3
+    w = np.array([[0.1, 0.2, 0.3, 0.4]], np.float32)
+    x = np.zeros((1, L, 1), np.float32)
+    x[0, t0, 0] = 1.0
+    y, _ = O.syntax_conv(x, w, conv_clamp=INF)
+    z = np.zeros(L)
+    for d in range(Kc):
+        z[t0 + d] = float(w[0, Kc - 1 - d])   # current token meets the LAST tap
+    np.testing.assert_allclose(y[0, :, 0], np_silu(z), rtol=1e-14)
+
+
+@pytest.mark.parametrize("Kc", [3, 4])
+def test_conv_matches_numpy_convolve_with_history_and_clamp(Kc):
+    r = rng_(6)
+    B, L, Cc = 2, 20, 3
+    x = (30 * r.standard_normal((B, L, Cc))).astype(np.float32)
+    w = r.standard_normal((Cc, Kc)).astype(np.float32)
+    bias = r.standard_normal(Cc).astype(np.float32)
+    hist = r.standard_normal((B, Kc - 1, Cc)).astype(np.float32)
+    y, hout = O.syntax_conv(x, w, bias, hist)
+    for b in range(B):
+        for c in range(Cc):
+            seq = np.concatenate([hist[b, :, c], x[b, :, c]]).astype(np.float64)
+            z = np.convolve(seq, w[c, ::-1].astype(np.float64), mode="valid") + float(bias[c])
+            assert z.shape == (L,)
+            np.testing.assert_allclose(y[b, :, c], np_silu(np.clip(z, -50, 50)), rtol=1e-12,
+                                       atol=1e-15)
+    assert (np.abs(y) <= 50).all() and np.abs(x).max() > 50
+    np.testing.assert_array_equal(hout, x[:, L - (Kc - 1):])
+
+
+def test_fused_front_end_equals_conv_then_scan():
+    B, L, H, F, Kc = 2, 25, 2, 2, 4
+    J = H * F
+    d = small(7, B, L, H, F, Kc)
+    _, tail = (None, rng_(8).standard_normal((B, Kc - 1, 2, J)).astype(np.float32))
+    fused = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc), d["mag"], d["ang"], d["gamma"], d["theta"],
+                        conv_w=d["conv_w"], conv_b=d["conv_b"], tail_in=tail)
+    xcat = np.concatenate([d["mag"], d["ang"]], axis=2)                  # [B,L,2J]
+    y, _ = O.syntax_conv(xcat, d["conv_w"].reshape(2 * J, Kc), d["conv_b"].reshape(2 * J),
+                         tail.reshape(B, Kc - 1, 2 * J))
+    p = y[..., :J] * np.exp(1j * y[..., J:])
+    S = brute_scan(p, lam(d["gamma"], d["theta"]))
+    np.testing.assert_allclose(fused["z_re"], S.real, atol=1e-12)
+    np.testing.assert_allclose(fused["z_im"], S.imag, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------------------- gate
+def test_gate_open_closed_and_fraction():
+    B, L, H, F = 1, 4000, 2, 8
+    J = H * F
+    r = rng_(9)
+    mag = r.standard_normal((B, L, J)).astype(np.float32)
+    ang = r.standard_normal((B, L, J)).astype(np.float32)
+    gamma = r.uniform(0.9, 0.99, J).astype(np.float32)
+    theta = r.uniform(0, 3, J).astype(np.float32)
+    s_in = r.standard_normal((B, 2, J))
+    o0 = O.phase_fwd(O.Cfg(B, L, H, F, gate_tau=0.0), mag, ang, gamma, theta)
+    assert o0["gate"].all()
+    oc = O.phase_fwd(O.Cfg(B, 50, H, F, gate_tau=INF), mag[:, :50], ang[:, :50], gamma, theta,
+                     scan_in=s_in)
+    assert not oc["gate"].any()
+    lmb = lam(gamma, theta)
+    n = np.arange(1, 51)[:, None]
+    free = (lmb[None] ** n) * (s_in[0, 0] + 1j * s_in[0, 1])[None]
+    np.testing.assert_allclose(oc["z_re"][0], free.real, atol=1e-13)
+    np.testing.assert_allclose(oc["z_im"][0], free.imag, atol=1e-13)
+    for tau in (0.1, 0.25):
+        o = O.phase_fwd(O.Cfg(B, L, H, F, gate_tau=tau), mag, ang, gamma, theta)
+        closed = 1.0 - o["gate"].mean()
+        expect = math.erf(tau / math.sqrt(2))        # P(|N(0,1)| < tau): 7.97 % / 19.74 %
+        assert abs(closed - expect) < 4 * math.sqrt(expect * (1 - expect) / (L * J))
+    # keep when equal to the threshold
+    m2 = np.array([[[0.25], [np.nextafter(np.float32(0.25), np.float32(0))], [-0.25]]], np.float32)
+    o = O.phase_fwd(O.Cfg(1, 3, 1, 1, gate_tau=0.25), m2, np.zeros_like(m2), gamma[:1], theta[:1])
+    assert o["gate"][0, :, 0].tolist() == [1, 0, 1]
+
+
+def test_fused_gate_is_taken_on_the_fp32_preactivation():
+    # decision = |SiLU(clamp(z32))| >= tau with z32 the fp32 fma chain, bias first, taps in order
+    B, L, H, F, Kc = 1, 300, 1, 4, 4
+    d = small(10, B, L, H, F, Kc)
+    tau = 0.1
+    o = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=tau), d["mag"], d["ang"], d["gamma"],
+                    d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"])
+    J = H * F
+    pad = np.concatenate([np.zeros((B, Kc - 1, J), np.float32), d["mag"]], axis=1)
+    z32 = np.broadcast_to(d["conv_b"][0][None, None], (B, L, J)).astype(np.float32).copy()
+    for i in range(Kc):
+        prod = d["conv_w"][0][None, None, :, i].astype(np.float64) * pad[:, i:i + L].astype(np.float64)
+        z32 = (prod + z32.astype(np.float64)).astype(np.float32)   # fp64 product+sum is exact enough: one rounding
+    gate = np.abs(np_silu(np.clip(z32.astype(np.float64), -50, 50))) >= float(np.float32(tau))
+    assert (o["gate"] == gate).mean() > 0.999   # numpy emulation of fma may differ by a double rounding
+    # gated-off lanes contribute nothing: zero them by hand and compare with tau = 0 on masked input
+    assert 0.02 < 1 - o["gate"].mean() < 0.6
+
+
+# ---------------------------------------------------------------------------------------- clamp
+def test_output_clamp_saturates_but_state_does_not():
+    L = 400
+    mag = np.full((1, L, 1), 5.0, np.float32)
+    ang = np.zeros((1, L, 1), np.float32)
+    one, zero = np.ones(1, np.float32), np.zeros(1, np.float32)
+    o = O.phase_fwd(O.Cfg(1, L, 1, 1), mag, ang, one, zero)
+    expect = np.minimum(5.0 * np.arange(1, L + 1), 100.0)
+    np.testing.assert_allclose(o["z_re"][0, :, 0], expect)
+    assert o["scan_out"][0, 0, 0] == 5.0 * L
+    # the other reading (clamped value carried), offered only to quantify the difference
+    of = O.phase_fwd(O.Cfg(1, L, 1, 1, clamp_feedback=1), mag, ang, one, zero)
+    assert of["scan_out"][0, 0, 0] == 100.0
+
+
+def test_amplitude_softplus_cap():
+    m = np.array([[[0.0], [20.0], [-3.0]]], np.float32)
+    z = np.zeros_like(m)
+    o = O.phase_fwd(O.Cfg(1, 3, 1, 1, amp_mode=1), m, z, np.zeros(1, np.float32), np.zeros(1, np.float32))
+    np.testing.assert_allclose(o["z_re"][0, :, 0], [math.log(2), 10.0, math.log1p(math.exp(-3))],
+                               rtol=1e-14)
+
+
+# ------------------------------------------------------------------------------------- backward
+def test_adjoint_dot_product_identity():
+    B, L, H, F = 2, 50, 2, 3
+    d = small(11, B, L, H, F)
+    r = rng_(12)
+    dz_re = r.standard_normal((B, L, H * F)).astype(np.float32)
+    dz_im = r.standard_normal((B, L, H * F)).astype(np.float32)
+    cfg = O.Cfg(B, L, H, F, out_clamp=INF, grad_clamp=INF)
+    f = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"])
+    g = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], dz_re, dz_im)
+    # <dZ, Scan(p)> = <Scan^T(dZ), p>, with Scan^T(dZ) recovered from (dmag, dang):
+    # dmag = Re(conj(G) e^{i phi}), dang = a Im(conj(G) e^{i phi})... so sum(G . p) = sum(a * dmag)
+    lhs = (dz_re * f["z_re"] + dz_im * f["z_im"]).sum()
+    rhs = (d["mag"].astype(np.float64) * g["dmag"]).sum()
+    assert abs(lhs - rhs) <= 1e-12 * abs(lhs)
+    G = brute_adjoint(dz_re.astype(np.float64) + 1j * dz_im, lam(d["gamma"], d["theta"]))
+    e = np.exp(1j * d["ang"].astype(np.float64))
+    np.testing.assert_allclose(g["dmag"], (np.conj(G) * e).real, atol=1e-12)
+    np.testing.assert_allclose(g["dang"], d["mag"] * (np.conj(G) * 1j * e).real, atol=1e-12)
+
+
+def _loss(cfg, d, up, scan_in, tail_in):
+    f = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d.get("conv_w"),
+                    conv_b=d.get("conv_b"), scan_in=scan_in, tail_in=tail_in)
+    v = (up["dz_re"] * f["z_re"]).sum() + (up["dz_im"] * f["z_im"]).sum()
+    v += (up["dscan_out"] * f["scan_out"]).sum()
+    if cfg.conv_k > 1:
+        v += (up["dtail_out"] * f["tail_out"]).sum()
+    return v
+
+
+@pytest.mark.parametrize("Kc,amp_mode,L", [(0, 0, 9), (4, 0, 9), (3, 1, 7), (4, 0, 2), (0, 1, 5)])
+def test_all_gradients_against_finite_differences(Kc, amp_mode, L):
+    B, H, F = 2, 1, 3
+    J = H * F
+    d = small(13 + Kc, B, L, H, F, Kc)
+    q = lambda a: (np.round(a * 1024) / 1024).astype(np.float32)     # leave room for exact +-h
+    for k in d:
+        d[k] = q(d[k])
+    r = rng_(14)
+    scan_in = np.round(r.standard_normal((B, 2, J)) * 1024) / 1024
+    tail_in = q(r.standard_normal((B, Kc - 1, 2, J))) if Kc > 1 else None
+    up = dict(dz_re=r.standard_normal((B, L, J)).astype(np.float32),
+              dz_im=r.standard_normal((B, L, J)).astype(np.float32),
+              dscan_out=r.standard_normal((B, 2, J)),
+              dtail_out=r.standard_normal((B, max(Kc - 1, 0), 2, J)))
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=0.0, conv_clamp=INF,
+                out_clamp=INF, grad_clamp=INF)
+    g = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], up["dz_re"], up["dz_im"],
+                    conv_w=d.get("conv_w"), conv_b=d.get("conv_b"), scan_in=scan_in,
+                    tail_in=tail_in, dscan_out=up["dscan_out"],
+                    dtail_out=up["dtail_out"] if Kc > 1 else None)
+
+    def fd(name, arr, idx, is_state=False):
+        def at(h):
+            a2 = arr.copy()
+            a2[idx] += h
+            dd = dict(d)
+            si, ti = scan_in, tail_in
+            if name == "scan_in":
+                si = a2
+            elif name == "tail_in":
+                ti = a2
+            else:
+                dd[name] = a2
+            return _loss(cfg, dd, up, si, ti)
+        h = 2.0 ** -7
+        d1 = (at(h) - at(-h)) / (2 * h)
+        d2 = (at(h / 2) - at(-h / 2)) / h
+        return (4 * d2 - d1) / 3                                        # Richardson, O(h^4)
+
+    checks = [("mag", d["mag"], g["dmag"]), ("ang", d["ang"], g["dang"]),
+              ("gamma", d["gamma"], g["dgamma"]), ("theta", d["theta"], g["dtheta"]),
+              ("scan_in", scan_in, g["dscan_in"])]
+    if Kc > 0:
+        checks += [("conv_w", d["conv_w"], g["dconv_w"]), ("conv_b", d["conv_b"], g["dconv_b"])]
+    if Kc > 1:
+        checks += [("tail_in", tail_in, g["dtail_in"])]
+    r2 = rng_(15)
+    for name, arr, grad in checks:
+        assert grad.shape == arr.shape, name
+        flat = r2.permutation(arr.size)[:10]
+        for f in flat:
+            idx = np.unravel_index(f, arr.shape)
+            num = fd(name, arr, idx)
+            assert abs(num - grad[idx]) <= 2e-7 * max(1.0, abs(num)), (name, idx, num, grad[idx])
+
+
+def test_ste_gradient_ignores_gate_for_amplitude_and_masks_phase():
+    B, L, H, F = 2, 30, 2, 3
+    d = small(16, B, L, H, F)
+    r = rng_(17)
+    dz_re = r.standard_normal((B, L, H * F)).astype(np.float32)
+    dz_im = r.standard_normal((B, L, H * F)).astype(np.float32)
+    g0 = O.phase_bwd(O.Cfg(B, L, H, F, gate_tau=0.0), d["mag"], d["ang"], d["gamma"], d["theta"],
+                     dz_re, dz_im)
+    tau = 0.5
+    g1 = O.phase_bwd(O.Cfg(B, L, H, F, gate_tau=tau), d["mag"], d["ang"], d["gamma"], d["theta"],
+                     dz_re, dz_im)
+    mask = np.abs(d["mag"]) >= np.float32(tau)
+    assert 0.2 < mask.mean() < 0.8
+    assert np.array_equal(g1["dmag"], g0["dmag"])              # gradient as if no threshold
+    assert np.array_equal(g1["dang"], mask * g0["dang"])
+    assert not np.array_equal(g1["dgamma"], g0["dgamma"])      # the state itself did change
+
+
+@pytest.mark.parametrize("tau", [0.0, 0.15])
+def test_fused_backward_equals_numpy_chain(tau):
+    # conv backward + STE with the gate active: rebuild every gradient from brute-force pieces
+    B, L, H, F, Kc = 2, 14, 1, 3, 4
+    J = H * F
+    d = small(18, B, L, H, F, Kc)
+    r = rng_(19)
+    tail = r.standard_normal((B, Kc - 1, 2, J)).astype(np.float32)
+    dz_re = r.standard_normal((B, L, J)).astype(np.float32)
+    dz_im = r.standard_normal((B, L, J)).astype(np.float32)
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=tau, out_clamp=INF, grad_clamp=INF)
+    fwd = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d["conv_w"],
+                      conv_b=d["conv_b"], tail_in=tail)
+    g = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], dz_re, dz_im,
+                    conv_w=d["conv_w"], conv_b=d["conv_b"], tail_in=tail)
+    lmb = lam(d["gamma"], d["theta"])
+    G = brute_adjoint(dz_re.astype(np.float64) + 1j * dz_im, lmb)
+    w = d["conv_w"].astype(np.float64)
+    useq = [np.concatenate([tail[:, :, s], (d["mag"], d["ang"])[s]], axis=1).astype(np.float64)
+            for s in range(2)]                                         # [B, Kc-1+L, J]
+    z = [sum(w[s][None, None, :, i] * useq[s][:, i:i + L] for i in range(Kc)) + d["conv_b"][s]
+         for s in range(2)]
+    a, phi = np_silu(z[0]), np_silu(z[1])
+    gate = fwd["gate"].astype(np.float64)
+    e = np.exp(1j * phi)
+    da = (np.conj(G) * e).real
+    dphi = gate * a * (np.conj(G) * 1j * e).real
+    dzc = [da * np_dsilu(z[0]), dphi * np_dsilu(z[1])]
+    S = brute_scan(gate * a * e, lmb)
+    Sprev = np.concatenate([np.zeros((B, 1, J)), S[:, :-1]], axis=1)
+    np.testing.assert_allclose(g["dgamma"], (np.conj(G) * np.exp(1j * d["theta"].astype(np.float64)) * Sprev).real.sum((0, 1)), atol=1e-11)
+    np.testing.assert_allclose(g["dtheta"], (np.conj(G) * 1j * lmb * Sprev).real.sum((0, 1)), atol=1e-11)
+    for s, name in ((0, "dmag"), (1, "dang")):
+        du = np.zeros((B, Kc - 1 + L, J))
+        dw = np.zeros((J, Kc))
+        for i in range(Kc):
+            du[:, i:i + L] += w[s][None, None, :, i] * dzc[s]
+            dw[:, i] = (dzc[s] * useq[s][:, i:i + L]).sum((0, 1))
+        np.testing.assert_allclose(g[name], du[:, Kc - 1:], atol=1e-12)
+        np.testing.assert_allclose(g["dtail_in"][:, :, s], du[:, :Kc - 1], atol=1e-12)
+        np.testing.assert_allclose(g["dconv_w"][s], dw, atol=1e-11)
+        np.testing.assert_allclose(g["dconv_b"][s], dzc[s].sum((0, 1)), atol=1e-11)
+
+
+def test_impulse_closed_forms_for_retention_and_rotation_gradients():
+    # one push p at t0, one unit of upstream gradient at t1: S_t1 = lambda^n p, n = t1 - t0
+    L, t0, t1 = 20, 3, 15
+    n = t1 - t0
+    gamma = np.array([0.93], np.float32)
+    theta = np.array([0.37], np.float32)
+    mag = np.zeros((1, L, 1), np.float32); ang = np.zeros((1, L, 1), np.float32)
+    mag[0, t0, 0], ang[0, t0, 0] = 1.25, 0.8
+    p = 1.25 * np.exp(1j * float(np.float32(0.8)))
+    lmb = lam(gamma, theta)[0]
+    cfg = O.Cfg(1, L, 1, 1, out_clamp=INF, grad_clamp=INF)
+    for (ur, ui) in ((1.0, 0.0), (0.0, 1.0)):
+        dz_re = np.zeros((1, L, 1), np.float32); dz_im = np.zeros((1, L, 1), np.float32)
+        dz_re[0, t1, 0], dz_im[0, t1, 0] = ur, ui
+        g = O.phase_bwd(cfg, mag, ang, gamma, theta, dz_re, dz_im)
+        dS_dgamma = n * float(gamma[0]) ** (n - 1) * np.exp(1j * n * float(theta[0])) * p
+        dS_dtheta = 1j * n * lmb ** n * p
+        pick = (lambda c: c.real) if ur else (lambda c: c.imag)
+        np.testing.assert_allclose(g["dgamma"][0], pick(dS_dgamma), rtol=1e-12)
+        np.testing.assert_allclose(g["dtheta"][0], pick(dS_dtheta), rtol=1e-12)
+
+
+def test_gradient_clamp_by_hand():
+    # L=2, gamma=1, theta=0, phi=0: G_1 = 150, G_0 = 300 -> returned dp clamps to 100;
+    # dgamma terms: t=1: G_1 * S_0 = 150 * 2 = 300 -> 100; t=0: S_-1 = 0.
+    mag = np.array([[[2.0], [1.0]]], np.float32)
+    ang = np.zeros_like(mag)
+    dz_re = np.full((1, 2, 1), 150.0, np.float32)
+    dz_im = np.zeros_like(dz_re)
+    one, zero = np.ones(1, np.float32), np.zeros(1, np.float32)
+    g = O.phase_bwd(O.Cfg(1, 2, 1, 1, grad_clamp=100.0), mag, ang, one, zero, dz_re, dz_im)
+    assert g["dmag"][0, :, 0].tolist() == [100.0, 100.0]
+    assert g["dgamma"][0] == 100.0
+    assert g["dscan_in"][0, 0, 0] == 300.0           # the carried adjoint is not clamped
+    g = O.phase_bwd(O.Cfg(1, 2, 1, 1, grad_clamp=INF), mag, ang, one, zero, dz_re, dz_im)
+    assert g["dmag"][0, :, 0].tolist() == [300.0, 150.0]
+    assert g["dgamma"][0] == 300.0
+
+
+def test_output_clamp_passes_gradient_straight_through():
+    L = 60
+    mag = np.full((1, L, 1), 5.0, np.float32)
+    ang = np.zeros_like(mag)
+    one, zero = np.ones(1, np.float32), np.zeros(1, np.float32)
+    dz = np.ones((1, L, 1), np.float32)
+    g = O.phase_bwd(O.Cfg(1, L, 1, 1, grad_clamp=INF), mag, ang, one, zero, dz, np.zeros_like(dz))
+    # saturated from t = 19 on, yet every upstream unit still flows back: dmag_t = L - t
+    np.testing.assert_allclose(g["dmag"][0, :, 0], np.arange(L, 0, -1.0))
+
+
+def test_conv_clamp_blocks_gradient_outside_range():
+    Kc = 1
+    mag = np.array([[[60.0], [1.0], [-70.0]]], np.float32)
+    ang = np.zeros_like(mag)
+    w = np.ones((2, 1, 1), np.float32)
+    dz = np.ones((1, 3, 1), np.float32)
+    g = O.phase_bwd(O.Cfg(1, 3, 1, 1, conv_k=Kc, grad_clamp=INF), mag, ang, np.zeros(1, np.float32),
+                    np.zeros(1, np.float32), dz, np.zeros_like(dz), conv_w=w,
+                    conv_b=np.zeros((2, 1), np.float32))
+    assert g["dmag"][0, 0, 0] == 0.0 and g["dmag"][0, 2, 0] == 0.0
+    np.testing.assert_allclose(g["dmag"][0, 1, 0], math.cos(np_silu(0.0)) * np_dsilu(1.0), rtol=1e-13)
+
+
+# -------------------------------------------------------------------------------------- theta_j
+def test_theta_init_endpoints_and_ratio():
+    H, F = 12, 64
+    th = O.theta_init(H, F).astype(np.float64)
+    assert th[0] == 1.0
+    J = H * F
+    np.testing.assert_allclose(th[1:] / th[:-1], 10000.0 ** (-2.0 / J), rtol=3e-7)
+    np.testing.assert_allclose(th[-1], 10.0 ** (-8.0 * (J - 1) / J), rtol=1e-7)
