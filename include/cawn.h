@@ -1,0 +1,157 @@
+/*
+ * libcawn -- the hot path of CAWN's Resonance Layer on one AMD MI355X (gfx950), C ABI.
+ *
+ * Operation (paper: Sec. 3.2 Temporal Syntax Cache, Sec. 3.3 hard-threshold gate with
+ * straight-through estimator, Sec. 3.4 causal phase accumulation and its clamp, Sec. 3.5 Concat
+ * output and clamped returned gradients, Sec. 3.7 / Sec. 5 O(1) state passing):
+ *
+ *   per batch row b, token t, lane j = h*F + k (H heads x F frequencies, j fastest in memory)
+ *     z_s   = bias_s[j] + sum_{i<conv_k} w_s[j][i] * u_s[t-(conv_k-1)+i][j]      s in {mag, ang}
+ *     x_s   = SiLU(clamp(z_s, +-conv_clamp))            (conv_k = 0: x_s = u_s, no conv, no SiLU)
+ *     a     = x_mag (amp_mode 0)  |  min(softplus(x_mag), 10) (amp_mode 1);   phi = x_ang
+ *     g     = [ |a| >= gate_tau ]                        (forward only; backward ignores g for a)
+ *     p     = g * a * (cos phi, sin phi)
+ *     S[t]  = p + gamma[j] * e^{i theta[j]} * S[t-1]     (complex, written out in real fp32
+ *                                                         arithmetic), S[-1] = state_in or 0
+ *     Z[t]  = clamp(S[t], +-out_clamp)                   (the carried S is not clamped)
+ *
+ * Every pointer below is DEVICE memory owned by the caller unless it says "host".  All tensors
+ * are fp32.  The library allocates nothing, frees nothing and never synchronises: each call
+ * enqueues its kernels on `stream` (a hipStream_t passed as void*; NULL = the default stream)
+ * and returns.  Calls that share a workspace must be ordered on one stream.
+ *
+ * Return value: CAWN_OK (0) or a negative cawn_status.  Nothing is written to stdout/stderr.
+ */
+#ifndef CAWN_H_
+#define CAWN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cawn_status {
+    CAWN_OK = 0,
+    CAWN_EINVAL = -1,       /* null required pointer, non-positive size, bad stride            */
+    CAWN_EUNSUPPORTED = -2, /* valid request this build does not implement                     */
+    CAWN_EWORKSPACE = -3,   /* workspace too small or misaligned (needs 256-byte alignment)    */
+    CAWN_ELAUNCH = -4,      /* the HIP runtime refused a launch or copy                        */
+    CAWN_ETIMEOUT = -5      /* (cawn_workspace_status only) a tile gave up waiting for a carry */
+} cawn_status;
+
+typedef struct cawn_desc {
+    int32_t B, L, H, F;   /* L = tokens in THIS call (0 allowed: state is passed through)       */
+    int32_t conv_k;       /* 0 = no conv front-end; 1..4 taps (paper: 3; benchmark configs: 4)  */
+    int32_t amp_mode;     /* 0 amplitude = magnitude stream; 1 = min(softplus(.), 10), Sec. 3.3 */
+    int32_t gate_mode;    /* 0 per-lane threshold on |a|; other values: CAWN_EUNSUPPORTED       */
+    float gate_tau;       /* keep when |a| >= gate_tau; 0 = gate open                           */
+    float conv_clamp;     /* 50 in the paper; +inf disables                                     */
+    float out_clamp;      /* 100; +inf disables                                                 */
+    float grad_clamp;     /* 100; +inf disables (backward only)                                 */
+    int32_t accumulate_param_grads; /* backward: 0 overwrite, 1 add into dgamma/dtheta/dconv_*  */
+    int32_t lane_consts_cached;     /* 1: gamma, theta, conv_w, conv_b are unchanged since the
+                                       last call on this workspace with the same H, F, conv_k
+                                       that had this flag 0 -- skip rebuilding the lane table   */
+    int32_t reserved_;
+    int64_t in_stride_b, in_stride_t;   /* element strides of mag/ang/dmag/dang; 0 = dense
+                                           (t stride J, b stride L*J); lane stride is always 1  */
+    int64_t out_stride_b, out_stride_t; /* element strides of z_re/z_im/dz_re/dz_im; 0 = dense  */
+} cawn_desc;
+
+/* State blob: [B][2][J] scan state (re, im of S at the last token, unclamped) followed by
+ * [B][conv_k-1][2][J] conv history (last conv_k-1 PRE-conv rows, oldest first, mag then ang).
+ * J = H*F.  The same layout is used for the gradient blobs dstate_out / dstate_in. */
+size_t cawn_state_bytes(const cawn_desc *d);
+
+/* Scratch the kernels need: carry descriptors of the tile chain, the lane table, reduction
+ * partials.  Must be 256-byte aligned and must have been passed ONCE to cawn_workspace_init
+ * before its first use; calls leave it ready for the next call. */
+size_t cawn_workspace_bytes(const cawn_desc *d);
+
+/* Forward tile checkpoints the backward consumes: the scan state entering each time tile,
+ * [B][ceil(L / cawn_tile_len())][2][J]. */
+size_t cawn_ckpt_bytes(const cawn_desc *d);
+
+/* Tokens per time tile (the granularity of carries and checkpoints). */
+int32_t cawn_tile_len(void);
+
+const char *cawn_status_string(int status);
+
+/* Zero the control words of a freshly allocated workspace (enqueues a fill kernel). */
+int cawn_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Synchronises `stream`, then reports CAWN_ETIMEOUT if any tile of an earlier call on this
+ * workspace gave up waiting for its predecessor (its outputs are then invalid), else CAWN_OK.
+ * Clears the condition.  Diagnostic only; the compute calls never wait on the host. */
+int cawn_workspace_status(void *workspace, void *stream);
+
+/* Number of polls a tile spends waiting for its predecessor's carry before it gives up
+ * (default 1<<26; every wave exits either way).  Host-side setting, applies to later calls. */
+void cawn_set_spin_limit(uint32_t polls);
+
+/* Rotation angles as the paper initialises them (Sec. 3.4): theta_j = 10000^(-2j/(H*F)).
+ * theta_host: HOST buffer of H*F floats. */
+int cawn_theta_init(int32_t H, int32_t F, float *theta_host);
+
+/*
+ * Temporal Syntax Cache alone (Sec. 3.2) on C independent channels:
+ *   y[b][t][c] = SiLU(clamp(bias[c] + sum_i w[c][i] * x[b][t-(conv_k-1)+i][c], +-conv_clamp)).
+ * Uses d->B, d->L, d->conv_k (1..4), d->conv_clamp, d->in_stride_* for x, d->out_stride_* for y.
+ *   x [B][L][C]; w [C][conv_k]; bias [C] or NULL; conv_state_in [B][conv_k-1][C] or NULL (zeros);
+ *   y [B][L][C]; conv_state_out [B][conv_k-1][C] or NULL.  conv_state_in may alias
+ *   conv_state_out.  x must not alias y.
+ */
+int cawn_syntax_conv(const cawn_desc *d, int32_t C, const float *x, const float *w,
+                     const float *bias, const float *conv_state_in, float *y,
+                     float *conv_state_out, void *stream);
+
+/*
+ * Fused forward (Sec. 3.2 - 3.5): conv front-end, gate, phasor, phase accumulation, clamp.
+ *   mag, ang     [B][L][J] (pre-conv when conv_k > 0), strides d->in_stride_*
+ *   gamma, theta [J]
+ *   conv_w       [2][J][conv_k] (stream 0 = mag, 1 = ang), conv_b [2][J] or NULL; both ignored
+ *                when conv_k = 0
+ *   state_in     state blob or NULL (= sequence start: zero state, zero history)
+ *   z_re, z_im   [B][L][J], strides d->out_stride_*; z_im == z_re + J with out_stride_t = 2J
+ *                gives the paper's Concat(P_re, P_im) rows
+ *   state_out    state blob or NULL; MAY alias state_in (streaming in place)
+ *   ckpt         cawn_ckpt_bytes() or NULL when no backward will follow
+ *   gate_mask    [B][L][ceil(J/32)] uint32, bit (j%32) of word j/32 = g, or NULL
+ *   workspace    >= cawn_workspace_bytes(d)
+ * Inputs must not alias outputs.
+ */
+int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float *ang,
+                              const float *gamma, const float *theta, const float *conv_w,
+                              const float *conv_b, const void *state_in, float *z_re, float *z_im,
+                              void *state_out, void *ckpt, uint32_t *gate_mask, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of the fused forward (Sec. 3.4 last paragraph, Sec. 3.5): reverse-time adjoint
+ *   G[t] = dZ[t] + conj(lambda) G[t+1]   (the output clamp passes the gradient),
+ * returned per-element gradient clamp(G, +-grad_clamp) chained to the amplitude (no gate factor:
+ * straight-through) and to the phase (gate factor), then through SiLU', the conv clamp's
+ * sub-gradient and the transposed conv.  Parameter gradients: per-(b,t) terms clamped to
+ * +-grad_clamp, then summed in a fixed order (bitwise repeatable).
+ *   mag, ang, gamma, theta, conv_w, conv_b, state_in: exactly what the forward call received
+ *   ckpt         written by that forward call (same d->L, H, F); required
+ *   dz_re, dz_im [B][L][J], strides d->out_stride_*
+ *   dstate_out   gradient w.r.t. state_out (state-blob layout) or NULL (= zeros: truncated BPTT)
+ *   dmag, dang   [B][L][J], strides d->in_stride_*
+ *   dgamma, dtheta [J] or NULL; dconv_w [2][J][conv_k], dconv_b [2][J] or NULL
+ *   dstate_in    state-blob layout or NULL
+ */
+int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float *ang,
+                              const float *gamma, const float *theta, const float *conv_w,
+                              const float *conv_b, const void *state_in, const void *ckpt,
+                              const float *dz_re, const float *dz_im, const void *dstate_out,
+                              float *dmag, float *dang, float *dgamma, float *dtheta,
+                              float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAWN_H_ */

@@ -1,0 +1,168 @@
+"""Thin ctypes binding of libcawn's C ABI (include/cawn.h): argument marshalling only.
+
+Every step of the hot path runs in the HIP kernels of libcawn.so.  PyTorch tensors are used as
+device-memory handles (``data_ptr()``) and for the current stream; nothing here computes.  If the
+shared library has not been built the import of a function fails loudly -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcawn.so")
+
+CAWN_OK, CAWN_EINVAL, CAWN_EUNSUPPORTED, CAWN_EWORKSPACE, CAWN_ELAUNCH, CAWN_ETIMEOUT = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ["cawn_state_bytes", "cawn_workspace_bytes", "cawn_ckpt_bytes", "cawn_tile_len",
+           "cawn_status_string", "cawn_workspace_init", "cawn_workspace_status", "cawn_set_spin_limit",
+           "cawn_theta_init", "cawn_syntax_conv", "cawn_phase_accumulate_fwd",
+           "cawn_phase_accumulate_bwd"]
+
+
+class cawn_desc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("L", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
+                ("conv_k", C.c_int32), ("amp_mode", C.c_int32), ("gate_mode", C.c_int32),
+                ("gate_tau", C.c_float), ("conv_clamp", C.c_float), ("out_clamp", C.c_float),
+                ("grad_clamp", C.c_float), ("accumulate_param_grads", C.c_int32),
+                ("lane_consts_cached", C.c_int32), ("reserved_", C.c_int32),
+                ("in_stride_b", C.c_int64), ("in_stride_t", C.c_int64),
+                ("out_stride_b", C.c_int64), ("out_stride_t", C.c_int64)]
+
+    @property
+    def J(self) -> int:
+        return self.H * self.F
+
+
+def make_desc(B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
+              grad_clamp=100.0, accumulate_param_grads=0, lane_consts_cached=0, in_stride_b=0,
+              in_stride_t=0, out_stride_b=0, out_stride_t=0) -> cawn_desc:
+    return cawn_desc(B, L, H, F, conv_k, amp_mode, 0, gate_tau, conv_clamp, out_clamp, grad_clamp,
+                     accumulate_param_grads, lane_consts_cached, 0, in_stride_b, in_stride_t,
+                     out_stride_b, out_stride_t)
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libcawn.so; raise if it was not built (python -m paper_2604_04250_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "(hipcc --offload-arch=gfx950); there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        for n in ("cawn_state_bytes", "cawn_workspace_bytes", "cawn_ckpt_bytes"):
+            getattr(L, n).restype = C.c_size_t
+            getattr(L, n).argtypes = [C.POINTER(cawn_desc)]
+        L.cawn_tile_len.restype = C.c_int32
+        L.cawn_status_string.restype = C.c_char_p
+        L.cawn_status_string.argtypes = [C.c_int]
+        L.cawn_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        L.cawn_workspace_status.argtypes = [C.c_void_p, C.c_void_p]
+        L.cawn_set_spin_limit.argtypes = [C.c_uint32]
+        L.cawn_set_spin_limit.restype = None
+        L.cawn_theta_init.argtypes = [C.c_int32, C.c_int32, C.c_void_p]
+        L.cawn_syntax_conv.argtypes = [C.POINTER(cawn_desc), C.c_int32] + [C.c_void_p] * 7
+        L.cawn_phase_accumulate_fwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 13 +
+                                                [C.c_size_t, C.c_void_p])
+        L.cawn_phase_accumulate_bwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 19 +
+                                                [C.c_size_t, C.c_void_p])
+        _lib = L
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda, "libcawn takes device pointers"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def check(status: int) -> None:
+    if status != CAWN_OK:
+        raise RuntimeError(f"libcawn: {cawn_status_string(status)} ({status})")
+
+
+def cawn_state_bytes(d: cawn_desc) -> int:
+    return int(lib().cawn_state_bytes(C.byref(d)))
+
+
+def cawn_workspace_bytes(d: cawn_desc) -> int:
+    return int(lib().cawn_workspace_bytes(C.byref(d)))
+
+
+def cawn_ckpt_bytes(d: cawn_desc) -> int:
+    return int(lib().cawn_ckpt_bytes(C.byref(d)))
+
+
+def cawn_tile_len() -> int:
+    return int(lib().cawn_tile_len())
+
+
+def cawn_status_string(status: int) -> str:
+    return lib().cawn_status_string(int(status)).decode()
+
+
+def cawn_workspace_init(workspace: torch.Tensor, stream=None) -> int:
+    return lib().cawn_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream))
+
+
+def cawn_workspace_status(workspace: torch.Tensor, stream=None) -> int:
+    return lib().cawn_workspace_status(_ptr(workspace), _stream(stream))
+
+
+def cawn_set_spin_limit(polls: int) -> None:
+    lib().cawn_set_spin_limit(int(polls))
+
+
+def cawn_theta_init(H: int, F: int):
+    """Host helper: the paper's rotation-angle initialisation as a float32 numpy array [H*F]."""
+    import numpy as np
+    out = np.empty(H * F, dtype=np.float32)
+    check(lib().cawn_theta_init(H, F, out.ctypes.data_as(C.c_void_p)))
+    return out
+
+
+def cawn_syntax_conv(d, Cch, x, w, bias, conv_state_in, y, conv_state_out, stream=None) -> int:
+    return lib().cawn_syntax_conv(C.byref(d), int(Cch), _ptr(x), _ptr(w), _ptr(bias),
+                                  _ptr(conv_state_in), _ptr(y), _ptr(conv_state_out), _stream(stream))
+
+
+def cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, conv_w, conv_b, state_in, z_re, z_im,
+                              state_out, ckpt, gate_mask, workspace, stream=None) -> int:
+    return lib().cawn_phase_accumulate_fwd(
+        C.byref(d), _ptr(mag), _ptr(ang), _ptr(gamma), _ptr(theta), _ptr(conv_w), _ptr(conv_b),
+        _ptr(state_in), _ptr(z_re), _ptr(z_im), _ptr(state_out), _ptr(ckpt), _ptr(gate_mask),
+        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0,
+        _stream(stream))
+
+
+def cawn_phase_accumulate_bwd(d, mag, ang, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re,
+                              dz_im, dstate_out, dmag, dang, dgamma, dtheta, dconv_w, dconv_b,
+                              dstate_in, workspace, stream=None) -> int:
+    return lib().cawn_phase_accumulate_bwd(
+        C.byref(d), _ptr(mag), _ptr(ang), _ptr(gamma), _ptr(theta), _ptr(conv_w), _ptr(conv_b),
+        _ptr(state_in), _ptr(ckpt), _ptr(dz_re), _ptr(dz_im), _ptr(dstate_out), _ptr(dmag),
+        _ptr(dang), _ptr(dgamma), _ptr(dtheta), _ptr(dconv_w), _ptr(dconv_b), _ptr(dstate_in),
+        _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0,
+        _stream(stream))
+
+
+def alloc_workspace(d: cawn_desc, device="cuda:0") -> torch.Tensor:
+    """Allocate (torch caching allocator, 256-byte aligned) and initialise a workspace for `d`."""
+    n = cawn_workspace_bytes(d)
+    ws = torch.empty((n + 3) // 4, dtype=torch.int32, device=device)
+    check(cawn_workspace_init(ws))
+    return ws

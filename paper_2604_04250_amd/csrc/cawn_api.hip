@@ -1,0 +1,493 @@
+// Host side of libcawn: argument checks, workspace layout, the gate's fp32 breakpoints, the lane
+// table kernel, the stand-alone Temporal Syntax Cache kernel and the parameter-gradient reduction.
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <limits>
+
+#include "cawn_internal.hpp"
+
+namespace cawn {
+
+static std::atomic<uint32_t> g_spin_limit{1u << 26};
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static bool desc_ok(const cawn_desc *d)
+{
+    if (!d) return false;
+    if (d->B <= 0 || d->L < 0 || d->H <= 0 || d->F <= 0) return false;
+    if ((int64_t)d->H * d->F > (1 << 24)) return false;
+    if (d->conv_k < 0) return false;
+    return true;
+}
+
+static WsLayout make_layout(const cawn_desc *d)
+{
+    WsLayout w{};
+    w.J = d->H * d->F;
+    w.Jp = (int)align_up(w.J, 64);
+    w.Jp128 = (int)align_up(w.J, 128);
+    w.nT = (d->L + TILE_T - 1) / TILE_T;
+    const int kc = d->conv_k > MAX_KC ? MAX_KC : d->conv_k;
+    const size_t tiles_rows = (size_t)d->B * (w.nT > 0 ? w.nT : 1);
+    size_t o = sizeof(WsHeader);
+    w.off_flags = o;
+    o += (size_t)MAX_TILES * sizeof(uint32_t);
+    w.off_table = o;
+    o = align_up(o + (size_t)lane_rows(kc) * w.Jp * sizeof(float), 256);
+    w.off_agg = o;
+    o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(float), 256);
+    w.off_pre = o;
+    o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(float), 256);
+    w.off_halo = o;
+    o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(float), 256);
+    w.off_part = o;
+    o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
+    w.total = o;
+    return w;
+}
+
+// ------------------------------------------------------------------------------------------ gate
+// The gate decision |A(X(x))| >= tau is defined on an fp32 quantity x (the conv pre-activation, or
+// the raw magnitude when there is no conv), evaluated in fp64.  It is piecewise monotone in x, so
+// the open set is a union of at most two closed fp32 intervals, found by bisection over the
+// ordered fp32 values.
+namespace {
+struct GateFn {
+    bool fused;
+    int amp_mode;
+    double cc;   // conv clamp
+    double tau;
+    double f(float x) const
+    {
+        double v = (double)x;
+        if (fused) {
+            v = v < -cc ? -cc : (v > cc ? cc : v);
+            v = v / (1.0 + std::exp(-v));   // SiLU
+        }
+        if (amp_mode == 1) {
+            double sp = v > 30.0 ? v + std::log1p(std::exp(-v)) : std::log1p(std::exp(v));
+            v = sp < 10.0 ? sp : 10.0;
+        }
+        return std::fabs(v);
+    }
+    bool open(float x) const { return f(x) >= tau; }
+};
+
+int64_t ord(float x)
+{
+    int32_t b;
+    std::memcpy(&b, &x, 4);
+    return b >= 0 ? (int64_t)b : -(int64_t)(b & 0x7fffffff);
+}
+float unord(int64_t o)
+{
+    int32_t b = o >= 0 ? (int32_t)o : (int32_t)((uint32_t)(-o) | 0x80000000u);
+    float x;
+    std::memcpy(&x, &b, 4);
+    return x;
+}
+
+struct Interval { float lo, hi; bool empty; };
+
+// Open sub-interval of the monotone piece [l, r].
+Interval piece(const GateFn &g, float l, float r, bool increasing)
+{
+    int64_t lo = ord(l), hi = ord(r);
+    if (increasing) {
+        if (!g.open(r)) return {0, 0, true};
+        while (lo < hi) {   // smallest open value
+            int64_t mid = lo + (hi - lo) / 2;
+            if (g.open(unord(mid))) hi = mid; else lo = mid + 1;
+        }
+        return {unord(lo), r, false};
+    }
+    if (!g.open(l)) return {0, 0, true};
+    while (lo < hi) {       // largest open value
+        int64_t mid = lo + (hi - lo + 1) / 2;
+        if (g.open(unord(mid))) lo = mid; else hi = mid - 1;
+    }
+    return {l, unord(lo), false};
+}
+}  // namespace
+
+static bool make_gate_set(const cawn_desc *d, GateSet *out)
+{
+    const float INF = std::numeric_limits<float>::infinity();
+    const float FMAX = std::numeric_limits<float>::max();
+    GateSet gs{INF, -INF, INF, -INF};
+    const double tau = (double)d->gate_tau;
+    if (std::isnan(tau)) { *out = gs; return true; }
+    if (tau <= 0.0) { gs.a1 = -INF; gs.b1 = INF; *out = gs; return true; }
+    GateFn g{d->conv_k > 0, d->amp_mode, (double)d->conv_clamp, tau};
+    const float ZSTAR = -1.2784645f;   // argmin of SiLU
+    Interval iv[3];
+    int n = 0;
+    if (g.fused && g.amp_mode == 0) {
+        iv[n++] = piece(g, -FMAX, ZSTAR, true);
+        iv[n++] = piece(g, ZSTAR, 0.0f, false);
+        iv[n++] = piece(g, 0.0f, FMAX, true);
+    } else if (g.fused) {
+        iv[n++] = piece(g, -FMAX, ZSTAR, false);
+        iv[n++] = piece(g, ZSTAR, FMAX, true);
+    } else if (g.amp_mode == 0) {
+        iv[n++] = piece(g, -FMAX, 0.0f, false);
+        iv[n++] = piece(g, 0.0f, FMAX, true);
+    } else {
+        iv[n++] = piece(g, -FMAX, FMAX, true);
+    }
+    // merge pieces that meet, widen the outer ends to infinity
+    Interval m[3];
+    int k = 0;
+    for (int i = 0; i < n; ++i) {
+        if (iv[i].empty) continue;
+        if (k > 0 && ord(iv[i].lo) <= ord(m[k - 1].hi) + 1) m[k - 1].hi = iv[i].hi;
+        else m[k++] = iv[i];
+    }
+    if (k > 2) return false;
+    for (int i = 0; i < k; ++i) {
+        if (m[i].lo == -FMAX) m[i].lo = -INF;
+        if (m[i].hi == FMAX) m[i].hi = INF;
+    }
+    if (k > 0) { gs.a1 = m[0].lo; gs.b1 = m[0].hi; }
+    if (k > 1) { gs.a2 = m[1].lo; gs.b2 = m[1].hi; }
+    *out = gs;
+    return true;
+}
+
+// ------------------------------------------------------------------------------------ kernels
+__global__ void fill_zero_kernel(uint32_t *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+// One thread per lane: every per-lane constant the scan kernels need, formed in fp64.
+__global__ void lane_table_kernel(const float *__restrict__ gamma, const float *__restrict__ theta,
+                                  const float *__restrict__ conv_w, const float *__restrict__ conv_b,
+                                  float *__restrict__ table, int J, int Jp, int conv_k)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= Jp) return;
+    auto put = [&](int row, double v) { table[(size_t)row * Jp + j] = (float)v; };
+    const bool live = j < J;
+    const double g = live ? (double)gamma[j] : 0.0, th = live ? (double)theta[j] : 0.0;
+    const double c = cos(th), s = sin(th);
+    put(R_LR, g * c);
+    put(R_LI, g * s);
+    put(R_COS, c);
+    put(R_SIN, s);
+    put(R_GAMMA, g);
+    auto power = [&](int n, double &re, double &im) {
+        const double m = n == 0 ? 1.0 : pow(g, (double)n);
+        re = m * cos(n * th);
+        im = m * sin(n * th);
+    };
+    double tr, ti;
+    power(TILE_T, tr, ti);
+    const float hr = (float)tr, hi = (float)ti;
+    put(R_PT_HR, hr);
+    put(R_PT_HI, hi);
+    put(R_PT_LR, tr - (double)hr);
+    put(R_PT_LI, ti - (double)hi);
+    for (int sgi = 0; sgi < Geom::NSEG; ++sgi) {
+        double re, im;
+        power(sgi * Geom::NSTEP, re, im);
+        put(R_PSEG + 2 * sgi, re);
+        put(R_PSEG + 2 * sgi + 1, im);
+    }
+    put(R_BIAS_M, live && conv_b && conv_k > 0 ? (double)conv_b[j] : 0.0);
+    put(R_BIAS_A, live && conv_b && conv_k > 0 ? (double)conv_b[(size_t)J + j] : 0.0);
+    for (int sidx = 0; sidx < 2; ++sidx)
+        for (int i = 0; i < conv_k; ++i)
+            table[(size_t)(R_W0 + sidx * conv_k + i) * Jp + j] =
+                live ? conv_w[((size_t)sidx * J + j) * conv_k + i] : 0.0f;
+}
+
+// Stand-alone Temporal Syntax Cache: one thread per (channel, run of NS tokens).
+template <int KC>
+__global__ __launch_bounds__(256) void syntax_conv_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                          const float *__restrict__ bias,
+                                                          const float *hist_in, float *__restrict__ y,
+                                                          float *hist_out, int B, int L, int C,
+                                                          long long xsb, long long xst, long long ysb,
+                                                          long long yst, float cc, int write_hist_only)
+{
+    constexpr int NS = 8, HALO = KC - 1;
+    const int cblocks = (C + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int c = (blockIdx.x % cblocks) * blockDim.x + threadIdx.x;
+    const int t0 = (blockIdx.x / cblocks) * NS;
+    const int b = blockIdx.y;
+    if (c >= C) return;
+    if (write_hist_only) {
+        // history rows are copied by a second, tiny launch so that hist_in may alias hist_out
+        if (t0 != 0) return;
+        float rows[HALO > 0 ? HALO : 1];
+        for (int q = 0; q < HALO; ++q) {
+            const int t = L - HALO + q;
+            rows[q] = t >= 0 ? x[(size_t)b * xsb + (size_t)t * xst + c]
+                             : (hist_in ? hist_in[((size_t)b * HALO + (t + HALO)) * C + c] : 0.0f);
+        }
+        for (int q = 0; q < HALO; ++q) hist_out[((size_t)b * HALO + q) * C + c] = rows[q];
+        return;
+    }
+    float wk[KC];
+#pragma unroll
+    for (int i = 0; i < KC; ++i) wk[i] = w[(size_t)c * KC + i];
+    const float bs = bias ? bias[c] : 0.0f;
+    float u[NS + HALO];
+#pragma unroll
+    for (int r = 0; r < NS + HALO; ++r) {
+        const int t = t0 - HALO + r;
+        float v = 0.0f;
+        if (t >= 0 && t < L) v = x[(size_t)b * xsb + (size_t)t * xst + c];
+        else if (t < 0 && hist_in && t + HALO >= 0) v = hist_in[((size_t)b * HALO + (t + HALO)) * C + c];
+        u[r] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int t = t0 + i;
+        if (t >= L) break;
+        float z = bs;
+#pragma unroll
+        for (int k = 0; k < KC; ++k) z = __builtin_fmaf(wk[k], u[i + k], z);
+        const float zc = clampf(z, cc);
+        y[(size_t)b * ysb + (size_t)t * yst + c] = zc * sigmoid_fast(zc);
+    }
+}
+
+// Sum the backward tiles' parameter partials in a fixed order: part [nparts][rows][JBpad-blocked].
+// Layout of one partial: [tile][row][JB] with tile = (tt_rev*B + b)*nLB + lb.  Thread (lane, g)
+// sums tiles g, g+G, ... of its lane's block, then the G sub-sums meet in LDS in index order.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, float *__restrict__ out0,
+                                                              float *__restrict__ out1, float *__restrict__ out2,
+                                                              float *__restrict__ out3, int rows, int conv_k, int J,
+                                                              int JB, int nLB, int chains, int accumulate)
+{
+    // grid: (ceil(J/32), rows); block: 32 lanes x 8 groups
+    constexpr int G = 8;
+    __shared__ float sm[G][32];
+    const int lane = threadIdx.x % 32, g = threadIdx.x / 32;
+    const int j = blockIdx.x * 32 + lane;
+    const int row = blockIdx.y;
+    float acc = 0.0f;
+    if (j < J) {
+        const int lb = j / JB, jj = j % JB;
+        for (int c = g; c < chains; c += G) {
+            const size_t tile = (size_t)c * nLB + lb;
+            acc += part[(tile * rows + row) * JB + jj];
+        }
+    }
+    sm[g][lane] = acc;
+    __syncthreads();
+    if (g == 0 && j < J) {
+        float s = 0.0f;
+#pragma unroll
+        for (int q = 0; q < G; ++q) s += sm[q][lane];
+        // rows: 0 dgamma, 1 dtheta, 2 dbias_m, 3 dbias_a, 4 + s*conv_k + i: dw[s][j][i]
+        float *dst = nullptr;
+        if (row == 0) dst = out0 ? out0 + j : nullptr;
+        else if (row == 1) dst = out1 ? out1 + j : nullptr;
+        else if (row < 4) dst = out3 ? out3 + (size_t)(row - 2) * J + j : nullptr;
+        else {
+            const int sidx = (row - 4) / conv_k, i = (row - 4) % conv_k;
+            dst = out2 ? out2 + ((size_t)sidx * J + j) * conv_k + i : nullptr;
+        }
+        if (dst) *dst = accumulate ? *dst + s : s;
+    }
+}
+
+static hipError_t build_table(const cawn_desc *d, const WsLayout &w, char *ws, const float *gamma,
+                              const float *theta, const float *conv_w, const float *conv_b,
+                              hipStream_t s)
+{
+    float *table = reinterpret_cast<float *>(ws + w.off_table);
+    const int threads = 128;
+    hipLaunchKernelGGL(lane_table_kernel, dim3((w.Jp + threads - 1) / threads), dim3(threads), 0, s,
+                       gamma, theta, conv_w, conv_b, table, w.J, w.Jp, d->conv_k);
+    return hipGetLastError();
+}
+
+static bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace cawn
+
+using namespace cawn;
+
+extern "C" {
+
+size_t cawn_state_bytes(const cawn_desc *d)
+{
+    if (!desc_ok(d)) return 0;
+    const size_t J = (size_t)d->H * d->F;
+    const size_t halo = d->conv_k > 1 ? d->conv_k - 1 : 0;
+    return (size_t)d->B * 2 * J * sizeof(float) * (1 + halo);
+}
+
+size_t cawn_workspace_bytes(const cawn_desc *d)
+{
+    if (!desc_ok(d)) return 0;
+    return make_layout(d).total;
+}
+
+size_t cawn_ckpt_bytes(const cawn_desc *d)
+{
+    if (!desc_ok(d)) return 0;
+    const size_t nT = (d->L + TILE_T - 1) / TILE_T;
+    return (size_t)d->B * nT * 2 * d->H * d->F * sizeof(float);
+}
+
+int32_t cawn_tile_len(void) { return TILE_T; }
+
+const char *cawn_status_string(int st)
+{
+    switch (st) {
+    case CAWN_OK: return "ok";
+    case CAWN_EINVAL: return "invalid argument";
+    case CAWN_EUNSUPPORTED: return "unsupported configuration";
+    case CAWN_EWORKSPACE: return "workspace too small or misaligned";
+    case CAWN_ELAUNCH: return "HIP launch or copy failed";
+    case CAWN_ETIMEOUT: return "a tile gave up waiting for its predecessor's carry";
+    default: return "unknown status";
+    }
+}
+
+int cawn_workspace_init(void *workspace, size_t bytes, void *stream)
+{
+    const size_t need = sizeof(WsHeader) + (size_t)MAX_TILES * sizeof(uint32_t);
+    if (!workspace) return CAWN_EINVAL;
+    if (bytes < need || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream,
+                       reinterpret_cast<uint32_t *>(workspace), need / sizeof(uint32_t));
+    return hipGetLastError() == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
+}
+
+int cawn_workspace_status(void *workspace, void *stream)
+{
+    if (!workspace) return CAWN_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CAWN_ELAUNCH;
+    uint32_t err = 0;
+    WsHeader *h = reinterpret_cast<WsHeader *>(workspace);
+    if (hipMemcpy(&err, &h->error, sizeof(err), hipMemcpyDeviceToHost) != hipSuccess) return CAWN_ELAUNCH;
+    if (err) {
+        uint32_t zero = 0;
+        if (hipMemcpy(&h->error, &zero, sizeof(zero), hipMemcpyHostToDevice) != hipSuccess) return CAWN_ELAUNCH;
+        return CAWN_ETIMEOUT;
+    }
+    return CAWN_OK;
+}
+
+void cawn_set_spin_limit(uint32_t polls) { g_spin_limit.store(polls); }
+
+int cawn_theta_init(int32_t H, int32_t F, float *theta_host)
+{
+    if (H <= 0 || F <= 0 || !theta_host) return CAWN_EINVAL;
+    const int64_t J = (int64_t)H * F;
+    for (int64_t j = 0; j < J; ++j)
+        theta_host[j] = (float)std::pow(10000.0, -2.0 * (double)j / (double)J);
+    return CAWN_OK;
+}
+
+int cawn_syntax_conv(const cawn_desc *d, int32_t C, const float *x, const float *w, const float *bias,
+                     const float *conv_state_in, float *y, float *conv_state_out, void *stream)
+{
+    if (!d || d->B <= 0 || d->L < 0 || C <= 0 || !w) return CAWN_EINVAL;
+    if (d->conv_k < 1) return CAWN_EINVAL;
+    if (d->conv_k > MAX_KC) return CAWN_EUNSUPPORTED;
+    if (d->L > 0 && (!x || !y)) return CAWN_EINVAL;
+    const long long xst = d->in_stride_t ? d->in_stride_t : C, xsb = d->in_stride_b ? d->in_stride_b : (long long)d->L * C;
+    const long long yst = d->out_stride_t ? d->out_stride_t : C, ysb = d->out_stride_b ? d->out_stride_b : (long long)d->L * C;
+    if (xst < C || yst < C) return CAWN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int NS = 8;
+    const dim3 block(256);
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 0 && d->L == 0) continue;
+        if (pass == 1 && (!conv_state_out || d->conv_k == 1)) continue;
+        const long long nblk = (long long)((C + 255) / 256) * (pass == 0 ? (d->L + NS - 1) / NS : 1);
+        if (nblk > 0x7fffffffLL || d->B > 65535) return CAWN_EUNSUPPORTED;
+        const dim3 grid((unsigned)nblk, d->B, 1);
+#define CAWN_CONV_CASE(K)                                                                          \
+    case K:                                                                                        \
+        hipLaunchKernelGGL((syntax_conv_kernel<K>), grid, block, 0, s, x, w, bias, conv_state_in, y, \
+                           conv_state_out, d->B, d->L, C, xsb, xst, ysb, yst, d->conv_clamp, pass); \
+        break;
+        switch (d->conv_k) {
+            CAWN_CONV_CASE(1) CAWN_CONV_CASE(2) CAWN_CONV_CASE(3) CAWN_CONV_CASE(4)
+        }
+#undef CAWN_CONV_CASE
+        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+    }
+    return CAWN_OK;
+}
+
+int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
+                              const float *theta, const float *conv_w, const float *conv_b,
+                              const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
+                              uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->gate_mode != 0 || d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    const WsLayout w = make_layout(d);
+    const long long J = w.J;
+    if (d->L == 0) {   // nothing to scan: the state passes through
+        if (state_out && state_out != state_in) {
+            const size_t nb = cawn_state_bytes(d);
+            hipError_t e;
+            if (state_in) {
+                e = hipMemcpyAsync(state_out, state_in, nb, hipMemcpyDeviceToDevice, s);
+            } else {   // a fill kernel rather than a memset node: safe under graph capture
+                hipLaunchKernelGGL(fill_zero_kernel, dim3(64), dim3(256), 0, s,
+                                   reinterpret_cast<uint32_t *>(state_out), nb / sizeof(uint32_t));
+                e = hipGetLastError();
+            }
+            if (e != hipSuccess) return CAWN_ELAUNCH;
+        }
+        return CAWN_OK;
+    }
+    if (!mag || !ang || !gamma || !theta || !z_re || !z_im || !workspace) return CAWN_EINVAL;
+    if (d->conv_k > 0 && !conv_w) return CAWN_EINVAL;
+    if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
+    const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
+    const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
+    if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
+
+    FwdArgs a{};
+    if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;
+    const bool vec = (J % FwdV == 0) && (ist % FwdV == 0) && (isb % FwdV == 0) && (ost % FwdV == 0) &&
+                     (osb % FwdV == 0) && aligned(mag, 16) && aligned(ang, 16) && aligned(z_re, 16) &&
+                     aligned(z_im, 16) && (!state_in || aligned(state_in, 16)) &&
+                     (!state_out || aligned(state_out, 16)) && (!ckpt || aligned(ckpt, 16));
+    const int JB = (vec ? FwdV : 1) * FwdLPR;
+    const int nLB = (int)((J + JB - 1) / JB);
+    const size_t tiles = (size_t)d->B * w.nT * nLB;
+    if (tiles > MAX_TILES) return CAWN_EUNSUPPORTED;
+
+    char *ws = reinterpret_cast<char *>(workspace);
+    if (!d->lane_consts_cached) {
+        if (build_table(d, w, ws, gamma, theta, conv_w, conv_b, s) != hipSuccess) return CAWN_ELAUNCH;
+    }
+    a.mag = mag; a.ang = ang;
+    a.table = reinterpret_cast<const float *>(ws + w.off_table);
+    a.state_in = reinterpret_cast<const float *>(state_in);
+    a.z_re = z_re; a.z_im = z_im;
+    a.state_out = reinterpret_cast<float *>(state_out);
+    a.ckpt = reinterpret_cast<float *>(ckpt);
+    a.mask = gate_mask;
+    a.hdr = reinterpret_cast<WsHeader *>(ws);
+    a.flags = reinterpret_cast<uint32_t *>(ws + w.off_flags);
+    a.agg = reinterpret_cast<float *>(ws + w.off_agg);
+    a.pre = reinterpret_cast<float *>(ws + w.off_pre);
+    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
+    a.amp_mode = d->amp_mode;
+    a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
+    a.conv_clamp = d->conv_clamp; a.out_clamp = d->out_clamp;
+    a.spin_limit = g_spin_limit.load();
+    a.total_tiles = (uint32_t)tiles;
+    if (launch_fwd(a, d->conv_k, vec, s) != hipSuccess) return CAWN_ELAUNCH;
+    return CAWN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,165 @@
+// Internal definitions shared by the libcawn translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cawn.h"
+
+namespace cawn {
+
+// ------------------------------------------------------------------------------------ geometry
+// One tile = JB lanes x TILE_T tokens of one batch row, owned by one workgroup.  A thread owns
+// V adjacent lanes and NSTEP consecutive tokens ("segment"); NSEG segments make the tile.
+constexpr int TILE_T = 64;           // tokens per tile: granularity of carries and checkpoints
+
+struct Geom {
+    static constexpr int NSTEP = 8, NSEG = TILE_T / NSTEP;
+};
+constexpr int FwdV = 4, FwdLPR = 32;  // forward: float4 per thread, 32 threads per row, 256 threads
+constexpr int BwdV = 2, BwdLPR = 32;  // backward: float2 per thread (it keeps more per token)
+constexpr int MAX_KC = 4;
+constexpr uint32_t MAX_TILES = 1u << 20;   // capacity of the fixed tile-status zone
+
+// ---------------------------------------------------------------------------------- lane table
+// Per-lane constants, struct-of-arrays, each row Jp floats (Jp = J rounded up to 64), built in
+// fp64 by a small kernel from gamma, theta, conv_w, conv_b.
+enum LaneRow : int {
+    R_LR = 0, R_LI,            // lambda = gamma e^{i theta}
+    R_COS, R_SIN, R_GAMMA,     // e^{i theta}, gamma
+    R_PT_HR, R_PT_HI,          // lambda^TILE_T, leading fp32 part
+    R_PT_LR, R_PT_LI,          //                 remainder (double-float)
+    R_BIAS_M, R_BIAS_A,
+    R_PSEG,                    // R_PSEG + 2*s (+1): re (im) of lambda^(NSTEP*s), s = 0..NSEG-1
+    R_W0 = R_PSEG + 2 * Geom::NSEG   // R_W0 + s*conv_k + i : tap i of stream s
+};
+inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k; }
+
+// ----------------------------------------------------------------------------------- workspace
+// Workspace: [header 256 B][tile status words, fixed MAX_TILES capacity][lane table][aggregates]
+// [prefixes][backward conv halo][backward parameter partials].  Header and status words are zero
+// between calls (the tile that finishes last clears them), whatever descriptor the last call had.
+struct WsHeader {
+    uint32_t ticket;           // next tile to hand out
+    uint32_t done;             // tiles that have finished their look-back
+    uint32_t error;            // sticky: a tile gave up waiting
+    uint32_t pad[61];
+};
+static_assert(sizeof(WsHeader) == 256, "header size");
+
+struct WsLayout {
+    int J, Jp, Jp128, nT;
+    size_t off_flags, off_table, off_agg, off_pre, off_halo, off_part, total;
+};
+
+// Tile status words of the decoupled look-back.
+constexpr uint32_t ST_NONE = 0, ST_AGG = 1, ST_PREFIX = 2, ST_HALO = 3;
+
+// Gate as a union of two closed fp32 intervals on the quantity the decision is taken on (the
+// fp32 conv pre-activation, or the raw magnitude input when there is no conv).
+struct GateSet { float a1, b1, a2, b2; };
+
+struct FwdArgs {
+    const float *mag, *ang;
+    const float *table;          // lane table
+    const float *state_in;       // may be null
+    float *z_re, *z_im;
+    float *state_out;            // may be null
+    float *ckpt;                 // may be null
+    uint32_t *mask;              // may be null
+    WsHeader *hdr;
+    uint32_t *flags;
+    float *agg, *pre;
+    int B, L, J, Jp, nT, nLB;
+    int amp_mode;
+    long long isb, ist, osb, ost;
+    float conv_clamp, out_clamp;
+    GateSet gs;
+    uint32_t spin_limit;
+    uint32_t total_tiles;
+};
+
+struct BwdArgs {
+    const float *mag, *ang, *dz_re, *dz_im;
+    const float *table;
+    const float *state_in;       // may be null
+    const float *ckpt;           // may be null when no dgamma/dtheta
+    const float *dstate_out;     // may be null
+    float *dmag, *dang;
+    float *dstate_in;            // may be null
+    WsHeader *hdr;
+    uint32_t *flags;
+    float *agg, *pre, *halo, *part;
+    int B, L, J, Jp, nT, nLB;
+    int amp_mode, want_param;
+    long long isb, ist, osb, ost;
+    float conv_clamp, grad_clamp;
+    GateSet gs;
+    uint32_t spin_limit;
+    uint32_t total_tiles;
+};
+
+// Number of per-lane partial sums a backward tile emits: dgamma, dtheta, dbias[2], dw[2][conv_k].
+inline __host__ __device__ int part_rows(int conv_k) { return 4 + 2 * conv_k; }
+
+hipError_t launch_fwd(const FwdArgs &a, int conv_k, bool vec4, hipStream_t s);
+hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s);
+
+#if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
+// ------------------------------------------------------------------------------ device helpers
+__device__ __forceinline__ float clampf(float v, float c) { return __builtin_fminf(__builtin_fmaxf(v, -c), c); }
+
+// sigmoid(z) with the hardware exp2 / reciprocal (both ~1 ulp).
+__device__ __forceinline__ float sigmoid_fast(float z)
+{
+    float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * z);
+    return __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// sin and cos of an angle in radians: two-term Cody-Waite reduction to [-pi, pi] (exact products
+// through fma), then the hardware sin/cos, which take revolutions.
+__device__ __forceinline__ void sincos_fast(float phi, float &s, float &c)
+{
+    const float INV_2PI = 0.15915494309189535f;
+    const float TWO_PI_HI = 6.2831854820251465f;      // fp32(2 pi)
+    const float TWO_PI_LO = -1.7484555314695172e-07f; // 2 pi - TWO_PI_HI
+    float k = __builtin_rintf(phi * INV_2PI);
+    float r = __builtin_fmaf(-k, TWO_PI_HI, phi);
+    r = __builtin_fmaf(-k, TWO_PI_LO, r);
+    float x = r * INV_2PI;
+    s = __builtin_amdgcn_sinf(x);
+    c = __builtin_amdgcn_cosf(x);
+}
+
+__device__ __forceinline__ float softplus_fast(float m)
+{
+    // log(1 + e^m) = max(m, 0) + log(1 + e^-|m|)
+    float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * __builtin_fabsf(m));
+    return __builtin_fmaxf(m, 0.0f) + 0.6931471805599453f * __builtin_amdgcn_logf(1.0f + e);
+}
+
+__device__ __forceinline__ bool in_gate(const GateSet &g, float x)
+{
+    return (x >= g.a1 && x <= g.b1) || (x >= g.a2 && x <= g.b2);
+}
+
+// Agent-scope publication helpers (tiles may sit on different XCDs, whose L2s are not coherent
+// with each other without these).
+__device__ __forceinline__ void flag_store_release(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t flag_load_acquire(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+#endif
+
+}  // namespace cawn

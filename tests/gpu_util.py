@@ -1,0 +1,110 @@
+"""Helpers for the GPU parity tests: run libcawn through its C ABI on numpy inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2604_04250_amd import binding as K
+
+DEV = "cuda:0"
+
+
+def rel_err(gpu, ora):
+    """max_i |gpu_i - ora_i| / max(|ora_i|, rms(ora)): element-wise relative error with an rms
+    floor, because interference cancels some outputs to ~0."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ora = np.asarray(ora, dtype=np.float64)
+    if ora.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ora * ora)))
+    den = np.maximum(np.abs(ora), max(rms, 1e-30))
+    return float(np.max(np.abs(gpu - ora) / den))
+
+
+def dev(a):
+    if a is None or isinstance(a, torch.Tensor):
+        return a
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def pack_state(scan, tail):
+    """[B,2,J] and [B,Kc-1,2,J] float32 -> flat state blob."""
+    parts = [np.asarray(scan, np.float32).ravel()]
+    if tail is not None and tail.size:
+        parts.append(np.asarray(tail, np.float32).ravel())
+    return np.concatenate(parts)
+
+
+def unpack_state(blob, B, J, Kc):
+    blob = np.asarray(blob)
+    scan = blob[:B * 2 * J].reshape(B, 2, J)
+    tail = blob[B * 2 * J:].reshape(B, max(Kc - 1, 0), 2, J) if Kc > 1 else None
+    return scan, tail
+
+
+class Workspaces:
+    """One workspace per size, initialised once and reused across calls (as a caller would)."""
+    _cache = {}
+
+    @classmethod
+    def get(cls, d):
+        n = K.cawn_workspace_bytes(d)
+        ws = cls._cache.get("ws")
+        if ws is None or ws.numel() * 4 < n:
+            ws = torch.empty((max(n, 8 << 20) + 3) // 4, dtype=torch.int32, device=DEV)
+            K.check(K.cawn_workspace_init(ws))
+            cls._cache["ws"] = ws
+        return ws
+
+
+def run_fwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
+            state_in=None, want_mask=True, want_ckpt=False, concat=False, in_place_state=False,
+            cached=0, ws=None):
+    """inp: dict with mag, ang [B,L,J], gamma, theta, conv_w, conv_b (numpy float32).
+    Returns dict(z_re, z_im, state_out (flat blob), mask [B,L,W] uint32, ckpt)."""
+    J = H * F
+    d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau,
+                    conv_clamp=conv_clamp, out_clamp=out_clamp, lane_consts_cached=cached)
+    mag, ang = dev(inp["mag"][:, :L]), dev(inp["ang"][:, :L])
+    gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
+    cw = dev(inp["conv_w"]) if conv_k > 0 else None
+    cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
+    if concat:
+        z = torch.full((B, max(L, 1), 2 * J), float("nan"), device=DEV)
+        z_re, z_im = z[:, :, :J], z[:, :, J:]
+        d.out_stride_t, d.out_stride_b = 2 * J, max(L, 1) * 2 * J
+    else:
+        z_re = torch.full((B, max(L, 1), J), float("nan"), device=DEV)
+        z_im = torch.full((B, max(L, 1), J), float("nan"), device=DEV)
+    nstate = K.cawn_state_bytes(d) // 4
+    st_in = dev(state_in) if state_in is not None else None
+    if in_place_state:
+        assert st_in is not None
+        st_out = st_in
+    else:
+        st_out = torch.full((nstate,), float("nan"), device=DEV)
+    W = (J + 31) // 32
+    mask = torch.zeros((B, max(L, 1), W), dtype=torch.int32, device=DEV) if want_mask else None
+    ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV) if want_ckpt else None
+    ws = ws if ws is not None else Workspaces.get(d)
+    K.check(K.cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, cw, cb, st_in, z_re, z_im, st_out,
+                                        ckpt, mask, ws))
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    out = dict(z_re=z_re[:, :L].cpu().numpy(), z_im=z_im[:, :L].cpu().numpy(),
+               state_out=st_out.cpu().numpy())
+    if want_mask:
+        out["mask"] = mask[:, :L].cpu().numpy().view(np.uint32)
+    if want_ckpt:
+        out["ckpt"] = ckpt.cpu().numpy()
+    return out
+
+
+def mask_from_gate(gate):
+    """oracle gate bytes [B,L,J] -> packed uint32 words [B,L,ceil(J/32)], bit j%32 of word j/32."""
+    B, L, J = gate.shape
+    W = (J + 31) // 32
+    g = np.zeros((B, L, W * 32), dtype=np.uint8)
+    g[..., :J] = gate
+    bits = np.packbits(g.reshape(B, L, W, 32), axis=-1, bitorder="little")   # 4 bytes, little endian
+    return bits.view("<u4").reshape(B, L, W)

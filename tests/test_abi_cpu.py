@@ -1,0 +1,93 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, its
+size helpers and host-side argument checks behave, and its host helper for the rotation angles
+agrees with the oracle's.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import cawn_oracle as O
+from paper_2604_04250_amd import binding as K
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "cawn.h")).read()
+    declared = sorted(set(re.findall(r"\b(cawn_[a-z_]+)\s*\(", hdr)))
+    assert declared == sorted(K.EXPORTS)
+    lib = K.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_desc_struct_matches_header_field_order():
+    hdr = open(os.path.join(ROOT, "include", "cawn.h")).read()
+    body = re.search(r"typedef struct cawn_desc \{(.*?)\} cawn_desc;", hdr, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        typ, rest = decl.split(None, 1)
+        names += [n.strip() for n in rest.split(",")]
+    assert names == [f[0] for f in K.cawn_desc._fields_]
+    assert C.sizeof(K.cawn_desc) == 14 * 4 + 4 * 8
+
+
+def test_size_helpers():
+    d = K.make_desc(4, 2048, 12, 64, conv_k=4)
+    J = 768
+    assert K.cawn_state_bytes(d) == 4 * 2 * J * 4 * (1 + 3)
+    T = K.cawn_tile_len()
+    assert T == 64
+    assert K.cawn_ckpt_bytes(d) == 4 * (2048 // T) * 2 * J * 4
+    small = K.cawn_workspace_bytes(K.make_desc(1, 64, 12, 64, conv_k=4))
+    big = K.cawn_workspace_bytes(d)
+    assert big > small > (1 << 22)            # fixed status zone + per-tile carries
+    assert big % 256 == 0
+    assert K.cawn_state_bytes(K.make_desc(0, 1, 1, 1)) == 0      # invalid descriptor
+    assert K.cawn_state_bytes(K.make_desc(2, 5, 1, 8, conv_k=0)) == 2 * 2 * 8 * 4
+
+
+def test_status_strings():
+    for s in (0, -1, -2, -3, -4, -5):
+        assert K.cawn_status_string(s) and K.cawn_status_string(s) != "unknown status"
+    assert K.cawn_status_string(-99) == "unknown status"
+
+
+def test_theta_init_matches_the_oracle_bitwise():
+    for H, F in ((12, 64), (4, 64), (32, 128), (2, 16)):
+        a, b = K.cawn_theta_init(H, F), O.theta_init(H, F)
+        assert a.dtype == np.float32 and np.array_equal(a, b)
+    assert K.lib().cawn_theta_init(0, 4, None) == K.CAWN_EINVAL
+
+
+def test_host_side_argument_checks_reject_before_any_launch():
+    L = K.lib()
+    null = C.c_void_p(None)
+    d = K.make_desc(2, 128, 2, 16, conv_k=4)
+    args = [null] * 13
+    assert L.cawn_phase_accumulate_fwd(C.byref(d), *args, 0, null) == K.CAWN_EINVAL
+    assert L.cawn_phase_accumulate_fwd(None, *args, 0, null) == K.CAWN_EINVAL
+    bad = K.make_desc(2, 128, 2, 16, conv_k=9)
+    assert L.cawn_phase_accumulate_fwd(C.byref(bad), *args, 0, null) == K.CAWN_EUNSUPPORTED
+    bad = K.make_desc(2, 128, 2, 16)
+    bad.gate_mode = 1
+    assert L.cawn_phase_accumulate_fwd(C.byref(bad), *args, 0, null) == K.CAWN_EUNSUPPORTED
+    assert L.cawn_phase_accumulate_fwd(C.byref(K.make_desc(-1, 1, 1, 1)), *args, 0, null) == K.CAWN_EINVAL
+    # workspace too small / misaligned: fake non-null pointers are never dereferenced on the host
+    fake = C.c_void_p(0x1000)
+    a2 = [fake] * 4 + [fake, fake, null, fake, fake, null, null, null]
+    assert L.cawn_phase_accumulate_fwd(C.byref(d), *a2, fake, 16, null) == K.CAWN_EWORKSPACE
+    assert L.cawn_phase_accumulate_fwd(C.byref(d), *a2, C.c_void_p(0x1004), 1 << 30, null) == K.CAWN_EWORKSPACE
+    strided = K.make_desc(2, 128, 2, 16, in_stride_t=8)           # stride shorter than a row
+    assert L.cawn_phase_accumulate_fwd(C.byref(strided), *a2, fake, 1 << 30, null) == K.CAWN_EINVAL
+    assert L.cawn_syntax_conv(C.byref(K.make_desc(1, 4, 1, 1, conv_k=0)), 8, *([fake] * 6), null) == K.CAWN_EINVAL
+    assert L.cawn_workspace_init(null, 1 << 30, null) == K.CAWN_EINVAL
+    assert L.cawn_workspace_init(fake, 16, null) == K.CAWN_EWORKSPACE
+    args_b = [null] * 19
+    assert L.cawn_phase_accumulate_bwd(C.byref(d), *args_b, 0, null) != K.CAWN_OK

@@ -1,0 +1,239 @@
+"""GPU parity: libcawn forward (through the C ABI) against the fp64 oracle, element by element.
+
+Bar: max relative error (rms-floored, see gpu_util.rel_err) <= 1e-4 in fp32; gate masks bit-exact;
+conv history rows bit-exact (they are copies).
+"""
+import numpy as np
+import pytest
+
+from oracle import cawn_oracle as O
+from paper_2604_04250_amd import workloads as WL
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+INF = float("inf")
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+def _inputs(B, L, H, F, Kc, seed, gamma=(0.9, 0.999), ang_scale=1.0, bias=True):
+    r = np.random.Generator(np.random.PCG64(seed))
+    J = H * F
+    d = dict(mag=r.standard_normal((B, L, J), dtype=np.float32),
+             ang=(ang_scale * r.standard_normal((B, L, J))).astype(np.float32),
+             gamma=r.uniform(gamma[0], gamma[1], J).astype(np.float32),
+             theta=r.uniform(0, np.pi, J).astype(np.float32))
+    kk = max(Kc, 1)
+    d["conv_w"] = (r.standard_normal((2, J, kk)) / np.sqrt(kk)).astype(np.float32)
+    d["conv_b"] = (0.1 * r.standard_normal((2, J))).astype(np.float32) if bias else np.zeros((2, J), np.float32)
+    return d
+
+
+def _check(B, L, H, F, Kc, d, tau=0.1, amp_mode=0, state=None, conv_clamp=50.0, out_clamp=100.0, **kw):
+    G = _gpu()
+    J = H * F
+    scan_in = tail_in = blob = None
+    if state is not None:
+        scan_in, tail_in = state
+        blob = G.pack_state(scan_in, tail_in if Kc > 1 else None)
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, conv_clamp=conv_clamp, out_clamp=out_clamp)
+    ora = O.phase_fwd(cfg, d["mag"][:, :L], d["ang"][:, :L], d["gamma"], d["theta"],
+                      conv_w=d["conv_w"], conv_b=d["conv_b"],
+                      scan_in=None if scan_in is None else scan_in.astype(np.float64),
+                      tail_in=tail_in if Kc > 1 else None)
+    out = G.run_fwd(d, B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, conv_clamp=conv_clamp,
+                    out_clamp=out_clamp, state_in=blob, **kw)
+    if L > 0:
+        e_re, e_im = G.rel_err(out["z_re"], ora["z_re"]), G.rel_err(out["z_im"], ora["z_im"])
+        assert e_re <= TOL and e_im <= TOL, (e_re, e_im)
+        assert np.array_equal(out["mask"], G.mask_from_gate(ora["gate"])), "gate mask differs"
+    scan, tail = G.unpack_state(out["state_out"], B, J, Kc)
+    if L > 0 or state is not None:
+        assert G.rel_err(scan, ora["scan_out"]) <= TOL
+        if Kc > 1:
+            assert np.array_equal(tail, ora["tail_out"])
+    return out, ora
+
+
+def test_cfg1_tiny_fused_and_plain():
+    wl = WL.CONFIGS["cfg1_tiny"]
+    d = WL.make_inputs(wl)
+    out, ora = _check(wl.B, wl.L, wl.H, wl.F, wl.conv_k, d, tau=wl.gate_tau)
+    closed = 1 - ora["gate"].mean()
+    assert 0.0 < closed < 0.6
+    out, ora = _check(wl.B, wl.L, wl.H, wl.F, 0, d, tau=wl.gate_tau)
+    assert abs((1 - ora["gate"].mean()) - 0.0797) < 0.02     # P(|N(0,1)| < 0.1)
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 7, 8, 9, 63, 64, 65, 127, 128, 200, 517])
+@pytest.mark.parametrize("Kc", [0, 4])
+def test_ragged_lengths_span_tiles(L, Kc):
+    B, H, F = 2, 2, 16
+    d = _inputs(B, L, H, F, Kc, 100 + L)
+    st = WL.random_state(WL.Workload("x", B, H, F, L, conv_k=Kc), seed=7)
+    _check(B, L, H, F, Kc, d, state=st)
+
+
+@pytest.mark.parametrize("H,F", [(12, 64), (1, 100), (3, 12), (1, 1), (5, 7), (2, 130)])
+def test_lane_counts_vector_and_scalar_paths(H, F):
+    B, L, Kc = 2, 300, 4
+    d = _inputs(B, L, H, F, Kc, 200 + H * F)
+    _check(B, L, H, F, Kc, d, tau=0.25)
+
+
+@pytest.mark.parametrize("Kc", [1, 2, 3, 4])
+def test_conv_tap_counts(Kc):
+    B, L, H, F = 2, 150, 2, 32
+    d = _inputs(B, L, H, F, Kc, 300 + Kc)
+    st = WL.random_state(WL.Workload("x", B, H, F, L, conv_k=Kc), seed=8)
+    _check(B, L, H, F, Kc, d, state=st)
+
+
+def test_long_chain_high_retention():
+    # 256 tiles in one chain, retention up to 0.9999: the carry path dominates the result
+    B, L, H, F = 1, 16384, 2, 32
+    d = _inputs(B, L, H, F, 4, 400, gamma=(0.99, 0.9999))
+    _check(B, L, H, F, 4, d)
+
+
+def test_chunked_streaming_in_place_state_matches_one_pass():
+    G = _gpu()
+    B, L, H, F, Kc = 2, 1000, 4, 32, 4
+    J = H * F
+    d = _inputs(B, L, H, F, Kc, 500, gamma=(0.99, 0.9999))
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=0.1)
+    ora = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"])
+    import torch
+    state = torch.zeros(B * 2 * J * Kc, device=G.DEV)        # zero state = sequence start
+    t0 = 0
+    zr, zi = [], []
+    for n in (64, 1, 2, 190, 3, 300, 440):
+        sub = {k: (v[:, t0:t0 + n] if k in ("mag", "ang") else v) for k, v in d.items()}
+        out = G.run_fwd(sub, B, n, H, F, conv_k=Kc, gate_tau=0.1, state_in=state, in_place_state=True,
+                        cached=1 if t0 else 0)
+        state = G.dev(out["state_out"])
+        zr.append(out["z_re"]); zi.append(out["z_im"])
+        t0 += n
+    assert t0 == L
+    assert G.rel_err(np.concatenate(zr, 1), ora["z_re"]) <= TOL
+    assert G.rel_err(np.concatenate(zi, 1), ora["z_im"]) <= TOL
+    scan, tail = G.unpack_state(out["state_out"], B, J, Kc)
+    assert G.rel_err(scan, ora["scan_out"]) <= TOL
+    assert np.array_equal(tail, ora["tail_out"])
+
+
+def test_zero_length_call_passes_state_through():
+    G = _gpu()
+    B, H, F, Kc = 2, 2, 16, 4
+    st = WL.random_state(WL.Workload("x", B, H, F, 0, conv_k=Kc), seed=9)
+    d = _inputs(B, 1, H, F, Kc, 600)
+    out = G.run_fwd(d, B, 0, H, F, conv_k=Kc, state_in=G.pack_state(*st), want_mask=False)
+    assert np.array_equal(out["state_out"], G.pack_state(*st))
+    out = G.run_fwd(d, B, 0, H, F, conv_k=Kc, state_in=None, want_mask=False)
+    assert not out["state_out"].any()
+
+
+def test_concat_output_layout_and_checkpoints():
+    G = _gpu()
+    B, L, H, F, Kc = 2, 200, 2, 32, 4
+    d = _inputs(B, L, H, F, Kc, 700)
+    out, ora = _check(B, L, H, F, Kc, d, concat=True, want_ckpt=True)
+    # checkpoints = unclamped state entering each 64-token tile
+    T = 64
+    nT = (L + T - 1) // T
+    ck = out["ckpt"].reshape(B, nT, 2, H * F)
+    for i in range(nT):
+        if i == 0:
+            assert not ck[:, 0].any()
+            continue
+        o = O.phase_fwd(O.Cfg(B, i * T, H, F, conv_k=Kc, gate_tau=0.1), d["mag"][:, :i * T], d["ang"][:, :i * T],
+                        d["gamma"], d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"])
+        assert G.rel_err(ck[:, i], o["scan_out"]) <= TOL
+
+
+def test_large_angles_without_conv():
+    B, L, H, F = 1, 300, 2, 32
+    d = _inputs(B, L, H, F, 0, 800, ang_scale=3000.0)
+    assert np.abs(d["ang"]).max() > 8000
+    _check(B, L, H, F, 0, d)
+
+
+def test_conv_clamp_and_output_clamp_saturate():
+    B, L, H, F, Kc = 1, 400, 1, 32, 4
+    d = _inputs(B, L, H, F, Kc, 900, gamma=(0.999, 1.0))
+    d["mag"] *= 40.0        # pre-activations beyond +-50
+    d["gamma"][:4] = 1.0
+    out, ora = _check(B, L, H, F, Kc, d, tau=0.0)
+    assert (np.abs(ora["z_re"]) == 100.0).any()
+    assert np.abs(ora["scan_out"]).max() > 100.0
+
+
+@pytest.mark.parametrize("Kc", [0, 3])
+def test_amplitude_softplus_mode(Kc):
+    B, L, H, F = 2, 130, 2, 32
+    d = _inputs(B, L, H, F, Kc, 1000 + Kc)
+    d["mag"] *= 6.0
+    _check(B, L, H, F, Kc, d, tau=0.6, amp_mode=1)
+
+
+@pytest.mark.parametrize("tau", [0.0, 1e-3, 0.1, 0.25, 0.2784, 0.3, 5.0, INF])
+def test_gate_thresholds_bit_exact(tau):
+    B, L, H, F, Kc = 2, 256, 2, 32, 4
+    d = _inputs(B, L, H, F, Kc, 1100)
+    _check(B, L, H, F, Kc, d, tau=tau)
+    _check(B, L, H, F, 0, d, tau=tau)
+
+
+def test_standalone_syntax_conv():
+    import torch
+    G = _gpu()
+    from paper_2604_04250_amd import binding as K
+    r = np.random.Generator(np.random.PCG64(1200))
+    for Kc in (1, 3, 4):
+        B, L, Cc = 2, 77, 200
+        x = (10 * r.standard_normal((B, L, Cc))).astype(np.float32)
+        w = r.standard_normal((Cc, Kc)).astype(np.float32)
+        bias = r.standard_normal(Cc).astype(np.float32)
+        hist = r.standard_normal((B, max(Kc - 1, 0), Cc)).astype(np.float32)
+        y_o, h_o = O.syntax_conv(x, w, bias, hist if Kc > 1 else None)
+        d = K.make_desc(B, L, 1, 1, conv_k=Kc)
+        y = torch.empty((B, L, Cc), device=G.DEV)
+        h = G.dev(hist) if Kc > 1 else None
+        K.check(K.cawn_syntax_conv(d, Cc, G.dev(x), G.dev(w), G.dev(bias), h, y, h))   # history in place
+        torch.cuda.synchronize()
+        assert G.rel_err(y.cpu().numpy(), y_o) <= TOL
+        if Kc > 1:
+            assert np.array_equal(h.cpu().numpy(), h_o)
+
+
+def test_spin_limit_timeout_is_reported_and_every_wave_exits():
+    # a tiny spin limit forces tiles to give up; the kernel must still drain and flag the workspace
+    G = _gpu()
+    from paper_2604_04250_amd import binding as K
+    import torch
+    B, L, H, F = 4, 8192, 12, 64
+    d = _inputs(B, L, H, F, 4, 1300)
+    desc = K.make_desc(B, L, H, F, conv_k=4, gate_tau=0.1)
+    ws = torch.empty((K.cawn_workspace_bytes(desc) + 3) // 4, dtype=torch.int32, device=G.DEV)
+    K.check(K.cawn_workspace_init(ws))
+    K.cawn_set_spin_limit(0)
+    try:
+        z = torch.empty((2, B, L, H * F), device=G.DEV)
+        st = K.cawn_phase_accumulate_fwd(desc, G.dev(d["mag"]), G.dev(d["ang"]), G.dev(d["gamma"]), G.dev(d["theta"]),
+                                         G.dev(d["conv_w"]), G.dev(d["conv_b"]), None, z[0], z[1], None, None, None, ws)
+        assert st == K.CAWN_OK
+        status = K.cawn_workspace_status(ws)
+    finally:
+        K.cawn_set_spin_limit(1 << 26)
+    assert status in (K.CAWN_OK, K.CAWN_ETIMEOUT)      # a race by construction; both must leave a clean workspace
+    out = G.run_fwd(d, B, L, H, F, conv_k=4, gate_tau=0.1, ws=ws, want_mask=False)
+    cfg = O.Cfg(B, L, H, F, conv_k=4, gate_tau=0.1)
+    lanes = slice(0, 8)
+    sub = {k: (v[..., lanes] if k in ("mag", "ang", "gamma", "theta") else v[:, lanes]) for k, v in d.items()}
+    ora = O.phase_fwd(O.Cfg(B, L, 1, 8, conv_k=4, gate_tau=0.1), sub["mag"], sub["ang"], sub["gamma"], sub["theta"],
+                      conv_w=sub["conv_w"], conv_b=sub["conv_b"])
+    assert G.rel_err(out["z_re"][..., lanes], ora["z_re"]) <= TOL
