@@ -218,8 +218,9 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
         }
     }
     if (tt > 0) {
+        wait_stores_done();
         __syncthreads();
-        if (tid == 0) flag_store_release(a.flags + ticket, ST_AGG);
+        if (tid == 0) flag_store(a.flags + ticket, ST_AGG);
     }
 
     // ---- carry into the tile: state_in for the first tile, look-back otherwise
@@ -245,13 +246,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
             }
             uint32_t idx = ticket - chain_stride;
             for (int d = 1; d <= tt; ++d) {
-                uint32_t st = flag_load_acquire(a.flags + idx);
-                uint32_t spins = 0;
-                while (st == ST_NONE && spins < a.spin_limit) {
-                    __builtin_amdgcn_s_sleep(2);
-                    st = flag_load_acquire(a.flags + idx);
-                    ++spins;
-                }
+                const uint32_t st = wait_flag(a.flags + idx, a.spin_limit);
                 if (st == ST_NONE) {   // gave up: flag the workspace, keep going so every wave exits
                     if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     break;
@@ -320,10 +315,12 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
             coherent_store(a.pre + slot + JB + v, P_i);
         }
     }
+    wait_stores_done();
     __syncthreads();
     if (tid == 0) {
-        if (publish_prefix) flag_store_release(a.flags + ticket, ST_PREFIX);
-        const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (publish_prefix) flag_store(a.flags + ticket, ST_PREFIX);
+        wait_stores_done();
+        const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (old + 1 == a.total_tiles) sLast = 1;
     }
 
@@ -379,10 +376,10 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
     // ---- the tile that finishes last leaves the control words zeroed for the next call
     __syncthreads();
     if (sLast) {
-        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) a.flags[i] = ST_NONE;
+        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + i, ST_NONE);
         if (tid == 0) {
-            a.hdr->ticket = 0;
-            a.hdr->done = 0;
+            flag_store(&a.hdr->ticket, 0u);
+            flag_store(&a.hdr->done, 0u);
         }
     }
 }

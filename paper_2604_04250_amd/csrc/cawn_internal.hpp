@@ -142,15 +142,24 @@ __device__ __forceinline__ bool in_gate(const GateSet &g, float x)
     return (x >= g.a1 && x <= g.b1) || (x >= g.a2 && x <= g.b2);
 }
 
-// Agent-scope publication helpers (tiles may sit on different XCDs, whose L2s are not coherent
-// with each other without these).
-__device__ __forceinline__ void flag_store_release(uint32_t *p, uint32_t v)
+// Cross-tile publication.  Tiles of one chain may run on different XCDs, whose L2 caches are not
+// coherent with each other.  Payload and status words therefore move with agent-scope relaxed
+// atomics (sc1 accesses, which go to the memory-side coherence point), and ordering is by waiting
+// for the stores to complete (vmcnt) before the status word is written.  Acquire/release atomics
+// are avoided on purpose: at agent scope they write back / invalidate the whole L2 on every use,
+// which a spin loop next to streaming stores cannot afford.
+__device__ __forceinline__ void wait_stores_done()
 {
-    __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
-__device__ __forceinline__ uint32_t flag_load_acquire(const uint32_t *p)
+__device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+__device__ __forceinline__ void flag_store(uint32_t *p, uint32_t v)
 {
-    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t flag_load(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float coherent_load(const float *p)
 {
@@ -159,6 +168,19 @@ __device__ __forceinline__ float coherent_load(const float *p)
 __device__ __forceinline__ void coherent_store(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Wait (bounded) until a tile's status word is set; returns ST_NONE if it gave up.
+__device__ __forceinline__ uint32_t wait_flag(const uint32_t *p, uint32_t spin_limit)
+{
+    uint32_t st = flag_load(p);
+    uint32_t spins = 0;
+    while (st == ST_NONE && spins < spin_limit) {
+        __builtin_amdgcn_s_sleep(1);
+        st = flag_load(p);
+        ++spins;
+    }
+    compiler_fence();
+    return st;
 }
 #endif
 
