@@ -490,4 +490,92 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     return CAWN_OK;
 }
 
+int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
+                              const float *theta, const float *conv_w, const float *conv_b,
+                              const void *state_in, const void *ckpt, const float *dz_re, const float *dz_im,
+                              const void *dstate_out, float *dmag, float *dang, float *dgamma, float *dtheta,
+                              float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->gate_mode != 0 || d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    const WsLayout w = make_layout(d);
+    const long long J = w.J;
+    const int kc = d->conv_k;
+    const bool want_w = kc > 0 && (dconv_w || dconv_b);
+    const bool want_param = dgamma || dtheta || want_w;
+    if (d->L == 0) {   // no tokens: the state gradient passes through, parameter gradients are zero
+        auto zero = [&](void *p, size_t nfloat) {
+            if (!p || !nfloat) return hipSuccess;
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(64), dim3(256), 0, s, reinterpret_cast<uint32_t *>(p), nfloat);
+            return hipGetLastError();
+        };
+        const size_t nb = cawn_state_bytes(d);
+        hipError_t e = hipSuccess;
+        if (dstate_in && dstate_in != dstate_out)
+            e = dstate_out ? hipMemcpyAsync(dstate_in, dstate_out, nb, hipMemcpyDeviceToDevice, s)
+                           : zero(dstate_in, nb / 4);
+        if (e == hipSuccess && !d->accumulate_param_grads) {
+            e = zero(dgamma, J);
+            if (e == hipSuccess) e = zero(dtheta, J);
+            if (e == hipSuccess && kc > 0) e = zero(dconv_w, 2 * J * kc);
+            if (e == hipSuccess && kc > 0) e = zero(dconv_b, 2 * J);
+        }
+        return e == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
+    }
+    if (!mag || !ang || !gamma || !theta || !dz_re || !dz_im || !dmag || !dang || !workspace) return CAWN_EINVAL;
+    if (kc > 0 && !conv_w) return CAWN_EINVAL;
+    if ((dgamma || dtheta) && !ckpt) return CAWN_EINVAL;
+    if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
+    const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
+    const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
+    if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
+
+    BwdArgs a{};
+    if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;
+    const bool vec = (J % BwdV == 0) && (ist % BwdV == 0) && (isb % BwdV == 0) && (ost % BwdV == 0) &&
+                     (osb % BwdV == 0) && aligned(mag, 8) && aligned(ang, 8) && aligned(dz_re, 8) &&
+                     aligned(dz_im, 8) && aligned(dmag, 8) && aligned(dang, 8) &&
+                     (!state_in || aligned(state_in, 8)) && (!ckpt || aligned(ckpt, 8)) &&
+                     (!dstate_out || aligned(dstate_out, 8)) && (!dstate_in || aligned(dstate_in, 8));
+    const int JB = (vec ? BwdV : 1) * BwdLPR;
+    const int nLB = (int)((J + JB - 1) / JB);
+    const size_t tiles = (size_t)d->B * w.nT * nLB;
+    if (tiles > MAX_TILES) return CAWN_EUNSUPPORTED;
+
+    char *ws = reinterpret_cast<char *>(workspace);
+    if (!d->lane_consts_cached) {
+        if (build_table(d, w, ws, gamma, theta, conv_w, conv_b, s) != hipSuccess) return CAWN_ELAUNCH;
+    }
+    a.mag = mag; a.ang = ang; a.dz_re = dz_re; a.dz_im = dz_im;
+    a.table = reinterpret_cast<const float *>(ws + w.off_table);
+    a.state_in = reinterpret_cast<const float *>(state_in);
+    a.ckpt = reinterpret_cast<const float *>(ckpt);
+    a.dstate_out = reinterpret_cast<const float *>(dstate_out);
+    a.dmag = dmag; a.dang = dang;
+    a.dstate_in = reinterpret_cast<float *>(dstate_in);
+    a.hdr = reinterpret_cast<WsHeader *>(ws);
+    a.flags = reinterpret_cast<uint32_t *>(ws + w.off_flags);
+    a.agg = reinterpret_cast<float *>(ws + w.off_agg);
+    a.pre = reinterpret_cast<float *>(ws + w.off_pre);
+    a.halo = reinterpret_cast<float *>(ws + w.off_halo);
+    a.part = reinterpret_cast<float *>(ws + w.off_part);
+    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
+    a.amp_mode = d->amp_mode; a.want_param = want_param ? 1 : 0;
+    a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
+    a.conv_clamp = d->conv_clamp; a.grad_clamp = d->grad_clamp;
+    a.spin_limit = g_spin_limit.load();
+    a.total_tiles = (uint32_t)tiles;
+    if (launch_bwd(a, kc, vec, s) != hipSuccess) return CAWN_ELAUNCH;
+    if (want_param) {
+        const int rows = part_rows(kc);
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((J + 31) / 32), rows), dim3(256), 0, s, a.part,
+                           dgamma, dtheta, dconv_w, dconv_b, rows, kc > 0 ? kc : 1, (int)J, JB, nLB,
+                           d->B * w.nT, d->accumulate_param_grads);
+        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+    }
+    return CAWN_OK;
+}
+
 }  // extern "C"

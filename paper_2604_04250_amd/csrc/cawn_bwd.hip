@@ -1,9 +1,645 @@
-// placeholder until the backward kernels land
+// Fused backward (Sec. 3.4 last paragraph, Sec. 3.5 of the paper): reverse-time adjoint scan
+//   G[t] = dZ[t] + conj(lambda) G[t+1]
+// with the front-end recomputed in-kernel, chained to the amplitude (straight-through: no gate
+// factor), the phase (gate factor), SiLU', the conv clamp's sub-gradient and the transposed conv.
+// Per token-lane HBM traffic: 8 B inputs + 8 B upstream gradient in, 8 B input gradient out.
+//
+// Same three-level structure as the forward, run against time: tiles of one (batch row, lane
+// block) form a chain from the last tile to the first, joined by a decoupled look-back over
+// adjoint aggregates.  Two things are added:
+//   * parameter gradients need the forward state S[t-1]; it is rebuilt inside the tile from the
+//     checkpoint the forward stored for the tile's first token;
+//   * the transposed conv needs the conv pre-activation gradients of the next conv_k-1 tokens.
+//     Inside a tile they cross segments through LDS; across tiles the later tile (earlier in the
+//     chain) publishes its first conv_k-1 rows through the workspace.
+// Parameter gradients leave each tile as per-lane partial sums (fixed order inside the tile) and
+// are summed over tiles by a second kernel in a fixed order: results are bitwise repeatable.
 #include "cawn_internal.hpp"
+
 namespace cawn {
-hipError_t launch_bwd(const BwdArgs &, int, bool, hipStream_t) { return hipErrorNotSupported; }
+
+template <int V> struct BVec;
+template <> struct BVec<1> {
+    static __device__ __forceinline__ void ld(float (&d)[1], const float *p) { d[0] = *p; }
+    static __device__ __forceinline__ void st(float *p, const float (&s)[1]) { *p = s[0]; }
+};
+template <> struct BVec<2> {
+    static __device__ __forceinline__ void ld(float (&d)[2], const float *p)
+    {
+        float2 t = *reinterpret_cast<const float2 *>(p);
+        d[0] = t.x; d[1] = t.y;
+    }
+    static __device__ __forceinline__ void st(float *p, const float (&s)[2])
+    {
+        *reinterpret_cast<float2 *>(p) = make_float2(s[0], s[1]);
+    }
+};
+
+template <int V, int KC, bool PARAM>
+__global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a)
+{
+    constexpr int NSTEP = Geom::NSTEP, NSEG = Geom::NSEG, LPR = BwdLPR;
+    constexpr int JB = V * LPR;
+    constexpr int HALO = KC > 0 ? KC - 1 : 0;
+    constexpr int HALO1 = HALO > 0 ? HALO : 1;
+    constexpr int KC1 = KC > 0 ? KC : 1;
+    constexpr int NR = NSTEP + HALO;
+    constexpr int ROWS = 4 + 2 * KC;
+    static_assert(HALO <= NSTEP, "conv halo must fit in one segment");
+
+    __shared__ float sEb[NSEG][2][JB];
+    __shared__ float sEf[PARAM ? NSEG : 1][2][JB];
+    __shared__ float sCarry[2][JB];
+    __shared__ float sHalo[NSEG][HALO1][2][JB];
+    __shared__ float sRed[PARAM ? NSEG : 1][ROWS][JB];
+    __shared__ uint32_t sTicket, sLast;
+
+    const int tid = threadIdx.x;
+    const int lv = tid % LPR, seg = tid / LPR;
+    if (tid == 0) {
+        sTicket = __hip_atomic_fetch_add(&a.hdr->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sLast = 0;
+    }
+    __syncthreads();
+    const uint32_t ticket = sTicket;
+    const int lb = ticket % a.nLB;
+    const int rest = ticket / a.nLB;
+    const int b = rest % a.B, ttr = rest / a.B;       // ttr: position in the chain (0 = last tile in time)
+    const int tt = a.nT - 1 - ttr;
+    const uint32_t chain_stride = (uint32_t)a.B * a.nLB;
+    const int j0 = lb * JB + lv * V;
+    const bool active = j0 < a.J;
+    const int t0 = tt * TILE_T + seg * NSTEP;
+    const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
+    const float *dtail_out = a.dstate_out ? a.dstate_out + (size_t)a.B * 2 * a.J : nullptr;
+
+    // ---- lane constants
+    float lr[V], li[V], pnr[V], pni[V], psr[V], psi[V], pfr[V], pfi[V], cth[V], sth[V], gam[V];
+    float wm[KC1][V], wa[KC1][V], bm[V], ba[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        lr[v] = li[v] = pnr[v] = pni[v] = psi[v] = pfi[v] = sth[v] = gam[v] = bm[v] = ba[v] = 0.f;
+        psr[v] = pfr[v] = cth[v] = 1.f;
+#pragma unroll
+        for (int k = 0; k < KC1; ++k) wm[k][v] = wa[k][v] = 0.f;
+    }
+    if (active) {
+        const float *tb = a.table + j0;
+        BVec<V>::ld(lr, tb + (size_t)R_LR * a.Jp);
+        BVec<V>::ld(li, tb + (size_t)R_LI * a.Jp);
+        BVec<V>::ld(pnr, tb + (size_t)(R_PSEG + 2) * a.Jp);                       // lambda^NSTEP
+        BVec<V>::ld(pni, tb + (size_t)(R_PSEG + 3) * a.Jp);
+        BVec<V>::ld(psr, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
+        BVec<V>::ld(psi, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
+        if (PARAM) {
+            BVec<V>::ld(pfr, tb + (size_t)(R_PSEG + 2 * seg) * a.Jp);             // forward: segments before mine
+            BVec<V>::ld(pfi, tb + (size_t)(R_PSEG + 2 * seg + 1) * a.Jp);
+            BVec<V>::ld(cth, tb + (size_t)R_COS * a.Jp);
+            BVec<V>::ld(sth, tb + (size_t)R_SIN * a.Jp);
+            BVec<V>::ld(gam, tb + (size_t)R_GAMMA * a.Jp);
+        }
+        if (KC > 0) {
+            BVec<V>::ld(bm, tb + (size_t)R_BIAS_M * a.Jp);
+            BVec<V>::ld(ba, tb + (size_t)R_BIAS_A * a.Jp);
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                BVec<V>::ld(wm[k], tb + (size_t)(R_W0 + k) * a.Jp);
+                BVec<V>::ld(wa[k], tb + (size_t)(R_W0 + KC + k) * a.Jp);
+            }
+        }
+    }
+
+    // ---- loads: pre-conv rows t0-HALO .. t0+NSTEP-1, upstream gradients t0 .. t0+NSTEP-1
+    float um[NR][V], ua[NR][V];
+    float dzr[NSTEP][V], dzi[NSTEP][V];     // upstream dS, later overwritten by d(pre-activation)
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const int t = t0 - HALO + r;
+#pragma unroll
+        for (int v = 0; v < V; ++v) um[r][v] = ua[r][v] = 0.f;
+        if (active) {
+            if (t >= 0 && t < a.L) {
+                const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + j0;
+                BVec<V>::ld(um[r], a.mag + off);
+                BVec<V>::ld(ua[r], a.ang + off);
+            } else if (HALO > 0 && t < 0 && tail_in && t + HALO >= 0) {
+                const size_t off = ((size_t)(b * HALO + (t + HALO)) * 2) * a.J + j0;
+                BVec<V>::ld(um[r], tail_in + off);
+                BVec<V>::ld(ua[r], tail_in + off + a.J);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NSTEP; ++i) {
+        const int t = t0 + i;
+#pragma unroll
+        for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
+        if (active && t < a.L) {
+            const size_t off = (size_t)b * a.osb + (size_t)t * a.ost + j0;
+            BVec<V>::ld(dzr[i], a.dz_re + off);
+            BVec<V>::ld(dzi[i], a.dz_im + off);
+            if (t == a.L - 1 && a.dstate_out) {   // gradient of the carried state joins the last token
+                float xr[V], xi[V];
+                BVec<V>::ld(xr, a.dstate_out + ((size_t)b * 2 + 0) * a.J + j0);
+                BVec<V>::ld(xi, a.dstate_out + ((size_t)b * 2 + 1) * a.J + j0);
+#pragma unroll
+                for (int v = 0; v < V; ++v) { dzr[i][v] += xr[v]; dzi[i][v] += xi[v]; }
+            }
+        }
+    }
+
+    // ---- adjoint from zero over my segment (needs only the upstream gradients)
+    float Ebr[V], Ebi[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) Ebr[v] = Ebi[v] = 0.f;
+#pragma unroll
+    for (int i = NSTEP - 1; i >= 0; --i) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float nr = __builtin_fmaf(lr[v], Ebr[v], __builtin_fmaf(li[v], Ebi[v], dzr[i][v]));
+            const float ni = __builtin_fmaf(lr[v], Ebi[v], __builtin_fmaf(-li[v], Ebr[v], dzi[i][v]));
+            Ebr[v] = nr;
+            Ebi[v] = ni;
+        }
+    }
+
+    // ---- front-end recompute
+    float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V], dsa[NSTEP][V];
+    float Efr[V], Efi[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) Efr[v] = Efi[v] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NSTEP; ++i) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            float zm, xm, phi, km, ka;
+            if (KC > 0) {
+                zm = bm[v];
+                float za = ba[v];
+#pragma unroll
+                for (int k = 0; k < KC; ++k) {
+                    zm = __builtin_fmaf(wm[k][v], um[i + k][v], zm);
+                    za = __builtin_fmaf(wa[k][v], ua[i + k][v], za);
+                }
+                const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
+                const float sgm = sigmoid_fast(cm), sga = sigmoid_fast(ca);
+                xm = cm * sgm;
+                phi = ca * sga;
+                // SiLU'(z) = sig (1 + z (1 - sig)); the clamp passes gradient only inside its range
+                km = __builtin_fabsf(zm) <= a.conv_clamp ? sgm * __builtin_fmaf(cm, 1.0f - sgm, 1.0f) : 0.0f;
+                ka = __builtin_fabsf(za) <= a.conv_clamp ? sga * __builtin_fmaf(ca, 1.0f - sga, 1.0f) : 0.0f;
+            } else {
+                zm = um[i][v];
+                xm = zm;
+                phi = ua[i][v];
+                km = 1.0f;
+                ka = 1.0f;
+            }
+            float amp = xm;
+            if (a.amp_mode) {
+                const float sp = softplus_fast(xm);
+                amp = __builtin_fminf(sp, 10.0f);
+                km *= sp < 10.0f ? sigmoid_fast(xm) : 0.0f;
+            }
+            const bool g = in_gate(a.gs, zm);
+            float s, c;
+            sincos_fast(phi, s, c);
+            const float agv = g ? amp : 0.0f;
+            cs[i][v] = c;
+            sn[i][v] = s;
+            dsm[i][v] = km;
+            if (PARAM) {
+                ag[i][v] = agv;
+                dsa[i][v] = ka;
+                const float pr = agv * c, pi = agv * s;
+                const float nr = __builtin_fmaf(lr[v], Efr[v], __builtin_fmaf(-li[v], Efi[v], pr));
+                const float ni = __builtin_fmaf(li[v], Efr[v], __builtin_fmaf(lr[v], Efi[v], pi));
+                Efr[v] = nr;
+                Efi[v] = ni;
+            } else {
+                ag[i][v] = agv * ka;       // only the product is needed without parameter gradients
+                dsa[i][v] = 0.f;
+            }
+        }
+    }
+
+    // ---- segments meet in LDS
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        sEb[seg][0][lv * V + v] = Ebr[v];
+        sEb[seg][1][lv * V + v] = Ebi[v];
+        if (PARAM) {
+            sEf[seg][0][lv * V + v] = Efr[v];
+            sEf[seg][1][lv * V + v] = Efi[v];
+        }
+    }
+    __syncthreads();
+    float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
+#pragma unroll
+    for (int v = 0; v < V; ++v) Xr[v] = Xi[v] = 0.f;
+    for (int q = NSEG - 1; q > seg; --q) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float er = sEb[q][0][lv * V + v], ei = sEb[q][1][lv * V + v];
+            const float nr = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], er));
+            const float ni = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], ei));
+            Xr[v] = nr;
+            Xi[v] = ni;
+        }
+    }
+    float Fr[V], Fi[V];     // forward state entering my segment
+    if (PARAM) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) Fr[v] = Fi[v] = 0.f;
+        for (int q = 0; q < seg; ++q) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float er = sEf[q][0][lv * V + v], ei = sEf[q][1][lv * V + v];
+                const float nr = __builtin_fmaf(pnr[v], Fr[v], __builtin_fmaf(-pni[v], Fi[v], er));
+                const float ni = __builtin_fmaf(pni[v], Fr[v], __builtin_fmaf(pnr[v], Fi[v], ei));
+                Fr[v] = nr;
+                Fi[v] = ni;
+            }
+        }
+        float kr[V], ki[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) kr[v] = ki[v] = 0.f;
+        if (active && a.ckpt) {
+            const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
+            BVec<V>::ld(kr, ck);
+            BVec<V>::ld(ki, ck + a.J);
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float nr = __builtin_fmaf(pfr[v], kr[v], __builtin_fmaf(-pfi[v], ki[v], Fr[v]));
+            const float ni = __builtin_fmaf(pfi[v], kr[v], __builtin_fmaf(pfr[v], ki[v], Fi[v]));
+            Fr[v] = nr;
+            Fi[v] = ni;
+        }
+    }
+
+    // ---- chain: aggregate, look-back, prefix.  The chain runs from the last tile in time to the first.
+    const bool head = seg == 0;              // threads holding the tile's first segment
+    float Tr[V], Ti[V];
+    const size_t slot = (size_t)ticket * 2 * JB + lv * V;
+    if (head) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            Tr[v] = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], Ebr[v]));
+            Ti[v] = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], Ebi[v]));
+        }
+        if (ttr > 0 && tt > 0) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                coherent_store(a.agg + slot + v, Tr[v]);
+                coherent_store(a.agg + slot + JB + v, Ti[v]);
+            }
+        }
+    }
+    if (ttr > 0 && tt > 0) {
+        wait_stores_done();
+        __syncthreads();
+        if (tid == 0) flag_store(a.flags + ticket, ST_AGG);
+    }
+    if (seg == NSEG - 1) {
+        float cr[V], ci[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) cr[v] = ci[v] = 0.f;
+        if (ttr > 0) {
+            float hr[V], hi[V], qr[V], qi[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
+            if (active) {
+                const float *tb = a.table + j0;
+                BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
+                BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
+                BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
+                BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+            }
+            if (!look_back<V, true>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
+                                    hr, hi, qr, qi, a.spin_limit, cr, ci)) {
+                if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            sCarry[0][lv * V + v] = cr[v];
+            sCarry[1][lv * V + v] = ci[v];
+        }
+    }
+    __syncthreads();
+
+    // ---- true adjoint entering my segment; the tile's inclusive prefix
+    float Gr[V], Gi[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
+        Gr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(psi[v], ci, Xr[v]));      // conj(ps) * carry
+        Gi[v] = __builtin_fmaf(psr[v], ci, __builtin_fmaf(-psi[v], cr, Xi[v]));
+    }
+    const bool publish_prefix = tt > 0;
+    if (head && publish_prefix) {
+        float hr[V], hi[V], qr[V], qi[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
+        if (active) {
+            const float *tb = a.table + j0;
+            BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
+            BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
+            BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
+            BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {   // P = T + conj(lambda^T) carry
+            const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
+            float P_r, P_i;
+            chain_step<true>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr, ci, P_r, P_i);
+            coherent_store(a.pre + slot + v, P_r);
+            coherent_store(a.pre + slot + JB + v, P_i);
+        }
+    }
+    wait_stores_done();
+    __syncthreads();
+    if (tid == 0 && publish_prefix) flag_store(a.flags + ticket, ST_PREFIX);
+
+    // ---- forward replay: S[t-1] for my tokens
+    float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];
+    if (PARAM) {
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                Spr[i][v] = Fr[v];
+                Spi[i][v] = Fi[v];
+                const float pr = ag[i][v] * cs[i][v], pi = ag[i][v] * sn[i][v];
+                const float nr = __builtin_fmaf(lr[v], Fr[v], __builtin_fmaf(-li[v], Fi[v], pr));
+                const float ni = __builtin_fmaf(li[v], Fr[v], __builtin_fmaf(lr[v], Fi[v], pi));
+                Fr[v] = nr;
+                Fi[v] = ni;
+                ag[i][v] *= dsa[i][v];      // from here on only a*g*SiLU'(z_ang) is needed
+            }
+        }
+    }
+
+    // ---- reverse pass: adjoint, returned gradients, parameter terms
+    float acc_g[V], acc_t[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc_g[v] = acc_t[v] = 0.f;
+#pragma unroll
+    for (int i = NSTEP - 1; i >= 0; --i) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float nr = __builtin_fmaf(lr[v], Gr[v], __builtin_fmaf(li[v], Gi[v], dzr[i][v]));
+            const float ni = __builtin_fmaf(lr[v], Gi[v], __builtin_fmaf(-li[v], Gr[v], dzi[i][v]));
+            Gr[v] = nr;
+            Gi[v] = ni;
+            if (PARAM) {
+                const float rr = __builtin_fmaf(cth[v], Spr[i][v], -sth[v] * Spi[i][v]);
+                const float ri = __builtin_fmaf(sth[v], Spr[i][v], cth[v] * Spi[i][v]);
+                const float tg = __builtin_fmaf(nr, rr, ni * ri);
+                const float tth = gam[v] * __builtin_fmaf(ni, rr, -nr * ri);
+                acc_g[v] += clampf(tg, a.grad_clamp);
+                acc_t[v] += clampf(tth, a.grad_clamp);
+            }
+            const float hr = clampf(nr, a.grad_clamp), hi = clampf(ni, a.grad_clamp);
+            const float da = __builtin_fmaf(hr, cs[i][v], hi * sn[i][v]);
+            const float dph = __builtin_fmaf(hi, cs[i][v], -hr * sn[i][v]);
+            dzr[i][v] = da * dsm[i][v];          // d/d(conv pre-activation), magnitude stream
+            dzi[i][v] = dph * ag[i][v];          //                           angle stream
+        }
+    }
+    // gradient of the incoming scan state: conj(lambda) G[0]
+    if (a.dstate_in && tt == 0 && head && active) {
+        float xr[V], xi[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            xr[v] = __builtin_fmaf(lr[v], Gr[v], li[v] * Gi[v]);
+            xi[v] = __builtin_fmaf(lr[v], Gi[v], -li[v] * Gr[v]);
+        }
+        BVec<V>::st(a.dstate_in + ((size_t)b * 2 + 0) * a.J + j0, xr);
+        BVec<V>::st(a.dstate_in + ((size_t)b * 2 + 1) * a.J + j0, xi);
+    }
+
+    if (KC == 0) {
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+            const int t = t0 + i;
+            if (active && t < a.L) {
+                const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + j0;
+                BVec<V>::st(a.dmag + off, dzr[i]);
+                BVec<V>::st(a.dang + off, dzi[i]);
+            }
+        }
+    } else {
+        // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
+        if (HALO > 0) {
+#pragma unroll
+            for (int q = 0; q < HALO; ++q)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    sHalo[seg][q][0][lv * V + v] = dzr[q][v];
+                    sHalo[seg][q][1][lv * V + v] = dzi[q][v];
+                }
+            if (head && tt > 0) {      // rows the earlier tile (next in the chain) needs
+                float *hp = a.halo + (size_t)ticket * HALO * 2 * JB + lv * V;
+#pragma unroll
+                for (int q = 0; q < HALO; ++q)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        coherent_store(hp + (q * 2 + 0) * JB + v, dzr[q][v]);
+                        coherent_store(hp + (q * 2 + 1) * JB + v, dzi[q][v]);
+                    }
+            }
+            wait_stores_done();
+            __syncthreads();
+            if (tid == 0 && tt > 0) flag_store(a.flags + ticket, ST_HALO);
+        }
+        float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
+#pragma unroll
+        for (int q = 0; q < HALO1; ++q)
+#pragma unroll
+            for (int v = 0; v < V; ++v) hm[q][v] = ha[q][v] = 0.f;
+        if (HALO > 0) {
+            if (seg < NSEG - 1) {
+#pragma unroll
+                for (int q = 0; q < HALO; ++q)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        hm[q][v] = sHalo[seg + 1][q][0][lv * V + v];
+                        ha[q][v] = sHalo[seg + 1][q][1][lv * V + v];
+                    }
+            } else if (ttr > 0) {
+                const uint32_t idx = ticket - chain_stride;
+                uint32_t st = flag_load(a.flags + idx);
+                uint32_t spins = 0;
+                while (st < ST_HALO && spins < a.spin_limit) {
+                    __builtin_amdgcn_s_sleep(1);
+                    st = flag_load(a.flags + idx);
+                    ++spins;
+                }
+                compiler_fence();
+                if (st >= ST_HALO) {
+                    const float *hp = a.halo + (size_t)idx * HALO * 2 * JB + lv * V;
+#pragma unroll
+                    for (int q = 0; q < HALO; ++q)
+#pragma unroll
+                        for (int v = 0; v < V; ++v) {
+                            hm[q][v] = coherent_load(hp + (q * 2 + 0) * JB + v);
+                            ha[q][v] = coherent_load(hp + (q * 2 + 1) * JB + v);
+                        }
+                } else if (lv == 0) {
+                    __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+            const int t = t0 + i;
+            float dm[V], da[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float sm_ = 0.f, sa_ = 0.f;
+#pragma unroll
+                for (int k = 0; k < KC; ++k) {
+                    const int idx = i + (KC - 1) - k;
+                    const float zm_ = idx < NSTEP ? dzr[idx < NSTEP ? idx : 0][v] : hm[idx >= NSTEP ? idx - NSTEP : 0][v];
+                    const float za_ = idx < NSTEP ? dzi[idx < NSTEP ? idx : 0][v] : ha[idx >= NSTEP ? idx - NSTEP : 0][v];
+                    sm_ = __builtin_fmaf(wm[k][v], zm_, sm_);
+                    sa_ = __builtin_fmaf(wa[k][v], za_, sa_);
+                }
+                dm[v] = sm_;
+                da[v] = sa_;
+            }
+            if (active && t < a.L) {
+                if (HALO > 0 && dtail_out && t >= a.L - HALO) {   // state_out's history rows are copies of these inputs
+                    const int r = t - (a.L - HALO);
+                    float xm_[V], xa_[V];
+                    const size_t o = ((size_t)(b * HALO + r) * 2) * a.J + j0;
+                    BVec<V>::ld(xm_, dtail_out + o);
+                    BVec<V>::ld(xa_, dtail_out + o + a.J);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
+                }
+                const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + j0;
+                BVec<V>::st(a.dmag + off, dm);
+                BVec<V>::st(a.dang + off, da);
+            }
+        }
+        // gradient of the incoming conv history: rows q <-> time q - HALO
+        if (HALO > 0 && a.dstate_in && tt == 0 && head && active) {
+            float *dtail_in = a.dstate_in + (size_t)a.B * 2 * a.J;
+#pragma unroll
+            for (int q = 0; q < HALO; ++q) {
+                float dm[V], da[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float sm_ = 0.f, sa_ = 0.f;
+#pragma unroll
+                    for (int k = 0; k <= q; ++k) {
+                        sm_ = __builtin_fmaf(wm[k][v], dzr[q - k][v], sm_);
+                        sa_ = __builtin_fmaf(wa[k][v], dzi[q - k][v], sa_);
+                    }
+                    dm[v] = sm_;
+                    da[v] = sa_;
+                }
+                const int r = q - a.L;                     // history row that state_out copied straight from state_in
+                if (dtail_out && r >= 0) {
+                    float xm_[V], xa_[V];
+                    const size_t o = ((size_t)(b * HALO + r) * 2) * a.J + j0;
+                    BVec<V>::ld(xm_, dtail_out + o);
+                    BVec<V>::ld(xa_, dtail_out + o + a.J);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
+                }
+                const size_t o = ((size_t)(b * HALO + q) * 2) * a.J + j0;
+                BVec<V>::st(dtail_in + o, dm);
+                BVec<V>::st(dtail_in + o + a.J, da);
+            }
+        }
+    }
+
+    // ---- parameter partials: sum over my tokens, then over segments in index order
+    if (PARAM) {
+        float dwm[KC1][V], dwa[KC1][V], dbm[V], dba[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            dbm[v] = dba[v] = 0.f;
+#pragma unroll
+            for (int k = 0; k < KC1; ++k) dwm[k][v] = dwa[k][v] = 0.f;
+        }
+        if (KC > 0) {
+#pragma unroll
+            for (int i = 0; i < NSTEP; ++i)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    dbm[v] += dzr[i][v];
+                    dba[v] += dzi[i][v];
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) {
+                        dwm[k][v] = __builtin_fmaf(dzr[i][v], um[i + k][v], dwm[k][v]);
+                        dwa[k][v] = __builtin_fmaf(dzi[i][v], ua[i + k][v], dwa[k][v]);
+                    }
+                }
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int c = lv * V + v;
+            sRed[seg][0][c] = acc_g[v];
+            sRed[seg][1][c] = acc_t[v];
+            sRed[seg][2][c] = dbm[v];
+            sRed[seg][3][c] = dba[v];
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                sRed[seg][4 + k][c] = dwm[k][v];
+                sRed[seg][4 + KC + k][c] = dwa[k][v];
+            }
+        }
+        __syncthreads();
+        for (int e = tid; e < ROWS * JB; e += blockDim.x) {
+            const int row = e / JB, c = e % JB;
+            float s = 0.f;
+#pragma unroll
+            for (int q = 0; q < NSEG; ++q) s += sRed[q][row][c];
+            a.part[((size_t)ticket * ROWS + row) * JB + c] = s;
+        }
+    }
+
+    // ---- bookkeeping: the tile that finishes last clears the control words
+    __syncthreads();
+    if (tid == 0) {
+        wait_stores_done();
+        const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sLast = (old + 1 == a.total_tiles) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (sLast) {
+        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + i, ST_NONE);
+        if (tid == 0) {
+            flag_store(&a.hdr->ticket, 0u);
+            flag_store(&a.hdr->done, 0u);
+        }
+    }
 }
-extern "C" int cawn_phase_accumulate_bwd(const cawn_desc *, const float *, const float *, const float *,
-                              const float *, const float *, const float *, const void *, const void *,
-                              const float *, const float *, const void *, float *, float *, float *, float *,
-                              float *, float *, void *, void *, size_t, void *) { return CAWN_EUNSUPPORTED; }
+
+template <int V, bool PARAM>
+static hipError_t launch_bwd_vp(const BwdArgs &a, int conv_k, hipStream_t s)
+{
+    dim3 grid(a.total_tiles), block(Geom::NSEG * BwdLPR);
+    switch (conv_k) {
+    case 0: hipLaunchKernelGGL((bwd_kernel<V, 0, PARAM>), grid, block, 0, s, a); break;
+    case 1: hipLaunchKernelGGL((bwd_kernel<V, 1, PARAM>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((bwd_kernel<V, 2, PARAM>), grid, block, 0, s, a); break;
+    case 3: hipLaunchKernelGGL((bwd_kernel<V, 3, PARAM>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((bwd_kernel<V, 4, PARAM>), grid, block, 0, s, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s)
+{
+    if (vec) return a.want_param ? launch_bwd_vp<BwdV, true>(a, conv_k, s) : launch_bwd_vp<BwdV, false>(a, conv_k, s);
+    return a.want_param ? launch_bwd_vp<1, true>(a, conv_k, s) : launch_bwd_vp<1, false>(a, conv_k, s);
+}
+
+}  // namespace cawn

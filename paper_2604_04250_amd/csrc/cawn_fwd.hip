@@ -234,9 +234,9 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
                 Vec<V>::ld(ci, a.state_in + ((size_t)b * 2 + 1) * a.J + j0);
             }
         } else {
-            float hr[V], hi[V], qr[V], qi[V], wr[V], wi[V];   // lambda^T hi, lo; running power
+            float hr[V], hi[V], qr[V], qi[V];   // lambda^T as a double-float
 #pragma unroll
-            for (int v = 0; v < V; ++v) { hr[v] = hi[v] = qr[v] = qi[v] = 0.f; wr[v] = 1.f; wi[v] = 0.f; }
+            for (int v = 0; v < V; ++v) hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
             if (active) {
                 const float *tb = a.table + j0;
                 Vec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
@@ -244,31 +244,10 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
                 Vec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
                 Vec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
             }
-            uint32_t idx = ticket - chain_stride;
-            for (int d = 1; d <= tt; ++d) {
-                const uint32_t st = wait_flag(a.flags + idx, a.spin_limit);
-                if (st == ST_NONE) {   // gave up: flag the workspace, keep going so every wave exits
-                    if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                const float *src = (st >= ST_PREFIX ? a.pre : a.agg) + (size_t)idx * 2 * JB + lv * V;
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    const float er = coherent_load(src + v), ei = coherent_load(src + JB + v);
-                    cr[v] = __builtin_fmaf(wr[v], er, __builtin_fmaf(-wi[v], ei, cr[v]));
-                    ci[v] = __builtin_fmaf(wi[v], er, __builtin_fmaf(wr[v], ei, ci[v]));
-                }
-                if (st >= ST_PREFIX) break;
-#pragma unroll
-                for (int v = 0; v < V; ++v) {   // running power *= lambda^T (double-float factor)
-                    const float nr = __builtin_fmaf(hr[v], wr[v], __builtin_fmaf(-hi[v], wi[v],
-                                     __builtin_fmaf(qr[v], wr[v], -qi[v] * wi[v])));
-                    const float ni = __builtin_fmaf(hi[v], wr[v], __builtin_fmaf(hr[v], wi[v],
-                                     __builtin_fmaf(qi[v], wr[v], qr[v] * wi[v])));
-                    wr[v] = nr;
-                    wi[v] = ni;
-                }
-                idx -= chain_stride;
+            if (!look_back<V, false>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, tt, JB, lv * V,
+                                     hr, hi, qr, qi, a.spin_limit, cr, ci)) {
+                // gave up: flag the workspace, keep going so that every wave exits
+                if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
 #pragma unroll
@@ -307,10 +286,8 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
-            const float lo_r = __builtin_fmaf(qr[v], cr, -qi[v] * ci);
-            const float lo_i = __builtin_fmaf(qi[v], cr, qr[v] * ci);
-            const float P_r = __builtin_fmaf(hr[v], cr, __builtin_fmaf(-hi[v], ci, Tr[v] + lo_r));
-            const float P_i = __builtin_fmaf(hi[v], cr, __builtin_fmaf(hr[v], ci, Ti[v] + lo_i));
+            float P_r, P_i;
+            chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr, ci, P_r, P_i);
             coherent_store(a.pre + slot + v, P_r);
             coherent_store(a.pre + slot + JB + v, P_i);
         }

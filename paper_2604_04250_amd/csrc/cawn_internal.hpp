@@ -182,6 +182,70 @@ __device__ __forceinline__ uint32_t wait_flag(const uint32_t *p, uint32_t spin_l
     compiler_fence();
     return st;
 }
+
+// One link of a tile chain: P = T + M c, with M = lambda^TILE_T held as a double-float (h + q) and
+// conjugated for the adjoint chain.  Publication of a prefix and the look-back both go through
+// this one function, so every tile's prefix has the value a strictly sequential chain would give,
+// wherever the look-back happened to find its starting prefix: results do not depend on timing.
+template <bool CONJ>
+__device__ __forceinline__ void chain_step(float Tr, float Ti, float hr, float hi, float qr, float qi,
+                                           float cr, float ci, float &Pr, float &Pi)
+{
+    if (!CONJ) {
+        const float lo_r = __builtin_fmaf(qr, cr, -qi * ci);
+        const float lo_i = __builtin_fmaf(qi, cr, qr * ci);
+        Pr = __builtin_fmaf(hr, cr, __builtin_fmaf(-hi, ci, Tr + lo_r));
+        Pi = __builtin_fmaf(hi, cr, __builtin_fmaf(hr, ci, Ti + lo_i));
+    } else {
+        const float lo_r = __builtin_fmaf(qr, cr, qi * ci);
+        const float lo_i = __builtin_fmaf(qr, ci, -qi * cr);
+        Pr = __builtin_fmaf(hr, cr, __builtin_fmaf(hi, ci, Tr + lo_r));
+        Pi = __builtin_fmaf(hr, ci, __builtin_fmaf(-hi, cr, Ti + lo_i));
+    }
+}
+
+// Decoupled look-back for V lanes starting at lane offset `lo` of the tile slots.  `pred` is the
+// chain predecessor's tile index, `depth` the number of tiles before this one in the chain
+// (the chain's first tile always publishes a prefix).  Pass 1 walks back over status words until
+// it meets a published prefix; pass 2 walks forward again from that prefix through the
+// aggregates.  Returns false if a wait gave up (carry is then meaningless).
+template <int V, bool CONJ>
+__device__ __forceinline__ bool look_back(const uint32_t *flags, const float *agg, const float *pre,
+                                          uint32_t pred, uint32_t stride, int depth, int JB, int lo,
+                                          const float (&hr)[V], const float (&hi)[V], const float (&qr)[V],
+                                          const float (&qi)[V], uint32_t spin_limit, float (&cr)[V],
+                                          float (&ci)[V])
+{
+    uint32_t idx = pred;
+    int k = 0;      // aggregates between the prefix found and this tile
+    for (;;) {
+        const uint32_t st = wait_flag(flags + idx, spin_limit);
+        if (st == ST_NONE) return false;
+        if (st >= ST_PREFIX) break;
+        if (k + 1 >= depth) return false;   // cannot happen: the chain's first tile has a prefix
+        ++k;
+        idx -= stride;
+    }
+    const float *src = pre + (size_t)idx * 2 * JB + lo;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        cr[v] = coherent_load(src + v);
+        ci[v] = coherent_load(src + JB + v);
+    }
+    for (; k > 0; --k) {
+        idx += stride;
+        const float *ag = agg + (size_t)idx * 2 * JB + lo;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const float er = coherent_load(ag + v), ei = coherent_load(ag + JB + v);
+            float nr, ni;
+            chain_step<CONJ>(er, ei, hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
+            cr[v] = nr;
+            ci[v] = ni;
+        }
+    }
+    return true;
+}
 #endif
 
 }  // namespace cawn
