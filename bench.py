@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused conv + phase-accumulation hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One "step" is one pass of the whole hot path over one batch of seeded synthetic input that is
+already resident in HBM: forward (writing the tile checkpoints) followed by backward with every
+gradient requested, on the training-step configuration (B=8, H=12, F=64, L=8192, fp32, conv
+kernel 4, threshold 0.1).  Other workloads: cfg2_layer_fwd (forward only), cfg4_stream (2,000,000
+tokens in 4096-token chunks with the state carried in place), cfg5_wide (forward + backward).
+
+Prints ONE JSON line: tokens/s of the whole step, plus
+  roofline     - algorithmic HBM bytes of the dominant kernel / its measured duration vs 8 TB/s;
+  cpu_baseline - the fp64 oracle timed on the host cores on a bounded sample of the same inputs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+FWD_BYTES_PER_TOKEN_LANE = 16   # read mag, ang; write z_re, z_im
+BWD_BYTES_PER_TOKEN_LANE = 24   # read mag, ang, dz_re, dz_im; write dmag, dang
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3_train",
+                    choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (profiles/*_pmc.txt holds a line 'TRAFFIC_BYTES_PER_LAUNCH <workload> <bytes>'), else None."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    for fn in sorted(os.listdir(pdir)):
+        if not fn.endswith("_pmc.txt"):
+            continue
+        for line in open(os.path.join(pdir, fn)):
+            p = line.split()
+            if len(p) == 3 and p[0] == "TRAFFIC_BYTES_PER_LAUNCH" and p[1] == workload:
+                return float(p[2])
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (lanes and batch rows shard with no traffic; see "
+              f"DESIGN.md); --gpus {args.gpus} is not available", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2604_04250_amd import binding as K
+    from paper_2604_04250_amd import workloads as WL
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    K.lib()   # fails loudly when libcawn.so was not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = WL.CONFIGS[args.workload]
+    B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
+    theta = K.cawn_theta_init(H, F)
+    do_bwd = args.workload in ("cfg3_train", "cfg5_wide")
+    stream_mode = args.workload == "cfg4_stream"
+    L = wl.chunk if stream_mode else wl.L
+
+    # ---- inputs: the seeded host recipe for one batch (one chunk pool entry when streaming)
+    t_gen = time.time()
+    inp = WL.make_inputs(wl, theta=theta, with_grads=do_bwd, L=L)
+    gamma, th = torch.from_numpy(inp["gamma"]).to(dev), torch.from_numpy(inp["theta"]).to(dev)
+    cw, cb = torch.from_numpy(inp["conv_w"]).to(dev), torch.from_numpy(inp["conv_b"]).to(dev)
+    per_set = (8 if do_bwd else 4) * B * L * J * 4
+    nsets = max(2, min(16, -(-(600 << 20) // per_set)))     # rotate over > 512 MiB so the LLC cannot serve it
+    names = ["mag", "ang"] + (["dz_re", "dz_im"] if do_bwd else [])
+    sets = []
+    base = {k: torch.from_numpy(inp[k]).to(dev) for k in names}
+    for s in range(nsets):
+        cur = {k: (base[k] if s == 0 else torch.roll(base[k], shifts=7 * s, dims=1).contiguous()) for k in names}
+        cur["z_re"] = torch.empty((B, L, J), device=dev)
+        cur["z_im"] = torch.empty((B, L, J), device=dev)
+        if do_bwd:
+            cur["dmag"] = torch.empty((B, L, J), device=dev)
+            cur["dang"] = torch.empty((B, L, J), device=dev)
+        sets.append(cur)
+    t_gen = time.time() - t_gen
+
+    d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau)
+    ws = K.alloc_workspace(d, dev)
+    ckpt = torch.empty(K.cawn_ckpt_bytes(d) // 4, device=dev) if do_bwd else None
+    dgamma, dtheta = torch.empty(J, device=dev), torch.empty(J, device=dev)
+    dcw, dcb = torch.empty((2, J, Kc), device=dev), torch.empty((2, J), device=dev)
+    nstate = K.cawn_state_bytes(d) // 4
+    state = torch.zeros(nstate, device=dev)
+
+    # first call builds the lane table; later calls reuse it (parameters do not change in the bench)
+    K.check(K.cawn_phase_accumulate_fwd(d, sets[0]["mag"], sets[0]["ang"], gamma, th, cw, cb, None,
+                                        sets[0]["z_re"], sets[0]["z_im"], None, ckpt, None, ws))
+    d.lane_consts_cached = 1
+    d_tail = None
+    if stream_mode:
+        nfull, rem = divmod(wl.L, wl.chunk)
+        d_tail = K.make_desc(B, rem, H, F, conv_k=Kc, gate_tau=wl.gate_tau, lane_consts_cached=1) if rem else None
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(i, rec=None):
+        s = sets[i % nsets]
+        if stream_mode:
+            state.zero_()
+            for c in range(nfull):
+                p = sets[c % nsets]
+                K.cawn_phase_accumulate_fwd(d, p["mag"], p["ang"], gamma, th, cw, cb, state, p["z_re"], p["z_im"],
+                                            state, None, None, ws)
+            if d_tail is not None:
+                p = sets[nfull % nsets]
+                K.cawn_phase_accumulate_fwd(d_tail, p["mag"], p["ang"], gamma, th, cw, cb, state, p["z_re"],
+                                            p["z_im"], state, None, None, ws)
+            return
+        if rec is not None:
+            rec[0].record()
+        st = K.cawn_phase_accumulate_fwd(d, s["mag"], s["ang"], gamma, th, cw, cb, None, s["z_re"], s["z_im"],
+                                         None, ckpt, None, ws)
+        if rec is not None:
+            rec[1].record()
+        if do_bwd:
+            st |= K.cawn_phase_accumulate_bwd(d, s["mag"], s["ang"], gamma, th, cw, cb, None, ckpt, s["dz_re"],
+                                              s["dz_im"], None, s["dmag"], s["dang"], dgamma, dtheta, dcw, dcb,
+                                              None, ws)
+            if rec is not None:
+                rec[2].record()
+        assert st == 0, st
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    mem0 = torch.cuda.memory_allocated()
+    recs = [(ev(), ev(), ev()) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, recs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    mem1 = torch.cuda.memory_allocated()
+    K.check(K.cawn_workspace_status(ws))
+    ms_per_step = wall * 1e3 / args.steps
+    tokens = wl.B * wl.L
+    value = tokens / (ms_per_step * 1e-3)
+
+    out = {"metric": "phase-accumulation tokens/s (fwd+bwd)" if do_bwd else "phase-accumulation tokens/s (fwd)",
+           "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{wl.name}: B={wl.B} H={H} F={F} L={wl.L} conv_k={Kc} tau={wl.gate_tau} "
+                                  f"gamma~U[{wl.gamma_lo},{wl.gamma_hi}] theta_j=10000^(-2j/J)"
+                                  + (f" chunk={wl.chunk} state carried in place" if stream_mode else ""),
+                      "pass": "fwd+bwd (all gradients)" if do_bwd else "fwd",
+                      "buffer_sets_rotated": nsets}}
+
+    # ---- roofline of the dominant kernel, from HIP events on the launch stream
+    if stream_mode:
+        ncalls = nfull + (1 if d_tail is not None else 0)
+        per_call_ms = ms_per_step / ncalls
+        alg = FWD_BYTES_PER_TOKEN_LANE * tokens * J / ncalls
+        achieved = alg / (per_call_ms * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<4,4> (per 4096-token chunk call, launch gaps included)",
+                           "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": read_traffic(args.workload), "avg_ms": per_call_ms}
+        out["stream"] = {"calls": ncalls, "state_bytes": nstate * 4, "device_mem_delta_bytes": int(mem1 - mem0)}
+    else:
+        fwd_ms = float(np.mean([r[0].elapsed_time(r[1]) for r in recs]))
+        out["fwd_ms"] = fwd_ms
+        out["fwd_tokens_per_s"] = tokens / (fwd_ms * 1e-3)
+        out["fwd_GBps"] = FWD_BYTES_PER_TOKEN_LANE * tokens * J / (fwd_ms * 1e-3) / 1e9
+        if do_bwd:
+            bwd_ms = float(np.mean([r[1].elapsed_time(r[2]) for r in recs]))
+            out["bwd_ms"] = bwd_ms
+            alg = BWD_BYTES_PER_TOKEN_LANE * tokens * J
+            achieved = alg / (bwd_ms * 1e-3) / 1e9
+            out["roofline"] = {"bound": "hbm", "kernel": "bwd_kernel<2,4,true> (+ its partial-sum reduction)",
+                               "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                               "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
+                               "avg_ms": bwd_ms}
+        else:
+            out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<4,4>", "achieved": out["fwd_GBps"],
+                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": out["fwd_GBps"] / HBM_PEAK_GBS,
+                               "traffic": read_traffic(args.workload), "avg_ms": fwd_ms}
+
+    # ---- the fp64 oracle on the host cores, on a bounded sample of the same inputs (baseline only)
+    if not args.no_cpu_baseline:
+        from oracle import cawn_oracle as O
+        import gpu_util as G
+        Ls = min(L, 8192)
+        Bs = max(1, min(B, (48 << 20) // (Ls * J)))       # about 10-30 s of CPU work over the host cores
+        sub = {k: np.ascontiguousarray(inp[k][:Bs, :Ls]) for k in names}
+        cfg = O.Cfg(Bs, Ls, H, F, conv_k=Kc, gate_tau=wl.gate_tau)
+        t1 = time.perf_counter()
+        of = O.phase_fwd(cfg, sub["mag"], sub["ang"], inp["gamma"], inp["theta"], conv_w=inp["conv_w"],
+                         conv_b=inp["conv_b"], want_gate=False)
+        if do_bwd:
+            ob = O.phase_bwd(cfg, sub["mag"], sub["ang"], inp["gamma"], inp["theta"], sub["dz_re"], sub["dz_im"],
+                             conv_w=inp["conv_w"], conv_b=inp["conv_b"])
+        cpu_s = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": Bs * Ls / cpu_s, "unit": "tokens/s", "cores": O.max_threads(),
+                               "kind": "oracle", "seconds": cpu_s,
+                               "sample": f"first {Bs} batch rows x {Ls} tokens x {J} lanes of the same inputs, "
+                                         f"{'fwd+bwd' if do_bwd else 'fwd'}, fp64, OpenMP over lanes"}
+        # parity of the timed configuration on that sample (the kernels are time-local: the first Ls
+        # tokens of a row do not depend on later ones; for the backward, compare a separate GPU run)
+        if not stream_mode:
+            s0 = sets[0]
+            step(0)
+            torch.cuda.synchronize()
+            err = max(G.rel_err(s0["z_re"][:Bs, :Ls].cpu().numpy(), of["z_re"]),
+                      G.rel_err(s0["z_im"][:Bs, :Ls].cpu().numpy(), of["z_im"]))
+            out["max_rel_err_fwd_sample"] = err
+            if do_bwd and Ls == L:
+                gb = G.run_fwd_bwd({**sub, **{k: inp[k] for k in ("gamma", "theta", "conv_w", "conv_b")}}, Bs, Ls, H, F,
+                                   conv_k=Kc, gate_tau=wl.gate_tau)
+                out["max_rel_err_bwd_sample"] = max(G.rel_err(gb[k], ob[k]) for k in
+                                                    ("dmag", "dang", "dgamma", "dtheta", "dconv_w", "dconv_b"))
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
