@@ -17,14 +17,16 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every translation unit (always: callers rebuild after a source change)."""
+def build(verbose: bool = False, defines=(), out: str = OUT, objdir: str = CSRC) -> str:
+    """Compile every translation unit (always: callers rebuild after a source change).
+    `defines` (e.g. ["CAWN_NSTEP=4"]) and `out` let a tuning sweep build geometry variants."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
+    os.makedirs(objdir, exist_ok=True)
 
     def cc(src):
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        cmd = [hipcc, *FLAGS, *[f"-D{d}" for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
@@ -32,11 +34,11 @@ def build(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(cc, SOURCES))
-    cmd = [hipcc, "-shared", "--offload-arch=gfx950", "-fno-gpu-rdc", "-o", OUT, *objs]
+    cmd = [hipcc, "-shared", "--offload-arch=gfx950", "-fno-gpu-rdc", "-o", out, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    return OUT
+    return out
 
 
 if __name__ == "__main__":

@@ -27,7 +27,7 @@ static WsLayout make_layout(const cawn_desc *d)
     WsLayout w{};
     w.J = d->H * d->F;
     w.Jp = (int)align_up(w.J, 64);
-    w.Jp128 = (int)align_up(w.J, 128);
+    w.Jp128 = (int)align_up(w.J, 256);   // covers the widest lane block of any kernel variant
     w.nT = (d->L + TILE_T - 1) / TILE_T;
     const int kc = d->conv_k > MAX_KC ? MAX_KC : d->conv_k;
     const size_t tiles_rows = (size_t)d->B * (w.nT > 0 ? w.nT : 1);
@@ -44,6 +44,10 @@ static WsLayout make_layout(const cawn_desc *d)
     o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(float), 256);
     w.off_part = o;
     o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
+    w.off_dbg = o;
+#ifdef CAWN_TIMING
+    o += (size_t)MAX_TILES * 16 * sizeof(unsigned long long);
+#endif
     w.total = o;
     return w;
 }
@@ -486,6 +490,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     a.conv_clamp = d->conv_clamp; a.out_clamp = d->out_clamp;
     a.spin_limit = g_spin_limit.load();
     a.total_tiles = (uint32_t)tiles;
+    a.dbg = reinterpret_cast<unsigned long long *>(ws + w.off_dbg);
     if (launch_fwd(a, d->conv_k, vec, s) != hipSuccess) return CAWN_ELAUNCH;
     return CAWN_OK;
 }

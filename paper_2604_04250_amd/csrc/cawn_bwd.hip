@@ -316,8 +316,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
                 BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
                 BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
             }
-            if (!look_back<V, true>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
-                                    hr, hi, qr, qi, a.spin_limit, cr, ci)) {
+            if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
+                                         lv, hr, hi, qr, qi, a.spin_limit, cr, ci)) {
                 if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }

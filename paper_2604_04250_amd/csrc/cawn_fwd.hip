@@ -17,6 +17,14 @@
 
 namespace cawn {
 
+// Tuning aid, compiled only with -DCAWN_TIMING: per-tile time stamps (100 MHz counter) of the
+// chain-owning thread, written behind the parameter partials in the workspace.
+#ifdef CAWN_TIMING
+#define CAWN_STAMP(k) do { if (tid == (NSEG - 1) * LPR) a.dbg[(size_t)ticket * 16 + (k)] = wall_clock64(); } while (0)
+#else
+#define CAWN_STAMP(k) do { } while (0)
+#endif
+
 template <int V> struct Vec;
 template <> struct Vec<1> {
     static __device__ __forceinline__ void ld(float (&d)[1], const float *p) { d[0] = *p; }
@@ -46,7 +54,7 @@ template <> struct Vec<4> {
 };
 
 template <int V, int KC>
-__global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a)
+__global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
     constexpr int NSTEP = Geom::NSTEP, NSEG = Geom::NSEG, LPR = FwdLPR;
     constexpr int JB = V * LPR;
@@ -65,6 +73,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
     }
     __syncthreads();
     const uint32_t ticket = sTicket;
+    CAWN_STAMP(0);
     const int lb = ticket % a.nLB;
     const int rest = ticket / a.nLB;
     const int b = rest % a.B, tt = rest / a.B;
@@ -122,6 +131,10 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
         }
     }
 
+#ifdef CAWN_TIMING
+    wait_stores_done();
+#endif
+    CAWN_STAMP(1);
     // ---- front-end, phasors, local scan from zero
     float pr[NSTEP][V], pi[NSTEP][V];
     float Er[V], Ei[V];
@@ -181,12 +194,14 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
     }
 
     // ---- segments meet in LDS
+    CAWN_STAMP(2);
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         sE[seg][0][lv * V + v] = Er[v];
         sE[seg][1][lv * V + v] = Ei[v];
     }
     __syncthreads();
+    CAWN_STAMP(3);
     float Xr[V], Xi[V];   // state entering my segment, from a zero tile input
 #pragma unroll
     for (int v = 0; v < V; ++v) Xr[v] = Xi[v] = 0.f;
@@ -200,31 +215,26 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
             Xi[v] = ni;
         }
     }
+    // ---- chain.  The threads of the last segment own the tile aggregate: they publish it, do the
+    //      look-back and publish the prefix, all within their own wave (stores are waited for with
+    //      that wave's vmcnt, so no workgroup barrier sits on the publication path).
     const bool is_tail_seg = seg == NSEG - 1;
-    float Tr[V], Ti[V];   // tile aggregate (last segment's threads only)
+    float Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
     const size_t slot = (size_t)ticket * 2 * JB + lv * V;
     if (is_tail_seg) {
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             Tr[v] = __builtin_fmaf(pfr[v], Xr[v], __builtin_fmaf(-pfi[v], Xi[v], Er[v]));
             Ti[v] = __builtin_fmaf(pfi[v], Xr[v], __builtin_fmaf(pfr[v], Xi[v], Ei[v]));
+            hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
         }
-        if (tt > 0) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                coherent_store(a.agg + slot + v, Tr[v]);
-                coherent_store(a.agg + slot + JB + v, Ti[v]);
-            }
+        if (active) {   // lambda^TILE_T as a double-float
+            const float *tb = a.table + j0;
+            Vec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
+            Vec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
+            Vec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
+            Vec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
         }
-    }
-    if (tt > 0) {
-        wait_stores_done();
-        __syncthreads();
-        if (tid == 0) flag_store(a.flags + ticket, ST_AGG);
-    }
-
-    // ---- carry into the tile: state_in for the first tile, look-back otherwise
-    if (seg == 0) {
         float cr[V], ci[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) cr[v] = ci[v] = 0.f;
@@ -234,22 +244,23 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
                 Vec<V>::ld(ci, a.state_in + ((size_t)b * 2 + 1) * a.J + j0);
             }
         } else {
-            float hr[V], hi[V], qr[V], qi[V];   // lambda^T as a double-float
+            if (tt + 1 < a.nT) {
 #pragma unroll
-            for (int v = 0; v < V; ++v) hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
-            if (active) {
-                const float *tb = a.table + j0;
-                Vec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
-                Vec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
-                Vec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
-                Vec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+                for (int v = 0; v < V; ++v) {
+                    coherent_store(a.agg + slot + v, Tr[v]);
+                    coherent_store(a.agg + slot + JB + v, Ti[v]);
+                }
+                wait_stores_done();
+                if (lv == 0) flag_store(a.flags + ticket, ST_AGG);
             }
-            if (!look_back<V, false>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, tt, JB, lv * V,
-                                     hr, hi, qr, qi, a.spin_limit, cr, ci)) {
+            CAWN_STAMP(4);
+            if (!look_back<V, false, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, tt, JB, lv * V,
+                                          lv, hr, hi, qr, qi, a.spin_limit, cr, ci)) {
                 // gave up: flag the workspace, keep going so that every wave exits
                 if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+        CAWN_STAMP(5);
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             sCarry[0][lv * V + v] = cr[v];
@@ -263,6 +274,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
     }
     __syncthreads();
 
+    CAWN_STAMP(6);
     // ---- true state entering my segment; the tile's inclusive prefix for the chain
     float Sr[V], Si[V];
 #pragma unroll
@@ -271,35 +283,26 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
         Sr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(-psi[v], ci, Xr[v]));
         Si[v] = __builtin_fmaf(psi[v], cr, __builtin_fmaf(psr[v], ci, Xi[v]));
     }
-    const bool publish_prefix = (tt + 1 < a.nT);
-    if (is_tail_seg && publish_prefix) {
-        float hr[V], hi[V], qr[V], qi[V];
+    if (is_tail_seg) {
+        if (tt + 1 < a.nT) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
-        if (active) {
-            const float *tb = a.table + j0;
-            Vec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
-            Vec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
-            Vec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
-            Vec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+            for (int v = 0; v < V; ++v) {
+                const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
+                float P_r, P_i;
+                chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr, ci, P_r, P_i);
+                coherent_store(a.pre + slot + v, P_r);
+                coherent_store(a.pre + slot + JB + v, P_i);
+            }
+            wait_stores_done();
+            if (lv == 0) flag_store(a.flags + ticket, ST_PREFIX);
         }
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
-            float P_r, P_i;
-            chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr, ci, P_r, P_i);
-            coherent_store(a.pre + slot + v, P_r);
-            coherent_store(a.pre + slot + JB + v, P_i);
+        if (lv == 0) {
+            wait_stores_done();
+            const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (old + 1 == a.total_tiles) sLast = 1;
         }
     }
-    wait_stores_done();
-    __syncthreads();
-    if (tid == 0) {
-        if (publish_prefix) flag_store(a.flags + ticket, ST_PREFIX);
-        wait_stores_done();
-        const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old + 1 == a.total_tiles) sLast = 1;
-    }
+    CAWN_STAMP(7);
 
     // ---- replay from the true state, clamp, store
 #pragma unroll
@@ -326,6 +329,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR) void fwd_kernel(const FwdArgs a
         }
     }
 
+    CAWN_STAMP(8);
     // ---- conv history for the next call: last HALO pre-conv rows (written by the last tile,
     //      after its carry arrived, i.e. after the first tile has consumed state_in: safe in place)
     if (HALO > 0 && a.state_out && tt == a.nT - 1 && seg == 0 && active) {

@@ -10,13 +10,37 @@ namespace cawn {
 // ------------------------------------------------------------------------------------ geometry
 // One tile = JB lanes x TILE_T tokens of one batch row, owned by one workgroup.  A thread owns
 // V adjacent lanes and NSTEP consecutive tokens ("segment"); NSEG segments make the tile.
-constexpr int TILE_T = 64;           // tokens per tile: granularity of carries and checkpoints
+#ifndef CAWN_TILE_T
+#define CAWN_TILE_T 64
+#endif
+#ifndef CAWN_NSTEP
+#define CAWN_NSTEP 8
+#endif
+#ifndef CAWN_FWD_V
+#define CAWN_FWD_V 4
+#endif
+#ifndef CAWN_FWD_LPR
+#define CAWN_FWD_LPR 32
+#endif
+#ifndef CAWN_BWD_V
+#define CAWN_BWD_V 2
+#endif
+#ifndef CAWN_BWD_LPR
+#define CAWN_BWD_LPR 32
+#endif
+#ifndef CAWN_FWD_WAVES
+#define CAWN_FWD_WAVES 2      // waves per SIMD the forward kernel's register budget is set for
+#endif
+#ifndef CAWN_BWD_WAVES
+#define CAWN_BWD_WAVES 1
+#endif
+constexpr int TILE_T = CAWN_TILE_T;  // tokens per tile: granularity of carries and checkpoints
 
 struct Geom {
-    static constexpr int NSTEP = 8, NSEG = TILE_T / NSTEP;
+    static constexpr int NSTEP = CAWN_NSTEP, NSEG = TILE_T / NSTEP;
 };
-constexpr int FwdV = 4, FwdLPR = 32;  // forward: float4 per thread, 32 threads per row, 256 threads
-constexpr int BwdV = 2, BwdLPR = 32;  // backward: float2 per thread (it keeps more per token)
+constexpr int FwdV = CAWN_FWD_V, FwdLPR = CAWN_FWD_LPR;  // forward: lanes per thread, threads per row
+constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;  // backward (it keeps more per token)
 constexpr int MAX_KC = 4;
 constexpr uint32_t MAX_TILES = 1u << 20;   // capacity of the fixed tile-status zone
 
@@ -48,7 +72,7 @@ static_assert(sizeof(WsHeader) == 256, "header size");
 
 struct WsLayout {
     int J, Jp, Jp128, nT;
-    size_t off_flags, off_table, off_agg, off_pre, off_halo, off_part, total;
+    size_t off_flags, off_table, off_agg, off_pre, off_halo, off_part, off_dbg, total;
 };
 
 // Tile status words of the decoupled look-back.
@@ -76,6 +100,7 @@ struct FwdArgs {
     GateSet gs;
     uint32_t spin_limit;
     uint32_t total_tiles;
+    unsigned long long *dbg;     // -DCAWN_TIMING builds only
 };
 
 struct BwdArgs {
@@ -204,44 +229,77 @@ __device__ __forceinline__ void chain_step(float Tr, float Ti, float hr, float h
     }
 }
 
-// Decoupled look-back for V lanes starting at lane offset `lo` of the tile slots.  `pred` is the
-// chain predecessor's tile index, `depth` the number of tiles before this one in the chain
-// (the chain's first tile always publishes a prefix).  Pass 1 walks back over status words until
-// it meets a published prefix; pass 2 walks forward again from that prefix through the
-// aggregates.  Returns false if a wait gave up (carry is then meaningless).
-template <int V, bool CONJ>
+// Decoupled look-back, run by one group of LPR consecutive threads of a wave (thread lv of the
+// group owns V lanes at lane offset `lo` of the tile slots).  `pred` is the chain predecessor's
+// tile index, `depth` the number of tiles before this one in the chain (the chain's first tile
+// always publishes a prefix).
+//   Pass 1: the group reads the status words of up to LPR predecessors at once (one memory round
+//           trip per window instead of one per tile) until it has found the nearest published
+//           prefix with only aggregates between it and this tile; it waits (bounded) on a tile
+//           that has published nothing yet.
+//   Pass 2: walks forward again from that prefix through the aggregates with chain_step().
+// Returns false if a wait gave up (the carry is then meaningless).
+template <int V, bool CONJ, int LPR>
 __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *agg, const float *pre,
-                                          uint32_t pred, uint32_t stride, int depth, int JB, int lo,
+                                          uint32_t pred, uint32_t stride, int depth, int JB, int lo, int lv,
                                           const float (&hr)[V], const float (&hi)[V], const float (&qr)[V],
                                           const float (&qi)[V], uint32_t spin_limit, float (&cr)[V],
                                           float (&ci)[V])
 {
-    uint32_t idx = pred;
-    int k = 0;      // aggregates between the prefix found and this tile
-    for (;;) {
-        const uint32_t st = wait_flag(flags + idx, spin_limit);
-        if (st == ST_NONE) return false;
-        if (st >= ST_PREFIX) break;
-        if (k + 1 >= depth) return false;   // cannot happen: the chain's first tile has a prefix
-        ++k;
-        idx -= stride;
+    const int gshift = (int)(threadIdx.x & 63) - lv;
+    const unsigned long long gmask = LPR >= 64 ? ~0ull : ((1ull << LPR) - 1ull);
+    int base = 0;   // tiles pred, pred-stride, ..., pred-(base-1)*stride are known to hold aggregates
+    int k = -1;     // distance of the nearest prefix
+    uint32_t spins = 0;
+    while (base < depth) {
+        const int w = depth - base < LPR ? depth - base : LPR;
+        uint32_t st = ST_AGG;
+        if (lv < w) st = flag_load(flags + (pred - (uint32_t)(base + lv) * stride));
+        compiler_fence();
+        const unsigned long long m_none = (__ballot(st == ST_NONE) >> gshift) & gmask;
+        const unsigned long long m_pre = (__ballot(st >= ST_PREFIX) >> gshift) & gmask;
+        const int fn = m_none ? __builtin_ctzll(m_none) : 64;
+        const int fp = m_pre ? __builtin_ctzll(m_pre) : 64;
+        if (fp < fn) { k = base + fp; break; }
+        if (fn < 64) {
+            base += fn;
+            if (++spins > spin_limit) return false;
+            __builtin_amdgcn_s_sleep(1);
+        } else {
+            base += w;
+        }
     }
-    const float *src = pre + (size_t)idx * 2 * JB + lo;
+    if (k < 0) return false;   // cannot happen: the chain's first tile publishes a prefix
+    const float *src = pre + (size_t)(pred - (uint32_t)k * stride) * 2 * JB + lo;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         cr[v] = coherent_load(src + v);
         ci[v] = coherent_load(src + JB + v);
     }
-    for (; k > 0; --k) {
-        idx += stride;
-        const float *ag = agg + (size_t)idx * 2 * JB + lo;
+    constexpr int NB = 4;      // aggregates fetched per round trip
+    for (int d = k - 1; d >= 0; d -= NB) {
+        float er[NB][V], ei[NB][V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const float er = coherent_load(ag + v), ei = coherent_load(ag + JB + v);
-            float nr, ni;
-            chain_step<CONJ>(er, ei, hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
-            cr[v] = nr;
-            ci[v] = ni;
+        for (int n = 0; n < NB; ++n) {
+            const int dd = d - n < 0 ? 0 : d - n;
+            const float *ag = agg + (size_t)(pred - (uint32_t)dd * stride) * 2 * JB + lo;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                er[n][v] = coherent_load(ag + v);
+                ei[n][v] = coherent_load(ag + JB + v);
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            if (d - n >= 0) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float nr, ni;
+                    chain_step<CONJ>(er[n][v], ei[n][v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
+                    cr[v] = nr;
+                    ci[v] = ni;
+                }
+            }
         }
     }
     return true;
