@@ -486,6 +486,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     a.pre = reinterpret_cast<float *>(ws + w.off_pre);
     a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
     a.amp_mode = d->amp_mode;
+    a.small_angle = (d->conv_k > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;   // |angle| <= SiLU(clamp) <= 41 revolutions
     a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
     a.conv_clamp = d->conv_clamp; a.out_clamp = d->out_clamp;
     a.spin_limit = g_spin_limit.load();
@@ -568,6 +569,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     a.part = reinterpret_cast<float *>(ws + w.off_part);
     a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
     a.amp_mode = d->amp_mode; a.want_param = want_param ? 1 : 0;
+    a.small_angle = (kc > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;
     a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
     a.conv_clamp = d->conv_clamp; a.grad_clamp = d->grad_clamp;
     a.spin_limit = g_spin_limit.load();

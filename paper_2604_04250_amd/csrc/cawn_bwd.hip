@@ -57,7 +57,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
     const int tid = threadIdx.x;
     const int lv = tid % LPR, seg = tid / LPR;
     if (tid == 0) {
-        sTicket = __hip_atomic_fetch_add(&a.hdr->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sTicket = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sLast = 0;
     }
     __syncthreads();
@@ -615,7 +615,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
     if (sLast) {
         for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + i, ST_NONE);
         if (tid == 0) {
-            flag_store(&a.hdr->ticket, 0u);
+            flag_store(&a.hdr->ticket[0], 0u);
             flag_store(&a.hdr->done, 0u);
         }
     }

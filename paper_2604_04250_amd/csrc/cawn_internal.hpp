@@ -62,13 +62,14 @@ inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k;
 // Workspace: [header 256 B][tile status words, fixed MAX_TILES capacity][lane table][aggregates]
 // [prefixes][backward conv halo][backward parameter partials].  Header and status words are zero
 // between calls (the tile that finishes last clears them), whatever descriptor the last call had.
+constexpr int MAX_QUEUES = 64;
 struct WsHeader {
-    uint32_t ticket;           // next tile to hand out
-    uint32_t done;             // tiles that have finished their look-back
-    uint32_t error;            // sticky: a tile gave up waiting
-    uint32_t pad[61];
+    uint32_t ticket[MAX_QUEUES];   // per work queue: next tile to hand out
+    uint32_t done;                 // tiles finished
+    uint32_t error;                // sticky: a tile gave up waiting
+    uint32_t pad[256 - MAX_QUEUES - 2];
 };
-static_assert(sizeof(WsHeader) == 256, "header size");
+static_assert(sizeof(WsHeader) == 1024, "header size");
 
 struct WsLayout {
     int J, Jp, Jp128, nT;
@@ -94,7 +95,9 @@ struct FwdArgs {
     uint32_t *flags;
     float *agg, *pre;
     int B, L, J, Jp, nT, nLB;
+    int nQ;                      // work queues (a queue owns lane blocks q, q+nQ, ...)
     int amp_mode;
+    int small_angle;             // angles are bounded (conv clamp): skip the two-term range reduction
     long long isb, ist, osb, ost;
     float conv_clamp, out_clamp;
     GateSet gs;
@@ -115,6 +118,8 @@ struct BwdArgs {
     uint32_t *flags;
     float *agg, *pre, *halo, *part;
     int B, L, J, Jp, nT, nLB;
+    int nQ;
+    int small_angle;
     int amp_mode, want_param;
     long long isb, ist, osb, ost;
     float conv_clamp, grad_clamp;
@@ -131,7 +136,7 @@ hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s);
 
 #if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
 // ------------------------------------------------------------------------------ device helpers
-__device__ __forceinline__ float clampf(float v, float c) { return __builtin_fminf(__builtin_fmaxf(v, -c), c); }
+__device__ __forceinline__ float clampf(float v, float c) { return __builtin_amdgcn_fmed3f(v, -c, c); }
 
 // sigmoid(z) with the hardware exp2 / reciprocal (both ~1 ulp).
 __device__ __forceinline__ float sigmoid_fast(float z)
@@ -151,6 +156,14 @@ __device__ __forceinline__ void sincos_fast(float phi, float &s, float &c)
     float r = __builtin_fmaf(-k, TWO_PI_HI, phi);
     r = __builtin_fmaf(-k, TWO_PI_LO, r);
     float x = r * INV_2PI;
+    s = __builtin_amdgcn_sinf(x);
+    c = __builtin_amdgcn_cosf(x);
+}
+
+// Same, for angles known to be small (a few revolutions): the hardware reduces the range itself.
+__device__ __forceinline__ void sincos_small(float phi, float &s, float &c)
+{
+    const float x = phi * 0.15915494309189535f;
     s = __builtin_amdgcn_sinf(x);
     c = __builtin_amdgcn_cosf(x);
 }
@@ -244,8 +257,10 @@ __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *ag
                                           uint32_t pred, uint32_t stride, int depth, int JB, int lo, int lv,
                                           const float (&hr)[V], const float (&hi)[V], const float (&qr)[V],
                                           const float (&qi)[V], uint32_t spin_limit, float (&cr)[V],
-                                          float (&ci)[V])
+                                          float (&ci)[V], uint32_t *own_agg_flag = nullptr)
 {
+    // own_agg_flag: this tile's status word when its aggregate stores are still in flight; it is set
+    // to ST_AGG once they have completed, which is waited for together with the first window.
     const int gshift = (int)(threadIdx.x & 63) - lv;
     const unsigned long long gmask = LPR >= 64 ? ~0ull : ((1ull << LPR) - 1ull);
     int base = 0;   // tiles pred, pred-stride, ..., pred-(base-1)*stride are known to hold aggregates
@@ -255,6 +270,11 @@ __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *ag
         const int w = depth - base < LPR ? depth - base : LPR;
         uint32_t st = ST_AGG;
         if (lv < w) st = flag_load(flags + (pred - (uint32_t)(base + lv) * stride));
+        if (own_agg_flag) {
+            wait_stores_done();
+            if (lv == 0) flag_store(own_agg_flag, ST_AGG);
+            own_agg_flag = nullptr;
+        }
         compiler_fence();
         const unsigned long long m_none = (__ballot(st == ST_NONE) >> gshift) & gmask;
         const unsigned long long m_pre = (__ballot(st >= ST_PREFIX) >> gshift) & gmask;
