@@ -33,7 +33,7 @@ static WsLayout make_layout(const cawn_desc *d)
     const size_t tiles_rows = (size_t)d->B * (w.nT > 0 ? w.nT : 1);
     size_t o = sizeof(WsHeader);
     w.off_flags = o;
-    o += (size_t)MAX_TILES * sizeof(uint32_t);
+    o += (size_t)MAX_TILES * FLAG_STRIDE * sizeof(uint32_t);
     w.off_table = o;
     o = align_up(o + (size_t)lane_rows(kc) * w.Jp * sizeof(float), 256);
     w.off_agg = o;
@@ -261,17 +261,18 @@ __global__ __launch_bounds__(256) void syntax_conv_kernel(const float *__restric
     }
 }
 
-// Sum the backward tiles' parameter partials in a fixed order: part [nparts][rows][JBpad-blocked].
-// Layout of one partial: [tile][row][JB] with tile = (tt_rev*B + b)*nLB + lb.  Thread (lane, g)
-// sums tiles g, g+G, ... of its lane's block, then the G sub-sums meet in LDS in index order.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, float *__restrict__ out0,
-                                                              float *__restrict__ out1, float *__restrict__ out2,
-                                                              float *__restrict__ out3, int rows, int conv_k, int J,
-                                                              int JB, int nLB, int chains, int accumulate)
+// Sum the backward tiles' parameter partials in a fixed order.  One partial is [tile][row][JB] with
+// tile = chain * nLB + lb (chain = position-in-time * B + b).  Block = 32 lanes x 32 groups: group g
+// sums chains g, g+32, ... of its lane's block in increasing order, then the 32 sub-sums meet in LDS
+// and are added in index order -- the association is fixed, so results are bitwise repeatable.
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, float *__restrict__ out0,
+                                                               float *__restrict__ out1, float *__restrict__ out2,
+                                                               float *__restrict__ out3, int rows, int conv_k, int J,
+                                                               int JB, int nLB, int chains, int accumulate)
 {
-    // grid: (ceil(J/32), rows); block: 32 lanes x 8 groups
-    constexpr int G = 8;
-    __shared__ float sm[G][32];
+    // grid: (ceil(J/32), rows)
+    constexpr int G = 32;
+    __shared__ float sm[G][33];
     const int lane = threadIdx.x % 32, g = threadIdx.x / 32;
     const int j = blockIdx.x * 32 + lane;
     const int row = blockIdx.y;
@@ -288,7 +289,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     if (g == 0 && j < J) {
         float s = 0.0f;
 #pragma unroll
-        for (int q = 0; q < G; ++q) s += sm[q][lane];
+        for (int qq = 0; qq < G; ++qq) s += sm[qq][lane];
         // rows: 0 dgamma, 1 dtheta, 2 dbias_m, 3 dbias_a, 4 + s*conv_k + i: dw[s][j][i]
         float *dst = nullptr;
         if (row == 0) dst = out0 ? out0 + j : nullptr;
@@ -359,7 +360,7 @@ const char *cawn_status_string(int st)
 
 int cawn_workspace_init(void *workspace, size_t bytes, void *stream)
 {
-    const size_t need = sizeof(WsHeader) + (size_t)MAX_TILES * sizeof(uint32_t);
+    const size_t need = sizeof(WsHeader) + (size_t)MAX_TILES * FLAG_STRIDE * sizeof(uint32_t);
     if (!workspace) return CAWN_EINVAL;
     if (bytes < need || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
     hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream,
@@ -487,6 +488,8 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
     a.amp_mode = d->amp_mode;
     a.small_angle = (d->conv_k > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;   // |angle| <= SiLU(clamp) <= 41 revolutions
+    a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&
+                 (!state_in || aligned(state_in, 16))) ? 1 : 0;
     a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
     a.conv_clamp = d->conv_clamp; a.out_clamp = d->out_clamp;
     a.spin_limit = g_spin_limit.load();
@@ -570,6 +573,8 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
     a.amp_mode = d->amp_mode; a.want_param = want_param ? 1 : 0;
     a.small_angle = (kc > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;
+    a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&
+                 (!state_in || aligned(state_in, 16))) ? 1 : 0;
     a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
     a.conv_clamp = d->conv_clamp; a.grad_clamp = d->grad_clamp;
     a.spin_limit = g_spin_limit.load();
@@ -577,7 +582,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     if (launch_bwd(a, kc, vec, s) != hipSuccess) return CAWN_ELAUNCH;
     if (want_param) {
         const int rows = part_rows(kc);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((J + 31) / 32), rows), dim3(256), 0, s, a.part,
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((J + 31) / 32), rows), dim3(1024), 0, s, a.part,
                            dgamma, dtheta, dconv_w, dconv_b, rows, kc > 0 ? kc : 1, (int)J, JB, nLB,
                            d->B * w.nT, d->accumulate_param_grads);
         if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;

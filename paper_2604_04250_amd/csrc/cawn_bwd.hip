@@ -6,7 +6,11 @@
 //
 // Same three-level structure as the forward, run against time: tiles of one (batch row, lane
 // block) form a chain from the last tile to the first, joined by a decoupled look-back over
-// adjoint aggregates.  Two things are added:
+// adjoint aggregates.  What differs:
+//   * the adjoint aggregate of a tile needs only the upstream gradients, so it is published
+//     BEFORE the expensive front-end recompute, which then hides the chain's memory round trips;
+//   * the pre-conv input rows are staged once per tile in LDS (direct global->LDS loads): the
+//     conv, its halo and the weight gradient all read them from there, not from registers;
 //   * parameter gradients need the forward state S[t-1]; it is rebuilt inside the tile from the
 //     checkpoint the forward stored for the tile's first token;
 //   * the transposed conv needs the conv pre-activation gradients of the next conv_k-1 tokens.
@@ -36,26 +40,32 @@ template <> struct BVec<2> {
 };
 
 template <int V, int KC, bool PARAM>
-__global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a)
+__global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
     constexpr int NSTEP = Geom::NSTEP, NSEG = Geom::NSEG, LPR = BwdLPR;
     constexpr int JB = V * LPR;
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
     constexpr int HALO1 = HALO > 0 ? HALO : 1;
     constexpr int KC1 = KC > 0 ? KC : 1;
-    constexpr int NR = NSTEP + HALO;
     constexpr int ROWS = 4 + 2 * KC;
+    constexpr int NT = NSEG * LPR, NW = NT / 64;
+    constexpr int NRT = TILE_T + HALO;             // staged rows per stream: time tile_t0-HALO+rr
+    constexpr int SROWS = ((2 * NRT + 3) / 4) * 4 + 4;
     static_assert(HALO <= NSTEP, "conv halo must fit in one segment");
+    static_assert(LPR == 32, "the partial-sum reduction pairs the two segments of a wave");
+    static_assert(JB <= 64 && 64 % JB == 0, "a staged row must fit a wave");
 
+    __shared__ __attribute__((aligned(16))) float sU[SROWS][JB];   // [stream*NRT + rr][lane]
     __shared__ float sEb[NSEG][2][JB];
     __shared__ float sEf[PARAM ? NSEG : 1][2][JB];
     __shared__ float sCarry[2][JB];
     __shared__ float sHalo[NSEG][HALO1][2][JB];
-    __shared__ float sRed[PARAM ? NSEG : 1][ROWS][JB];
+    __shared__ float sRed[PARAM ? NW : 1][ROWS][JB];
     __shared__ uint32_t sTicket, sLast;
 
     const int tid = threadIdx.x;
     const int lv = tid % LPR, seg = tid / LPR;
+    const int wave = tid >> 6, lane = tid & 63;
     if (tid == 0) {
         sTicket = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sLast = 0;
@@ -70,8 +80,56 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
     const int j0 = lb * JB + lv * V;
     const bool active = j0 < a.J;
     const int t0 = tt * TILE_T + seg * NSTEP;
+    const bool head = seg == 0;                       // owns the tile's adjoint aggregate and the chain
+    const bool chained = ttr > 0;                     // has a predecessor in the chain
+    const bool feeds = tt > 0;                        // has a successor in the chain
     const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
     const float *dtail_out = a.dstate_out ? a.dstate_out + (size_t)a.B * 2 * a.J : nullptr;
+
+    // ---- upstream gradients of my tokens (registers), then the tile's input rows (LDS)
+    float dzr[NSTEP][V], dzi[NSTEP][V];     // upstream dS, later overwritten by d(pre-activation)
+#pragma unroll
+    for (int i = 0; i < NSTEP; ++i) {
+        const int t = t0 + i;
+#pragma unroll
+        for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
+        if (active && t < a.L) {
+            const size_t off = (size_t)b * a.osb + (size_t)t * a.ost + j0;
+            BVec<V>::ld(dzr[i], a.dz_re + off);
+            BVec<V>::ld(dzi[i], a.dz_im + off);
+        }
+    }
+    // Rows outside [0, L) and lanes beyond J read a clamped (valid, finite) address: they only ever
+    // meet a zero adjoint.  Rows before a sequence start are zeroed at the point of use.
+    {
+        const int tile_t0 = tt * TILE_T;
+        const int LB = a.stage16 ? 16 : 4;
+        const int LR = JB * 4 / LB, RPI = 64 / LR;
+        const int ninst = (2 * NRT + RPI - 1) / RPI;
+        for (int i = wave; i < ninst; i += NW) {
+            int f = i * RPI + lane / LR;
+            if (f >= 2 * NRT) f = 2 * NRT - 1;
+            const int sidx = f >= NRT ? 1 : 0;
+            const int rr = f - sidx * NRT;
+            const int t = tile_t0 - HALO + rr;
+            int j = lb * JB + (lane % LR) * (LB / 4);
+            if (j >= a.J) j = 0;
+            const float *src;
+            if (HALO > 0 && t < 0 && tail_in) {
+                const int hrow = t + HALO < 0 ? 0 : t + HALO;
+                src = tail_in + ((size_t)(b * HALO + hrow) * 2 + sidx) * a.J + j;
+            } else {
+                const int tc = t < 0 ? 0 : (t >= a.L ? a.L - 1 : t);
+                src = (sidx ? a.ang : a.mag) + (size_t)b * a.isb + (size_t)tc * a.ist + j;
+            }
+#if defined(__HIP_DEVICE_COMPILE__)
+            if (a.stage16) __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 4, 0, 0);
+#else
+            (void)src;
+#endif
+        }
+    }
 
     // ---- lane constants
     float lr[V], li[V], pnr[V], pni[V], psr[V], psi[V], pfr[V], pfi[V], cth[V], sth[V], gam[V];
@@ -109,43 +167,17 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
         }
     }
 
-    // ---- loads: pre-conv rows t0-HALO .. t0+NSTEP-1, upstream gradients t0 .. t0+NSTEP-1
-    float um[NR][V], ua[NR][V];
-    float dzr[NSTEP][V], dzi[NSTEP][V];     // upstream dS, later overwritten by d(pre-activation)
+    // gradient of the carried state joins the last token
+    if (a.dstate_out && active && a.L - 1 >= t0 && a.L - 1 < t0 + NSTEP) {
+        float xr[V], xi[V];
+        BVec<V>::ld(xr, a.dstate_out + ((size_t)b * 2 + 0) * a.J + j0);
+        BVec<V>::ld(xi, a.dstate_out + ((size_t)b * 2 + 1) * a.J + j0);
 #pragma unroll
-    for (int r = 0; r < NR; ++r) {
-        const int t = t0 - HALO + r;
-#pragma unroll
-        for (int v = 0; v < V; ++v) um[r][v] = ua[r][v] = 0.f;
-        if (active) {
-            if (t >= 0 && t < a.L) {
-                const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + j0;
-                BVec<V>::ld(um[r], a.mag + off);
-                BVec<V>::ld(ua[r], a.ang + off);
-            } else if (HALO > 0 && t < 0 && tail_in && t + HALO >= 0) {
-                const size_t off = ((size_t)(b * HALO + (t + HALO)) * 2) * a.J + j0;
-                BVec<V>::ld(um[r], tail_in + off);
-                BVec<V>::ld(ua[r], tail_in + off + a.J);
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < NSTEP; ++i) {
-        const int t = t0 + i;
-#pragma unroll
-        for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
-        if (active && t < a.L) {
-            const size_t off = (size_t)b * a.osb + (size_t)t * a.ost + j0;
-            BVec<V>::ld(dzr[i], a.dz_re + off);
-            BVec<V>::ld(dzi[i], a.dz_im + off);
-            if (t == a.L - 1 && a.dstate_out) {   // gradient of the carried state joins the last token
-                float xr[V], xi[V];
-                BVec<V>::ld(xr, a.dstate_out + ((size_t)b * 2 + 0) * a.J + j0);
-                BVec<V>::ld(xi, a.dstate_out + ((size_t)b * 2 + 1) * a.J + j0);
+        for (int i = 0; i < NSTEP; ++i)
+            if (t0 + i == a.L - 1) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) { dzr[i][v] += xr[v]; dzi[i][v] += xi[v]; }
             }
-        }
     }
 
     // ---- adjoint from zero over my segment (needs only the upstream gradients)
@@ -162,99 +194,158 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
             Ebi[v] = ni;
         }
     }
-
-    // ---- front-end recompute
-    float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V], dsa[NSTEP][V];
-    float Efr[V], Efi[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) Efr[v] = Efi[v] = 0.f;
-#pragma unroll
-    for (int i = 0; i < NSTEP; ++i) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            float zm, xm, phi, km, ka;
-            if (KC > 0) {
-                zm = bm[v];
-                float za = ba[v];
-#pragma unroll
-                for (int k = 0; k < KC; ++k) {
-                    zm = __builtin_fmaf(wm[k][v], um[i + k][v], zm);
-                    za = __builtin_fmaf(wa[k][v], ua[i + k][v], za);
-                }
-                const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
-                const float sgm = sigmoid_fast(cm), sga = sigmoid_fast(ca);
-                xm = cm * sgm;
-                phi = ca * sga;
-                // SiLU'(z) = sig (1 + z (1 - sig)); the clamp passes gradient only inside its range
-                km = __builtin_fabsf(zm) <= a.conv_clamp ? sgm * __builtin_fmaf(cm, 1.0f - sgm, 1.0f) : 0.0f;
-                ka = __builtin_fabsf(za) <= a.conv_clamp ? sga * __builtin_fmaf(ca, 1.0f - sga, 1.0f) : 0.0f;
-            } else {
-                zm = um[i][v];
-                xm = zm;
-                phi = ua[i][v];
-                km = 1.0f;
-                ka = 1.0f;
-            }
-            float amp = xm;
-            if (a.amp_mode) {
-                const float sp = softplus_fast(xm);
-                amp = __builtin_fminf(sp, 10.0f);
-                km *= sp < 10.0f ? sigmoid_fast(xm) : 0.0f;
-            }
-            const bool g = in_gate(a.gs, zm);
-            float s, c;
-            sincos_fast(phi, s, c);
-            const float agv = g ? amp : 0.0f;
-            cs[i][v] = c;
-            sn[i][v] = s;
-            dsm[i][v] = km;
-            if (PARAM) {
-                ag[i][v] = agv;
-                dsa[i][v] = ka;
-                const float pr = agv * c, pi = agv * s;
-                const float nr = __builtin_fmaf(lr[v], Efr[v], __builtin_fmaf(-li[v], Efi[v], pr));
-                const float ni = __builtin_fmaf(li[v], Efr[v], __builtin_fmaf(lr[v], Efi[v], pi));
-                Efr[v] = nr;
-                Efi[v] = ni;
-            } else {
-                ag[i][v] = agv * ka;       // only the product is needed without parameter gradients
-                dsa[i][v] = 0.f;
-            }
-        }
-    }
-
-    // ---- segments meet in LDS
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         sEb[seg][0][lv * V + v] = Ebr[v];
         sEb[seg][1][lv * V + v] = Ebi[v];
-        if (PARAM) {
-            sEf[seg][0][lv * V + v] = Efr[v];
-            sEf[seg][1][lv * V + v] = Efi[v];
-        }
     }
     __syncthreads();
     float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
 #pragma unroll
     for (int v = 0; v < V; ++v) Xr[v] = Xi[v] = 0.f;
-    for (int q = NSEG - 1; q > seg; --q) {
+    for (int qq = NSEG - 1; qq > seg; --qq) {
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            const float er = sEb[q][0][lv * V + v], ei = sEb[q][1][lv * V + v];
+            const float er = sEb[qq][0][lv * V + v], ei = sEb[qq][1][lv * V + v];
             const float nr = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], er));
             const float ni = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], ei));
             Xr[v] = nr;
             Xi[v] = ni;
         }
     }
-    float Fr[V], Fi[V];     // forward state entering my segment
-    if (PARAM) {
+
+    // ---- chain, first half: the aggregate goes out before the front-end recompute
+    float Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
+    const size_t slot = (size_t)ticket * 2 * JB + lv * V;
+    if (head) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) Fr[v] = Fi[v] = 0.f;
-        for (int q = 0; q < seg; ++q) {
+        for (int v = 0; v < V; ++v) {
+            Tr[v] = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], Ebr[v]));
+            Ti[v] = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], Ebi[v]));
+            hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
+        }
+        if (active) {
+            const float *tb = a.table + j0;
+            BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
+            BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
+            BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
+            BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+        }
+        if (chained && feeds) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                const float er = sEf[q][0][lv * V + v], ei = sEf[q][1][lv * V + v];
+                coherent_store(a.agg + slot + v, Tr[v]);
+                coherent_store(a.agg + slot + JB + v, Ti[v]);
+            }
+        }
+    }
+    // the staged rows have landed; so have the aggregate stores of the head group's wave
+    wait_stores_done();
+    if (tid == 0 && chained && feeds) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, ST_AGG);
+    __syncthreads();
+
+    // ---- front-end recompute, rows from LDS as a sliding window
+    float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V], dsa[NSTEP][V];
+    float Efr[V], Efi[V];
+    {
+        float wnm[KC1][V], wna[KC1][V];
+        const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
+#pragma unroll
+        for (int k = 0; k < KC1 - 1; ++k) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                wnm[k][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
+                wna[k][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) Efr[v] = Efi[v] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                wnm[KC1 - 1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
+                wna[KC1 - 1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
+            }
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float zm, xm, phi, km, ka;
+                if (KC > 0) {
+                    zm = bm[v];
+                    float za = ba[v];
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) {
+                        zm = __builtin_fmaf(wm[k][v], wnm[k][v], zm);
+                        za = __builtin_fmaf(wa[k][v], wna[k][v], za);
+                    }
+                    const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
+                    const float sgm = sigmoid_fast(cm), sga = sigmoid_fast(ca);
+                    xm = cm * sgm;
+                    phi = ca * sga;
+                    // SiLU'(z) = sig (1 + z (1 - sig)); the clamp passes gradient only inside its range
+                    km = __builtin_fabsf(zm) <= a.conv_clamp ? sgm * __builtin_fmaf(cm, 1.0f - sgm, 1.0f) : 0.0f;
+                    ka = __builtin_fabsf(za) <= a.conv_clamp ? sga * __builtin_fmaf(ca, 1.0f - sga, 1.0f) : 0.0f;
+                } else {
+                    zm = wnm[0][v];
+                    xm = zm;
+                    phi = wna[0][v];
+                    km = 1.0f;
+                    ka = 1.0f;
+                }
+                float amp = xm;
+                if (a.amp_mode) {
+                    const float sp = softplus_fast(xm);
+                    amp = __builtin_fminf(sp, 10.0f);
+                    km *= sp < 10.0f ? sigmoid_fast(xm) : 0.0f;
+                }
+                const bool g = in_gate(a.gs, zm);
+                float s, c;
+                if (a.small_angle) sincos_small(phi, s, c);
+                else sincos_fast(phi, s, c);
+                const float agv = g ? amp : 0.0f;
+                cs[i][v] = c;
+                sn[i][v] = s;
+                dsm[i][v] = km;
+                if (PARAM) {
+                    ag[i][v] = agv;
+                    dsa[i][v] = ka;
+                    const float pr = agv * c, pi = agv * s;
+                    const float nr = __builtin_fmaf(lr[v], Efr[v], __builtin_fmaf(-li[v], Efi[v], pr));
+                    const float ni = __builtin_fmaf(li[v], Efr[v], __builtin_fmaf(lr[v], Efi[v], pi));
+                    Efr[v] = nr;
+                    Efi[v] = ni;
+                } else {
+                    ag[i][v] = agv * ka;       // only the product is needed without parameter gradients
+                    dsa[i][v] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < KC1 - 1; ++k) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    wnm[k][v] = wnm[k + 1][v];
+                    wna[k][v] = wna[k + 1][v];
+                }
+            }
+        }
+    }
+
+    // ---- forward state entering my segment (checkpoint + earlier segments), then S[t-1] per token
+    float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];
+    if (PARAM) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            sEf[seg][0][lv * V + v] = Efr[v];
+            sEf[seg][1][lv * V + v] = Efi[v];
+        }
+        __syncthreads();
+        float Fr[V], Fi[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) Fr[v] = Fi[v] = 0.f;
+        for (int qq = 0; qq < seg; ++qq) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float er = sEf[qq][0][lv * V + v], ei = sEf[qq][1][lv * V + v];
                 const float nr = __builtin_fmaf(pnr[v], Fr[v], __builtin_fmaf(-pni[v], Fi[v], er));
                 const float ni = __builtin_fmaf(pni[v], Fr[v], __builtin_fmaf(pnr[v], Fi[v], ei));
                 Fr[v] = nr;
@@ -276,95 +367,6 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
             Fr[v] = nr;
             Fi[v] = ni;
         }
-    }
-
-    // ---- chain: aggregate, look-back, prefix.  The chain runs from the last tile in time to the first.
-    const bool head = seg == 0;              // threads holding the tile's first segment
-    float Tr[V], Ti[V];
-    const size_t slot = (size_t)ticket * 2 * JB + lv * V;
-    if (head) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            Tr[v] = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], Ebr[v]));
-            Ti[v] = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], Ebi[v]));
-        }
-        if (ttr > 0 && tt > 0) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                coherent_store(a.agg + slot + v, Tr[v]);
-                coherent_store(a.agg + slot + JB + v, Ti[v]);
-            }
-        }
-    }
-    if (ttr > 0 && tt > 0) {
-        wait_stores_done();
-        __syncthreads();
-        if (tid == 0) flag_store(a.flags + ticket, ST_AGG);
-    }
-    if (seg == NSEG - 1) {
-        float cr[V], ci[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) cr[v] = ci[v] = 0.f;
-        if (ttr > 0) {
-            float hr[V], hi[V], qr[V], qi[V];
-#pragma unroll
-            for (int v = 0; v < V; ++v) hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
-            if (active) {
-                const float *tb = a.table + j0;
-                BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
-                BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
-                BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
-                BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
-            }
-            if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
-                                         lv, hr, hi, qr, qi, a.spin_limit, cr, ci)) {
-                if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            sCarry[0][lv * V + v] = cr[v];
-            sCarry[1][lv * V + v] = ci[v];
-        }
-    }
-    __syncthreads();
-
-    // ---- true adjoint entering my segment; the tile's inclusive prefix
-    float Gr[V], Gi[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
-        Gr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(psi[v], ci, Xr[v]));      // conj(ps) * carry
-        Gi[v] = __builtin_fmaf(psr[v], ci, __builtin_fmaf(-psi[v], cr, Xi[v]));
-    }
-    const bool publish_prefix = tt > 0;
-    if (head && publish_prefix) {
-        float hr[V], hi[V], qr[V], qi[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
-        if (active) {
-            const float *tb = a.table + j0;
-            BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
-            BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
-            BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
-            BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
-        }
-#pragma unroll
-        for (int v = 0; v < V; ++v) {   // P = T + conj(lambda^T) carry
-            const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
-            float P_r, P_i;
-            chain_step<true>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr, ci, P_r, P_i);
-            coherent_store(a.pre + slot + v, P_r);
-            coherent_store(a.pre + slot + JB + v, P_i);
-        }
-    }
-    wait_stores_done();
-    __syncthreads();
-    if (tid == 0 && publish_prefix) flag_store(a.flags + ticket, ST_PREFIX);
-
-    // ---- forward replay: S[t-1] for my tokens
-    float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];
-    if (PARAM) {
 #pragma unroll
         for (int i = 0; i < NSTEP; ++i) {
 #pragma unroll
@@ -379,6 +381,43 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
                 ag[i][v] *= dsa[i][v];      // from here on only a*g*SiLU'(z_ang) is needed
             }
         }
+    }
+
+    // ---- chain, second half: look-back (its round trips were hidden behind the recompute above)
+    if (head) {
+        float cr[V], ci[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) cr[v] = ci[v] = 0.f;
+        if (chained) {
+            if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
+                                         lv, hr, hi, qr, qi, a.spin_limit, cr, ci)) {
+                if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            sCarry[0][lv * V + v] = cr[v];
+            sCarry[1][lv * V + v] = ci[v];
+        }
+        if (feeds) {    // P = T + conj(lambda^T) carry: the tile's inclusive prefix
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float P_r, P_i;
+                chain_step<true>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], P_r, P_i);
+                coherent_store(a.pre + slot + v, P_r);
+                coherent_store(a.pre + slot + JB + v, P_i);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- true adjoint entering my segment
+    float Gr[V], Gi[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
+        Gr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(psi[v], ci, Xr[v]));      // conj(ps) * carry
+        Gi[v] = __builtin_fmaf(psr[v], ci, __builtin_fmaf(-psi[v], cr, Xi[v]));
     }
 
     // ---- reverse pass: adjoint, returned gradients, parameter terms
@@ -401,9 +440,9 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
                 acc_g[v] += clampf(tg, a.grad_clamp);
                 acc_t[v] += clampf(tth, a.grad_clamp);
             }
-            const float hr = clampf(nr, a.grad_clamp), hi = clampf(ni, a.grad_clamp);
-            const float da = __builtin_fmaf(hr, cs[i][v], hi * sn[i][v]);
-            const float dph = __builtin_fmaf(hi, cs[i][v], -hr * sn[i][v]);
+            const float gr_ = clampf(nr, a.grad_clamp), gi_ = clampf(ni, a.grad_clamp);
+            const float da = __builtin_fmaf(gr_, cs[i][v], gi_ * sn[i][v]);
+            const float dph = __builtin_fmaf(gi_, cs[i][v], -gr_ * sn[i][v]);
             dzr[i][v] = da * dsm[i][v];          // d/d(conv pre-activation), magnitude stream
             dzi[i][v] = dph * ag[i][v];          //                           angle stream
         }
@@ -430,62 +469,68 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
                 BVec<V>::st(a.dang + off, dzi[i]);
             }
         }
+        if (head && feeds) {   // the prefix stores were issued before the reverse pass
+            wait_stores_done();
+            if (lv == 0) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, ST_PREFIX);
+        }
     } else {
         // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
         if (HALO > 0) {
 #pragma unroll
-            for (int q = 0; q < HALO; ++q)
+            for (int r = 0; r < HALO; ++r)
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
-                    sHalo[seg][q][0][lv * V + v] = dzr[q][v];
-                    sHalo[seg][q][1][lv * V + v] = dzi[q][v];
+                    sHalo[seg][r][0][lv * V + v] = dzr[r][v];
+                    sHalo[seg][r][1][lv * V + v] = dzi[r][v];
                 }
-            if (head && tt > 0) {      // rows the earlier tile (next in the chain) needs
+        }
+        if (head && feeds) {      // prefix (issued earlier) and the rows the earlier tile needs
+            if (HALO > 0) {
                 float *hp = a.halo + (size_t)ticket * HALO * 2 * JB + lv * V;
 #pragma unroll
-                for (int q = 0; q < HALO; ++q)
+                for (int r = 0; r < HALO; ++r)
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        coherent_store(hp + (q * 2 + 0) * JB + v, dzr[q][v]);
-                        coherent_store(hp + (q * 2 + 1) * JB + v, dzi[q][v]);
+                        coherent_store(hp + (r * 2 + 0) * JB + v, dzr[r][v]);
+                        coherent_store(hp + (r * 2 + 1) * JB + v, dzi[r][v]);
                     }
             }
             wait_stores_done();
-            __syncthreads();
-            if (tid == 0 && tt > 0) flag_store(a.flags + ticket, ST_HALO);
+            if (lv == 0) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, HALO > 0 ? ST_HALO : ST_PREFIX);
         }
+        __syncthreads();
         float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
 #pragma unroll
-        for (int q = 0; q < HALO1; ++q)
+        for (int r = 0; r < HALO1; ++r)
 #pragma unroll
-            for (int v = 0; v < V; ++v) hm[q][v] = ha[q][v] = 0.f;
+            for (int v = 0; v < V; ++v) hm[r][v] = ha[r][v] = 0.f;
         if (HALO > 0) {
             if (seg < NSEG - 1) {
 #pragma unroll
-                for (int q = 0; q < HALO; ++q)
+                for (int r = 0; r < HALO; ++r)
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        hm[q][v] = sHalo[seg + 1][q][0][lv * V + v];
-                        ha[q][v] = sHalo[seg + 1][q][1][lv * V + v];
+                        hm[r][v] = sHalo[seg + 1][r][0][lv * V + v];
+                        ha[r][v] = sHalo[seg + 1][r][1][lv * V + v];
                     }
-            } else if (ttr > 0) {
+            } else if (chained) {
                 const uint32_t idx = ticket - chain_stride;
-                uint32_t st = flag_load(a.flags + idx);
+                uint32_t st = flag_load(a.flags + (size_t)idx * FLAG_STRIDE);
                 uint32_t spins = 0;
                 while (st < ST_HALO && spins < a.spin_limit) {
                     __builtin_amdgcn_s_sleep(1);
-                    st = flag_load(a.flags + idx);
+                    st = flag_load(a.flags + (size_t)idx * FLAG_STRIDE);
                     ++spins;
                 }
                 compiler_fence();
                 if (st >= ST_HALO) {
                     const float *hp = a.halo + (size_t)idx * HALO * 2 * JB + lv * V;
 #pragma unroll
-                    for (int q = 0; q < HALO; ++q)
+                    for (int r = 0; r < HALO; ++r)
 #pragma unroll
                         for (int v = 0; v < V; ++v) {
-                            hm[q][v] = coherent_load(hp + (q * 2 + 0) * JB + v);
-                            ha[q][v] = coherent_load(hp + (q * 2 + 1) * JB + v);
+                            hm[r][v] = coherent_load(hp + (r * 2 + 0) * JB + v);
+                            ha[r][v] = coherent_load(hp + (r * 2 + 1) * JB + v);
                         }
                 } else if (lv == 0) {
                     __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -525,81 +570,81 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
                 BVec<V>::st(a.dang + off, da);
             }
         }
-        // gradient of the incoming conv history: rows q <-> time q - HALO
+        // gradient of the incoming conv history: rows r <-> time r - HALO
         if (HALO > 0 && a.dstate_in && tt == 0 && head && active) {
             float *dtail_in = a.dstate_in + (size_t)a.B * 2 * a.J;
 #pragma unroll
-            for (int q = 0; q < HALO; ++q) {
+            for (int r = 0; r < HALO; ++r) {
                 float dm[V], da[V];
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     float sm_ = 0.f, sa_ = 0.f;
 #pragma unroll
-                    for (int k = 0; k <= q; ++k) {
-                        sm_ = __builtin_fmaf(wm[k][v], dzr[q - k][v], sm_);
-                        sa_ = __builtin_fmaf(wa[k][v], dzi[q - k][v], sa_);
+                    for (int k = 0; k <= r; ++k) {
+                        sm_ = __builtin_fmaf(wm[k][v], dzr[r - k][v], sm_);
+                        sa_ = __builtin_fmaf(wa[k][v], dzi[r - k][v], sa_);
                     }
                     dm[v] = sm_;
                     da[v] = sa_;
                 }
-                const int r = q - a.L;                     // history row that state_out copied straight from state_in
-                if (dtail_out && r >= 0) {
+                const int rs = r - a.L;                    // history row that state_out copied straight from state_in
+                if (dtail_out && rs >= 0) {
                     float xm_[V], xa_[V];
-                    const size_t o = ((size_t)(b * HALO + r) * 2) * a.J + j0;
+                    const size_t o = ((size_t)(b * HALO + rs) * 2) * a.J + j0;
                     BVec<V>::ld(xm_, dtail_out + o);
                     BVec<V>::ld(xa_, dtail_out + o + a.J);
 #pragma unroll
                     for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
                 }
-                const size_t o = ((size_t)(b * HALO + q) * 2) * a.J + j0;
+                const size_t o = ((size_t)(b * HALO + r) * 2) * a.J + j0;
                 BVec<V>::st(dtail_in + o, dm);
                 BVec<V>::st(dtail_in + o + a.J, da);
             }
         }
     }
 
-    // ---- parameter partials: sum over my tokens, then over segments in index order
+    // ---- parameter partials: my tokens, then the wave's two segments, then the waves in order
     if (PARAM) {
-        float dwm[KC1][V], dwa[KC1][V], dbm[V], dba[V];
+        float part[ROWS][V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            dbm[v] = dba[v] = 0.f;
+            part[0][v] = acc_g[v];
+            part[1][v] = acc_t[v];
 #pragma unroll
-            for (int k = 0; k < KC1; ++k) dwm[k][v] = dwa[k][v] = 0.f;
+            for (int r = 2; r < ROWS; ++r) part[r][v] = 0.f;
         }
         if (KC > 0) {
+            const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i)
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
-                    dbm[v] += dzr[i][v];
-                    dba[v] += dzi[i][v];
+                    part[2][v] += dzr[i][v];
+                    part[3][v] += dzi[i][v];
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
-                        dwm[k][v] = __builtin_fmaf(dzr[i][v], um[i + k][v], dwm[k][v]);
-                        dwa[k][v] = __builtin_fmaf(dzi[i][v], ua[i + k][v], dwa[k][v]);
+                        const bool z = zero_hist && (i + k < HALO);
+                        const float um_ = z ? 0.f : sU[seg * NSTEP + i + k][lv * V + v];
+                        const float ua_ = z ? 0.f : sU[NRT + seg * NSTEP + i + k][lv * V + v];
+                        part[4 + k][v] = __builtin_fmaf(dzr[i][v], um_, part[4 + k][v]);
+                        part[4 + KC + k][v] = __builtin_fmaf(dzi[i][v], ua_, part[4 + KC + k][v]);
                     }
                 }
         }
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const int c = lv * V + v;
-            sRed[seg][0][c] = acc_g[v];
-            sRed[seg][1][c] = acc_t[v];
-            sRed[seg][2][c] = dbm[v];
-            sRed[seg][3][c] = dba[v];
+        for (int r = 0; r < ROWS; ++r)
 #pragma unroll
-            for (int k = 0; k < KC; ++k) {
-                sRed[seg][4 + k][c] = dwm[k][v];
-                sRed[seg][4 + KC + k][c] = dwa[k][v];
+            for (int v = 0; v < V; ++v) {
+                const float other = __shfl_xor(part[r][v], 32, 64);    // the wave's other segment
+                const float s = (seg & 1) ? other + part[r][v] : part[r][v] + other;
+                if (!(seg & 1)) sRed[wave][r][lv * V + v] = s;
             }
-        }
         __syncthreads();
-        for (int e = tid; e < ROWS * JB; e += blockDim.x) {
+        for (int e = tid; e < ROWS * JB; e += NT) {
             const int row = e / JB, c = e % JB;
             float s = 0.f;
 #pragma unroll
-            for (int q = 0; q < NSEG; ++q) s += sRed[q][row][c];
+            for (int w = 0; w < NW; ++w) s += sRed[w][row][c];
             a.part[((size_t)ticket * ROWS + row) * JB + c] = s;
         }
     }
@@ -613,7 +658,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR) void bwd_kernel(const BwdArgs a
     }
     __syncthreads();
     if (sLast) {
-        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + i, ST_NONE);
+        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + (size_t)i * FLAG_STRIDE, ST_NONE);
         if (tid == 0) {
             flag_store(&a.hdr->ticket[0], 0u);
             flag_store(&a.hdr->done, 0u);

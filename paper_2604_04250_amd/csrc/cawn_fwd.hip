@@ -22,6 +22,13 @@
 
 namespace cawn {
 
+#ifndef CAWN_EXPERIMENT_NO_CHAIN
+#define CAWN_EXPERIMENT_NO_CHAIN 0   // tuning experiment only: skip the chain (results are then wrong)
+#endif
+#ifndef CAWN_FWD_ITER_TICKS
+#define CAWN_FWD_ITER_TICKS 1000     // estimated time of one tile iteration, in 10 ns ticks
+#endif
+
 // Tuning aid, compiled only with -DCAWN_TIMING: per-tile time stamps (100 MHz counter) of the
 // chain-owning thread, written behind the parameter partials in the workspace.
 #ifdef CAWN_TIMING
@@ -85,15 +92,11 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     constexpr int NT = NSEG * LPR;                 // threads
     constexpr int NW = NT / 64;                    // waves
     constexpr int NRT = TILE_T + HALO;             // staged rows per stream: time tile_t0-HALO+rr
-    // staging loads: LB bytes per lane, LR lanes per row, RPI rows per wave instruction
-    constexpr int LB = V == 4 ? 16 : 4;
-    constexpr int LR = JB * 4 / LB;
-    constexpr int RPI = 64 / LR;
-    constexpr int NINST = (2 * NRT + RPI - 1) / RPI;
-    static_assert(LR <= 64 && 64 % LR == 0, "a staged row must fit a wave");
+    constexpr int SROWS = ((2 * NRT + 3) / 4) * 4 + 4;   // staged rows, padded for the widest load
+    static_assert(JB <= 256 && 256 % JB == 0, "a staged row must fit a wave");
     static_assert(NW >= 2, "one wave owns the chain, the others stage the next tile");
 
-    __shared__ __attribute__((aligned(16))) float sU[NINST * RPI][JB];   // [stream*NRT + rr][lane]
+    __shared__ __attribute__((aligned(16))) float sU[SROWS][JB];   // [stream*NRT + rr][lane]
     __shared__ float sE[NSEG][2][JB];
     __shared__ float sCarry[2][JB];
     __shared__ uint32_t sTicket[2], sLast;
@@ -125,7 +128,11 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     auto stage_tile = [&](const TileId &T) {
         if (owner_wave) return;
         const int tile_t0 = T.tt * TILE_T;
-        for (int i = wave; i < NINST; i += NW - 1) {
+        // LB bytes per lane, LR lanes per row, RPI rows per wave instruction
+        const int LB = a.stage16 ? 16 : 4;
+        const int LR = JB * 4 / LB, RPI = 64 / LR;
+        const int ninst = (2 * NRT + RPI - 1) / RPI;
+        for (int i = wave; i < ninst; i += NW - 1) {
             int f = i * RPI + lane / LR;
             if (f >= 2 * NRT) f = 2 * NRT - 1;
             const int sidx = f >= NRT ? 1 : 0;
@@ -142,7 +149,8 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 src = (sidx ? a.ang : a.mag) + (size_t)T.b * a.isb + (size_t)tc * a.ist + j;
             }
 #if defined(__HIP_DEVICE_COMPILE__)
-            __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], LB, 0, 0);
+            if (a.stage16) __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 4, 0, 0);
 #else
             (void)src;
 #endif
@@ -153,6 +161,20 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     if (ticket < qtiles) {
         T = decode_tile(ticket, q, a.nQ, a.B, a.nT);
         stage_tile(T);
+        // Start-up skew.  All workgroups start together; left alone, the workgroups that hold the
+        // consecutive tiles of one chain would reach their look-back at the same instant, find only
+        // aggregates and walk back over all of them, every iteration.  Starting tile tt of a chain
+        // a little later than tile tt-1 turns the chain into a pipeline: by the time a tile looks
+        // back, its predecessor has usually published its prefix.
+        if (a.stagger_ticks > 0) {
+            const unsigned long long t_begin = wall_clock64();
+#ifdef CAWN_EXPERIMENT_RANDOM_SKEW
+            const unsigned long long wait = ((blockIdx.x * 2654435761u) >> 20) % CAWN_EXPERIMENT_RANDOM_SKEW;
+#else
+            const unsigned long long wait = (unsigned long long)T.tt * a.stagger_ticks;
+#endif
+            while (wall_clock64() - t_begin < wait) __builtin_amdgcn_s_sleep(8);
+        }
     }
 
     float lr[V], li[V], pfr[V], pfi[V], psr[V], psi[V];
@@ -347,6 +369,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                     Vec<V>::ld(cr, a.state_in + ((size_t)b * 2 + 0) * a.J + j0);
                     Vec<V>::ld(ci, a.state_in + ((size_t)b * 2 + 1) * a.J + j0);
                 }
+            } else if (CAWN_EXPERIMENT_NO_CHAIN == 1) {
             } else {
                 uint32_t *own = nullptr;
                 if (tt + 1 < a.nT) {
@@ -355,8 +378,11 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                         coherent_store(a.agg + slot + v, Tr[v]);
                         coherent_store(a.agg + slot + JB + v, Ti[v]);
                     }
-                    own = a.flags + id;   // set once those stores are done, together with the first poll
+                    own = a.flags + (size_t)id * FLAG_STRIDE;   // set once those stores are done, together with the first poll
                 }
+                if (CAWN_EXPERIMENT_NO_CHAIN == 2) {
+                    if (own) { wait_stores_done(); if (lv == 0) flag_store(own, ST_AGG); }
+                } else
                 if (!look_back<V, false, LPR>(a.flags, a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB,
                                               lv * V, lv, hr, hi, qr, qi, a.spin_limit, cr, ci, own)) {
                     // gave up: flag the workspace, keep going so that every wave exits
@@ -374,7 +400,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 Vec<V>::st(ck, cr);
                 Vec<V>::st(ck + a.J, ci);
             }
-            if (tt + 1 < a.nT) {   // the tile's inclusive prefix for the chain
+            if (tt + 1 < a.nT && CAWN_EXPERIMENT_NO_CHAIN != 1) {   // the tile's inclusive prefix for the chain
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     float P_r, P_i;
@@ -423,7 +449,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         // the prefix stores were issued before the replay; by now they have (nearly) landed
         if (is_tail_seg && tt + 1 < a.nT) {
             wait_stores_done();
-            if (lv == 0) flag_store(a.flags + id, ST_PREFIX);
+            if (lv == 0) flag_store(a.flags + (size_t)id * FLAG_STRIDE, ST_PREFIX);
         }
         CAWN_STAMP(8);
 
@@ -465,7 +491,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     }
     __syncthreads();
     if (sLast) {
-        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + i, ST_NONE);
+        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + (size_t)i * FLAG_STRIDE, ST_NONE);
         if (tid < MAX_QUEUES) flag_store(&a.hdr->ticket[tid], 0u);
         if (tid == 0) flag_store(&a.hdr->done, 0u);
     }
@@ -493,6 +519,9 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     long long wq = resident / a.nQ;
     if (wq > per_queue_tiles) wq = per_queue_tiles;
     if (wq < 1) wq = 1;
+    // skew so that the ~wq/B workgroups working on one chain spread over one iteration (~10 us)
+    const long long per_chain = wq / a.B > 0 ? wq / a.B : 1;
+    a.stagger_ticks = per_chain > 1 ? (int)(CAWN_FWD_ITER_TICKS / per_chain) : 0;
     dim3 grid((unsigned)(wq * a.nQ)), block(Geom::NSEG * FwdLPR);
     hipLaunchKernelGGL((fwd_kernel<V, KC>), grid, block, 0, s, a);
     return hipGetLastError();

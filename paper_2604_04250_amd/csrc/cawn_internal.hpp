@@ -32,7 +32,7 @@ namespace cawn {
 #define CAWN_FWD_WAVES 2      // waves per SIMD the forward kernel's register budget is set for
 #endif
 #ifndef CAWN_BWD_WAVES
-#define CAWN_BWD_WAVES 1
+#define CAWN_BWD_WAVES 2
 #endif
 constexpr int TILE_T = CAWN_TILE_T;  // tokens per tile: granularity of carries and checkpoints
 
@@ -42,7 +42,11 @@ struct Geom {
 constexpr int FwdV = CAWN_FWD_V, FwdLPR = CAWN_FWD_LPR;  // forward: lanes per thread, threads per row
 constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;  // backward (it keeps more per token)
 constexpr int MAX_KC = 4;
-constexpr uint32_t MAX_TILES = 1u << 20;   // capacity of the fixed tile-status zone
+#ifndef CAWN_FLAG_STRIDE
+#define CAWN_FLAG_STRIDE 16
+#endif
+constexpr uint32_t MAX_TILES = 1u << 18;   // capacity of the fixed tile-status zone
+constexpr int FLAG_STRIDE = CAWN_FLAG_STRIDE;   // words between status words (spreads them over cache lines)
 
 // ---------------------------------------------------------------------------------- lane table
 // Per-lane constants, struct-of-arrays, each row Jp floats (Jp = J rounded up to 64), built in
@@ -96,6 +100,8 @@ struct FwdArgs {
     float *agg, *pre;
     int B, L, J, Jp, nT, nLB;
     int nQ;                      // work queues (a queue owns lane blocks q, q+nQ, ...)
+    int stagger_ticks;           // start-up skew per time tile, in 10 ns ticks (see fwd kernel)
+    int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int amp_mode;
     int small_angle;             // angles are bounded (conv clamp): skip the two-term range reduction
     long long isb, ist, osb, ost;
@@ -120,6 +126,7 @@ struct BwdArgs {
     int B, L, J, Jp, nT, nLB;
     int nQ;
     int small_angle;
+    int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int amp_mode, want_param;
     long long isb, ist, osb, ost;
     float conv_clamp, grad_clamp;
@@ -269,7 +276,7 @@ __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *ag
     while (base < depth) {
         const int w = depth - base < LPR ? depth - base : LPR;
         uint32_t st = ST_AGG;
-        if (lv < w) st = flag_load(flags + (pred - (uint32_t)(base + lv) * stride));
+        if (lv < w) st = flag_load(flags + (size_t)(pred - (uint32_t)(base + lv) * stride) * FLAG_STRIDE);
         if (own_agg_flag) {
             wait_stores_done();
             if (lv == 0) flag_store(own_agg_flag, ST_AGG);
