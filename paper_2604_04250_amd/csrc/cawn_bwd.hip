@@ -132,14 +132,13 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     }
 
     // ---- lane constants
-    float lr[V], li[V], pnr[V], pni[V], psr[V], psi[V], pfr[V], pfi[V], cth[V], sth[V], gam[V];
-    float wm[KC1][V], wa[KC1][V], bm[V], ba[V];
+    float lr[V], li[V], pnr[V], pni[V];
+    float wmf[KC1][V], waf[KC1][V], bm[V], ba[V];   // taps for the front-end
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        lr[v] = li[v] = pnr[v] = pni[v] = psi[v] = pfi[v] = sth[v] = gam[v] = bm[v] = ba[v] = 0.f;
-        psr[v] = pfr[v] = cth[v] = 1.f;
+        lr[v] = li[v] = pnr[v] = pni[v] = bm[v] = ba[v] = 0.f;
 #pragma unroll
-        for (int k = 0; k < KC1; ++k) wm[k][v] = wa[k][v] = 0.f;
+        for (int k = 0; k < KC1; ++k) wmf[k][v] = waf[k][v] = 0.f;
     }
     if (active) {
         const float *tb = a.table + j0;
@@ -147,22 +146,13 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         BVec<V>::ld(li, tb + (size_t)R_LI * a.Jp);
         BVec<V>::ld(pnr, tb + (size_t)(R_PSEG + 2) * a.Jp);                       // lambda^NSTEP
         BVec<V>::ld(pni, tb + (size_t)(R_PSEG + 3) * a.Jp);
-        BVec<V>::ld(psr, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
-        BVec<V>::ld(psi, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
-        if (PARAM) {
-            BVec<V>::ld(pfr, tb + (size_t)(R_PSEG + 2 * seg) * a.Jp);             // forward: segments before mine
-            BVec<V>::ld(pfi, tb + (size_t)(R_PSEG + 2 * seg + 1) * a.Jp);
-            BVec<V>::ld(cth, tb + (size_t)R_COS * a.Jp);
-            BVec<V>::ld(sth, tb + (size_t)R_SIN * a.Jp);
-            BVec<V>::ld(gam, tb + (size_t)R_GAMMA * a.Jp);
-        }
         if (KC > 0) {
             BVec<V>::ld(bm, tb + (size_t)R_BIAS_M * a.Jp);
             BVec<V>::ld(ba, tb + (size_t)R_BIAS_A * a.Jp);
 #pragma unroll
             for (int k = 0; k < KC; ++k) {
-                BVec<V>::ld(wm[k], tb + (size_t)(R_W0 + k) * a.Jp);
-                BVec<V>::ld(wa[k], tb + (size_t)(R_W0 + KC + k) * a.Jp);
+                BVec<V>::ld(wmf[k], tb + (size_t)(R_W0 + k) * a.Jp);
+                BVec<V>::ld(waf[k], tb + (size_t)(R_W0 + KC + k) * a.Jp);
             }
         }
     }
@@ -215,21 +205,15 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     }
 
     // ---- chain, first half: the aggregate goes out before the front-end recompute
-    float Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
     const size_t slot = (size_t)ticket * 2 * JB + lv * V;
     if (head) {
+        float Tr[V], Ti[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             Tr[v] = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], Ebr[v]));
             Ti[v] = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], Ebi[v]));
-            hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
-        }
-        if (active) {
-            const float *tb = a.table + j0;
-            BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
-            BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
-            BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
-            BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+            sCarry[0][lv * V + v] = Tr[v];     // parked here until the look-back (frees registers)
+            sCarry[1][lv * V + v] = Ti[v];
         }
         if (chained && feeds) {
 #pragma unroll
@@ -245,7 +229,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     __syncthreads();
 
     // ---- front-end recompute, rows from LDS as a sliding window
-    float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V], dsa[NSTEP][V];
+    float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V];   // ag: a*g*SiLU'(z_ang)
+    float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];      // forward state before each token
     float Efr[V], Efi[V];
     {
         float wnm[KC1][V], wna[KC1][V];
@@ -262,6 +247,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         for (int v = 0; v < V; ++v) Efr[v] = Efi[v] = 0.f;
 #pragma unroll
         for (int i = 0; i < NSTEP; ++i) {
+            if ((i & 1) == 0) compiler_fence();   // keeps the LDS reads of later tokens from piling up in registers
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 wnm[KC1 - 1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
@@ -275,8 +261,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                     float za = ba[v];
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
-                        zm = __builtin_fmaf(wm[k][v], wnm[k][v], zm);
-                        za = __builtin_fmaf(wa[k][v], wna[k][v], za);
+                        zm = __builtin_fmaf(wmf[k][v], wnm[k][v], zm);
+                        za = __builtin_fmaf(waf[k][v], wna[k][v], za);
                     }
                     const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
                     const float sgm = sigmoid_fast(cm), sga = sigmoid_fast(ca);
@@ -306,17 +292,15 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 cs[i][v] = c;
                 sn[i][v] = s;
                 dsm[i][v] = km;
-                if (PARAM) {
-                    ag[i][v] = agv;
-                    dsa[i][v] = ka;
+                ag[i][v] = agv * ka;
+                if (PARAM) {   // forward scan from zero; the state before token i is kept
+                    Spr[i][v] = Efr[v];
+                    Spi[i][v] = Efi[v];
                     const float pr = agv * c, pi = agv * s;
                     const float nr = __builtin_fmaf(lr[v], Efr[v], __builtin_fmaf(-li[v], Efi[v], pr));
                     const float ni = __builtin_fmaf(li[v], Efr[v], __builtin_fmaf(lr[v], Efi[v], pi));
                     Efr[v] = nr;
                     Efi[v] = ni;
-                } else {
-                    ag[i][v] = agv * ka;       // only the product is needed without parameter gradients
-                    dsa[i][v] = 0.f;
                 }
             }
 #pragma unroll
@@ -331,7 +315,6 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     }
 
     // ---- forward state entering my segment (checkpoint + earlier segments), then S[t-1] per token
-    float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];
     if (PARAM) {
 #pragma unroll
         for (int v = 0; v < V; ++v) {
@@ -339,9 +322,13 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             sEf[seg][1][lv * V + v] = Efi[v];
         }
         __syncthreads();
-        float Fr[V], Fi[V];
+        float Fr[V], Fi[V], pfr[V], pfi[V];   // lambda^(NSTEP*seg): the segments before mine
 #pragma unroll
-        for (int v = 0; v < V; ++v) Fr[v] = Fi[v] = 0.f;
+        for (int v = 0; v < V; ++v) { Fr[v] = Fi[v] = pfi[v] = 0.f; pfr[v] = 1.f; }
+        if (active) {
+            BVec<V>::ld(pfr, a.table + j0 + (size_t)(R_PSEG + 2 * seg) * a.Jp);
+            BVec<V>::ld(pfi, a.table + j0 + (size_t)(R_PSEG + 2 * seg + 1) * a.Jp);
+        }
         for (int qq = 0; qq < seg; ++qq) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
@@ -367,27 +354,52 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             Fr[v] = nr;
             Fi[v] = ni;
         }
+        // S[t-1] = (scan from zero) + lambda^i * (true state entering the segment)
 #pragma unroll
         for (int i = 0; i < NSTEP; ++i) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                Spr[i][v] = Fr[v];
-                Spi[i][v] = Fi[v];
-                const float pr = ag[i][v] * cs[i][v], pi = ag[i][v] * sn[i][v];
-                const float nr = __builtin_fmaf(lr[v], Fr[v], __builtin_fmaf(-li[v], Fi[v], pr));
-                const float ni = __builtin_fmaf(li[v], Fr[v], __builtin_fmaf(lr[v], Fi[v], pi));
+                Spr[i][v] += Fr[v];
+                Spi[i][v] += Fi[v];
+                const float nr = __builtin_fmaf(lr[v], Fr[v], -li[v] * Fi[v]);
+                const float ni = __builtin_fmaf(li[v], Fr[v], lr[v] * Fi[v]);
                 Fr[v] = nr;
                 Fi[v] = ni;
-                ag[i][v] *= dsa[i][v];      // from here on only a*g*SiLU'(z_ang) is needed
             }
+        }
+    }
+
+    // constants of the reverse pass, fetched now so that they arrive during the look-back
+    float psr[V], psi[V], cth[V], sth[V], gam[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) { psi[v] = sth[v] = gam[v] = 0.f; psr[v] = cth[v] = 1.f; }
+    if (active) {
+        const float *tb = a.table + j0;
+        BVec<V>::ld(psr, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
+        BVec<V>::ld(psi, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
+        if (PARAM) {
+            BVec<V>::ld(cth, tb + (size_t)R_COS * a.Jp);
+            BVec<V>::ld(sth, tb + (size_t)R_SIN * a.Jp);
+            BVec<V>::ld(gam, tb + (size_t)R_GAMMA * a.Jp);
         }
     }
 
     // ---- chain, second half: look-back (its round trips were hidden behind the recompute above)
     if (head) {
-        float cr[V], ci[V];
+        float cr[V], ci[V], Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) cr[v] = ci[v] = 0.f;
+        for (int v = 0; v < V; ++v) {
+            cr[v] = ci[v] = hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
+            Tr[v] = sCarry[0][lv * V + v];
+            Ti[v] = sCarry[1][lv * V + v];
+        }
+        if (active) {   // lambda^TILE_T as a double-float
+            const float *tb = a.table + j0;
+            BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
+            BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
+            BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
+            BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+        }
         if (chained) {
             if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
                                          lv, hr, hi, qr, qi, a.spin_limit, cr, ci)) {
@@ -475,6 +487,20 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
     } else {
         // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
+        // (the taps are fetched again here rather than kept in registers across the whole kernel)
+        float wm[KC1][V], wa[KC1][V];
+#pragma unroll
+        for (int k = 0; k < KC1; ++k)
+#pragma unroll
+            for (int v = 0; v < V; ++v) wm[k][v] = wa[k][v] = 0.f;
+        if (active) {
+            const float *tb = a.table + j0;
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                BVec<V>::ld(wm[k], tb + (size_t)(R_W0 + k) * a.Jp);
+                BVec<V>::ld(wa[k], tb + (size_t)(R_W0 + KC + k) * a.Jp);
+            }
+        }
         if (HALO > 0) {
 #pragma unroll
             for (int r = 0; r < HALO; ++r)

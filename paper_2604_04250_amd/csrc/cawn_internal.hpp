@@ -23,7 +23,7 @@ namespace cawn {
 #define CAWN_FWD_LPR 32
 #endif
 #ifndef CAWN_BWD_V
-#define CAWN_BWD_V 2
+#define CAWN_BWD_V 1
 #endif
 #ifndef CAWN_BWD_LPR
 #define CAWN_BWD_LPR 32
@@ -32,7 +32,7 @@ namespace cawn {
 #define CAWN_FWD_WAVES 2      // waves per SIMD the forward kernel's register budget is set for
 #endif
 #ifndef CAWN_BWD_WAVES
-#define CAWN_BWD_WAVES 2
+#define CAWN_BWD_WAVES 3
 #endif
 constexpr int TILE_T = CAWN_TILE_T;  // tokens per tile: granularity of carries and checkpoints
 
@@ -40,7 +40,8 @@ struct Geom {
     static constexpr int NSTEP = CAWN_NSTEP, NSEG = TILE_T / NSTEP;
 };
 constexpr int FwdV = CAWN_FWD_V, FwdLPR = CAWN_FWD_LPR;  // forward: lanes per thread, threads per row
-constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;  // backward (it keeps more per token)
+constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;  // backward: it keeps ~10 values per token-lane,
+                                                         // so one lane per thread buys a third wave per SIMD
 constexpr int MAX_KC = 4;
 #ifndef CAWN_FLAG_STRIDE
 #define CAWN_FLAG_STRIDE 16
