@@ -192,7 +192,7 @@ def main():
             out["bwd_ms"] = bwd_ms
             alg = BWD_BYTES_PER_TOKEN_LANE * tokens * J
             achieved = alg / (bwd_ms * 1e-3) / 1e9
-            out["roofline"] = {"bound": "hbm", "kernel": "bwd_kernel<2,4,true> (+ its partial-sum reduction)",
+            out["roofline"] = {"bound": "hbm", "kernel": "bwd_kernel<1,4,true> (+ its partial-sum reduction)",
                                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
                                "avg_ms": bwd_ms}
