@@ -116,7 +116,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         sLast = 0;
     }
     __syncthreads();
-    uint32_t ticket = sTicket[0];
+    uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
     uint32_t my_tiles = 0;
 
     // Stage a tile's input rows in LDS with direct global->LDS loads (no registers involved).  The
@@ -232,14 +232,16 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         float pr[NSTEP][V], pi[NSTEP][V];
         float Er[V], Ei[V];
         uint32_t gbits[NSTEP];
+        const bool want_mask = a.mask != nullptr;
         float wnm[KC1][V], wna[KC1][V];           // window: rows i .. i+KC-1 of my segment
         const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
+        // (row r of my segment lives in slot r % KC1: no register shuffling as the window slides)
 #pragma unroll
         for (int k = 0; k < KC1 - 1; ++k) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                wnm[k][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
-                wna[k][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
+                wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
+                wna[k % KC1][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
             }
         }
 #pragma unroll
@@ -249,8 +251,8 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             gbits[i] = 0;
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                wnm[KC1 - 1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
-                wna[KC1 - 1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
+                wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
+                wna[(i + HALO) % KC1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
             }
 #pragma unroll
             for (int v = 0; v < V; ++v) {
@@ -260,16 +262,16 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                     float za = ba[v];
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
-                        zm = __builtin_fmaf(wm[k][v], wnm[k][v], zm);
-                        za = __builtin_fmaf(wa[k][v], wna[k][v], za);
+                        zm = __builtin_fmaf(wm[k][v], wnm[(i + k) % KC1][v], zm);
+                        za = __builtin_fmaf(wa[k][v], wna[(i + k) % KC1][v], za);
                     }
                     const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
                     xm = cm * sigmoid_fast(cm);
                     phi = ca * sigmoid_fast(ca);
                 } else {
-                    zm = wnm[0][v];
+                    zm = wnm[i % KC1][v];
                     xm = zm;
-                    phi = wna[0][v];
+                    phi = wna[i % KC1][v];
                 }
                 const float amp = a.amp_mode ? __builtin_fminf(softplus_fast(xm), 10.0f) : xm;
                 const bool g = in_gate(a.gs, zm);
@@ -279,19 +281,11 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 const float ag = g ? amp : 0.0f;
                 pr[i][v] = ag * c;
                 pi[i][v] = ag * s;
-                gbits[i] |= (g && active ? 1u : 0u) << v;
+                if (want_mask) gbits[i] |= (g && active ? 1u : 0u) << v;
                 const float nr = __builtin_fmaf(lr[v], Er[v], __builtin_fmaf(-li[v], Ei[v], pr[i][v]));
                 const float ni = __builtin_fmaf(li[v], Er[v], __builtin_fmaf(lr[v], Ei[v], pi[i][v]));
                 Er[v] = nr;
                 Ei[v] = ni;
-            }
-#pragma unroll
-            for (int k = 0; k < KC1 - 1; ++k) {
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    wnm[k][v] = wnm[k + 1][v];
-                    wna[k][v] = wna[k + 1][v];
-                }
             }
         }
         CAWN_STAMP(2);
@@ -321,7 +315,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         CAWN_STAMP(3);
 
         // ---- start staging the next tile (it lands during this tile's communication phase)
-        const uint32_t next_ticket = sTicket[(it + 1) & 1];
+        const uint32_t next_ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
         TileId Tn{};
         if (next_ticket < qtiles) {
             Tn = decode_tile(next_ticket, q, a.nQ, a.B, a.nT);
@@ -422,28 +416,39 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             Si[v] = __builtin_fmaf(psi[v], cr, __builtin_fmaf(psr[v], ci, Xi[v]));
         }
 
-        // ---- replay from the true state, clamp, store
+        // ---- replay from the true state, clamp, store.  Addresses are a wave-uniform base plus a
+        //      32-bit offset; a tile that lies wholly inside the tensor stores without per-row checks.
+        {
+            float *zre = a.z_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)T.lb * JB;
+            float *zim = a.z_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)T.lb * JB;
+            const uint32_t ost32 = (uint32_t)a.ost;
+            uint32_t off = (uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V);
+            const bool full = (tt + 1) * TILE_T <= a.L && (T.lb + 1) * JB <= a.J;
 #pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-            const int t = t0 + i;
-            float zr[V], zi[V];
+            for (int i = 0; i < NSTEP; ++i) {
+                const int t = t0 + i;
+                float zr[V], zi[V];
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const float nr = __builtin_fmaf(lr[v], Sr[v], __builtin_fmaf(-li[v], Si[v], pr[i][v]));
-                const float ni = __builtin_fmaf(li[v], Sr[v], __builtin_fmaf(lr[v], Si[v], pi[i][v]));
-                Sr[v] = nr;
-                Si[v] = ni;
-                zr[v] = clampf(nr, a.out_clamp);
-                zi[v] = clampf(ni, a.out_clamp);
-            }
-            if (active && t < a.L) {
-                const size_t off = (size_t)b * a.osb + (size_t)t * a.ost + j0;
-                Vec<V>::st(a.z_re + off, zr);
-                Vec<V>::st(a.z_im + off, zi);
-                if (t == a.L - 1 && a.state_out) {
+                for (int v = 0; v < V; ++v) {
+                    const float nr = __builtin_fmaf(lr[v], Sr[v], __builtin_fmaf(-li[v], Si[v], pr[i][v]));
+                    const float ni = __builtin_fmaf(li[v], Sr[v], __builtin_fmaf(lr[v], Si[v], pi[i][v]));
+                    Sr[v] = nr;
+                    Si[v] = ni;
+                    zr[v] = clampf(nr, a.out_clamp);
+                    zi[v] = clampf(ni, a.out_clamp);
+                }
+                if (full) {
+                    Vec<V>::st(zre + off, zr);
+                    Vec<V>::st(zim + off, zi);
+                } else if (active && t < a.L) {
+                    Vec<V>::st(zre + off, zr);
+                    Vec<V>::st(zim + off, zi);
+                }
+                if (t == a.L - 1 && a.state_out && active) {
                     Vec<V>::st(a.state_out + ((size_t)b * 2 + 0) * a.J + j0, Sr);
                     Vec<V>::st(a.state_out + ((size_t)b * 2 + 1) * a.J + j0, Si);
                 }
+                off += ost32;
             }
         }
         // the prefix stores were issued before the replay; by now they have (nearly) landed
