@@ -71,7 +71,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         sLast = 0;
     }
     __syncthreads();
-    const uint32_t ticket = sTicket;
+    const uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket);   // wave-uniform: index math stays scalar
     const int lb = ticket % a.nLB;
     const int rest = ticket / a.nLB;
     const int b = rest % a.B, ttr = rest / a.B;       // ttr: position in the chain (0 = last tile in time)
@@ -88,15 +88,27 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
 
     // ---- upstream gradients of my tokens (registers), then the tile's input rows (LDS)
     float dzr[NSTEP][V], dzi[NSTEP][V];     // upstream dS, later overwritten by d(pre-activation)
+    // a tile that lies wholly inside the tensors loads and stores without per-row checks
+    const bool full = (tt + 1) * TILE_T <= a.L && (lb + 1) * JB <= a.J;
+    const uint32_t ost32 = (uint32_t)a.ost, ist32 = (uint32_t)a.ist;
+    {
+        const float *gre = a.dz_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
+        const float *gim = a.dz_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
+        uint32_t off = (uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V);
 #pragma unroll
-    for (int i = 0; i < NSTEP; ++i) {
-        const int t = t0 + i;
+        for (int i = 0; i < NSTEP; ++i) {
+            if (full) {
+                BVec<V>::ld(dzr[i], gre + off);
+                BVec<V>::ld(dzi[i], gim + off);
+            } else {
 #pragma unroll
-        for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
-        if (active && t < a.L) {
-            const size_t off = (size_t)b * a.osb + (size_t)t * a.ost + j0;
-            BVec<V>::ld(dzr[i], a.dz_re + off);
-            BVec<V>::ld(dzi[i], a.dz_im + off);
+                for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
+                if (active && t0 + i < a.L) {
+                    BVec<V>::ld(dzr[i], gre + off);
+                    BVec<V>::ld(dzi[i], gim + off);
+                }
+            }
+            off += ost32;
         }
     }
     // Rows outside [0, L) and lanes beyond J read a clamped (valid, finite) address: they only ever
@@ -235,23 +247,23 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     {
         float wnm[KC1][V], wna[KC1][V];
         const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
+        // (row r of my segment lives in slot r % KC1: no register shuffling as the window slides)
 #pragma unroll
         for (int k = 0; k < KC1 - 1; ++k) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                wnm[k][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
-                wna[k][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
+                wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
+                wna[k % KC1][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
             }
         }
 #pragma unroll
         for (int v = 0; v < V; ++v) Efr[v] = Efi[v] = 0.f;
 #pragma unroll
         for (int i = 0; i < NSTEP; ++i) {
-            if ((i & 1) == 0) compiler_fence();   // keeps the LDS reads of later tokens from piling up in registers
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                wnm[KC1 - 1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
-                wna[KC1 - 1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
+                wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
+                wna[(i + HALO) % KC1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
             }
 #pragma unroll
             for (int v = 0; v < V; ++v) {
@@ -261,8 +273,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                     float za = ba[v];
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
-                        zm = __builtin_fmaf(wmf[k][v], wnm[k][v], zm);
-                        za = __builtin_fmaf(waf[k][v], wna[k][v], za);
+                        zm = __builtin_fmaf(wmf[k][v], wnm[(i + k) % KC1][v], zm);
+                        za = __builtin_fmaf(waf[k][v], wna[(i + k) % KC1][v], za);
                     }
                     const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
                     const float sgm = sigmoid_fast(cm), sga = sigmoid_fast(ca);
@@ -272,9 +284,9 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                     km = __builtin_fabsf(zm) <= a.conv_clamp ? sgm * __builtin_fmaf(cm, 1.0f - sgm, 1.0f) : 0.0f;
                     ka = __builtin_fabsf(za) <= a.conv_clamp ? sga * __builtin_fmaf(ca, 1.0f - sga, 1.0f) : 0.0f;
                 } else {
-                    zm = wnm[0][v];
+                    zm = wnm[i % KC1][v];
                     xm = zm;
-                    phi = wna[0][v];
+                    phi = wna[i % KC1][v];
                     km = 1.0f;
                     ka = 1.0f;
                 }
@@ -301,14 +313,6 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                     const float ni = __builtin_fmaf(li[v], Efr[v], __builtin_fmaf(lr[v], Efi[v], pi));
                     Efr[v] = nr;
                     Efi[v] = ni;
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < KC1 - 1; ++k) {
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    wnm[k][v] = wnm[k + 1][v];
-                    wna[k][v] = wna[k + 1][v];
                 }
             }
         }
@@ -471,15 +475,17 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         BVec<V>::st(a.dstate_in + ((size_t)b * 2 + 1) * a.J + j0, xi);
     }
 
+    float *omag = a.dmag + (size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB;
+    float *oang = a.dang + (size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB;
+    uint32_t ooff = (uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V);
     if (KC == 0) {
 #pragma unroll
         for (int i = 0; i < NSTEP; ++i) {
-            const int t = t0 + i;
-            if (active && t < a.L) {
-                const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + j0;
-                BVec<V>::st(a.dmag + off, dzr[i]);
-                BVec<V>::st(a.dang + off, dzi[i]);
+            if (full || (active && t0 + i < a.L)) {
+                BVec<V>::st(omag + ooff, dzr[i]);
+                BVec<V>::st(oang + ooff, dzi[i]);
             }
+            ooff += ist32;
         }
         if (head && feeds) {   // the prefix stores were issued before the reverse pass
             wait_stores_done();
@@ -581,7 +587,10 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 dm[v] = sm_;
                 da[v] = sa_;
             }
-            if (active && t < a.L) {
+            if (full && !dtail_out) {
+                BVec<V>::st(omag + ooff, dm);
+                BVec<V>::st(oang + ooff, da);
+            } else if (active && t < a.L) {
                 if (HALO > 0 && dtail_out && t >= a.L - HALO) {   // state_out's history rows are copies of these inputs
                     const int r = t - (a.L - HALO);
                     float xm_[V], xa_[V];
@@ -591,10 +600,10 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
 #pragma unroll
                     for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
                 }
-                const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + j0;
-                BVec<V>::st(a.dmag + off, dm);
-                BVec<V>::st(a.dang + off, da);
+                BVec<V>::st(omag + ooff, dm);
+                BVec<V>::st(oang + ooff, da);
             }
+            ooff += ist32;
         }
         // gradient of the incoming conv history: rows r <-> time r - HALO
         if (HALO > 0 && a.dstate_in && tt == 0 && head && active) {
