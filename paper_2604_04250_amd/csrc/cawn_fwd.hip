@@ -22,11 +22,8 @@
 
 namespace cawn {
 
-#ifndef CAWN_EXPERIMENT_NO_CHAIN
-#define CAWN_EXPERIMENT_NO_CHAIN 0   // tuning experiment only: skip the chain (results are then wrong)
-#endif
 #ifndef CAWN_FWD_ITER_TICKS
-#define CAWN_FWD_ITER_TICKS 1000     // estimated time of one tile iteration, in 10 ns ticks
+#define CAWN_FWD_ITER_TICKS 500      // start-up skew spread over this many 10 ns ticks per chain
 #endif
 
 // Tuning aid, compiled only with -DCAWN_TIMING: per-tile time stamps (100 MHz counter) of the
@@ -166,13 +163,9 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         // aggregates and walk back over all of them, every iteration.  Starting tile tt of a chain
         // a little later than tile tt-1 turns the chain into a pipeline: by the time a tile looks
         // back, its predecessor has usually published its prefix.
-        if (a.stagger_ticks > 0) {
+        if (a.stagger_ticks > 0 && T.tt > 0) {
             const unsigned long long t_begin = wall_clock64();
-#ifdef CAWN_EXPERIMENT_RANDOM_SKEW
-            const unsigned long long wait = ((blockIdx.x * 2654435761u) >> 20) % CAWN_EXPERIMENT_RANDOM_SKEW;
-#else
             const unsigned long long wait = (unsigned long long)T.tt * a.stagger_ticks;
-#endif
             while (wall_clock64() - t_begin < wait) __builtin_amdgcn_s_sleep(8);
         }
     }
@@ -363,7 +356,6 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                     Vec<V>::ld(cr, a.state_in + ((size_t)b * 2 + 0) * a.J + j0);
                     Vec<V>::ld(ci, a.state_in + ((size_t)b * 2 + 1) * a.J + j0);
                 }
-            } else if (CAWN_EXPERIMENT_NO_CHAIN == 1) {
             } else {
                 uint32_t *own = nullptr;
                 if (tt + 1 < a.nT) {
@@ -374,9 +366,6 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                     }
                     own = a.flags + (size_t)id * FLAG_STRIDE;   // set once those stores are done, together with the first poll
                 }
-                if (CAWN_EXPERIMENT_NO_CHAIN == 2) {
-                    if (own) { wait_stores_done(); if (lv == 0) flag_store(own, ST_AGG); }
-                } else
                 if (!look_back<V, false, LPR>(a.flags, a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB,
                                               lv * V, lv, hr, hi, qr, qi, a.spin_limit, cr, ci, own)) {
                     // gave up: flag the workspace, keep going so that every wave exits
@@ -394,7 +383,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 Vec<V>::st(ck, cr);
                 Vec<V>::st(ck + a.J, ci);
             }
-            if (tt + 1 < a.nT && CAWN_EXPERIMENT_NO_CHAIN != 1) {   // the tile's inclusive prefix for the chain
+            if (tt + 1 < a.nT) {   // the tile's inclusive prefix for the chain
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     float P_r, P_i;

@@ -511,3 +511,26 @@ def test_theta_init_endpoints_and_ratio():
     J = H * F
     np.testing.assert_allclose(th[1:] / th[:-1], 10000.0 ** (-2.0 / J), rtol=3e-7)
     np.testing.assert_allclose(th[-1], 10.0 ** (-8.0 * (J - 1) / J), rtol=1e-7)
+
+
+# ------------------------------------------------------------------------------- regression anchor
+def test_oracle_matches_its_stored_samples():
+    """tests/golden/cfg1_oracle_samples.txt was written by tests/golden/make_golden.py from the oracle
+    alone (the paper prints no numeric example for this path).  It does not pin the oracle to the
+    mathematics -- the tests above do -- it flags any later drift of the oracle's arithmetic."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = {(n, t, j): v for n, t, j, v in mod.samples()}
+    stored = {}
+    for line in open(os.path.join(here, "cfg1_oracle_samples.txt")):
+        if line.startswith("#"):
+            continue
+        n, t, j, v = line.split()
+        stored[(n, int(t), int(j))] = float(v)
+    assert stored.keys() == now.keys()
+    for k, v in stored.items():
+        assert abs(now[k] - v) <= 1e-12 * max(1.0, abs(v)), (k, now[k], v)
