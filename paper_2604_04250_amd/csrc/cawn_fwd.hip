@@ -359,11 +359,8 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             } else {
                 uint32_t *own = nullptr;
                 if (tt + 1 < a.nT) {
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        coherent_store(a.agg + slot + v, Tr[v]);
-                        coherent_store(a.agg + slot + JB + v, Ti[v]);
-                    }
+                    coherent_store_v<V>(a.agg + slot, Tr);
+                    coherent_store_v<V>(a.agg + slot + JB, Ti);
                     own = a.flags + (size_t)id * FLAG_STRIDE;   // set once those stores are done, together with the first poll
                 }
                 if (!look_back<V, false, LPR>(a.flags, a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB,
@@ -384,13 +381,12 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 Vec<V>::st(ck + a.J, ci);
             }
             if (tt + 1 < a.nT) {   // the tile's inclusive prefix for the chain
+                float P_r[V], P_i[V];
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    float P_r, P_i;
-                    chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], P_r, P_i);
-                    coherent_store(a.pre + slot + v, P_r);
-                    coherent_store(a.pre + slot + JB + v, P_i);
-                }
+                for (int v = 0; v < V; ++v)
+                    chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], P_r[v], P_i[v]);
+                coherent_store_v<V>(a.pre + slot, P_r);
+                coherent_store_v<V>(a.pre + slot + JB, P_i);
             }
         }
         __syncthreads();

@@ -215,6 +215,41 @@ __device__ __forceinline__ void coherent_store(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// V consecutive floats at once, in the widest agent-scope atomic accesses available (8 bytes): a
+// 4-byte write-through store or bypassing load costs the memory system as much as a wide one.
+template <int V>
+__device__ __forceinline__ void coherent_store_v(float *p, const float (&x)[V])
+{
+    if constexpr (V % 2 == 0) {
+#pragma unroll
+        for (int v = 0; v < V; v += 2) {
+            const unsigned long long bits = (unsigned long long)__float_as_uint(x[v]) |
+                                            ((unsigned long long)__float_as_uint(x[v + 1]) << 32);
+            __hip_atomic_store(reinterpret_cast<unsigned long long *>(p + v), bits, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v) coherent_store(p + v, x[v]);
+    }
+}
+template <int V>
+__device__ __forceinline__ void coherent_load_v(const float *p, float (&x)[V])
+{
+    if constexpr (V % 2 == 0) {
+#pragma unroll
+        for (int v = 0; v < V; v += 2) {
+            const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p + v),
+                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            x[v] = __uint_as_float((unsigned)(bits & 0xffffffffull));
+            x[v + 1] = __uint_as_float((unsigned)(bits >> 32));
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[v] = coherent_load(p + v);
+    }
+}
+
 // Wait (bounded) until a tile's status word is set; returns ST_NONE if it gave up.
 __device__ __forceinline__ uint32_t wait_flag(const uint32_t *p, uint32_t spin_limit)
 {
@@ -299,11 +334,8 @@ __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *ag
     }
     if (k < 0) return false;   // cannot happen: the chain's first tile publishes a prefix
     const float *src = pre + (size_t)(pred - (uint32_t)k * stride) * 2 * JB + lo;
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        cr[v] = coherent_load(src + v);
-        ci[v] = coherent_load(src + JB + v);
-    }
+    coherent_load_v<V>(src, cr);
+    coherent_load_v<V>(src + JB, ci);
     constexpr int NB = 4;      // aggregates fetched per round trip
     for (int d = k - 1; d >= 0; d -= NB) {
         float er[NB][V], ei[NB][V];
@@ -311,11 +343,8 @@ __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *ag
         for (int n = 0; n < NB; ++n) {
             const int dd = d - n < 0 ? 0 : d - n;
             const float *ag = agg + (size_t)(pred - (uint32_t)dd * stride) * 2 * JB + lo;
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                er[n][v] = coherent_load(ag + v);
-                ei[n][v] = coherent_load(ag + JB + v);
-            }
+            coherent_load_v<V>(ag, er[n]);
+            coherent_load_v<V>(ag + JB, ei[n]);
         }
 #pragma unroll
         for (int n = 0; n < NB; ++n) {
