@@ -579,6 +579,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     a.conv_clamp = d->conv_clamp; a.grad_clamp = d->grad_clamp;
     a.spin_limit = g_spin_limit.load();
     a.total_tiles = (uint32_t)tiles;
+    a.dbg = reinterpret_cast<unsigned long long *>(ws + w.off_dbg);
     if (launch_bwd(a, kc, vec, s) != hipSuccess) return CAWN_ELAUNCH;
     if (want_param) {
         const int rows = part_rows(kc);

@@ -22,6 +22,12 @@
 
 namespace cawn {
 
+#ifdef CAWN_TIMING
+#define BWD_STAMP(k) do { if (threadIdx.x == 0) a.dbg[(size_t)sTicket * 16 + (k)] = wall_clock64(); } while (0)
+#else
+#define BWD_STAMP(k) do { } while (0)
+#endif
+
 template <int V> struct BVec;
 template <> struct BVec<1> {
     static __device__ __forceinline__ void ld(float (&d)[1], const float *p) { d[0] = *p; }
@@ -71,6 +77,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         sLast = 0;
     }
     __syncthreads();
+    BWD_STAMP(1);
     const uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket);   // wave-uniform: index math stays scalar
     const int lb = ticket % a.nLB;
     const int rest = ticket / a.nLB;
@@ -202,6 +209,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         sEb[seg][1][lv * V + v] = Ebi[v];
     }
     __syncthreads();
+    BWD_STAMP(2);
     float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
 #pragma unroll
     for (int v = 0; v < V; ++v) Xr[v] = Xi[v] = 0.f;
@@ -239,6 +247,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     wait_stores_done();
     if (tid == 0 && chained && feeds) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, ST_AGG);
     __syncthreads();
+    BWD_STAMP(3);
 
     // ---- front-end recompute, rows from LDS as a sliding window
     float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V];   // ag: a*g*SiLU'(z_ang)
@@ -326,6 +335,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             sEf[seg][1][lv * V + v] = Efi[v];
         }
         __syncthreads();
+    BWD_STAMP(4);
         float Fr[V], Fi[V], pfr[V], pfi[V];   // lambda^(NSTEP*seg): the segments before mine
 #pragma unroll
         for (int v = 0; v < V; ++v) { Fr[v] = Fi[v] = pfi[v] = 0.f; pfr[v] = 1.f; }
@@ -388,6 +398,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
     }
 
+    BWD_STAMP(5);
     // ---- chain, second half: look-back (its round trips were hidden behind the recompute above)
     if (head) {
         float cr[V], ci[V], Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
@@ -426,6 +437,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
     }
     __syncthreads();
+    BWD_STAMP(6);
 
     // ---- true adjoint entering my segment
     float Gr[V], Gi[V];
@@ -463,6 +475,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             dzi[i][v] = dph * ag[i][v];          //                           angle stream
         }
     }
+    BWD_STAMP(7);
     // gradient of the incoming scan state: conj(lambda) G[0]
     if (a.dstate_in && tt == 0 && head && active) {
         float xr[V], xi[V];
@@ -531,6 +544,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             if (lv == 0) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, HALO > 0 ? ST_HALO : ST_PREFIX);
         }
         __syncthreads();
+    BWD_STAMP(8);
         float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
 #pragma unroll
         for (int r = 0; r < HALO1; ++r)
@@ -675,6 +689,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 if (!(seg & 1)) sRed[wave][r][lv * V + v] = s;
             }
         __syncthreads();
+    BWD_STAMP(9);
         for (int e = tid; e < ROWS * JB; e += NT) {
             const int row = e / JB, c = e % JB;
             float s = 0.f;
@@ -686,6 +701,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
 
     // ---- bookkeeping: the tile that finishes last clears the control words
     __syncthreads();
+    BWD_STAMP(10);
     if (tid == 0) {
         wait_stores_done();
         const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

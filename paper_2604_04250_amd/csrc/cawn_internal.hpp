@@ -134,6 +134,7 @@ struct BwdArgs {
     GateSet gs;
     uint32_t spin_limit;
     uint32_t total_tiles;
+    unsigned long long *dbg;     // -DCAWN_TIMING builds only
 };
 
 // Number of per-lane partial sums a backward tile emits: dgamma, dtheta, dbias[2], dw[2][conv_k].
