@@ -458,6 +458,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
+    if (ist > (1ll << 24) || ost > (1ll << 24)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     FwdArgs a{};
     if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;
@@ -540,6 +541,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
+    if (ist > (1ll << 24) || ost > (1ll << 24)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     BwdArgs a{};
     if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;

@@ -18,6 +18,8 @@
 //     chain) publishes its first conv_k-1 rows through the workspace.
 // Parameter gradients leave each tile as per-lane partial sums (fixed order inside the tile) and
 // are summed over tiles by a second kernel in a fixed order: results are bitwise repeatable.
+#include <type_traits>
+
 #include "cawn_internal.hpp"
 
 namespace cawn {
@@ -65,7 +67,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     __shared__ float sEb[NSEG][2][JB];
     __shared__ float sEf[PARAM ? NSEG : 1][2][JB];
     __shared__ float sCarry[2][JB];
-    __shared__ float sHalo[NSEG][HALO1][2][JB];
+    __shared__ float sHalo[NSEG + 1][HALO1][2][JB];   // [NSEG]: rows of the next tile
     __shared__ float sRed[PARAM ? NW : 1][ROWS][JB];
     __shared__ uint32_t sTicket, sLast;
 
@@ -102,54 +104,26 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         const float *gre = a.dz_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
         const float *gim = a.dz_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
         uint32_t off = (uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V);
+        if (full) {
 #pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-            if (full) {
+            for (int i = 0; i < NSTEP; ++i) {
                 BVec<V>::ld(dzr[i], gre + off);
                 BVec<V>::ld(dzi[i], gim + off);
-            } else {
+                off += ost32;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NSTEP; ++i) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
                 if (active && t0 + i < a.L) {
                     BVec<V>::ld(dzr[i], gre + off);
                     BVec<V>::ld(dzi[i], gim + off);
                 }
+                off += ost32;
             }
-            off += ost32;
         }
     }
-    // Rows outside [0, L) and lanes beyond J read a clamped (valid, finite) address: they only ever
-    // meet a zero adjoint.  Rows before a sequence start are zeroed at the point of use.
-    {
-        const int tile_t0 = tt * TILE_T;
-        const int LB = a.stage16 ? 16 : 4;
-        const int LR = JB * 4 / LB, RPI = 64 / LR;
-        const int ninst = (2 * NRT + RPI - 1) / RPI;
-        for (int i = wave; i < ninst; i += NW) {
-            int f = i * RPI + lane / LR;
-            if (f >= 2 * NRT) f = 2 * NRT - 1;
-            const int sidx = f >= NRT ? 1 : 0;
-            const int rr = f - sidx * NRT;
-            const int t = tile_t0 - HALO + rr;
-            int j = lb * JB + (lane % LR) * (LB / 4);
-            if (j >= a.J) j = 0;
-            const float *src;
-            if (HALO > 0 && t < 0 && tail_in) {
-                const int hrow = t + HALO < 0 ? 0 : t + HALO;
-                src = tail_in + ((size_t)(b * HALO + hrow) * 2 + sidx) * a.J + j;
-            } else {
-                const int tc = t < 0 ? 0 : (t >= a.L ? a.L - 1 : t);
-                src = (sidx ? a.ang : a.mag) + (size_t)b * a.isb + (size_t)tc * a.ist + j;
-            }
-#if defined(__HIP_DEVICE_COMPILE__)
-            if (a.stage16) __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 16, 0, 0);
-            else __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 4, 0, 0);
-#else
-            (void)src;
-#endif
-        }
-    }
-
     // ---- lane constants
     float lr[V], li[V], pnr[V], pni[V];
     float wmf[KC1][V], waf[KC1][V], bm[V], ba[V];   // taps for the front-end
@@ -175,6 +149,15 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             }
         }
     }
+
+    // ---- the tile's input rows go to LDS (needed from the front-end on; issued after the loads the
+    //      local adjoint waits for, so that it does not wait for these as well)
+    if (a.stage16)
+        stage_rows<JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
+                                 NW, lane);
+    else
+        stage_rows<JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
+                                NW, lane);
 
     // gradient of the carried state joins the last token
     if (a.dstate_out && active && a.L - 1 >= t0 && a.L - 1 < t0 + NSTEP) {
@@ -208,7 +191,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         sEb[seg][0][lv * V + v] = Ebr[v];
         sEb[seg][1][lv * V + v] = Ebi[v];
     }
-    __syncthreads();
+    lds_barrier_raw();     // the staged rows are still on their way
     BWD_STAMP(2);
     float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
 #pragma unroll
@@ -246,16 +229,43 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     // the staged rows have landed; so have the aggregate stores of the head group's wave
     wait_stores_done();
     if (tid == 0 && chained && feeds) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, ST_AGG);
-    __syncthreads();
+    lds_barrier();
     BWD_STAMP(3);
+
+    // the forward state entering the tile (checkpoint) and the constants of the reverse pass, fetched
+    // now so that they arrive during the front-end
+    float kr[V], ki[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) kr[v] = ki[v] = 0.f;
+    if (PARAM && active && a.ckpt) {
+        const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
+        BVec<V>::ld(kr, ck);
+        BVec<V>::ld(ki, ck + a.J);
+    }
+    float psr[V], psi[V], cth[V], sth[V], gam[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) { psi[v] = sth[v] = gam[v] = 0.f; psr[v] = cth[v] = 1.f; }
+    if (active) {
+        const float *tb = a.table + j0;
+        BVec<V>::ld(psr, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
+        BVec<V>::ld(psi, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
+        if (PARAM) {
+            BVec<V>::ld(cth, tb + (size_t)R_COS * a.Jp);
+            BVec<V>::ld(sth, tb + (size_t)R_SIN * a.Jp);
+            BVec<V>::ld(gam, tb + (size_t)R_GAMMA * a.Jp);
+        }
+    }
 
     // ---- front-end recompute, rows from LDS as a sliding window
     float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V];   // ag: a*g*SiLU'(z_ang)
     float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];      // forward state before each token
     float Efr[V], Efi[V];
-    {
+    const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
+    // The mode switches are uniform over the launch; each combination gets its own straight-line
+    // copy of the loop, so that the tokens' dependent chains (exp -> rcp -> sin/cos) interleave.
+    auto front_end = [&](auto amp_c, auto small_c) {
+        constexpr bool AMP = decltype(amp_c)::value, SMALL = decltype(small_c)::value;
         float wnm[KC1][V], wna[KC1][V];
-        const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
         // (row r of my segment lives in slot r % KC1: no register shuffling as the window slides)
 #pragma unroll
         for (int k = 0; k < KC1 - 1; ++k) {
@@ -300,14 +310,14 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                     ka = 1.0f;
                 }
                 float amp = xm;
-                if (a.amp_mode) {
+                if (AMP) {
                     const float sp = softplus_fast(xm);
                     amp = __builtin_fminf(sp, 10.0f);
                     km *= sp < 10.0f ? sigmoid_fast(xm) : 0.0f;
                 }
                 const bool g = in_gate(a.gs, zm);
                 float s, c;
-                if (a.small_angle) sincos_small(phi, s, c);
+                if (SMALL) sincos_small(phi, s, c);
                 else sincos_fast(phi, s, c);
                 const float agv = g ? amp : 0.0f;
                 cs[i][v] = c;
@@ -325,6 +335,16 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 }
             }
         }
+    };
+    {
+        using T_ = std::true_type;
+        using F_ = std::false_type;
+        switch ((a.amp_mode ? 2 : 0) | (a.small_angle ? 1 : 0)) {
+        case 0: front_end(F_{}, F_{}); break;
+        case 1: front_end(F_{}, T_{}); break;
+        case 2: front_end(T_{}, F_{}); break;
+        default: front_end(T_{}, T_{}); break;
+        }
     }
 
     // ---- forward state entering my segment (checkpoint + earlier segments), then S[t-1] per token
@@ -334,7 +354,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             sEf[seg][0][lv * V + v] = Efr[v];
             sEf[seg][1][lv * V + v] = Efi[v];
         }
-        __syncthreads();
+        lds_barrier();
     BWD_STAMP(4);
         float Fr[V], Fi[V], pfr[V], pfi[V];   // lambda^(NSTEP*seg): the segments before mine
 #pragma unroll
@@ -352,14 +372,6 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 Fr[v] = nr;
                 Fi[v] = ni;
             }
-        }
-        float kr[V], ki[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) kr[v] = ki[v] = 0.f;
-        if (active && a.ckpt) {
-            const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
-            BVec<V>::ld(kr, ck);
-            BVec<V>::ld(ki, ck + a.J);
         }
 #pragma unroll
         for (int v = 0; v < V; ++v) {
@@ -383,20 +395,12 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
     }
 
-    // constants of the reverse pass, fetched now so that they arrive during the look-back
-    float psr[V], psi[V], cth[V], sth[V], gam[V];
+    // The reverse-pass constants must have arrived before the chain's stores below are issued: a
+    // wave's memory operations complete in order, so a wait placed after those stores (where the
+    // compiler would put it, at the first use) would also wait for the stores' round trip.
 #pragma unroll
-    for (int v = 0; v < V; ++v) { psi[v] = sth[v] = gam[v] = 0.f; psr[v] = cth[v] = 1.f; }
-    if (active) {
-        const float *tb = a.table + j0;
-        BVec<V>::ld(psr, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
-        BVec<V>::ld(psi, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
-        if (PARAM) {
-            BVec<V>::ld(cth, tb + (size_t)R_COS * a.Jp);
-            BVec<V>::ld(sth, tb + (size_t)R_SIN * a.Jp);
-            BVec<V>::ld(gam, tb + (size_t)R_GAMMA * a.Jp);
-        }
-    }
+    for (int v = 0; v < V; ++v)
+        asm volatile("" ::"v"(psr[v]), "v"(psi[v]), "v"(cth[v]), "v"(sth[v]), "v"(gam[v]));
 
     BWD_STAMP(5);
     // ---- chain, second half: look-back (its round trips were hidden behind the recompute above)
@@ -421,6 +425,9 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+        // every load of this block has arrived before its stores go out (see above)
+#pragma unroll
+        for (int v = 0; v < V; ++v) asm volatile("" ::"v"(hr[v]), "v"(hi[v]), "v"(qr[v]), "v"(qi[v]));
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             sCarry[0][lv * V + v] = cr[v];
@@ -436,7 +443,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
     BWD_STAMP(6);
 
     // ---- true adjoint entering my segment
@@ -447,6 +454,15 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         Gr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(psi[v], ci, Xr[v]));      // conj(ps) * carry
         Gi[v] = __builtin_fmaf(psr[v], ci, __builtin_fmaf(-psi[v], cr, Xi[v]));
     }
+
+    // The tile's last segment needs the conv pre-activation gradients of the next tile's first HALO
+    // tokens.  The head group fetches them (all chain traffic stays in one wave, whose memory
+    // operations then have one known order); that tile's status word is asked for now and the
+    // answer comes back during the reverse pass.
+    const bool fetch_halo = KC > 0 && HALO > 0 && head && chained;
+    const uint32_t *halo_flag = a.flags + (size_t)(ticket - (chained ? chain_stride : 0u)) * FLAG_STRIDE;
+    uint32_t halo_st = ST_NONE;
+    if (fetch_halo) halo_st = flag_load(halo_flag);
 
     // ---- reverse pass: adjoint, returned gradients, parameter terms
     float acc_g[V], acc_t[V];
@@ -492,13 +508,22 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     float *oang = a.dang + (size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB;
     uint32_t ooff = (uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V);
     if (KC == 0) {
+        if (full) {
 #pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-            if (full || (active && t0 + i < a.L)) {
+            for (int i = 0; i < NSTEP; ++i) {
                 BVec<V>::st(omag + ooff, dzr[i]);
                 BVec<V>::st(oang + ooff, dzi[i]);
+                ooff += ist32;
             }
-            ooff += ist32;
+        } else {
+#pragma unroll
+            for (int i = 0; i < NSTEP; ++i) {
+                if (active && t0 + i < a.L) {
+                    BVec<V>::st(omag + ooff, dzr[i]);
+                    BVec<V>::st(oang + ooff, dzi[i]);
+                }
+                ooff += ist32;
+            }
         }
         if (head && feeds) {   // the prefix stores were issued before the reverse pass
             wait_stores_done();
@@ -506,20 +531,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
     } else {
         // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
-        // (the taps are fetched again here rather than kept in registers across the whole kernel)
-        float wm[KC1][V], wa[KC1][V];
-#pragma unroll
-        for (int k = 0; k < KC1; ++k)
-#pragma unroll
-            for (int v = 0; v < V; ++v) wm[k][v] = wa[k][v] = 0.f;
-        if (active) {
-            const float *tb = a.table + j0;
-#pragma unroll
-            for (int k = 0; k < KC; ++k) {
-                BVec<V>::ld(wm[k], tb + (size_t)(R_W0 + k) * a.Jp);
-                BVec<V>::ld(wa[k], tb + (size_t)(R_W0 + KC + k) * a.Jp);
-            }
-        }
+        const auto &wm = wmf;
+        const auto &wa = waf;
         if (HALO > 0) {
 #pragma unroll
             for (int r = 0; r < HALO; ++r)
@@ -529,8 +542,9 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                     sHalo[seg][r][1][lv * V + v] = dzi[r][v];
                 }
         }
-        if (head && feeds) {      // prefix (issued earlier) and the rows the earlier tile needs
-            if (HALO > 0) {
+        if (head) {
+            // the rows the earlier tile needs go out; the rows of the later tile come in
+            if (feeds && HALO > 0) {
                 float *hp = a.halo + (size_t)ticket * HALO * 2 * JB + lv * V;
 #pragma unroll
                 for (int r = 0; r < HALO; ++r)
@@ -540,84 +554,103 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                         coherent_store(hp + (r * 2 + 1) * JB + v, dzi[r][v]);
                     }
             }
-            wait_stores_done();
-            if (lv == 0) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, HALO > 0 ? ST_HALO : ST_PREFIX);
-        }
-        __syncthreads();
-    BWD_STAMP(8);
-        float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
+            float xm[HALO1][V], xa[HALO1][V];
 #pragma unroll
-        for (int r = 0; r < HALO1; ++r)
+            for (int r = 0; r < HALO1; ++r)
 #pragma unroll
-            for (int v = 0; v < V; ++v) hm[r][v] = ha[r][v] = 0.f;
-        if (HALO > 0) {
-            if (seg < NSEG - 1) {
-#pragma unroll
-                for (int r = 0; r < HALO; ++r)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        hm[r][v] = sHalo[seg + 1][r][0][lv * V + v];
-                        ha[r][v] = sHalo[seg + 1][r][1][lv * V + v];
-                    }
-            } else if (chained) {
-                const uint32_t idx = ticket - chain_stride;
-                uint32_t st = flag_load(a.flags + (size_t)idx * FLAG_STRIDE);
+                for (int v = 0; v < V; ++v) xm[r][v] = xa[r][v] = 0.f;
+            if (fetch_halo) {
                 uint32_t spins = 0;
-                while (st < ST_HALO && spins < a.spin_limit) {
+                while (halo_st < ST_HALO && spins < a.spin_limit) {
                     __builtin_amdgcn_s_sleep(1);
-                    st = flag_load(a.flags + (size_t)idx * FLAG_STRIDE);
+                    halo_st = flag_load(halo_flag);
                     ++spins;
                 }
                 compiler_fence();
-                if (st >= ST_HALO) {
-                    const float *hp = a.halo + (size_t)idx * HALO * 2 * JB + lv * V;
+                if (halo_st >= ST_HALO) {
+                    const float *hp = a.halo + (size_t)(ticket - chain_stride) * HALO * 2 * JB + lv * V;
 #pragma unroll
                     for (int r = 0; r < HALO; ++r)
 #pragma unroll
                         for (int v = 0; v < V; ++v) {
-                            hm[r][v] = coherent_load(hp + (r * 2 + 0) * JB + v);
-                            ha[r][v] = coherent_load(hp + (r * 2 + 1) * JB + v);
+                            xm[r][v] = coherent_load(hp + (r * 2 + 0) * JB + v);
+                            xa[r][v] = coherent_load(hp + (r * 2 + 1) * JB + v);
                         }
                 } else if (lv == 0) {
                     __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-        }
+            if (HALO > 0) {
 #pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-            const int t = t0 + i;
-            float dm[V], da[V];
+                for (int r = 0; r < HALO; ++r)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        sHalo[NSEG][r][0][lv * V + v] = xm[r][v];
+                        sHalo[NSEG][r][1][lv * V + v] = xa[r][v];
+                    }
+            }
+        }
+        // Every wave: nothing of the above is in flight any more (a no-op for the waves that took no
+        // part).  Only then the status word: it covers the prefix and the halo rows.
+        wait_vm<0>();
+        if (tid == 0 && feeds) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, HALO > 0 ? ST_HALO : ST_PREFIX);
+        lds_barrier();
+    BWD_STAMP(8);
+        float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
+#pragma unroll
+        for (int r = 0; r < HALO1; ++r)
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                float sm_ = 0.f, sa_ = 0.f;
-#pragma unroll
-                for (int k = 0; k < KC; ++k) {
-                    const int idx = i + (KC - 1) - k;
-                    const float zm_ = idx < NSTEP ? dzr[idx < NSTEP ? idx : 0][v] : hm[idx >= NSTEP ? idx - NSTEP : 0][v];
-                    const float za_ = idx < NSTEP ? dzi[idx < NSTEP ? idx : 0][v] : ha[idx >= NSTEP ? idx - NSTEP : 0][v];
-                    sm_ = __builtin_fmaf(wm[k][v], zm_, sm_);
-                    sa_ = __builtin_fmaf(wa[k][v], za_, sa_);
-                }
-                dm[v] = sm_;
-                da[v] = sa_;
+                hm[r][v] = HALO > 0 ? sHalo[seg + 1][r][0][lv * V + v] : 0.f;
+                ha[r][v] = HALO > 0 ? sHalo[seg + 1][r][1][lv * V + v] : 0.f;
             }
-            if (full && !dtail_out) {
-                BVec<V>::st(omag + ooff, dm);
-                BVec<V>::st(oang + ooff, da);
-            } else if (active && t < a.L) {
-                if (HALO > 0 && dtail_out && t >= a.L - HALO) {   // state_out's history rows are copies of these inputs
-                    const int r = t - (a.L - HALO);
-                    float xm_[V], xa_[V];
-                    const size_t o = ((size_t)(b * HALO + r) * 2) * a.J + j0;
-                    BVec<V>::ld(xm_, dtail_out + o);
-                    BVec<V>::ld(xa_, dtail_out + o + a.J);
+        auto conv_t = [&](auto plain_c) {
+            constexpr bool PLAIN = decltype(plain_c)::value;     // no per-row checks
 #pragma unroll
-                    for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
+            for (int i = 0; i < NSTEP; ++i) {
+                const int t = t0 + i;
+                float dm[V], da[V];
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float sm_ = 0.f, sa_ = 0.f;
+#pragma unroll
+                    for (int k = 0; k < KC; ++k) {
+                        const int idx = i + (KC - 1) - k;
+                        const float zm_ = idx < NSTEP ? dzr[idx < NSTEP ? idx : 0][v] : hm[idx >= NSTEP ? idx - NSTEP : 0][v];
+                        const float za_ = idx < NSTEP ? dzi[idx < NSTEP ? idx : 0][v] : ha[idx >= NSTEP ? idx - NSTEP : 0][v];
+                        sm_ = __builtin_fmaf(wm[k][v], zm_, sm_);
+                        sa_ = __builtin_fmaf(wa[k][v], za_, sa_);
+                    }
+                    dm[v] = sm_;
+                    da[v] = sa_;
                 }
-                BVec<V>::st(omag + ooff, dm);
-                BVec<V>::st(oang + ooff, da);
+                if (PLAIN) {
+                    BVec<V>::st(omag + ooff, dm);
+                    BVec<V>::st(oang + ooff, da);
+                } else if (active && t < a.L) {
+                    if (HALO > 0 && dtail_out && t >= a.L - HALO) {   // state_out's history rows are copies of these inputs
+                        const int r = t - (a.L - HALO);
+                        float xm_[V], xa_[V];
+                        const size_t o = ((size_t)(b * HALO + r) * 2) * a.J + j0;
+                        BVec<V>::ld(xm_, dtail_out + o);
+                        BVec<V>::ld(xa_, dtail_out + o + a.J);
+#pragma unroll
+                        for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
+                    }
+                    BVec<V>::st(omag + ooff, dm);
+                    BVec<V>::st(oang + ooff, da);
+                }
+                ooff += ist32;
             }
-            ooff += ist32;
+        };
+        // Both paths end with every load complete, so that no wait for one of them can land behind
+        // the output stores (where it would drain them); the stores themselves stay in flight.
+        if (full && !dtail_out) {
+            conv_t(std::true_type{});
+            wait_vm<2 * NSTEP>();
+        } else {
+            conv_t(std::false_type{});
+            wait_vm<0>();
         }
         // gradient of the incoming conv history: rows r <-> time r - HALO
         if (HALO > 0 && a.dstate_in && tt == 0 && head && active) {
@@ -688,7 +721,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 const float s = (seg & 1) ? other + part[r][v] : part[r][v] + other;
                 if (!(seg & 1)) sRed[wave][r][lv * V + v] = s;
             }
-        __syncthreads();
+        lds_barrier();
     BWD_STAMP(9);
         for (int e = tid; e < ROWS * JB; e += NT) {
             const int row = e / JB, c = e % JB;
@@ -700,14 +733,14 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     }
 
     // ---- bookkeeping: the tile that finishes last clears the control words
-    __syncthreads();
+    lds_barrier();
     BWD_STAMP(10);
     if (tid == 0) {
         wait_stores_done();
         const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sLast = (old + 1 == a.total_tiles) ? 1u : 0u;
     }
-    __syncthreads();
+    lds_barrier();
     if (sLast) {
         for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + (size_t)i * FLAG_STRIDE, ST_NONE);
         if (tid == 0) {

@@ -18,6 +18,8 @@
 // an atomic ticket, so a tile only ever waits for tiles that a running workgroup already holds.
 // The ticket and the input rows of the NEXT tile are fetched while the current tile is in its
 // communication phase, whose memory round trips would otherwise leave the SIMDs idle.
+#include <type_traits>
+
 #include "cawn_internal.hpp"
 
 namespace cawn {
@@ -116,42 +118,18 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
     uint32_t my_tiles = 0;
 
-    // Stage a tile's input rows in LDS with direct global->LDS loads (no registers involved).  The
-    // chain-owning wave stays out of it: a wave's memory operations complete in order, and its
-    // polls of other tiles must not queue behind a tile's worth of HBM reads.  Rows outside [0, L)
-    // and lanes beyond J read a clamped (valid) address; their values never reach anything that is
-    // stored (the scan is causal, a lane only reads its own LDS column), and rows before a sequence
-    // start are zeroed at the point of use.
+    // Stage a tile's input rows in LDS.  The chain-owning wave stays out of it: a wave's memory
+    // operations complete in order, and its polls of other tiles must not queue behind a tile's
+    // worth of HBM reads.
+    const int ist32 = (int)a.ist;
     auto stage_tile = [&](const TileId &T) {
         if (owner_wave) return;
-        const int tile_t0 = T.tt * TILE_T;
-        // LB bytes per lane, LR lanes per row, RPI rows per wave instruction
-        const int LB = a.stage16 ? 16 : 4;
-        const int LR = JB * 4 / LB, RPI = 64 / LR;
-        const int ninst = (2 * NRT + RPI - 1) / RPI;
-        for (int i = wave; i < ninst; i += NW - 1) {
-            int f = i * RPI + lane / LR;
-            if (f >= 2 * NRT) f = 2 * NRT - 1;
-            const int sidx = f >= NRT ? 1 : 0;
-            const int rr = f - sidx * NRT;
-            const int t = tile_t0 - HALO + rr;
-            int j = T.lb * JB + (lane % LR) * (LB / 4);
-            if (j >= a.J) j = 0;
-            const float *src;
-            if (HALO > 0 && t < 0 && tail_in) {
-                const int hr_ = t + HALO < 0 ? 0 : t + HALO;
-                src = tail_in + ((size_t)(T.b * HALO + hr_) * 2 + sidx) * a.J + j;
-            } else {
-                const int tc = t < 0 ? 0 : (t >= a.L ? a.L - 1 : t);
-                src = (sidx ? a.ang : a.mag) + (size_t)T.b * a.isb + (size_t)tc * a.ist + j;
-            }
-#if defined(__HIP_DEVICE_COMPILE__)
-            if (a.stage16) __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 16, 0, 0);
-            else __builtin_amdgcn_global_load_lds(src, &sU[i * RPI][0], 4, 0, 0);
-#else
-            (void)src;
-#endif
-        }
+        if (a.stage16)
+            stage_rows<JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
+                                     ist32, wave, NW - 1, lane);
+        else
+            stage_rows<JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
+                                    ist32, wave, NW - 1, lane);
     };
 
     TileId T{};
@@ -170,6 +148,8 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         }
     }
 
+    wait_vm<0>();     // the first tile's staged rows
+
     float lr[V], li[V], pfr[V], pfi[V], psr[V], psi[V];
     float wm[KC1][V], wa[KC1][V], bm[V], ba[V];
     int lb_loaded = -1;
@@ -182,9 +162,11 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         const int t0 = tt * TILE_T + seg * NSTEP;
         ++my_tiles;
 
-        // ticket of the next tile: asked for now, needed after the front-end
+        // ticket of the next tile: asked for now, parked in LDS after the front-end (the round trip
+        // of the atomic stays off the path to the barrier below)
+        uint32_t ticket_ahead = 0;
         if (tid == 0)
-            sTicket[(it + 1) & 1] = __hip_atomic_fetch_add(&a.hdr->ticket[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---- lane constants (change only when the queue moves on to its next lane block)
         if (T.lb != lb_loaded) {
@@ -214,71 +196,93 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                     }
                 }
             }
+            // waited for here, inside the rare branch: left to the compiler, the wait would sit at the
+            // first use, on every iteration, and drain the previous tile's output stores with it
+            wait_vm<0>();
         }
 
-        // ---- the staged rows have landed
-        wait_stores_done();
-        __syncthreads();
+        // ---- the staged rows have landed (each wave waited for its own loads: before the loop, or
+        //      at the end of the previous iteration)
+        lds_barrier();
         CAWN_STAMP(0);
 
         // ---- front-end, phasors, local scan from zero.  Rows come from LDS as a sliding window.
         float pr[NSTEP][V], pi[NSTEP][V];
         float Er[V], Ei[V];
         uint32_t gbits[NSTEP];
-        const bool want_mask = a.mask != nullptr;
-        float wnm[KC1][V], wna[KC1][V];           // window: rows i .. i+KC-1 of my segment
         const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
-        // (row r of my segment lives in slot r % KC1: no register shuffling as the window slides)
+        // The mode switches are uniform over the launch; each combination gets its own straight-line
+        // copy of the loop, so that the tokens' dependent chains (exp -> rcp -> sin/cos) interleave.
+        auto front_end = [&](auto amp_c, auto small_c, auto mask_c) {
+            constexpr bool AMP = decltype(amp_c)::value, SMALL = decltype(small_c)::value;
+            constexpr bool MASK = decltype(mask_c)::value;
+            float wnm[KC1][V], wna[KC1][V];           // window: rows i .. i+KC-1 of my segment
+            // (row r of my segment lives in slot r % KC1: no register shuffling as the window slides)
 #pragma unroll
-        for (int k = 0; k < KC1 - 1; ++k) {
+            for (int k = 0; k < KC1 - 1; ++k) {
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
-                wna[k % KC1][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
-            }
-        }
-#pragma unroll
-        for (int v = 0; v < V; ++v) Er[v] = Ei[v] = 0.f;
-#pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-            gbits[i] = 0;
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
-                wna[(i + HALO) % KC1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
-            }
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                float zm, xm, phi;
-                if (KC > 0) {
-                    zm = bm[v];
-                    float za = ba[v];
-#pragma unroll
-                    for (int k = 0; k < KC; ++k) {
-                        zm = __builtin_fmaf(wm[k][v], wnm[(i + k) % KC1][v], zm);
-                        za = __builtin_fmaf(wa[k][v], wna[(i + k) % KC1][v], za);
-                    }
-                    const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
-                    xm = cm * sigmoid_fast(cm);
-                    phi = ca * sigmoid_fast(ca);
-                } else {
-                    zm = wnm[i % KC1][v];
-                    xm = zm;
-                    phi = wna[i % KC1][v];
+                for (int v = 0; v < V; ++v) {
+                    wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
+                    wna[k % KC1][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
                 }
-                const float amp = a.amp_mode ? __builtin_fminf(softplus_fast(xm), 10.0f) : xm;
-                const bool g = in_gate(a.gs, zm);
-                float s, c;
-                if (a.small_angle) sincos_small(phi, s, c);
-                else sincos_fast(phi, s, c);
-                const float ag = g ? amp : 0.0f;
-                pr[i][v] = ag * c;
-                pi[i][v] = ag * s;
-                if (want_mask) gbits[i] |= (g && active ? 1u : 0u) << v;
-                const float nr = __builtin_fmaf(lr[v], Er[v], __builtin_fmaf(-li[v], Ei[v], pr[i][v]));
-                const float ni = __builtin_fmaf(li[v], Er[v], __builtin_fmaf(lr[v], Ei[v], pi[i][v]));
-                Er[v] = nr;
-                Ei[v] = ni;
+            }
+#pragma unroll
+            for (int v = 0; v < V; ++v) Er[v] = Ei[v] = 0.f;
+#pragma unroll
+            for (int i = 0; i < NSTEP; ++i) {
+                gbits[i] = 0;
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
+                    wna[(i + HALO) % KC1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
+                }
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    float zm, xm, phi;
+                    if (KC > 0) {
+                        zm = bm[v];
+                        float za = ba[v];
+#pragma unroll
+                        for (int k = 0; k < KC; ++k) {
+                            zm = __builtin_fmaf(wm[k][v], wnm[(i + k) % KC1][v], zm);
+                            za = __builtin_fmaf(wa[k][v], wna[(i + k) % KC1][v], za);
+                        }
+                        const float cm = clampf(zm, a.conv_clamp), ca = clampf(za, a.conv_clamp);
+                        xm = cm * sigmoid_fast(cm);
+                        phi = ca * sigmoid_fast(ca);
+                    } else {
+                        zm = wnm[i % KC1][v];
+                        xm = zm;
+                        phi = wna[i % KC1][v];
+                    }
+                    const float amp = AMP ? __builtin_fminf(softplus_fast(xm), 10.0f) : xm;
+                    const bool g = in_gate(a.gs, zm);
+                    float s, c;
+                    if (SMALL) sincos_small(phi, s, c);
+                    else sincos_fast(phi, s, c);
+                    const float ag = g ? amp : 0.0f;
+                    pr[i][v] = ag * c;
+                    pi[i][v] = ag * s;
+                    if (MASK) gbits[i] |= g ? (1u << v) : 0u;
+                    const float nr = __builtin_fmaf(lr[v], Er[v], __builtin_fmaf(-li[v], Ei[v], pr[i][v]));
+                    const float ni = __builtin_fmaf(li[v], Er[v], __builtin_fmaf(lr[v], Ei[v], pi[i][v]));
+                    Er[v] = nr;
+                    Ei[v] = ni;
+                }
+            }
+        };
+        {
+            using T_ = std::true_type;
+            using F_ = std::false_type;
+            switch ((a.amp_mode ? 4 : 0) | (a.small_angle ? 2 : 0) | (a.mask ? 1 : 0)) {
+            case 0: front_end(F_{}, F_{}, F_{}); break;
+            case 1: front_end(F_{}, F_{}, T_{}); break;
+            case 2: front_end(F_{}, T_{}, F_{}); break;
+            case 3: front_end(F_{}, T_{}, T_{}); break;
+            case 4: front_end(T_{}, F_{}, F_{}); break;
+            case 5: front_end(T_{}, F_{}, T_{}); break;
+            case 6: front_end(T_{}, T_{}, F_{}); break;
+            default: front_end(T_{}, T_{}, T_{}); break;
             }
         }
         CAWN_STAMP(2);
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             const int W = (a.J + 31) >> 5;
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
-                uint32_t m = gbits[i] << (V * (lv % TPW));
+                uint32_t m = (active ? gbits[i] : 0u) << (V * (lv % TPW));
 #pragma unroll
                 for (int o = 1; o < TPW; o <<= 1) m |= (uint32_t)__shfl_xor((int)m, o, 64);
                 const int t = t0 + i;
@@ -304,7 +308,8 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             sE[seg][0][lv * V + v] = Er[v];
             sE[seg][1][lv * V + v] = Ei[v];
         }
-        __syncthreads();
+        if (tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
+        lds_barrier();
         CAWN_STAMP(3);
 
         // ---- start staging the next tile (it lands during this tile's communication phase)
@@ -389,7 +394,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 coherent_store_v<V>(a.pre + slot + JB, P_i);
             }
         }
-        __syncthreads();
+        lds_barrier_raw();     // the next tile's rows are still on their way
         CAWN_STAMP(6);
 
         // ---- true state entering my segment
@@ -409,38 +414,46 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             const uint32_t ost32 = (uint32_t)a.ost;
             uint32_t off = (uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V);
             const bool full = (tt + 1) * TILE_T <= a.L && (T.lb + 1) * JB <= a.J;
+            const bool plain = full && !(a.state_out && tt == a.nT - 1);   // no per-row checks at all
+            auto replay = [&](auto plain_c) {
+                constexpr bool PLAIN = decltype(plain_c)::value;
 #pragma unroll
-            for (int i = 0; i < NSTEP; ++i) {
-                const int t = t0 + i;
-                float zr[V], zi[V];
+                for (int i = 0; i < NSTEP; ++i) {
+                    const int t = t0 + i;
+                    float zr[V], zi[V];
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    const float nr = __builtin_fmaf(lr[v], Sr[v], __builtin_fmaf(-li[v], Si[v], pr[i][v]));
-                    const float ni = __builtin_fmaf(li[v], Sr[v], __builtin_fmaf(lr[v], Si[v], pi[i][v]));
-                    Sr[v] = nr;
-                    Si[v] = ni;
-                    zr[v] = clampf(nr, a.out_clamp);
-                    zi[v] = clampf(ni, a.out_clamp);
+                    for (int v = 0; v < V; ++v) {
+                        const float nr = __builtin_fmaf(lr[v], Sr[v], __builtin_fmaf(-li[v], Si[v], pr[i][v]));
+                        const float ni = __builtin_fmaf(li[v], Sr[v], __builtin_fmaf(lr[v], Si[v], pi[i][v]));
+                        Sr[v] = nr;
+                        Si[v] = ni;
+                        zr[v] = clampf(nr, a.out_clamp);
+                        zi[v] = clampf(ni, a.out_clamp);
+                    }
+                    if (PLAIN || (active && t < a.L)) {
+                        Vec<V>::st(zre + off, zr);
+                        Vec<V>::st(zim + off, zi);
+                    }
+                    if (!PLAIN && t == a.L - 1 && a.state_out && active) {
+                        Vec<V>::st(a.state_out + ((size_t)b * 2 + 0) * a.J + j0, Sr);
+                        Vec<V>::st(a.state_out + ((size_t)b * 2 + 1) * a.J + j0, Si);
+                    }
+                    off += ost32;
                 }
-                if (full) {
-                    Vec<V>::st(zre + off, zr);
-                    Vec<V>::st(zim + off, zi);
-                } else if (active && t < a.L) {
-                    Vec<V>::st(zre + off, zr);
-                    Vec<V>::st(zim + off, zi);
-                }
-                if (t == a.L - 1 && a.state_out && active) {
-                    Vec<V>::st(a.state_out + ((size_t)b * 2 + 0) * a.J + j0, Sr);
-                    Vec<V>::st(a.state_out + ((size_t)b * 2 + 1) * a.J + j0, Si);
-                }
-                off += ost32;
+            };
+            // What is still in flight ahead of this tile's output stores must be complete now: the next
+            // tile's staged rows (needed after the next barrier) and, on the chain-owning wave, the
+            // prefix (its status word is set next).  The output stores themselves (the 2 * NSTEP
+            // youngest operations when no row needed a check) are left in flight.
+            if (plain) {
+                replay(std::true_type{});
+                wait_vm<2 * NSTEP>();
+            } else {
+                replay(std::false_type{});
+                wait_vm<0>();
             }
         }
-        // the prefix stores were issued before the replay; by now they have (nearly) landed
-        if (is_tail_seg && tt + 1 < a.nT) {
-            wait_stores_done();
-            if (lv == 0) flag_store(a.flags + (size_t)id * FLAG_STRIDE, ST_PREFIX);
-        }
+        if (is_tail_seg && tt + 1 < a.nT && lv == 0) flag_store(a.flags + (size_t)id * FLAG_STRIDE, ST_PREFIX);
         CAWN_STAMP(8);
 
         // ---- conv history for the next call: last HALO pre-conv rows (written by the last tile,

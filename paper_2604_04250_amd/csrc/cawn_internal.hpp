@@ -186,7 +186,8 @@ __device__ __forceinline__ float softplus_fast(float m)
 
 __device__ __forceinline__ bool in_gate(const GateSet &g, float x)
 {
-    return (x >= g.a1 && x <= g.b1) || (x >= g.a2 && x <= g.b2);
+    // bitwise on purpose: short-circuit forms compile to divergent branches
+    return (bool)(((int)(x >= g.a1) & (int)(x <= g.b1)) | ((int)(x >= g.a2) & (int)(x <= g.b2)));
 }
 
 // Cross-tile publication.  Tiles of one chain may run on different XCDs, whose L2 caches are not
@@ -195,11 +196,80 @@ __device__ __forceinline__ bool in_gate(const GateSet &g, float x)
 // for the stores to complete (vmcnt) before the status word is written.  Acquire/release atomics
 // are avoided on purpose: at agent scope they write back / invalidate the whole L2 on every use,
 // which a spin loop next to streaming stores cannot afford.
-__device__ __forceinline__ void wait_stores_done()
-{
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
 __device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+// Wait until at most N of this wave's vector memory operations are outstanding.  They complete in
+// issue order (loads, stores and direct-to-LDS loads alike), so this waits for everything except
+// the N youngest.  The builtin (not inline assembly) lets the compiler's own wait insertion see it.
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    compiler_fence();
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);   // expcnt, lgkmcnt: no wait
+    compiler_fence();
+}
+__device__ __forceinline__ void wait_stores_done() { wait_vm<0>(); }
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding
+// global load and store of every wave, which would serialise a tile's output stores and the next
+// tile's staging loads with the barrier; global data here is never exchanged inside a workgroup.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+// The same barrier for a point where direct-to-LDS loads are still in flight: there the compiler
+// makes the fences above wait for those loads.  Hardware barrier only; LDS accesses of this wave
+// are waited for explicitly and the compiler may not move memory accesses across.
+__device__ __forceinline__ void lds_barrier_raw()
+{
+    compiler_fence();
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0); vmcnt, expcnt: no wait
+    __builtin_amdgcn_s_barrier();
+    compiler_fence();
+}
+
+// Stage the pre-conv input rows of one tile in LDS with direct global->LDS loads (no registers):
+// rows tile_t0-HALO .. tile_t0+TILE_T-1 of the magnitude stream, then the same rows of the angle
+// stream, JB lanes each, row-major.  Called by `nwaves` waves (index `wave` among them).  Rows
+// outside [0, L) and lanes beyond J read a clamped (valid) address: their values never reach a
+// result (the scan is causal, a lane only reads its own LDS column; rows before a sequence start
+// are zeroed at the point of use).  Rows before the call's first token come from the carried conv
+// history when there is one.  LB: bytes per lane per load (16 needs 16-byte aligned rows).
+template <int JB, int HALO, int LB>
+__device__ __forceinline__ void stage_rows(float *sU, const float *mag, const float *ang, const float *tail_in,
+                                           int b, int tile_t0, int lb, int J, int L, long long isb, int ist,
+                                           int wave, int nwaves, int lane)
+{
+    constexpr int NRT = TILE_T + HALO;
+    constexpr int LR = JB * 4 / LB;                // lanes per row
+    if constexpr (LR <= 64) {
+        constexpr int RPI = 64 / LR;               // rows per wave instruction
+        constexpr int NINST = (2 * NRT + RPI - 1) / RPI;
+        // wave-uniform bases of the two streams at the tile's first token; per-lane offsets are 32-bit
+        const float *base_m = mag + (size_t)b * isb + (long long)tile_t0 * ist;
+        const float *base_a = ang + (size_t)b * isb + (long long)tile_t0 * ist;
+        int j = lb * JB + (lane % LR) * (LB / 4);
+        if (j >= J) j = 0;
+        const bool hist = HALO > 0 && tile_t0 == 0 && tail_in != nullptr;
+        for (int i = wave; i < NINST; i += nwaves) {
+            int f = i * RPI + lane / LR;
+            if (f >= 2 * NRT) f = 2 * NRT - 1;
+            const int sidx = f >= NRT ? 1 : 0;
+            const int rr = f - sidx * NRT;
+            const int t = tile_t0 - HALO + rr;
+            const int tc = t < 0 ? 0 : (t >= L ? L - 1 : t);
+            const float *src = (sidx ? base_a : base_m) + ((tc - tile_t0) * ist + j);
+            if (hist && t < 0) src = tail_in + ((size_t)(b * HALO + rr) * 2 + sidx) * J + j;
+#if defined(__HIP_DEVICE_COMPILE__)
+            if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)i * RPI * JB, 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(src, sU + (size_t)i * RPI * JB, 4, 0, 0);
+#else
+            (void)src;
+#endif
+        }
+    }
+}
 __device__ __forceinline__ void flag_store(uint32_t *p, uint32_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
