@@ -11,9 +11,16 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libcawn.so")
 SOURCES = ["cawn_api.hip", "cawn_fwd.hip", "cawn_bwd.hip"]
+# The backward kernel is a persistent loop whose body fills its register budget (4 waves per SIMD).
+# Hoisting loop-invariant copies of uniform values and addresses out of that loop costs ~10 VGPRs
+# and a wave of occupancy; they are a few ALU ops per tile when left inside.
+FILE_FLAGS = {"cawn_bwd.hip": ["-mllvm", "-disable-machine-licm"]}
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-ffp-contract=off", "-Wall", "-Wno-unused-function",
+         # every atomic here is issued by one lane; the wave-level atomic combiner would only add a
+         # read-back of the result right behind the atomic, i.e. a wait for its round trip
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
@@ -26,7 +33,8 @@ def build(verbose: bool = False, defines=(), out: str = OUT, objdir: str = CSRC)
 
     def cc(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *[f"-D{d}" for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *FILE_FLAGS.get(src, []), *[f"-D{d}" for d in defines], "-c",
+               os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

@@ -25,7 +25,7 @@
 namespace cawn {
 
 #ifdef CAWN_TIMING
-#define BWD_STAMP(k) do { if (threadIdx.x == 0) a.dbg[(size_t)sTicket * 16 + (k)] = wall_clock64(); } while (0)
+#define BWD_STAMP(k) do { if (threadIdx.x == 0) a.dbg[(size_t)ticket * 16 + (k)] = wall_clock64(); } while (0)
 #else
 #define BWD_STAMP(k) do { } while (0)
 #endif
@@ -69,37 +69,54 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     __shared__ float sCarry[2][JB];
     __shared__ float sHalo[NSEG + 1][HALO1][2][JB];   // [NSEG]: rows of the next tile
     __shared__ float sRed[PARAM ? NW : 1][ROWS][JB];
-    __shared__ uint32_t sTicket, sLast;
+    __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
-    const int tid = threadIdx.x;
-    const int lv = tid % LPR, seg = tid / LPR;
-    const int wave = tid >> 6, lane = tid & 63;
-    if (tid == 0) {
-        sTicket = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int tid_ = threadIdx.x;
+    const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
+    const float *dtail_out = a.dstate_out ? a.dstate_out + (size_t)a.B * 2 * a.J : nullptr;
+    const uint32_t chain_stride = (uint32_t)a.B * a.nLB;
+    const uint32_t ost32 = (uint32_t)a.ost, ist32 = (uint32_t)a.ist;
+    if (tid_ == 0) {
+        const uint32_t e = flag_load(&a.hdr->epoch);     // both round trips at once
+        const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sEpoch = e;
+        sTicket[0] = t;
         sLast = 0;
     }
     __syncthreads();
+    uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
+    const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
+
+    // Persistent: each workgroup loops over tiles, handed out in chain order by an atomic ticket (a
+    // tile only ever waits for tiles that a running workgroup already holds).  The next ticket is
+    // asked for at the top of a tile and has long arrived when it is needed.
+    for (int it = 0; ticket < a.total_tiles; ++it) {
+    // (opaque copies: anything computed from them is computed inside the loop and does not occupy
+    // registers across it)
+    int tid = tid_;
+    asm volatile("" : "+v"(tid));
+    const int lv = tid % LPR, seg = tid / LPR;
+    const int wave = tid >> 6, lane = tid & 63;
+    uint32_t ticket_ahead;   // (only thread 0's copy is ever set or read; no initialiser, so no
+                             // merge of values that would wait for the atomic right here)
+    if (tid == 0)
+        ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     BWD_STAMP(1);
-    const uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket);   // wave-uniform: index math stays scalar
     const int lb = ticket % a.nLB;
     const int rest = ticket / a.nLB;
     const int b = rest % a.B, ttr = rest / a.B;       // ttr: position in the chain (0 = last tile in time)
     const int tt = a.nT - 1 - ttr;
-    const uint32_t chain_stride = (uint32_t)a.B * a.nLB;
     const int j0 = lb * JB + lv * V;
     const bool active = j0 < a.J;
     const int t0 = tt * TILE_T + seg * NSTEP;
     const bool head = seg == 0;                       // owns the tile's adjoint aggregate and the chain
     const bool chained = ttr > 0;                     // has a predecessor in the chain
     const bool feeds = tt > 0;                        // has a successor in the chain
-    const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
-    const float *dtail_out = a.dstate_out ? a.dstate_out + (size_t)a.B * 2 * a.J : nullptr;
 
     // ---- upstream gradients of my tokens (registers), then the tile's input rows (LDS)
     float dzr[NSTEP][V], dzi[NSTEP][V];     // upstream dS, later overwritten by d(pre-activation)
     // a tile that lies wholly inside the tensors loads and stores without per-row checks
     const bool full = (tt + 1) * TILE_T <= a.L && (lb + 1) * JB <= a.J;
-    const uint32_t ost32 = (uint32_t)a.ost, ist32 = (uint32_t)a.ist;
     {
         const float *gre = a.dz_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
         const float *gim = a.dz_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
@@ -191,6 +208,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         sEb[seg][0][lv * V + v] = Ebr[v];
         sEb[seg][1][lv * V + v] = Ebi[v];
     }
+    if (tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
     lds_barrier_raw();     // the staged rows are still on their way
     BWD_STAMP(2);
     float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
@@ -228,7 +246,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     }
     // the staged rows have landed; so have the aggregate stores of the head group's wave
     wait_stores_done();
-    if (tid == 0 && chained && feeds) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, ST_AGG);
+    if (tid == 0 && chained && feeds) status_store(a.flags + (size_t)ticket * FLAG_STRIDE, epoch, ST_AGG);
     lds_barrier();
     BWD_STAMP(3);
 
@@ -421,7 +439,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
         if (chained) {
             if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
-                                         lv, hr, hi, qr, qi, a.spin_limit, cr, ci)) {
+                                         lv, hr, hi, qr, qi, a.spin_limit, epoch, cr, ci)) {
                 if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -462,7 +480,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     const bool fetch_halo = KC > 0 && HALO > 0 && head && chained;
     const uint32_t *halo_flag = a.flags + (size_t)(ticket - (chained ? chain_stride : 0u)) * FLAG_STRIDE;
     uint32_t halo_st = ST_NONE;
-    if (fetch_halo) halo_st = flag_load(halo_flag);
+    if (fetch_halo) halo_st = status_load(halo_flag, epoch);
 
     // ---- reverse pass: adjoint, returned gradients, parameter terms
     float acc_g[V], acc_t[V];
@@ -527,7 +545,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
         if (head && feeds) {   // the prefix stores were issued before the reverse pass
             wait_stores_done();
-            if (lv == 0) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, ST_PREFIX);
+            if (lv == 0) status_store(a.flags + (size_t)ticket * FLAG_STRIDE, epoch, ST_PREFIX);
         }
     } else {
         // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
@@ -563,7 +581,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
                 uint32_t spins = 0;
                 while (halo_st < ST_HALO && spins < a.spin_limit) {
                     __builtin_amdgcn_s_sleep(1);
-                    halo_st = flag_load(halo_flag);
+                    halo_st = status_load(halo_flag, epoch);
                     ++spins;
                 }
                 compiler_fence();
@@ -593,7 +611,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         // Every wave: nothing of the above is in flight any more (a no-op for the waves that took no
         // part).  Only then the status word: it covers the prefix and the halo rows.
         wait_vm<0>();
-        if (tid == 0 && feeds) flag_store(a.flags + (size_t)ticket * FLAG_STRIDE, HALO > 0 ? ST_HALO : ST_PREFIX);
+        if (tid == 0 && feeds) status_store(a.flags + (size_t)ticket * FLAG_STRIDE, epoch, HALO > 0 ? ST_HALO : ST_PREFIX);
         lds_barrier();
     BWD_STAMP(8);
         float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
@@ -732,37 +750,53 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
     }
 
-    // ---- bookkeeping: the tile that finishes last clears the control words
+    // ---- LDS is reused by the next tile
     lds_barrier();
     BWD_STAMP(10);
-    if (tid == 0) {
-        wait_stores_done();
+    ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
+    }
+
+    // ---- the workgroup that leaves last resets the ticket and advances the epoch for the next call.
+    //      Workgroups are counted, not tiles: every one of the grid has then drawn its last ticket.
+    if (tid_ == 0) {
         const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sLast = (old + 1 == a.total_tiles) ? 1u : 0u;
+        sLast = (old + 1 == gridDim.x) ? 1u : 0u;
     }
-    lds_barrier();
-    if (sLast) {
-        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + (size_t)i * FLAG_STRIDE, ST_NONE);
-        if (tid == 0) {
-            flag_store(&a.hdr->ticket[0], 0u);
-            flag_store(&a.hdr->done, 0u);
-        }
+    __syncthreads();
+    if (sLast) finish_call(a.hdr, a.flags, epoch, tid_, blockDim.x);
+}
+
+// Persistent grid: what fits on the chip at once (asked once per kernel), never more than tiles.
+template <int V, int KC, bool PARAM>
+static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
+{
+    static int per_cu = 0, cus = 0;
+    if (per_cu == 0) {
+        int dev = 0, n = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM>, Geom::NSEG * BwdLPR, 0) != hipSuccess)
+            return hipErrorUnknown;
+        cus = prop.multiProcessorCount;
+        per_cu = n > 0 ? n : 1;
     }
+    long long g = (long long)per_cu * cus;
+    if (g > (long long)a.total_tiles) g = a.total_tiles;
+    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM>), dim3((unsigned)g), dim3(Geom::NSEG * BwdLPR), 0, s, a);
+    return hipGetLastError();
 }
 
 template <int V, bool PARAM>
 static hipError_t launch_bwd_vp(const BwdArgs &a, int conv_k, hipStream_t s)
 {
-    dim3 grid(a.total_tiles), block(Geom::NSEG * BwdLPR);
     switch (conv_k) {
-    case 0: hipLaunchKernelGGL((bwd_kernel<V, 0, PARAM>), grid, block, 0, s, a); break;
-    case 1: hipLaunchKernelGGL((bwd_kernel<V, 1, PARAM>), grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL((bwd_kernel<V, 2, PARAM>), grid, block, 0, s, a); break;
-    case 3: hipLaunchKernelGGL((bwd_kernel<V, 3, PARAM>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((bwd_kernel<V, 4, PARAM>), grid, block, 0, s, a); break;
+    case 0: return launch_bwd_vkp<V, 0, PARAM>(a, s);
+    case 1: return launch_bwd_vkp<V, 1, PARAM>(a, s);
+    case 2: return launch_bwd_vkp<V, 2, PARAM>(a, s);
+    case 3: return launch_bwd_vkp<V, 3, PARAM>(a, s);
+    case 4: return launch_bwd_vkp<V, 4, PARAM>(a, s);
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s)

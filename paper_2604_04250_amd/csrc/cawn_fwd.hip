@@ -98,7 +98,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     __shared__ __attribute__((aligned(16))) float sU[SROWS][JB];   // [stream*NRT + rr][lane]
     __shared__ float sE[NSEG][2][JB];
     __shared__ float sCarry[2][JB];
-    __shared__ uint32_t sTicket[2], sLast;
+    __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid = threadIdx.x;
     const int lv = tid % LPR, seg = tid / LPR;
@@ -111,12 +111,15 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
 
     if (tid == 0) {
-        sTicket[0] = __hip_atomic_fetch_add(&a.hdr->ticket[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t e = flag_load(&a.hdr->epoch);     // both round trips at once
+        const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sEpoch = e;
+        sTicket[0] = t;
         sLast = 0;
     }
     __syncthreads();
     uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
-    uint32_t my_tiles = 0;
+    const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
 
     // Stage a tile's input rows in LDS.  The chain-owning wave stays out of it: a wave's memory
     // operations complete in order, and its polls of other tiles must not queue behind a tile's
@@ -160,11 +163,11 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         const int j0 = T.lb * JB + lv * V;
         const bool active = j0 < a.J;
         const int t0 = tt * TILE_T + seg * NSTEP;
-        ++my_tiles;
 
         // ticket of the next tile: asked for now, parked in LDS after the front-end (the round trip
         // of the atomic stays off the path to the barrier below)
-        uint32_t ticket_ahead = 0;
+        uint32_t ticket_ahead;   // (only thread 0's copy is ever set or read; no initialiser, so no
+                             // merge of values that would wait for the atomic right here)
         if (tid == 0)
             ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
@@ -369,7 +372,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                     own = a.flags + (size_t)id * FLAG_STRIDE;   // set once those stores are done, together with the first poll
                 }
                 if (!look_back<V, false, LPR>(a.flags, a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB,
-                                              lv * V, lv, hr, hi, qr, qi, a.spin_limit, cr, ci, own)) {
+                                              lv * V, lv, hr, hi, qr, qi, a.spin_limit, epoch, cr, ci, own)) {
                     // gave up: flag the workspace, keep going so that every wave exits
                     if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
@@ -453,7 +456,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 wait_vm<0>();
             }
         }
-        if (is_tail_seg && tt + 1 < a.nT && lv == 0) flag_store(a.flags + (size_t)id * FLAG_STRIDE, ST_PREFIX);
+        if (is_tail_seg && tt + 1 < a.nT && lv == 0) status_store(a.flags + (size_t)id * FLAG_STRIDE, epoch, ST_PREFIX);
         CAWN_STAMP(8);
 
         // ---- conv history for the next call: last HALO pre-conv rows (written by the last tile,
@@ -484,20 +487,14 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
         T = Tn;
     }
 
-    // ---- the workgroup that finishes last leaves the control words zeroed for the next call
-    if (my_tiles == 0) return;
-    __syncthreads();
+    // ---- the workgroup that leaves last resets the tickets and advances the epoch for the next call.
+    //      Workgroups are counted, not tiles: every one of the grid has then drawn its last ticket.
     if (tid == 0) {
-        wait_stores_done();
-        const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, my_tiles, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sLast = (old + my_tiles == a.total_tiles) ? 1u : 0u;
+        const uint32_t old = __hip_atomic_fetch_add(&a.hdr->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sLast = (old + 1 == gridDim.x) ? 1u : 0u;
     }
     __syncthreads();
-    if (sLast) {
-        for (uint32_t i = tid; i < a.total_tiles; i += blockDim.x) flag_store(a.flags + (size_t)i * FLAG_STRIDE, ST_NONE);
-        if (tid < MAX_QUEUES) flag_store(&a.hdr->ticket[tid], 0u);
-        if (tid == 0) flag_store(&a.hdr->done, 0u);
-    }
+    if (sLast) finish_call(a.hdr, a.flags, epoch, tid, blockDim.x);
 }
 
 template <int V, int KC>

@@ -64,15 +64,18 @@ enum LaneRow : int {
 inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k; }
 
 // ----------------------------------------------------------------------------------- workspace
-// Workspace: [header 256 B][tile status words, fixed MAX_TILES capacity][lane table][aggregates]
-// [prefixes][backward conv halo][backward parameter partials].  Header and status words are zero
-// between calls (the tile that finishes last clears them), whatever descriptor the last call had.
+// Workspace: [header 1 KiB][tile status words, fixed MAX_TILES capacity][lane table][aggregates]
+// [prefixes][backward conv halo][backward parameter partials].  A status word holds the epoch of
+// the call that wrote it next to the tile's state, so words left by earlier calls (whatever their
+// descriptor) read as "nothing published"; the workgroup that finishes last resets the tickets and
+// advances the epoch.  Nothing is cleared per tile.
 constexpr int MAX_QUEUES = 64;
 struct WsHeader {
     uint32_t ticket[MAX_QUEUES];   // per work queue: next tile to hand out
     uint32_t done;                 // tiles finished
     uint32_t error;                // sticky: a tile gave up waiting
-    uint32_t pad[256 - MAX_QUEUES - 2];
+    uint32_t epoch;                // calls completed on this workspace (mod 2^30): tags the status words
+    uint32_t pad[256 - MAX_QUEUES - 3];
 };
 static_assert(sizeof(WsHeader) == 1024, "header size");
 
@@ -81,8 +84,9 @@ struct WsLayout {
     size_t off_flags, off_table, off_agg, off_pre, off_halo, off_part, off_dbg, total;
 };
 
-// Tile status words of the decoupled look-back.
+// Tile states of the decoupled look-back (low two bits of a status word; the rest is the epoch).
 constexpr uint32_t ST_NONE = 0, ST_AGG = 1, ST_PREFIX = 2, ST_HALO = 3;
+constexpr uint32_t EPOCH_MOD = 1u << 30;
 
 // Gate as a union of two closed fp32 intervals on the quantity the decision is taken on (the
 // fp32 conv pre-activation, or the raw magnitude input when there is no conv).
@@ -278,6 +282,31 @@ __device__ __forceinline__ uint32_t flag_load(const uint32_t *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Tile status: state tagged with the call's epoch; a word from another epoch reads as ST_NONE.
+__device__ __forceinline__ void status_store(uint32_t *p, uint32_t epoch, uint32_t state)
+{
+    flag_store(p, (epoch << 2) | state);
+}
+__device__ __forceinline__ uint32_t status_load(const uint32_t *p, uint32_t epoch)
+{
+    const uint32_t w = flag_load(p);
+    return (w >> 2) == epoch ? (w & 3u) : ST_NONE;
+}
+// End of a call, run by thread `tid` of the `nthreads` of the workgroup that finished last: tickets
+// and the finished-tile count return to zero and the epoch advances.  When the epoch wraps, status
+// words of 2^30 calls ago would become current again: the whole zone is cleared then.
+__device__ __forceinline__ void finish_call(WsHeader *hdr, uint32_t *flags, uint32_t epoch, uint32_t tid,
+                                            uint32_t nthreads)
+{
+    const uint32_t next = (epoch + 1) % EPOCH_MOD;
+    if (next == 0)
+        for (uint32_t i = tid; i < MAX_TILES; i += nthreads) flag_store(flags + (size_t)i * FLAG_STRIDE, 0u);
+    if (tid < (uint32_t)MAX_QUEUES) flag_store(&hdr->ticket[tid], 0u);
+    if (tid == 0) {
+        flag_store(&hdr->done, 0u);
+        flag_store(&hdr->epoch, next);
+    }
+}
 __device__ __forceinline__ float coherent_load(const float *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -321,20 +350,6 @@ __device__ __forceinline__ void coherent_load_v(const float *p, float (&x)[V])
     }
 }
 
-// Wait (bounded) until a tile's status word is set; returns ST_NONE if it gave up.
-__device__ __forceinline__ uint32_t wait_flag(const uint32_t *p, uint32_t spin_limit)
-{
-    uint32_t st = flag_load(p);
-    uint32_t spins = 0;
-    while (st == ST_NONE && spins < spin_limit) {
-        __builtin_amdgcn_s_sleep(1);
-        st = flag_load(p);
-        ++spins;
-    }
-    compiler_fence();
-    return st;
-}
-
 // One link of a tile chain: P = T + M c, with M = lambda^TILE_T held as a double-float (h + q) and
 // conjugated for the adjoint chain.  Publication of a prefix and the look-back both go through
 // this one function, so every tile's prefix has the value a strictly sequential chain would give,
@@ -370,8 +385,8 @@ template <int V, bool CONJ, int LPR>
 __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *agg, const float *pre,
                                           uint32_t pred, uint32_t stride, int depth, int JB, int lo, int lv,
                                           const float (&hr)[V], const float (&hi)[V], const float (&qr)[V],
-                                          const float (&qi)[V], uint32_t spin_limit, float (&cr)[V],
-                                          float (&ci)[V], uint32_t *own_agg_flag = nullptr)
+                                          const float (&qi)[V], uint32_t spin_limit, uint32_t epoch,
+                                          float (&cr)[V], float (&ci)[V], uint32_t *own_agg_flag = nullptr)
 {
     // own_agg_flag: this tile's status word when its aggregate stores are still in flight; it is set
     // to ST_AGG once they have completed, which is waited for together with the first window.
@@ -383,10 +398,10 @@ __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *ag
     while (base < depth) {
         const int w = depth - base < LPR ? depth - base : LPR;
         uint32_t st = ST_AGG;
-        if (lv < w) st = flag_load(flags + (size_t)(pred - (uint32_t)(base + lv) * stride) * FLAG_STRIDE);
+        if (lv < w) st = status_load(flags + (size_t)(pred - (uint32_t)(base + lv) * stride) * FLAG_STRIDE, epoch);
         if (own_agg_flag) {
             wait_stores_done();
-            if (lv == 0) flag_store(own_agg_flag, ST_AGG);
+            if (lv == 0) status_store(own_agg_flag, epoch, ST_AGG);
             own_agg_flag = nullptr;
         }
         compiler_fence();
