@@ -28,7 +28,7 @@ static WsLayout make_layout(const cawn_desc *d)
     w.J = d->H * d->F;
     w.Jp = (int)align_up(w.J, 64);
     w.Jp128 = (int)align_up(w.J, 256);   // covers the widest lane block of any kernel variant
-    w.nT = (d->L + TILE_T - 1) / TILE_T;
+    w.nT = (d->L + CKPT_T - 1) / CKPT_T;      // backward tiles = checkpoint intervals (the finer of the two tilings)
     const int kc = d->conv_k > MAX_KC ? MAX_KC : d->conv_k;
     const size_t tiles_rows = (size_t)d->B * (w.nT > 0 ? w.nT : 1);
     size_t o = sizeof(WsHeader);
@@ -189,17 +189,30 @@ __global__ void lane_table_kernel(const float *__restrict__ gamma, const float *
         im = m * sin(n * th);
     };
     double tr, ti;
-    power(TILE_T, tr, ti);
-    const float hr = (float)tr, hi = (float)ti;
+    float hr, hi;
+    power(FwdGeom::TILE_T, tr, ti);
+    hr = (float)tr; hi = (float)ti;
     put(R_PT_HR, hr);
     put(R_PT_HI, hi);
     put(R_PT_LR, tr - (double)hr);
     put(R_PT_LI, ti - (double)hi);
-    for (int sgi = 0; sgi < Geom::NSEG; ++sgi) {
+    power(BwdGeom::TILE_T, tr, ti);
+    hr = (float)tr; hi = (float)ti;
+    put(R_PTB_HR, hr);
+    put(R_PTB_HI, hi);
+    put(R_PTB_LR, tr - (double)hr);
+    put(R_PTB_LI, ti - (double)hi);
+    for (int sgi = 0; sgi < FwdGeom::NSEG; ++sgi) {
         double re, im;
-        power(sgi * Geom::NSTEP, re, im);
+        power(sgi * FwdGeom::NSTEP, re, im);
         put(R_PSEG + 2 * sgi, re);
         put(R_PSEG + 2 * sgi + 1, im);
+    }
+    for (int sgi = 0; sgi < BwdGeom::NSEG; ++sgi) {
+        double re, im;
+        power(sgi * BwdGeom::NSTEP, re, im);
+        put(R_PSEGB + 2 * sgi, re);
+        put(R_PSEGB + 2 * sgi + 1, im);
     }
     put(R_BIAS_M, live && conv_b && conv_k > 0 ? (double)conv_b[j] : 0.0);
     put(R_BIAS_A, live && conv_b && conv_k > 0 ? (double)conv_b[(size_t)J + j] : 0.0);
@@ -339,11 +352,11 @@ size_t cawn_workspace_bytes(const cawn_desc *d)
 size_t cawn_ckpt_bytes(const cawn_desc *d)
 {
     if (!desc_ok(d)) return 0;
-    const size_t nT = (d->L + TILE_T - 1) / TILE_T;
+    const size_t nT = (d->L + CKPT_T - 1) / CKPT_T;
     return (size_t)d->B * nT * 2 * d->H * d->F * sizeof(float);
 }
 
-int32_t cawn_tile_len(void) { return TILE_T; }
+int32_t cawn_tile_len(void) { return CKPT_T; }
 
 const char *cawn_status_string(int st)
 {
@@ -458,7 +471,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
-    if (ist > (1ll << 24) || ost > (1ll << 24)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
+    if (ist > (1ll << 22) || ost > (1ll << 22)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     FwdArgs a{};
     if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;
@@ -468,7 +481,8 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
                      (!state_out || aligned(state_out, 16)) && (!ckpt || aligned(ckpt, 16));
     const int JB = (vec ? FwdV : 1) * FwdLPR;
     const int nLB = (int)((J + JB - 1) / JB);
-    const size_t tiles = (size_t)d->B * w.nT * nLB;
+    const int nTf = (d->L + FwdGeom::TILE_T - 1) / FwdGeom::TILE_T;
+    const size_t tiles = (size_t)d->B * nTf * nLB;
     if (tiles > MAX_TILES) return CAWN_EUNSUPPORTED;
 
     char *ws = reinterpret_cast<char *>(workspace);
@@ -486,7 +500,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     a.flags = reinterpret_cast<uint32_t *>(ws + w.off_flags);
     a.agg = reinterpret_cast<float *>(ws + w.off_agg);
     a.pre = reinterpret_cast<float *>(ws + w.off_pre);
-    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
+    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = nTf; a.nTc = w.nT; a.nLB = nLB;
     a.amp_mode = d->amp_mode;
     a.small_angle = (d->conv_k > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;   // |angle| <= SiLU(clamp) <= 41 revolutions
     a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&
@@ -541,7 +555,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
-    if (ist > (1ll << 24) || ost > (1ll << 24)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
+    if (ist > (1ll << 22) || ost > (1ll << 22)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     BwdArgs a{};
     if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;

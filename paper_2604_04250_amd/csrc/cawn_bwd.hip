@@ -48,9 +48,9 @@ template <> struct BVec<2> {
 };
 
 template <int V, int KC, bool PARAM>
-__global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
+__global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
-    constexpr int NSTEP = Geom::NSTEP, NSEG = Geom::NSEG, LPR = BwdLPR;
+    constexpr int TILE_T = BwdGeom::TILE_T, NSTEP = BwdGeom::NSTEP, NSEG = BwdGeom::NSEG, LPR = BwdLPR;
     constexpr int JB = V * LPR;
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
     constexpr int HALO1 = HALO > 0 ? HALO : 1;
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         const float *tb = a.table + j0;
         BVec<V>::ld(lr, tb + (size_t)R_LR * a.Jp);
         BVec<V>::ld(li, tb + (size_t)R_LI * a.Jp);
-        BVec<V>::ld(pnr, tb + (size_t)(R_PSEG + 2) * a.Jp);                       // lambda^NSTEP
-        BVec<V>::ld(pni, tb + (size_t)(R_PSEG + 3) * a.Jp);
+        BVec<V>::ld(pnr, tb + (size_t)(R_PSEGB + 2) * a.Jp);                       // lambda^NSTEP
+        BVec<V>::ld(pni, tb + (size_t)(R_PSEGB + 3) * a.Jp);
         if (KC > 0) {
             BVec<V>::ld(bm, tb + (size_t)R_BIAS_M * a.Jp);
             BVec<V>::ld(ba, tb + (size_t)R_BIAS_A * a.Jp);
@@ -170,10 +170,10 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     // ---- the tile's input rows go to LDS (needed from the front-end on; issued after the loads the
     //      local adjoint waits for, so that it does not wait for these as well)
     if (a.stage16)
-        stage_rows<JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
+        stage_rows<TILE_T, JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
                                  NW, lane);
     else
-        stage_rows<JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
+        stage_rows<TILE_T, JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
                                 NW, lane);
 
     // gradient of the carried state joins the last token
@@ -265,8 +265,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
     for (int v = 0; v < V; ++v) { psi[v] = sth[v] = gam[v] = 0.f; psr[v] = cth[v] = 1.f; }
     if (active) {
         const float *tb = a.table + j0;
-        BVec<V>::ld(psr, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
-        BVec<V>::ld(psi, tb + (size_t)(R_PSEG + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
+        BVec<V>::ld(psr, tb + (size_t)(R_PSEGB + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
+        BVec<V>::ld(psi, tb + (size_t)(R_PSEGB + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
         if (PARAM) {
             BVec<V>::ld(cth, tb + (size_t)R_COS * a.Jp);
             BVec<V>::ld(sth, tb + (size_t)R_SIN * a.Jp);
@@ -378,8 +378,8 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
 #pragma unroll
         for (int v = 0; v < V; ++v) { Fr[v] = Fi[v] = pfi[v] = 0.f; pfr[v] = 1.f; }
         if (active) {
-            BVec<V>::ld(pfr, a.table + j0 + (size_t)(R_PSEG + 2 * seg) * a.Jp);
-            BVec<V>::ld(pfi, a.table + j0 + (size_t)(R_PSEG + 2 * seg + 1) * a.Jp);
+            BVec<V>::ld(pfr, a.table + j0 + (size_t)(R_PSEGB + 2 * seg) * a.Jp);
+            BVec<V>::ld(pfi, a.table + j0 + (size_t)(R_PSEGB + 2 * seg + 1) * a.Jp);
         }
         for (int qq = 0; qq < seg; ++qq) {
 #pragma unroll
@@ -432,10 +432,10 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         }
         if (active) {   // lambda^TILE_T as a double-float
             const float *tb = a.table + j0;
-            BVec<V>::ld(hr, tb + (size_t)R_PT_HR * a.Jp);
-            BVec<V>::ld(hi, tb + (size_t)R_PT_HI * a.Jp);
-            BVec<V>::ld(qr, tb + (size_t)R_PT_LR * a.Jp);
-            BVec<V>::ld(qi, tb + (size_t)R_PT_LI * a.Jp);
+            BVec<V>::ld(hr, tb + (size_t)R_PTB_HR * a.Jp);
+            BVec<V>::ld(hi, tb + (size_t)R_PTB_HI * a.Jp);
+            BVec<V>::ld(qr, tb + (size_t)R_PTB_LR * a.Jp);
+            BVec<V>::ld(qi, tb + (size_t)R_PTB_LI * a.Jp);
         }
         if (chained) {
             if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
@@ -665,7 +665,7 @@ __global__ __launch_bounds__(Geom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel
         // the output stores (where it would drain them); the stores themselves stay in flight.
         if (full && !dtail_out) {
             conv_t(std::true_type{});
-            wait_vm<2 * NSTEP>();
+            wait_vm<(2 * NSTEP < 63 ? 2 * NSTEP : 63)>();
         } else {
             conv_t(std::false_type{});
             wait_vm<0>();
@@ -775,14 +775,14 @@ static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM>, Geom::NSEG * BwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
     }
     long long g = (long long)per_cu * cus;
     if (g > (long long)a.total_tiles) g = a.total_tiles;
-    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM>), dim3((unsigned)g), dim3(Geom::NSEG * BwdLPR), 0, s, a);
+    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
     return hipGetLastError();
 }
 

@@ -82,9 +82,9 @@ __device__ __forceinline__ TileId decode_tile(uint32_t ticket, int q, int nQ, in
 }
 
 template <int V, int KC>
-__global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
+__global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
-    constexpr int NSTEP = Geom::NSTEP, NSEG = Geom::NSEG, LPR = FwdLPR;
+    constexpr int TILE_T = FwdGeom::TILE_T, NSTEP = FwdGeom::NSTEP, NSEG = FwdGeom::NSEG, LPR = FwdLPR;
     constexpr int JB = V * LPR;
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
     constexpr int KC1 = KC > 0 ? KC : 1;
@@ -128,10 +128,10 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
     auto stage_tile = [&](const TileId &T) {
         if (owner_wave) return;
         if (a.stage16)
-            stage_rows<JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
+            stage_rows<TILE_T, JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
                                      ist32, wave, NW - 1, lane);
         else
-            stage_rows<JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
+            stage_rows<TILE_T, JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
                                     ist32, wave, NW - 1, lane);
     };
 
@@ -383,11 +383,6 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
                 sCarry[0][lv * V + v] = cr[v];
                 sCarry[1][lv * V + v] = ci[v];
             }
-            if (a.ckpt && active) {
-                float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
-                Vec<V>::st(ck, cr);
-                Vec<V>::st(ck + a.J, ci);
-            }
             if (tt + 1 < a.nT) {   // the tile's inclusive prefix for the chain
                 float P_r[V], P_i[V];
 #pragma unroll
@@ -407,6 +402,13 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
             Sr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(-psi[v], ci, Xr[v]));
             Si[v] = __builtin_fmaf(psi[v], cr, __builtin_fmaf(psr[v], ci, Xi[v]));
+        }
+
+        // ---- checkpoints for the backward pass: the state before every CKPT_T-th token
+        if (a.ckpt && (seg * NSTEP) % CKPT_T == 0 && active && t0 < a.L) {
+            float *ck = a.ckpt + (((size_t)b * a.nTc + t0 / CKPT_T) * 2) * a.J + j0;
+            Vec<V>::st(ck, Sr);
+            Vec<V>::st(ck + a.J, Si);
         }
 
         // ---- replay from the true state, clamp, store.  Addresses are a wave-uniform base plus a
@@ -450,7 +452,7 @@ __global__ __launch_bounds__(Geom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel
             // youngest operations when no row needed a check) are left in flight.
             if (plain) {
                 replay(std::true_type{});
-                wait_vm<2 * NSTEP>();
+                wait_vm<(2 * NSTEP < 63 ? 2 * NSTEP : 63)>();
             } else {
                 replay(std::false_type{});
                 wait_vm<0>();
@@ -506,7 +508,7 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC>, Geom::NSEG * FwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
@@ -522,7 +524,7 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     // skew so that the ~wq/B workgroups working on one chain spread over one iteration (~10 us)
     const long long per_chain = wq / a.B > 0 ? wq / a.B : 1;
     a.stagger_ticks = per_chain > 1 ? (int)(CAWN_FWD_ITER_TICKS / per_chain) : 0;
-    dim3 grid((unsigned)(wq * a.nQ)), block(Geom::NSEG * FwdLPR);
+    dim3 grid((unsigned)(wq * a.nQ)), block(FwdGeom::NSEG * FwdLPR);
     hipLaunchKernelGGL((fwd_kernel<V, KC>), grid, block, 0, s, a);
     return hipGetLastError();
 }

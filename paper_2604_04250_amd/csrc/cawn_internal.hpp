@@ -8,19 +8,32 @@
 namespace cawn {
 
 // ------------------------------------------------------------------------------------ geometry
-// One tile = JB lanes x TILE_T tokens of one batch row, owned by one workgroup.  A thread owns
-// V adjacent lanes and NSTEP consecutive tokens ("segment"); NSEG segments make the tile.
-#ifndef CAWN_TILE_T
-#define CAWN_TILE_T 64
+// One tile = JB lanes x TILE_T tokens of one batch row, processed by one workgroup at a time.  A
+// thread owns V adjacent lanes and NSTEP consecutive tokens ("segment"); NSEG segments make the
+// tile.  The two kernels pick their own shape:
+//   forward : long tiles.  Its tiles of one chain are joined by memory round trips, so the fewer
+//             tiles a chain has the better; it keeps only 2 values per token-lane in registers,
+//             which allows 32 tokens per thread.
+//   backward: keeps ~10 values per token-lane, hence 8 tokens per thread and one lane per thread
+//             (4 waves per SIMD).
+// Checkpoints of the scan state are kept every CKPT_T tokens = one backward tile.
+#ifndef CAWN_FWD_TILE_T
+#define CAWN_FWD_TILE_T 256
 #endif
-#ifndef CAWN_NSTEP
-#define CAWN_NSTEP 8
+#ifndef CAWN_FWD_NSTEP
+#define CAWN_FWD_NSTEP 32
 #endif
 #ifndef CAWN_FWD_V
-#define CAWN_FWD_V 4
+#define CAWN_FWD_V 1
 #endif
 #ifndef CAWN_FWD_LPR
 #define CAWN_FWD_LPR 32
+#endif
+#ifndef CAWN_BWD_TILE_T
+#define CAWN_BWD_TILE_T 64
+#endif
+#ifndef CAWN_BWD_NSTEP
+#define CAWN_BWD_NSTEP 8
 #endif
 #ifndef CAWN_BWD_V
 #define CAWN_BWD_V 1
@@ -32,16 +45,19 @@ namespace cawn {
 #define CAWN_FWD_WAVES 2      // waves per SIMD the forward kernel's register budget is set for
 #endif
 #ifndef CAWN_BWD_WAVES
-#define CAWN_BWD_WAVES 3
+#define CAWN_BWD_WAVES 4
 #endif
-constexpr int TILE_T = CAWN_TILE_T;  // tokens per tile: granularity of carries and checkpoints
-
-struct Geom {
-    static constexpr int NSTEP = CAWN_NSTEP, NSEG = TILE_T / NSTEP;
+struct FwdGeom {
+    static constexpr int TILE_T = CAWN_FWD_TILE_T, NSTEP = CAWN_FWD_NSTEP, NSEG = TILE_T / NSTEP;
 };
-constexpr int FwdV = CAWN_FWD_V, FwdLPR = CAWN_FWD_LPR;  // forward: lanes per thread, threads per row
-constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;  // backward: it keeps ~10 values per token-lane,
-                                                         // so one lane per thread buys a third wave per SIMD
+struct BwdGeom {
+    static constexpr int TILE_T = CAWN_BWD_TILE_T, NSTEP = CAWN_BWD_NSTEP, NSEG = TILE_T / NSTEP;
+};
+constexpr int CKPT_T = BwdGeom::TILE_T;
+static_assert(FwdGeom::TILE_T % CKPT_T == 0, "a forward tile spans whole checkpoint intervals");
+static_assert(CKPT_T % FwdGeom::NSTEP == 0, "checkpoints fall on forward segment boundaries");
+constexpr int FwdV = CAWN_FWD_V, FwdLPR = CAWN_FWD_LPR;  // lanes per thread, threads per row
+constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;
 constexpr int MAX_KC = 4;
 #ifndef CAWN_FLAG_STRIDE
 #define CAWN_FLAG_STRIDE 16
@@ -55,11 +71,14 @@ constexpr int FLAG_STRIDE = CAWN_FLAG_STRIDE;   // words between status words (s
 enum LaneRow : int {
     R_LR = 0, R_LI,            // lambda = gamma e^{i theta}
     R_COS, R_SIN, R_GAMMA,     // e^{i theta}, gamma
-    R_PT_HR, R_PT_HI,          // lambda^TILE_T, leading fp32 part
-    R_PT_LR, R_PT_LI,          //                 remainder (double-float)
+    R_PT_HR, R_PT_HI,          // lambda^(forward TILE_T), leading fp32 part
+    R_PT_LR, R_PT_LI,          //                          remainder (double-float)
+    R_PTB_HR, R_PTB_HI,        // the same for the backward tile length
+    R_PTB_LR, R_PTB_LI,
     R_BIAS_M, R_BIAS_A,
-    R_PSEG,                    // R_PSEG + 2*s (+1): re (im) of lambda^(NSTEP*s), s = 0..NSEG-1
-    R_W0 = R_PSEG + 2 * Geom::NSEG   // R_W0 + s*conv_k + i : tap i of stream s
+    R_PSEG,                    // R_PSEG + 2*s (+1): re (im) of lambda^(NSTEP*s), forward segments
+    R_PSEGB = R_PSEG + 2 * FwdGeom::NSEG,   // the same for the backward segments
+    R_W0 = R_PSEGB + 2 * BwdGeom::NSEG      // R_W0 + s*conv_k + i : tap i of stream s
 };
 inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k; }
 
@@ -103,7 +122,8 @@ struct FwdArgs {
     WsHeader *hdr;
     uint32_t *flags;
     float *agg, *pre;
-    int B, L, J, Jp, nT, nLB;
+    int B, L, J, Jp, nT, nLB;    // nT: forward tiles per sequence
+    int nTc;                     // checkpoint intervals per sequence
     int nQ;                      // work queues (a queue owns lane blocks q, q+nQ, ...)
     int stagger_ticks;           // start-up skew per time tile, in 10 ns ticks (see fwd kernel)
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
@@ -234,18 +254,18 @@ __device__ __forceinline__ void lds_barrier_raw()
 }
 
 // Stage the pre-conv input rows of one tile in LDS with direct global->LDS loads (no registers):
-// rows tile_t0-HALO .. tile_t0+TILE_T-1 of the magnitude stream, then the same rows of the angle
+// rows tile_t0-HALO .. tile_t0+TT-1 of the magnitude stream, then the same rows of the angle
 // stream, JB lanes each, row-major.  Called by `nwaves` waves (index `wave` among them).  Rows
 // outside [0, L) and lanes beyond J read a clamped (valid) address: their values never reach a
 // result (the scan is causal, a lane only reads its own LDS column; rows before a sequence start
 // are zeroed at the point of use).  Rows before the call's first token come from the carried conv
 // history when there is one.  LB: bytes per lane per load (16 needs 16-byte aligned rows).
-template <int JB, int HALO, int LB>
+template <int TT, int JB, int HALO, int LB>
 __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const float *ang, const float *tail_in,
                                            int b, int tile_t0, int lb, int J, int L, long long isb, int ist,
                                            int wave, int nwaves, int lane)
 {
-    constexpr int NRT = TILE_T + HALO;
+    constexpr int NRT = TT + HALO;
     constexpr int LR = JB * 4 / LB;                // lanes per row
     if constexpr (LR <= 64) {
         constexpr int RPI = 64 / LR;               // rows per wave instruction
