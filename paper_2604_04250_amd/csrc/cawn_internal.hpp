@@ -30,7 +30,7 @@ namespace cawn {
 #define CAWN_FWD_LPR 32
 #endif
 #ifndef CAWN_BWD_TILE_T
-#define CAWN_BWD_TILE_T 64
+#define CAWN_BWD_TILE_T 128
 #endif
 #ifndef CAWN_BWD_NSTEP
 #define CAWN_BWD_NSTEP 8

@@ -77,7 +77,7 @@ def test_cfg1_tiny_fused_and_plain():
     _check(wl.B, wl.L, wl.H, wl.F, wl.conv_k, d, tau=wl.gate_tau, with_state=True)
 
 
-@pytest.mark.parametrize("L", [1, 2, 3, 7, 8, 9, 63, 64, 65, 130, 517])
+@pytest.mark.parametrize("L", [1, 2, 3, 7, 8, 9, 63, 64, 65, 127, 128, 129, 257, 517, 1030])
 @pytest.mark.parametrize("Kc", [0, 4])
 def test_ragged_lengths_span_tiles(L, Kc):
     B, H, F = 2, 2, 16

@@ -69,7 +69,7 @@ def test_cfg1_tiny_fused_and_plain():
     assert abs((1 - ora["gate"].mean()) - 0.0797) < 0.02     # P(|N(0,1)| < 0.1)
 
 
-@pytest.mark.parametrize("L", [1, 2, 3, 7, 8, 9, 63, 64, 65, 127, 128, 200, 517])
+@pytest.mark.parametrize("L", [1, 2, 3, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 128, 200, 255, 256, 257, 517, 1030])
 @pytest.mark.parametrize("Kc", [0, 4])
 def test_ragged_lengths_span_tiles(L, Kc):
     B, H, F = 2, 2, 16
@@ -139,11 +139,11 @@ def test_zero_length_call_passes_state_through():
 
 def test_concat_output_layout_and_checkpoints():
     G = _gpu()
-    B, L, H, F, Kc = 2, 200, 2, 32, 4
+    B, L, H, F, Kc = 2, 600, 2, 32, 4
     d = _inputs(B, L, H, F, Kc, 700)
     out, ora = _check(B, L, H, F, Kc, d, concat=True, want_ckpt=True)
-    # checkpoints = unclamped state entering each 64-token tile
-    T = 64
+    # checkpoints = unclamped state entering each checkpoint interval
+    T = G.K.cawn_tile_len()
     nT = (L + T - 1) // T
     ck = out["ckpt"].reshape(B, nT, 2, H * F)
     for i in range(nT):
