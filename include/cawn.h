@@ -57,7 +57,7 @@ typedef struct cawn_desc {
     int32_t reserved_;
     int64_t in_stride_b, in_stride_t;   /* element strides of mag/ang/dmag/dang; 0 = dense
                                            (t stride J, b stride L*J); lane stride is always 1;
-                                           t strides above 2^22 elements: CAWN_EUNSUPPORTED     */
+                                           t strides above 2^21 elements: CAWN_EUNSUPPORTED     */
     int64_t out_stride_b, out_stride_t; /* element strides of z_re/z_im/dz_re/dz_im; 0 = dense  */
 } cawn_desc;
 

@@ -471,7 +471,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
-    if (ist > (1ll << 22) || ost > (1ll << 22)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
+    if (ist > (1ll << 21) || ost > (1ll << 21)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     FwdArgs a{};
     if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;
@@ -555,7 +555,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
-    if (ist > (1ll << 22) || ost > (1ll << 22)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
+    if (ist > (1ll << 21) || ost > (1ll << 21)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     BwdArgs a{};
     if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;

@@ -47,6 +47,19 @@ template <> struct BVec<2> {
     }
 };
 
+// Access at a wave-uniform base plus a 32-bit per-lane byte offset: the addressing mode that costs no
+// vector ALU work (scalar base register + 32-bit offset register).
+template <int V>
+__device__ __forceinline__ void ldu(float (&d)[V], const float *ubase, uint32_t boff)
+{
+    BVec<V>::ld(d, reinterpret_cast<const float *>(reinterpret_cast<const char *>(ubase) + boff));
+}
+template <int V>
+__device__ __forceinline__ void stu(float *ubase, uint32_t boff, const float (&x)[V])
+{
+    BVec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(ubase) + boff), x);
+}
+
 template <int V, int KC, bool PARAM>
 __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
@@ -57,13 +70,12 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     constexpr int KC1 = KC > 0 ? KC : 1;
     constexpr int ROWS = 4 + 2 * KC;
     constexpr int NT = NSEG * LPR, NW = NT / 64;
-    constexpr int NRT = TILE_T + HALO;             // staged rows per stream: time tile_t0-HALO+rr
-    constexpr int SROWS = ((2 * NRT + 3) / 4) * 4 + 4;
+    constexpr int NRTP = staged_rows<TILE_T, JB, HALO>();   // staged rows per stream: time tile_t0-HALO+rr
     static_assert(HALO <= NSTEP, "conv halo must fit in one segment");
     static_assert(LPR == 32, "the partial-sum reduction pairs the two segments of a wave");
     static_assert(JB <= 64 && 64 % JB == 0, "a staged row must fit a wave");
 
-    __shared__ __attribute__((aligned(16))) float sU[SROWS][JB];   // [stream*NRT + rr][lane]
+    __shared__ __attribute__((aligned(16))) float sU[2 * NRTP][JB];   // [stream*NRTP + rr][lane]
     __shared__ float sEb[NSEG][2][JB];
     __shared__ float sEf[PARAM ? NSEG : 1][2][JB];
     __shared__ float sCarry[2][JB];
@@ -96,7 +108,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     int tid = tid_;
     asm volatile("" : "+v"(tid));
     const int lv = tid % LPR, seg = tid / LPR;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // (wave index: scalar)
+    const float *table = a.table;      // (the same for the lane table's base and row pitch: the ~30 row
+    int Jp = a.Jp;                     // addresses are then formed per tile instead of living in scalar
+    asm volatile("" : "+s"(table), "+s"(Jp));   // registers across the loop, which spilled)
     uint32_t ticket_ahead;   // (only thread 0's copy is ever set or read; no initialiser, so no
                              // merge of values that would wait for the atomic right here)
     if (tid == 0)
@@ -108,6 +123,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     const int tt = a.nT - 1 - ttr;
     const int j0 = lb * JB + lv * V;
     const bool active = j0 < a.J;
+    // Lane constants are read unconditionally; lanes beyond J read lane 0's (their results are never
+    // stored, and no value crosses lanes).
+    const uint32_t jb = (uint32_t)(active ? j0 : 0) * 4u;
+    auto row = [&](int r) { return table + (size_t)r * Jp; };
     const int t0 = tt * TILE_T + seg * NSTEP;
     const bool head = seg == 0;                       // owns the tile's adjoint aggregate and the chain
     const bool chained = ttr > 0;                     // has a predecessor in the chain
@@ -120,13 +139,13 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     {
         const float *gre = a.dz_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
         const float *gim = a.dz_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
-        uint32_t off = (uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V);
+        uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * 4u;      // bytes
         if (full) {
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
-                BVec<V>::ld(dzr[i], gre + off);
-                BVec<V>::ld(dzi[i], gim + off);
-                off += ost32;
+                ldu<V>(dzr[i], gre, off);
+                ldu<V>(dzi[i], gim, off);
+                off += ost32 * 4u;
             }
         } else {
 #pragma unroll
@@ -134,36 +153,33 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
                 for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
                 if (active && t0 + i < a.L) {
-                    BVec<V>::ld(dzr[i], gre + off);
-                    BVec<V>::ld(dzi[i], gim + off);
+                    ldu<V>(dzr[i], gre, off);
+                    ldu<V>(dzi[i], gim, off);
                 }
-                off += ost32;
+                off += ost32 * 4u;
             }
         }
     }
     // ---- lane constants
     float lr[V], li[V], pnr[V], pni[V];
     float wmf[KC1][V], waf[KC1][V], bm[V], ba[V];   // taps for the front-end
+    ldu<V>(lr, row(R_LR), jb);
+    ldu<V>(li, row(R_LI), jb);
+    ldu<V>(pnr, row(R_PSEGB + 2), jb);                       // lambda^NSTEP
+    ldu<V>(pni, row(R_PSEGB + 3), jb);
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        lr[v] = li[v] = pnr[v] = pni[v] = bm[v] = ba[v] = 0.f;
+        bm[v] = ba[v] = 0.f;
 #pragma unroll
         for (int k = 0; k < KC1; ++k) wmf[k][v] = waf[k][v] = 0.f;
     }
-    if (active) {
-        const float *tb = a.table + j0;
-        BVec<V>::ld(lr, tb + (size_t)R_LR * a.Jp);
-        BVec<V>::ld(li, tb + (size_t)R_LI * a.Jp);
-        BVec<V>::ld(pnr, tb + (size_t)(R_PSEGB + 2) * a.Jp);                       // lambda^NSTEP
-        BVec<V>::ld(pni, tb + (size_t)(R_PSEGB + 3) * a.Jp);
-        if (KC > 0) {
-            BVec<V>::ld(bm, tb + (size_t)R_BIAS_M * a.Jp);
-            BVec<V>::ld(ba, tb + (size_t)R_BIAS_A * a.Jp);
+    if (KC > 0) {
+        ldu<V>(bm, row(R_BIAS_M), jb);
+        ldu<V>(ba, row(R_BIAS_A), jb);
 #pragma unroll
-            for (int k = 0; k < KC; ++k) {
-                BVec<V>::ld(wmf[k], tb + (size_t)(R_W0 + k) * a.Jp);
-                BVec<V>::ld(waf[k], tb + (size_t)(R_W0 + KC + k) * a.Jp);
-            }
+        for (int k = 0; k < KC; ++k) {
+            ldu<V>(wmf[k], row(R_W0 + k), jb);
+            ldu<V>(waf[k], row(R_W0 + KC + k), jb);
         }
     }
 
@@ -262,16 +278,13 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     }
     float psr[V], psi[V], cth[V], sth[V], gam[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) { psi[v] = sth[v] = gam[v] = 0.f; psr[v] = cth[v] = 1.f; }
-    if (active) {
-        const float *tb = a.table + j0;
-        BVec<V>::ld(psr, tb + (size_t)(R_PSEGB + 2 * (NSEG - 1 - seg)) * a.Jp);    // adjoint: segments after mine
-        BVec<V>::ld(psi, tb + (size_t)(R_PSEGB + 2 * (NSEG - 1 - seg) + 1) * a.Jp);
-        if (PARAM) {
-            BVec<V>::ld(cth, tb + (size_t)R_COS * a.Jp);
-            BVec<V>::ld(sth, tb + (size_t)R_SIN * a.Jp);
-            BVec<V>::ld(gam, tb + (size_t)R_GAMMA * a.Jp);
-        }
+    for (int v = 0; v < V; ++v) { sth[v] = gam[v] = 0.f; cth[v] = 1.f; }
+    ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);    // adjoint: segments after mine
+    ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
+    if (PARAM) {
+        ldu<V>(cth, row(R_COS), jb);
+        ldu<V>(sth, row(R_SIN), jb);
+        ldu<V>(gam, row(R_GAMMA), jb);
     }
 
     // ---- front-end recompute, rows from LDS as a sliding window
@@ -290,7 +303,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
-                wna[k % KC1][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
+                wna[k % KC1][v] = zero_hist ? 0.f : sU[NRTP + seg * NSTEP + k][lv * V + v];
             }
         }
 #pragma unroll
@@ -300,7 +313,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
-                wna[(i + HALO) % KC1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
+                wna[(i + HALO) % KC1][v] = sU[NRTP + seg * NSTEP + i + HALO][lv * V + v];
             }
 #pragma unroll
             for (int v = 0; v < V; ++v) {
@@ -376,11 +389,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     BWD_STAMP(4);
         float Fr[V], Fi[V], pfr[V], pfi[V];   // lambda^(NSTEP*seg): the segments before mine
 #pragma unroll
-        for (int v = 0; v < V; ++v) { Fr[v] = Fi[v] = pfi[v] = 0.f; pfr[v] = 1.f; }
-        if (active) {
-            BVec<V>::ld(pfr, a.table + j0 + (size_t)(R_PSEGB + 2 * seg) * a.Jp);
-            BVec<V>::ld(pfi, a.table + j0 + (size_t)(R_PSEGB + 2 * seg + 1) * a.Jp);
-        }
+        for (int v = 0; v < V; ++v) Fr[v] = Fi[v] = 0.f;
+        ldu<V>(pfr, row(R_PSEGB + 2 * seg), jb);
+        ldu<V>(pfi, row(R_PSEGB + 2 * seg + 1), jb);
         for (int qq = 0; qq < seg; ++qq) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
@@ -430,13 +441,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             Tr[v] = sCarry[0][lv * V + v];
             Ti[v] = sCarry[1][lv * V + v];
         }
-        if (active) {   // lambda^TILE_T as a double-float
-            const float *tb = a.table + j0;
-            BVec<V>::ld(hr, tb + (size_t)R_PTB_HR * a.Jp);
-            BVec<V>::ld(hi, tb + (size_t)R_PTB_HI * a.Jp);
-            BVec<V>::ld(qr, tb + (size_t)R_PTB_LR * a.Jp);
-            BVec<V>::ld(qi, tb + (size_t)R_PTB_LI * a.Jp);
-        }
+        ldu<V>(hr, row(R_PTB_HR), jb);      // lambda^TILE_T as a double-float
+        ldu<V>(hi, row(R_PTB_HI), jb);
+        ldu<V>(qr, row(R_PTB_LR), jb);
+        ldu<V>(qi, row(R_PTB_LI), jb);
         if (chained) {
             if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
                                          lv, hr, hi, qr, qi, a.spin_limit, epoch, cr, ci)) {
@@ -524,23 +532,23 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 
     float *omag = a.dmag + (size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB;
     float *oang = a.dang + (size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB;
-    uint32_t ooff = (uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V);
+    uint32_t ooff = ((uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V)) * 4u;      // bytes
     if (KC == 0) {
         if (full) {
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
-                BVec<V>::st(omag + ooff, dzr[i]);
-                BVec<V>::st(oang + ooff, dzi[i]);
-                ooff += ist32;
+                stu<V>(omag, ooff, dzr[i]);
+                stu<V>(oang, ooff, dzi[i]);
+                ooff += ist32 * 4u;
             }
         } else {
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
                 if (active && t0 + i < a.L) {
-                    BVec<V>::st(omag + ooff, dzr[i]);
-                    BVec<V>::st(oang + ooff, dzi[i]);
+                    stu<V>(omag, ooff, dzr[i]);
+                    stu<V>(oang, ooff, dzi[i]);
                 }
-                ooff += ist32;
+                ooff += ist32 * 4u;
             }
         }
         if (head && feeds) {   // the prefix stores were issued before the reverse pass
@@ -643,8 +651,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     da[v] = sa_;
                 }
                 if (PLAIN) {
-                    BVec<V>::st(omag + ooff, dm);
-                    BVec<V>::st(oang + ooff, da);
+                    stu<V>(omag, ooff, dm);
+                    stu<V>(oang, ooff, da);
                 } else if (active && t < a.L) {
                     if (HALO > 0 && dtail_out && t >= a.L - HALO) {   // state_out's history rows are copies of these inputs
                         const int r = t - (a.L - HALO);
@@ -655,10 +663,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
                         for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
                     }
-                    BVec<V>::st(omag + ooff, dm);
-                    BVec<V>::st(oang + ooff, da);
+                    stu<V>(omag, ooff, dm);
+                    stu<V>(oang, ooff, da);
                 }
-                ooff += ist32;
+                ooff += ist32 * 4u;
             }
         };
         // Both paths end with every load complete, so that no wait for one of them can land behind
@@ -725,7 +733,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     for (int k = 0; k < KC; ++k) {
                         const bool z = zero_hist && (i + k < HALO);
                         const float um_ = z ? 0.f : sU[seg * NSTEP + i + k][lv * V + v];
-                        const float ua_ = z ? 0.f : sU[NRT + seg * NSTEP + i + k][lv * V + v];
+                        const float ua_ = z ? 0.f : sU[NRTP + seg * NSTEP + i + k][lv * V + v];
                         part[4 + k][v] = __builtin_fmaf(dzr[i][v], um_, part[4 + k][v]);
                         part[4 + KC + k][v] = __builtin_fmaf(dzi[i][v], ua_, part[4 + KC + k][v]);
                     }

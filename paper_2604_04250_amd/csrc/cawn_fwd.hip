@@ -90,19 +90,18 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     constexpr int KC1 = KC > 0 ? KC : 1;
     constexpr int NT = NSEG * LPR;                 // threads
     constexpr int NW = NT / 64;                    // waves
-    constexpr int NRT = TILE_T + HALO;             // staged rows per stream: time tile_t0-HALO+rr
-    constexpr int SROWS = ((2 * NRT + 3) / 4) * 4 + 4;   // staged rows, padded for the widest load
+    constexpr int NRTP = staged_rows<TILE_T, JB, HALO>();   // staged rows per stream: time tile_t0-HALO+rr
     static_assert(JB <= 256 && 256 % JB == 0, "a staged row must fit a wave");
     static_assert(NW >= 2, "one wave owns the chain, the others stage the next tile");
 
-    __shared__ __attribute__((aligned(16))) float sU[SROWS][JB];   // [stream*NRT + rr][lane]
+    __shared__ __attribute__((aligned(16))) float sU[2 * NRTP][JB];   // [stream*NRTP + rr][lane]
     __shared__ float sE[NSEG][2][JB];
     __shared__ float sCarry[2][JB];
     __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid = threadIdx.x;
     const int lv = tid % LPR, seg = tid / LPR;
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // (wave index: scalar)
     const int q = blockIdx.x % a.nQ;
     const int nLBq = (a.nLB - q + a.nQ - 1) / a.nQ;
     const uint32_t qtiles = (uint32_t)nLBq * a.B * a.nT;
@@ -226,7 +225,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
-                    wna[k % KC1][v] = zero_hist ? 0.f : sU[NRT + seg * NSTEP + k][lv * V + v];
+                    wna[k % KC1][v] = zero_hist ? 0.f : sU[NRTP + seg * NSTEP + k][lv * V + v];
                 }
             }
 #pragma unroll
@@ -237,7 +236,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
-                    wna[(i + HALO) % KC1][v] = sU[NRT + seg * NSTEP + i + HALO][lv * V + v];
+                    wna[(i + HALO) % KC1][v] = sU[NRTP + seg * NSTEP + i + HALO][lv * V + v];
                 }
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
@@ -417,7 +416,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
             float *zre = a.z_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)T.lb * JB;
             float *zim = a.z_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)T.lb * JB;
             const uint32_t ost32 = (uint32_t)a.ost;
-            uint32_t off = (uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V);
+            uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * 4u;   // bytes
             const bool full = (tt + 1) * TILE_T <= a.L && (T.lb + 1) * JB <= a.J;
             const bool plain = full && !(a.state_out && tt == a.nT - 1);   // no per-row checks at all
             auto replay = [&](auto plain_c) {
@@ -436,14 +435,14 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                         zi[v] = clampf(ni, a.out_clamp);
                     }
                     if (PLAIN || (active && t < a.L)) {
-                        Vec<V>::st(zre + off, zr);
-                        Vec<V>::st(zim + off, zi);
+                        Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + off), zr);
+                        Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + off), zi);
                     }
                     if (!PLAIN && t == a.L - 1 && a.state_out && active) {
                         Vec<V>::st(a.state_out + ((size_t)b * 2 + 0) * a.J + j0, Sr);
                         Vec<V>::st(a.state_out + ((size_t)b * 2 + 1) * a.J + j0, Si);
                     }
-                    off += ost32;
+                    off += ost32 * 4u;
                 }
             };
             // What is still in flight ahead of this tile's output stores must be complete now: the next

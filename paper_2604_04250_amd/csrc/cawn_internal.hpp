@@ -255,39 +255,65 @@ __device__ __forceinline__ void lds_barrier_raw()
 
 // Stage the pre-conv input rows of one tile in LDS with direct global->LDS loads (no registers):
 // rows tile_t0-HALO .. tile_t0+TT-1 of the magnitude stream, then the same rows of the angle
-// stream, JB lanes each, row-major.  Called by `nwaves` waves (index `wave` among them).  Rows
-// outside [0, L) and lanes beyond J read a clamped (valid) address: their values never reach a
-// result (the scan is causal, a lane only reads its own LDS column; rows before a sequence start
-// are zeroed at the point of use).  Rows before the call's first token come from the carried conv
-// history when there is one.  LB: bytes per lane per load (16 needs 16-byte aligned rows).
+// stream, JB lanes each, row-major; each stream occupies staged_rows<TT, JB, HALO>() rows (padded
+// to whole load instructions).  Called by `nwaves` waves (index `wave` among them).  Rows outside
+// [0, L) and lanes beyond J read a clamped (valid) address: their values never reach a result (the
+// scan is causal, a lane only reads its own LDS column; rows before a sequence start are zeroed at
+// the point of use).  Rows before the call's first token come from the carried conv history when
+// there is one.  LB: bytes per lane per load (16 needs 16-byte aligned rows).
+template <int TT, int JB, int HALO>
+__host__ __device__ constexpr int staged_rows()
+{
+    constexpr int g = 256 / JB > 0 ? 256 / JB : 1;      // rows per instruction of the widest load
+    return (TT + HALO + g - 1) / g * g;
+}
 template <int TT, int JB, int HALO, int LB>
 __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const float *ang, const float *tail_in,
                                            int b, int tile_t0, int lb, int J, int L, long long isb, int ist,
                                            int wave, int nwaves, int lane)
 {
     constexpr int NRT = TT + HALO;
+    constexpr int NRTP = staged_rows<TT, JB, HALO>();
     constexpr int LR = JB * 4 / LB;                // lanes per row
     if constexpr (LR <= 64) {
         constexpr int RPI = 64 / LR;               // rows per wave instruction
-        constexpr int NINST = (2 * NRT + RPI - 1) / RPI;
-        // wave-uniform bases of the two streams at the tile's first token; per-lane offsets are 32-bit
-        const float *base_m = mag + (size_t)b * isb + (long long)tile_t0 * ist;
-        const float *base_a = ang + (size_t)b * isb + (long long)tile_t0 * ist;
-        int j = lb * JB + (lane % LR) * (LB / 4);
+        static_assert(NRTP % RPI == 0, "a stream is a whole number of load instructions");
+        constexpr int NIS = NRTP / RPI;            // instructions per stream
+        const int t_first = tile_t0 - HALO;
+        // wave-uniform bases of the two streams at the first staged row
+        const float *base_m = mag + (size_t)b * isb + (long long)t_first * ist;
+        const float *base_a = ang + (size_t)b * isb + (long long)t_first * ist;
+        const int r_in = lane / LR, c_in = (lane % LR) * (LB / 4);      // my row within an instruction, my lane
+        if (t_first >= 0 && t_first + NRTP <= L && (lb + 1) * JB <= J) {
+            // every staged row (padding included) exists: uniform base + one per-lane byte offset
+            const uint32_t loff = (uint32_t)(r_in * ist + lb * JB + c_in) * 4u;
+            for (int i = wave; i < 2 * NIS; i += nwaves) {
+                const int sidx = i >= NIS ? 1 : 0, ii = i - sidx * NIS;
+                const float *ub = (sidx ? base_a : base_m) + (long long)(ii * RPI) * ist;
+                const float *src = reinterpret_cast<const float *>(reinterpret_cast<const char *>(ub) + loff);
+#if defined(__HIP_DEVICE_COMPILE__)
+                if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 16, 0, 0);
+                else __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 4, 0, 0);
+#else
+                (void)src;
+#endif
+            }
+            return;
+        }
+        int j = lb * JB + c_in;
         if (j >= J) j = 0;
         const bool hist = HALO > 0 && tile_t0 == 0 && tail_in != nullptr;
-        for (int i = wave; i < NINST; i += nwaves) {
-            int f = i * RPI + lane / LR;
-            if (f >= 2 * NRT) f = 2 * NRT - 1;
-            const int sidx = f >= NRT ? 1 : 0;
-            const int rr = f - sidx * NRT;
-            const int t = tile_t0 - HALO + rr;
+        for (int i = wave; i < 2 * NIS; i += nwaves) {
+            const int sidx = i >= NIS ? 1 : 0, ii = i - sidx * NIS;
+            int rr = ii * RPI + r_in;
+            if (rr >= NRT) rr = NRT - 1;
+            const int t = t_first + rr;
             const int tc = t < 0 ? 0 : (t >= L ? L - 1 : t);
-            const float *src = (sidx ? base_a : base_m) + ((tc - tile_t0) * ist + j);
+            const float *src = (sidx ? base_a : base_m) + ((tc - t_first) * ist + j);
             if (hist && t < 0) src = tail_in + ((size_t)(b * HALO + rr) * 2 + sidx) * J + j;
 #if defined(__HIP_DEVICE_COMPILE__)
-            if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)i * RPI * JB, 16, 0, 0);
-            else __builtin_amdgcn_global_load_lds(src, sU + (size_t)i * RPI * JB, 4, 0, 0);
+            if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 16, 0, 0);
+            else __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 4, 0, 0);
 #else
             (void)src;
 #endif
