@@ -284,13 +284,14 @@ __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const fl
         const float *base_m = mag + (size_t)b * isb + (long long)t_first * ist;
         const float *base_a = ang + (size_t)b * isb + (long long)t_first * ist;
         const int r_in = lane / LR, c_in = (lane % LR) * (LB / 4);      // my row within an instruction, my lane
-        if (t_first >= 0 && t_first + NRTP <= L && (lb + 1) * JB <= J) {
-            // every staged row (padding included) exists: uniform base + one per-lane byte offset
+        if (t_first >= 0 && t_first + NRT <= L && (lb + 1) * JB <= J) {
+            // every staged row exists: uniform base + one per-lane byte offset
             const uint32_t loff = (uint32_t)(r_in * ist + lb * JB + c_in) * 4u;
             for (int i = wave; i < 2 * NIS; i += nwaves) {
                 const int sidx = i >= NIS ? 1 : 0, ii = i - sidx * NIS;
                 const float *ub = (sidx ? base_a : base_m) + (long long)(ii * RPI) * ist;
                 const float *src = reinterpret_cast<const float *>(reinterpret_cast<const char *>(ub) + loff);
+                if (ii * RPI + r_in >= NRT) continue;      // padding rows of a stream's last instruction: not fetched
 #if defined(__HIP_DEVICE_COMPILE__)
                 if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 16, 0, 0);
                 else __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 4, 0, 0);
