@@ -71,11 +71,11 @@ size_t cawn_state_bytes(const cawn_desc *d);
  * before its first use; calls leave it ready for the next call. */
 size_t cawn_workspace_bytes(const cawn_desc *d);
 
-/* Forward tile checkpoints the backward consumes: the scan state entering each time tile,
- * [B][ceil(L / cawn_tile_len())][2][J]. */
+/* Forward checkpoints the backward consumes: the unclamped scan state before every
+ * cawn_tile_len()-th token, [B][ceil(L / cawn_tile_len())][2][J]. */
 size_t cawn_ckpt_bytes(const cawn_desc *d);
 
-/* Tokens per time tile (the granularity of carries and checkpoints). */
+/* Tokens between checkpoints (the backward kernel's time tile). */
 int32_t cawn_tile_len(void);
 
 const char *cawn_status_string(int status);
@@ -137,7 +137,8 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
  * sub-gradient and the transposed conv.  Parameter gradients: per-(b,t) terms clamped to
  * +-grad_clamp, then summed in a fixed order (bitwise repeatable).
  *   mag, ang, gamma, theta, conv_w, conv_b, state_in: exactly what the forward call received
- *   ckpt         written by that forward call (same d->L, H, F); required
+ *   ckpt         written by that forward call (same d->L, H, F); required when dgamma or dtheta
+ *                is requested, may be NULL otherwise
  *   dz_re, dz_im [B][L][J], strides d->out_stride_*
  *   dstate_out   gradient w.r.t. state_out (state-blob layout) or NULL (= zeros: truncated BPTT)
  *   dmag, dang   [B][L][J], strides d->in_stride_*
