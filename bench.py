@@ -7,7 +7,8 @@ One "step" is one pass of the whole hot path over one batch of seeded synthetic 
 already resident in HBM: forward (writing the tile checkpoints) followed by backward with every
 gradient requested, on the training-step configuration (B=8, H=12, F=64, L=8192, fp32, conv
 kernel 4, threshold 0.1).  Other workloads: cfg2_layer_fwd (forward only), cfg4_stream (2,000,000
-tokens in 4096-token chunks with the state carried in place), cfg5_wide (forward + backward).
+tokens in 4096-token chunks with the state carried in place), cfg5_wide (forward + backward),
+decode (one token per call, state in place: eager launches and a replayed HIP graph).
 
 Prints ONE JSON line: tokens/s of the whole step, plus
   roofline     - algorithmic HBM bytes of the dominant kernel / its measured duration vs 8 TB/s;
@@ -36,7 +37,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3_train",
-                    choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide"])
+                    choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "decode"])
+    ap.add_argument("--decode-batch", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -57,6 +59,79 @@ def read_traffic(workload):
     return None
 
 
+def decode_bench(args, np, torch, K, WL, dev):
+    """Autoregressive steps of the 150M-shaped layer: one token per call, state carried in place.
+    Measured twice: plain launches, and 64 steps captured in a HIP graph and replayed."""
+    wl = WL.CONFIGS["cfg2_layer_fwd"].with_(B=args.decode_batch, L=64)
+    B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
+    theta = K.cawn_theta_init(H, F)
+    inp = WL.make_inputs(wl, theta=theta, with_grads=False)
+    t = lambda a: torch.from_numpy(a).to(dev)
+    gamma, th, cw, cb = t(inp["gamma"]), t(inp["theta"]), t(inp["conv_w"]), t(inp["conv_b"])
+    # one [B,1,J] slice per step at a fixed address (a graph replays fixed pointers)
+    mag = [t(np.ascontiguousarray(inp["mag"][:, i:i + 1])) for i in range(wl.L)]
+    ang = [t(np.ascontiguousarray(inp["ang"][:, i:i + 1])) for i in range(wl.L)]
+    zr = [torch.empty((B, 1, J), device=dev) for _ in range(wl.L)]
+    zi = [torch.empty((B, 1, J), device=dev) for _ in range(wl.L)]
+    d = K.make_desc(B, 1, H, F, conv_k=Kc, gate_tau=wl.gate_tau)
+    ws = K.alloc_workspace(d, dev)
+    state = torch.zeros(K.cawn_state_bytes(d) // 4, device=dev)
+
+    def steps():
+        for i in range(wl.L):
+            st = K.cawn_phase_accumulate_fwd(d, mag[i], ang[i], gamma, th, cw, cb, state, zr[i], zi[i], state,
+                                             None, None, ws)
+            assert st == 0, st
+
+    steps()                      # builds the lane table
+    d.lane_consts_cached = 1
+    torch.cuda.synchronize()
+    # eager
+    state.zero_()
+    for _ in range(args.warmup):
+        steps()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        steps()
+    torch.cuda.synchronize()
+    eager_us = (time.perf_counter() - t0) * 1e6 / (args.steps * wl.L)
+    # graph: capture on a side stream (default priority), replay
+    state.zero_()
+    steps()
+    torch.cuda.synchronize()
+    ref_state = state.clone()
+    ref_z = zr[-1].clone()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    state.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        steps()
+    state.zero_()
+    g.replay()
+    torch.cuda.synchronize()
+    graph_ok = bool(torch.equal(state, ref_state) and torch.equal(zr[-1], ref_z))
+    for _ in range(args.warmup):
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g.replay()
+    torch.cuda.synchronize()
+    graph_us = (time.perf_counter() - t0) * 1e6 / (args.steps * wl.L)
+    K.check(K.cawn_workspace_status(ws))
+    out = {"metric": "decode tokens/s (one token per call, state in place)", "value": B / (graph_us * 1e-6),
+           "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": graph_us * wl.L * 1e-3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"decode: B={B} H={H} F={F} conv_k={Kc} tau={wl.gate_tau}, {wl.L} single-token "
+                                  f"calls per step, state carried in place"},
+           "us_per_token_eager": eager_us, "us_per_token_graph": graph_us, "graph_matches_eager": graph_ok,
+           "state_bytes": int(state.numel() * 4)}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -72,6 +147,8 @@ def main():
     K.lib()   # fails loudly when libcawn.so was not built
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "decode":
+        return decode_bench(args, np, torch, K, WL, dev)
     wl = WL.CONFIGS[args.workload]
     B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
     theta = K.cawn_theta_init(H, F)

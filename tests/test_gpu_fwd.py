@@ -126,6 +126,88 @@ def test_chunked_streaming_in_place_state_matches_one_pass():
     assert np.array_equal(tail, ora["tail_out"])
 
 
+@pytest.mark.parametrize("Kc,amp_mode,J_shape", [(4, 0, (3, 50)), (3, 1, (2, 32)), (0, 0, (1, 70)), (1, 0, (2, 16))])
+def test_decode_steps_in_place_state_match_one_pass(Kc, amp_mode, J_shape):
+    """Autoregressive use: a prefill call, then one token per call with the state carried in place
+    (short calls take the sequential kernel), against the oracle over the whole sequence."""
+    G = _gpu()
+    H, F = J_shape
+    B, Lp, nsteps = 3, 150, 45
+    L = Lp + nsteps + 5
+    J = H * F
+    d = _inputs(B, L, H, F, Kc, 900 + Kc, gamma=(0.95, 0.9999))
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=0.1)
+    ora = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"])
+    import torch
+    state = torch.zeros(B * 2 * J * max(Kc, 1), device=G.DEV)
+    t0 = 0
+    zr, zi, mk = [], [], []
+    for n in [Lp] + [1] * nsteps + [5]:
+        sub = {k: (v[:, t0:t0 + n] if k in ("mag", "ang") else v) for k, v in d.items()}
+        out = G.run_fwd(sub, B, n, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=0.1, state_in=state,
+                        in_place_state=True, cached=1 if t0 else 0, want_ckpt=(n == 1))
+        state = G.dev(out["state_out"])
+        zr.append(out["z_re"]); zi.append(out["z_im"]); mk.append(out["mask"])
+        if n == 1:      # a one-token call's checkpoint is the scan state it started from
+            assert np.array_equal(out["ckpt"].reshape(B, 2, J), prev_scan)
+        prev_scan = G.unpack_state(out["state_out"], B, J, Kc)[0].copy()
+        t0 += n
+    assert t0 == L
+    assert G.rel_err(np.concatenate(zr, 1), ora["z_re"]) <= TOL
+    assert G.rel_err(np.concatenate(zi, 1), ora["z_im"]) <= TOL
+    assert np.array_equal(np.concatenate(mk, 1), G.mask_from_gate(ora["gate"])), "gate mask differs"
+    scan, tail = G.unpack_state(out["state_out"], B, J, Kc)
+    assert G.rel_err(scan, ora["scan_out"]) <= TOL
+    if Kc > 1:
+        assert np.array_equal(tail, ora["tail_out"])
+
+
+def test_decode_steps_replayed_from_a_hip_graph_match_eager():
+    """Eight one-token calls captured in a HIP graph; three replays with eager work and
+    synchronisation in between, each compared with the eager result (bitwise: same kernels)."""
+    G = _gpu()
+    import torch
+    K = G.K
+    B, H, F, Kc, n = 2, 2, 48, 4, 8
+    J = H * F
+    d = _inputs(B, n, H, F, Kc, 950)
+    mag = [G.dev(d["mag"][:, i:i + 1]) for i in range(n)]
+    ang = [G.dev(d["ang"][:, i:i + 1]) for i in range(n)]
+    gamma, theta, cw, cb = (G.dev(d[k]) for k in ("gamma", "theta", "conv_w", "conv_b"))
+    zr = [torch.empty((B, 1, J), device=G.DEV) for _ in range(n)]
+    zi = [torch.empty((B, 1, J), device=G.DEV) for _ in range(n)]
+    desc = K.make_desc(B, 1, H, F, conv_k=Kc, gate_tau=0.1)
+    ws = G.Workspaces.get(desc)
+    state = torch.zeros(K.cawn_state_bytes(desc) // 4, device=G.DEV)
+
+    def steps():
+        for i in range(n):
+            K.check(K.cawn_phase_accumulate_fwd(desc, mag[i], ang[i], gamma, theta, cw, cb, state, zr[i], zi[i],
+                                                state, None, None, ws))
+
+    steps()
+    torch.cuda.synchronize()
+    desc.lane_consts_cached = 1
+    state.zero_()
+    steps()
+    torch.cuda.synchronize()
+    ref = [z.clone() for z in zr + zi] + [state.clone()]
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(g, stream=side):
+        steps()
+    for rep in range(3):
+        for z in zr + zi:
+            z.fill_(float("nan"))           # eager work between the replays
+        state.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = zr + zi + [state]
+        assert all(torch.equal(x, y) for x, y in zip(got, ref)), f"replay {rep} differs from eager"
+    K.check(K.cawn_workspace_status(ws))
+
+
 def test_zero_length_call_passes_state_through():
     G = _gpu()
     B, H, F, Kc = 2, 2, 16, 4
