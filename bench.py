@@ -34,8 +34,8 @@ BWD_BYTES_PER_TOKEN_LANE = 24   # read mag, ang, dz_re, dz_im; write dmag, dang
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default 100; 3 for cfg4_stream)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 20; 1 for cfg4_stream)")
     ap.add_argument("--workload", default="cfg3_train",
                     choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "decode"])
     ap.add_argument("--decode-batch", type=int, default=1)
@@ -134,6 +134,10 @@ def decode_bench(args, np, torch, K, WL, dev):
 
 def main():
     args = parse()
+    if args.steps is None:
+        args.steps = 3 if args.workload == "cfg4_stream" else 100
+    if args.warmup is None:
+        args.warmup = 1 if args.workload == "cfg4_stream" else 20
     if args.gpus != 1:
         print(f"bench.py: this build runs on ONE GPU (lanes and batch rows shard with no traffic; see "
               f"DESIGN.md); --gpus {args.gpus} is not available", file=sys.stderr)
@@ -162,7 +166,7 @@ def main():
     gamma, th = torch.from_numpy(inp["gamma"]).to(dev), torch.from_numpy(inp["theta"]).to(dev)
     cw, cb = torch.from_numpy(inp["conv_w"]).to(dev), torch.from_numpy(inp["conv_b"]).to(dev)
     per_set = (8 if do_bwd else 4) * B * L * J * 4
-    nsets = max(2, min(16, -(-(600 << 20) // per_set)))     # rotate over > 512 MiB so the LLC cannot serve it
+    nsets = max(4, min(16, -(-(600 << 20) // per_set)))     # >= 4 disjoint sets, > 512 MiB in total: the LLC cannot serve them
     names = ["mag", "ang"] + (["dz_re", "dz_im"] if do_bwd else [])
     sets = []
     base = {k: torch.from_numpy(inp[k]).to(dev) for k in names}
@@ -260,13 +264,17 @@ def main():
                            "traffic": read_traffic(args.workload), "avg_ms": per_call_ms}
         out["stream"] = {"calls": ncalls, "state_bytes": nstate * 4, "device_mem_delta_bytes": int(mem1 - mem0)}
     else:
-        fwd_ms = float(np.mean([r[0].elapsed_time(r[1]) for r in recs]))
+        fwd_all = [r[0].elapsed_time(r[1]) for r in recs]
+        fwd_ms = float(np.mean(fwd_all))
         out["fwd_ms"] = fwd_ms
+        out["fwd_ms_median_min"] = [float(np.median(fwd_all)), float(np.min(fwd_all))]
         out["fwd_tokens_per_s"] = tokens / (fwd_ms * 1e-3)
         out["fwd_GBps"] = FWD_BYTES_PER_TOKEN_LANE * tokens * J / (fwd_ms * 1e-3) / 1e9
         if do_bwd:
-            bwd_ms = float(np.mean([r[1].elapsed_time(r[2]) for r in recs]))
+            bwd_all = [r[1].elapsed_time(r[2]) for r in recs]
+            bwd_ms = float(np.mean(bwd_all))
             out["bwd_ms"] = bwd_ms
+            out["bwd_ms_median_min"] = [float(np.median(bwd_all)), float(np.min(bwd_all))]
             alg = BWD_BYTES_PER_TOKEN_LANE * tokens * J
             achieved = alg / (bwd_ms * 1e-3) / 1e9
             out["roofline"] = {"bound": "hbm", "kernel": "bwd_kernel<1,4,true> (+ its partial-sum reduction)",
@@ -285,7 +293,8 @@ def main():
         Ls = min(L, 8192)
         Bs = max(1, min(B, (48 << 20) // (Ls * J)))       # about 10-30 s of CPU work over the host cores
         sub = {k: np.ascontiguousarray(inp[k][:Bs, :Ls]) for k in names}
-        cfg = O.Cfg(Bs, Ls, H, F, conv_k=Kc, gate_tau=wl.gate_tau)
+        cores = O.max_threads()
+        cfg = O.Cfg(Bs, Ls, H, F, conv_k=Kc, gate_tau=wl.gate_tau, nthreads=cores)
         t1 = time.perf_counter()
         of = O.phase_fwd(cfg, sub["mag"], sub["ang"], inp["gamma"], inp["theta"], conv_w=inp["conv_w"],
                          conv_b=inp["conv_b"], want_gate=False)
@@ -293,8 +302,19 @@ def main():
             ob = O.phase_bwd(cfg, sub["mag"], sub["ang"], inp["gamma"], inp["theta"], sub["dz_re"], sub["dz_im"],
                              conv_w=inp["conv_w"], conv_b=inp["conv_b"])
         cpu_s = time.perf_counter() - t1
-        out["cpu_baseline"] = {"value": Bs * Ls / cpu_s, "unit": "tokens/s", "cores": O.max_threads(),
-                               "kind": "oracle", "seconds": cpu_s,
+        # the same on one thread, on 1/8 of the lanes' worth of tokens
+        Ls1 = max(64, Ls // 8)
+        cfg1 = O.Cfg(1, Ls1, H, F, conv_k=Kc, gate_tau=wl.gate_tau, nthreads=1)
+        sub1 = {k: np.ascontiguousarray(inp[k][:1, :Ls1]) for k in names}
+        t2 = time.perf_counter()
+        O.phase_fwd(cfg1, sub1["mag"], sub1["ang"], inp["gamma"], inp["theta"], conv_w=inp["conv_w"],
+                    conv_b=inp["conv_b"], want_gate=False)
+        if do_bwd:
+            O.phase_bwd(cfg1, sub1["mag"], sub1["ang"], inp["gamma"], inp["theta"], sub1["dz_re"], sub1["dz_im"],
+                        conv_w=inp["conv_w"], conv_b=inp["conv_b"])
+        cpu1_s = time.perf_counter() - t2
+        out["cpu_baseline"] = {"value": Bs * Ls / cpu_s, "unit": "tokens/s", "cores": cores,
+                               "kind": "oracle", "seconds": cpu_s, "single_thread_value": Ls1 / cpu1_s,
                                "sample": f"first {Bs} batch rows x {Ls} tokens x {J} lanes of the same inputs, "
                                          f"{'fwd+bwd' if do_bwd else 'fwd'}, fp64, OpenMP over lanes"}
         # parity of the timed configuration on that sample (the kernels are time-local: the first Ls
