@@ -89,7 +89,7 @@ int cawn_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 int cawn_workspace_status(void *workspace, void *stream);
 
 /* Number of polls a tile spends waiting for its predecessor's carry before it gives up
- * (default 1<<26; every wave exits either way).  Host-side setting, applies to later calls. */
+ * (default 1<<20, about a second; every wave exits either way).  Host-side setting, applies to later calls. */
 void cawn_set_spin_limit(uint32_t polls);
 
 /* Rotation angles as the paper initialises them (Sec. 3.4): theta_j = 10000^(-2j/(H*F)).

@@ -9,7 +9,7 @@
 
 namespace cawn {
 
-static std::atomic<uint32_t> g_spin_limit{1u << 26};
+static std::atomic<uint32_t> g_spin_limit{1u << 20};   // polls (~1 us each): a second of waiting, far beyond any real wait
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -32,16 +32,14 @@ static WsLayout make_layout(const cawn_desc *d)
     const int kc = d->conv_k > MAX_KC ? MAX_KC : d->conv_k;
     const size_t tiles_rows = (size_t)d->B * (w.nT > 0 ? w.nT : 1);
     size_t o = sizeof(WsHeader);
-    w.off_flags = o;
-    o += (size_t)MAX_TILES * FLAG_STRIDE * sizeof(uint32_t);
     w.off_table = o;
     o = align_up(o + (size_t)lane_rows(kc) * w.Jp * sizeof(float), 256);
-    w.off_agg = o;
-    o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(float), 256);
+    w.off_agg = o;      // published words are 8 bytes each: value + tag
+    o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_pre = o;
-    o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(float), 256);
+    o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_halo = o;
-    o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(float), 256);
+    o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_part = o;
     o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
     w.off_dbg = o;
@@ -371,13 +369,21 @@ const char *cawn_status_string(int st)
     }
 }
 
+__global__ void init_header_kernel(WsHeader *h, unsigned long long bytes)
+{
+    h->bytes_lo = (uint32_t)bytes;
+    h->bytes_hi = (uint32_t)(bytes >> 32);
+}
+
 int cawn_workspace_init(void *workspace, size_t bytes, void *stream)
 {
-    const size_t need = sizeof(WsHeader) + (size_t)MAX_TILES * FLAG_STRIDE * sizeof(uint32_t);
     if (!workspace) return CAWN_EINVAL;
-    if (bytes < need || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
+    if (bytes < sizeof(WsHeader) || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
+    // the whole buffer: a word counts as published only when its tag matches, and tag 0 never does
     hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream,
-                       reinterpret_cast<uint32_t *>(workspace), need / sizeof(uint32_t));
+                       reinterpret_cast<uint32_t *>(workspace), bytes / sizeof(uint32_t));
+    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream,
+                       reinterpret_cast<WsHeader *>(workspace), (unsigned long long)bytes);
     return hipGetLastError() == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
 }
 
@@ -497,9 +503,9 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     a.ckpt = reinterpret_cast<float *>(ckpt);
     a.mask = gate_mask;
     a.hdr = reinterpret_cast<WsHeader *>(ws);
-    a.flags = reinterpret_cast<uint32_t *>(ws + w.off_flags);
-    a.agg = reinterpret_cast<float *>(ws + w.off_agg);
-    a.pre = reinterpret_cast<float *>(ws + w.off_pre);
+    a.agg = reinterpret_cast<tagged_t *>(ws + w.off_agg);
+    a.pre = reinterpret_cast<tagged_t *>(ws + w.off_pre);
+    a.clear_from = w.off_agg;
     a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = nTf; a.nTc = w.nT; a.nLB = nLB;
     a.amp_mode = d->amp_mode;
     a.small_angle = (d->conv_k > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;   // |angle| <= SiLU(clamp) <= 41 revolutions
@@ -581,10 +587,10 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     a.dmag = dmag; a.dang = dang;
     a.dstate_in = reinterpret_cast<float *>(dstate_in);
     a.hdr = reinterpret_cast<WsHeader *>(ws);
-    a.flags = reinterpret_cast<uint32_t *>(ws + w.off_flags);
-    a.agg = reinterpret_cast<float *>(ws + w.off_agg);
-    a.pre = reinterpret_cast<float *>(ws + w.off_pre);
-    a.halo = reinterpret_cast<float *>(ws + w.off_halo);
+    a.agg = reinterpret_cast<tagged_t *>(ws + w.off_agg);
+    a.pre = reinterpret_cast<tagged_t *>(ws + w.off_pre);
+    a.clear_from = w.off_agg;
+    a.halo = reinterpret_cast<tagged_t *>(ws + w.off_halo);
     a.part = reinterpret_cast<float *>(ws + w.off_part);
     a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
     a.amp_mode = d->amp_mode; a.want_param = want_param ? 1 : 0;

@@ -98,6 +98,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     __syncthreads();
     uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
     const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
+    const uint32_t tag = epoch + 1;      // of every word this call publishes (0 is never valid)
 
     // Persistent: each workgroup loops over tiles, handed out in chain order by an atomic ticket (a
     // tile only ever waits for tiles that a running workgroup already holds).  The next ticket is
@@ -255,14 +256,13 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         if (chained && feeds) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                coherent_store(a.agg + slot + v, Tr[v]);
-                coherent_store(a.agg + slot + JB + v, Ti[v]);
+                tagged_store(a.agg + slot + v, Tr[v], tag);
+                tagged_store(a.agg + slot + JB + v, Ti[v], tag);
             }
         }
     }
-    // the staged rows have landed; so have the aggregate stores of the head group's wave
+    // the staged rows have landed
     wait_stores_done();
-    if (tid == 0 && chained && feeds) status_store(a.flags + (size_t)ticket * FLAG_STRIDE, epoch, ST_AGG);
     lds_barrier();
     BWD_STAMP(3);
 
@@ -446,8 +446,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         ldu<V>(qr, row(R_PTB_LR), jb);
         ldu<V>(qi, row(R_PTB_LI), jb);
         if (chained) {
-            if (!look_back<V, true, LPR>(a.flags, a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V,
-                                         lv, hr, hi, qr, qi, a.spin_limit, epoch, cr, ci)) {
+            if (!look_back<V, true, LPR, 1>(a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V, lv,
+                                            hr, hi, qr, qi, a.spin_limit, tag, cr, ci)) {
                 if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -464,8 +464,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             for (int v = 0; v < V; ++v) {
                 float P_r, P_i;
                 chain_step<true>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], P_r, P_i);
-                coherent_store(a.pre + slot + v, P_r);
-                coherent_store(a.pre + slot + JB + v, P_i);
+                tagged_store(a.pre + slot + v, P_r, tag);
+                tagged_store(a.pre + slot + JB + v, P_i, tag);
             }
         }
     }
@@ -483,12 +483,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 
     // The tile's last segment needs the conv pre-activation gradients of the next tile's first HALO
     // tokens.  The head group fetches them (all chain traffic stays in one wave, whose memory
-    // operations then have one known order); that tile's status word is asked for now and the
-    // answer comes back during the reverse pass.
+    // operations then have one known order).
     const bool fetch_halo = KC > 0 && HALO > 0 && head && chained;
-    const uint32_t *halo_flag = a.flags + (size_t)(ticket - (chained ? chain_stride : 0u)) * FLAG_STRIDE;
-    uint32_t halo_st = ST_NONE;
-    if (fetch_halo) halo_st = status_load(halo_flag, epoch);
 
     // ---- reverse pass: adjoint, returned gradients, parameter terms
     float acc_g[V], acc_t[V];
@@ -551,10 +547,6 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 ooff += ist32 * 4u;
             }
         }
-        if (head && feeds) {   // the prefix stores were issued before the reverse pass
-            wait_stores_done();
-            if (lv == 0) status_store(a.flags + (size_t)ticket * FLAG_STRIDE, epoch, ST_PREFIX);
-        }
     } else {
         // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
         const auto &wm = wmf;
@@ -569,16 +561,37 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 }
         }
         if (head) {
-            // the rows the earlier tile needs go out; the rows of the later tile come in
-            if (feeds && HALO > 0) {
-                float *hp = a.halo + (size_t)ticket * HALO * 2 * JB + lv * V;
+            // The rows of the later tile come in, the rows the earlier tile needs go out.  The loads
+            // are issued first: a wave's memory operations complete in order, so waiting for them
+            // then does not wait for the stores' round trip as well.
+            const tagged_t *hin = a.halo + (size_t)(ticket - (chained ? chain_stride : 0u)) * HALO * 2 * JB + lv * V;
+            tagged_t xw[HALO1][2][V];
+#pragma unroll
+            for (int r = 0; r < HALO1; ++r)
+#pragma unroll
+                for (int v = 0; v < V; ++v) xw[r][0][v] = xw[r][1][v] = 0;
+            auto fetch = [&]() {
 #pragma unroll
                 for (int r = 0; r < HALO; ++r)
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        coherent_store(hp + (r * 2 + 0) * JB + v, dzr[r][v]);
-                        coherent_store(hp + (r * 2 + 1) * JB + v, dzi[r][v]);
+                        xw[r][0][v] = tagged_load(hin + (r * 2 + 0) * JB + v);
+                        xw[r][1][v] = tagged_load(hin + (r * 2 + 1) * JB + v);
                     }
+            };
+            if (fetch_halo) fetch();
+            if (feeds && HALO > 0) {
+                tagged_t *hp = a.halo + (size_t)ticket * HALO * 2 * JB + lv * V;
+#pragma unroll
+                for (int r = 0; r < HALO; ++r)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        tagged_store(hp + (r * 2 + 0) * JB + v, dzr[r][v], tag);
+                        tagged_store(hp + (r * 2 + 1) * JB + v, dzi[r][v], tag);
+                    }
+                wait_vm<2 * HALO1 * V>();     // everything but those stores
+            } else {
+                wait_vm<0>();
             }
             float xm[HALO1][V], xa[HALO1][V];
 #pragma unroll
@@ -586,21 +599,30 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
                 for (int v = 0; v < V; ++v) xm[r][v] = xa[r][v] = 0.f;
             if (fetch_halo) {
+                const int gshift = (int)(threadIdx.x & 63) - lv;
+                const unsigned long long gmask = (1ull << LPR) - 1ull;
                 uint32_t spins = 0;
-                while (halo_st < ST_HALO && spins < a.spin_limit) {
-                    __builtin_amdgcn_s_sleep(1);
-                    halo_st = status_load(halo_flag, epoch);
+                bool ok;
+                while (true) {       // valid when every lane of the group found all its tags
+                    bool mine = true;
+#pragma unroll
+                    for (int r = 0; r < HALO; ++r)
+#pragma unroll
+                        for (int v = 0; v < V; ++v) mine = mine && tagged_ok(xw[r][0][v], tag) && tagged_ok(xw[r][1][v], tag);
+                    ok = ((__ballot(mine) >> gshift) & gmask) == gmask;
+                    if (ok || spins >= a.spin_limit) break;
                     ++spins;
+                    __builtin_amdgcn_s_sleep(1);
+                    fetch();
+                    wait_vm<0>();
                 }
-                compiler_fence();
-                if (halo_st >= ST_HALO) {
-                    const float *hp = a.halo + (size_t)(ticket - chain_stride) * HALO * 2 * JB + lv * V;
+                if (ok) {
 #pragma unroll
                     for (int r = 0; r < HALO; ++r)
 #pragma unroll
                         for (int v = 0; v < V; ++v) {
-                            xm[r][v] = coherent_load(hp + (r * 2 + 0) * JB + v);
-                            xa[r][v] = coherent_load(hp + (r * 2 + 1) * JB + v);
+                            xm[r][v] = tagged_value(xw[r][0][v]);
+                            xa[r][v] = tagged_value(xw[r][1][v]);
                         }
                 } else if (lv == 0) {
                     __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -616,10 +638,6 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     }
             }
         }
-        // Every wave: nothing of the above is in flight any more (a no-op for the waves that took no
-        // part).  Only then the status word: it covers the prefix and the halo rows.
-        wait_vm<0>();
-        if (tid == 0 && feeds) status_store(a.flags + (size_t)ticket * FLAG_STRIDE, epoch, HALO > 0 ? ST_HALO : ST_PREFIX);
         lds_barrier();
     BWD_STAMP(8);
         float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
@@ -771,7 +789,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         sLast = (old + 1 == gridDim.x) ? 1u : 0u;
     }
     __syncthreads();
-    if (sLast) finish_call(a.hdr, a.flags, epoch, tid_, blockDim.x);
+    if (sLast) finish_call(a.hdr, a.clear_from, epoch, tid_, blockDim.x);
 }
 
 // Persistent grid: what fits on the chip at once (asked once per kernel), never more than tiles.

@@ -24,6 +24,9 @@
 
 namespace cawn {
 
+#ifndef CAWN_FWD_NB
+#define CAWN_FWD_NB 4       // predecessors read per look-back round trip
+#endif
 #ifndef CAWN_FWD_ITER_TICKS
 #define CAWN_FWD_ITER_TICKS 500      // start-up skew spread over this many 10 ns ticks per chain
 #endif
@@ -119,6 +122,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     __syncthreads();
     uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
     const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
+    const uint32_t tag = epoch + 1;      // of every word this call publishes (0 is never valid)
 
     // Stage a tile's input rows in LDS.  The chain-owning wave stays out of it: a wave's memory
     // operations complete in order, and its polls of other tiles must not queue behind a tile's
@@ -364,19 +368,25 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                     Vec<V>::ld(ci, a.state_in + ((size_t)b * 2 + 1) * a.J + j0);
                 }
             } else {
-                uint32_t *own = nullptr;
                 if (tt + 1 < a.nT) {
-                    coherent_store_v<V>(a.agg + slot, Tr);
-                    coherent_store_v<V>(a.agg + slot + JB, Ti);
-                    own = a.flags + (size_t)id * FLAG_STRIDE;   // set once those stores are done, together with the first poll
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        tagged_store(a.agg + slot + v, Tr[v], tag);
+                        tagged_store(a.agg + slot + JB + v, Ti[v], tag);
+                    }
                 }
-                if (!look_back<V, false, LPR>(a.flags, a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB,
-                                              lv * V, lv, hr, hi, qr, qi, a.spin_limit, epoch, cr, ci, own)) {
+                if (!look_back<V, false, LPR, CAWN_FWD_NB>(a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB, lv * V, lv,
+                                                 hr, hi, qr, qi, a.spin_limit, tag, cr, ci)) {
                     // gave up: flag the workspace, keep going so that every wave exits
                     if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
             CAWN_STAMP(5);
+            // Every load of this block is complete from here on, on every path: a load that some path
+            // never uses would stay "in flight" in the compiler's bookkeeping and cost a full wait
+            // where its register is reused -- in the replay below, behind the prefix stores.
+#pragma unroll
+            for (int v = 0; v < V; ++v) asm volatile("" ::"v"(hr[v]), "v"(hi[v]), "v"(qr[v]), "v"(qi[v]));
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 sCarry[0][lv * V + v] = cr[v];
@@ -387,8 +397,11 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 #pragma unroll
                 for (int v = 0; v < V; ++v)
                     chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], P_r[v], P_i[v]);
-                coherent_store_v<V>(a.pre + slot, P_r);
-                coherent_store_v<V>(a.pre + slot + JB, P_i);
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    tagged_store(a.pre + slot + v, P_r[v], tag);
+                    tagged_store(a.pre + slot + JB + v, P_i[v], tag);
+                }
             }
         }
         lds_barrier_raw();     // the next tile's rows are still on their way
@@ -446,9 +459,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                 }
             };
             // What is still in flight ahead of this tile's output stores must be complete now: the next
-            // tile's staged rows (needed after the next barrier) and, on the chain-owning wave, the
-            // prefix (its status word is set next).  The output stores themselves (the 2 * NSTEP
-            // youngest operations when no row needed a check) are left in flight.
+            // tile's staged rows (needed after the next barrier).  The output stores themselves (the
+            // 2 * NSTEP youngest operations when no row needed a check) are left in flight.
             if (plain) {
                 replay(std::true_type{});
                 wait_vm<(2 * NSTEP < 63 ? 2 * NSTEP : 63)>();
@@ -457,7 +469,6 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                 wait_vm<0>();
             }
         }
-        if (is_tail_seg && tt + 1 < a.nT && lv == 0) status_store(a.flags + (size_t)id * FLAG_STRIDE, epoch, ST_PREFIX);
         CAWN_STAMP(8);
 
         // ---- conv history for the next call: last HALO pre-conv rows (written by the last tile,
@@ -495,7 +506,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         sLast = (old + 1 == gridDim.x) ? 1u : 0u;
     }
     __syncthreads();
-    if (sLast) finish_call(a.hdr, a.flags, epoch, tid, blockDim.x);
+    if (sLast) finish_call(a.hdr, a.clear_from, epoch, tid, blockDim.x);
 }
 
 // Short calls (autoregressive decoding, Sec. 5.2 of the paper: one token per call with the state

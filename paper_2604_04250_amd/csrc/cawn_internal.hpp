@@ -59,11 +59,7 @@ static_assert(CKPT_T % FwdGeom::NSTEP == 0, "checkpoints fall on forward segment
 constexpr int FwdV = CAWN_FWD_V, FwdLPR = CAWN_FWD_LPR;  // lanes per thread, threads per row
 constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;
 constexpr int MAX_KC = 4;
-#ifndef CAWN_FLAG_STRIDE
-#define CAWN_FLAG_STRIDE 16
-#endif
-constexpr uint32_t MAX_TILES = 1u << 18;   // capacity of the fixed tile-status zone
-constexpr int FLAG_STRIDE = CAWN_FLAG_STRIDE;   // words between status words (spreads them over cache lines)
+constexpr uint32_t MAX_TILES = 1u << 18;   // most tiles one call may have (tile indices, tickets)
 
 // ---------------------------------------------------------------------------------- lane table
 // Per-lane constants, struct-of-arrays, each row Jp floats (Jp = J rounded up to 64), built in
@@ -83,29 +79,32 @@ enum LaneRow : int {
 inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k; }
 
 // ----------------------------------------------------------------------------------- workspace
-// Workspace: [header 1 KiB][tile status words, fixed MAX_TILES capacity][lane table][aggregates]
-// [prefixes][backward conv halo][backward parameter partials].  A status word holds the epoch of
-// the call that wrote it next to the tile's state, so words left by earlier calls (whatever their
-// descriptor) read as "nothing published"; the workgroup that finishes last resets the tickets and
-// advances the epoch.  Nothing is cleared per tile.
+// Workspace: [header 1 KiB][lane table][aggregates][prefixes][backward conv halo][backward parameter
+// partials].  Everything tiles publish to each other (aggregates, prefixes, halo rows) is stored as
+// 8-byte words {value, tag}: the tag is the epoch of the call plus one, so a word is valid exactly
+// when its tag matches -- no separate status words, no ordering between stores, one memory round trip
+// from publication to use.  Words left by earlier calls (whatever their descriptor) carry other tags
+// and read as "not published"; cawn_workspace_init zeroes the whole buffer (tag 0 is never valid).
+// Nothing is cleared per tile or per call: the workgroup that leaves last resets the tickets and
+// advances the epoch.
 constexpr int MAX_QUEUES = 64;
 struct WsHeader {
     uint32_t ticket[MAX_QUEUES];   // per work queue: next tile to hand out
     uint32_t done;                 // tiles finished
     uint32_t error;                // sticky: a tile gave up waiting
-    uint32_t epoch;                // calls completed on this workspace (mod 2^30): tags the status words
-    uint32_t pad[256 - MAX_QUEUES - 3];
+    uint32_t epoch;                // calls completed on this workspace (mod 2^30): tag of published words - 1
+    uint32_t bytes_lo, bytes_hi;   // size given to cawn_workspace_init (what an epoch wrap has to clear)
+    uint32_t pad[256 - MAX_QUEUES - 5];
 };
 static_assert(sizeof(WsHeader) == 1024, "header size");
 
 struct WsLayout {
     int J, Jp, Jp128, nT;
-    size_t off_flags, off_table, off_agg, off_pre, off_halo, off_part, off_dbg, total;
+    size_t off_table, off_agg, off_pre, off_halo, off_part, off_dbg, total;
 };
 
-// Tile states of the decoupled look-back (low two bits of a status word; the rest is the epoch).
-constexpr uint32_t ST_NONE = 0, ST_AGG = 1, ST_PREFIX = 2, ST_HALO = 3;
 constexpr uint32_t EPOCH_MOD = 1u << 30;
+typedef unsigned long long tagged_t;     // {fp32 value (low half), tag (high half)}
 
 // Gate as a union of two closed fp32 intervals on the quantity the decision is taken on (the
 // fp32 conv pre-activation, or the raw magnitude input when there is no conv).
@@ -120,8 +119,7 @@ struct FwdArgs {
     float *ckpt;                 // may be null
     uint32_t *mask;              // may be null
     WsHeader *hdr;
-    uint32_t *flags;
-    float *agg, *pre;
+    tagged_t *agg, *pre;
     int B, L, J, Jp, nT, nLB;    // nT: forward tiles per sequence
     int nTc;                     // checkpoint intervals per sequence
     int nQ;                      // work queues (a queue owns lane blocks q, q+nQ, ...)
@@ -134,6 +132,7 @@ struct FwdArgs {
     GateSet gs;
     uint32_t spin_limit;
     uint32_t total_tiles;
+    size_t clear_from;           // byte offset of the first published word (cleared when the epoch wraps)
     unsigned long long *dbg;     // -DCAWN_TIMING builds only
 };
 
@@ -146,8 +145,8 @@ struct BwdArgs {
     float *dmag, *dang;
     float *dstate_in;            // may be null
     WsHeader *hdr;
-    uint32_t *flags;
-    float *agg, *pre, *halo, *part;
+    tagged_t *agg, *pre, *halo;
+    float *part;
     int B, L, J, Jp, nT, nLB;
     int nQ;
     int small_angle;
@@ -158,6 +157,7 @@ struct BwdArgs {
     GateSet gs;
     uint32_t spin_limit;
     uint32_t total_tiles;
+    size_t clear_from;           // byte offset of the first published word (cleared when the epoch wraps)
     unsigned long long *dbg;     // -DCAWN_TIMING builds only
 };
 
@@ -329,71 +329,40 @@ __device__ __forceinline__ uint32_t flag_load(const uint32_t *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Tile status: state tagged with the call's epoch; a word from another epoch reads as ST_NONE.
-__device__ __forceinline__ void status_store(uint32_t *p, uint32_t epoch, uint32_t state)
+// Published words.  One 8-byte relaxed agent-scope store carries a value and the call's tag; the
+// reader takes the value only from a word whose tag matches.  8-byte naturally aligned accesses are
+// single-copy atomic, so a reader sees either the whole new word or an old one.
+__device__ __forceinline__ void tagged_store(tagged_t *p, float v, uint32_t tag)
 {
-    flag_store(p, (epoch << 2) | state);
+    __hip_atomic_store(p, (tagged_t)__float_as_uint(v) | ((tagged_t)tag << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint32_t status_load(const uint32_t *p, uint32_t epoch)
+__device__ __forceinline__ tagged_t tagged_load(const tagged_t *p)
 {
-    const uint32_t w = flag_load(p);
-    return (w >> 2) == epoch ? (w & 3u) : ST_NONE;
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// End of a call, run by thread `tid` of the `nthreads` of the workgroup that finished last: tickets
-// and the finished-tile count return to zero and the epoch advances.  When the epoch wraps, status
-// words of 2^30 calls ago would become current again: the whole zone is cleared then.
-__device__ __forceinline__ void finish_call(WsHeader *hdr, uint32_t *flags, uint32_t epoch, uint32_t tid,
+__device__ __forceinline__ bool tagged_ok(tagged_t w, uint32_t tag) { return (uint32_t)(w >> 32) == tag; }
+__device__ __forceinline__ float tagged_value(tagged_t w) { return __uint_as_float((uint32_t)w); }
+
+// End of a call, run by thread `tid` of the `nthreads` of the workgroup that left last: tickets and
+// the finished-workgroup count return to zero and the epoch advances.  When the epoch wraps, words of
+// 2^30 calls ago would become valid again: everything behind the lane table is cleared then
+// (`clear_from`: byte offset of this call's first published word).
+__device__ __forceinline__ void finish_call(WsHeader *hdr, size_t clear_from, uint32_t epoch, uint32_t tid,
                                             uint32_t nthreads)
 {
     const uint32_t next = (epoch + 1) % EPOCH_MOD;
-    if (next == 0)
-        for (uint32_t i = tid; i < MAX_TILES; i += nthreads) flag_store(flags + (size_t)i * FLAG_STRIDE, 0u);
+    if (next == 0) {
+        const size_t bytes = (size_t)hdr->bytes_lo | ((size_t)hdr->bytes_hi << 32);
+        tagged_t *base = reinterpret_cast<tagged_t *>(reinterpret_cast<char *>(hdr) + clear_from);
+        const size_t n = bytes > clear_from ? (bytes - clear_from) / sizeof(tagged_t) : 0;
+        for (size_t i = tid; i < n; i += nthreads)
+            __hip_atomic_store(base + i, (tagged_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (tid < (uint32_t)MAX_QUEUES) flag_store(&hdr->ticket[tid], 0u);
     if (tid == 0) {
         flag_store(&hdr->done, 0u);
         flag_store(&hdr->epoch, next);
-    }
-}
-__device__ __forceinline__ float coherent_load(const float *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void coherent_store(float *p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// V consecutive floats at once, in the widest agent-scope atomic accesses available (8 bytes): a
-// 4-byte write-through store or bypassing load costs the memory system as much as a wide one.
-template <int V>
-__device__ __forceinline__ void coherent_store_v(float *p, const float (&x)[V])
-{
-    if constexpr (V % 2 == 0) {
-#pragma unroll
-        for (int v = 0; v < V; v += 2) {
-            const unsigned long long bits = (unsigned long long)__float_as_uint(x[v]) |
-                                            ((unsigned long long)__float_as_uint(x[v + 1]) << 32);
-            __hip_atomic_store(reinterpret_cast<unsigned long long *>(p + v), bits, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        }
-    } else {
-#pragma unroll
-        for (int v = 0; v < V; ++v) coherent_store(p + v, x[v]);
-    }
-}
-template <int V>
-__device__ __forceinline__ void coherent_load_v(const float *p, float (&x)[V])
-{
-    if constexpr (V % 2 == 0) {
-#pragma unroll
-        for (int v = 0; v < V; v += 2) {
-            const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p + v),
-                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            x[v] = __uint_as_float((unsigned)(bits & 0xffffffffull));
-            x[v + 1] = __uint_as_float((unsigned)(bits >> 32));
-        }
-    } else {
-#pragma unroll
-        for (int v = 0; v < V; ++v) x[v] = coherent_load(p + v);
     }
 }
 
@@ -419,65 +388,103 @@ __device__ __forceinline__ void chain_step(float Tr, float Ti, float hr, float h
 }
 
 // Decoupled look-back, run by one group of LPR consecutive threads of a wave (thread lv of the
-// group owns V lanes at lane offset `lo` of the tile slots).  `pred` is the chain predecessor's
-// tile index, `depth` the number of tiles before this one in the chain (the chain's first tile
-// always publishes a prefix).
-//   Pass 1: the group reads the status words of up to LPR predecessors at once (one memory round
-//           trip per window instead of one per tile) until it has found the nearest published
-//           prefix with only aggregates between it and this tile; it waits (bounded) on a tile
-//           that has published nothing yet.
-//   Pass 2: walks forward again from that prefix through the aggregates with chain_step().
+// group owns V lanes at lane offset `lo` of the tile slots; a slot is [2][JB] tagged words).
+// `pred` is the chain predecessor's tile index, `depth` the number of tiles before this one in the
+// chain (the chain's first tile always publishes a prefix).
+//   The group reads the prefixes AND aggregates of the next NB predecessors in one round trip; a
+//   tile's words count only when all of the group's lanes found their tags valid.  It stops at the
+//   nearest tile with a valid prefix, provided every nearer tile has a valid aggregate; it waits
+//   (bounded, polling one word per lane) on the nearest tile that has published nothing yet.  Then it walks forward from that
+//   prefix through the aggregates with chain_step(), from the registers of the last window and, for
+//   nearer tiles seen in earlier windows, by reading them again (published words never change
+//   within a call).  In the common case -- a prefix within NB tiles -- that is one round trip.
 // Returns false if a wait gave up (the carry is then meaningless).
-template <int V, bool CONJ, int LPR>
-__device__ __forceinline__ bool look_back(const uint32_t *flags, const float *agg, const float *pre,
-                                          uint32_t pred, uint32_t stride, int depth, int JB, int lo, int lv,
-                                          const float (&hr)[V], const float (&hi)[V], const float (&qr)[V],
-                                          const float (&qi)[V], uint32_t spin_limit, uint32_t epoch,
-                                          float (&cr)[V], float (&ci)[V], uint32_t *own_agg_flag = nullptr)
+template <int V, bool CONJ, int LPR, int NB>
+__device__ __forceinline__ bool look_back(const tagged_t *agg, const tagged_t *pre, uint32_t pred, uint32_t stride,
+                                          int depth, int JB, int lo, int lv, const float (&hr)[V],
+                                          const float (&hi)[V], const float (&qr)[V], const float (&qi)[V],
+                                          uint32_t spin_limit, uint32_t tag, float (&cr)[V], float (&ci)[V])
 {
-    // own_agg_flag: this tile's status word when its aggregate stores are still in flight; it is set
-    // to ST_AGG once they have completed, which is waited for together with the first window.
     const int gshift = (int)(threadIdx.x & 63) - lv;
     const unsigned long long gmask = LPR >= 64 ? ~0ull : ((1ull << LPR) - 1ull);
-    int base = 0;   // tiles pred, pred-stride, ..., pred-(base-1)*stride are known to hold aggregates
-    int k = -1;     // distance of the nearest prefix
+    auto group_all = [&](bool ok) { return ((__ballot(ok) >> gshift) & gmask) == gmask; };
+    int base = 0;       // tiles at distance < base are known to hold aggregates
     uint32_t spins = 0;
-    while (base < depth) {
-        const int w = depth - base < LPR ? depth - base : LPR;
-        uint32_t st = ST_AGG;
-        if (lv < w) st = status_load(flags + (size_t)(pred - (uint32_t)(base + lv) * stride) * FLAG_STRIDE, epoch);
-        if (own_agg_flag) {
-            wait_stores_done();
-            if (lv == 0) status_store(own_agg_flag, epoch, ST_AGG);
-            own_agg_flag = nullptr;
+    float ar[NB][V], ai[NB][V];      // aggregates of the current window
+    int found = -1;                  // position of the prefix in the current window
+    while (true) {
+        const int w = depth - base < NB ? depth - base : NB;
+        bool pok[NB], aok[NB];
+        float pr_[NB][V], pi_[NB][V];
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            const int dd = n < w ? base + n : base;      // (positions past the chain's start repeat a valid one)
+            const size_t slot = (size_t)(pred - (uint32_t)dd * stride) * 2 * JB + lo;
+            pok[n] = aok[n] = true;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const tagged_t w0 = tagged_load(pre + slot + v), w1 = tagged_load(pre + slot + JB + v);
+                const tagged_t w2 = tagged_load(agg + slot + v), w3 = tagged_load(agg + slot + JB + v);
+                pok[n] = pok[n] && tagged_ok(w0, tag) && tagged_ok(w1, tag);
+                aok[n] = aok[n] && tagged_ok(w2, tag) && tagged_ok(w3, tag);
+                pr_[n][v] = tagged_value(w0); pi_[n][v] = tagged_value(w1);
+                ar[n][v] = tagged_value(w2);  ai[n][v] = tagged_value(w3);
+            }
         }
         compiler_fence();
-        const unsigned long long m_none = (__ballot(st == ST_NONE) >> gshift) & gmask;
-        const unsigned long long m_pre = (__ballot(st >= ST_PREFIX) >> gshift) & gmask;
-        const int fn = m_none ? __builtin_ctzll(m_none) : 64;
-        const int fp = m_pre ? __builtin_ctzll(m_pre) : 64;
-        if (fp < fn) { k = base + fp; break; }
-        if (fn < 64) {
-            base += fn;
-            if (++spins > spin_limit) return false;
-            __builtin_amdgcn_s_sleep(1);
+        int stall = -1;
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            if (found < 0 && stall < 0 && n < w) {
+                if (group_all(pok[n])) {
+                    found = n;
+#pragma unroll
+                    for (int v = 0; v < V; ++v) { cr[v] = pr_[n][v]; ci[v] = pi_[n][v]; }
+                } else if (!group_all(aok[n])) {
+                    stall = n;
+                }
+            }
+        }
+        if (found >= 0) break;
+        if (stall >= 0) {           // the tile at base + stall has published nothing yet
+            base += stall;
+            // wait for it on one word per lane (a light poll), then read the window again.  The
+            // chain's first tile publishes a prefix only; every other tile publishes its aggregate first.
+            const tagged_t *probe = (base == depth - 1 ? pre : agg) + (size_t)(pred - (uint32_t)base * stride) * 2 * JB + lo;
+            while (true) {
+                if (++spins > spin_limit) return false;
+                __builtin_amdgcn_s_sleep(1);
+                if (group_all(tagged_ok(tagged_load(probe), tag))) break;
+            }
         } else {
-            base += w;
+            base += w;              // aggregates only: look further back
+            if (base >= depth) return false;   // cannot happen: the chain's first tile publishes a prefix
         }
     }
-    if (k < 0) return false;   // cannot happen: the chain's first tile publishes a prefix
-    const float *src = pre + (size_t)(pred - (uint32_t)k * stride) * 2 * JB + lo;
-    coherent_load_v<V>(src, cr);
-    coherent_load_v<V>(src + JB, ci);
-    constexpr int NB = 4;      // aggregates fetched per round trip
-    for (int d = k - 1; d >= 0; d -= NB) {
-        float er[NB][V], ei[NB][V];
+    // forward again: first the aggregates of the last window, nearest last
+#pragma unroll
+    for (int n = NB - 1; n >= 0; --n) {
+        if (n < found) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                float nr, ni;
+                chain_step<CONJ>(ar[n][v], ai[n][v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
+                cr[v] = nr;
+                ci[v] = ni;
+            }
+        }
+    }
+    // then the tiles of earlier windows (nearer than `base`)
+    for (int d = base - 1; d >= 0; d -= NB) {
 #pragma unroll
         for (int n = 0; n < NB; ++n) {
             const int dd = d - n < 0 ? 0 : d - n;
-            const float *ag = agg + (size_t)(pred - (uint32_t)dd * stride) * 2 * JB + lo;
-            coherent_load_v<V>(ag, er[n]);
-            coherent_load_v<V>(ag + JB, ei[n]);
+            const size_t slot = (size_t)(pred - (uint32_t)dd * stride) * 2 * JB + lo;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                ar[n][v] = tagged_value(tagged_load(agg + slot + v));
+                ai[n][v] = tagged_value(tagged_load(agg + slot + JB + v));
+            }
         }
 #pragma unroll
         for (int n = 0; n < NB; ++n) {
@@ -485,7 +492,7 @@ __device__ __forceinline__ bool look_back(const uint32_t *flags, const float *ag
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     float nr, ni;
-                    chain_step<CONJ>(er[n][v], ei[n][v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
+                    chain_step<CONJ>(ar[n][v], ai[n][v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
                     cr[v] = nr;
                     ci[v] = ni;
                 }
