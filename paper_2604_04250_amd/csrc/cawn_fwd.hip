@@ -13,11 +13,14 @@
 // clamps and stores.  Per token-lane HBM traffic: 8 bytes in, 8 bytes out.
 //
 // Scheduling.  The kernel is persistent: about as many workgroups as fit on the chip are launched
-// and each loops over tiles.  Work is split into queues (a queue owns every nQ-th lane block, so a
-// workgroup keeps its lane constants in registers); a queue hands out its tiles in time order from
-// an atomic ticket, so a tile only ever waits for tiles that a running workgroup already holds.
-// The ticket and the input rows of the NEXT tile are fetched while the current tile is in its
-// communication phase, whose memory round trips would otherwise leave the SIMDs idle.
+// and each loops over tiles, handed out by one atomic ticket in the order (time tile, batch row,
+// lane block).  Tickets go out in time order, so a tile only ever waits for tiles that a running
+// workgroup already holds; all chains advance together, so tiles that happen to be slow (some
+// address classes of the 128-byte lane-block rows are, by a quarter) are spread over every
+// workgroup instead of leaving a few chains to finish alone; and the lane blocks of one row are
+// in flight together, which keeps DRAM pages busy.  The ticket, the input rows and the lane
+// constants of the NEXT tile are fetched while the current tile is in its communication phase,
+// whose memory round trips would otherwise leave the SIMDs idle.
 #include <type_traits>
 
 #include "cawn_internal.hpp"
@@ -67,21 +70,43 @@ template <> struct Vec<4> {
     }
 };
 
-// Position of a queue's ticket in the problem.
+// Position of a ticket in the problem: tickets count (time tile, batch row, lane block), lane block fastest.
 struct TileId {
     int lb, b, tt;
-    uint32_t id;     // unique tile index; the chain predecessor is id - B
+    uint32_t id;     // unique tile index (workspace slot); the chain predecessor is id - B
 };
-__device__ __forceinline__ TileId decode_tile(uint32_t ticket, int q, int nQ, int B, int nT)
+__device__ __forceinline__ TileId decode_tile(uint32_t ticket, int nLB, int B, int nT)
 {
-    const uint32_t per_lb = (uint32_t)B * nT;
-    const uint32_t li = ticket / per_lb, r = ticket - li * per_lb;
+    const uint32_t per_tt = (uint32_t)B * nLB;
+    const uint32_t tt = ticket / per_tt, r = ticket - tt * per_tt;
     TileId t;
-    t.lb = q + (int)li * nQ;
-    t.tt = (int)(r / B);
-    t.b = (int)(r - (uint32_t)t.tt * B);
+    t.tt = (int)tt;
+    t.b = (int)(r / nLB);
+    t.lb = (int)(r - (uint32_t)t.b * nLB);
     t.id = ((uint32_t)t.lb * nT + t.tt) * B + t.b;
     return t;
+}
+
+// Stage the lane constants a forward tile keeps in registers (table rows R_LR .. R_LR + NCR - 1 of
+// lane block lb) in LDS, 16 bytes per lane per load: 8 lanes cover a 32-lane row, a wave 8 rows.
+// Called by one wave.  Table rows are 256-byte aligned and padded, so every address is valid.
+template <int NCR, int JB>
+__device__ __forceinline__ void stage_consts(float *sC, const float *table, int Jp, int lb, int lane)
+{
+    static_assert(JB == 32, "8 lanes x 16 bytes per row");
+    const int r_in = lane >> 3, c_in = (lane & 7) * 4;
+    const float *src = table + ((size_t)(R_LR + r_in) * Jp + (size_t)lb * JB + c_in);
+#pragma unroll
+    for (int i = 0; i < (NCR + 7) / 8; ++i) {
+        if (i * 8 + r_in < NCR) {
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_global_load_lds(src + (size_t)(i * 8) * Jp, sC + (size_t)(i * 8) * JB, 16, 0, 0);
+#else
+            (void)src;
+            (void)sC;
+#endif
+        }
+    }
 }
 
 template <int V, int KC>
@@ -100,21 +125,21 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     __shared__ __attribute__((aligned(16))) float sU[2 * NRTP][JB];   // [stream*NRTP + rr][lane]
     __shared__ float sE[NSEG][2][JB];
     __shared__ float sCarry[2][JB];
+    constexpr int NCR = R_W0 - R_LR + 2 * KC;     // staged lane-constant rows
+    __shared__ __attribute__((aligned(16))) float sC[(NCR + 7) / 8 * 8][JB];
     __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid = threadIdx.x;
     const int lv = tid % LPR, seg = tid / LPR;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // (wave index: scalar)
-    const int q = blockIdx.x % a.nQ;
-    const int nLBq = (a.nLB - q + a.nQ - 1) / a.nQ;
-    const uint32_t qtiles = (uint32_t)nLBq * a.B * a.nT;
+    const uint32_t qtiles = (uint32_t)a.nLB * a.B * a.nT;     // all tiles of the call
     const bool is_tail_seg = seg == NSEG - 1;
     const bool owner_wave = wave == NW - 1;        // the wave holding the last segment owns the chain
     const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
 
     if (tid == 0) {
         const uint32_t e = flag_load(&a.hdr->epoch);     // both round trips at once
-        const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sEpoch = e;
         sTicket[0] = t;
         sLast = 0;
@@ -130,6 +155,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     const int ist32 = (int)a.ist;
     auto stage_tile = [&](const TileId &T) {
         if (owner_wave) return;
+        if (wave == 0) stage_consts<NCR, JB>(&sC[0][0], a.table, a.Jp, T.lb, lane);
         if (a.stage16)
             stage_rows<TILE_T, JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
                                      ist32, wave, NW - 1, lane);
@@ -140,7 +166,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 
     TileId T{};
     if (ticket < qtiles) {
-        T = decode_tile(ticket, q, a.nQ, a.B, a.nT);
+        T = decode_tile(ticket, a.nLB, a.B, a.nT);
         stage_tile(T);
         // Start-up skew.  All workgroups start together; left alone, the workgroups that hold the
         // consecutive tiles of one chain would reach their look-back at the same instant, find only
@@ -158,7 +184,6 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 
     float lr[V], li[V], pfr[V], pfi[V], psr[V], psi[V];
     float wm[KC1][V], wa[KC1][V], bm[V], ba[V];
-    int lb_loaded = -1;
 
     for (int it = 0; ticket < qtiles; ++it) {
         const uint32_t id = T.id;
@@ -172,45 +197,41 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         uint32_t ticket_ahead;   // (only thread 0's copy is ever set or read; no initialiser, so no
                              // merge of values that would wait for the atomic right here)
         if (tid == 0)
-            ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
-        // ---- lane constants (change only when the queue moves on to its next lane block)
-        if (T.lb != lb_loaded) {
-            lb_loaded = T.lb;
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                lr[v] = li[v] = pfr[v] = pfi[v] = psi[v] = bm[v] = ba[v] = 0.f;
-                psr[v] = 1.f;
-#pragma unroll
-                for (int k = 0; k < KC1; ++k) wm[k][v] = wa[k][v] = 0.f;
-            }
-            if (active) {
-                const float *tb = a.table + j0;
-                Vec<V>::ld(lr, tb + (size_t)R_LR * a.Jp);
-                Vec<V>::ld(li, tb + (size_t)R_LI * a.Jp);
-                Vec<V>::ld(pfr, tb + (size_t)(R_PSEG + 2) * a.Jp);       // lambda^NSTEP
-                Vec<V>::ld(pfi, tb + (size_t)(R_PSEG + 3) * a.Jp);
-                Vec<V>::ld(psr, tb + (size_t)(R_PSEG + 2 * seg) * a.Jp); // lambda^(NSTEP*seg)
-                Vec<V>::ld(psi, tb + (size_t)(R_PSEG + 2 * seg + 1) * a.Jp);
-                if (KC > 0) {
-                    Vec<V>::ld(bm, tb + (size_t)R_BIAS_M * a.Jp);
-                    Vec<V>::ld(ba, tb + (size_t)R_BIAS_A * a.Jp);
-#pragma unroll
-                    for (int k = 0; k < KC; ++k) {
-                        Vec<V>::ld(wm[k], tb + (size_t)(R_W0 + k) * a.Jp);
-                        Vec<V>::ld(wa[k], tb + (size_t)(R_W0 + KC + k) * a.Jp);
-                    }
-                }
-            }
-            // waited for here, inside the rare branch: left to the compiler, the wait would sit at the
-            // first use, on every iteration, and drain the previous tile's output stores with it
-            wait_vm<0>();
-        }
+            ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---- the staged rows have landed (each wave waited for its own loads: before the loop, or
         //      at the end of the previous iteration)
         lds_barrier();
         CAWN_STAMP(0);
+
+        // ---- lane constants of this tile's lane block, staged with its rows
+        {
+            auto cst = [&](float(&d)[V], int r) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) d[v] = sC[r - R_LR][lv * V + v];
+            };
+            cst(lr, R_LR);
+            cst(li, R_LI);
+            cst(pfr, R_PSEG + 2);                 // lambda^NSTEP
+            cst(pfi, R_PSEG + 3);
+            cst(psr, R_PSEG + 2 * seg);           // lambda^(NSTEP*seg)
+            cst(psi, R_PSEG + 2 * seg + 1);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                bm[v] = ba[v] = 0.f;
+#pragma unroll
+                for (int k = 0; k < KC1; ++k) wm[k][v] = wa[k][v] = 0.f;
+            }
+            if (KC > 0) {
+                cst(bm, R_BIAS_M);
+                cst(ba, R_BIAS_A);
+#pragma unroll
+                for (int k = 0; k < KC; ++k) {
+                    cst(wm[k], R_W0 + k);
+                    cst(wa[k], R_W0 + KC + k);
+                }
+            }
+        }
 
         // ---- front-end, phasors, local scan from zero.  Rows come from LDS as a sliding window.
         float pr[NSTEP][V], pi[NSTEP][V];
@@ -322,7 +343,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         const uint32_t next_ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
         TileId Tn{};
         if (next_ticket < qtiles) {
-            Tn = decode_tile(next_ticket, q, a.nQ, a.B, a.nT);
+            Tn = decode_tile(next_ticket, a.nLB, a.B, a.nT);
             stage_tile(Tn);
         }
 
@@ -632,7 +653,7 @@ static hipError_t launch_step(const FwdArgs &a, int conv_k, hipStream_t s)
 template <int V, int KC>
 static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
 {
-    // persistent grid: what fits on the chip (asked once per kernel), a whole number of workgroups per queue
+    // persistent grid: what fits on the chip (asked once per kernel)
     static int per_cu = 0, cus = 0;
     if (per_cu == 0) {
         int dev = 0, n = 0;
@@ -645,16 +666,12 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     }
     FwdArgs a = a0;
     const long long resident = (long long)per_cu * cus;
-    a.nQ = a.nLB < MAX_QUEUES ? a.nLB : MAX_QUEUES;
-    if (a.nQ > resident) a.nQ = (int)resident;
-    const long long per_queue_tiles = (long long)((a.nLB + a.nQ - 1) / a.nQ) * a.B * a.nT;
-    long long wq = resident / a.nQ;
-    if (wq > per_queue_tiles) wq = per_queue_tiles;
-    if (wq < 1) wq = 1;
-    // skew so that the ~wq/B workgroups working on one chain spread over one iteration (~10 us)
-    const long long per_chain = wq / a.B > 0 ? wq / a.B : 1;
+    const long long tiles = (long long)a.nLB * a.B * a.nT;
+    const long long wgs = tiles < resident ? (tiles > 0 ? tiles : 1) : resident;
+    // skew so that the workgroups working on one chain at a time spread over one iteration (~5 us)
+    const long long per_chain = wgs / ((long long)a.B * a.nLB);
     a.stagger_ticks = per_chain > 1 ? (int)(CAWN_FWD_ITER_TICKS / per_chain) : 0;
-    dim3 grid((unsigned)(wq * a.nQ)), block(FwdGeom::NSEG * FwdLPR);
+    dim3 grid((unsigned)wgs), block(FwdGeom::NSEG * FwdLPR);
     hipLaunchKernelGGL((fwd_kernel<V, KC>), grid, block, 0, s, a);
     return hipGetLastError();
 }

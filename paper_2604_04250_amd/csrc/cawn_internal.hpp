@@ -65,16 +65,18 @@ constexpr uint32_t MAX_TILES = 1u << 18;   // most tiles one call may have (tile
 // Per-lane constants, struct-of-arrays, each row Jp floats (Jp = J rounded up to 64), built in
 // fp64 by a small kernel from gamma, theta, conv_w, conv_b.
 enum LaneRow : int {
-    R_LR = 0, R_LI,            // lambda = gamma e^{i theta}
-    R_COS, R_SIN, R_GAMMA,     // e^{i theta}, gamma
+    R_COS = 0, R_SIN, R_GAMMA, // e^{i theta}, gamma
     R_PT_HR, R_PT_HI,          // lambda^(forward TILE_T), leading fp32 part
     R_PT_LR, R_PT_LI,          //                          remainder (double-float)
     R_PTB_HR, R_PTB_HI,        // the same for the backward tile length
     R_PTB_LR, R_PTB_LI,
-    R_BIAS_M, R_BIAS_A,
-    R_PSEG,                    // R_PSEG + 2*s (+1): re (im) of lambda^(NSTEP*s), forward segments
-    R_PSEGB = R_PSEG + 2 * FwdGeom::NSEG,   // the same for the backward segments
-    R_W0 = R_PSEGB + 2 * BwdGeom::NSEG      // R_W0 + s*conv_k + i : tap i of stream s
+    R_PSEGB,                   // R_PSEGB + 2*s (+1): re (im) of lambda^(NSTEP*s), backward segments
+    // The rows below are what a forward tile's threads keep in registers; they are contiguous so
+    // that a tile stages them in LDS with a few wide loads (R_LR .. R_W0 + 2*conv_k - 1).
+    R_LR = R_PSEGB + 2 * BwdGeom::NSEG, R_LI,   // lambda = gamma e^{i theta}
+    R_PSEG,                    // R_PSEG + 2*s (+1): the same powers for the forward segments
+    R_BIAS_M = R_PSEG + 2 * FwdGeom::NSEG, R_BIAS_A,
+    R_W0                       // R_W0 + s*conv_k + i : tap i of stream s
 };
 inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k; }
 
@@ -89,7 +91,7 @@ inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k;
 // advances the epoch.
 constexpr int MAX_QUEUES = 64;
 struct WsHeader {
-    uint32_t ticket[MAX_QUEUES];   // per work queue: next tile to hand out
+    uint32_t ticket[MAX_QUEUES];   // ticket[0]: next tile to hand out (the other words are spare)
     uint32_t done;                 // tiles finished
     uint32_t error;                // sticky: a tile gave up waiting
     uint32_t epoch;                // calls completed on this workspace (mod 2^30): tag of published words - 1
@@ -122,7 +124,6 @@ struct FwdArgs {
     tagged_t *agg, *pre;
     int B, L, J, Jp, nT, nLB;    // nT: forward tiles per sequence
     int nTc;                     // checkpoint intervals per sequence
-    int nQ;                      // work queues (a queue owns lane blocks q, q+nQ, ...)
     int stagger_ticks;           // start-up skew per time tile, in 10 ns ticks (see fwd kernel)
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int amp_mode;
@@ -148,7 +149,6 @@ struct BwdArgs {
     tagged_t *agg, *pre, *halo;
     float *part;
     int B, L, J, Jp, nT, nLB;
-    int nQ;
     int small_angle;
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int amp_mode, want_param;
