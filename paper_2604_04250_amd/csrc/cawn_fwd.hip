@@ -28,10 +28,7 @@
 namespace cawn {
 
 #ifndef CAWN_FWD_NB
-#define CAWN_FWD_NB 4       // predecessors read per look-back round trip
-#endif
-#ifndef CAWN_FWD_ITER_TICKS
-#define CAWN_FWD_ITER_TICKS 500      // start-up skew spread over this many 10 ns ticks per chain
+#define CAWN_FWD_NB 2       // predecessors read per look-back round trip
 #endif
 
 // Tuning aid, compiled only with -DCAWN_TIMING: per-tile time stamps (100 MHz counter) of the
@@ -168,16 +165,6 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     if (ticket < qtiles) {
         T = decode_tile(ticket, a.nLB, a.B, a.nT);
         stage_tile(T);
-        // Start-up skew.  All workgroups start together; left alone, the workgroups that hold the
-        // consecutive tiles of one chain would reach their look-back at the same instant, find only
-        // aggregates and walk back over all of them, every iteration.  Starting tile tt of a chain
-        // a little later than tile tt-1 turns the chain into a pipeline: by the time a tile looks
-        // back, its predecessor has usually published its prefix.
-        if (a.stagger_ticks > 0 && T.tt > 0) {
-            const unsigned long long t_begin = wall_clock64();
-            const unsigned long long wait = (unsigned long long)T.tt * a.stagger_ticks;
-            while (wall_clock64() - t_begin < wait) __builtin_amdgcn_s_sleep(8);
-        }
     }
 
     wait_vm<0>();     // the first tile's staged rows
@@ -668,9 +655,6 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     const long long resident = (long long)per_cu * cus;
     const long long tiles = (long long)a.nLB * a.B * a.nT;
     const long long wgs = tiles < resident ? (tiles > 0 ? tiles : 1) : resident;
-    // skew so that the workgroups working on one chain at a time spread over one iteration (~5 us)
-    const long long per_chain = wgs / ((long long)a.B * a.nLB);
-    a.stagger_ticks = per_chain > 1 ? (int)(CAWN_FWD_ITER_TICKS / per_chain) : 0;
     dim3 grid((unsigned)wgs), block(FwdGeom::NSEG * FwdLPR);
     hipLaunchKernelGGL((fwd_kernel<V, KC>), grid, block, 0, s, a);
     return hipGetLastError();

@@ -124,7 +124,6 @@ struct FwdArgs {
     tagged_t *agg, *pre;
     int B, L, J, Jp, nT, nLB;    // nT: forward tiles per sequence
     int nTc;                     // checkpoint intervals per sequence
-    int stagger_ticks;           // start-up skew per time tile, in 10 ns ticks (see fwd kernel)
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int amp_mode;
     int small_angle;             // angles are bounded (conv clamp): skip the two-term range reduction
