@@ -35,9 +35,30 @@ def build(verbose: bool = False, defines=(), out: str = OUT, objdir: str = CSRC)
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         cmd = [hipcc, *FLAGS, *FILE_FLAGS.get(src, []), *[f"-D{d}" for d in defines], "-c",
                os.path.join(CSRC, src), "-o", obj]
+        # the compiler's per-kernel resource report (registers, scratch, occupancy) goes to a text
+        # file beside the object; tests read it to catch a kernel that starts to spill
+        cmd.insert(-4, "-Rpass-analysis=kernel-resource-usage")
         if verbose:
             print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
+        r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+        report, rest, in_remark = [], [], False
+        for line in r.stderr.splitlines():
+            if "[-Rpass-analysis=kernel-resource-usage]" in line:
+                report.append(line)
+                in_remark = True
+            elif in_remark and line.lstrip()[:1].isdigit() is False and "|" in line[:12] or \
+                    in_remark and line.lstrip().split(" ", 1)[0].isdigit() and "|" in line[:12]:
+                pass            # the source excerpt and caret under a remark
+            else:
+                rest.append(line)
+                in_remark = False
+        if rest:
+            print("\n".join(rest), file=sys.stderr, flush=True)
+        if r.returncode != 0:
+            raise subprocess.CalledProcessError(r.returncode, cmd)
+        with open(obj[:-2] + ".res.txt", "w") as f:
+            for line in report:
+                f.write(line.split("remark: ", 1)[-1].replace(" [-Rpass-analysis=kernel-resource-usage]", "").strip() + "\n")
         return obj
 
     with ThreadPoolExecutor(max_workers=4) as ex:

@@ -261,10 +261,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             }
         }
     }
-    // the staged rows have landed (a wave's memory operations complete in order: the head wave
-    // does not wait for its aggregate's stores, issued after its share of the rows)
-    if (wave == 0 && chained && feeds) wait_vm<2 * V>();
-    else wait_vm<0>();
+    // the staged rows have landed
+    wait_stores_done();
     lds_barrier();
     BWD_STAMP(3);
 

@@ -91,3 +91,67 @@ def test_host_side_argument_checks_reject_before_any_launch():
     assert L.cawn_workspace_init(fake, 16, null) == K.CAWN_EWORKSPACE
     args_b = [null] * 19
     assert L.cawn_phase_accumulate_bwd(C.byref(d), *args_b, 0, null) != K.CAWN_OK
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """A C99 translation unit that includes the header, fills a descriptor and calls the size
+    helpers compiles without warnings and links against the shared library (no compute call)."""
+    import shutil
+    import subprocess
+
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include "cawn.h"\n'
+        "#include <stdio.h>\n"
+        "#include <string.h>\n"
+        "int main(void) {\n"
+        "    cawn_desc d;\n"
+        "    memset(&d, 0, sizeof d);\n"
+        "    d.B = 2; d.L = 300; d.H = 3; d.F = 32; d.conv_k = 4;\n"
+        "    d.conv_clamp = 50.f; d.out_clamp = 100.f; d.grad_clamp = 100.f; d.gate_tau = 0.1f;\n"
+        '    printf("%zu %zu %zu %d %s\\n", cawn_state_bytes(&d), cawn_workspace_bytes(&d),\n'
+        "           cawn_ckpt_bytes(&d), (int)cawn_tile_len(), cawn_status_string(CAWN_EWORKSPACE));\n"
+        "    /* a compute entry point with a null required pointer is refused on the host */\n"
+        "    return cawn_phase_accumulate_fwd(&d, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) == CAWN_EINVAL ? 0 : 1;\n"
+        "}\n")
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(K.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I",
+                           os.path.join(ROOT, "include"), str(src), "-o", str(exe), "-L", libdir,
+                           "-l:libcawn.so", "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stderr
+    st, ws, ck, tl, msg = out.stdout.split(None, 4)
+    J = 96
+    assert int(st) == 2 * 2 * J * 4 * (1 + 3)
+    assert int(ws) == K.cawn_workspace_bytes(K.make_desc(2, 300, 3, 32, conv_k=4))
+    assert int(ck) == 2 * -(-300 // int(tl)) * 2 * J * 4
+    assert msg.strip() == K.cawn_status_string(-3)
+
+
+def test_kernels_do_not_spill_and_keep_their_occupancy():
+    """The compiler's resource report of the last build: the scan kernels use no scratch memory
+    (a spill in their loops costs far more than it looks) and keep the waves per SIMD their
+    geometry was chosen for."""
+    import glob
+
+    reports = glob.glob(os.path.join(ROOT, "paper_2604_04250_amd", "csrc", "*.res.txt"))
+    if not reports:
+        pytest.skip("no resource report: library was not built by paper_2604_04250_amd.build")
+    seen = 0
+    for path in reports:
+        name = None
+        for line in open(path):
+            key, _, val = line.partition(":")
+            if key == "Function Name":
+                name = val.strip()
+            elif name and ("fwd_kernel" in name or "bwd_kernel" in name or "step_kernel" in name):
+                if key.startswith("ScratchSize"):
+                    assert int(val) == 0, (name, line)
+                    seen += 1
+                elif key.startswith("Occupancy"):
+                    want = 4 if "bwd_kernel" in name else 2
+                    assert int(val) >= want, (name, line)
+    assert seen >= 15       # 5 tap counts x (forward, short-call forward, backward with/without parameters)
