@@ -11,6 +11,11 @@
  *     SiLU.
  *   - Gated phasor push (Sec. 3.3 hard-threshold gate with straight-through estimator;
  *     Sec. 3.4 gated-push equations): p = g * a * (cos phi, sin phi).
+ *   - gate_mode 1, the input valve as Sec. 3.3 states it ("Hard-Threshold Gating"): one logit
+ *     v per (token, head); beta_sig = sigmoid(v - 3); beta_hard = beta_sig if beta_sig >= eps
+ *     else 0; forward p = beta_hard * a * (cos phi, sin phi) (Sec. 3.4 gated-push equations);
+ *     backward through beta = beta_hard - sg(beta_sig) + beta_sig, i.e. d beta / d v =
+ *     beta_sig (1 - beta_sig) whatever the threshold did.  No per-lane threshold in this mode.
  *   - Causal phase accumulation (Sec. 3.4 accumulation equations, real form):
  *       S_r[t] = p_r[t] + gamma (S_r[t-1] cos th - S_i[t-1] sin th)
  *       S_i[t] = p_i[t] + gamma (S_r[t-1] sin th + S_i[t-1] cos th),  S[-1] = state_in or 0.
@@ -52,7 +57,9 @@ typedef struct {
     int32_t amp_mode;        /* 0: a = m;  1: a = min(softplus(m), 10) (Sec. 3.3 item 1)   */
     int32_t clamp_feedback;  /* 0: clamp only what is emitted; 1: carry the clamped value  */
     int32_t nthreads;        /* <=0: leave the OpenMP default                              */
+    int32_t gate_mode;       /* 0: per-lane threshold on |a|;  1: per-head valve (Sec. 3.3) */
     float gate_tau;          /* threshold, same fp32 value the GPU gets; 0 = open           */
+    float valve_eps;         /* gate_mode 1: the valve closes below this (paper: 0.001)     */
     float pad_;
     double conv_clamp;       /* 50 in the paper; +inf disables                              */
     double out_clamp;        /* 100; +inf disables                                          */
@@ -151,12 +158,14 @@ typedef struct {
     double zm, za;   /* conv pre-activations (fp64); the raw inputs when conv_k = 0 */
     double m, phi;   /* magnitude-stream and angle-stream values after the front-end */
     double a;        /* amplitude */
-    int g;           /* gate */
+    int g;           /* gate (gate_mode 1: the valve is open) */
+    double scale;    /* what multiplies a e^{i phi} in the forward: g, or beta_hard */
+    double bsig;     /* gate_mode 1: sigmoid(v - 3) */
 } front_t;
 
 static front_t front_end(const oracle_cfg *c, const float *mag, const float *ang,
-                         const float *conv_w, const float *conv_b, const float *tail_in, int b,
-                         int t, int j)
+                         const float *valve, const float *conv_w, const float *conv_b,
+                         const float *tail_in, int b, int t, int j)
 {
     const int J = c->H * c->F, L = c->L, Kc = c->conv_k;
     front_t f;
@@ -190,7 +199,17 @@ static front_t front_end(const oracle_cfg *c, const float *mag, const float *ang
         gate_arg = f.zm;
     }
     f.a = amp(c->amp_mode, f.m);
-    f.g = fabs(amp(c->amp_mode, gate_arg)) >= (double)c->gate_tau ? 1 : 0;
+    if (c->gate_mode == 1) {
+        /* the decision is taken on the fp32 logit, evaluated in fp64 */
+        const double v = (double)valve[((size_t)b * L + t) * c->H + j / c->F];
+        f.bsig = sigmoid(v - 3.0);
+        f.g = f.bsig >= (double)c->valve_eps ? 1 : 0;
+        f.scale = f.g ? f.bsig : 0.0;
+    } else {
+        f.g = fabs(amp(c->amp_mode, gate_arg)) >= (double)c->gate_tau ? 1 : 0;
+        f.scale = (double)f.g;
+        f.bsig = 0.0;
+    }
     return f;
 }
 
@@ -202,12 +221,13 @@ static front_t front_end(const oracle_cfg *c, const float *mag, const float *ang
  *   z_re, z_im [B][L][J] fp64          scan_out [B][2][J] fp64 or NULL (unclamped S[L-1])
  *   tail_out   [B][Kc-1][2][J] fp32 or NULL      gate [B][L][J] bytes (0/1) or NULL
  */
-int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, const float *gamma,
-                     const float *theta, const float *conv_w, const float *conv_b,
+int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, const float *valve,
+                     const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                      const double *scan_in, const float *tail_in, double *z_re, double *z_im,
                      double *scan_out, float *tail_out, uint8_t *gate)
 {
     if (!c || c->B <= 0 || c->L < 0 || c->H <= 0 || c->F <= 0 || c->conv_k < 0) return -1;
+    if (c->gate_mode == 1 && !valve) return -1;
     const int B = c->B, L = c->L, J = c->H * c->F, Kc = c->conv_k;
 #ifdef _OPENMP
     if (c->nthreads > 0) omp_set_num_threads(c->nthreads);
@@ -219,9 +239,9 @@ int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, co
         double Sr = scan_in ? scan_in[((size_t)b * 2 + 0) * J + j] : 0.0;
         double Si = scan_in ? scan_in[((size_t)b * 2 + 1) * J + j] : 0.0;
         for (int t = 0; t < L; ++t) {
-            front_t f = front_end(c, mag, ang, conv_w, conv_b, tail_in, b, t, j);
-            double pr = f.g ? f.a * cos(f.phi) : 0.0;
-            double pi = f.g ? f.a * sin(f.phi) : 0.0;
+            front_t f = front_end(c, mag, ang, valve, conv_w, conv_b, tail_in, b, t, j);
+            double pr = f.g ? f.scale * f.a * cos(f.phi) : 0.0;
+            double pi = f.g ? f.scale * f.a * sin(f.phi) : 0.0;
             double nr = pr + ga * (Sr * ct - Si * st);
             double ni = pi + ga * (Sr * st + Si * ct);
             double zr = clampd(nr, c->out_clamp), zi = clampd(ni, c->out_clamp);
@@ -256,19 +276,22 @@ int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, co
  *   dtail_out    [B][Kc-1][2][J] fp64 or NULL gradient w.r.t. tail_out
  * Outputs (fp64, any may be NULL except dmag, dang):
  *   dmag, dang [B][L][J]; dgamma, dtheta [J]; dconv_w [2][J][Kc]; dconv_b [2][J];
- *   dscan_in [B][2][J]; dtail_in [B][Kc-1][2][J].
+ *   dscan_in [B][2][J]; dtail_in [B][Kc-1][2][J]; gate_mode 1: dvalve [B][L][H] (needs
+ *   valve_term, scratch of [B][L][J] doubles: the per-lane terms, summed per head afterwards).
  * Parameter gradients are overwritten (summed over b and t).
  */
-int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, const float *gamma,
-                     const float *theta, const float *conv_w, const float *conv_b,
+int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, const float *valve,
+                     const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                      const double *scan_in, const float *tail_in, const float *dz_re,
                      const float *dz_im, const double *dscan_out, const double *dtail_out,
                      double *dmag, double *dang, double *dgamma, double *dtheta, double *dconv_w,
-                     double *dconv_b, double *dscan_in, double *dtail_in)
+                     double *dconv_b, double *dscan_in, double *dtail_in, double *dvalve,
+                     double *valve_term)
 {
     if (!c || c->B <= 0 || c->L < 0 || c->H <= 0 || c->F <= 0 || c->conv_k < 0 || c->conv_k > 16)
         return -1;
     if (c->clamp_feedback) return -2;
+    if (c->gate_mode == 1 && (!valve || (dvalve && !valve_term))) return -1;
     const int B = c->B, L = c->L, J = c->H * c->F, Kc = c->conv_k;
     const double gc = c->grad_clamp;
 #ifdef _OPENMP
@@ -291,9 +314,9 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
             Sr[0] = scan_in ? scan_in[((size_t)b * 2 + 0) * J + j] : 0.0;
             Si[0] = scan_in ? scan_in[((size_t)b * 2 + 1) * J + j] : 0.0;
             for (int t = 0; t < L; ++t) {
-                fr[t] = front_end(c, mag, ang, conv_w, conv_b, tail_in, b, t, j);
-                double pr = fr[t].g ? fr[t].a * cos(fr[t].phi) : 0.0;
-                double pi = fr[t].g ? fr[t].a * sin(fr[t].phi) : 0.0;
+                fr[t] = front_end(c, mag, ang, valve, conv_w, conv_b, tail_in, b, t, j);
+                double pr = fr[t].g ? fr[t].scale * fr[t].a * cos(fr[t].phi) : 0.0;
+                double pi = fr[t].g ? fr[t].scale * fr[t].a * sin(fr[t].phi) : 0.0;
                 Sr[t + 1] = pr + ga * (Sr[t] * ct - Si[t] * st);
                 Si[t + 1] = pi + ga * (Sr[t] * st + Si[t] * ct);
             }
@@ -319,7 +342,13 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
                 double hr = clampd(Gr, gc), hi = clampd(Gi, gc);
                 double cph = cos(fr[t].phi), sph = sin(fr[t].phi);
                 double da = hr * cph + hi * sph;                 /* straight-through: no gate */
-                double dphi = fr[t].g ? fr[t].a * (-hr * sph + hi * cph) : 0.0;
+                double dphi = fr[t].g ? fr[t].scale * fr[t].a * (-hr * sph + hi * cph) : 0.0;
+                if (c->gate_mode == 1) {
+                    /* p = beta a e^{i phi}: the valve's value multiplies d/da; its own gradient is
+                       a Re(conj(dp) e^{i phi}), whatever the threshold did (straight-through) */
+                    if (dvalve) valve_term[o] = fr[t].a * da;
+                    da *= fr[t].scale;
+                }
                 double dm = da * damp(c->amp_mode, fr[t].m);
                 if (Kc > 0) {
                     double km = fabs(fr[t].zm) <= c->conv_clamp ? dsilu(fr[t].zm) : 0.0;
@@ -384,5 +413,14 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
         free(fr);
         free(dzc);
     }
+    if (c->gate_mode == 1 && dvalve)
+        for (int b = 0; b < B; ++b)
+            for (int t = 0; t < L; ++t)
+                for (int h = 0; h < c->H; ++h) {
+                    double sum = 0.0;
+                    for (int k = 0; k < c->F; ++k) sum += valve_term[((size_t)b * L + t) * J + h * c->F + k];
+                    const double bs = sigmoid((double)valve[((size_t)b * L + t) * c->H + h] - 3.0);
+                    dvalve[((size_t)b * L + t) * c->H + h] = bs * (1.0 - bs) * sum;
+                }
     return 0;
 }

@@ -38,7 +38,8 @@ def build(force: bool = False) -> str:
 class _Cfg(C.Structure):
     _fields_ = [("B", C.c_int32), ("L", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
                 ("conv_k", C.c_int32), ("amp_mode", C.c_int32), ("clamp_feedback", C.c_int32),
-                ("nthreads", C.c_int32), ("gate_tau", C.c_float), ("pad_", C.c_float),
+                ("nthreads", C.c_int32), ("gate_mode", C.c_int32), ("gate_tau", C.c_float),
+                ("valve_eps", C.c_float), ("pad_", C.c_float),
                 ("conv_clamp", C.c_double), ("out_clamp", C.c_double), ("grad_clamp", C.c_double)]
 
 
@@ -71,6 +72,8 @@ class Cfg:
     grad_clamp: float = 100.0
     clamp_feedback: int = 0
     nthreads: int = 0
+    gate_mode: int = 0          # 1: per-head valve (valve logits [B, L, H]), Sec. 3.3
+    valve_eps: float = 0.001
 
     @property
     def J(self) -> int:
@@ -78,8 +81,8 @@ class Cfg:
 
     def c(self) -> _Cfg:
         return _Cfg(self.B, self.L, self.H, self.F, self.conv_k, self.amp_mode, self.clamp_feedback,
-                    self.nthreads, np.float32(self.gate_tau), 0.0, self.conv_clamp, self.out_clamp,
-                    self.grad_clamp)
+                    self.nthreads, self.gate_mode, np.float32(self.gate_tau),
+                    np.float32(self.valve_eps), 0.0, self.conv_clamp, self.out_clamp, self.grad_clamp)
 
 
 def _p(a):
@@ -129,7 +132,7 @@ def syntax_conv(x, w, bias=None, hist_in=None, conv_clamp=50.0, want_hist=True):
 
 
 def phase_fwd(cfg: Cfg, mag, ang, gamma, theta, conv_w=None, conv_b=None, scan_in=None,
-              tail_in=None, want_gate=True):
+              tail_in=None, want_gate=True, valve=None):
     """Forward.  Returns dict(z_re, z_im [B,L,J] f64, scan_out [B,2,J] f64,
     tail_out [B,Kc-1,2,J] f32 or None, gate [B,L,J] uint8)."""
     B, L, J, Kc = cfg.B, cfg.L, cfg.J, cfg.conv_k
@@ -149,8 +152,9 @@ def phase_fwd(cfg: Cfg, mag, ang, gamma, theta, conv_w=None, conv_b=None, scan_i
     scan_out = np.empty((B, 2, J), dtype=np.float64)
     tail_out = np.empty((B, Kc - 1, 2, J), dtype=np.float32) if Kc > 1 else None
     gate = np.empty((B, L, J), dtype=np.uint8) if want_gate else None
+    valve = _f32(valve, (B, L, cfg.H)) if cfg.gate_mode == 1 else None
     cc = cfg.c()
-    rc = lib().oracle_phase_fwd(C.byref(cc), _p(mag), _p(ang), _p(gamma), _p(theta), _p(conv_w),
+    rc = lib().oracle_phase_fwd(C.byref(cc), _p(mag), _p(ang), _p(valve), _p(gamma), _p(theta), _p(conv_w),
                                 _p(conv_b), _p(scan_in), _p(tail_in), _p(z_re), _p(z_im),
                                 _p(scan_out), _p(tail_out), _p(gate))
     assert rc == 0, rc
@@ -158,9 +162,9 @@ def phase_fwd(cfg: Cfg, mag, ang, gamma, theta, conv_w=None, conv_b=None, scan_i
 
 
 def phase_bwd(cfg: Cfg, mag, ang, gamma, theta, dz_re, dz_im, conv_w=None, conv_b=None,
-              scan_in=None, tail_in=None, dscan_out=None, dtail_out=None):
+              scan_in=None, tail_in=None, dscan_out=None, dtail_out=None, valve=None):
     """Backward.  Returns dict(dmag, dang [B,L,J], dgamma, dtheta [J], dconv_w [2,J,Kc],
-    dconv_b [2,J], dscan_in [B,2,J], dtail_in [B,Kc-1,2,J]) in f64."""
+    dconv_b [2,J], dscan_in [B,2,J], dtail_in [B,Kc-1,2,J]; gate_mode 1: dvalve [B,L,H]) in f64."""
     B, L, J, Kc = cfg.B, cfg.L, cfg.J, cfg.conv_k
     mag = _f32(mag, (B, L, J))
     ang = _f32(ang, (B, L, J))
@@ -182,11 +186,19 @@ def phase_bwd(cfg: Cfg, mag, ang, gamma, theta, dz_re, dz_im, conv_w=None, conv_
     if Kc > 0:
         out.update(dconv_w=np.zeros((2, J, Kc)), dconv_b=np.zeros((2, J)),
                    dtail_in=np.zeros((B, max(Kc - 1, 0), 2, J)))
+    term = None
+    if cfg.gate_mode == 1:
+        valve = _f32(valve, (B, L, cfg.H))
+        out["dvalve"] = np.zeros((B, L, cfg.H))
+        term = np.zeros((B, L, J))
+    else:
+        valve = None
     cc = cfg.c()
-    rc = lib().oracle_phase_bwd(C.byref(cc), _p(mag), _p(ang), _p(gamma), _p(theta), _p(conv_w),
+    rc = lib().oracle_phase_bwd(C.byref(cc), _p(mag), _p(ang), _p(valve), _p(gamma), _p(theta), _p(conv_w),
                                 _p(conv_b), _p(scan_in), _p(tail_in), _p(dz_re), _p(dz_im),
                                 _p(dscan_out), _p(dtail_out), _p(out["dmag"]), _p(out["dang"]),
                                 _p(out["dgamma"]), _p(out["dtheta"]), _p(out.get("dconv_w")),
-                                _p(out.get("dconv_b")), _p(out["dscan_in"]), _p(out.get("dtail_in")))
+                                _p(out.get("dconv_b")), _p(out["dscan_in"]), _p(out.get("dtail_in")),
+                                _p(out.get("dvalve")), _p(term))
     assert rc == 0, rc
     return out

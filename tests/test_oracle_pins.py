@@ -504,6 +504,107 @@ def test_conv_clamp_blocks_gradient_outside_range():
 
 
 # -------------------------------------------------------------------------------------- theta_j
+# ------------------------------------------------------------------------- per-head valve (mode 1)
+def np_sigmoid(v):
+    return 1.0 / (1.0 + np.exp(-v))
+
+
+def test_valve_brute_force_and_mask():
+    """gate_mode 1 (Sec. 3.3 "Hard-Threshold Gating", Sec. 3.4 gated-push equations): every lane of
+    head h pushes beta_hard[t,h] * a * e^{i phi}; beta_sig = sigmoid(v - 3), closed below eps."""
+    B, L, H, F = 2, 30, 3, 4
+    d = small(31, B, L, H, F)
+    r = rng_(32)
+    valve = (3.0 + 4.0 * r.standard_normal((B, L, H))).astype(np.float32)   # beta_sig from ~0 to ~1
+    eps = 0.2                                                              # closes a good fraction
+    cfg = O.Cfg(B, L, H, F, gate_mode=1, valve_eps=eps, gate_tau=5.0, out_clamp=INF)   # tau plays no part
+    out = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], valve=valve)
+    bsig = np_sigmoid(valve.astype(np.float64) - 3.0)
+    opened = bsig >= np.float64(np.float32(eps))
+    assert 0.2 < opened.mean() < 0.8
+    beta = np.where(opened, bsig, 0.0)
+    p = np.repeat(beta, F, axis=2) * d["mag"].astype(np.float64) * np.exp(1j * d["ang"].astype(np.float64))
+    S = brute_scan(p, lam(d["gamma"], d["theta"]))
+    np.testing.assert_allclose(out["z_re"], S.real, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["z_im"], S.imag, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(out["gate"], np.repeat(opened, F, axis=2).astype(np.uint8))
+
+
+def test_valve_half_open_by_hand_and_threshold_edge():
+    # v = 3 -> beta = sigmoid(0) = 1/2: one token, Z = a/2 e^{i phi}
+    cfg = O.Cfg(1, 1, 1, 1, gate_mode=1, out_clamp=INF)
+    one = lambda v: np.full((1, 1, 1), v, dtype=np.float32)
+    out = O.phase_fwd(cfg, one(1.5), one(0.25), one(0.9)[0, 0], one(0.1)[0, 0], valve=one(3.0))
+    assert out["z_re"][0, 0, 0] == pytest.approx(0.75 * math.cos(0.25), abs=1e-15)
+    assert out["z_im"][0, 0, 0] == pytest.approx(0.75 * math.sin(0.25), abs=1e-15)
+    # the paper's eps = 0.001 closes the valve exactly where sigmoid(v - 3) < 0.001, i.e. below
+    # v* = 3 + ln(0.001 / 0.999); the fp32 neighbours of v* fall on either side (keep when >=)
+    vstar = 3.0 + math.log(0.001 / 0.999)
+    lo = np.nextafter(np.float32(vstar), np.float32(-INF))
+    hi = np.nextafter(np.float32(vstar), np.float32(INF))
+    assert float(lo) < vstar < float(hi) or float(lo) <= vstar <= float(hi)
+    cfg = O.Cfg(1, 1, 1, 1, gate_mode=1, valve_eps=0.001, out_clamp=INF)
+    z_lo = O.phase_fwd(cfg, one(1.0), one(0.0), one(0.9)[0, 0], one(0.1)[0, 0], valve=one(lo - np.float32(1e-4)))
+    z_hi = O.phase_fwd(cfg, one(1.0), one(0.0), one(0.9)[0, 0], one(0.1)[0, 0], valve=one(hi + np.float32(1e-4)))
+    assert z_lo["z_re"][0, 0, 0] == 0.0 and z_lo["gate"][0, 0, 0] == 0
+    assert z_hi["z_re"][0, 0, 0] == pytest.approx(0.001, rel=2e-4) and z_hi["gate"][0, 0, 0] == 1
+
+
+def test_valve_gradients_against_numpy_chain_and_finite_differences():
+    """Backward of gate_mode 1: da carries beta_hard, dphi carries beta_hard a, and the valve logit
+    receives beta_sig (1 - beta_sig) * sum_k a_k Re(conj(G_k) e^{i phi_k}) whatever the threshold did
+    (Sec. 3.3: beta = beta_hard - sg(beta_sig) + beta_sig).  The adjoint G does not depend on
+    beta, so that gradient equals the exact derivative of the un-thresholded forward: checked by
+    central differences of the eps = 0 forward."""
+    B, L, H, F = 2, 14, 2, 3
+    J = H * F
+    d = small(41, B, L, H, F)
+    r = rng_(42)
+    valve = (3.0 + 3.0 * r.standard_normal((B, L, H))).astype(np.float32)
+    dz = r.standard_normal((2, B, L, J)).astype(np.float32)
+    eps = 0.3
+    cfg = O.Cfg(B, L, H, F, gate_mode=1, valve_eps=eps, out_clamp=INF, grad_clamp=INF)
+    g = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], dz[0], dz[1], valve=valve)
+    # numpy chain
+    bsig = np_sigmoid(valve.astype(np.float64) - 3.0)
+    beta = np.repeat(np.where(bsig >= np.float64(np.float32(eps)), bsig, 0.0), F, axis=2)
+    G = brute_adjoint(dz[0].astype(np.float64) + 1j * dz[1].astype(np.float64), lam(d["gamma"], d["theta"]))
+    a = d["mag"].astype(np.float64)
+    e = np.exp(1j * d["ang"].astype(np.float64))
+    re = (np.conj(G) * e).real            # Re(conj(G) e^{i phi})
+    np.testing.assert_allclose(g["dmag"], beta * re, atol=1e-12)
+    np.testing.assert_allclose(g["dang"], beta * a * (np.conj(G) * 1j * e).real, atol=1e-12)
+    want = bsig * (1 - bsig) * (a * re).reshape(B, L, H, F).sum(axis=3)
+    np.testing.assert_allclose(g["dvalve"], want, atol=1e-12)
+    assert (np.abs(g["dvalve"][np.where(bsig < eps)]) > 1e-6).any()      # closed valves still learn
+    # finite differences of the soft forward
+    soft = O.Cfg(B, L, H, F, gate_mode=1, valve_eps=0.0, out_clamp=INF)
+
+    def loss(v):
+        o = O.phase_fwd(soft, d["mag"], d["ang"], d["gamma"], d["theta"], valve=v, want_gate=False)
+        return float((o["z_re"] * dz[0]).sum() + (o["z_im"] * dz[1]).sum())
+
+    h = 2.0 ** -6          # exactly representable steps around fp32 logits
+    for (b, t, hh) in [(0, 0, 0), (1, 5, 1), (0, 13, 1), (1, 9, 0)]:
+        vp = valve.copy(); vm = valve.copy()
+        vp[b, t, hh] += np.float32(h); vm[b, t, hh] -= np.float32(h)
+        fd = (loss(vp) - loss(vm)) / (float(vp[b, t, hh]) - float(vm[b, t, hh]))
+        assert g["dvalve"][b, t, hh] == pytest.approx(fd, rel=2e-3, abs=1e-6)
+
+
+def test_valve_full_open_reduces_to_the_ungated_path():
+    # beta_sig -> 1 for a large logit (sigmoid(37) = 1 - 9e-17): same result as mode 0 with tau = 0
+    B, L, H, F, Kc = 1, 20, 2, 4, 3
+    d = small(51, B, L, H, F, Kc)
+    valve = np.full((B, L, H), 40.0, dtype=np.float32)
+    a = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc, gate_mode=1), d["mag"], d["ang"], d["gamma"], d["theta"],
+                    d["conv_w"], d["conv_b"], valve=valve)
+    b = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=0.0), d["mag"], d["ang"], d["gamma"], d["theta"],
+                    d["conv_w"], d["conv_b"])
+    np.testing.assert_allclose(a["z_re"], b["z_re"], rtol=1e-14, atol=1e-14)
+    np.testing.assert_allclose(a["z_im"], b["z_im"], rtol=1e-14, atol=1e-14)
+
+
 def test_theta_init_endpoints_and_ratio():
     H, F = 12, 64
     th = O.theta_init(H, F).astype(np.float64)
