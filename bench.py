@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 100; 3 for cfg4_stream)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 20; 1 for cfg4_stream)")
+    ap.add_argument("--valve", action="store_true",
+                    help="gate_mode 1: the per-head input valve of Sec. 3.3 instead of the per-lane threshold "
+                         "(extra line, not the headline; no CPU baseline)")
     ap.add_argument("--workload", default="cfg3_train",
                     choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "decode"])
     ap.add_argument("--decode-batch", type=int, default=1)
@@ -180,7 +183,15 @@ def main():
         sets.append(cur)
     t_gen = time.time() - t_gen
 
-    d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau)
+    d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau, gate_mode=1 if args.valve else 0)
+    valve = dvalve = None
+    if args.valve:
+        assert not stream_mode, "--valve: cfg2_layer_fwd, cfg3_train or cfg5_wide"
+        args.no_cpu_baseline = True
+        # logits around the closing point 3 + ln(0.001/0.999) = -3.9: about half the valves are shut
+        rv = np.random.Generator(np.random.PCG64(4250 + 99))
+        valve = torch.from_numpy((-3.9 + 3.0 * rv.standard_normal((B, L, H))).astype(np.float32)).to(dev)
+        dvalve = torch.empty((B, L, H), device=dev)
     ws = K.alloc_workspace(d, dev)
     ckpt = torch.empty(K.cawn_ckpt_bytes(d) // 4, device=dev) if do_bwd else None
     dgamma, dtheta = torch.empty(J, device=dev), torch.empty(J, device=dev)
@@ -189,8 +200,14 @@ def main():
     state = torch.zeros(nstate, device=dev)
 
     # first call builds the lane table; later calls reuse it (parameters do not change in the bench)
-    K.check(K.cawn_phase_accumulate_fwd(d, sets[0]["mag"], sets[0]["ang"], gamma, th, cw, cb, None,
-                                        sets[0]["z_re"], sets[0]["z_im"], None, ckpt, None, ws))
+    def fwd_call(dd, p, st_in, st_out, ck):
+        if valve is not None:
+            return K.cawn_phase_accumulate_valve_fwd(dd, p["mag"], p["ang"], valve, gamma, th, cw, cb, st_in,
+                                                     p["z_re"], p["z_im"], st_out, ck, None, ws)
+        return K.cawn_phase_accumulate_fwd(dd, p["mag"], p["ang"], gamma, th, cw, cb, st_in, p["z_re"], p["z_im"],
+                                           st_out, ck, None, ws)
+
+    K.check(fwd_call(d, sets[0], None, None, ckpt))
     d.lane_consts_cached = 1
     d_tail = None
     if stream_mode:
@@ -214,14 +231,18 @@ def main():
             return
         if rec is not None:
             rec[0].record()
-        st = K.cawn_phase_accumulate_fwd(d, s["mag"], s["ang"], gamma, th, cw, cb, None, s["z_re"], s["z_im"],
-                                         None, ckpt, None, ws)
+        st = fwd_call(d, s, None, None, ckpt)
         if rec is not None:
             rec[1].record()
         if do_bwd:
-            st |= K.cawn_phase_accumulate_bwd(d, s["mag"], s["ang"], gamma, th, cw, cb, None, ckpt, s["dz_re"],
-                                              s["dz_im"], None, s["dmag"], s["dang"], dgamma, dtheta, dcw, dcb,
-                                              None, ws)
+            if valve is not None:
+                st |= K.cawn_phase_accumulate_valve_bwd(d, s["mag"], s["ang"], valve, gamma, th, cw, cb, None, ckpt,
+                                                        s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"], dvalve,
+                                                        dgamma, dtheta, dcw, dcb, None, ws)
+            else:
+                st |= K.cawn_phase_accumulate_bwd(d, s["mag"], s["ang"], gamma, th, cw, cb, None, ckpt, s["dz_re"],
+                                                  s["dz_im"], None, s["dmag"], s["dang"], dgamma, dtheta, dcw, dcb,
+                                                  None, ws)
             if rec is not None:
                 rec[2].record()
         assert st == 0, st
@@ -251,6 +272,7 @@ def main():
                                   f"gamma~U[{wl.gamma_lo},{wl.gamma_hi}] theta_j=10000^(-2j/J)"
                                   + (f" chunk={wl.chunk} state carried in place" if stream_mode else ""),
                       "pass": "fwd+bwd (all gradients)" if do_bwd else "fwd",
+                      "gate": "per-head valve (gate_mode 1), about half shut" if args.valve else "per-lane threshold",
                       "buffer_sets_rotated": nsets}}
 
     # ---- roofline of the dominant kernel, from HIP events on the launch stream
@@ -259,7 +281,7 @@ def main():
         per_call_ms = ms_per_step / ncalls
         alg = FWD_BYTES_PER_TOKEN_LANE * tokens * J / ncalls
         achieved = alg / (per_call_ms * 1e-3) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4> (per 4096-token chunk call, launch gaps included)",
+        out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4,false> (per 4096-token chunk call, launch gaps included)",
                            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                            "traffic": read_traffic(args.workload), "avg_ms": per_call_ms}
         out["stream"] = {"calls": ncalls, "state_bytes": nstate * 4, "device_mem_delta_bytes": int(mem1 - mem0)}
@@ -277,14 +299,14 @@ def main():
             out["bwd_ms_median_min"] = [float(np.median(bwd_all)), float(np.min(bwd_all))]
             alg = BWD_BYTES_PER_TOKEN_LANE * tokens * J
             achieved = alg / (bwd_ms * 1e-3) / 1e9
-            out["roofline"] = {"bound": "hbm", "kernel": "bwd_kernel<1,4,true> (+ its partial-sum reduction)",
+            out["roofline"] = {"bound": "hbm", "kernel": ("bwd_kernel<1,4,true,true>" if args.valve else "bwd_kernel<1,4,true,false>") + " (+ its partial-sum reduction)",
                                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                               "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
+                               "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.valve else read_traffic(args.workload),
                                "avg_ms": bwd_ms}
         else:
-            out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4>", "achieved": out["fwd_GBps"],
+            out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4,true>" if args.valve else "fwd_kernel<1,4,false>", "achieved": out["fwd_GBps"],
                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": out["fwd_GBps"] / HBM_PEAK_GBS,
-                               "traffic": read_traffic(args.workload), "avg_ms": fwd_ms}
+                               "traffic": None if args.valve else read_traffic(args.workload), "avg_ms": fwd_ms}
 
     # ---- the fp64 oracle on the host cores, on a bounded sample of the same inputs (baseline only)
     if not args.no_cpu_baseline:

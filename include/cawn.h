@@ -11,6 +11,10 @@
  *     a     = x_mag (amp_mode 0)  |  min(softplus(x_mag), 10) (amp_mode 1);   phi = x_ang
  *     g     = [ |a| >= gate_tau ]                        (forward only; backward ignores g for a)
  *     p     = g * a * (cos phi, sin phi)
+ *   gate_mode 1 (the *_valve_* entry points; Sec. 3.3 "Hard-Threshold Gating"): one logit v per
+ *   (token, head) replaces g:
+ *     beta  = sigmoid(v - 3) if sigmoid(v - 3) >= valve_eps else 0
+ *     p     = beta * a * (cos phi, sin phi);  backward: d beta / d v = sig (1 - sig) always
  *     S[t]  = p + gamma[j] * e^{i theta[j]} * S[t-1]     (complex, written out in real fp32
  *                                                         arithmetic), S[-1] = state_in or 0
  *     Z[t]  = clamp(S[t], +-out_clamp)                   (the carried S is not clamped)
@@ -45,8 +49,10 @@ typedef struct cawn_desc {
     int32_t B, L, H, F;   /* L = tokens in THIS call (0 allowed: state is passed through)       */
     int32_t conv_k;       /* 0 = no conv front-end; 1..4 taps (paper: 3; benchmark configs: 4)  */
     int32_t amp_mode;     /* 0 amplitude = magnitude stream; 1 = min(softplus(.), 10), Sec. 3.3 */
-    int32_t gate_mode;    /* 0 per-lane threshold on |a|; other values: CAWN_EUNSUPPORTED       */
-    float gate_tau;       /* keep when |a| >= gate_tau; 0 = gate open                           */
+    int32_t gate_mode;    /* 0 per-lane threshold on |a| (cawn_phase_accumulate_fwd/_bwd);
+                             1 per-head input valve (cawn_phase_accumulate_valve_fwd/_bwd; needs
+                             F % 32 == 0, F == 16 or F == 8); else CAWN_EUNSUPPORTED            */
+    float gate_tau;       /* gate_mode 0: keep when |a| >= gate_tau; 0 = gate open              */
     float conv_clamp;     /* 50 in the paper; +inf disables                                     */
     float out_clamp;      /* 100; +inf disables                                                 */
     float grad_clamp;     /* 100; +inf disables (backward only)                                 */
@@ -54,7 +60,7 @@ typedef struct cawn_desc {
     int32_t lane_consts_cached;     /* 1: gamma, theta, conv_w, conv_b are unchanged since the
                                        last call on this workspace with the same H, F, conv_k
                                        that had this flag 0 -- skip rebuilding the lane table   */
-    int32_t reserved_;
+    float valve_eps;      /* gate_mode 1: the valve closes below this (paper: 0.001)            */
     int64_t in_stride_b, in_stride_t;   /* element strides of mag/ang/dmag/dang; 0 = dense
                                            (t stride J, b stride L*J); lane stride is always 1;
                                            t strides above 2^21 elements: CAWN_EUNSUPPORTED     */
@@ -153,6 +159,31 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
                               float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
                               size_t workspace_bytes, void *stream);
 
+/*
+ * The same two operations with the per-head input valve of Sec. 3.3 ("Hard-Threshold Gating",
+ * gated-push equations of Sec. 3.4) in place of the per-lane threshold; d->gate_mode must be 1.
+ *   valve        [B][L][H] fp32 logits, dense.  The decision sigmoid(v - 3) >= valve_eps is
+ *                taken on the fp32 logit, evaluated in double precision.
+ *   gate_mask    bit j = the valve of lane j's head is open
+ *   dvalve       [B][L][H] gradient w.r.t. the logits (straight-through: closed valves get one
+ *                too), or NULL
+ * Everything else as in cawn_phase_accumulate_fwd / _bwd (d->gate_tau is ignored).  The workspace
+ * size depends on gate_mode: ask cawn_workspace_bytes with the same descriptor.
+ */
+int cawn_phase_accumulate_valve_fwd(const cawn_desc *d, const float *mag, const float *ang,
+                                    const float *valve, const float *gamma, const float *theta,
+                                    const float *conv_w, const float *conv_b, const void *state_in,
+                                    float *z_re, float *z_im, void *state_out, void *ckpt,
+                                    uint32_t *gate_mask, void *workspace, size_t workspace_bytes,
+                                    void *stream);
+int cawn_phase_accumulate_valve_bwd(const cawn_desc *d, const float *mag, const float *ang,
+                                    const float *valve, const float *gamma, const float *theta,
+                                    const float *conv_w, const float *conv_b, const void *state_in,
+                                    const void *ckpt, const float *dz_re, const float *dz_im,
+                                    const void *dstate_out, float *dmag, float *dang, float *dvalve,
+                                    float *dgamma, float *dtheta, float *dconv_w, float *dconv_b,
+                                    void *dstate_in, void *workspace, size_t workspace_bytes,
+                                    void *stream);
 #ifdef __cplusplus
 }
 #endif

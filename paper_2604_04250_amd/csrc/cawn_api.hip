@@ -42,6 +42,9 @@ static WsLayout make_layout(const cawn_desc *d)
     o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_part = o;
     o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
+    w.off_vpart = o;    // gate_mode 1: per-group sums of the valve's gradient terms, [B][groups][L]
+    if (d->gate_mode == 1)
+        o = align_up(o + (size_t)d->B * (size_t)(d->H * (d->F >= 32 ? d->F / 32 : 1)) * (size_t)(d->L > 0 ? d->L : 1) * sizeof(float), 256);
     w.off_dbg = o;
 #ifdef CAWN_TIMING
     o += (size_t)MAX_TILES * 16 * sizeof(unsigned long long);
@@ -158,7 +161,50 @@ static bool make_gate_set(const cawn_desc *d, GateSet *out)
     return true;
 }
 
+// gate_mode 1: the valve of Sec. 3.3 is open when sigmoid(v - 3) >= eps, a decision defined on the
+// fp32 logit v and evaluated in fp64.  sigmoid is increasing, so the open set is [thr, +inf): thr is
+// found by bisection over the ordered fp32 values.  +inf: never open; -inf: always open.
+static float valve_threshold(float eps)
+{
+    const float INF = std::numeric_limits<float>::infinity();
+    const float FMAX = std::numeric_limits<float>::max();
+    const double e = (double)eps;
+    auto open = [&](float v) { return 1.0 / (1.0 + std::exp(-((double)v - 3.0))) >= e; };
+    if (std::isnan(e)) return INF;
+    if (open(-FMAX)) return -INF;
+    if (!open(FMAX)) return INF;
+    int64_t lo = ord(-FMAX), hi = ord(FMAX);
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (open(unord(mid))) hi = mid; else lo = mid + 1;
+    }
+    return unord(lo);
+}
+// lanes of a 32-lane block that share a valve: heads of F >= 32 lanes span whole blocks
+static bool valve_shape_ok(const cawn_desc *d) { return d->F % 32 == 0 || d->F == 16 || d->F == 8; }
+static int valve_groups(const cawn_desc *d) { return d->H * (d->F >= 32 ? d->F / 32 : 1); }   // per token
+
 // ------------------------------------------------------------------------------------ kernels
+// gate_mode 1: dvalve[b][t][h] = sig (1 - sig) * (sum over the head's groups of vpart[b][g][t]),
+// sig = sigmoid(valve - 3): the straight-through gradient of Sec. 3.3.  One thread per (b, h, t),
+// t fastest; the groups of a head are summed in index order.
+__global__ void valve_reduce_kernel(const float *__restrict__ vpart, const float *__restrict__ valve,
+                                    float *__restrict__ dvalve, int B, int L, int H, int G)
+{
+    const long long n = (long long)B * H * L;
+    const int gph = G / H;       // groups per head
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long long)gridDim.x * blockDim.x) {
+        const int t = (int)(e % L);
+        const long long r = e / L;
+        const int h = (int)(r % H), b = (int)(r / H);
+        float sum = 0.f;
+        for (int g = 0; g < gph; ++g) sum += vpart[((size_t)b * G + (size_t)h * gph + g) * L + t];
+        const size_t o = ((size_t)b * L + t) * H + h;
+        const float sg = 1.0f / (1.0f + expf(-(valve[o] - 3.0f)));
+        dvalve[o] = sg * (1.0f - sg) * sum;
+    }
+}
+
 __global__ void fill_zero_kernel(uint32_t *p, size_t n)
 {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
@@ -446,13 +492,13 @@ int cawn_syntax_conv(const cawn_desc *d, int32_t C, const float *x, const float 
     return CAWN_OK;
 }
 
-int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
-                              const float *theta, const float *conv_w, const float *conv_b,
-                              const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
-                              uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
+static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
+                    const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
+                    const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
+                    uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 0 || d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode == 1 && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
     const WsLayout w = make_layout(d);
     const long long J = w.J;
@@ -472,6 +518,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
         return CAWN_OK;
     }
     if (!mag || !ang || !gamma || !theta || !z_re || !z_im || !workspace) return CAWN_EINVAL;
+    if (d->gate_mode == 1 && !valve) return CAWN_EINVAL;
     if (d->conv_k > 0 && !conv_w) return CAWN_EINVAL;
     if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
@@ -480,7 +527,16 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     if (ist > (1ll << 21) || ost > (1ll << 21)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     FwdArgs a{};
-    if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode == 1) {
+        const float INF = std::numeric_limits<float>::infinity();
+        a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
+        a.valve = valve;
+        a.valve_thr = valve_threshold(d->valve_eps);
+        a.gpb = d->F >= 32 ? 1 : 32 / d->F;
+    } else if (!make_gate_set(d, &a.gs)) {
+        return CAWN_EUNSUPPORTED;
+    }
+    a.H = d->H; a.F = d->F;
     const bool vec = (J % FwdV == 0) && (ist % FwdV == 0) && (isb % FwdV == 0) && (ost % FwdV == 0) &&
                      (osb % FwdV == 0) && aligned(mag, 16) && aligned(ang, 16) && aligned(z_re, 16) &&
                      aligned(z_im, 16) && (!state_in || aligned(state_in, 16)) &&
@@ -520,15 +576,38 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
     return CAWN_OK;
 }
 
-int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
+int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
                               const float *theta, const float *conv_w, const float *conv_b,
-                              const void *state_in, const void *ckpt, const float *dz_re, const float *dz_im,
-                              const void *dstate_out, float *dmag, float *dang, float *dgamma, float *dtheta,
-                              float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
-                              size_t workspace_bytes, void *stream)
+                              const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
+                              uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 0 || d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode != 0) return CAWN_EUNSUPPORTED;
+    return fwd_impl(d, mag, ang, nullptr, gamma, theta, conv_w, conv_b, state_in, z_re, z_im, state_out, ckpt,
+                    gate_mask, workspace, workspace_bytes, stream);
+}
+
+int cawn_phase_accumulate_valve_fwd(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
+                                    const float *gamma, const float *theta, const float *conv_w,
+                                    const float *conv_b, const void *state_in, float *z_re, float *z_im,
+                                    void *state_out, void *ckpt, uint32_t *gate_mask, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->gate_mode != 1) return CAWN_EINVAL;
+    return fwd_impl(d, mag, ang, valve, gamma, theta, conv_w, conv_b, state_in, z_re, z_im, state_out, ckpt,
+                    gate_mask, workspace, workspace_bytes, stream);
+}
+
+static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
+                    const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
+                    const void *state_in, const void *ckpt, const float *dz_re, const float *dz_im,
+                    const void *dstate_out, float *dmag, float *dang, float *dvalve, float *dgamma,
+                    float *dtheta, float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode == 1 && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
     const WsLayout w = make_layout(d);
     const long long J = w.J;
@@ -555,6 +634,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
         return e == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
     }
     if (!mag || !ang || !gamma || !theta || !dz_re || !dz_im || !dmag || !dang || !workspace) return CAWN_EINVAL;
+    if (d->gate_mode == 1 && !valve) return CAWN_EINVAL;
     if (kc > 0 && !conv_w) return CAWN_EINVAL;
     if ((dgamma || dtheta) && !ckpt) return CAWN_EINVAL;
     if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
@@ -564,7 +644,18 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
     if (ist > (1ll << 21) || ost > (1ll << 21)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
 
     BwdArgs a{};
-    if (!make_gate_set(d, &a.gs)) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode == 1) {
+        const float INF = std::numeric_limits<float>::infinity();
+        a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
+        a.valve = valve;
+        a.valve_thr = valve_threshold(d->valve_eps);
+        a.gpb = d->F >= 32 ? 1 : 32 / d->F;
+        a.G = valve_groups(d);
+        a.vpart = dvalve ? reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + w.off_vpart) : nullptr;
+    } else if (!make_gate_set(d, &a.gs)) {
+        return CAWN_EUNSUPPORTED;
+    }
+    a.H = d->H; a.F = d->F;
     const bool vec = (J % BwdV == 0) && (ist % BwdV == 0) && (isb % BwdV == 0) && (ost % BwdV == 0) &&
                      (osb % BwdV == 0) && aligned(mag, 8) && aligned(ang, 8) && aligned(dz_re, 8) &&
                      aligned(dz_im, 8) && aligned(dmag, 8) && aligned(dang, 8) &&
@@ -610,7 +701,43 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
                            d->B * w.nT, d->accumulate_param_grads);
         if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
     }
+    if (a.vpart) {
+        const long long n = (long long)d->B * d->H * d->L;
+        const long long nb = (n + 255) / 256;
+        hipLaunchKernelGGL(valve_reduce_kernel, dim3((unsigned)(nb < 4096 ? nb : 4096)), dim3(256), 0, s, a.vpart,
+                           valve, dvalve, d->B, d->L, d->H, a.G);
+        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+    }
     return CAWN_OK;
+}
+
+int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
+                              const float *theta, const float *conv_w, const float *conv_b,
+                              const void *state_in, const void *ckpt, const float *dz_re, const float *dz_im,
+                              const void *dstate_out, float *dmag, float *dang, float *dgamma, float *dtheta,
+                              float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
+                              size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->gate_mode != 0) return CAWN_EUNSUPPORTED;
+    return bwd_impl(d, mag, ang, nullptr, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im, dstate_out,
+                    dmag, dang, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace, workspace_bytes,
+                    stream);
+}
+
+int cawn_phase_accumulate_valve_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
+                                    const float *gamma, const float *theta, const float *conv_w,
+                                    const float *conv_b, const void *state_in, const void *ckpt,
+                                    const float *dz_re, const float *dz_im, const void *dstate_out, float *dmag,
+                                    float *dang, float *dvalve, float *dgamma, float *dtheta, float *dconv_w,
+                                    float *dconv_b, void *dstate_in, void *workspace, size_t workspace_bytes,
+                                    void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->gate_mode != 1) return CAWN_EINVAL;
+    return bwd_impl(d, mag, ang, valve, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im, dstate_out,
+                    dmag, dang, dvalve, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace, workspace_bytes,
+                    stream);
 }
 
 }  // extern "C"

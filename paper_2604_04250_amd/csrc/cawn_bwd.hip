@@ -30,6 +30,18 @@ namespace cawn {
 #define BWD_STAMP(k) do { } while (0)
 #endif
 
+// x + (x moved across lanes by a DPP control): row_ror:n is 0x120 + n (rotate within a row of 16).
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x)
+{
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+// rows 1 and 3 of the wave add lane 15 of the row below them (row_bcast:15); rows 0 and 2 add zero
+__device__ __forceinline__ float dpp_add_bcast15(float x)
+{
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x142, 0xA, 0xF, false));
+}
+
 template <int V> struct BVec;
 template <> struct BVec<1> {
     static __device__ __forceinline__ void ld(float (&d)[1], const float *p) { d[0] = *p; }
@@ -60,7 +72,8 @@ __device__ __forceinline__ void stu(float *ubase, uint32_t boff, const float (&x
     BVec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(ubase) + boff), x);
 }
 
-template <int V, int KC, bool PARAM>
+// VALVE: gate_mode 1, the per-head input valve of Sec. 3.3 in place of the per-lane threshold.
+template <int V, int KC, bool PARAM, bool VALVE>
 __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
     constexpr int TILE_T = BwdGeom::TILE_T, NSTEP = BwdGeom::NSTEP, NSEG = BwdGeom::NSEG, LPR = BwdLPR;
@@ -72,6 +85,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     constexpr int NT = NSEG * LPR, NW = NT / 64;
     constexpr int NRTP = staged_rows<TILE_T, JB, HALO>();   // staged rows per stream: time tile_t0-HALO+rr
     static_assert(HALO <= NSTEP, "conv halo must fit in one segment");
+    static_assert(!VALVE || V == 1, "the valve's lane reduction takes one lane per thread");
     static_assert(LPR == 32, "the partial-sum reduction pairs the two segments of a wave");
     static_assert(JB <= 64 && 64 % JB == 0, "a staged row must fit a wave");
 
@@ -81,6 +95,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     __shared__ float sCarry[2][JB];
     __shared__ float sHalo[NSEG + 1][HALO1][2][JB];   // [NSEG]: rows of the next tile
     __shared__ float sRed[PARAM ? NW : 1][ROWS][JB];
+    constexpr int GPB_MAX = 4;                    // valve groups per lane block (F >= 8)
+    __shared__ float sV[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];      // valve logits, [group][token]
+    __shared__ float sVp[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
+    __shared__ float sTaps[VALVE ? 2 * KC1 : 1][JB];                 // conv taps of the lane block (valve kernels)
     __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid_ = threadIdx.x;
@@ -183,6 +201,15 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             ldu<V>(waf[k], row(R_W0 + KC + k), jb);
         }
     }
+    if (VALVE && KC > 0 && seg == 0) {      // (read back after the barrier before the transposed conv)
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                sTaps[k][lv * V + v] = wmf[k][v];
+                sTaps[KC + k][lv * V + v] = waf[k][v];
+            }
+    }
 
     // ---- the tile's input rows go to LDS (needed from the front-end on; issued after the loads the
     //      local adjoint waits for, so that it does not wait for these as well)
@@ -192,6 +219,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     else
         stage_rows<TILE_T, JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
                                 NW, lane);
+
+    if (VALVE && wave == 0) stage_valve<TILE_T, JB>(&sV[0], a.valve, b, tt * TILE_T, lb, a.L, a.H, a.F, a.gpb, lane);
 
     // gradient of the carried state joins the last token
     if (a.dstate_out && active && a.L - 1 >= t0 && a.L - 1 < t0 + NSTEP) {
@@ -267,28 +296,42 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     BWD_STAMP(3);
 
     // the forward state entering the tile (checkpoint) and the constants of the reverse pass, fetched
-    // now so that they arrive during the front-end
+    // now so that they arrive during the front-end (the valve kernels, at their register budget in
+    // the front-end, fetch them after it)
     float kr[V], ki[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) kr[v] = ki[v] = 0.f;
-    if (PARAM && active && a.ckpt) {
-        const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
-        BVec<V>::ld(kr, ck);
-        BVec<V>::ld(ki, ck + a.J);
-    }
     float psr[V], psi[V], cth[V], sth[V], gam[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) { sth[v] = gam[v] = 0.f; cth[v] = 1.f; }
-    ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);    // adjoint: segments after mine
-    ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
-    if (PARAM) {
-        ldu<V>(cth, row(R_COS), jb);
-        ldu<V>(sth, row(R_SIN), jb);
-        ldu<V>(gam, row(R_GAMMA), jb);
-    }
+    for (int v = 0; v < V; ++v) { kr[v] = ki[v] = sth[v] = gam[v] = 0.f; cth[v] = 1.f; }
+    auto fetch_reverse_consts = [&]() {
+        if (PARAM && active && a.ckpt) {
+            const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
+            BVec<V>::ld(kr, ck);
+            BVec<V>::ld(ki, ck + a.J);
+        }
+        ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);    // adjoint: segments after mine
+        ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
+        if (PARAM) {
+            ldu<V>(cth, row(R_COS), jb);
+            ldu<V>(sth, row(R_SIN), jb);
+            ldu<V>(gam, row(R_GAMMA), jb);
+        }
+    };
+    if (!VALVE) fetch_reverse_consts();
 
     // ---- front-end recompute, rows from LDS as a sliding window
     float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V];   // ag: a*g*SiLU'(z_ang)
+    float am[VALVE ? NSTEP : 1][V];                                  // the amplitude itself (valve gradient)
+    // lanes that share a valve: a head, or the part of it inside the 32-lane block (8, 16 or 32).
+    // Where my tokens' entries start in sV / sVp is formed again at each use (from an opaque copy of
+    // the thread index) rather than kept in a register across the tile.
+    const int vwidth = VALVE ? (a.F >= JB ? JB : a.F) : 1;
+    auto valve_base = [&]() {
+        int t_ = tid_;
+        asm volatile("" : "+v"(t_));
+        const int lv_ = t_ % LPR, seg_ = t_ / LPR;
+        const int grp = vwidth == 32 ? 0 : (vwidth == 16 ? lv_ >> 4 : lv_ >> 3);
+        return grp * TILE_T + seg_ * NSTEP;
+    };
     float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];      // forward state before each token
     float Efr[V], Efi[V];
     const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
@@ -296,6 +339,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // copy of the loop, so that the tokens' dependent chains (exp -> rcp -> sin/cos) interleave.
     auto front_end = [&](auto amp_c, auto small_c) {
         constexpr bool AMP = decltype(amp_c)::value, SMALL = decltype(small_c)::value;
+        const int vbase = VALVE ? valve_base() : 0;
         float wnm[KC1][V], wna[KC1][V];
         // (row r of my segment lives in slot r % KC1: no register shuffling as the window slides)
 #pragma unroll
@@ -346,12 +390,21 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     amp = __builtin_fminf(sp, 10.0f);
                     km *= sp < 10.0f ? sigmoid_fast(xm) : 0.0f;
                 }
-                const bool g = in_gate(a.gs, zm);
-                float s, c;
-                if (SMALL) sincos_small(phi, s, c);
-                else sincos_fast(phi, s, c);
-                const float agv = g ? amp : 0.0f;
-                cs[i][v] = c;
+                // (the valve kernels keep the reduced angle, not its sin and cos: one register per
+                // token-lane less, paid for with two hardware sin/cos in the reverse pass)
+                const float rev = SMALL ? revolutions_small(phi) : revolutions_fast(phi);
+                const float s = __builtin_amdgcn_sinf(rev), c = __builtin_amdgcn_cosf(rev);
+                float agv;
+                if (VALVE) {      // p = beta a e^{i phi}: beta multiplies both returned gradients
+                    const float vl = sV[vbase + i];
+                    const float beta = vl >= a.valve_thr ? sigmoid_fast(vl - 3.0f) : 0.0f;
+                    agv = beta * amp;
+                    km *= beta;
+                    am[i][v] = amp;
+                } else {
+                    agv = in_gate(a.gs, zm) ? amp : 0.0f;
+                }
+                cs[i][v] = VALVE ? rev : c;
                 sn[i][v] = s;
                 dsm[i][v] = km;
                 ag[i][v] = agv * ka;
@@ -377,6 +430,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         default: front_end(T_{}, T_{}); break;
         }
     }
+    if (VALVE) fetch_reverse_consts();
 
     // ---- forward state entering my segment (checkpoint + earlier segments), then S[t-1] per token
     if (PARAM) {
@@ -490,6 +544,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float acc_g[V], acc_t[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc_g[v] = acc_t[v] = 0.f;
+    const int vbase = VALVE ? valve_base() : 0;
 #pragma unroll
     for (int i = NSTEP - 1; i >= 0; --i) {
 #pragma unroll
@@ -507,11 +562,34 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 acc_t[v] += clampf(tth, a.grad_clamp);
             }
             const float gr_ = clampf(nr, a.grad_clamp), gi_ = clampf(ni, a.grad_clamp);
-            const float da = __builtin_fmaf(gr_, cs[i][v], gi_ * sn[i][v]);
-            const float dph = __builtin_fmaf(gi_, cs[i][v], -gr_ * sn[i][v]);
+            const float c_ = VALVE ? __builtin_amdgcn_cosf(cs[i][v]) : cs[i][v];
+            const float s_ = VALVE ? __builtin_amdgcn_sinf(cs[i][v]) : sn[i][v];
+            const float da = __builtin_fmaf(gr_, c_, gi_ * s_);
+            const float dph = __builtin_fmaf(gi_, c_, -gr_ * s_);
+            if (VALVE) {      // d/d beta, summed over the lanes that share the valve
+                float wv = active ? am[i][v] * da : 0.0f;
+                if (vwidth >= 16) {
+                    // rotations within each row of 16 lanes leave the row's sum in all of its lanes
+                    // (four full-rate adds); a 32-lane group then takes the lower row's sum into its
+                    // upper row, whose lanes end up with the group's total
+                    wv = dpp_add<0x128>(wv);
+                    wv = dpp_add<0x124>(wv);
+                    wv = dpp_add<0x122>(wv);
+                    wv = dpp_add<0x121>(wv);
+                    if (vwidth == 32) wv = dpp_add_bcast15(wv);
+                    if (lv == vwidth - 16 || (vwidth == 16 && lv == 16)) sVp[vbase + i] = wv;
+                } else {
+#pragma unroll
+                    for (int o = 4; o >= 1; o >>= 1)
+                        if (o < vwidth) wv += __shfl_xor(wv, o, 64);
+                    if (lv % vwidth == 0) sVp[vbase + i] = wv;
+                }
+            }
             dzr[i][v] = da * dsm[i][v];          // d/d(conv pre-activation), magnitude stream
             dzi[i][v] = dph * ag[i][v];          //                           angle stream
         }
+        // (the valve kernels are at their register budget: keep the tokens' work from interleaving)
+        if (VALVE) __builtin_amdgcn_sched_barrier(0);
     }
     BWD_STAMP(7);
     // gradient of the incoming scan state: conj(lambda) G[0]
@@ -549,8 +627,16 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
     } else {
         // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
-        const auto &wm = wmf;
-        const auto &wa = waf;
+        // (the valve kernels are at their register budget: their taps wait in LDS during the reverse
+        // pass instead of in 2*KC registers)
+        float wm[KC1][V], wa[KC1][V];
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                wm[k][v] = VALVE ? sTaps[k][lv * V + v] : wmf[k][v];
+                wa[k][v] = VALVE ? sTaps[KC + k][lv * V + v] : waf[k][v];
+            }
         if (HALO > 0) {
 #pragma unroll
             for (int r = 0; r < HALO; ++r)
@@ -776,6 +862,16 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
     }
 
+    // ---- the valve's gradient terms of the tile go out, token-contiguous per group
+    if (VALVE && a.vpart) {
+        lds_barrier();
+        for (int e = tid; e < a.gpb * TILE_T; e += NT) {
+            const int g = e / TILE_T, tok = e - g * TILE_T;
+            const int t = tt * TILE_T + tok, grp = lb * a.gpb + g;
+            if (t < a.L && grp < a.G) a.vpart[((size_t)b * a.G + grp) * a.L + t] = sVp[e];
+        }
+    }
+
     // ---- LDS is reused by the next tile
     lds_barrier();
     BWD_STAMP(10);
@@ -793,7 +889,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 }
 
 // Persistent grid: what fits on the chip at once (asked once per kernel), never more than tiles.
-template <int V, int KC, bool PARAM>
+template <int V, int KC, bool PARAM, bool VALVE>
 static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
 {
     static int per_cu = 0, cus = 0;
@@ -801,34 +897,37 @@ static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM, VALVE>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
     }
     long long g = (long long)per_cu * cus;
     if (g > (long long)a.total_tiles) g = a.total_tiles;
-    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
+    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM, VALVE>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
     return hipGetLastError();
 }
 
-template <int V, bool PARAM>
+template <int V, bool PARAM, bool VALVE>
 static hipError_t launch_bwd_vp(const BwdArgs &a, int conv_k, hipStream_t s)
 {
     switch (conv_k) {
-    case 0: return launch_bwd_vkp<V, 0, PARAM>(a, s);
-    case 1: return launch_bwd_vkp<V, 1, PARAM>(a, s);
-    case 2: return launch_bwd_vkp<V, 2, PARAM>(a, s);
-    case 3: return launch_bwd_vkp<V, 3, PARAM>(a, s);
-    case 4: return launch_bwd_vkp<V, 4, PARAM>(a, s);
+    case 0: return launch_bwd_vkp<V, 0, PARAM, VALVE>(a, s);
+    case 1: return launch_bwd_vkp<V, 1, PARAM, VALVE>(a, s);
+    case 2: return launch_bwd_vkp<V, 2, PARAM, VALVE>(a, s);
+    case 3: return launch_bwd_vkp<V, 3, PARAM, VALVE>(a, s);
+    case 4: return launch_bwd_vkp<V, 4, PARAM, VALVE>(a, s);
     default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s)
 {
-    if (vec) return a.want_param ? launch_bwd_vp<BwdV, true>(a, conv_k, s) : launch_bwd_vp<BwdV, false>(a, conv_k, s);
-    return a.want_param ? launch_bwd_vp<1, true>(a, conv_k, s) : launch_bwd_vp<1, false>(a, conv_k, s);
+    (void)vec;      // one lane per thread in every build of the backward kernel
+    static_assert(BwdV == 1, "the vectorised backward was dropped");
+    if (a.valve)
+        return a.want_param ? launch_bwd_vp<1, true, true>(a, conv_k, s) : launch_bwd_vp<1, false, true>(a, conv_k, s);
+    return a.want_param ? launch_bwd_vp<1, true, false>(a, conv_k, s) : launch_bwd_vp<1, false, false>(a, conv_k, s);
 }
 
 }  // namespace cawn

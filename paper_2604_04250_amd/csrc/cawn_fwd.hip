@@ -106,7 +106,8 @@ __device__ __forceinline__ void stage_consts(float *sC, const float *table, int 
     }
 }
 
-template <int V, int KC>
+// VALVE: gate_mode 1, the per-head input valve of Sec. 3.3 in place of the per-lane threshold.
+template <int V, int KC, bool VALVE>
 __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
     constexpr int TILE_T = FwdGeom::TILE_T, NSTEP = FwdGeom::NSTEP, NSEG = FwdGeom::NSEG, LPR = FwdLPR;
@@ -124,6 +125,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     __shared__ float sCarry[2][JB];
     constexpr int NCR = R_W0 - R_LR + 2 * KC;     // staged lane-constant rows
     __shared__ __attribute__((aligned(16))) float sC[(NCR + 7) / 8 * 8][JB];
+    constexpr int GPB_MAX = 4;                    // valve groups per lane block (F >= 8)
+    __shared__ float sV[VALVE ? FwdGeom::TILE_T * GPB_MAX : 1];
     __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid = threadIdx.x;
@@ -153,6 +156,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     auto stage_tile = [&](const TileId &T) {
         if (owner_wave) return;
         if (wave == 0) stage_consts<NCR, JB>(&sC[0][0], a.table, a.Jp, T.lb, lane);
+        if (VALVE && wave == 0) stage_valve<TILE_T, JB>(&sV[0], a.valve, T.b, T.tt * TILE_T, T.lb, a.L, a.H, a.F, a.gpb, lane);
         if (a.stage16)
             stage_rows<TILE_T, JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
                                      ist32, wave, NW - 1, lane);
@@ -225,6 +229,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         float Er[V], Ei[V];
         uint32_t gbits[NSTEP];
         const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
+        // (my lane's valve group in the block is lane / F when heads are narrower than the block)
+        const int vbase = VALVE ? (a.F >= JB ? 0 : (lv * V) / a.F) * TILE_T + seg * NSTEP : 0;
         // The mode switches are uniform over the launch; each combination gets its own straight-line
         // copy of the loop, so that the tokens' dependent chains (exp -> rcp -> sin/cos) interleave.
         auto front_end = [&](auto amp_c, auto small_c, auto mask_c) {
@@ -270,11 +276,19 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                         phi = wna[i % KC1][v];
                     }
                     const float amp = AMP ? __builtin_fminf(softplus_fast(xm), 10.0f) : xm;
-                    const bool g = in_gate(a.gs, zm);
+                    bool g;
+                    float ag;
+                    if (VALVE) {      // beta = sigmoid(logit - 3), zero when the valve is closed
+                        const float vl = sV[vbase + i];
+                        g = vl >= a.valve_thr;
+                        ag = g ? amp * sigmoid_fast(vl - 3.0f) : 0.0f;
+                    } else {
+                        g = in_gate(a.gs, zm);
+                        ag = g ? amp : 0.0f;
+                    }
                     float s, c;
                     if (SMALL) sincos_small(phi, s, c);
                     else sincos_fast(phi, s, c);
-                    const float ag = g ? amp : 0.0f;
                     pr[i][v] = ag * c;
                     pi[i][v] = ag * s;
                     if (MASK) gbits[i] |= g ? (1u << v) : 0u;
@@ -587,11 +601,19 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
             phi = ua;
         }
         const float amp = a.amp_mode ? __builtin_fminf(softplus_fast(xm), 10.0f) : xm;
-        const bool g = in_gate(a.gs, zm);
+        bool g;
+        float ag;
+        if (a.valve) {      // per-head valve (Sec. 3.3): beta = sigmoid(logit - 3), zero when closed
+            const float vl = a.valve[((size_t)b * a.L + t) * a.H + jc / a.F];
+            g = vl >= a.valve_thr;
+            ag = g ? amp * sigmoid_fast(vl - 3.0f) : 0.0f;
+        } else {
+            g = in_gate(a.gs, zm);
+            ag = g ? amp : 0.0f;
+        }
         float sn, cs;
         if (a.small_angle) sincos_small(phi, sn, cs);
         else sincos_fast(phi, sn, cs);
-        const float ag = g ? amp : 0.0f;
         const float pr = ag * cs, pi = ag * sn;
         const float nr = __builtin_fmaf(lr, Sr, __builtin_fmaf(-li, Si, pr));
         const float ni = __builtin_fmaf(li, Sr, __builtin_fmaf(lr, Si, pi));
@@ -637,7 +659,7 @@ static hipError_t launch_step(const FwdArgs &a, int conv_k, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int V, int KC>
+template <int V, int KC, bool VALVE>
 static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
 {
     // persistent grid: what fits on the chip (asked once per kernel)
@@ -646,7 +668,7 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC, VALVE>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
@@ -656,19 +678,29 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     const long long tiles = (long long)a.nLB * a.B * a.nT;
     const long long wgs = tiles < resident ? (tiles > 0 ? tiles : 1) : resident;
     dim3 grid((unsigned)wgs), block(FwdGeom::NSEG * FwdLPR);
-    hipLaunchKernelGGL((fwd_kernel<V, KC>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((fwd_kernel<V, KC, VALVE>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
 template <int V>
 static hipError_t launch_fwd_v(const FwdArgs &a, int conv_k, hipStream_t s)
 {
+    if (a.valve) {
+        switch (conv_k) {
+        case 0: return launch_fwd_vk<V, 0, true>(a, s);
+        case 1: return launch_fwd_vk<V, 1, true>(a, s);
+        case 2: return launch_fwd_vk<V, 2, true>(a, s);
+        case 3: return launch_fwd_vk<V, 3, true>(a, s);
+        case 4: return launch_fwd_vk<V, 4, true>(a, s);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (conv_k) {
-    case 0: return launch_fwd_vk<V, 0>(a, s);
-    case 1: return launch_fwd_vk<V, 1>(a, s);
-    case 2: return launch_fwd_vk<V, 2>(a, s);
-    case 3: return launch_fwd_vk<V, 3>(a, s);
-    case 4: return launch_fwd_vk<V, 4>(a, s);
+    case 0: return launch_fwd_vk<V, 0, false>(a, s);
+    case 1: return launch_fwd_vk<V, 1, false>(a, s);
+    case 2: return launch_fwd_vk<V, 2, false>(a, s);
+    case 3: return launch_fwd_vk<V, 3, false>(a, s);
+    case 4: return launch_fwd_vk<V, 4, false>(a, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -102,7 +102,7 @@ static_assert(sizeof(WsHeader) == 1024, "header size");
 
 struct WsLayout {
     int J, Jp, Jp128, nT;
-    size_t off_table, off_agg, off_pre, off_halo, off_part, off_dbg, total;
+    size_t off_table, off_agg, off_pre, off_halo, off_part, off_vpart, off_dbg, total;
 };
 
 constexpr uint32_t EPOCH_MOD = 1u << 30;
@@ -126,6 +126,11 @@ struct FwdArgs {
     int nTc;                     // checkpoint intervals per sequence
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int amp_mode;
+    // gate_mode 1 (per-head input valve, Sec. 3.3): logits [B][L][H]; a lane block of 32 lanes
+    // holds gpb = max(1, 32 / F) heads (groups); the valve is open when the logit >= valve_thr
+    const float *valve;          // null: gate_mode 0
+    int H, F, gpb;
+    float valve_thr;
     int small_angle;             // angles are bounded (conv clamp): skip the two-term range reduction
     long long isb, ist, osb, ost;
     float conv_clamp, out_clamp;
@@ -150,6 +155,13 @@ struct BwdArgs {
     int B, L, J, Jp, nT, nLB;
     int small_angle;
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
+    // gate_mode 1 (per-head input valve): see FwdArgs; vpart [B][G][L] receives, per valve group
+    // (a head, or the 32-lane slice of a head) and token, the sum over the group's lanes of
+    // a Re(conj(dp) e^{i phi}); G groups per token
+    const float *valve;          // null: gate_mode 0
+    float *vpart;                // null: no valve gradient wanted
+    int H, F, gpb, G;
+    float valve_thr;
     int amp_mode, want_param;
     long long isb, ist, osb, ost;
     float conv_clamp, grad_clamp;
@@ -199,6 +211,19 @@ __device__ __forceinline__ void sincos_small(float phi, float &s, float &c)
     s = __builtin_amdgcn_sinf(x);
     c = __builtin_amdgcn_cosf(x);
 }
+// The reduced angle in revolutions those two hand to the hardware (a caller short of registers
+// keeps this one value and asks the hardware for sin and cos again).
+__device__ __forceinline__ float revolutions_fast(float phi)
+{
+    const float INV_2PI = 0.15915494309189535f;
+    const float TWO_PI_HI = 6.2831854820251465f;
+    const float TWO_PI_LO = -1.7484555314695172e-07f;
+    float k = __builtin_rintf(phi * INV_2PI);
+    float r = __builtin_fmaf(-k, TWO_PI_HI, phi);
+    r = __builtin_fmaf(-k, TWO_PI_LO, r);
+    return r * INV_2PI;
+}
+__device__ __forceinline__ float revolutions_small(float phi) { return phi * 0.15915494309189535f; }
 
 __device__ __forceinline__ float softplus_fast(float m)
 {
@@ -320,6 +345,28 @@ __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const fl
         }
     }
 }
+// Stage the valve logits of one tile (gate_mode 1): entry (group, token) of the tile lands at
+// sV[group * TT + token]; the lane block's groups are the heads (gpb = 32 / F of them) or the
+// one head its 32 lanes lie in.  4 bytes per lane per load; called by one wave.
+template <int TT, int JB>
+__device__ __forceinline__ void stage_valve(float *sV, const float *valve, int b, int tile_t0, int lb, int L, int H,
+                                            int F, int gpb, int lane)
+{
+    const int h0 = (lb * JB) / F;
+    for (int i = 0; i < TT * gpb / 64; ++i) {
+        const int idx = i * 64 + lane;
+        int t = tile_t0 + idx % TT, h = h0 + idx / TT;
+        t = t < L ? t : L - 1;          // rows past the end, heads past the last: a valid address,
+        h = h < H ? h : H - 1;          // the value is never used
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_global_load_lds(valve + ((size_t)b * L + t) * H + h, sV + i * 64, 4, 0, 0);
+#else
+        (void)sV;
+        (void)valve;
+#endif
+    }
+}
+
 __device__ __forceinline__ void flag_store(uint32_t *p, uint32_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

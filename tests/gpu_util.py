@@ -59,12 +59,13 @@ class Workspaces:
 
 def run_fwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
             state_in=None, want_mask=True, want_ckpt=False, concat=False, in_place_state=False,
-            cached=0, ws=None):
+            cached=0, ws=None, valve=None, valve_eps=0.001):
     """inp: dict with mag, ang [B,L,J], gamma, theta, conv_w, conv_b (numpy float32).
     Returns dict(z_re, z_im, state_out (flat blob), mask [B,L,W] uint32, ckpt)."""
     J = H * F
     d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau,
-                    conv_clamp=conv_clamp, out_clamp=out_clamp, lane_consts_cached=cached)
+                    conv_clamp=conv_clamp, out_clamp=out_clamp, lane_consts_cached=cached,
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps)
     mag, ang = dev(inp["mag"][:, :L]), dev(inp["ang"][:, :L])
     gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
     cw = dev(inp["conv_w"]) if conv_k > 0 else None
@@ -87,8 +88,12 @@ def run_fwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0
     mask = torch.zeros((B, max(L, 1), W), dtype=torch.int32, device=DEV) if want_mask else None
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV) if want_ckpt else None
     ws = ws if ws is not None else Workspaces.get(d)
-    K.check(K.cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, cw, cb, st_in, z_re, z_im, st_out,
-                                        ckpt, mask, ws))
+    if valve is None:
+        K.check(K.cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, cw, cb, st_in, z_re, z_im, st_out,
+                                            ckpt, mask, ws))
+    else:
+        K.check(K.cawn_phase_accumulate_valve_fwd(d, mag, ang, dev(np.ascontiguousarray(valve[:, :L])), gamma,
+                                                  theta, cw, cb, st_in, z_re, z_im, st_out, ckpt, mask, ws))
     torch.cuda.synchronize()
     K.check(K.cawn_workspace_status(ws))
     out = dict(z_re=z_re[:, :L].cpu().numpy(), z_im=z_im[:, :L].cpu().numpy(),
@@ -112,13 +117,15 @@ def mask_from_gate(gate):
 
 def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
                 grad_clamp=100.0, state_in=None, dstate_out=None, want_param=True, want_dstate=True,
-                accumulate=0, preset=None, ws=None):
+                accumulate=0, preset=None, ws=None, valve=None, valve_eps=0.001, want_dvalve=True):
     """Forward (to get the checkpoints) then backward through the C ABI.  inp additionally holds
     dz_re, dz_im [B,L,J].  Returns dict of numpy arrays: dmag, dang, dgamma, dtheta, dconv_w, dconv_b,
     dstate_in (flat blob)."""
     J = H * F
     d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau, conv_clamp=conv_clamp,
-                    out_clamp=out_clamp, grad_clamp=grad_clamp, accumulate_param_grads=accumulate)
+                    out_clamp=out_clamp, grad_clamp=grad_clamp, accumulate_param_grads=accumulate,
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps)
+    vlv = None if valve is None else dev(np.ascontiguousarray(valve[:, :L]))
     mag, ang = dev(inp["mag"][:, :L]), dev(inp["ang"][:, :L])
     gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
     cw = dev(inp["conv_w"]) if conv_k > 0 else None
@@ -128,7 +135,11 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
     st_in = dev(state_in)
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
     ws = ws if ws is not None else Workspaces.get(d)
-    K.check(K.cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, cw, cb, st_in, z_re, z_im, None, ckpt, None, ws))
+    if valve is None:
+        K.check(K.cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, cw, cb, st_in, z_re, z_im, None, ckpt, None, ws))
+    else:
+        K.check(K.cawn_phase_accumulate_valve_fwd(d, mag, ang, vlv, gamma, theta, cw, cb, st_in, z_re, z_im, None,
+                                                  ckpt, None, ws))
     dz_re, dz_im = dev(inp["dz_re"][:, :L]), dev(inp["dz_im"][:, :L])
     dmag = torch.full((B, max(L, 1), J), float("nan"), device=DEV)
     dang = torch.full((B, max(L, 1), J), float("nan"), device=DEV)
@@ -140,11 +151,20 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
     dcb = torch.full((2, J), fill, device=DEV) if want_param and conv_k > 0 else None
     dst_in = torch.full((nstate,), float("nan"), device=DEV) if want_dstate else None
     d.lane_consts_cached = 1
-    K.check(K.cawn_phase_accumulate_bwd(d, mag, ang, gamma, theta, cw, cb, st_in, ckpt, dz_re, dz_im,
-                                        dev(dstate_out), dmag, dang, dgamma, dtheta, dcw, dcb, dst_in, ws))
+    dvalve = None
+    if valve is None:
+        K.check(K.cawn_phase_accumulate_bwd(d, mag, ang, gamma, theta, cw, cb, st_in, ckpt, dz_re, dz_im,
+                                            dev(dstate_out), dmag, dang, dgamma, dtheta, dcw, dcb, dst_in, ws))
+    else:
+        dvalve = torch.full((B, max(L, 1), H), float("nan"), device=DEV) if want_dvalve else None
+        K.check(K.cawn_phase_accumulate_valve_bwd(d, mag, ang, vlv, gamma, theta, cw, cb, st_in, ckpt, dz_re, dz_im,
+                                                  dev(dstate_out), dmag, dang, dvalve, dgamma, dtheta, dcw, dcb,
+                                                  dst_in, ws))
     torch.cuda.synchronize()
     K.check(K.cawn_workspace_status(ws))
     out = dict(dmag=dmag[:, :L].cpu().numpy(), dang=dang[:, :L].cpu().numpy())
+    if dvalve is not None:
+        out["dvalve"] = dvalve[:, :L].cpu().numpy()
     for k, v in (("dgamma", dgamma), ("dtheta", dtheta), ("dconv_w", dcw), ("dconv_b", dcb), ("dstate_in", dst_in)):
         if v is not None:
             out[k] = v.cpu().numpy()
