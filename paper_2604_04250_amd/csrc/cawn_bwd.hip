@@ -298,11 +298,15 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // the forward state entering the tile (checkpoint) and the constants of the reverse pass, fetched
     // now so that they arrive during the front-end (the valve kernels, at their register budget in
     // the front-end, fetch them after it)
+    // (written out twice rather than as a lambda called from two places: with the lambda the
+    // compiler allocates scalar registers differently over the whole loop and spills 2.7x as many)
     float kr[V], ki[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) kr[v] = ki[v] = 0.f;
     float psr[V], psi[V], cth[V], sth[V], gam[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) { kr[v] = ki[v] = sth[v] = gam[v] = 0.f; cth[v] = 1.f; }
-    auto fetch_reverse_consts = [&]() {
+    for (int v = 0; v < V; ++v) { sth[v] = gam[v] = 0.f; cth[v] = 1.f; }
+    if (!VALVE) {
         if (PARAM && active && a.ckpt) {
             const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
             BVec<V>::ld(kr, ck);
@@ -315,8 +319,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             ldu<V>(sth, row(R_SIN), jb);
             ldu<V>(gam, row(R_GAMMA), jb);
         }
-    };
-    if (!VALVE) fetch_reverse_consts();
+    }
 
     // ---- front-end recompute, rows from LDS as a sliding window
     float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V];   // ag: a*g*SiLU'(z_ang)
@@ -430,7 +433,20 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         default: front_end(T_{}, T_{}); break;
         }
     }
-    if (VALVE) fetch_reverse_consts();
+    if (VALVE) {
+        if (PARAM && active && a.ckpt) {
+            const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
+            BVec<V>::ld(kr, ck);
+            BVec<V>::ld(ki, ck + a.J);
+        }
+        ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);
+        ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
+        if (PARAM) {
+            ldu<V>(cth, row(R_COS), jb);
+            ldu<V>(sth, row(R_SIN), jb);
+            ldu<V>(gam, row(R_GAMMA), jb);
+        }
+    }
 
     // ---- forward state entering my segment (checkpoint + earlier segments), then S[t-1] per token
     if (PARAM) {

@@ -126,11 +126,6 @@ struct FwdArgs {
     int nTc;                     // checkpoint intervals per sequence
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int amp_mode;
-    // gate_mode 1 (per-head input valve, Sec. 3.3): logits [B][L][H]; a lane block of 32 lanes
-    // holds gpb = max(1, 32 / F) heads (groups); the valve is open when the logit >= valve_thr
-    const float *valve;          // null: gate_mode 0
-    int H, F, gpb;
-    float valve_thr;
     int small_angle;             // angles are bounded (conv clamp): skip the two-term range reduction
     long long isb, ist, osb, ost;
     float conv_clamp, out_clamp;
@@ -139,6 +134,12 @@ struct FwdArgs {
     uint32_t total_tiles;
     size_t clear_from;           // byte offset of the first published word (cleared when the epoch wraps)
     unsigned long long *dbg;     // -DCAWN_TIMING builds only
+    // (kept behind everything else: the kernels that do not use them fetch none of this)
+    // gate_mode 1 (per-head input valve, Sec. 3.3): logits [B][L][H]; a lane block of 32 lanes
+    // holds gpb = max(1, 32 / F) heads (groups); the valve is open when the logit >= valve_thr
+    const float *valve;          // null: gate_mode 0
+    int H, F, gpb;
+    float valve_thr;
 };
 
 struct BwdArgs {
@@ -155,13 +156,6 @@ struct BwdArgs {
     int B, L, J, Jp, nT, nLB;
     int small_angle;
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
-    // gate_mode 1 (per-head input valve): see FwdArgs; vpart [B][G][L] receives, per valve group
-    // (a head, or the 32-lane slice of a head) and token, the sum over the group's lanes of
-    // a Re(conj(dp) e^{i phi}); G groups per token
-    const float *valve;          // null: gate_mode 0
-    float *vpart;                // null: no valve gradient wanted
-    int H, F, gpb, G;
-    float valve_thr;
     int amp_mode, want_param;
     long long isb, ist, osb, ost;
     float conv_clamp, grad_clamp;
@@ -170,6 +164,14 @@ struct BwdArgs {
     uint32_t total_tiles;
     size_t clear_from;           // byte offset of the first published word (cleared when the epoch wraps)
     unsigned long long *dbg;     // -DCAWN_TIMING builds only
+    // (kept behind everything else: the kernels that do not use them fetch none of this)
+    // gate_mode 1 (per-head input valve): see FwdArgs; vpart [B][G][L] receives, per valve group
+    // (a head, or the 32-lane slice of a head) and token, the sum over the group's lanes of
+    // a Re(conj(dp) e^{i phi}); G groups per token
+    const float *valve;          // null: gate_mode 0
+    float *vpart;                // null: no valve gradient wanted
+    int H, F, gpb, G;
+    float valve_thr;
 };
 
 // Number of per-lane partial sums a backward tile emits: dgamma, dtheta, dbias[2], dw[2][conv_k].

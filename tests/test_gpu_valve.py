@@ -53,7 +53,7 @@ def _check_fwd(B, L, H, F, Kc, d, amp_mode=0, eps=0.001, state=None, **kw):
     return out, ora
 
 
-@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (8, 8), (1, 128), (5, 32)])
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (8, 8), (1, 128), (5, 32), (3, 16), (5, 8)])
 @pytest.mark.parametrize("Kc", [0, 4])
 def test_valve_forward_head_widths(H, F, Kc):
     B, L = 2, 700                      # three forward tiles, ragged tail
@@ -122,7 +122,7 @@ def _check_bwd(B, L, H, F, Kc, d, amp_mode=0, eps=0.001, state=None, dstate=None
     return out, ora
 
 
-@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (8, 8), (1, 128)])
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (8, 8), (1, 128), (3, 16), (5, 8)])
 @pytest.mark.parametrize("Kc", [0, 2, 4])
 def test_valve_backward_head_widths(H, F, Kc):
     B, L = 2, 333                      # three backward tiles, ragged tail
