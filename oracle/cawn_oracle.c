@@ -19,6 +19,14 @@
  *   - Causal phase accumulation (Sec. 3.4 accumulation equations, real form):
  *       S_r[t] = p_r[t] + gamma (S_r[t-1] cos th - S_i[t-1] sin th)
  *       S_i[t] = p_i[t] + gamma (S_r[t-1] sin th + S_i[t-1] cos th),  S[-1] = state_in or 0.
+ *   - ret_mode 1, the retention gate as Sec. 3.3 item 4 and "Frequency-Dependent Retention" state
+ *     it: one logit r per (token, head) (the per-head projection, its own bias included) plus a
+ *     static per-harmonic bias b_k; gamma[t][h][k] = sigmoid(r[t][h] + b_k) takes the place of the
+ *     constant gamma_j in the accumulation equations, which are printed with gamma_{t,j}: the
+ *     retention of token t multiplies the rotated state of token t-1.  Backward: the adjoint of
+ *     token t reaches token t-1 through gamma[t]; d gamma[t] = Re(conj(G[t]) e^{i th} S[t-1]) per
+ *     lane (clamped like every returned per-element gradient), chained through the sigmoid and
+ *     summed over the harmonics of a head into d r[t][h].  b_k is static: no gradient.
  *   - Output clamp (Sec. 3.4 clamp equation), Concat layout (Sec. 3.5).
  *   - State passing (Sec. 3.7 / Sec. 5 chunked prefill): the phase state plus the last
  *     conv_k-1 pre-conv rows.
@@ -60,7 +68,7 @@ typedef struct {
     int32_t gate_mode;       /* 0: per-lane threshold on |a|;  1: per-head valve (Sec. 3.3) */
     float gate_tau;          /* threshold, same fp32 value the GPU gets; 0 = open           */
     float valve_eps;         /* gate_mode 1: the valve closes below this (paper: 0.001)     */
-    float pad_;
+    int32_t ret_mode;        /* 0: constant gamma[j];  1: sigmoid(ret[t][h] + ret_bias[k])  */
     double conv_clamp;       /* 50 in the paper; +inf disables                              */
     double out_clamp;        /* 100; +inf disables                                          */
     double grad_clamp;       /* 100; +inf disables                                          */
@@ -213,21 +221,33 @@ static front_t front_end(const oracle_cfg *c, const float *mag, const float *ang
     return f;
 }
 
+/* Retention of token t on lane j = h F + k (Sec. 3.3 item 4): what multiplies the rotated S[t-1]. */
+static double retention(const oracle_cfg *c, const float *ret, const float *ret_bias,
+                        const float *gamma, int b, int t, int j)
+{
+    if (c->ret_mode != 1) return (double)gamma[j];
+    return sigmoid((double)ret[((size_t)b * c->L + t) * c->H + j / c->F] + (double)ret_bias[j % c->F]);
+}
+
 /*
  * Forward: front-end, gate, phasor, accumulation, clamp.
  *   mag, ang   [B][L][J] fp32          gamma, theta [J] fp32
+ *   valve      [B][L][H] fp32 (gate_mode 1)
+ *   ret        [B][L][H] fp32, ret_bias [F] fp32 (ret_mode 1; gamma is then unused)
  *   conv_w     [2][J][Kc] fp32         conv_b [2][J] fp32 or NULL   (unused when conv_k = 0)
  *   scan_in    [B][2][J] fp64 or NULL  tail_in [B][Kc-1][2][J] fp32 or NULL
  *   z_re, z_im [B][L][J] fp64          scan_out [B][2][J] fp64 or NULL (unclamped S[L-1])
  *   tail_out   [B][Kc-1][2][J] fp32 or NULL      gate [B][L][J] bytes (0/1) or NULL
  */
 int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, const float *valve,
+                     const float *ret, const float *ret_bias,
                      const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                      const double *scan_in, const float *tail_in, double *z_re, double *z_im,
                      double *scan_out, float *tail_out, uint8_t *gate)
 {
     if (!c || c->B <= 0 || c->L < 0 || c->H <= 0 || c->F <= 0 || c->conv_k < 0) return -1;
     if (c->gate_mode == 1 && !valve) return -1;
+    if (c->ret_mode == 1 ? (!ret || !ret_bias) : !gamma) return -1;
     const int B = c->B, L = c->L, J = c->H * c->F, Kc = c->conv_k;
 #ifdef _OPENMP
     if (c->nthreads > 0) omp_set_num_threads(c->nthreads);
@@ -235,13 +255,14 @@ int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, co
 #pragma omp parallel for schedule(static)
     for (int bj = 0; bj < B * J; ++bj) {
         const int b = bj / J, j = bj % J;
-        const double ga = (double)gamma[j], ct = cos((double)theta[j]), st = sin((double)theta[j]);
+        const double ct = cos((double)theta[j]), st = sin((double)theta[j]);
         double Sr = scan_in ? scan_in[((size_t)b * 2 + 0) * J + j] : 0.0;
         double Si = scan_in ? scan_in[((size_t)b * 2 + 1) * J + j] : 0.0;
         for (int t = 0; t < L; ++t) {
             front_t f = front_end(c, mag, ang, valve, conv_w, conv_b, tail_in, b, t, j);
             double pr = f.g ? f.scale * f.a * cos(f.phi) : 0.0;
             double pi = f.g ? f.scale * f.a * sin(f.phi) : 0.0;
+            const double ga = retention(c, ret, ret_bias, gamma, b, t, j);
             double nr = pr + ga * (Sr * ct - Si * st);
             double ni = pi + ga * (Sr * st + Si * ct);
             double zr = clampd(nr, c->out_clamp), zi = clampd(ni, c->out_clamp);
@@ -277,21 +298,24 @@ int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, co
  * Outputs (fp64, any may be NULL except dmag, dang):
  *   dmag, dang [B][L][J]; dgamma, dtheta [J]; dconv_w [2][J][Kc]; dconv_b [2][J];
  *   dscan_in [B][2][J]; dtail_in [B][Kc-1][2][J]; gate_mode 1: dvalve [B][L][H] (needs
- *   valve_term, scratch of [B][L][J] doubles: the per-lane terms, summed per head afterwards).
+ *   valve_term, scratch of [B][L][J] doubles: the per-lane terms, summed per head afterwards);
+ *   ret_mode 1: dret [B][L][H] (needs ret_term, the same kind of scratch); dgamma is not written.
  * Parameter gradients are overwritten (summed over b and t).
  */
 int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, const float *valve,
+                     const float *ret, const float *ret_bias,
                      const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                      const double *scan_in, const float *tail_in, const float *dz_re,
                      const float *dz_im, const double *dscan_out, const double *dtail_out,
                      double *dmag, double *dang, double *dgamma, double *dtheta, double *dconv_w,
                      double *dconv_b, double *dscan_in, double *dtail_in, double *dvalve,
-                     double *valve_term)
+                     double *valve_term, double *dret, double *ret_term)
 {
     if (!c || c->B <= 0 || c->L < 0 || c->H <= 0 || c->F <= 0 || c->conv_k < 0 || c->conv_k > 16)
         return -1;
     if (c->clamp_feedback) return -2;
     if (c->gate_mode == 1 && (!valve || (dvalve && !valve_term))) return -1;
+    if (c->ret_mode == 1 ? (!ret || !ret_bias || (dret && !ret_term)) : !gamma) return -1;
     const int B = c->B, L = c->L, J = c->H * c->F, Kc = c->conv_k;
     const double gc = c->grad_clamp;
 #ifdef _OPENMP
@@ -299,7 +323,7 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
 #endif
 #pragma omp parallel for schedule(static)
     for (int j = 0; j < J; ++j) {
-        const double ga = (double)gamma[j], ct = cos((double)theta[j]), st = sin((double)theta[j]);
+        const double ct = cos((double)theta[j]), st = sin((double)theta[j]);
         double acc_g = 0.0, acc_t = 0.0;
         double acc_w[2][16], acc_b[2] = {0.0, 0.0};
         for (int s = 0; s < 2; ++s)
@@ -317,27 +341,32 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
                 fr[t] = front_end(c, mag, ang, valve, conv_w, conv_b, tail_in, b, t, j);
                 double pr = fr[t].g ? fr[t].scale * fr[t].a * cos(fr[t].phi) : 0.0;
                 double pi = fr[t].g ? fr[t].scale * fr[t].a * sin(fr[t].phi) : 0.0;
+                const double ga = retention(c, ret, ret_bias, gamma, b, t, j);
                 Sr[t + 1] = pr + ga * (Sr[t] * ct - Si[t] * st);
                 Si[t + 1] = pi + ga * (Sr[t] * st + Si[t] * ct);
             }
             /* reverse-time adjoint */
-            double Gr = 0.0, Gi = 0.0; /* conj(lambda) * G[t+1] enters below */
+            double Gr = 0.0, Gi = 0.0;
+            double Mr = 0.0, Mi = 0.0; /* what token t+1 hands back: gamma[t+1] conj(e^{i th}) G[t+1] */
             for (int t = L - 1; t >= 0; --t) {
+                const double ga = retention(c, ret, ret_bias, gamma, b, t, j);
                 size_t o = ((size_t)b * L + t) * J + j;
                 double dSr = (double)dz_re[o], dSi = (double)dz_im[o]; /* clamp passes gradient */
                 if (t == L - 1 && dscan_out) {
                     dSr += dscan_out[((size_t)b * 2 + 0) * J + j];
                     dSi += dscan_out[((size_t)b * 2 + 1) * J + j];
                 }
-                /* G[t] = dS[t] + conj(lambda) G[t+1] */
-                double nGr = dSr + ga * (Gr * ct + Gi * st);
-                double nGi = dSi + ga * (-Gr * st + Gi * ct);
-                Gr = nGr;
-                Gi = nGi;
+                /* G[t] = dS[t] + gamma[t+1] conj(e^{i th}) G[t+1] */
+                Gr = dSr + Mr;
+                Gi = dSi + Mi;
+                Mr = ga * (Gr * ct + Gi * st);
+                Mi = ga * (-Gr * st + Gi * ct);
                 /* parameter terms use S[t-1] and the unclamped adjoint */
                 double rr = Sr[t] * ct - Si[t] * st, ri = Sr[t] * st + Si[t] * ct; /* e^{i th} S[t-1] */
                 acc_g += clampd(Gr * rr + Gi * ri, gc);
                 acc_t += clampd(ga * (Gr * (-ri) + Gi * rr), gc);
+                /* d gamma[t] on this lane, chained through the sigmoid */
+                if (c->ret_mode == 1 && dret) ret_term[o] = clampd(Gr * rr + Gi * ri, gc) * ga * (1.0 - ga);
                 /* returned dp, clamped, then chained to amplitude and phase */
                 double hr = clampd(Gr, gc), hi = clampd(Gi, gc);
                 double cph = cos(fr[t].phi), sph = sin(fr[t].phi);
@@ -361,8 +390,8 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
                 }
             }
             if (dscan_in) {
-                dscan_in[((size_t)b * 2 + 0) * J + j] = ga * (Gr * ct + Gi * st);
-                dscan_in[((size_t)b * 2 + 1) * J + j] = ga * (-Gr * st + Gi * ct);
+                dscan_in[((size_t)b * 2 + 0) * J + j] = Mr;
+                dscan_in[((size_t)b * 2 + 1) * J + j] = Mi;
             }
             if (Kc > 0) {
                 /* transposed conv, weight and bias gradients, history gradient */
@@ -400,7 +429,7 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
                 }
             }
         }
-        if (dgamma) dgamma[j] = acc_g;
+        if (dgamma && c->ret_mode != 1) dgamma[j] = acc_g;
         if (dtheta) dtheta[j] = acc_t;
         if (Kc > 0) {
             for (int s = 0; s < 2; ++s) {
@@ -421,6 +450,14 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
                     for (int k = 0; k < c->F; ++k) sum += valve_term[((size_t)b * L + t) * J + h * c->F + k];
                     const double bs = sigmoid((double)valve[((size_t)b * L + t) * c->H + h] - 3.0);
                     dvalve[((size_t)b * L + t) * c->H + h] = bs * (1.0 - bs) * sum;
+                }
+    if (c->ret_mode == 1 && dret)
+        for (int b = 0; b < B; ++b)
+            for (int t = 0; t < L; ++t)
+                for (int h = 0; h < c->H; ++h) {
+                    double sum = 0.0;
+                    for (int k = 0; k < c->F; ++k) sum += ret_term[((size_t)b * L + t) * J + h * c->F + k];
+                    dret[((size_t)b * L + t) * c->H + h] = sum;
                 }
     return 0;
 }

@@ -6,7 +6,9 @@ imports nothing of the GPU package.
 
 Array conventions (numpy, C-contiguous):
   mag, ang          float32 [B, L, J]       J = H*F, lane j = h*F + k fastest
-  gamma, theta      float32 [J]
+  gamma, theta      float32 [J]             (gamma may be None with ret_mode 1)
+  valve, ret        float32 [B, L, H]       per-head logits (gate_mode 1 / ret_mode 1)
+  ret_bias          float32 [F]             static per-harmonic retention bias b_k
   conv_w            float32 [2, J, Kc]      stream 0 = magnitude, 1 = angle
   conv_b            float32 [2, J] or None
   scan state        float64 [B, 2, J]       (re, im) of S at the last token, unclamped
@@ -39,7 +41,7 @@ class _Cfg(C.Structure):
     _fields_ = [("B", C.c_int32), ("L", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
                 ("conv_k", C.c_int32), ("amp_mode", C.c_int32), ("clamp_feedback", C.c_int32),
                 ("nthreads", C.c_int32), ("gate_mode", C.c_int32), ("gate_tau", C.c_float),
-                ("valve_eps", C.c_float), ("pad_", C.c_float),
+                ("valve_eps", C.c_float), ("ret_mode", C.c_int32),
                 ("conv_clamp", C.c_double), ("out_clamp", C.c_double), ("grad_clamp", C.c_double)]
 
 
@@ -74,6 +76,7 @@ class Cfg:
     nthreads: int = 0
     gate_mode: int = 0          # 1: per-head valve (valve logits [B, L, H]), Sec. 3.3
     valve_eps: float = 0.001
+    ret_mode: int = 0           # 1: retention sigmoid(ret[B,L,H] + ret_bias[F]), Sec. 3.3 item 4
 
     @property
     def J(self) -> int:
@@ -82,7 +85,7 @@ class Cfg:
     def c(self) -> _Cfg:
         return _Cfg(self.B, self.L, self.H, self.F, self.conv_k, self.amp_mode, self.clamp_feedback,
                     self.nthreads, self.gate_mode, np.float32(self.gate_tau),
-                    np.float32(self.valve_eps), 0.0, self.conv_clamp, self.out_clamp, self.grad_clamp)
+                    np.float32(self.valve_eps), self.ret_mode, self.conv_clamp, self.out_clamp, self.grad_clamp)
 
 
 def _p(a):
@@ -131,8 +134,14 @@ def syntax_conv(x, w, bias=None, hist_in=None, conv_clamp=50.0, want_hist=True):
     return y, hist
 
 
+def _ret_args(cfg: Cfg, ret, ret_bias):
+    if cfg.ret_mode != 1:
+        return None, None
+    return _f32(ret, (cfg.B, cfg.L, cfg.H)), _f32(ret_bias, (cfg.F,))
+
+
 def phase_fwd(cfg: Cfg, mag, ang, gamma, theta, conv_w=None, conv_b=None, scan_in=None,
-              tail_in=None, want_gate=True, valve=None):
+              tail_in=None, want_gate=True, valve=None, ret=None, ret_bias=None):
     """Forward.  Returns dict(z_re, z_im [B,L,J] f64, scan_out [B,2,J] f64,
     tail_out [B,Kc-1,2,J] f32 or None, gate [B,L,J] uint8)."""
     B, L, J, Kc = cfg.B, cfg.L, cfg.J, cfg.conv_k
@@ -140,6 +149,7 @@ def phase_fwd(cfg: Cfg, mag, ang, gamma, theta, conv_w=None, conv_b=None, scan_i
     ang = _f32(ang, (B, L, J))
     gamma = _f32(gamma, (J,))
     theta = _f32(theta, (J,))
+    ret, ret_bias = _ret_args(cfg, ret, ret_bias)
     if Kc > 0:
         conv_w = _f32(conv_w, (2, J, Kc))
         conv_b = _f32(conv_b, (2, J))
@@ -154,7 +164,7 @@ def phase_fwd(cfg: Cfg, mag, ang, gamma, theta, conv_w=None, conv_b=None, scan_i
     gate = np.empty((B, L, J), dtype=np.uint8) if want_gate else None
     valve = _f32(valve, (B, L, cfg.H)) if cfg.gate_mode == 1 else None
     cc = cfg.c()
-    rc = lib().oracle_phase_fwd(C.byref(cc), _p(mag), _p(ang), _p(valve), _p(gamma), _p(theta), _p(conv_w),
+    rc = lib().oracle_phase_fwd(C.byref(cc), _p(mag), _p(ang), _p(valve), _p(ret), _p(ret_bias), _p(gamma), _p(theta), _p(conv_w),
                                 _p(conv_b), _p(scan_in), _p(tail_in), _p(z_re), _p(z_im),
                                 _p(scan_out), _p(tail_out), _p(gate))
     assert rc == 0, rc
@@ -162,9 +172,11 @@ def phase_fwd(cfg: Cfg, mag, ang, gamma, theta, conv_w=None, conv_b=None, scan_i
 
 
 def phase_bwd(cfg: Cfg, mag, ang, gamma, theta, dz_re, dz_im, conv_w=None, conv_b=None,
-              scan_in=None, tail_in=None, dscan_out=None, dtail_out=None, valve=None):
+              scan_in=None, tail_in=None, dscan_out=None, dtail_out=None, valve=None, ret=None,
+              ret_bias=None):
     """Backward.  Returns dict(dmag, dang [B,L,J], dgamma, dtheta [J], dconv_w [2,J,Kc],
-    dconv_b [2,J], dscan_in [B,2,J], dtail_in [B,Kc-1,2,J]; gate_mode 1: dvalve [B,L,H]) in f64."""
+    dconv_b [2,J], dscan_in [B,2,J], dtail_in [B,Kc-1,2,J]; gate_mode 1: dvalve [B,L,H];
+    ret_mode 1: dret [B,L,H] and no dgamma) in f64."""
     B, L, J, Kc = cfg.B, cfg.L, cfg.J, cfg.conv_k
     mag = _f32(mag, (B, L, J))
     ang = _f32(ang, (B, L, J))
@@ -193,12 +205,18 @@ def phase_bwd(cfg: Cfg, mag, ang, gamma, theta, dz_re, dz_im, conv_w=None, conv_
         term = np.zeros((B, L, J))
     else:
         valve = None
+    ret, ret_bias = _ret_args(cfg, ret, ret_bias)
+    rterm = None
+    if cfg.ret_mode == 1:
+        out["dret"] = np.zeros((B, L, cfg.H))
+        rterm = np.zeros((B, L, J))
+        del out["dgamma"]
     cc = cfg.c()
-    rc = lib().oracle_phase_bwd(C.byref(cc), _p(mag), _p(ang), _p(valve), _p(gamma), _p(theta), _p(conv_w),
+    rc = lib().oracle_phase_bwd(C.byref(cc), _p(mag), _p(ang), _p(valve), _p(ret), _p(ret_bias), _p(gamma), _p(theta), _p(conv_w),
                                 _p(conv_b), _p(scan_in), _p(tail_in), _p(dz_re), _p(dz_im),
                                 _p(dscan_out), _p(dtail_out), _p(out["dmag"]), _p(out["dang"]),
-                                _p(out["dgamma"]), _p(out["dtheta"]), _p(out.get("dconv_w")),
+                                _p(out.get("dgamma")), _p(out["dtheta"]), _p(out.get("dconv_w")),
                                 _p(out.get("dconv_b")), _p(out["dscan_in"]), _p(out.get("dtail_in")),
-                                _p(out.get("dvalve")), _p(term))
+                                _p(out.get("dvalve")), _p(term), _p(out.get("dret")), _p(rterm))
     assert rc == 0, rc
     return out

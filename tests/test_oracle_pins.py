@@ -605,6 +605,165 @@ def test_valve_full_open_reduces_to_the_ungated_path():
     np.testing.assert_allclose(a["z_im"], b["z_im"], rtol=1e-14, atol=1e-14)
 
 
+def _ret_inputs(seed, B, L, H, F):
+    r = rng_(seed)
+    ret = (-0.5 + 1.5 * r.standard_normal((B, L, H))).astype(np.float32)
+    bias = np.linspace(3.0, 0.0, F).astype(np.float32)          # Sec. 3.3: b_k falls from +3 to 0
+    gam = np_sigmoid(ret.astype(np.float64)[..., None] + bias.astype(np.float64)).reshape(B, L, H * F)
+    return ret, bias, gam
+
+
+def test_retention_brute_force_sum_with_per_token_decay():
+    """ret_mode 1 (Sec. 3.3 item 4, accumulation equations with gamma_{t,j}):
+    S_t = sum_{s<=t} p_s e^{i theta (t-s)} prod_{r=s+1..t} gamma_r: the retention of token r scales
+    what arrives from r-1, so a push is never scaled by its own token's retention."""
+    B, L, H, F = 2, 19, 2, 3
+    J = H * F
+    d = small(61, B, L, H, F)
+    ret, bias, gam = _ret_inputs(62, B, L, H, F)
+    s_in = rng_(63).standard_normal((B, 2, J))
+    o = O.phase_fwd(O.Cfg(B, L, H, F, ret_mode=1, out_clamp=INF), d["mag"], d["ang"], None, d["theta"],
+                    scan_in=s_in, ret=ret, ret_bias=bias)
+    p = d["mag"].astype(np.float64) * np.exp(1j * d["ang"].astype(np.float64))
+    th = d["theta"].astype(np.float64)
+    want = np.zeros((B, L, J), dtype=complex)
+    for t in range(L):
+        for s in range(-1, t + 1):
+            src = (s_in[:, 0] + 1j * s_in[:, 1]) if s < 0 else p[:, s]
+            decay = np.ones((B, J))
+            for r in range(s + 1, t + 1):
+                decay = decay * gam[:, r]
+            want[:, t] += src * decay * np.exp(1j * th * (t - s))
+    np.testing.assert_allclose(o["z_re"], want.real, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(o["z_im"], want.imag, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(o["scan_out"][:, 0], want[:, -1].real, rtol=1e-12, atol=1e-12)
+
+
+def test_retention_two_tokens_by_hand_and_bias_runs_over_harmonics():
+    # one head, two harmonics, theta = 0, unit pushes: S_1 = 1 + sigmoid(r_1 + b_k), r_0 plays no role
+    B, L, H, F = 1, 2, 1, 2
+    mag = np.ones((B, L, 2), np.float32)
+    ang = np.zeros((B, L, 2), np.float32)
+    ret = np.array([[[5.0], [-1.0]]], np.float32)
+    bias = np.array([3.0, 0.0], np.float32)
+    o = O.phase_fwd(O.Cfg(B, L, H, F, ret_mode=1), mag, ang, None, np.zeros(2, np.float32), ret=ret, ret_bias=bias)
+    assert o["z_re"][0, 0].tolist() == [1.0, 1.0]
+    assert o["z_re"][0, 1, 0] == pytest.approx(1.0 + 1.0 / (1.0 + math.exp(-2.0)), rel=1e-15)   # 1.8807970779778824
+    assert o["z_re"][0, 1, 1] == pytest.approx(1.0 + 1.0 / (1.0 + math.exp(1.0)), rel=1e-15)    # 1.2689414213699951
+    # two heads: the bias index is the harmonic k = j mod F, the logit index the head h = j div F
+    H = 2
+    mag = np.ones((B, L, 4), np.float32); ang = np.zeros((B, L, 4), np.float32)
+    ret = np.array([[[0.0, 0.0], [-1.0, 2.0]]], np.float32)
+    o = O.phase_fwd(O.Cfg(B, L, H, F, ret_mode=1), mag, ang, None, np.zeros(4, np.float32), ret=ret, ret_bias=bias)
+    want = [1 + 1 / (1 + math.exp(-2.0)), 1 + 1 / (1 + math.exp(1.0)), 1 + 1 / (1 + math.exp(-5.0)), 1 + 1 / (1 + math.exp(-2.0))]
+    np.testing.assert_allclose(o["z_re"][0, 1], want, rtol=1e-15)
+
+
+def test_retention_constant_logit_reduces_to_constant_gamma():
+    # logits chosen so that sigmoid(r + b_k) is a dyadic number: the constant-gamma path gets it exactly
+    B, L, H, F, Kc = 2, 40, 2, 2, 3
+    d = small(71, B, L, H, F, Kc)
+    bias = np.zeros(F, np.float32)
+    ret = np.zeros((B, L, H), np.float32)                  # sigmoid(0) = 0.5 exactly
+    gamma = np.full(H * F, 0.5, np.float32)
+    a = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc, ret_mode=1), d["mag"], d["ang"], None, d["theta"], d["conv_w"],
+                    d["conv_b"], ret=ret, ret_bias=bias)
+    b = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc), d["mag"], d["ang"], gamma, d["theta"], d["conv_w"], d["conv_b"])
+    assert np.array_equal(a["z_re"], b["z_re"]) and np.array_equal(a["z_im"], b["z_im"])
+    dz = rng_(72).standard_normal((2, B, L, H * F)).astype(np.float32)
+    ga = O.phase_bwd(O.Cfg(B, L, H, F, conv_k=Kc, ret_mode=1), d["mag"], d["ang"], None, d["theta"], dz[0], dz[1],
+                     d["conv_w"], d["conv_b"], ret=ret, ret_bias=bias)
+    gb = O.phase_bwd(O.Cfg(B, L, H, F, conv_k=Kc), d["mag"], d["ang"], gamma, d["theta"], dz[0], dz[1],
+                     d["conv_w"], d["conv_b"])
+    for k in ("dmag", "dang", "dtheta", "dconv_w", "dconv_b", "dscan_in"):
+        assert np.array_equal(ga[k], gb[k]), k
+    assert "dgamma" not in ga
+
+
+def test_retention_chunked_equals_unchunked_bitwise():
+    B, L, H, F = 2, 33, 2, 3
+    d = small(81, B, L, H, F)
+    ret, bias, _ = _ret_inputs(82, B, L, H, F)
+    full = O.phase_fwd(O.Cfg(B, L, H, F, ret_mode=1), d["mag"], d["ang"], None, d["theta"], ret=ret, ret_bias=bias)
+    st, outs = None, []
+    for lo, hi in ((0, 7), (7, 8), (8, 33)):
+        o = O.phase_fwd(O.Cfg(B, hi - lo, H, F, ret_mode=1), d["mag"][:, lo:hi], d["ang"][:, lo:hi], None, d["theta"],
+                        scan_in=st, ret=ret[:, lo:hi], ret_bias=bias)
+        st = o["scan_out"]
+        outs.append(o["z_re"])
+    assert np.array_equal(np.concatenate(outs, axis=1), full["z_re"])
+
+
+def test_retention_gradients_numpy_chain_and_finite_differences():
+    """Adjoint with per-token retention: G_t = dS_t + gamma_{t+1} conj(e^{i theta}) G_{t+1};
+    d gamma_t = Re(conj(G_t) e^{i theta} S_{t-1}); d r[t][h] = sum_k d gamma_t gamma_t (1 - gamma_t);
+    d S_in = gamma_0 conj(e^{i theta}) G_0.  Then every gradient against central differences."""
+    B, L, H, F = 2, 12, 2, 3
+    J = H * F
+    d = small(91, B, L, H, F)
+    ret, bias, gam = _ret_inputs(92, B, L, H, F)
+    r = rng_(93)
+    dz = r.standard_normal((2, B, L, J)).astype(np.float32)
+    s_in = r.standard_normal((B, 2, J))
+    ds_out = r.standard_normal((B, 2, J))
+    cfg = O.Cfg(B, L, H, F, ret_mode=1, out_clamp=INF, grad_clamp=INF)
+    g = O.phase_bwd(cfg, d["mag"], d["ang"], None, d["theta"], dz[0], dz[1], scan_in=s_in, dscan_out=ds_out,
+                    ret=ret, ret_bias=bias)
+    th = d["theta"].astype(np.float64)
+    rot = np.exp(1j * th)
+    p = d["mag"].astype(np.float64) * np.exp(1j * d["ang"].astype(np.float64))
+    S = np.zeros((B, L + 1, J), dtype=complex)           # S[:, t+1] = S_t
+    S[:, 0] = s_in[:, 0] + 1j * s_in[:, 1]
+    for t in range(L):
+        S[:, t + 1] = p[:, t] + gam[:, t] * rot * S[:, t]
+    dS = dz[0].astype(np.float64) + 1j * dz[1].astype(np.float64)
+    dS[:, L - 1] += ds_out[:, 0] + 1j * ds_out[:, 1]
+    G = np.zeros((B, L, J), dtype=complex)
+    for t in range(L - 1, -1, -1):
+        G[:, t] = dS[:, t] + (gam[:, t + 1] * np.conj(rot) * G[:, t + 1] if t + 1 < L else 0.0)
+    dgam = (np.conj(G) * rot * S[:, :L]).real
+    np.testing.assert_allclose(g["dret"], (dgam * gam * (1 - gam)).reshape(B, L, H, F).sum(axis=3), atol=1e-11)
+    np.testing.assert_allclose(g["dtheta"], (np.conj(G) * 1j * gam * rot * S[:, :L]).real.sum(axis=(0, 1)), atol=1e-10)
+    m0 = gam[:, 0] * np.conj(rot) * G[:, 0]
+    np.testing.assert_allclose(g["dscan_in"][:, 0], m0.real, atol=1e-12)
+    np.testing.assert_allclose(g["dscan_in"][:, 1], m0.imag, atol=1e-12)
+    np.testing.assert_allclose(g["dmag"], (np.conj(G) * np.exp(1j * d["ang"].astype(np.float64))).real, atol=1e-12)
+
+    def loss(ret_=ret, mag_=d["mag"], theta_=d["theta"], s_in_=s_in):
+        o = O.phase_fwd(O.Cfg(B, L, H, F, ret_mode=1, out_clamp=INF), mag_, d["ang"], None, theta_, scan_in=s_in_,
+                        ret=ret_, ret_bias=bias, want_gate=False)
+        return float((o["z_re"] * dz[0]).sum() + (o["z_im"] * dz[1]).sum()
+                     + (o["scan_out"] * ds_out).sum())
+
+    h = np.float32(2.0 ** -7)
+    for (b, t, hh) in [(0, 0, 0), (1, 4, 1), (0, 11, 1), (1, 7, 0)]:
+        rp = ret.copy(); rm = ret.copy()
+        rp[b, t, hh] += h; rm[b, t, hh] -= h
+        fd = (loss(ret_=rp) - loss(ret_=rm)) / (float(rp[b, t, hh]) - float(rm[b, t, hh]))
+        assert g["dret"][b, t, hh] == pytest.approx(fd, rel=2e-3, abs=1e-6)
+    for j in (0, 4):
+        tp = d["theta"].copy(); tm = d["theta"].copy()
+        tp[j] += h; tm[j] -= h
+        fd = (loss(theta_=tp) - loss(theta_=tm)) / (float(tp[j]) - float(tm[j]))
+        assert g["dtheta"][j] == pytest.approx(fd, rel=2e-3, abs=1e-6)
+    sp = s_in.copy(); sp[1, 1, 2] += 1e-5
+    sm = s_in.copy(); sm[1, 1, 2] -= 1e-5
+    assert g["dscan_in"][1, 1, 2] == pytest.approx((loss(s_in_=sp) - loss(s_in_=sm)) / 2e-5, rel=1e-5, abs=1e-8)
+
+
+def test_retention_gradient_term_is_clamped_before_the_sigmoid_chain():
+    # one lane, one head: d gamma_1 = G_1 S_0 = 1000 * 1 -> clamped to 100, times gamma (1 - gamma)
+    B, L, H, F = 1, 2, 1, 1
+    mag = np.array([[[1.0], [0.0]]], np.float32)
+    ang = np.zeros((B, L, 1), np.float32)
+    dz_re = np.array([[[0.0], [1000.0]]], np.float32)
+    ret = np.zeros((B, L, 1), np.float32)
+    g = O.phase_bwd(O.Cfg(B, L, H, F, ret_mode=1, grad_clamp=100.0), mag, ang, None, np.zeros(1, np.float32), dz_re,
+                    np.zeros_like(dz_re), ret=ret, ret_bias=np.zeros(1, np.float32))
+    assert g["dret"][0, 1, 0] == 100.0 * 0.25
+    assert g["dret"][0, 0, 0] == 0.0          # S_{-1} = 0
+
+
 def test_theta_init_endpoints_and_ratio():
     H, F = 12, 64
     th = O.theta_init(H, F).astype(np.float64)
