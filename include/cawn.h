@@ -61,6 +61,10 @@ typedef struct cawn_desc {
                                        last call on this workspace with the same H, F, conv_k
                                        that had this flag 0 -- skip rebuilding the lane table   */
     float valve_eps;      /* gate_mode 1: the valve closes below this (paper: 0.001)            */
+    int32_t ret_mode;     /* 0 constant per-lane retention gamma[j]; 1 data-dependent retention
+                             sigmoid(ret[t][h] + ret_bias[k]) (cawn_phase_accumulate_ret_fwd; same
+                             head widths as gate_mode 1)                                        */
+    int32_t reserved_;    /* 0 */
     int64_t in_stride_b, in_stride_t;   /* element strides of mag/ang/dmag/dang; 0 = dense
                                            (t stride J, b stride L*J); lane stride is always 1;
                                            t strides above 2^21 elements: CAWN_EUNSUPPORTED     */
@@ -184,6 +188,28 @@ int cawn_phase_accumulate_valve_bwd(const cawn_desc *d, const float *mag, const 
                                     float *dgamma, float *dtheta, float *dconv_w, float *dconv_b,
                                     void *dstate_in, void *workspace, size_t workspace_bytes,
                                     void *stream);
+
+/*
+ * Forward with the data-dependent retention gate of Sec. 3.3 (item 4 of the projection list,
+ * "Frequency-Dependent Retention"): in the accumulation equations of Sec. 3.4 the constant
+ * gamma[j] is replaced by gamma[t][h][k] = sigmoid(ret[t][h] + ret_bias[k]), which scales what
+ * arrives from token t-1.  d->ret_mode must be 1; d->gate_mode selects the gate as above.
+ *   valve        [B][L][H] logits when d->gate_mode == 1, ignored (may be NULL) otherwise
+ *   ret          [B][L][H] fp32 retention logits, dense (the per-head projection, its own bias
+ *                included)
+ *   ret_bias     [F] fp32, the static per-harmonic bias b_k (paper: linear from +3 to 0); part
+ *                of the lane constants (see d->lane_consts_cached)
+ * There is no gamma argument.  Everything else, errors included, as in
+ * cawn_phase_accumulate_fwd; head widths as for gate_mode 1; the workspace size depends on
+ * ret_mode.  A workspace's cached lane constants are only valid for the ret_mode they were built
+ * with.
+ */
+int cawn_phase_accumulate_ret_fwd(const cawn_desc *d, const float *mag, const float *ang,
+                                  const float *valve, const float *ret, const float *ret_bias,
+                                  const float *theta, const float *conv_w, const float *conv_b,
+                                  const void *state_in, float *z_re, float *z_im, void *state_out,
+                                  void *ckpt, uint32_t *gate_mask, void *workspace,
+                                  size_t workspace_bytes, void *stream);
 #ifdef __cplusplus
 }
 #endif

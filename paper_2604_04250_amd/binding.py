@@ -20,7 +20,7 @@ CAWN_OK, CAWN_EINVAL, CAWN_EUNSUPPORTED, CAWN_EWORKSPACE, CAWN_ELAUNCH, CAWN_ETI
 EXPORTS = ["cawn_state_bytes", "cawn_workspace_bytes", "cawn_ckpt_bytes", "cawn_tile_len",
            "cawn_status_string", "cawn_workspace_init", "cawn_workspace_status", "cawn_set_spin_limit",
            "cawn_theta_init", "cawn_syntax_conv", "cawn_phase_accumulate_fwd",
-           "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_valve_fwd",
+           "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_ret_fwd", "cawn_phase_accumulate_valve_fwd",
            "cawn_phase_accumulate_valve_bwd"]
 
 
@@ -30,6 +30,7 @@ class cawn_desc(C.Structure):
                 ("gate_tau", C.c_float), ("conv_clamp", C.c_float), ("out_clamp", C.c_float),
                 ("grad_clamp", C.c_float), ("accumulate_param_grads", C.c_int32),
                 ("lane_consts_cached", C.c_int32), ("valve_eps", C.c_float),
+                ("ret_mode", C.c_int32), ("reserved_", C.c_int32),
                 ("in_stride_b", C.c_int64), ("in_stride_t", C.c_int64),
                 ("out_stride_b", C.c_int64), ("out_stride_t", C.c_int64)]
 
@@ -40,9 +41,10 @@ class cawn_desc(C.Structure):
 
 def make_desc(B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
               grad_clamp=100.0, accumulate_param_grads=0, lane_consts_cached=0, in_stride_b=0,
-              in_stride_t=0, out_stride_b=0, out_stride_t=0, gate_mode=0, valve_eps=0.001) -> cawn_desc:
+              in_stride_t=0, out_stride_b=0, out_stride_t=0, gate_mode=0, valve_eps=0.001,
+              ret_mode=0) -> cawn_desc:
     return cawn_desc(B, L, H, F, conv_k, amp_mode, gate_mode, gate_tau, conv_clamp, out_clamp, grad_clamp,
-                     accumulate_param_grads, lane_consts_cached, valve_eps, in_stride_b, in_stride_t,
+                     accumulate_param_grads, lane_consts_cached, valve_eps, ret_mode, 0, in_stride_b, in_stride_t,
                      out_stride_b, out_stride_t)
 
 
@@ -77,6 +79,8 @@ def lib() -> C.CDLL:
                                                       [C.c_size_t, C.c_void_p])
         L.cawn_phase_accumulate_valve_bwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 21 +
                                                       [C.c_size_t, C.c_void_p])
+        L.cawn_phase_accumulate_ret_fwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 15 +
+                                                    [C.c_size_t, C.c_void_p])
         _lib = L
     return _lib
 
@@ -182,6 +186,15 @@ def cawn_phase_accumulate_valve_bwd(d, mag, ang, valve, gamma, theta, conv_w, co
         _ptr(conv_b), _ptr(state_in), _ptr(ckpt), _ptr(dz_re), _ptr(dz_im), _ptr(dstate_out),
         _ptr(dmag), _ptr(dang), _ptr(dvalve), _ptr(dgamma), _ptr(dtheta), _ptr(dconv_w),
         _ptr(dconv_b), _ptr(dstate_in), _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(stream))
+
+
+def cawn_phase_accumulate_ret_fwd(d, mag, ang, valve, ret, ret_bias, theta, conv_w, conv_b, state_in, z_re,
+                                  z_im, state_out, ckpt, gate_mask, workspace, stream=None) -> int:
+    return lib().cawn_phase_accumulate_ret_fwd(
+        C.byref(d), _ptr(mag), _ptr(ang), _ptr(valve), _ptr(ret), _ptr(ret_bias), _ptr(theta), _ptr(conv_w),
+        _ptr(conv_b), _ptr(state_in), _ptr(z_re), _ptr(z_im), _ptr(state_out), _ptr(ckpt),
+        _ptr(gate_mask), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(stream))
 
 

@@ -19,6 +19,7 @@ static bool desc_ok(const cawn_desc *d)
     if (d->B <= 0 || d->L < 0 || d->H <= 0 || d->F <= 0) return false;
     if ((int64_t)d->H * d->F > (1 << 24)) return false;
     if (d->conv_k < 0) return false;
+    if (d->ret_mode != 0 && d->ret_mode != 1) return false;
     return true;
 }
 
@@ -44,6 +45,11 @@ static WsLayout make_layout(const cawn_desc *d)
     o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
     w.off_vpart = o;    // gate_mode 1: per-group sums of the valve's gradient terms, [B][groups][L]
     if (d->gate_mode == 1)
+        o = align_up(o + (size_t)d->B * (size_t)(d->H * (d->F >= 32 ? d->F / 32 : 1)) * (size_t)(d->L > 0 ? d->L : 1) * sizeof(float), 256);
+    w.off_aggp = o;     // ret_mode 1: third chained word of a tile's aggregate (product of its retentions)
+    if (d->ret_mode == 1) o = align_up(o + tiles_rows * w.Jp128 * sizeof(tagged_t), 256);
+    w.off_rpart = o;    // ret_mode 1: per-group sums of the retention logits' gradient terms, [B][groups][L]
+    if (d->ret_mode == 1)
         o = align_up(o + (size_t)d->B * (size_t)(d->H * (d->F >= 32 ? d->F / 32 : 1)) * (size_t)(d->L > 0 ? d->L : 1) * sizeof(float), 256);
     w.off_dbg = o;
 #ifdef CAWN_TIMING
@@ -212,15 +218,18 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t n)
 }
 
 // One thread per lane: every per-lane constant the scan kernels need, formed in fp64.
+// gamma == nullptr (data-dependent retention): the table is built with gamma = 1, i.e. its powers
+// are pure rotations, and row R_RBIAS receives the static retention bias b_k of the lane's harmonic.
 __global__ void lane_table_kernel(const float *__restrict__ gamma, const float *__restrict__ theta,
                                   const float *__restrict__ conv_w, const float *__restrict__ conv_b,
+                                  const float *__restrict__ ret_bias, int F,
                                   float *__restrict__ table, int J, int Jp, int conv_k)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= Jp) return;
     auto put = [&](int row, double v) { table[(size_t)row * Jp + j] = (float)v; };
     const bool live = j < J;
-    const double g = live ? (double)gamma[j] : 0.0, th = live ? (double)theta[j] : 0.0;
+    const double g = live ? (gamma ? (double)gamma[j] : 1.0) : 0.0, th = live ? (double)theta[j] : 0.0;
     const double c = cos(th), s = sin(th);
     put(R_LR, g * c);
     put(R_LI, g * s);
@@ -258,6 +267,7 @@ __global__ void lane_table_kernel(const float *__restrict__ gamma, const float *
         put(R_PSEGB + 2 * sgi, re);
         put(R_PSEGB + 2 * sgi + 1, im);
     }
+    put(R_RBIAS, live && ret_bias ? (double)ret_bias[j % F] : 0.0);
     put(R_BIAS_M, live && conv_b && conv_k > 0 ? (double)conv_b[j] : 0.0);
     put(R_BIAS_A, live && conv_b && conv_k > 0 ? (double)conv_b[(size_t)J + j] : 0.0);
     for (int sidx = 0; sidx < 2; ++sidx)
@@ -362,12 +372,12 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
 
 static hipError_t build_table(const cawn_desc *d, const WsLayout &w, char *ws, const float *gamma,
                               const float *theta, const float *conv_w, const float *conv_b,
-                              hipStream_t s)
+                              const float *ret_bias, hipStream_t s)
 {
     float *table = reinterpret_cast<float *>(ws + w.off_table);
     const int threads = 128;
     hipLaunchKernelGGL(lane_table_kernel, dim3((w.Jp + threads - 1) / threads), dim3(threads), 0, s,
-                       gamma, theta, conv_w, conv_b, table, w.J, w.Jp, d->conv_k);
+                       gamma, theta, conv_w, conv_b, ret_bias, d->F, table, w.J, w.Jp, d->conv_k);
     return hipGetLastError();
 }
 
@@ -493,12 +503,13 @@ int cawn_syntax_conv(const cawn_desc *d, int32_t C, const float *x, const float 
 }
 
 static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
-                    const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
+                    const float *ret, const float *ret_bias, const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                     const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
                     uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
-    if (d->gate_mode == 1 && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
+    if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode == 1 && d->ret_mode == 1 && d->F < 16) return CAWN_EUNSUPPORTED;   // LDS for both logit tiles
     hipStream_t s = (hipStream_t)stream;
     const WsLayout w = make_layout(d);
     const long long J = w.J;
@@ -517,7 +528,8 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
         }
         return CAWN_OK;
     }
-    if (!mag || !ang || !gamma || !theta || !z_re || !z_im || !workspace) return CAWN_EINVAL;
+    if (!mag || !ang || !theta || !z_re || !z_im || !workspace) return CAWN_EINVAL;
+    if (d->ret_mode == 1 ? (!ret || !ret_bias) : !gamma) return CAWN_EINVAL;
     if (d->gate_mode == 1 && !valve) return CAWN_EINVAL;
     if (d->conv_k > 0 && !conv_w) return CAWN_EINVAL;
     if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
@@ -532,11 +544,15 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
         a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
         a.valve = valve;
         a.valve_thr = valve_threshold(d->valve_eps);
-        a.gpb = d->F >= 32 ? 1 : 32 / d->F;
     } else if (!make_gate_set(d, &a.gs)) {
         return CAWN_EUNSUPPORTED;
     }
     a.H = d->H; a.F = d->F;
+    a.gpb = d->F >= 32 ? 1 : 32 / d->F;
+    if (d->ret_mode == 1) {
+        a.ret = ret;
+        a.aggp = reinterpret_cast<tagged_t *>(reinterpret_cast<char *>(workspace) + w.off_aggp);
+    }
     const bool vec = (J % FwdV == 0) && (ist % FwdV == 0) && (isb % FwdV == 0) && (ost % FwdV == 0) &&
                      (osb % FwdV == 0) && aligned(mag, 16) && aligned(ang, 16) && aligned(z_re, 16) &&
                      aligned(z_im, 16) && (!state_in || aligned(state_in, 16)) &&
@@ -549,7 +565,8 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
 
     char *ws = reinterpret_cast<char *>(workspace);
     if (!d->lane_consts_cached) {
-        if (build_table(d, w, ws, gamma, theta, conv_w, conv_b, s) != hipSuccess) return CAWN_ELAUNCH;
+        if (build_table(d, w, ws, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
+                        d->ret_mode == 1 ? ret_bias : nullptr, s) != hipSuccess) return CAWN_ELAUNCH;
     }
     a.mag = mag; a.ang = ang;
     a.table = reinterpret_cast<const float *>(ws + w.off_table);
@@ -582,8 +599,8 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
                               uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 0) return CAWN_EUNSUPPORTED;
-    return fwd_impl(d, mag, ang, nullptr, gamma, theta, conv_w, conv_b, state_in, z_re, z_im, state_out, ckpt,
+    if (d->gate_mode != 0 || d->ret_mode != 0) return CAWN_EUNSUPPORTED;
+    return fwd_impl(d, mag, ang, nullptr, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, z_re, z_im, state_out, ckpt,
                     gate_mask, workspace, workspace_bytes, stream);
 }
 
@@ -594,9 +611,21 @@ int cawn_phase_accumulate_valve_fwd(const cawn_desc *d, const float *mag, const 
                                     size_t workspace_bytes, void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 1) return CAWN_EINVAL;
-    return fwd_impl(d, mag, ang, valve, gamma, theta, conv_w, conv_b, state_in, z_re, z_im, state_out, ckpt,
-                    gate_mask, workspace, workspace_bytes, stream);
+    if (d->gate_mode != 1 || d->ret_mode != 0) return CAWN_EINVAL;
+    return fwd_impl(d, mag, ang, valve, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, z_re, z_im,
+                    state_out, ckpt, gate_mask, workspace, workspace_bytes, stream);
+}
+
+int cawn_phase_accumulate_ret_fwd(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
+                                  const float *ret, const float *ret_bias, const float *theta,
+                                  const float *conv_w, const float *conv_b, const void *state_in, float *z_re,
+                                  float *z_im, void *state_out, void *ckpt, uint32_t *gate_mask, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->ret_mode != 1) return CAWN_EINVAL;
+    return fwd_impl(d, mag, ang, d->gate_mode == 1 ? valve : nullptr, ret, ret_bias, nullptr, theta, conv_w, conv_b,
+                    state_in, z_re, z_im, state_out, ckpt, gate_mask, workspace, workspace_bytes, stream);
 }
 
 static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
@@ -668,7 +697,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
 
     char *ws = reinterpret_cast<char *>(workspace);
     if (!d->lane_consts_cached) {
-        if (build_table(d, w, ws, gamma, theta, conv_w, conv_b, s) != hipSuccess) return CAWN_ELAUNCH;
+        if (build_table(d, w, ws, gamma, theta, conv_w, conv_b, nullptr, s) != hipSuccess) return CAWN_ELAUNCH;
     }
     a.mag = mag; a.ang = ang; a.dz_re = dz_re; a.dz_im = dz_im;
     a.table = reinterpret_cast<const float *>(ws + w.off_table);

@@ -107,7 +107,11 @@ __device__ __forceinline__ void stage_consts(float *sC, const float *table, int 
 }
 
 // VALVE: gate_mode 1, the per-head input valve of Sec. 3.3 in place of the per-lane threshold.
-template <int V, int KC, bool VALVE>
+// RET: ret_mode 1, the retention of Sec. 3.3 item 4: gamma[t] = sigmoid(logit[t][head] + b_k) scales
+// what arrives from token t-1 (accumulation equations of Sec. 3.4, printed with gamma_{t,j}).  A run of
+// tokens then acts on an incoming state as S_out = E + (product of the run's gammas) e^{i n theta} S_in:
+// the lane table holds pure rotations and every level carries the real product beside its aggregate.
+template <int V, int KC, bool VALVE, bool RET>
 __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
     constexpr int TILE_T = FwdGeom::TILE_T, NSTEP = FwdGeom::NSTEP, NSEG = FwdGeom::NSEG, LPR = FwdLPR;
@@ -125,8 +129,11 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     __shared__ float sCarry[2][JB];
     constexpr int NCR = R_W0 - R_LR + 2 * KC;     // staged lane-constant rows
     __shared__ __attribute__((aligned(16))) float sC[(NCR + 7) / 8 * 8][JB];
-    constexpr int GPB_MAX = 4;                    // valve groups per lane block (F >= 8)
+    // valve / retention groups per lane block: F >= 8, or F >= 16 with both (LDS: two workgroups per CU)
+    constexpr int GPB_MAX = (VALVE && RET) ? 2 : 4;
     __shared__ float sV[VALVE ? FwdGeom::TILE_T * GPB_MAX : 1];
+    __shared__ float sR[RET ? FwdGeom::TILE_T * GPB_MAX : 1];     // retention logits, laid out like sV
+    __shared__ float sP[RET ? NSEG : 1][JB];                      // product of each segment's retentions
     __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid = threadIdx.x;
@@ -157,6 +164,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         if (owner_wave) return;
         if (wave == 0) stage_consts<NCR, JB>(&sC[0][0], a.table, a.Jp, T.lb, lane);
         if (VALVE && wave == 0) stage_valve<TILE_T, JB>(&sV[0], a.valve, T.b, T.tt * TILE_T, T.lb, a.L, a.H, a.F, a.gpb, lane);
+        if (RET && wave == 0) stage_valve<TILE_T, JB>(&sR[0], a.ret, T.b, T.tt * TILE_T, T.lb, a.L, a.H, a.F, a.gpb, lane);
         if (a.stage16)
             stage_rows<TILE_T, JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
                                      ist32, wave, NW - 1, lane);
@@ -175,6 +183,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 
     float lr[V], li[V], pfr[V], pfi[V], psr[V], psi[V];
     float wm[KC1][V], wa[KC1][V], bm[V], ba[V];
+    float rb[V];                                   // RET: static retention bias of my lanes
 
     for (int it = 0; ticket < qtiles; ++it) {
         const uint32_t id = T.id;
@@ -213,6 +222,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 #pragma unroll
                 for (int k = 0; k < KC1; ++k) wm[k][v] = wa[k][v] = 0.f;
             }
+            if (RET) cst(rb, R_RBIAS);
             if (KC > 0) {
                 cst(bm, R_BIAS_M);
                 cst(ba, R_BIAS_A);
@@ -227,10 +237,11 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         // ---- front-end, phasors, local scan from zero.  Rows come from LDS as a sliding window.
         float pr[NSTEP][V], pi[NSTEP][V];
         float Er[V], Ei[V];
+        float gm[RET ? NSTEP : 1][V], Pth[V];     // RET: retention of each token, product over my tokens
         uint32_t gbits[NSTEP];
         const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
         // (my lane's valve group in the block is lane / F when heads are narrower than the block)
-        const int vbase = VALVE ? (a.F >= JB ? 0 : (lv * V) / a.F) * TILE_T + seg * NSTEP : 0;
+        const int vbase = (VALVE || RET) ? (a.F >= JB ? 0 : (lv * V) / a.F) * TILE_T + seg * NSTEP : 0;
         // The mode switches are uniform over the launch; each combination gets its own straight-line
         // copy of the loop, so that the tokens' dependent chains (exp -> rcp -> sin/cos) interleave.
         auto front_end = [&](auto amp_c, auto small_c, auto mask_c) {
@@ -247,7 +258,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                 }
             }
 #pragma unroll
-            for (int v = 0; v < V; ++v) Er[v] = Ei[v] = 0.f;
+            for (int v = 0; v < V; ++v) { Er[v] = Ei[v] = 0.f; Pth[v] = 1.f; }
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
                 gbits[i] = 0;
@@ -292,8 +303,19 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                     pr[i][v] = ag * c;
                     pi[i][v] = ag * s;
                     if (MASK) gbits[i] |= g ? (1u << v) : 0u;
-                    const float nr = __builtin_fmaf(lr[v], Er[v], __builtin_fmaf(-li[v], Ei[v], pr[i][v]));
-                    const float ni = __builtin_fmaf(li[v], Er[v], __builtin_fmaf(lr[v], Ei[v], pi[i][v]));
+                    float nr, ni;
+                    if (RET) {
+                        const float gmv = sigmoid_fast(sR[vbase + i] + rb[v]);
+                        gm[i][v] = gmv;
+                        Pth[v] *= gmv;
+                        const float rr = __builtin_fmaf(lr[v], Er[v], -li[v] * Ei[v]);
+                        const float ri = __builtin_fmaf(li[v], Er[v], lr[v] * Ei[v]);
+                        nr = __builtin_fmaf(gmv, rr, pr[i][v]);
+                        ni = __builtin_fmaf(gmv, ri, pi[i][v]);
+                    } else {
+                        nr = __builtin_fmaf(lr[v], Er[v], __builtin_fmaf(-li[v], Ei[v], pr[i][v]));
+                        ni = __builtin_fmaf(li[v], Er[v], __builtin_fmaf(lr[v], Ei[v], pi[i][v]));
+                    }
                     Er[v] = nr;
                     Ei[v] = ni;
                 }
@@ -335,6 +357,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         for (int v = 0; v < V; ++v) {
             sE[seg][0][lv * V + v] = Er[v];
             sE[seg][1][lv * V + v] = Ei[v];
+            if (RET) sP[seg][lv * V + v] = Pth[v];
         }
         if (tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
         lds_barrier();
@@ -349,14 +372,25 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         }
 
         float Xr[V], Xi[V];   // state entering my segment, from a zero tile input
+        float Cs[V];          // RET: product of the retentions of the segments before mine
 #pragma unroll
-        for (int v = 0; v < V; ++v) Xr[v] = Xi[v] = 0.f;
+        for (int v = 0; v < V; ++v) { Xr[v] = Xi[v] = 0.f; Cs[v] = 1.f; }
         for (int qq = 0; qq < seg; ++qq) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const float er = sE[qq][0][lv * V + v], ei = sE[qq][1][lv * V + v];
-                const float nr = __builtin_fmaf(pfr[v], Xr[v], __builtin_fmaf(-pfi[v], Xi[v], er));
-                const float ni = __builtin_fmaf(pfi[v], Xr[v], __builtin_fmaf(pfr[v], Xi[v], ei));
+                float nr, ni;
+                if (RET) {
+                    const float pq = sP[qq][lv * V + v];
+                    const float rr = __builtin_fmaf(pfr[v], Xr[v], -pfi[v] * Xi[v]);
+                    const float ri = __builtin_fmaf(pfi[v], Xr[v], pfr[v] * Xi[v]);
+                    nr = __builtin_fmaf(pq, rr, er);
+                    ni = __builtin_fmaf(pq, ri, ei);
+                    Cs[v] *= pq;
+                } else {
+                    nr = __builtin_fmaf(pfr[v], Xr[v], __builtin_fmaf(-pfi[v], Xi[v], er));
+                    ni = __builtin_fmaf(pfi[v], Xr[v], __builtin_fmaf(pfr[v], Xi[v], ei));
+                }
                 Xr[v] = nr;
                 Xi[v] = ni;
             }
@@ -368,10 +402,20 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         const size_t slot = (size_t)id * 2 * JB + lv * V;
         if (is_tail_seg) {
             float Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
+            float Pt[V];      // RET: product of the whole tile's retentions
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                Tr[v] = __builtin_fmaf(pfr[v], Xr[v], __builtin_fmaf(-pfi[v], Xi[v], Er[v]));
-                Ti[v] = __builtin_fmaf(pfi[v], Xr[v], __builtin_fmaf(pfr[v], Xi[v], Ei[v]));
+                if (RET) {
+                    const float rr = __builtin_fmaf(pfr[v], Xr[v], -pfi[v] * Xi[v]);
+                    const float ri = __builtin_fmaf(pfi[v], Xr[v], pfr[v] * Xi[v]);
+                    Tr[v] = __builtin_fmaf(Pth[v], rr, Er[v]);
+                    Ti[v] = __builtin_fmaf(Pth[v], ri, Ei[v]);
+                    Pt[v] = Cs[v] * Pth[v];
+                } else {
+                    Tr[v] = __builtin_fmaf(pfr[v], Xr[v], __builtin_fmaf(-pfi[v], Xi[v], Er[v]));
+                    Ti[v] = __builtin_fmaf(pfi[v], Xr[v], __builtin_fmaf(pfr[v], Xi[v], Ei[v]));
+                    Pt[v] = 1.f;
+                }
                 hr[v] = hi[v] = qr[v] = qi[v] = 0.f;
             }
             if (active) {   // lambda^TILE_T as a double-float
@@ -395,10 +439,11 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                     for (int v = 0; v < V; ++v) {
                         tagged_store(a.agg + slot + v, Tr[v], tag);
                         tagged_store(a.agg + slot + JB + v, Ti[v], tag);
+                        if (RET) tagged_store(a.aggp + (size_t)id * JB + lv * V + v, Pt[v], tag);
                     }
                 }
-                if (!look_back<V, false, LPR, CAWN_FWD_NB>(a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB, lv * V, lv,
-                                                 hr, hi, qr, qi, a.spin_limit, tag, cr, ci)) {
+                if (!look_back<V, false, LPR, CAWN_FWD_NB, RET>(a.agg, a.pre, id - (uint32_t)a.B, (uint32_t)a.B, tt, JB, lv * V, lv,
+                                                 hr, hi, qr, qi, a.spin_limit, tag, cr, ci, a.aggp)) {
                     // gave up: flag the workspace, keep going so that every wave exits
                     if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
@@ -418,7 +463,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                 float P_r[V], P_i[V];
 #pragma unroll
                 for (int v = 0; v < V; ++v)
-                    chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], P_r[v], P_i[v]);
+                    chain_step<false>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], RET ? Pt[v] * cr[v] : cr[v],
+                                      RET ? Pt[v] * ci[v] : ci[v], P_r[v], P_i[v]);
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     tagged_store(a.pre + slot + v, P_r[v], tag);
@@ -434,8 +480,15 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
-            Sr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(-psi[v], ci, Xr[v]));
-            Si[v] = __builtin_fmaf(psi[v], cr, __builtin_fmaf(psr[v], ci, Xi[v]));
+            if (RET) {
+                const float rr = __builtin_fmaf(psr[v], cr, -psi[v] * ci);
+                const float ri = __builtin_fmaf(psi[v], cr, psr[v] * ci);
+                Sr[v] = __builtin_fmaf(Cs[v], rr, Xr[v]);
+                Si[v] = __builtin_fmaf(Cs[v], ri, Xi[v]);
+            } else {
+                Sr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(-psi[v], ci, Xr[v]));
+                Si[v] = __builtin_fmaf(psi[v], cr, __builtin_fmaf(psr[v], ci, Xi[v]));
+            }
         }
 
         // ---- checkpoints for the backward pass: the state before every CKPT_T-th token
@@ -462,8 +515,16 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                     float zr[V], zi[V];
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        const float nr = __builtin_fmaf(lr[v], Sr[v], __builtin_fmaf(-li[v], Si[v], pr[i][v]));
-                        const float ni = __builtin_fmaf(li[v], Sr[v], __builtin_fmaf(lr[v], Si[v], pi[i][v]));
+                        float nr, ni;
+                        if (RET) {
+                            const float rr = __builtin_fmaf(lr[v], Sr[v], -li[v] * Si[v]);
+                            const float ri = __builtin_fmaf(li[v], Sr[v], lr[v] * Si[v]);
+                            nr = __builtin_fmaf(gm[i][v], rr, pr[i][v]);
+                            ni = __builtin_fmaf(gm[i][v], ri, pi[i][v]);
+                        } else {
+                            nr = __builtin_fmaf(lr[v], Sr[v], __builtin_fmaf(-li[v], Si[v], pr[i][v]));
+                            ni = __builtin_fmaf(li[v], Sr[v], __builtin_fmaf(lr[v], Si[v], pi[i][v]));
+                        }
                         Sr[v] = nr;
                         Si[v] = ni;
                         zr[v] = clampf(nr, a.out_clamp);
@@ -547,6 +608,7 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
     const int jc = active ? j : 0;      // lanes beyond J compute on lane 0's data and store nothing
     const float *tb = a.table + jc;
     const float lr = tb[(size_t)R_LR * a.Jp], li = tb[(size_t)R_LI * a.Jp];
+    const float rb = tb[(size_t)R_RBIAS * a.Jp];
     float wm[KC1], wa[KC1], bm = 0.f, ba = 0.f;
 #pragma unroll
     for (int k = 0; k < KC1; ++k) wm[k] = wa[k] = 0.f;
@@ -615,8 +677,17 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
         if (a.small_angle) sincos_small(phi, sn, cs);
         else sincos_fast(phi, sn, cs);
         const float pr = ag * cs, pi = ag * sn;
-        const float nr = __builtin_fmaf(lr, Sr, __builtin_fmaf(-li, Si, pr));
-        const float ni = __builtin_fmaf(li, Sr, __builtin_fmaf(lr, Si, pi));
+        float nr, ni;
+        if (a.ret) {        // data-dependent retention (Sec. 3.3 item 4); lr, li are then e^{i theta}
+            const float gmv = sigmoid_fast(a.ret[((size_t)b * a.L + t) * a.H + jc / a.F] + rb);
+            const float rr = __builtin_fmaf(lr, Sr, -li * Si);
+            const float ri = __builtin_fmaf(li, Sr, lr * Si);
+            nr = __builtin_fmaf(gmv, rr, pr);
+            ni = __builtin_fmaf(gmv, ri, pi);
+        } else {
+            nr = __builtin_fmaf(lr, Sr, __builtin_fmaf(-li, Si, pr));
+            ni = __builtin_fmaf(li, Sr, __builtin_fmaf(lr, Si, pi));
+        }
         Sr = nr;
         Si = ni;
         if (active) {
@@ -659,7 +730,7 @@ static hipError_t launch_step(const FwdArgs &a, int conv_k, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int V, int KC, bool VALVE>
+template <int V, int KC, bool VALVE, bool RET>
 static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
 {
     // persistent grid: what fits on the chip (asked once per kernel)
@@ -668,7 +739,7 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC, VALVE>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC, VALVE, RET>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
@@ -678,31 +749,28 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     const long long tiles = (long long)a.nLB * a.B * a.nT;
     const long long wgs = tiles < resident ? (tiles > 0 ? tiles : 1) : resident;
     dim3 grid((unsigned)wgs), block(FwdGeom::NSEG * FwdLPR);
-    hipLaunchKernelGGL((fwd_kernel<V, KC, VALVE>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((fwd_kernel<V, KC, VALVE, RET>), grid, block, 0, s, a);
     return hipGetLastError();
+}
+
+template <int V, bool VALVE, bool RET>
+static hipError_t launch_fwd_vm(const FwdArgs &a, int conv_k, hipStream_t s)
+{
+    switch (conv_k) {
+    case 0: return launch_fwd_vk<V, 0, VALVE, RET>(a, s);
+    case 1: return launch_fwd_vk<V, 1, VALVE, RET>(a, s);
+    case 2: return launch_fwd_vk<V, 2, VALVE, RET>(a, s);
+    case 3: return launch_fwd_vk<V, 3, VALVE, RET>(a, s);
+    case 4: return launch_fwd_vk<V, 4, VALVE, RET>(a, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 template <int V>
 static hipError_t launch_fwd_v(const FwdArgs &a, int conv_k, hipStream_t s)
 {
-    if (a.valve) {
-        switch (conv_k) {
-        case 0: return launch_fwd_vk<V, 0, true>(a, s);
-        case 1: return launch_fwd_vk<V, 1, true>(a, s);
-        case 2: return launch_fwd_vk<V, 2, true>(a, s);
-        case 3: return launch_fwd_vk<V, 3, true>(a, s);
-        case 4: return launch_fwd_vk<V, 4, true>(a, s);
-        default: return hipErrorInvalidValue;
-        }
-    }
-    switch (conv_k) {
-    case 0: return launch_fwd_vk<V, 0, false>(a, s);
-    case 1: return launch_fwd_vk<V, 1, false>(a, s);
-    case 2: return launch_fwd_vk<V, 2, false>(a, s);
-    case 3: return launch_fwd_vk<V, 3, false>(a, s);
-    case 4: return launch_fwd_vk<V, 4, false>(a, s);
-    default: return hipErrorInvalidValue;
-    }
+    if (a.ret) return a.valve ? launch_fwd_vm<V, true, true>(a, conv_k, s) : launch_fwd_vm<V, false, true>(a, conv_k, s);
+    return a.valve ? launch_fwd_vm<V, true, false>(a, conv_k, s) : launch_fwd_vm<V, false, false>(a, conv_k, s);
 }
 
 hipError_t launch_fwd(const FwdArgs &a, int conv_k, bool vec, hipStream_t s)

@@ -76,6 +76,7 @@ enum LaneRow : int {
     R_LR = R_PSEGB + 2 * BwdGeom::NSEG, R_LI,   // lambda = gamma e^{i theta}
     R_PSEG,                    // R_PSEG + 2*s (+1): the same powers for the forward segments
     R_BIAS_M = R_PSEG + 2 * FwdGeom::NSEG, R_BIAS_A,
+    R_RBIAS,                   // ret_mode 1: the lane's static retention bias b_k (k = j mod F)
     R_W0                       // R_W0 + s*conv_k + i : tap i of stream s
 };
 inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k; }
@@ -102,7 +103,7 @@ static_assert(sizeof(WsHeader) == 1024, "header size");
 
 struct WsLayout {
     int J, Jp, Jp128, nT;
-    size_t off_table, off_agg, off_pre, off_halo, off_part, off_vpart, off_dbg, total;
+    size_t off_table, off_agg, off_pre, off_halo, off_part, off_vpart, off_aggp, off_rpart, off_dbg, total;
 };
 
 constexpr uint32_t EPOCH_MOD = 1u << 30;
@@ -140,6 +141,11 @@ struct FwdArgs {
     const float *valve;          // null: gate_mode 0
     int H, F, gpb;
     float valve_thr;
+    // ret_mode 1 (data-dependent retention, Sec. 3.3 item 4): logits [B][L][H], staged like the valve's;
+    // the lane table is then built with gamma = 1 (its powers are pure rotations) and a tile's
+    // aggregate has a third chained word, the product of the tile's retentions: aggp [tile][JB]
+    const float *ret;            // null: ret_mode 0
+    tagged_t *aggp;
 };
 
 struct BwdArgs {
@@ -447,11 +453,14 @@ __device__ __forceinline__ void chain_step(float Tr, float Ti, float hr, float h
 //   nearer tiles seen in earlier windows, by reading them again (published words never change
 //   within a call).  In the common case -- a prefix within NB tiles -- that is one round trip.
 // Returns false if a wait gave up (the carry is then meaningless).
-template <int V, bool CONJ, int LPR, int NB>
+// RET (data-dependent retention): an aggregate has a third word per lane, the product of the tile's
+// retentions (aggp, [tile][JB]); a link then is P = T + product * M c.
+template <int V, bool CONJ, int LPR, int NB, bool RET = false>
 __device__ __forceinline__ bool look_back(const tagged_t *agg, const tagged_t *pre, uint32_t pred, uint32_t stride,
                                           int depth, int JB, int lo, int lv, const float (&hr)[V],
                                           const float (&hi)[V], const float (&qr)[V], const float (&qi)[V],
-                                          uint32_t spin_limit, uint32_t tag, float (&cr)[V], float (&ci)[V])
+                                          uint32_t spin_limit, uint32_t tag, float (&cr)[V], float (&ci)[V],
+                                          const tagged_t *aggp = nullptr)
 {
     const int gshift = (int)(threadIdx.x & 63) - lv;
     const unsigned long long gmask = LPR >= 64 ? ~0ull : ((1ull << LPR) - 1ull);
@@ -459,6 +468,7 @@ __device__ __forceinline__ bool look_back(const tagged_t *agg, const tagged_t *p
     int base = 0;       // tiles at distance < base are known to hold aggregates
     uint32_t spins = 0;
     float ar[NB][V], ai[NB][V];      // aggregates of the current window
+    float ap[RET ? NB : 1][V];
     int found = -1;                  // position of the prefix in the current window
     while (true) {
         const int w = depth - base < NB ? depth - base : NB;
@@ -477,6 +487,11 @@ __device__ __forceinline__ bool look_back(const tagged_t *agg, const tagged_t *p
                 aok[n] = aok[n] && tagged_ok(w2, tag) && tagged_ok(w3, tag);
                 pr_[n][v] = tagged_value(w0); pi_[n][v] = tagged_value(w1);
                 ar[n][v] = tagged_value(w2);  ai[n][v] = tagged_value(w3);
+                if constexpr (RET) {
+                    const tagged_t w4 = tagged_load(aggp + (size_t)(pred - (uint32_t)dd * stride) * JB + lo + v);
+                    aok[n] = aok[n] && tagged_ok(w4, tag);
+                    ap[n][v] = tagged_value(w4);
+                }
             }
         }
         compiler_fence();
@@ -516,6 +531,7 @@ __device__ __forceinline__ bool look_back(const tagged_t *agg, const tagged_t *p
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 float nr, ni;
+                if constexpr (RET) { cr[v] *= ap[n][v]; ci[v] *= ap[n][v]; }
                 chain_step<CONJ>(ar[n][v], ai[n][v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
                 cr[v] = nr;
                 ci[v] = ni;
@@ -532,6 +548,8 @@ __device__ __forceinline__ bool look_back(const tagged_t *agg, const tagged_t *p
             for (int v = 0; v < V; ++v) {
                 ar[n][v] = tagged_value(tagged_load(agg + slot + v));
                 ai[n][v] = tagged_value(tagged_load(agg + slot + JB + v));
+                if constexpr (RET)
+                    ap[n][v] = tagged_value(tagged_load(aggp + (size_t)(pred - (uint32_t)dd * stride) * JB + lo + v));
             }
         }
 #pragma unroll
@@ -540,6 +558,7 @@ __device__ __forceinline__ bool look_back(const tagged_t *agg, const tagged_t *p
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     float nr, ni;
+                    if constexpr (RET) { cr[v] *= ap[n][v]; ci[v] *= ap[n][v]; }
                     chain_step<CONJ>(ar[n][v], ai[n][v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], nr, ni);
                     cr[v] = nr;
                     ci[v] = ni;

@@ -59,15 +59,15 @@ class Workspaces:
 
 def run_fwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
             state_in=None, want_mask=True, want_ckpt=False, concat=False, in_place_state=False,
-            cached=0, ws=None, valve=None, valve_eps=0.001):
+            cached=0, ws=None, valve=None, valve_eps=0.001, ret=None, ret_bias=None):
     """inp: dict with mag, ang [B,L,J], gamma, theta, conv_w, conv_b (numpy float32).
     Returns dict(z_re, z_im, state_out (flat blob), mask [B,L,W] uint32, ckpt)."""
     J = H * F
     d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau,
                     conv_clamp=conv_clamp, out_clamp=out_clamp, lane_consts_cached=cached,
-                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps)
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps, ret_mode=0 if ret is None else 1)
     mag, ang = dev(inp["mag"][:, :L]), dev(inp["ang"][:, :L])
-    gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
+    gamma, theta = dev(inp.get("gamma")), dev(inp["theta"])
     cw = dev(inp["conv_w"]) if conv_k > 0 else None
     cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
     if concat:
@@ -88,7 +88,11 @@ def run_fwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0
     mask = torch.zeros((B, max(L, 1), W), dtype=torch.int32, device=DEV) if want_mask else None
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV) if want_ckpt else None
     ws = ws if ws is not None else Workspaces.get(d)
-    if valve is None:
+    if ret is not None:
+        vl = None if valve is None else dev(np.ascontiguousarray(valve[:, :L]))
+        K.check(K.cawn_phase_accumulate_ret_fwd(d, mag, ang, vl, dev(np.ascontiguousarray(ret[:, :L])), dev(ret_bias),
+                                                theta, cw, cb, st_in, z_re, z_im, st_out, ckpt, mask, ws))
+    elif valve is None:
         K.check(K.cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, cw, cb, st_in, z_re, z_im, st_out,
                                             ckpt, mask, ws))
     else:

@@ -35,7 +35,7 @@ def test_desc_struct_matches_header_field_order():
         typ, rest = decl.split(None, 1)
         names += [n.strip() for n in rest.split(",")]
     assert names == [f[0] for f in K.cawn_desc._fields_]
-    assert C.sizeof(K.cawn_desc) == 14 * 4 + 4 * 8
+    assert C.sizeof(K.cawn_desc) == 16 * 4 + 4 * 8
 
 
 def test_size_helpers():
@@ -152,7 +152,10 @@ def test_kernels_do_not_spill_and_keep_their_occupancy():
                     # the per-head valve variants of the backward kernel (last template argument
                     # true) sit at the register budget: a few spilled values per tile are tolerated
                     valve_bwd = "bwd_kernel" in name and name.endswith("ELb1EEEvNS_7BwdArgsE")
-                    assert int(val) <= (64 if valve_bwd else 0), (name, line)
+                    # the data-dependent-retention variants of the forward kernel (last template
+                    # argument true) keep 32 more values per thread: the same allowance
+                    ret_fwd = "fwd_kernel" in name and name.endswith("ELb1EEEvNS_7FwdArgsE")
+                    assert int(val) <= (64 if valve_bwd or ret_fwd else 0), (name, line)
                     seen += 1
                 elif key.startswith("Occupancy"):
                     want = 4 if "bwd_kernel" in name else 2

@@ -1,0 +1,147 @@
+"""GPU parity of the data-dependent retention gate (ret_mode 1, Sec. 3.3 item 4: gamma[t][h][k] =
+sigmoid(r[t][h] + b_k) in the accumulation equations of Sec. 3.4) against the fp64 oracle, through
+the C ABI.  Bar as for the other parity tests: rms-floored relative error <= 1e-4, masks bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import cawn_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+def _inputs(B, L, H, F, Kc, seed, ret_mean=-2.0, ret_std=1.5):
+    """Retention logits around the paper's initial projection bias -2 plus b_k falling from +3 to 0:
+    retentions from ~0.02 to ~0.98, i.e. memories from one token to a few dozen tokens."""
+    r = np.random.Generator(np.random.PCG64(seed))
+    J = H * F
+    d = dict(mag=r.standard_normal((B, L, J), dtype=np.float32),
+             ang=r.standard_normal((B, L, J), dtype=np.float32),
+             theta=r.uniform(0, np.pi, J).astype(np.float32),
+             ret=(ret_mean + ret_std * r.standard_normal((B, L, H))).astype(np.float32),
+             ret_bias=np.linspace(3.0, 0.0, F).astype(np.float32),
+             valve=(-3.9 + 3.0 * r.standard_normal((B, L, H))).astype(np.float32),
+             dz_re=r.standard_normal((B, L, J), dtype=np.float32),
+             dz_im=r.standard_normal((B, L, J), dtype=np.float32))
+    kk = max(Kc, 1)
+    d["conv_w"] = (r.standard_normal((2, J, kk)) / np.sqrt(kk)).astype(np.float32)
+    d["conv_b"] = (0.1 * r.standard_normal((2, J))).astype(np.float32)
+    return d
+
+
+def _check_fwd(B, L, H, F, Kc, d, amp_mode=0, valve=False, tau=0.0, state=None, tol=TOL, **kw):
+    G = _gpu()
+    J = H * F
+    scan_in = tail_in = blob = None
+    if state is not None:
+        scan_in, tail_in = state
+        blob = G.pack_state(scan_in, tail_in if Kc > 1 else None)
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_mode=1 if valve else 0, gate_tau=tau, ret_mode=1)
+    ora = O.phase_fwd(cfg, d["mag"][:, :L], d["ang"][:, :L], None, d["theta"], conv_w=d["conv_w"],
+                      conv_b=d["conv_b"], valve=d["valve"][:, :L] if valve else None, ret=d["ret"][:, :L],
+                      ret_bias=d["ret_bias"],
+                      scan_in=None if scan_in is None else scan_in.astype(np.float64),
+                      tail_in=tail_in if Kc > 1 else None)
+    out = G.run_fwd(d, B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, state_in=blob,
+                    valve=d["valve"] if valve else None, ret=d["ret"], ret_bias=d["ret_bias"], **kw)
+    e = max(G.rel_err(out["z_re"], ora["z_re"]), G.rel_err(out["z_im"], ora["z_im"]))
+    assert e <= tol, e
+    assert np.array_equal(out["mask"], G.mask_from_gate(ora["gate"])), "gate mask differs"
+    scan, tail = G.unpack_state(out["state_out"], B, J, Kc)
+    assert G.rel_err(scan, ora["scan_out"]) <= tol
+    return out, ora
+
+
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (8, 8), (1, 128), (5, 32), (3, 16)])
+@pytest.mark.parametrize("Kc", [0, 4])
+def test_retention_forward_head_widths(H, F, Kc):
+    B, L = 2, 700                      # three forward tiles, ragged tail
+    d = _inputs(B, L, H, F, Kc, 3700 + H * 131 + F + Kc)
+    _check_fwd(B, L, H, F, Kc, d, tau=0.25)
+
+
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 16), (1, 128)])
+@pytest.mark.parametrize("Kc", [0, 3])
+def test_retention_forward_with_the_valve(H, F, Kc):
+    B, L = 2, 600
+    d = _inputs(B, L, H, F, Kc, 3900 + H * 131 + F + Kc)
+    _check_fwd(B, L, H, F, Kc, d, amp_mode=1, valve=True)
+
+
+def test_retention_long_memory_crosses_many_tiles():
+    """Logits near +7 (retention 0.999): a token is still heard 2000 tokens, i.e. eight tiles, later, so
+    the chained products and the look-back carry real weight."""
+    B, L, H, F, Kc = 2, 3000, 2, 64, 4
+    d = _inputs(B, L, H, F, Kc, 4100, ret_mean=5.0, ret_std=0.7)
+    out, ora = _check_fwd(B, L, H, F, Kc, d)
+    # the case is what it claims: dropping everything older than one tile would be far outside the bar
+    G = _gpu()
+    cfg = O.Cfg(B, 256, H, F, conv_k=Kc, ret_mode=1)
+    cut = O.phase_fwd(cfg, d["mag"][:, -256:], d["ang"][:, -256:], None, d["theta"], conv_w=d["conv_w"],
+                      conv_b=d["conv_b"], ret=d["ret"][:, -256:], ret_bias=d["ret_bias"],
+                      tail_in=np.ascontiguousarray(np.stack([d["mag"][:, -259:-256], d["ang"][:, -259:-256]], axis=2)))
+    assert G.rel_err(cut["z_re"][:, -1], ora["z_re"][:, -1]) > 100 * TOL
+
+
+@pytest.mark.parametrize("L", [1, 5, 16, 17, 255, 256, 257])
+def test_retention_forward_lengths_and_short_calls(L):
+    B, H, F, Kc = 3, 2, 64, 3
+    d = _inputs(B, 300, H, F, Kc, 4300 + L)
+    r = np.random.Generator(np.random.PCG64(5))
+    state = (r.standard_normal((B, 2, H * F)).astype(np.float32),
+             r.standard_normal((B, Kc - 1, 2, H * F)).astype(np.float32))
+    _check_fwd(B, L, H, F, Kc, d, amp_mode=1, state=state)
+
+
+def test_retention_forward_chunked_state_matches_one_pass():
+    G = _gpu()
+    B, L, H, F, Kc = 2, 1000, 2, 64, 4
+    J = H * F
+    d = _inputs(B, L, H, F, Kc, 4400, ret_mean=2.0)
+    one, _ = _check_fwd(B, L, H, F, Kc, d)
+    blob = None
+    zs = []
+    for lo, hi in ((0, 300), (300, 310), (310, 1000)):     # a long, a short (step kernel) and a long call
+        part = {k: (v[:, lo:hi] if k in ("mag", "ang", "ret") else v) for k, v in d.items()}
+        o = G.run_fwd(part, B, hi - lo, H, F, conv_k=Kc, state_in=blob, ret=part["ret"], ret_bias=d["ret_bias"])
+        blob = o["state_out"]
+        zs.append(o["z_re"])
+    z = np.concatenate(zs, axis=1)
+    assert G.rel_err(z, one["z_re"]) <= TOL
+    assert G.rel_err(G.unpack_state(blob, B, J, Kc)[0], G.unpack_state(one["state_out"], B, J, Kc)[0]) <= TOL
+
+
+def test_retention_then_constant_gamma_on_one_workspace():
+    """The lane table of a workspace follows the call: pure rotations for ret_mode 1, gamma-scaled
+    powers for ret_mode 0; calls of both kinds alternate on one workspace."""
+    G = _gpu()
+    B, L, H, F, Kc = 1, 520, 2, 32, 2
+    d = _inputs(B, L, H, F, Kc, 4500)
+    d["gamma"] = np.random.Generator(np.random.PCG64(1)).uniform(0.9, 0.999, H * F).astype(np.float32)
+    for _ in range(2):
+        _check_fwd(B, L, H, F, Kc, d)
+        out = G.run_fwd(d, B, L, H, F, conv_k=Kc)
+        ora = O.phase_fwd(O.Cfg(B, L, H, F, conv_k=Kc), d["mag"], d["ang"], d["gamma"], d["theta"],
+                          conv_w=d["conv_w"], conv_b=d["conv_b"])
+        assert G.rel_err(out["z_re"], ora["z_re"]) <= TOL
+
+
+def test_retention_errors():
+    import torch
+    from paper_2604_04250_amd import binding as K
+    x = torch.zeros(64, device="cuda:0")
+    d = K.make_desc(1, 8, 2, 12, ret_mode=1)          # F = 12: heads do not tile the 32-lane blocks
+    assert K.cawn_phase_accumulate_ret_fwd(d, x, x, None, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EUNSUPPORTED
+    d = K.make_desc(1, 8, 4, 8, ret_mode=1, gate_mode=1)      # both per-head streams need F >= 16
+    assert K.cawn_phase_accumulate_ret_fwd(d, x, x, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EUNSUPPORTED
+    d = K.make_desc(1, 8, 2, 32, ret_mode=0)
+    assert K.cawn_phase_accumulate_ret_fwd(d, x, x, None, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL
+    d = K.make_desc(1, 8, 2, 32, ret_mode=1)
+    assert K.cawn_phase_accumulate_fwd(d, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EUNSUPPORTED
+    assert K.cawn_phase_accumulate_ret_fwd(d, x, x, None, None, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL
