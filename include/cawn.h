@@ -62,7 +62,7 @@ typedef struct cawn_desc {
                                        that had this flag 0 -- skip rebuilding the lane table   */
     float valve_eps;      /* gate_mode 1: the valve closes below this (paper: 0.001)            */
     int32_t ret_mode;     /* 0 constant per-lane retention gamma[j]; 1 data-dependent retention
-                             sigmoid(ret[t][h] + ret_bias[k]) (cawn_phase_accumulate_ret_fwd; same
+                             sigmoid(ret[t][h] + ret_bias[k]) (cawn_phase_accumulate_ret_fwd/_bwd; same
                              head widths as gate_mode 1)                                        */
     int32_t reserved_;    /* 0 */
     int64_t in_stride_b, in_stride_t;   /* element strides of mag/ang/dmag/dang; 0 = dense
@@ -209,6 +209,26 @@ int cawn_phase_accumulate_ret_fwd(const cawn_desc *d, const float *mag, const fl
                                   const float *theta, const float *conv_w, const float *conv_b,
                                   const void *state_in, float *z_re, float *z_im, void *state_out,
                                   void *ckpt, uint32_t *gate_mask, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of cawn_phase_accumulate_ret_fwd.  The adjoint of token t reaches token t-1 through
+ * gamma[t]: G[t] = dZ[t] + gamma[t+1] conj(e^{i theta}) G[t+1]; the retention's own gradient is
+ * d gamma[t] = Re(conj(G[t]) e^{i theta} S[t-1]) per lane, clamped to +-grad_clamp like every
+ * returned per-element gradient, chained through the sigmoid and summed over the harmonics of a
+ * head.  ret_bias is static (Sec. 3.3): it receives no gradient.
+ *   dvalve       [B][L][H] or NULL (d->gate_mode == 1 only, ignored otherwise)
+ *   dret         [B][L][H] gradient w.r.t. the retention logits, or NULL
+ *   ckpt         required: the forward state before each token enters d gamma
+ * There is no gamma / dgamma.  Everything else as in cawn_phase_accumulate_bwd.
+ */
+int cawn_phase_accumulate_ret_bwd(const cawn_desc *d, const float *mag, const float *ang,
+                                  const float *valve, const float *ret, const float *ret_bias,
+                                  const float *theta, const float *conv_w, const float *conv_b,
+                                  const void *state_in, const void *ckpt, const float *dz_re,
+                                  const float *dz_im, const void *dstate_out, float *dmag,
+                                  float *dang, float *dvalve, float *dret, float *dtheta,
+                                  float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
                                   size_t workspace_bytes, void *stream);
 #ifdef __cplusplus
 }

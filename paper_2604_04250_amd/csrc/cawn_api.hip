@@ -193,7 +193,8 @@ static int valve_groups(const cawn_desc *d) { return d->H * (d->F >= 32 ? d->F /
 // ------------------------------------------------------------------------------------ kernels
 // gate_mode 1: dvalve[b][t][h] = sig (1 - sig) * (sum over the head's groups of vpart[b][g][t]),
 // sig = sigmoid(valve - 3): the straight-through gradient of Sec. 3.3.  One thread per (b, h, t),
-// t fastest; the groups of a head are summed in index order.
+// t fastest; the groups of a head are summed in index order.  valve == nullptr: the plain sum (the
+// retention logits' gradient, whose terms already carry their sigmoid factor per lane).
 __global__ void valve_reduce_kernel(const float *__restrict__ vpart, const float *__restrict__ valve,
                                     float *__restrict__ dvalve, int B, int L, int H, int G)
 {
@@ -206,8 +207,11 @@ __global__ void valve_reduce_kernel(const float *__restrict__ vpart, const float
         float sum = 0.f;
         for (int g = 0; g < gph; ++g) sum += vpart[((size_t)b * G + (size_t)h * gph + g) * L + t];
         const size_t o = ((size_t)b * L + t) * H + h;
-        const float sg = 1.0f / (1.0f + expf(-(valve[o] - 3.0f)));
-        dvalve[o] = sg * (1.0f - sg) * sum;
+        if (valve) {
+            const float sg = 1.0f / (1.0f + expf(-(valve[o] - 3.0f)));
+            sum *= sg * (1.0f - sg);
+        }
+        dvalve[o] = sum;
     }
 }
 
@@ -629,20 +633,23 @@ int cawn_phase_accumulate_ret_fwd(const cawn_desc *d, const float *mag, const fl
 }
 
 static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
+                    const float *ret, const float *ret_bias,
                     const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                     const void *state_in, const void *ckpt, const float *dz_re, const float *dz_im,
-                    const void *dstate_out, float *dmag, float *dang, float *dvalve, float *dgamma,
+                    const void *dstate_out, float *dmag, float *dang, float *dvalve, float *dret, float *dgamma,
                     float *dtheta, float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
                     size_t workspace_bytes, void *stream)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
-    if (d->gate_mode == 1 && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
+    if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode == 1 && d->ret_mode == 1 && d->F < 16) return CAWN_EUNSUPPORTED;   // as in the forward
     hipStream_t s = (hipStream_t)stream;
     const WsLayout w = make_layout(d);
     const long long J = w.J;
     const int kc = d->conv_k;
     const bool want_w = kc > 0 && (dconv_w || dconv_b);
-    const bool want_param = dgamma || dtheta || want_w;
+    // (the retention kernels rebuild the forward state in any case and always emit their partials)
+    const bool want_param = dgamma || dtheta || want_w || d->ret_mode == 1;
     if (d->L == 0) {   // no tokens: the state gradient passes through, parameter gradients are zero
         auto zero = [&](void *p, size_t nfloat) {
             if (!p || !nfloat) return hipSuccess;
@@ -662,10 +669,11 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
         }
         return e == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
     }
-    if (!mag || !ang || !gamma || !theta || !dz_re || !dz_im || !dmag || !dang || !workspace) return CAWN_EINVAL;
+    if (!mag || !ang || !theta || !dz_re || !dz_im || !dmag || !dang || !workspace) return CAWN_EINVAL;
+    if (d->ret_mode == 1 ? (!ret || !ret_bias || dgamma) : !gamma) return CAWN_EINVAL;
     if (d->gate_mode == 1 && !valve) return CAWN_EINVAL;
     if (kc > 0 && !conv_w) return CAWN_EINVAL;
-    if ((dgamma || dtheta) && !ckpt) return CAWN_EINVAL;
+    if ((dgamma || dtheta || d->ret_mode == 1) && !ckpt) return CAWN_EINVAL;
     if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
@@ -678,13 +686,18 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
         a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
         a.valve = valve;
         a.valve_thr = valve_threshold(d->valve_eps);
-        a.gpb = d->F >= 32 ? 1 : 32 / d->F;
-        a.G = valve_groups(d);
         a.vpart = dvalve ? reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + w.off_vpart) : nullptr;
     } else if (!make_gate_set(d, &a.gs)) {
         return CAWN_EUNSUPPORTED;
     }
     a.H = d->H; a.F = d->F;
+    a.gpb = d->F >= 32 ? 1 : 32 / d->F;
+    a.G = valve_groups(d);
+    if (d->ret_mode == 1) {
+        a.ret = ret;
+        a.rpart = dret ? reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + w.off_rpart) : nullptr;
+        a.aggp = reinterpret_cast<tagged_t *>(reinterpret_cast<char *>(workspace) + w.off_aggp);
+    }
     const bool vec = (J % BwdV == 0) && (ist % BwdV == 0) && (isb % BwdV == 0) && (ost % BwdV == 0) &&
                      (osb % BwdV == 0) && aligned(mag, 8) && aligned(ang, 8) && aligned(dz_re, 8) &&
                      aligned(dz_im, 8) && aligned(dmag, 8) && aligned(dang, 8) &&
@@ -697,7 +710,8 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
 
     char *ws = reinterpret_cast<char *>(workspace);
     if (!d->lane_consts_cached) {
-        if (build_table(d, w, ws, gamma, theta, conv_w, conv_b, nullptr, s) != hipSuccess) return CAWN_ELAUNCH;
+        if (build_table(d, w, ws, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
+                        d->ret_mode == 1 ? ret_bias : nullptr, s) != hipSuccess) return CAWN_ELAUNCH;
     }
     a.mag = mag; a.ang = ang; a.dz_re = dz_re; a.dz_im = dz_im;
     a.table = reinterpret_cast<const float *>(ws + w.off_table);
@@ -723,7 +737,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.total_tiles = (uint32_t)tiles;
     a.dbg = reinterpret_cast<unsigned long long *>(ws + w.off_dbg);
     if (launch_bwd(a, kc, vec, s) != hipSuccess) return CAWN_ELAUNCH;
-    if (want_param) {
+    if (dgamma || dtheta || want_w) {
         const int rows = part_rows(kc);
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((J + 31) / 32), rows), dim3(1024), 0, s, a.part,
                            dgamma, dtheta, dconv_w, dconv_b, rows, kc > 0 ? kc : 1, (int)J, JB, nLB,
@@ -737,6 +751,13 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
                            valve, dvalve, d->B, d->L, d->H, a.G);
         if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
     }
+    if (a.rpart) {
+        const long long n = (long long)d->B * d->H * d->L;
+        const long long nb = (n + 255) / 256;
+        hipLaunchKernelGGL(valve_reduce_kernel, dim3((unsigned)(nb < 4096 ? nb : 4096)), dim3(256), 0, s, a.rpart,
+                           static_cast<const float *>(nullptr), dret, d->B, d->L, d->H, a.G);
+        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+    }
     return CAWN_OK;
 }
 
@@ -748,9 +769,9 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
                               size_t workspace_bytes, void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 0) return CAWN_EUNSUPPORTED;
-    return bwd_impl(d, mag, ang, nullptr, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im, dstate_out,
-                    dmag, dang, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace, workspace_bytes,
+    if (d->gate_mode != 0 || d->ret_mode != 0) return CAWN_EUNSUPPORTED;
+    return bwd_impl(d, mag, ang, nullptr, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im, dstate_out,
+                    dmag, dang, nullptr, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace, workspace_bytes,
                     stream);
 }
 
@@ -763,10 +784,26 @@ int cawn_phase_accumulate_valve_bwd(const cawn_desc *d, const float *mag, const 
                                     void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 1) return CAWN_EINVAL;
-    return bwd_impl(d, mag, ang, valve, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im, dstate_out,
-                    dmag, dang, dvalve, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace, workspace_bytes,
-                    stream);
+    if (d->gate_mode != 1 || d->ret_mode != 0) return CAWN_EINVAL;
+    return bwd_impl(d, mag, ang, valve, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im,
+                    dstate_out, dmag, dang, dvalve, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace,
+                    workspace_bytes, stream);
+}
+
+int cawn_phase_accumulate_ret_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
+                                  const float *ret, const float *ret_bias, const float *theta,
+                                  const float *conv_w, const float *conv_b, const void *state_in, const void *ckpt,
+                                  const float *dz_re, const float *dz_im, const void *dstate_out, float *dmag,
+                                  float *dang, float *dvalve, float *dret, float *dtheta, float *dconv_w,
+                                  float *dconv_b, void *dstate_in, void *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->ret_mode != 1) return CAWN_EINVAL;
+    const bool valved = d->gate_mode == 1;
+    return bwd_impl(d, mag, ang, valved ? valve : nullptr, ret, ret_bias, nullptr, theta, conv_w, conv_b, state_in,
+                    ckpt, dz_re, dz_im, dstate_out, dmag, dang, valved ? dvalve : nullptr, dret, nullptr, dtheta,
+                    dconv_w, dconv_b, dstate_in, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

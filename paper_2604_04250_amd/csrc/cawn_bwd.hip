@@ -72,10 +72,41 @@ __device__ __forceinline__ void stu(float *ubase, uint32_t boff, const float (&x
     BVec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(ubase) + boff), x);
 }
 
+// Sum of w over the lanes that share a head inside the 32-lane block (8, 16 or 32 lanes).  Rotations
+// within each row of 16 lanes leave the row's sum in all of its lanes (four full-rate adds); a 32-lane
+// group then takes the lower row's sum into its upper row.  The total is valid in the lanes for which
+// head_sum_lane() holds.
+__device__ __forceinline__ float head_sum(float w, int vwidth)
+{
+    if (vwidth >= 16) {
+        w = dpp_add<0x128>(w);
+        w = dpp_add<0x124>(w);
+        w = dpp_add<0x122>(w);
+        w = dpp_add<0x121>(w);
+        if (vwidth == 32) w = dpp_add_bcast15(w);
+    } else {
+#pragma unroll
+        for (int o = 4; o >= 1; o >>= 1)
+            if (o < vwidth) w += __shfl_xor(w, o, 64);
+    }
+    return w;
+}
+__device__ __forceinline__ bool head_sum_lane(int lv, int vwidth)
+{
+    return vwidth >= 16 ? (lv == vwidth - 16 || (vwidth == 16 && lv == 16)) : (lv % vwidth == 0);
+}
+
 // VALVE: gate_mode 1, the per-head input valve of Sec. 3.3 in place of the per-lane threshold.
-template <int V, int KC, bool PARAM, bool VALVE>
+// RET: ret_mode 1, the retention gamma[t] = sigmoid(logit[t][head] + b_k) of Sec. 3.3 item 4.  The
+// adjoint then is G[t] = dZ[t] + gamma[t+1] conj(e^{i theta}) G[t+1]; every level carries the MESSAGE
+// M[t] = gamma[t] conj(e^{i theta}) G[t] that token t hands to token t-1 (so a run of tokens never needs
+// its neighbour's retention) and, beside each aggregate, the real product of the run's retentions; the
+// lane table holds pure rotations.  The logit's gradient needs S[t-1], so these kernels always rebuild
+// the forward state (PARAM).
+template <int V, int KC, bool PARAM, bool VALVE, bool RET>
 __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
+    static_assert(!RET || (PARAM && V == 1), "retention kernels rebuild the forward state; one lane per thread");
     constexpr int TILE_T = BwdGeom::TILE_T, NSTEP = BwdGeom::NSTEP, NSEG = BwdGeom::NSEG, LPR = BwdLPR;
     constexpr int JB = V * LPR;
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
@@ -99,6 +130,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     __shared__ float sV[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];      // valve logits, [group][token]
     __shared__ float sVp[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
     __shared__ float sTaps[VALVE ? 2 * KC1 : 1][JB];                 // conv taps of the lane block (valve kernels)
+    __shared__ float sPb[RET ? NSEG : 1][JB];                        // product of each segment's retentions
+    __shared__ float sPt[RET ? 1 : 1][JB];                           // product of the tile's retentions (head group)
+    __shared__ float sRp[RET ? BwdGeom::TILE_T * GPB_MAX : 1];       // retention-logit gradient terms per (group, token)
     __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid_ = threadIdx.x;
@@ -179,6 +213,16 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             }
         }
     }
+    // ---- retention logits of my tokens (one per token and head: the lanes of a head read one address)
+    float gm[RET ? NSTEP : 1][V];           // logit, then the retention itself
+    if (RET) {
+        const float *rp = a.ret + (size_t)b * a.L * a.H + (active ? j0 : 0) / a.F;
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+            const int t = t0 + i < a.L ? t0 + i : a.L - 1;     // rows past the end: a valid address, the value is harmless
+            gm[i][0] = rp[(size_t)t * a.H];
+        }
+    }
     // ---- lane constants
     float lr[V], li[V], pnr[V], pni[V];
     float wmf[KC1][V], waf[KC1][V], bm[V], ba[V];   // taps for the front-end
@@ -186,6 +230,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     ldu<V>(li, row(R_LI), jb);
     ldu<V>(pnr, row(R_PSEGB + 2), jb);                       // lambda^NSTEP
     ldu<V>(pni, row(R_PSEGB + 3), jb);
+    float rb[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) rb[v] = 0.f;
+    if (RET) ldu<V>(rb, row(R_RBIAS), jb);
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         bm[v] = ba[v] = 0.f;
@@ -237,35 +285,55 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 
     // ---- adjoint from zero over my segment (needs only the upstream gradients)
     float Ebr[V], Ebi[V];
+    float Pth[V];           // RET: product of my tokens' retentions
 #pragma unroll
-    for (int v = 0; v < V; ++v) Ebr[v] = Ebi[v] = 0.f;
+    for (int v = 0; v < V; ++v) { Ebr[v] = Ebi[v] = 0.f; Pth[v] = 1.f; }
 #pragma unroll
     for (int i = NSTEP - 1; i >= 0; --i) {
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            const float nr = __builtin_fmaf(lr[v], Ebr[v], __builtin_fmaf(li[v], Ebi[v], dzr[i][v]));
-            const float ni = __builtin_fmaf(lr[v], Ebi[v], __builtin_fmaf(-li[v], Ebr[v], dzi[i][v]));
-            Ebr[v] = nr;
-            Ebi[v] = ni;
+            if (RET) {      // G = dZ + message from the next token; my message = gamma conj(e^{i theta}) G
+                const float gmv = sigmoid_fast(gm[i][v] + rb[v]);
+                gm[i][v] = gmv;
+                Pth[v] *= gmv;
+                const float gr_ = dzr[i][v] + Ebr[v], gi_ = dzi[i][v] + Ebi[v];
+                Ebr[v] = gmv * __builtin_fmaf(lr[v], gr_, li[v] * gi_);
+                Ebi[v] = gmv * __builtin_fmaf(lr[v], gi_, -li[v] * gr_);
+            } else {
+                const float nr = __builtin_fmaf(lr[v], Ebr[v], __builtin_fmaf(li[v], Ebi[v], dzr[i][v]));
+                const float ni = __builtin_fmaf(lr[v], Ebi[v], __builtin_fmaf(-li[v], Ebr[v], dzi[i][v]));
+                Ebr[v] = nr;
+                Ebi[v] = ni;
+            }
         }
     }
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         sEb[seg][0][lv * V + v] = Ebr[v];
         sEb[seg][1][lv * V + v] = Ebi[v];
+        if (RET) sPb[seg][lv * V + v] = Pth[v];
     }
     if (tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
     lds_barrier_raw();     // the staged rows are still on their way
     BWD_STAMP(2);
     float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
+    float Cb[V];            // RET: product of the retentions of the segments after mine
 #pragma unroll
-    for (int v = 0; v < V; ++v) Xr[v] = Xi[v] = 0.f;
+    for (int v = 0; v < V; ++v) { Xr[v] = Xi[v] = 0.f; Cb[v] = 1.f; }
     for (int qq = NSEG - 1; qq > seg; --qq) {
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const float er = sEb[qq][0][lv * V + v], ei = sEb[qq][1][lv * V + v];
-            const float nr = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], er));
-            const float ni = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], ei));
+            float nr, ni;
+            if (RET) {
+                const float pq = sPb[qq][lv * V + v];
+                nr = __builtin_fmaf(pq, __builtin_fmaf(pnr[v], Xr[v], pni[v] * Xi[v]), er);
+                ni = __builtin_fmaf(pq, __builtin_fmaf(pnr[v], Xi[v], -pni[v] * Xr[v]), ei);
+                Cb[v] *= pq;
+            } else {
+                nr = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], er));
+                ni = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], ei));
+            }
             Xr[v] = nr;
             Xi[v] = ni;
         }
@@ -277,8 +345,14 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         float Tr[V], Ti[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            Tr[v] = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], Ebr[v]));
-            Ti[v] = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], Ebi[v]));
+            if (RET) {
+                Tr[v] = __builtin_fmaf(Pth[v], __builtin_fmaf(pnr[v], Xr[v], pni[v] * Xi[v]), Ebr[v]);
+                Ti[v] = __builtin_fmaf(Pth[v], __builtin_fmaf(pnr[v], Xi[v], -pni[v] * Xr[v]), Ebi[v]);
+                sPt[0][lv * V + v] = Cb[v] * Pth[v];
+            } else {
+                Tr[v] = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], Ebr[v]));
+                Ti[v] = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], Ebi[v]));
+            }
             sCarry[0][lv * V + v] = Tr[v];     // parked here until the look-back (frees registers)
             sCarry[1][lv * V + v] = Ti[v];
         }
@@ -287,6 +361,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             for (int v = 0; v < V; ++v) {
                 tagged_store(a.agg + slot + v, Tr[v], tag);
                 tagged_store(a.agg + slot + JB + v, Ti[v], tag);
+                if (RET) tagged_store(a.aggp + (size_t)ticket * JB + lv * V + v, Cb[v] * Pth[v], tag);
             }
         }
     }
@@ -327,7 +402,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // lanes that share a valve: a head, or the part of it inside the 32-lane block (8, 16 or 32).
     // Where my tokens' entries start in sV / sVp is formed again at each use (from an opaque copy of
     // the thread index) rather than kept in a register across the tile.
-    const int vwidth = VALVE ? (a.F >= JB ? JB : a.F) : 1;
+    const int vwidth = (VALVE || RET) ? (a.F >= JB ? JB : a.F) : 1;
     auto valve_base = [&]() {
         int t_ = tid_;
         asm volatile("" : "+v"(t_));
@@ -415,8 +490,14 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     Spr[i][v] = Efr[v];
                     Spi[i][v] = Efi[v];
                     const float pr = agv * c, pi = agv * s;
-                    const float nr = __builtin_fmaf(lr[v], Efr[v], __builtin_fmaf(-li[v], Efi[v], pr));
-                    const float ni = __builtin_fmaf(li[v], Efr[v], __builtin_fmaf(lr[v], Efi[v], pi));
+                    float nr, ni;
+                    if (RET) {
+                        nr = __builtin_fmaf(gm[i][v], __builtin_fmaf(lr[v], Efr[v], -li[v] * Efi[v]), pr);
+                        ni = __builtin_fmaf(gm[i][v], __builtin_fmaf(li[v], Efr[v], lr[v] * Efi[v]), pi);
+                    } else {
+                        nr = __builtin_fmaf(lr[v], Efr[v], __builtin_fmaf(-li[v], Efi[v], pr));
+                        ni = __builtin_fmaf(li[v], Efr[v], __builtin_fmaf(lr[v], Efi[v], pi));
+                    }
                     Efr[v] = nr;
                     Efi[v] = ni;
                 }
@@ -458,24 +539,39 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         lds_barrier();
     BWD_STAMP(4);
         float Fr[V], Fi[V], pfr[V], pfi[V];   // lambda^(NSTEP*seg): the segments before mine
+        float Cf[V];        // RET: product of the retentions of the segments before mine
 #pragma unroll
-        for (int v = 0; v < V; ++v) Fr[v] = Fi[v] = 0.f;
+        for (int v = 0; v < V; ++v) { Fr[v] = Fi[v] = 0.f; Cf[v] = 1.f; }
         ldu<V>(pfr, row(R_PSEGB + 2 * seg), jb);
         ldu<V>(pfi, row(R_PSEGB + 2 * seg + 1), jb);
         for (int qq = 0; qq < seg; ++qq) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const float er = sEf[qq][0][lv * V + v], ei = sEf[qq][1][lv * V + v];
-                const float nr = __builtin_fmaf(pnr[v], Fr[v], __builtin_fmaf(-pni[v], Fi[v], er));
-                const float ni = __builtin_fmaf(pni[v], Fr[v], __builtin_fmaf(pnr[v], Fi[v], ei));
+                float nr, ni;
+                if (RET) {
+                    const float pq = sPb[qq][lv * V + v];
+                    nr = __builtin_fmaf(pq, __builtin_fmaf(pnr[v], Fr[v], -pni[v] * Fi[v]), er);
+                    ni = __builtin_fmaf(pq, __builtin_fmaf(pni[v], Fr[v], pnr[v] * Fi[v]), ei);
+                    Cf[v] *= pq;
+                } else {
+                    nr = __builtin_fmaf(pnr[v], Fr[v], __builtin_fmaf(-pni[v], Fi[v], er));
+                    ni = __builtin_fmaf(pni[v], Fr[v], __builtin_fmaf(pnr[v], Fi[v], ei));
+                }
                 Fr[v] = nr;
                 Fi[v] = ni;
             }
         }
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            const float nr = __builtin_fmaf(pfr[v], kr[v], __builtin_fmaf(-pfi[v], ki[v], Fr[v]));
-            const float ni = __builtin_fmaf(pfi[v], kr[v], __builtin_fmaf(pfr[v], ki[v], Fi[v]));
+            float nr, ni;
+            if (RET) {
+                nr = __builtin_fmaf(Cf[v], __builtin_fmaf(pfr[v], kr[v], -pfi[v] * ki[v]), Fr[v]);
+                ni = __builtin_fmaf(Cf[v], __builtin_fmaf(pfi[v], kr[v], pfr[v] * ki[v]), Fi[v]);
+            } else {
+                nr = __builtin_fmaf(pfr[v], kr[v], __builtin_fmaf(-pfi[v], ki[v], Fr[v]));
+                ni = __builtin_fmaf(pfi[v], kr[v], __builtin_fmaf(pfr[v], ki[v], Fi[v]));
+            }
             Fr[v] = nr;
             Fi[v] = ni;
         }
@@ -486,8 +582,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             for (int v = 0; v < V; ++v) {
                 Spr[i][v] += Fr[v];
                 Spi[i][v] += Fi[v];
-                const float nr = __builtin_fmaf(lr[v], Fr[v], -li[v] * Fi[v]);
-                const float ni = __builtin_fmaf(li[v], Fr[v], lr[v] * Fi[v]);
+                float nr = __builtin_fmaf(lr[v], Fr[v], -li[v] * Fi[v]);
+                float ni = __builtin_fmaf(li[v], Fr[v], lr[v] * Fi[v]);
+                if (RET) { nr *= gm[i][v]; ni *= gm[i][v]; }
                 Fr[v] = nr;
                 Fi[v] = ni;
             }
@@ -516,8 +613,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         ldu<V>(qr, row(R_PTB_LR), jb);
         ldu<V>(qi, row(R_PTB_LI), jb);
         if (chained) {
-            if (!look_back<V, true, LPR, 1>(a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V, lv,
-                                            hr, hi, qr, qi, a.spin_limit, tag, cr, ci)) {
+            if (!look_back<V, true, LPR, 1, RET>(a.agg, a.pre, ticket - chain_stride, chain_stride, ttr, JB, lv * V, lv,
+                                                 hr, hi, qr, qi, a.spin_limit, tag, cr, ci, a.aggp)) {
                 if (lv == 0) __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -533,7 +630,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 float P_r, P_i;
-                chain_step<true>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], cr[v], ci[v], P_r, P_i);
+                const float pt = RET ? sPt[0][lv * V + v] : 1.f;
+                chain_step<true>(Tr[v], Ti[v], hr[v], hi[v], qr[v], qi[v], RET ? pt * cr[v] : cr[v],
+                                 RET ? pt * ci[v] : ci[v], P_r, P_i);
                 tagged_store(a.pre + slot + v, P_r, tag);
                 tagged_store(a.pre + slot + JB + v, P_i, tag);
             }
@@ -547,8 +646,13 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const float cr = sCarry[0][lv * V + v], ci = sCarry[1][lv * V + v];
-        Gr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(psi[v], ci, Xr[v]));      // conj(ps) * carry
-        Gi[v] = __builtin_fmaf(psr[v], ci, __builtin_fmaf(-psi[v], cr, Xi[v]));
+        if (RET) {          // the message entering my segment
+            Gr[v] = __builtin_fmaf(Cb[v], __builtin_fmaf(psr[v], cr, psi[v] * ci), Xr[v]);
+            Gi[v] = __builtin_fmaf(Cb[v], __builtin_fmaf(psr[v], ci, -psi[v] * cr), Xi[v]);
+        } else {
+            Gr[v] = __builtin_fmaf(psr[v], cr, __builtin_fmaf(psi[v], ci, Xr[v]));      // conj(ps) * carry
+            Gi[v] = __builtin_fmaf(psr[v], ci, __builtin_fmaf(-psi[v], cr, Xi[v]));
+        }
     }
 
     // The tile's last segment needs the conv pre-activation gradients of the next tile's first HALO
@@ -560,22 +664,35 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float acc_g[V], acc_t[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc_g[v] = acc_t[v] = 0.f;
-    const int vbase = VALVE ? valve_base() : 0;
+    const int vbase = (VALVE || RET) ? valve_base() : 0;
 #pragma unroll
     for (int i = NSTEP - 1; i >= 0; --i) {
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            const float nr = __builtin_fmaf(lr[v], Gr[v], __builtin_fmaf(li[v], Gi[v], dzr[i][v]));
-            const float ni = __builtin_fmaf(lr[v], Gi[v], __builtin_fmaf(-li[v], Gr[v], dzi[i][v]));
-            Gr[v] = nr;
-            Gi[v] = ni;
+            float nr, ni;
+            if (RET) {      // G = dZ + message; the message to the previous token takes my retention
+                nr = dzr[i][v] + Gr[v];
+                ni = dzi[i][v] + Gi[v];
+                Gr[v] = gm[i][v] * __builtin_fmaf(lr[v], nr, li[v] * ni);
+                Gi[v] = gm[i][v] * __builtin_fmaf(lr[v], ni, -li[v] * nr);
+            } else {
+                nr = __builtin_fmaf(lr[v], Gr[v], __builtin_fmaf(li[v], Gi[v], dzr[i][v]));
+                ni = __builtin_fmaf(lr[v], Gi[v], __builtin_fmaf(-li[v], Gr[v], dzi[i][v]));
+                Gr[v] = nr;
+                Gi[v] = ni;
+            }
             if (PARAM) {
                 const float rr = __builtin_fmaf(cth[v], Spr[i][v], -sth[v] * Spi[i][v]);
                 const float ri = __builtin_fmaf(sth[v], Spr[i][v], cth[v] * Spi[i][v]);
                 const float tg = __builtin_fmaf(nr, rr, ni * ri);
-                const float tth = gam[v] * __builtin_fmaf(ni, rr, -nr * ri);
+                const float tth = (RET ? gm[i][v] : gam[v]) * __builtin_fmaf(ni, rr, -nr * ri);
                 acc_g[v] += clampf(tg, a.grad_clamp);
                 acc_t[v] += clampf(tth, a.grad_clamp);
+                if (RET) {  // d gamma, clamped, through the sigmoid, summed over the lanes of the head
+                    float wr = active ? clampf(tg, a.grad_clamp) * gm[i][v] * (1.0f - gm[i][v]) : 0.0f;
+                    wr = head_sum(wr, vwidth);
+                    if (head_sum_lane(lv, vwidth)) sRp[vbase + i] = wr;
+                }
             }
             const float gr_ = clampf(nr, a.grad_clamp), gi_ = clampf(ni, a.grad_clamp);
             const float c_ = VALVE ? __builtin_amdgcn_cosf(cs[i][v]) : cs[i][v];
@@ -605,7 +722,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             dzi[i][v] = dph * ag[i][v];          //                           angle stream
         }
         // (the valve kernels are at their register budget: keep the tokens' work from interleaving)
-        if (VALVE) __builtin_amdgcn_sched_barrier(0);
+        if (VALVE || RET) __builtin_amdgcn_sched_barrier(0);
     }
     BWD_STAMP(7);
     // gradient of the incoming scan state: conj(lambda) G[0]
@@ -613,8 +730,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         float xr[V], xi[V];
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            xr[v] = __builtin_fmaf(lr[v], Gr[v], li[v] * Gi[v]);
-            xi[v] = __builtin_fmaf(lr[v], Gi[v], -li[v] * Gr[v]);
+            xr[v] = RET ? Gr[v] : __builtin_fmaf(lr[v], Gr[v], li[v] * Gi[v]);
+            xi[v] = RET ? Gi[v] : __builtin_fmaf(lr[v], Gi[v], -li[v] * Gr[v]);
         }
         BVec<V>::st(a.dstate_in + ((size_t)b * 2 + 0) * a.J + j0, xr);
         BVec<V>::st(a.dstate_in + ((size_t)b * 2 + 1) * a.J + j0, xi);
@@ -887,6 +1004,15 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             if (t < a.L && grp < a.G) a.vpart[((size_t)b * a.G + grp) * a.L + t] = sVp[e];
         }
     }
+    // ---- and the retention logits' in the same layout
+    if (RET && a.rpart) {
+        if (!(VALVE && a.vpart)) lds_barrier();
+        for (int e = tid; e < a.gpb * TILE_T; e += NT) {
+            const int g = e / TILE_T, tok = e - g * TILE_T;
+            const int t = tt * TILE_T + tok, grp = lb * a.gpb + g;
+            if (t < a.L && grp < a.G) a.rpart[((size_t)b * a.G + grp) * a.L + t] = sRp[e];
+        }
+    }
 
     // ---- LDS is reused by the next tile
     lds_barrier();
@@ -905,7 +1031,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 }
 
 // Persistent grid: what fits on the chip at once (asked once per kernel), never more than tiles.
-template <int V, int KC, bool PARAM, bool VALVE>
+template <int V, int KC, bool PARAM, bool VALVE, bool RET>
 static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
 {
     static int per_cu = 0, cus = 0;
@@ -913,26 +1039,26 @@ static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM, VALVE>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM, VALVE, RET>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
     }
     long long g = (long long)per_cu * cus;
     if (g > (long long)a.total_tiles) g = a.total_tiles;
-    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM, VALVE>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
+    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM, VALVE, RET>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
     return hipGetLastError();
 }
 
-template <int V, bool PARAM, bool VALVE>
+template <int V, bool PARAM, bool VALVE, bool RET = false>
 static hipError_t launch_bwd_vp(const BwdArgs &a, int conv_k, hipStream_t s)
 {
     switch (conv_k) {
-    case 0: return launch_bwd_vkp<V, 0, PARAM, VALVE>(a, s);
-    case 1: return launch_bwd_vkp<V, 1, PARAM, VALVE>(a, s);
-    case 2: return launch_bwd_vkp<V, 2, PARAM, VALVE>(a, s);
-    case 3: return launch_bwd_vkp<V, 3, PARAM, VALVE>(a, s);
-    case 4: return launch_bwd_vkp<V, 4, PARAM, VALVE>(a, s);
+    case 0: return launch_bwd_vkp<V, 0, PARAM, VALVE, RET>(a, s);
+    case 1: return launch_bwd_vkp<V, 1, PARAM, VALVE, RET>(a, s);
+    case 2: return launch_bwd_vkp<V, 2, PARAM, VALVE, RET>(a, s);
+    case 3: return launch_bwd_vkp<V, 3, PARAM, VALVE, RET>(a, s);
+    case 4: return launch_bwd_vkp<V, 4, PARAM, VALVE, RET>(a, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -941,6 +1067,7 @@ hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s)
 {
     (void)vec;      // one lane per thread in every build of the backward kernel
     static_assert(BwdV == 1, "the vectorised backward was dropped");
+    if (a.ret) return a.valve ? launch_bwd_vp<1, true, true, true>(a, conv_k, s) : launch_bwd_vp<1, true, false, true>(a, conv_k, s);
     if (a.valve)
         return a.want_param ? launch_bwd_vp<1, true, true>(a, conv_k, s) : launch_bwd_vp<1, false, true>(a, conv_k, s);
     return a.want_param ? launch_bwd_vp<1, true, false>(a, conv_k, s) : launch_bwd_vp<1, false, false>(a, conv_k, s);

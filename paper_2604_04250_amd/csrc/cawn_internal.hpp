@@ -178,6 +178,10 @@ struct BwdArgs {
     float *vpart;                // null: no valve gradient wanted
     int H, F, gpb, G;
     float valve_thr;
+    // ret_mode 1 (data-dependent retention): see FwdArgs; rpart like vpart, for the retention logits
+    const float *ret;            // null: ret_mode 0
+    float *rpart;                // null: no gradient of the retention logits wanted
+    tagged_t *aggp;
 };
 
 // Number of per-lane partial sums a backward tile emits: dgamma, dtheta, dbias[2], dw[2][conv_k].

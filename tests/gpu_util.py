@@ -121,17 +121,20 @@ def mask_from_gate(gate):
 
 def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
                 grad_clamp=100.0, state_in=None, dstate_out=None, want_param=True, want_dstate=True,
-                accumulate=0, preset=None, ws=None, valve=None, valve_eps=0.001, want_dvalve=True):
+                accumulate=0, preset=None, ws=None, valve=None, valve_eps=0.001, want_dvalve=True,
+                ret=None, ret_bias=None, want_dret=True):
     """Forward (to get the checkpoints) then backward through the C ABI.  inp additionally holds
     dz_re, dz_im [B,L,J].  Returns dict of numpy arrays: dmag, dang, dgamma, dtheta, dconv_w, dconv_b,
     dstate_in (flat blob)."""
     J = H * F
     d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau, conv_clamp=conv_clamp,
                     out_clamp=out_clamp, grad_clamp=grad_clamp, accumulate_param_grads=accumulate,
-                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps)
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps, ret_mode=0 if ret is None else 1)
     vlv = None if valve is None else dev(np.ascontiguousarray(valve[:, :L]))
+    rt = None if ret is None else dev(np.ascontiguousarray(ret[:, :L]))
+    rbias = dev(ret_bias)
     mag, ang = dev(inp["mag"][:, :L]), dev(inp["ang"][:, :L])
-    gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
+    gamma, theta = dev(inp.get("gamma")), dev(inp["theta"])
     cw = dev(inp["conv_w"]) if conv_k > 0 else None
     cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
     z_re = torch.empty((B, max(L, 1), J), device=DEV)
@@ -139,7 +142,10 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
     st_in = dev(state_in)
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
     ws = ws if ws is not None else Workspaces.get(d)
-    if valve is None:
+    if ret is not None:
+        K.check(K.cawn_phase_accumulate_ret_fwd(d, mag, ang, vlv, rt, rbias, theta, cw, cb, st_in, z_re, z_im, None,
+                                                ckpt, None, ws))
+    elif valve is None:
         K.check(K.cawn_phase_accumulate_fwd(d, mag, ang, gamma, theta, cw, cb, st_in, z_re, z_im, None, ckpt, None, ws))
     else:
         K.check(K.cawn_phase_accumulate_valve_fwd(d, mag, ang, vlv, gamma, theta, cw, cb, st_in, z_re, z_im, None,
@@ -149,14 +155,20 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
     dang = torch.full((B, max(L, 1), J), float("nan"), device=DEV)
     nstate = K.cawn_state_bytes(d) // 4
     fill = float("nan") if preset is None else preset
-    dgamma = torch.full((J,), fill, device=DEV) if want_param else None
+    dgamma = torch.full((J,), fill, device=DEV) if want_param and ret is None else None
     dtheta = torch.full((J,), fill, device=DEV) if want_param else None
     dcw = torch.full((2, J, conv_k), fill, device=DEV) if want_param and conv_k > 0 else None
     dcb = torch.full((2, J), fill, device=DEV) if want_param and conv_k > 0 else None
     dst_in = torch.full((nstate,), float("nan"), device=DEV) if want_dstate else None
     d.lane_consts_cached = 1
-    dvalve = None
-    if valve is None:
+    dvalve = dret = None
+    if ret is not None:
+        dvalve = torch.full((B, max(L, 1), H), float("nan"), device=DEV) if want_dvalve and valve is not None else None
+        dret = torch.full((B, max(L, 1), H), float("nan"), device=DEV) if want_dret else None
+        K.check(K.cawn_phase_accumulate_ret_bwd(d, mag, ang, vlv, rt, rbias, theta, cw, cb, st_in, ckpt, dz_re, dz_im,
+                                                dev(dstate_out), dmag, dang, dvalve, dret, dtheta, dcw, dcb,
+                                                dst_in, ws))
+    elif valve is None:
         K.check(K.cawn_phase_accumulate_bwd(d, mag, ang, gamma, theta, cw, cb, st_in, ckpt, dz_re, dz_im,
                                             dev(dstate_out), dmag, dang, dgamma, dtheta, dcw, dcb, dst_in, ws))
     else:
@@ -169,6 +181,8 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
     out = dict(dmag=dmag[:, :L].cpu().numpy(), dang=dang[:, :L].cpu().numpy())
     if dvalve is not None:
         out["dvalve"] = dvalve[:, :L].cpu().numpy()
+    if dret is not None:
+        out["dret"] = dret[:, :L].cpu().numpy()
     for k, v in (("dgamma", dgamma), ("dtheta", dtheta), ("dconv_w", dcw), ("dconv_b", dcb), ("dstate_in", dst_in)):
         if v is not None:
             out[k] = v.cpu().numpy()

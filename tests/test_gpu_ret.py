@@ -145,3 +145,81 @@ def test_retention_errors():
     d = K.make_desc(1, 8, 2, 32, ret_mode=1)
     assert K.cawn_phase_accumulate_fwd(d, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EUNSUPPORTED
     assert K.cawn_phase_accumulate_ret_fwd(d, x, x, None, None, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL
+
+
+def _check_bwd(B, L, H, F, Kc, d, amp_mode=0, valve=False, tau=0.0, state=None, dstate=None, tol=TOL, **kw):
+    G = _gpu()
+    J = H * F
+    scan_in = tail_in = blob = dblob = None
+    if state is not None:
+        scan_in, tail_in = state
+        blob = G.pack_state(scan_in, tail_in if Kc > 1 else None)
+    dscan = dtail = None
+    if dstate is not None:
+        dscan, dtail = dstate
+        dblob = G.pack_state(dscan, dtail if Kc > 1 else None)
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_mode=1 if valve else 0, gate_tau=tau, ret_mode=1)
+    ora = O.phase_bwd(cfg, d["mag"][:, :L], d["ang"][:, :L], None, d["theta"], d["dz_re"][:, :L],
+                      d["dz_im"][:, :L], conv_w=d["conv_w"], conv_b=d["conv_b"],
+                      valve=d["valve"][:, :L] if valve else None, ret=d["ret"][:, :L], ret_bias=d["ret_bias"],
+                      scan_in=None if scan_in is None else scan_in.astype(np.float64),
+                      tail_in=tail_in if Kc > 1 else None,
+                      dscan_out=None if dscan is None else dscan.astype(np.float64),
+                      dtail_out=None if dtail is None or Kc <= 1 else dtail.astype(np.float64))
+    out = G.run_fwd_bwd(d, B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, state_in=blob, dstate_out=dblob,
+                        valve=d["valve"] if valve else None, ret=d["ret"], ret_bias=d["ret_bias"], **kw)
+    names = ["dmag", "dang", "dret", "dvalve", "dtheta"] + (["dconv_w", "dconv_b"] if Kc > 0 else [])
+    for n in names:
+        if n in out:
+            e = G.rel_err(out[n], ora[n])
+            assert e <= tol, (n, e)
+    if "dstate_in" in out:
+        dsi, dti = G.unpack_state(out["dstate_in"], B, J, Kc)
+        assert G.rel_err(dsi, ora["dscan_in"]) <= tol
+        if Kc > 1:
+            assert G.rel_err(dti, ora["dtail_in"]) <= tol
+    assert "dgamma" not in out
+    return out, ora
+
+
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (8, 8), (1, 128), (3, 16)])
+@pytest.mark.parametrize("Kc", [0, 2, 4])
+def test_retention_backward_head_widths(H, F, Kc):
+    B, L = 2, 333                      # three backward tiles, ragged tail
+    d = _inputs(B, L, H, F, Kc, 5700 + H * 131 + F + Kc)
+    out, ora = _check_bwd(B, L, H, F, Kc, d, tau=0.25)
+    assert np.abs(ora["dret"]).max() > 1e-3
+
+
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 16), (1, 128)])
+@pytest.mark.parametrize("Kc", [0, 3])
+def test_retention_backward_with_the_valve(H, F, Kc):
+    B, L = 2, 300
+    d = _inputs(B, L, H, F, Kc, 5900 + H * 131 + F + Kc)
+    _check_bwd(B, L, H, F, Kc, d, amp_mode=1, valve=True)
+
+
+def test_retention_backward_long_memory_and_state_gradients():
+    """Retention near 0.999: adjoints travel across many tiles; with incoming state, its gradient, and the
+    gradient of the outgoing state."""
+    B, L, H, F, Kc = 2, 1500, 2, 64, 4
+    J = H * F
+    d = _inputs(B, L, H, F, Kc, 6100, ret_mean=5.0, ret_std=0.7)
+    r = np.random.Generator(np.random.PCG64(6))
+    state = (r.standard_normal((B, 2, J)).astype(np.float32), r.standard_normal((B, Kc - 1, 2, J)).astype(np.float32))
+    dstate = (r.standard_normal((B, 2, J)).astype(np.float32), r.standard_normal((B, Kc - 1, 2, J)).astype(np.float32))
+    _check_bwd(B, L, H, F, Kc, d, state=state, dstate=dstate)
+
+
+@pytest.mark.parametrize("L", [1, 7, 127, 128, 129])
+def test_retention_backward_lengths(L):
+    B, H, F, Kc = 3, 2, 64, 3
+    d = _inputs(B, 200, H, F, Kc, 6300 + L)
+    _check_bwd(B, L, H, F, Kc, d, amp_mode=1)
+
+
+def test_retention_backward_without_logit_gradient_or_parameters():
+    B, L, H, F, Kc = 2, 400, 2, 64, 4
+    d = _inputs(B, L, H, F, Kc, 6400)
+    _check_bwd(B, L, H, F, Kc, d, want_dret=False)
+    _check_bwd(B, L, H, F, Kc, d, want_param=False)
