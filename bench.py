@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--valve", action="store_true",
                     help="gate_mode 1: the per-head input valve of Sec. 3.3 instead of the per-lane threshold "
                          "(extra line, not the headline; no CPU baseline)")
+    ap.add_argument("--ret", action="store_true",
+                    help="ret_mode 1: the data-dependent retention of Sec. 3.3 item 4 instead of the constant gamma "
+                         "(extra line, not the headline; no CPU baseline; with --valve: the paper's literal layer)")
     ap.add_argument("--workload", default="cfg3_train",
                     choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "decode"])
     ap.add_argument("--decode-batch", type=int, default=1)
@@ -183,7 +186,17 @@ def main():
         sets.append(cur)
     t_gen = time.time() - t_gen
 
-    d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau, gate_mode=1 if args.valve else 0)
+    d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau, gate_mode=1 if args.valve else 0,
+                    ret_mode=1 if args.ret else 0)
+    ret = ret_bias = dret = None
+    if args.ret:
+        assert not stream_mode, "--ret: cfg2_layer_fwd, cfg3_train or cfg5_wide"
+        args.no_cpu_baseline = True
+        # logits around the paper's initial projection bias -2, b_k falling from +3 to 0 over the harmonics
+        rr = np.random.Generator(np.random.PCG64(4250 + 98))
+        ret = torch.from_numpy((-2.0 + 1.5 * rr.standard_normal((B, L, H))).astype(np.float32)).to(dev)
+        ret_bias = torch.from_numpy(np.linspace(3.0, 0.0, F).astype(np.float32)).to(dev)
+        dret = torch.empty((B, L, H), device=dev)
     valve = dvalve = None
     if args.valve:
         assert not stream_mode, "--valve: cfg2_layer_fwd, cfg3_train or cfg5_wide"
@@ -201,6 +214,9 @@ def main():
 
     # first call builds the lane table; later calls reuse it (parameters do not change in the bench)
     def fwd_call(dd, p, st_in, st_out, ck):
+        if ret is not None:
+            return K.cawn_phase_accumulate_ret_fwd(dd, p["mag"], p["ang"], valve, ret, ret_bias, th, cw, cb, st_in,
+                                                   p["z_re"], p["z_im"], st_out, ck, None, ws)
         if valve is not None:
             return K.cawn_phase_accumulate_valve_fwd(dd, p["mag"], p["ang"], valve, gamma, th, cw, cb, st_in,
                                                      p["z_re"], p["z_im"], st_out, ck, None, ws)
@@ -235,7 +251,11 @@ def main():
         if rec is not None:
             rec[1].record()
         if do_bwd:
-            if valve is not None:
+            if ret is not None:
+                st |= K.cawn_phase_accumulate_ret_bwd(d, s["mag"], s["ang"], valve, ret, ret_bias, th, cw, cb, None,
+                                                      ckpt, s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"],
+                                                      dvalve, dret, dtheta, dcw, dcb, None, ws)
+            elif valve is not None:
                 st |= K.cawn_phase_accumulate_valve_bwd(d, s["mag"], s["ang"], valve, gamma, th, cw, cb, None, ckpt,
                                                         s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"], dvalve,
                                                         dgamma, dtheta, dcw, dcb, None, ws)
@@ -273,7 +293,13 @@ def main():
                                   + (f" chunk={wl.chunk} state carried in place" if stream_mode else ""),
                       "pass": "fwd+bwd (all gradients)" if do_bwd else "fwd",
                       "gate": "per-head valve (gate_mode 1), about half shut" if args.valve else "per-lane threshold",
+                      "retention": "sigmoid(logit[t][h] + b_k) (ret_mode 1), logits ~ N(-2, 1.5^2), b_k from +3 to 0"
+                                   if args.ret else "constant per lane",
                       "buffer_sets_rotated": nsets}}
+    bflag = lambda x: "true" if x else "false"
+    fwd_label = f"fwd_kernel<1,4,{bflag(args.valve)},{bflag(args.ret)}>"
+    bwd_label = f"bwd_kernel<1,4,true,{bflag(args.valve)},{bflag(args.ret)}>"
+    extra = args.valve or args.ret
 
     # ---- roofline of the dominant kernel, from HIP events on the launch stream
     if stream_mode:
@@ -281,7 +307,7 @@ def main():
         per_call_ms = ms_per_step / ncalls
         alg = FWD_BYTES_PER_TOKEN_LANE * tokens * J / ncalls
         achieved = alg / (per_call_ms * 1e-3) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4,false> (per 4096-token chunk call, launch gaps included)",
+        out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4,false,false> (per 4096-token chunk call, launch gaps included)",
                            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                            "traffic": read_traffic(args.workload), "avg_ms": per_call_ms}
         out["stream"] = {"calls": ncalls, "state_bytes": nstate * 4, "device_mem_delta_bytes": int(mem1 - mem0)}
@@ -299,14 +325,14 @@ def main():
             out["bwd_ms_median_min"] = [float(np.median(bwd_all)), float(np.min(bwd_all))]
             alg = BWD_BYTES_PER_TOKEN_LANE * tokens * J
             achieved = alg / (bwd_ms * 1e-3) / 1e9
-            out["roofline"] = {"bound": "hbm", "kernel": ("bwd_kernel<1,4,true,true>" if args.valve else "bwd_kernel<1,4,true,false>") + " (+ its partial-sum reduction)",
+            out["roofline"] = {"bound": "hbm", "kernel": bwd_label + " (+ its partial-sum reduction)",
                                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                               "frac": achieved / HBM_PEAK_GBS, "traffic": None if args.valve else read_traffic(args.workload),
+                               "frac": achieved / HBM_PEAK_GBS, "traffic": None if extra else read_traffic(args.workload),
                                "avg_ms": bwd_ms}
         else:
-            out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4,true>" if args.valve else "fwd_kernel<1,4,false>", "achieved": out["fwd_GBps"],
+            out["roofline"] = {"bound": "hbm", "kernel": fwd_label, "achieved": out["fwd_GBps"],
                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": out["fwd_GBps"] / HBM_PEAK_GBS,
-                               "traffic": None if args.valve else read_traffic(args.workload), "avg_ms": fwd_ms}
+                               "traffic": None if extra else read_traffic(args.workload), "avg_ms": fwd_ms}
 
     # ---- the fp64 oracle on the host cores, on a bounded sample of the same inputs (baseline only)
     if not args.no_cpu_baseline:
