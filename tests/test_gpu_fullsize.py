@@ -185,3 +185,72 @@ def test_cfg4_streaming_two_million_tokens_constant_memory():
     scan, tail = G.unpack_state(state.cpu().numpy(), B, J, Kc)
     assert G.rel_err(scan[..., lanes], ora["scan_out"]) <= TOL
     assert np.array_equal(tail[..., lanes], ora["tail_out"])
+
+
+@pytest.mark.parametrize("valve,ret", [(True, False), (False, True), (True, True)])
+def test_cfg3_training_step_full_size_valve_and_retention(valve, ret):
+    """The training-step shape with the per-head valve (Sec. 3.3 "Hard-Threshold Gating"), the
+    data-dependent retention (Sec. 3.3 item 4) and both, launched as bench.py --valve / --ret launches
+    them.  Heads are independent: the oracle computes two whole heads (all their lanes, so that the
+    per-head logit gradients are complete) over the full sequences."""
+    import torch
+    import gpu_util as G
+    from paper_2604_04250_amd import binding as K
+    wl = WL.CONFIGS["cfg3_train"]
+    B, L, H, F, J, Kc = wl.B, wl.L, wl.H, wl.F, wl.J, wl.conv_k
+    theta = K.cawn_theta_init(H, F)
+    inp = WL.make_inputs(wl, theta=theta, with_grads=True)
+    r = np.random.Generator(np.random.PCG64(4250 + 97))
+    vlog = (-3.9 + 3.0 * r.standard_normal((B, L, H))).astype(np.float32)
+    rlog = (-2.0 + 1.5 * r.standard_normal((B, L, H))).astype(np.float32)
+    rbias = np.linspace(3.0, 0.0, F).astype(np.float32)
+    dev = G.DEV
+    t = {k: torch.from_numpy(inp[k]).to(dev) for k in inp}
+    tv, tr, tb = (torch.from_numpy(x).to(dev) for x in (vlog, rlog, rbias))
+    d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau, gate_mode=1 if valve else 0, ret_mode=1 if ret else 0)
+    ws = K.alloc_workspace(d, dev)
+    z_re, z_im = torch.empty((B, L, J), device=dev), torch.empty((B, L, J), device=dev)
+    ckpt = torch.empty(K.cawn_ckpt_bytes(d) // 4, device=dev)
+    dmag, dang = torch.empty((B, L, J), device=dev), torch.empty((B, L, J), device=dev)
+    dg, dt = torch.empty(J, device=dev), torch.empty(J, device=dev)
+    dcw, dcb = torch.empty((2, J, Kc), device=dev), torch.empty((2, J), device=dev)
+    dvalve = torch.empty((B, L, H), device=dev) if valve else None
+    dret = torch.empty((B, L, H), device=dev) if ret else None
+    if ret:
+        K.check(K.cawn_phase_accumulate_ret_fwd(d, t["mag"], t["ang"], tv if valve else None, tr, tb, t["theta"], t["conv_w"],
+                                                t["conv_b"], None, z_re, z_im, None, ckpt, None, ws))
+        d.lane_consts_cached = 1
+        K.check(K.cawn_phase_accumulate_ret_bwd(d, t["mag"], t["ang"], tv if valve else None, tr, tb, t["theta"], t["conv_w"],
+                                                t["conv_b"], None, ckpt, t["dz_re"], t["dz_im"], None, dmag, dang, dvalve,
+                                                dret, dt, dcw, dcb, None, ws))
+    else:
+        K.check(K.cawn_phase_accumulate_valve_fwd(d, t["mag"], t["ang"], tv, t["gamma"], t["theta"], t["conv_w"], t["conv_b"],
+                                                  None, z_re, z_im, None, ckpt, None, ws))
+        d.lane_consts_cached = 1
+        K.check(K.cawn_phase_accumulate_valve_bwd(d, t["mag"], t["ang"], tv, t["gamma"], t["theta"], t["conv_w"], t["conv_b"],
+                                                  None, ckpt, t["dz_re"], t["dz_im"], None, dmag, dang, dvalve, dg, dt,
+                                                  dcw, dcb, None, ws))
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    for h in (0, H - 1):
+        lanes = np.arange(h * F, (h + 1) * F)
+        sub = _sub(inp, lanes)
+        cfg = O.Cfg(B, L, 1, F, conv_k=Kc, gate_tau=wl.gate_tau, gate_mode=1 if valve else 0, ret_mode=1 if ret else 0)
+        kw = dict(conv_w=sub["conv_w"], conv_b=sub["conv_b"], valve=np.ascontiguousarray(vlog[:, :, h:h + 1]) if valve else None,
+                  ret=np.ascontiguousarray(rlog[:, :, h:h + 1]) if ret else None, ret_bias=rbias if ret else None)
+        of = O.phase_fwd(cfg, sub["mag"], sub["ang"], None if ret else sub["gamma"], sub["theta"], want_gate=False, **kw)
+        ob = O.phase_bwd(cfg, sub["mag"], sub["ang"], None if ret else sub["gamma"], sub["theta"], sub["dz_re"], sub["dz_im"], **kw)
+        sl = slice(h * F, (h + 1) * F)
+        errs = dict(z_re=G.rel_err(z_re[..., sl].cpu().numpy(), of["z_re"]), z_im=G.rel_err(z_im[..., sl].cpu().numpy(), of["z_im"]),
+                    dmag=G.rel_err(dmag[..., sl].cpu().numpy(), ob["dmag"]), dang=G.rel_err(dang[..., sl].cpu().numpy(), ob["dang"]),
+                    dtheta=G.rel_err(dt.cpu().numpy()[sl], ob["dtheta"]),
+                    dconv_w=G.rel_err(dcw.cpu().numpy()[:, sl], ob["dconv_w"]),
+                    dconv_b=G.rel_err(dcb.cpu().numpy()[:, sl], ob["dconv_b"]))
+        if valve:
+            errs["dvalve"] = G.rel_err(dvalve[..., h].cpu().numpy(), ob["dvalve"][..., 0])
+        if ret:
+            errs["dret"] = G.rel_err(dret[..., h].cpu().numpy(), ob["dret"][..., 0])
+        else:
+            errs["dgamma"] = G.rel_err(dg.cpu().numpy()[sl], ob["dgamma"])
+        bad = {k: v for k, v in errs.items() if not v <= TOL}
+        assert not bad, (h, bad, errs)
