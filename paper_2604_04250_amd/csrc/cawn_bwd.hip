@@ -107,6 +107,10 @@ template <int V, int KC, bool PARAM, bool VALVE, bool RET>
 __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
     static_assert(!RET || (PARAM && V == 1), "retention kernels rebuild the forward state; one lane per thread");
+    // The valve and retention kernels sit at the register budget.  They keep the reduced angle instead
+    // of its sin and cos between the front-end and the reverse pass, park the conv taps in LDS during
+    // the reverse pass and fetch the reverse-pass constants after the front-end.
+    constexpr bool LEAN = VALVE || RET;
     constexpr int TILE_T = BwdGeom::TILE_T, NSTEP = BwdGeom::NSTEP, NSEG = BwdGeom::NSEG, LPR = BwdLPR;
     constexpr int JB = V * LPR;
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
@@ -129,7 +133,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     constexpr int GPB_MAX = 4;                    // valve groups per lane block (F >= 8)
     __shared__ float sV[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];      // valve logits, [group][token]
     __shared__ float sVp[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
-    __shared__ float sTaps[VALVE ? 2 * KC1 : 1][JB];                 // conv taps of the lane block (valve kernels)
+    __shared__ float sTaps[LEAN ? 2 * KC1 : 1][JB];                 // conv taps of the lane block (valve kernels)
     __shared__ float sPb[RET ? NSEG : 1][JB];                        // product of each segment's retentions
     __shared__ float sPt[RET ? 1 : 1][JB];                           // product of the tile's retentions (head group)
     __shared__ float sRp[RET ? BwdGeom::TILE_T * GPB_MAX : 1];       // retention-logit gradient terms per (group, token)
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             ldu<V>(waf[k], row(R_W0 + KC + k), jb);
         }
     }
-    if (VALVE && KC > 0 && seg == 0) {      // (read back after the barrier before the transposed conv)
+    if (LEAN && KC > 0 && seg == 0) {      // (read back after the barrier before the transposed conv)
 #pragma unroll
         for (int k = 0; k < KC; ++k)
 #pragma unroll
@@ -381,7 +385,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float psr[V], psi[V], cth[V], sth[V], gam[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) { sth[v] = gam[v] = 0.f; cth[v] = 1.f; }
-    if (!VALVE) {
+    if (!LEAN) {
         if (PARAM && active && a.ckpt) {
             const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
             BVec<V>::ld(kr, ck);
@@ -482,7 +486,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 } else {
                     agv = in_gate(a.gs, zm) ? amp : 0.0f;
                 }
-                cs[i][v] = VALVE ? rev : c;
+                cs[i][v] = LEAN ? rev : c;
                 sn[i][v] = s;
                 dsm[i][v] = km;
                 ag[i][v] = agv * ka;
@@ -514,7 +518,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         default: front_end(T_{}, T_{}); break;
         }
     }
-    if (VALVE) {
+    if (LEAN) {
         if (PARAM && active && a.ckpt) {
             const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
             BVec<V>::ld(kr, ck);
@@ -522,7 +526,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
         ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);
         ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
-        if (PARAM) {
+        if (PARAM && !RET) {      // (retention kernels: the table's lambda is e^{i theta} itself, and gamma is per token)
             ldu<V>(cth, row(R_COS), jb);
             ldu<V>(sth, row(R_SIN), jb);
             ldu<V>(gam, row(R_GAMMA), jb);
@@ -682,8 +686,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 Gi[v] = ni;
             }
             if (PARAM) {
-                const float rr = __builtin_fmaf(cth[v], Spr[i][v], -sth[v] * Spi[i][v]);
-                const float ri = __builtin_fmaf(sth[v], Spr[i][v], cth[v] * Spi[i][v]);
+                const float ct_ = RET ? lr[v] : cth[v], st_ = RET ? li[v] : sth[v];
+                const float rr = __builtin_fmaf(ct_, Spr[i][v], -st_ * Spi[i][v]);
+                const float ri = __builtin_fmaf(st_, Spr[i][v], ct_ * Spi[i][v]);
                 const float tg = __builtin_fmaf(nr, rr, ni * ri);
                 const float tth = (RET ? gm[i][v] : gam[v]) * __builtin_fmaf(ni, rr, -nr * ri);
                 acc_g[v] += clampf(tg, a.grad_clamp);
@@ -695,8 +700,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 }
             }
             const float gr_ = clampf(nr, a.grad_clamp), gi_ = clampf(ni, a.grad_clamp);
-            const float c_ = VALVE ? __builtin_amdgcn_cosf(cs[i][v]) : cs[i][v];
-            const float s_ = VALVE ? __builtin_amdgcn_sinf(cs[i][v]) : sn[i][v];
+            const float c_ = LEAN ? __builtin_amdgcn_cosf(cs[i][v]) : cs[i][v];
+            const float s_ = LEAN ? __builtin_amdgcn_sinf(cs[i][v]) : sn[i][v];
             const float da = __builtin_fmaf(gr_, c_, gi_ * s_);
             const float dph = __builtin_fmaf(gi_, c_, -gr_ * s_);
             if (VALVE) {      // d/d beta, summed over the lanes that share the valve
@@ -767,8 +772,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         for (int k = 0; k < KC; ++k)
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                wm[k][v] = VALVE ? sTaps[k][lv * V + v] : wmf[k][v];
-                wa[k][v] = VALVE ? sTaps[KC + k][lv * V + v] : waf[k][v];
+                wm[k][v] = LEAN ? sTaps[k][lv * V + v] : wmf[k][v];
+                wa[k][v] = LEAN ? sTaps[KC + k][lv * V + v] : waf[k][v];
             }
         if (HALO > 0) {
 #pragma unroll
