@@ -230,6 +230,23 @@ int cawn_phase_accumulate_ret_bwd(const cawn_desc *d, const float *mag, const fl
                                   float *dang, float *dvalve, float *dret, float *dtheta,
                                   float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
                                   size_t workspace_bytes, void *stream);
+/*
+ * Forward with bfloat16 activations in memory (the paper runs the network in bf16 and this
+ * accumulator in fp32: Sec. 3.5, Sec. 6.1): mag, ang, z_re, z_im hold bf16 values (the upper 16 bits
+ * of an fp32), strides count bf16 elements; inputs are widened exactly, all arithmetic, the carried
+ * state, the checkpoints and the lane constants stay fp32, outputs are rounded to nearest even.
+ * d->gate_mode and d->ret_mode select the variant: valve is read when gate_mode == 1; ret and
+ * ret_bias when ret_mode == 1 (gamma is then ignored), gamma otherwise; unused ones may be NULL.
+ * Needs an even H*F, even strides and 4-byte aligned mag/ang (CAWN_EUNSUPPORTED otherwise).
+ * Everything else as in cawn_phase_accumulate_fwd.
+ */
+int cawn_phase_accumulate_bf16_fwd(const cawn_desc *d, const uint16_t *mag, const uint16_t *ang,
+                                   const float *valve, const float *ret, const float *ret_bias,
+                                   const float *gamma, const float *theta, const float *conv_w,
+                                   const float *conv_b, const void *state_in, uint16_t *z_re,
+                                   uint16_t *z_im, void *state_out, void *ckpt, uint32_t *gate_mask,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

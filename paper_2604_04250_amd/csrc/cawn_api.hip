@@ -509,7 +509,7 @@ int cawn_syntax_conv(const cawn_desc *d, int32_t C, const float *x, const float 
 static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
                     const float *ret, const float *ret_bias, const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                     const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
-                    uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
+                    uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream, bool bf16 = false)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
     if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
@@ -541,8 +541,11 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
     if (ist > (1ll << 21) || ost > (1ll << 21)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
+    // bf16 rows are staged as four-byte words: an even number of lanes, even strides, aligned rows
+    if (bf16 && (J % 2 || ist % 2 || isb % 2 || !aligned(mag, 4) || !aligned(ang, 4))) return CAWN_EUNSUPPORTED;
 
     FwdArgs a{};
+    a.bf16 = bf16 ? 1 : 0;
     if (d->gate_mode == 1) {
         const float INF = std::numeric_limits<float>::infinity();
         a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
@@ -588,6 +591,7 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.small_angle = (d->conv_k > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;   // |angle| <= SiLU(clamp) <= 41 revolutions
     a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&
                  (!state_in || aligned(state_in, 16))) ? 1 : 0;
+    if (bf16) a.stage16 = (J % 8 == 0 && ist % 8 == 0 && isb % 8 == 0 && aligned(mag, 16) && aligned(ang, 16)) ? 1 : 0;
     a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
     a.conv_clamp = d->conv_clamp; a.out_clamp = d->out_clamp;
     a.spin_limit = g_spin_limit.load();
@@ -788,6 +792,20 @@ int cawn_phase_accumulate_valve_bwd(const cawn_desc *d, const float *mag, const 
     return bwd_impl(d, mag, ang, valve, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im,
                     dstate_out, dmag, dang, dvalve, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace,
                     workspace_bytes, stream);
+}
+
+int cawn_phase_accumulate_bf16_fwd(const cawn_desc *d, const uint16_t *mag, const uint16_t *ang, const float *valve,
+                                   const float *ret, const float *ret_bias, const float *gamma, const float *theta,
+                                   const float *conv_w, const float *conv_b, const void *state_in, uint16_t *z_re,
+                                   uint16_t *z_im, void *state_out, void *ckpt, uint32_t *gate_mask, void *workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    return fwd_impl(d, reinterpret_cast<const float *>(mag), reinterpret_cast<const float *>(ang),
+                    d->gate_mode == 1 ? valve : nullptr, d->ret_mode == 1 ? ret : nullptr,
+                    d->ret_mode == 1 ? ret_bias : nullptr, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
+                    state_in, reinterpret_cast<float *>(z_re), reinterpret_cast<float *>(z_im), state_out, ckpt,
+                    gate_mask, workspace, workspace_bytes, stream, true);
 }
 
 int cawn_phase_accumulate_ret_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *valve,

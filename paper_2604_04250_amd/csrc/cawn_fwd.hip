@@ -111,20 +111,31 @@ __device__ __forceinline__ void stage_consts(float *sC, const float *table, int 
 // what arrives from token t-1 (accumulation equations of Sec. 3.4, printed with gamma_{t,j}).  A run of
 // tokens then acts on an incoming state as S_out = E + (product of the run's gammas) e^{i n theta} S_in:
 // the lane table holds pure rotations and every level carries the real product beside its aggregate.
-template <int V, int KC, bool VALVE, bool RET>
+// BF: activations (mag, ang in; z_re, z_im out) are bfloat16 in memory; arithmetic, state and
+// checkpoints stay fp32 (Sec. 3.5 / Sec. 6.1 of the paper: the network runs in bf16, the accumulator in
+// fp32).  A staged row of JB bf16 lanes is handled as JB/2 four-byte words; outputs are rounded to
+// nearest even by the hardware conversion.
+template <int V, int KC, bool VALVE, bool RET, bool BF>
 __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
+    static_assert(!BF || V == 1, "bf16 activations: one lane per thread");
     constexpr int TILE_T = FwdGeom::TILE_T, NSTEP = FwdGeom::NSTEP, NSEG = FwdGeom::NSEG, LPR = FwdLPR;
     constexpr int JB = V * LPR;
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
     constexpr int KC1 = KC > 0 ? KC : 1;
     constexpr int NT = NSEG * LPR;                 // threads
     constexpr int NW = NT / 64;                    // waves
-    constexpr int NRTP = staged_rows<TILE_T, JB, HALO>();   // staged rows per stream: time tile_t0-HALO+rr
+    constexpr int JBS = BF ? JB / 2 : JB;          // four-byte words per staged row
+    constexpr int NRTP = staged_rows<TILE_T, JBS, HALO>();   // staged rows per stream: time tile_t0-HALO+rr
     static_assert(JB <= 256 && 256 % JB == 0, "a staged row must fit a wave");
     static_assert(NW >= 2, "one wave owns the chain, the others stage the next tile");
 
-    __shared__ __attribute__((aligned(16))) float sU[2 * NRTP][JB];   // [stream*NRTP + rr][lane]
+    __shared__ __attribute__((aligned(16))) float sU[2 * NRTP][JBS];  // [stream*NRTP + rr][lane]
+    // element (row, lane) of the staged rows as fp32
+    auto su = [&](int r, int l) -> float {
+        if constexpr (BF) return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(&sU[r][0])[l] << 16);
+        else return sU[r][l];
+    };
     __shared__ float sE[NSEG][2][JB];
     __shared__ float sCarry[2][JB];
     constexpr int NCR = R_W0 - R_LR + 2 * KC;     // staged lane-constant rows
@@ -165,12 +176,13 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         if (wave == 0) stage_consts<NCR, JB>(&sC[0][0], a.table, a.Jp, T.lb, lane);
         if (VALVE && wave == 0) stage_valve<TILE_T, JB>(&sV[0], a.valve, T.b, T.tt * TILE_T, T.lb, a.L, a.H, a.F, a.gpb, lane);
         if (RET && wave == 0) stage_valve<TILE_T, JB>(&sR[0], a.ret, T.b, T.tt * TILE_T, T.lb, a.L, a.H, a.F, a.gpb, lane);
+        // (bf16: rows of J/2 words at half the strides; the fp32 conv history is read at its point of use)
         if (a.stage16)
-            stage_rows<TILE_T, JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
-                                     ist32, wave, NW - 1, lane);
+            stage_rows<TILE_T, JBS, HALO, 16>(&sU[0][0], a.mag, a.ang, BF ? nullptr : tail_in, T.b, T.tt * TILE_T, T.lb,
+                                      BF ? a.J / 2 : a.J, a.L, BF ? a.isb / 2 : a.isb, BF ? ist32 / 2 : ist32, wave, NW - 1, lane);
         else
-            stage_rows<TILE_T, JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, T.b, T.tt * TILE_T, T.lb, a.J, a.L, a.isb,
-                                    ist32, wave, NW - 1, lane);
+            stage_rows<TILE_T, JBS, HALO, 4>(&sU[0][0], a.mag, a.ang, BF ? nullptr : tail_in, T.b, T.tt * TILE_T, T.lb,
+                                     BF ? a.J / 2 : a.J, a.L, BF ? a.isb / 2 : a.isb, BF ? ist32 / 2 : ist32, wave, NW - 1, lane);
     };
 
     TileId T{};
@@ -240,6 +252,23 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         float gm[RET ? NSTEP : 1][V], Pth[V];     // RET: retention of each token, product over my tokens
         uint32_t gbits[NSTEP];
         const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
+        // bf16: the carried conv history is fp32 and is not staged; the one segment that needs it reads it
+        // here (and waits for it here, so that no wait for it lands in the common path)
+        float hwm[KC1][V], hwa[KC1][V];
+#pragma unroll
+        for (int k = 0; k < KC1; ++k)
+#pragma unroll
+            for (int v = 0; v < V; ++v) hwm[k][v] = hwa[k][v] = 0.f;
+        const bool hist_bf = BF && HALO > 0 && tail_in && tt == 0 && seg == 0;
+        if (hist_bf) {
+#pragma unroll
+            for (int k = 0; k < HALO; ++k) {
+                const size_t o = ((size_t)(b * HALO + k) * 2) * a.J + (active ? j0 : 0);
+                hwm[k][0] = tail_in[o];
+                hwa[k][0] = tail_in[o + a.J];
+            }
+            wait_vm<0>();
+        }
         // (my lane's valve group in the block is lane / F when heads are narrower than the block)
         const int vbase = (VALVE || RET) ? (a.F >= JB ? 0 : (lv * V) / a.F) * TILE_T + seg * NSTEP : 0;
         // The mode switches are uniform over the launch; each combination gets its own straight-line
@@ -253,8 +282,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
             for (int k = 0; k < KC1 - 1; ++k) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
-                    wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
-                    wna[k % KC1][v] = zero_hist ? 0.f : sU[NRTP + seg * NSTEP + k][lv * V + v];
+                    wnm[k % KC1][v] = zero_hist ? 0.f : (hist_bf ? hwm[k][v] : su(seg * NSTEP + k, lv * V + v));
+                    wna[k % KC1][v] = zero_hist ? 0.f : (hist_bf ? hwa[k][v] : su(NRTP + seg * NSTEP + k, lv * V + v));
                 }
             }
 #pragma unroll
@@ -264,8 +293,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                 gbits[i] = 0;
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
-                    wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
-                    wna[(i + HALO) % KC1][v] = sU[NRTP + seg * NSTEP + i + HALO][lv * V + v];
+                    wnm[(i + HALO) % KC1][v] = su(seg * NSTEP + i + HALO, lv * V + v);
+                    wna[(i + HALO) % KC1][v] = su(NRTP + seg * NSTEP + i + HALO, lv * V + v);
                 }
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
@@ -501,10 +530,12 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         // ---- replay from the true state, clamp, store.  Addresses are a wave-uniform base plus a
         //      32-bit offset; a tile that lies wholly inside the tensor stores without per-row checks.
         {
-            float *zre = a.z_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)T.lb * JB;
-            float *zim = a.z_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)T.lb * JB;
+            constexpr uint32_t ES = BF ? 2u : 4u;          // bytes per output element
+            const size_t obase = ((size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)T.lb * JB) * ES;
+            float *zre = reinterpret_cast<float *>(reinterpret_cast<char *>(a.z_re) + obase);
+            float *zim = reinterpret_cast<float *>(reinterpret_cast<char *>(a.z_im) + obase);
             const uint32_t ost32 = (uint32_t)a.ost;
-            uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * 4u;   // bytes
+            uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * ES;   // bytes
             const bool full = (tt + 1) * TILE_T <= a.L && (T.lb + 1) * JB <= a.J;
             const bool plain = full && !(a.state_out && tt == a.nT - 1);   // no per-row checks at all
             auto replay = [&](auto plain_c) {
@@ -531,14 +562,19 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                         zi[v] = clampf(ni, a.out_clamp);
                     }
                     if (PLAIN || (active && t < a.L)) {
-                        Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + off), zr);
-                        Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + off), zi);
+                        if constexpr (BF) {
+                            *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off) = to_bf16(zr[0]);
+                            *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + off) = to_bf16(zi[0]);
+                        } else {
+                            Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + off), zr);
+                            Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + off), zi);
+                        }
                     }
                     if (!PLAIN && t == a.L - 1 && a.state_out && active) {
                         Vec<V>::st(a.state_out + ((size_t)b * 2 + 0) * a.J + j0, Sr);
                         Vec<V>::st(a.state_out + ((size_t)b * 2 + 1) * a.J + j0, Si);
                     }
-                    off += ost32 * 4u;
+                    off += ost32 * ES;
                 }
             };
             // What is still in flight ahead of this tile's output stores must be complete now: the next
@@ -565,8 +601,13 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                 for (int v = 0; v < V; ++v) vm[v] = va[v] = 0.f;
                 if (t >= 0) {
                     const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + j0;
-                    Vec<V>::ld(vm, a.mag + off);
-                    Vec<V>::ld(va, a.ang + off);
+                    if constexpr (BF) {
+                        vm[0] = from_bf16(reinterpret_cast<const uint16_t *>(a.mag)[off]);
+                        va[0] = from_bf16(reinterpret_cast<const uint16_t *>(a.ang)[off]);
+                    } else {
+                        Vec<V>::ld(vm, a.mag + off);
+                        Vec<V>::ld(va, a.ang + off);
+                    }
                 } else if (tail_in) {
                     const size_t off = ((size_t)(b * HALO + (t + HALO)) * 2) * a.J + j0;
                     Vec<V>::ld(vm, tail_in + off);
@@ -642,7 +683,8 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
     const int W = (a.J + 31) >> 5;
     for (int t = 0; t < a.L; ++t) {
         const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + jc;
-        const float um = a.mag[off], ua = a.ang[off];
+        const float um = a.bf16 ? from_bf16(reinterpret_cast<const uint16_t *>(a.mag)[off]) : a.mag[off];
+        const float ua = a.bf16 ? from_bf16(reinterpret_cast<const uint16_t *>(a.ang)[off]) : a.ang[off];
         float zm, xm, phi;
         if (KC > 0) {
             zm = bm;
@@ -692,8 +734,13 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
         Si = ni;
         if (active) {
             const size_t o = (size_t)b * a.osb + (size_t)t * a.ost + j;
-            a.z_re[o] = clampf(nr, a.out_clamp);
-            a.z_im[o] = clampf(ni, a.out_clamp);
+            if (a.bf16) {
+                reinterpret_cast<uint16_t *>(a.z_re)[o] = to_bf16(clampf(nr, a.out_clamp));
+                reinterpret_cast<uint16_t *>(a.z_im)[o] = to_bf16(clampf(ni, a.out_clamp));
+            } else {
+                a.z_re[o] = clampf(nr, a.out_clamp);
+                a.z_im[o] = clampf(ni, a.out_clamp);
+            }
         }
         if (a.mask) {   // bit j%32 of word j/32: one ballot covers two words
             const unsigned long long bal = __ballot(g && active);
@@ -730,7 +777,7 @@ static hipError_t launch_step(const FwdArgs &a, int conv_k, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int V, int KC, bool VALVE, bool RET>
+template <int V, int KC, bool VALVE, bool RET, bool BF>
 static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
 {
     // persistent grid: what fits on the chip (asked once per kernel)
@@ -739,7 +786,7 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC, VALVE, RET>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC, VALVE, RET, BF>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
@@ -749,21 +796,26 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     const long long tiles = (long long)a.nLB * a.B * a.nT;
     const long long wgs = tiles < resident ? (tiles > 0 ? tiles : 1) : resident;
     dim3 grid((unsigned)wgs), block(FwdGeom::NSEG * FwdLPR);
-    hipLaunchKernelGGL((fwd_kernel<V, KC, VALVE, RET>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((fwd_kernel<V, KC, VALVE, RET, BF>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
+template <int V, bool VALVE, bool RET, bool BF>
+static hipError_t launch_fwd_vmb(const FwdArgs &a, int conv_k, hipStream_t s)
+{
+    switch (conv_k) {
+    case 0: return launch_fwd_vk<V, 0, VALVE, RET, BF>(a, s);
+    case 1: return launch_fwd_vk<V, 1, VALVE, RET, BF>(a, s);
+    case 2: return launch_fwd_vk<V, 2, VALVE, RET, BF>(a, s);
+    case 3: return launch_fwd_vk<V, 3, VALVE, RET, BF>(a, s);
+    case 4: return launch_fwd_vk<V, 4, VALVE, RET, BF>(a, s);
+    default: return hipErrorInvalidValue;
+    }
+}
 template <int V, bool VALVE, bool RET>
 static hipError_t launch_fwd_vm(const FwdArgs &a, int conv_k, hipStream_t s)
 {
-    switch (conv_k) {
-    case 0: return launch_fwd_vk<V, 0, VALVE, RET>(a, s);
-    case 1: return launch_fwd_vk<V, 1, VALVE, RET>(a, s);
-    case 2: return launch_fwd_vk<V, 2, VALVE, RET>(a, s);
-    case 3: return launch_fwd_vk<V, 3, VALVE, RET>(a, s);
-    case 4: return launch_fwd_vk<V, 4, VALVE, RET>(a, s);
-    default: return hipErrorInvalidValue;
-    }
+    return a.bf16 ? launch_fwd_vmb<V, VALVE, RET, true>(a, conv_k, s) : launch_fwd_vmb<V, VALVE, RET, false>(a, conv_k, s);
 }
 
 template <int V>

@@ -146,6 +146,9 @@ struct FwdArgs {
     // aggregate has a third chained word, the product of the tile's retentions: aggp [tile][JB]
     const float *ret;            // null: ret_mode 0
     tagged_t *aggp;
+    // activations are bfloat16 in memory (mag, ang, z_re, z_im then point to 2-byte elements; strides
+    // are in elements); J and the strides are even
+    int bf16;
 };
 
 struct BwdArgs {
@@ -193,6 +196,14 @@ hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s);
 #if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
 // ------------------------------------------------------------------------------ device helpers
 __device__ __forceinline__ float clampf(float v, float c) { return __builtin_amdgcn_fmed3f(v, -c, c); }
+
+// bfloat16 in memory: the upper half of an fp32; to bf16 with the hardware's round-to-nearest-even.
+__device__ __forceinline__ float from_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ uint16_t to_bf16(float x)
+{
+    const __bf16 h = (__bf16)x;
+    return __builtin_bit_cast(uint16_t, h);
+}
 
 // sigmoid(z) with the hardware exp2 / reciprocal (both ~1 ulp).
 __device__ __forceinline__ float sigmoid_fast(float z)

@@ -187,3 +187,81 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
         if v is not None:
             out[k] = v.cpu().numpy()
     return out
+
+
+# ---------------------------------------------------------------- bfloat16 activations
+def to_bf16(x):
+    """float32 array -> uint16 bfloat16 bit patterns, round to nearest even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = ((u >> 16) & 1) + np.uint32(0x7FFF)
+    return ((u + r) >> 16).astype(np.uint16)
+
+
+def from_bf16(h):
+    return (np.asarray(h, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def bf16_exact(x):
+    """float32 array rounded to values bfloat16 holds exactly."""
+    return from_bf16(to_bf16(x))
+
+
+def dev_bf16(a):
+    """float32 numpy array of bf16-exact values -> torch.bfloat16 device tensor."""
+    return torch.from_numpy(to_bf16(a).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def host_bf16(t):
+    return from_bf16(t.view(torch.int16).cpu().numpy().view(np.uint16))
+
+
+def bf16_err(gpu, ora, tol=1e-4):
+    """Worst excess over the bar for an output stored as bfloat16: the kernel's fp32 value may differ from
+    the oracle by tol (rms-floored, as everywhere) and is then rounded to nearest: bf16 keeps 8 significant
+    bits, so half a unit in the last place is at most 2^-8 relative.  Returns max(|gpu - ora| / bound); <= 1 passes."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ora = np.asarray(ora, dtype=np.float64)
+    if ora.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ora * ora)))
+    den = np.maximum(np.abs(ora), max(rms, 1e-30))
+    bound = 2.0 ** -8 * np.abs(ora) * (1 + tol) + tol * den * (1 + 2.0 ** -8)
+    return float(np.max(np.abs(gpu - ora) / bound))
+
+
+def run_fwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, state_in=None, valve=None, ret=None,
+                 ret_bias=None, want_ckpt=False, concat=False, valve_eps=0.001):
+    """Forward with bfloat16 activations; inp["mag"], inp["ang"] hold bf16-exact float32 values.
+    Returns z_re, z_im as float32 (widened from what the kernel stored), state_out, mask."""
+    J = H * F
+    d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau,
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps, ret_mode=0 if ret is None else 1)
+    mag, ang = dev_bf16(inp["mag"][:, :L]), dev_bf16(inp["ang"][:, :L])
+    gamma, theta = dev(inp.get("gamma")), dev(inp["theta"])
+    cw = dev(inp["conv_w"]) if conv_k > 0 else None
+    cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
+    if concat:
+        z = torch.full((B, max(L, 1), 2 * J), float("nan"), device=DEV, dtype=torch.bfloat16)
+        z_re, z_im = z[:, :, :J], z[:, :, J:]
+        d.out_stride_t, d.out_stride_b = 2 * J, max(L, 1) * 2 * J
+    else:
+        z_re = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
+        z_im = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
+    nstate = K.cawn_state_bytes(d) // 4
+    st_in = dev(state_in) if state_in is not None else None
+    st_out = torch.full((nstate,), float("nan"), device=DEV)
+    W = (J + 31) // 32
+    mask = torch.zeros((B, max(L, 1), W), dtype=torch.int32, device=DEV)
+    ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV) if want_ckpt else None
+    ws = Workspaces.get(d)
+    vl = None if valve is None else dev(np.ascontiguousarray(valve[:, :L]))
+    rt = None if ret is None else dev(np.ascontiguousarray(ret[:, :L]))
+    K.check(K.cawn_phase_accumulate_bf16_fwd(d, mag, ang, vl, rt, dev(ret_bias), gamma, theta, cw, cb, st_in, z_re, z_im,
+                                             st_out, ckpt, mask, ws))
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    out = dict(z_re=host_bf16(z_re[:, :L].contiguous()), z_im=host_bf16(z_im[:, :L].contiguous()),
+               state_out=st_out.cpu().numpy(), mask=mask[:, :L].cpu().numpy().view(np.uint32))
+    if want_ckpt:
+        out["ckpt"] = ckpt.cpu().numpy()
+    return out

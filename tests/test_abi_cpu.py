@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "cawn.h")).read()
-    declared = sorted(set(re.findall(r"\b(cawn_[a-z_]+)\s*\(", hdr)))
+    declared = sorted(set(re.findall(r"\b(cawn_[a-z0-9_]+)\s*\(", hdr)))
     assert declared == sorted(K.EXPORTS)
     lib = K.lib()
     for name in declared:
@@ -149,21 +149,17 @@ def test_kernels_do_not_spill_and_keep_their_occupancy():
                 name = val.strip()
             elif name and ("fwd_kernel" in name or "bwd_kernel" in name or "step_kernel" in name):
                 if key.startswith("ScratchSize"):
-                    # the per-head valve variants of the backward kernel (last template argument
-                    # true) sit at the register budget: a few spilled values per tile are tolerated
-                    # (template arguments of bwd_kernel: V, conv taps, PARAM, VALVE, RET)
-                    valve_bwd = "bwd_kernel" in name and re.search(r"ELb1ELb[01]EEEvNS_7BwdArgsE$", name) is not None
-                    # the data-dependent-retention variants of the backward kernel keep a retention
-                    # per token-lane on top of that: up to 128 bytes
-                    ret_bwd = "bwd_kernel" in name and name.endswith("ELb1EEEvNS_7BwdArgsE")
-                    if ret_bwd:
-                        assert int(val) <= 128, (name, line)
-                        seen += 1
-                        continue
-                    # the data-dependent-retention variants of the forward kernel (last template
-                    # argument true) keep 32 more values per thread: the same allowance
-                    ret_fwd = "fwd_kernel" in name and name.endswith("ELb1EEEvNS_7FwdArgsE")
-                    assert int(val) <= (64 if valve_bwd or ret_fwd else 0), (name, line)
+                    # boolean template arguments: forward (VALVE, RET, BF), backward (PARAM, VALVE, RET[, BF])
+                    flags = [f == "1" for f in re.findall(r"Lb([01])E", name)]
+                    allowed = 0
+                    if "fwd_kernel" in name and flags[1]:
+                        allowed = 64      # data-dependent retention keeps 32 more values per thread
+                    if "bwd_kernel" in name:
+                        # the per-head valve variants sit at the register budget: a few spilled values
+                        # per tile are tolerated; the retention variants keep a retention per token-lane
+                        # on top of that
+                        allowed = 128 if flags[2] else (64 if flags[1] else 0)
+                    assert int(val) <= allowed, (name, line)
                     seen += 1
                 elif key.startswith("Occupancy"):
                     want = 4 if "bwd_kernel" in name else 2

@@ -1,0 +1,130 @@
+"""GPU parity with bfloat16 activations in memory (the paper's precision split, Sec. 3.5 / Sec. 6.1:
+bf16 network, fp32 accumulator) against the fp64 oracle on the same bf16-exact inputs, through the C
+ABI.  Outputs stored as bf16 are allowed the rounding to nearest on top of the usual 1e-4; everything
+that stays fp32 (state, checkpoints, parameter gradients) keeps the 1e-4 bar; gate masks bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import cawn_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+def _inputs(B, L, H, F, Kc, seed):
+    G = _gpu()
+    r = np.random.Generator(np.random.PCG64(seed))
+    J = H * F
+    d = dict(mag=G.bf16_exact(r.standard_normal((B, L, J), dtype=np.float32)),
+             ang=G.bf16_exact(r.standard_normal((B, L, J), dtype=np.float32)),
+             gamma=r.uniform(0.9, 0.999, J).astype(np.float32),
+             theta=r.uniform(0, np.pi, J).astype(np.float32),
+             valve=(-3.9 + 3.0 * r.standard_normal((B, L, H))).astype(np.float32),
+             ret=(1.0 + 1.5 * r.standard_normal((B, L, H))).astype(np.float32),
+             ret_bias=np.linspace(3.0, 0.0, F).astype(np.float32),
+             dz_re=G.bf16_exact(r.standard_normal((B, L, J), dtype=np.float32)),
+             dz_im=G.bf16_exact(r.standard_normal((B, L, J), dtype=np.float32)))
+    kk = max(Kc, 1)
+    d["conv_w"] = (r.standard_normal((2, J, kk)) / np.sqrt(kk)).astype(np.float32)
+    d["conv_b"] = (0.1 * r.standard_normal((2, J))).astype(np.float32)
+    return d
+
+
+def _check_fwd(B, L, H, F, Kc, d, amp_mode=0, valve=False, ret=False, tau=0.0, state=None, **kw):
+    G = _gpu()
+    J = H * F
+    scan_in = tail_in = blob = None
+    if state is not None:
+        scan_in, tail_in = state
+        blob = G.pack_state(scan_in, tail_in if Kc > 1 else None)
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_mode=1 if valve else 0, gate_tau=tau,
+                ret_mode=1 if ret else 0)
+    ora = O.phase_fwd(cfg, d["mag"][:, :L], d["ang"][:, :L], None if ret else d["gamma"], d["theta"],
+                      conv_w=d["conv_w"], conv_b=d["conv_b"], valve=d["valve"][:, :L] if valve else None,
+                      ret=d["ret"][:, :L] if ret else None, ret_bias=d["ret_bias"] if ret else None,
+                      scan_in=None if scan_in is None else scan_in.astype(np.float64),
+                      tail_in=tail_in if Kc > 1 else None)
+    out = G.run_fwd_bf16(d, B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, state_in=blob,
+                         valve=d["valve"] if valve else None, ret=d["ret"] if ret else None,
+                         ret_bias=d["ret_bias"] if ret else None, **kw)
+    e = max(G.bf16_err(out["z_re"], ora["z_re"]), G.bf16_err(out["z_im"], ora["z_im"]))
+    assert e <= 1.0, e
+    assert np.array_equal(out["mask"], G.mask_from_gate(ora["gate"])), "gate mask differs"
+    scan, tail = G.unpack_state(out["state_out"], B, J, Kc)
+    assert G.rel_err(scan, ora["scan_out"]) <= TOL               # the carried state stays fp32
+    if Kc > 1:
+        assert np.array_equal(tail, ora["tail_out"])
+    return out, ora
+
+
+def test_bf16_helpers_round_to_nearest_even():
+    G = _gpu()
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.0e38, 1e-40, 0.0], np.float32)
+    # 1 + 2^-8 lies halfway between 1 and 1 + 2^-7: ties go to the even mantissa (1.0);
+    # 1 + 3 * 2^-8 lies halfway between 1 + 2^-7 and 1 + 2^-6: the even one is 1 + 2^-6
+    got = G.bf16_exact(x)
+    assert got[0] == 1.0 and got[1] == 1.0 and got[2] == 1.015625 and got[3] == -2.5 and got[6] == 0.0
+    assert abs(float(got[4]) / float(x[4]) - 1) <= 2.0 ** -8
+
+
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (1, 128), (5, 32)])
+@pytest.mark.parametrize("Kc", [0, 4])
+def test_bf16_forward_head_widths(H, F, Kc):
+    B, L = 2, 700                      # three forward tiles, ragged tail
+    d = _inputs(B, L, H, F, Kc, 7700 + H * 131 + F + Kc)
+    out, ora = _check_fwd(B, L, H, F, Kc, d, tau=0.25)
+    # the outputs really are bf16 values
+    G = _gpu()
+    assert np.array_equal(out["z_re"], G.bf16_exact(out["z_re"]))
+
+
+@pytest.mark.parametrize("valve,ret", [(True, False), (False, True), (True, True)])
+@pytest.mark.parametrize("Kc", [0, 3])
+def test_bf16_forward_valve_and_retention(valve, ret, Kc):
+    B, L, H, F = 2, 600, 3, 64
+    d = _inputs(B, L, H, F, Kc, 7900 + Kc + 2 * valve + 4 * ret)
+    _check_fwd(B, L, H, F, Kc, d, amp_mode=1, valve=valve, ret=ret)
+
+
+@pytest.mark.parametrize("L", [1, 5, 16, 17, 255, 256, 257, 515])
+def test_bf16_forward_lengths_with_carried_state(L):
+    B, H, F, Kc = 3, 2, 64, 4
+    d = _inputs(B, 520, H, F, Kc, 8100 + L)
+    r = np.random.Generator(np.random.PCG64(8))
+    state = (r.standard_normal((B, 2, H * F)).astype(np.float32),
+             r.standard_normal((B, Kc - 1, 2, H * F)).astype(np.float32))
+    _check_fwd(B, L, H, F, Kc, d, state=state)
+
+
+def test_bf16_forward_chunked_state_and_concat_layout():
+    G = _gpu()
+    B, L, H, F, Kc = 2, 1000, 2, 64, 4
+    J = H * F
+    d = _inputs(B, L, H, F, Kc, 8200)
+    one, ora = _check_fwd(B, L, H, F, Kc, d, concat=True)
+    blob = None
+    zs = []
+    for lo, hi in ((0, 300), (300, 310), (310, 1000)):     # a long, a short (step kernel) and a long call
+        part = {k: (v[:, lo:hi] if k in ("mag", "ang") else v) for k, v in d.items()}
+        o = G.run_fwd_bf16(part, B, hi - lo, H, F, conv_k=Kc, state_in=blob)
+        blob = o["state_out"]
+        zs.append(o["z_re"])
+    z = np.concatenate(zs, axis=1)
+    assert G.bf16_err(z, ora["z_re"]) <= 1.0
+    assert G.rel_err(G.unpack_state(blob, B, J, Kc)[0], ora["scan_out"]) <= TOL
+
+
+def test_bf16_odd_lane_count_is_refused():
+    import torch
+    from paper_2604_04250_amd import binding as K
+    x = torch.zeros(64, device="cuda:0")
+    h = torch.zeros(64, device="cuda:0", dtype=torch.bfloat16)
+    d = K.make_desc(1, 32, 1, 7)
+    assert K.cawn_phase_accumulate_bf16_fwd(d, h, h, None, None, None, x, x, None, None, None, h, h, None, None, None,
+                                            K.alloc_workspace(d)) == K.CAWN_EUNSUPPORTED
