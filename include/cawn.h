@@ -247,6 +247,24 @@ int cawn_phase_accumulate_bf16_fwd(const cawn_desc *d, const uint16_t *mag, cons
                                    uint16_t *z_im, void *state_out, void *ckpt, uint32_t *gate_mask,
                                    void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Backward of cawn_phase_accumulate_bf16_fwd: mag, ang, dz_re, dz_im are read and dmag, dang are
+ * written as bfloat16 (rounded to nearest even); every other gradient, the state gradients and
+ * the checkpoints are fp32.  Streams and gradients that the descriptor's modes do not use are
+ * ignored and may be NULL (dgamma with ret_mode 1, dvalve without gate_mode 1, dret without
+ * ret_mode 1).  The conv history inside state_in is fp32 as in every other call.  Everything else
+ * as in cawn_phase_accumulate_bwd / _valve_bwd / _ret_bwd.
+ */
+int cawn_phase_accumulate_bf16_bwd(const cawn_desc *d, const uint16_t *mag, const uint16_t *ang,
+                                   const float *valve, const float *ret, const float *ret_bias,
+                                   const float *gamma, const float *theta, const float *conv_w,
+                                   const float *conv_b, const void *state_in, const void *ckpt,
+                                   const uint16_t *dz_re, const uint16_t *dz_im,
+                                   const void *dstate_out, uint16_t *dmag, uint16_t *dang,
+                                   float *dvalve, float *dret, float *dgamma, float *dtheta,
+                                   float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

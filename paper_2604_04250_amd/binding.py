@@ -20,7 +20,7 @@ CAWN_OK, CAWN_EINVAL, CAWN_EUNSUPPORTED, CAWN_EWORKSPACE, CAWN_ELAUNCH, CAWN_ETI
 EXPORTS = ["cawn_state_bytes", "cawn_workspace_bytes", "cawn_ckpt_bytes", "cawn_tile_len",
            "cawn_status_string", "cawn_workspace_init", "cawn_workspace_status", "cawn_set_spin_limit",
            "cawn_theta_init", "cawn_syntax_conv", "cawn_phase_accumulate_fwd",
-           "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_bf16_fwd", "cawn_phase_accumulate_ret_bwd", "cawn_phase_accumulate_ret_fwd",
+           "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_bf16_bwd", "cawn_phase_accumulate_bf16_fwd", "cawn_phase_accumulate_ret_bwd", "cawn_phase_accumulate_ret_fwd",
            "cawn_phase_accumulate_valve_fwd",
            "cawn_phase_accumulate_valve_bwd"]
 
@@ -85,6 +85,8 @@ def lib() -> C.CDLL:
         L.cawn_phase_accumulate_ret_bwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 22 +
                                                     [C.c_size_t, C.c_void_p])
         L.cawn_phase_accumulate_bf16_fwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 16 +
+                                                     [C.c_size_t, C.c_void_p])
+        L.cawn_phase_accumulate_bf16_bwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 24 +
                                                      [C.c_size_t, C.c_void_p])
         _lib = L
     return _lib
@@ -221,6 +223,18 @@ def cawn_phase_accumulate_bf16_fwd(d, mag, ang, valve, ret, ret_bias, gamma, the
         C.byref(d), _ptr(mag), _ptr(ang), _ptr(valve), _ptr(ret), _ptr(ret_bias), _ptr(gamma), _ptr(theta),
         _ptr(conv_w), _ptr(conv_b), _ptr(state_in), _ptr(z_re), _ptr(z_im), _ptr(state_out), _ptr(ckpt),
         _ptr(gate_mask), _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(stream))
+
+
+def cawn_phase_accumulate_bf16_bwd(d, mag, ang, valve, ret, ret_bias, gamma, theta, conv_w, conv_b, state_in, ckpt,
+                                   dz_re, dz_im, dstate_out, dmag, dang, dvalve, dret, dgamma, dtheta, dconv_w,
+                                   dconv_b, dstate_in, workspace, stream=None) -> int:
+    """mag, ang, dz_re, dz_im, dmag, dang: torch.bfloat16 tensors."""
+    return lib().cawn_phase_accumulate_bf16_bwd(
+        C.byref(d), _ptr(mag), _ptr(ang), _ptr(valve), _ptr(ret), _ptr(ret_bias), _ptr(gamma), _ptr(theta),
+        _ptr(conv_w), _ptr(conv_b), _ptr(state_in), _ptr(ckpt), _ptr(dz_re), _ptr(dz_im), _ptr(dstate_out),
+        _ptr(dmag), _ptr(dang), _ptr(dvalve), _ptr(dret), _ptr(dgamma), _ptr(dtheta), _ptr(dconv_w),
+        _ptr(dconv_b), _ptr(dstate_in), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(stream))
 
 

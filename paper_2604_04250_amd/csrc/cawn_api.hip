@@ -642,7 +642,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
                     const void *state_in, const void *ckpt, const float *dz_re, const float *dz_im,
                     const void *dstate_out, float *dmag, float *dang, float *dvalve, float *dret, float *dgamma,
                     float *dtheta, float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
-                    size_t workspace_bytes, void *stream)
+                    size_t workspace_bytes, void *stream, bool bf16 = false)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
     if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
@@ -683,8 +683,11 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
     if (ist > (1ll << 21) || ost > (1ll << 21)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
+    // bf16 rows are staged as four-byte words: an even number of lanes, even strides, aligned rows
+    if (bf16 && (J % 2 || ist % 2 || isb % 2 || !aligned(mag, 4) || !aligned(ang, 4))) return CAWN_EUNSUPPORTED;
 
     BwdArgs a{};
+    a.bf16 = bf16 ? 1 : 0;
     if (d->gate_mode == 1) {
         const float INF = std::numeric_limits<float>::infinity();
         a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
@@ -735,6 +738,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.small_angle = (kc > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;
     a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&
                  (!state_in || aligned(state_in, 16))) ? 1 : 0;
+    if (bf16) a.stage16 = (J % 8 == 0 && ist % 8 == 0 && isb % 8 == 0 && aligned(mag, 16) && aligned(ang, 16)) ? 1 : 0;
     a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
     a.conv_clamp = d->conv_clamp; a.grad_clamp = d->grad_clamp;
     a.spin_limit = g_spin_limit.load();
@@ -806,6 +810,25 @@ int cawn_phase_accumulate_bf16_fwd(const cawn_desc *d, const uint16_t *mag, cons
                     d->ret_mode == 1 ? ret_bias : nullptr, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
                     state_in, reinterpret_cast<float *>(z_re), reinterpret_cast<float *>(z_im), state_out, ckpt,
                     gate_mask, workspace, workspace_bytes, stream, true);
+}
+
+int cawn_phase_accumulate_bf16_bwd(const cawn_desc *d, const uint16_t *mag, const uint16_t *ang, const float *valve,
+                                   const float *ret, const float *ret_bias, const float *gamma, const float *theta,
+                                   const float *conv_w, const float *conv_b, const void *state_in, const void *ckpt,
+                                   const uint16_t *dz_re, const uint16_t *dz_im, const void *dstate_out, uint16_t *dmag,
+                                   uint16_t *dang, float *dvalve, float *dret, float *dgamma, float *dtheta,
+                                   float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    const bool valved = d->gate_mode == 1, rmode = d->ret_mode == 1;
+    return bwd_impl(d, reinterpret_cast<const float *>(mag), reinterpret_cast<const float *>(ang),
+                    valved ? valve : nullptr, rmode ? ret : nullptr, rmode ? ret_bias : nullptr,
+                    rmode ? nullptr : gamma, theta, conv_w, conv_b, state_in, ckpt,
+                    reinterpret_cast<const float *>(dz_re), reinterpret_cast<const float *>(dz_im), dstate_out,
+                    reinterpret_cast<float *>(dmag), reinterpret_cast<float *>(dang), valved ? dvalve : nullptr,
+                    rmode ? dret : nullptr, rmode ? nullptr : dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace,
+                    workspace_bytes, stream, true);
 }
 
 int cawn_phase_accumulate_ret_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *valve,

@@ -103,9 +103,11 @@ __device__ __forceinline__ bool head_sum_lane(int lv, int vwidth)
 // its neighbour's retention) and, beside each aggregate, the real product of the run's retentions; the
 // lane table holds pure rotations.  The logit's gradient needs S[t-1], so these kernels always rebuild
 // the forward state (PARAM).
-template <int V, int KC, bool PARAM, bool VALVE, bool RET>
+// BF: activations (mag, ang, dz_re, dz_im in; dmag, dang out) are bfloat16 in memory, as in the forward.
+template <int V, int KC, bool PARAM, bool VALVE, bool RET, bool BF>
 __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
+    static_assert(!BF || V == 1, "bf16 activations: one lane per thread");
     static_assert(!RET || (PARAM && V == 1), "retention kernels rebuild the forward state; one lane per thread");
     // The valve and retention kernels sit at the register budget.  They keep the reduced angle instead
     // of its sin and cos between the front-end and the reverse pass, park the conv taps in LDS during
@@ -118,13 +120,20 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     constexpr int KC1 = KC > 0 ? KC : 1;
     constexpr int ROWS = 4 + 2 * KC;
     constexpr int NT = NSEG * LPR, NW = NT / 64;
-    constexpr int NRTP = staged_rows<TILE_T, JB, HALO>();   // staged rows per stream: time tile_t0-HALO+rr
+    constexpr int JBS = BF ? JB / 2 : JB;          // four-byte words per staged row
+    constexpr uint32_t ES = BF ? 2u : 4u;          // bytes per activation element
+    constexpr int NRTP = staged_rows<TILE_T, JBS, HALO>();   // staged rows per stream: time tile_t0-HALO+rr
     static_assert(HALO <= NSTEP, "conv halo must fit in one segment");
     static_assert(!VALVE || V == 1, "the valve's lane reduction takes one lane per thread");
     static_assert(LPR == 32, "the partial-sum reduction pairs the two segments of a wave");
     static_assert(JB <= 64 && 64 % JB == 0, "a staged row must fit a wave");
 
-    __shared__ __attribute__((aligned(16))) float sU[2 * NRTP][JB];   // [stream*NRTP + rr][lane]
+    __shared__ __attribute__((aligned(16))) float sU[2 * NRTP][JBS];  // [stream*NRTP + rr][lane]
+    // element (row, lane) of the staged rows as fp32
+    auto su = [&](int r, int l) -> float {
+        if constexpr (BF) return from_bf16(reinterpret_cast<const uint16_t *>(&sU[r][0])[l]);
+        else return sU[r][l];
+    };
     __shared__ float sEb[NSEG][2][JB];
     __shared__ float sEf[PARAM ? NSEG : 1][2][JB];
     __shared__ float sCarry[2][JB];
@@ -194,15 +203,20 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // a tile that lies wholly inside the tensors loads and stores without per-row checks
     const bool full = (tt + 1) * TILE_T <= a.L && (lb + 1) * JB <= a.J;
     {
-        const float *gre = a.dz_re + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
-        const float *gim = a.dz_im + (size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB;
-        uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * 4u;      // bytes
+        const size_t gbase = ((size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB) * ES;
+        const float *gre = reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.dz_re) + gbase);
+        const float *gim = reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.dz_im) + gbase);
+        uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * ES;      // bytes
+        auto ldg = [&](float (&d)[V], const float *ub, uint32_t bo) {
+            if constexpr (BF) d[0] = from_bf16(*reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(ub) + bo));
+            else ldu<V>(d, ub, bo);
+        };
         if (full) {
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
-                ldu<V>(dzr[i], gre, off);
-                ldu<V>(dzi[i], gim, off);
-                off += ost32 * 4u;
+                ldg(dzr[i], gre, off);
+                ldg(dzi[i], gim, off);
+                off += ost32 * ES;
             }
         } else {
 #pragma unroll
@@ -210,10 +224,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
                 for (int v = 0; v < V; ++v) dzr[i][v] = dzi[i][v] = 0.f;
                 if (active && t0 + i < a.L) {
-                    ldu<V>(dzr[i], gre, off);
-                    ldu<V>(dzi[i], gim, off);
+                    ldg(dzr[i], gre, off);
+                    ldg(dzi[i], gim, off);
                 }
-                off += ost32 * 4u;
+                off += ost32 * ES;
             }
         }
     }
@@ -265,12 +279,13 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 
     // ---- the tile's input rows go to LDS (needed from the front-end on; issued after the loads the
     //      local adjoint waits for, so that it does not wait for these as well)
+    // (bf16: rows of J/2 words at half the strides; the fp32 conv history is read at its points of use)
     if (a.stage16)
-        stage_rows<TILE_T, JB, HALO, 16>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
-                                 NW, lane);
+        stage_rows<TILE_T, JBS, HALO, 16>(&sU[0][0], a.mag, a.ang, BF ? nullptr : tail_in, b, tt * TILE_T, lb, BF ? a.J / 2 : a.J,
+                                  a.L, BF ? a.isb / 2 : a.isb, BF ? (int)a.ist / 2 : (int)a.ist, wave, NW, lane);
     else
-        stage_rows<TILE_T, JB, HALO, 4>(&sU[0][0], a.mag, a.ang, tail_in, b, tt * TILE_T, lb, a.J, a.L, a.isb, (int)a.ist, wave,
-                                NW, lane);
+        stage_rows<TILE_T, JBS, HALO, 4>(&sU[0][0], a.mag, a.ang, BF ? nullptr : tail_in, b, tt * TILE_T, lb, BF ? a.J / 2 : a.J,
+                                 a.L, BF ? a.isb / 2 : a.isb, BF ? (int)a.ist / 2 : (int)a.ist, wave, NW, lane);
 
     if (VALVE && wave == 0) stage_valve<TILE_T, JB>(&sV[0], a.valve, b, tt * TILE_T, lb, a.L, a.H, a.F, a.gpb, lane);
 
@@ -417,6 +432,12 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];      // forward state before each token
     float Efr[V], Efi[V];
     const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
+    // bf16: the carried conv history is fp32 and is not staged; the one segment that needs it reads it
+    // where it uses it (and waits for it there, so that no wait for it lands in the common path)
+    const bool hist_bf = BF && HALO > 0 && tail_in && tt == 0 && seg == 0;
+    auto hist_row = [&](int k, int sidx) -> float {
+        return tail_in[((size_t)(b * HALO + k) * 2 + sidx) * a.J + (active ? j0 : 0)];
+    };
     // The mode switches are uniform over the launch; each combination gets its own straight-line
     // copy of the loop, so that the tokens' dependent chains (exp -> rcp -> sin/cos) interleave.
     auto front_end = [&](auto amp_c, auto small_c) {
@@ -428,9 +449,17 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         for (int k = 0; k < KC1 - 1; ++k) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                wnm[k % KC1][v] = zero_hist ? 0.f : sU[seg * NSTEP + k][lv * V + v];
-                wna[k % KC1][v] = zero_hist ? 0.f : sU[NRTP + seg * NSTEP + k][lv * V + v];
+                wnm[k % KC1][v] = zero_hist ? 0.f : su(seg * NSTEP + k, lv * V + v);
+                wna[k % KC1][v] = zero_hist ? 0.f : su(NRTP + seg * NSTEP + k, lv * V + v);
             }
+        }
+        if (BF && hist_bf) {
+#pragma unroll
+            for (int k = 0; k < KC1 - 1; ++k) {
+                wnm[k % KC1][0] = hist_row(k, 0);
+                wna[k % KC1][0] = hist_row(k, 1);
+            }
+            wait_vm<0>();
         }
 #pragma unroll
         for (int v = 0; v < V; ++v) Efr[v] = Efi[v] = 0.f;
@@ -438,8 +467,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         for (int i = 0; i < NSTEP; ++i) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                wnm[(i + HALO) % KC1][v] = sU[seg * NSTEP + i + HALO][lv * V + v];
-                wna[(i + HALO) % KC1][v] = sU[NRTP + seg * NSTEP + i + HALO][lv * V + v];
+                wnm[(i + HALO) % KC1][v] = su(seg * NSTEP + i + HALO, lv * V + v);
+                wna[(i + HALO) % KC1][v] = su(NRTP + seg * NSTEP + i + HALO, lv * V + v);
             }
 #pragma unroll
             for (int v = 0; v < V; ++v) {
@@ -742,25 +771,30 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         BVec<V>::st(a.dstate_in + ((size_t)b * 2 + 1) * a.J + j0, xi);
     }
 
-    float *omag = a.dmag + (size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB;
-    float *oang = a.dang + (size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB;
-    uint32_t ooff = ((uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V)) * 4u;      // bytes
+    const size_t dbase = ((size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB) * ES;
+    float *omag = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dmag) + dbase);
+    float *oang = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dang) + dbase);
+    uint32_t ooff = ((uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V)) * ES;      // bytes
+    auto sto = [&](float *ub, uint32_t bo, const float (&x)[V]) {
+        if constexpr (BF) *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(ub) + bo) = to_bf16(x[0]);
+        else stu<V>(ub, bo, x);
+    };
     if (KC == 0) {
         if (full) {
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
-                stu<V>(omag, ooff, dzr[i]);
-                stu<V>(oang, ooff, dzi[i]);
-                ooff += ist32 * 4u;
+                sto(omag, ooff, dzr[i]);
+                sto(oang, ooff, dzi[i]);
+                ooff += ist32 * ES;
             }
         } else {
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
                 if (active && t0 + i < a.L) {
-                    stu<V>(omag, ooff, dzr[i]);
-                    stu<V>(oang, ooff, dzi[i]);
+                    sto(omag, ooff, dzr[i]);
+                    sto(oang, ooff, dzi[i]);
                 }
-                ooff += ist32 * 4u;
+                ooff += ist32 * ES;
             }
         }
     } else {
@@ -893,8 +927,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     da[v] = sa_;
                 }
                 if (PLAIN) {
-                    stu<V>(omag, ooff, dm);
-                    stu<V>(oang, ooff, da);
+                    sto(omag, ooff, dm);
+                    sto(oang, ooff, da);
                 } else if (active && t < a.L) {
                     if (HALO > 0 && dtail_out && t >= a.L - HALO) {   // state_out's history rows are copies of these inputs
                         const int r = t - (a.L - HALO);
@@ -905,10 +939,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
                         for (int v = 0; v < V; ++v) { dm[v] += xm_[v]; da[v] += xa_[v]; }
                     }
-                    stu<V>(omag, ooff, dm);
-                    stu<V>(oang, ooff, da);
+                    sto(omag, ooff, dm);
+                    sto(oang, ooff, da);
                 }
-                ooff += ist32 * 4u;
+                ooff += ist32 * ES;
             }
         };
         // Both paths end with every load complete, so that no wait for one of them can land behind
@@ -965,6 +999,17 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
         if (KC > 0) {
             const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;
+            float hm_[HALO1], ha_[HALO1];       // bf16: the fp32 history rows again (first segment of a call with history)
+#pragma unroll
+            for (int k = 0; k < HALO1; ++k) hm_[k] = ha_[k] = 0.f;
+            if (BF && hist_bf) {
+#pragma unroll
+                for (int k = 0; k < HALO; ++k) {
+                    hm_[k] = hist_row(k, 0);
+                    ha_[k] = hist_row(k, 1);
+                }
+                wait_vm<0>();
+            }
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i)
 #pragma unroll
@@ -974,8 +1019,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #pragma unroll
                     for (int k = 0; k < KC; ++k) {
                         const bool z = zero_hist && (i + k < HALO);
-                        const float um_ = z ? 0.f : sU[seg * NSTEP + i + k][lv * V + v];
-                        const float ua_ = z ? 0.f : sU[NRTP + seg * NSTEP + i + k][lv * V + v];
+                        const bool hrow = BF && hist_bf && (i + k < HALO);
+                        const float um_ = z ? 0.f : (hrow ? hm_[i + k < HALO ? i + k : 0] : su(seg * NSTEP + i + k, lv * V + v));
+                        const float ua_ = z ? 0.f : (hrow ? ha_[i + k < HALO ? i + k : 0] : su(NRTP + seg * NSTEP + i + k, lv * V + v));
                         part[4 + k][v] = __builtin_fmaf(dzr[i][v], um_, part[4 + k][v]);
                         part[4 + KC + k][v] = __builtin_fmaf(dzi[i][v], ua_, part[4 + KC + k][v]);
                     }
@@ -1036,7 +1082,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 }
 
 // Persistent grid: what fits on the chip at once (asked once per kernel), never more than tiles.
-template <int V, int KC, bool PARAM, bool VALVE, bool RET>
+template <int V, int KC, bool PARAM, bool VALVE, bool RET, bool BF>
 static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
 {
     static int per_cu = 0, cus = 0;
@@ -1044,26 +1090,33 @@ static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM, VALVE, RET>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM, VALVE, RET, BF>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
     }
     long long g = (long long)per_cu * cus;
     if (g > (long long)a.total_tiles) g = a.total_tiles;
-    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM, VALVE, RET>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
+    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM, VALVE, RET, BF>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
     return hipGetLastError();
 }
 
+template <int V, bool PARAM, bool VALVE, bool RET, bool BF>
+static hipError_t launch_bwd_vpb(const BwdArgs &a, int conv_k, hipStream_t s);
 template <int V, bool PARAM, bool VALVE, bool RET = false>
 static hipError_t launch_bwd_vp(const BwdArgs &a, int conv_k, hipStream_t s)
 {
+    return a.bf16 ? launch_bwd_vpb<V, PARAM, VALVE, RET, true>(a, conv_k, s) : launch_bwd_vpb<V, PARAM, VALVE, RET, false>(a, conv_k, s);
+}
+template <int V, bool PARAM, bool VALVE, bool RET, bool BF>
+static hipError_t launch_bwd_vpb(const BwdArgs &a, int conv_k, hipStream_t s)
+{
     switch (conv_k) {
-    case 0: return launch_bwd_vkp<V, 0, PARAM, VALVE, RET>(a, s);
-    case 1: return launch_bwd_vkp<V, 1, PARAM, VALVE, RET>(a, s);
-    case 2: return launch_bwd_vkp<V, 2, PARAM, VALVE, RET>(a, s);
-    case 3: return launch_bwd_vkp<V, 3, PARAM, VALVE, RET>(a, s);
-    case 4: return launch_bwd_vkp<V, 4, PARAM, VALVE, RET>(a, s);
+    case 0: return launch_bwd_vkp<V, 0, PARAM, VALVE, RET, BF>(a, s);
+    case 1: return launch_bwd_vkp<V, 1, PARAM, VALVE, RET, BF>(a, s);
+    case 2: return launch_bwd_vkp<V, 2, PARAM, VALVE, RET, BF>(a, s);
+    case 3: return launch_bwd_vkp<V, 3, PARAM, VALVE, RET, BF>(a, s);
+    case 4: return launch_bwd_vkp<V, 4, PARAM, VALVE, RET, BF>(a, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -185,6 +185,7 @@ struct BwdArgs {
     const float *ret;            // null: ret_mode 0
     float *rpart;                // null: no gradient of the retention logits wanted
     tagged_t *aggp;
+    int bf16;                    // activations (mag, ang, dz_*, dmag, dang) are bfloat16 in memory: see FwdArgs
 };
 
 // Number of per-lane partial sums a backward tile emits: dgamma, dtheta, dbias[2], dw[2][conv_k].

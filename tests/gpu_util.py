@@ -265,3 +265,54 @@ def run_fwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, state_in=N
     if want_ckpt:
         out["ckpt"] = ckpt.cpu().numpy()
     return out
+
+
+def run_fwd_bwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, grad_clamp=100.0, state_in=None,
+                     dstate_out=None, want_param=True, valve=None, ret=None, ret_bias=None, valve_eps=0.001):
+    """Forward (for the checkpoints) then backward, bfloat16 activations.  dmag, dang come back as float32
+    (widened from what the kernel stored); the other gradients are fp32."""
+    J = H * F
+    d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau, grad_clamp=grad_clamp,
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps, ret_mode=0 if ret is None else 1)
+    mag, ang = dev_bf16(inp["mag"][:, :L]), dev_bf16(inp["ang"][:, :L])
+    dz_re, dz_im = dev_bf16(inp["dz_re"][:, :L]), dev_bf16(inp["dz_im"][:, :L])
+    gamma, theta = dev(inp.get("gamma")), dev(inp["theta"])
+    cw = dev(inp["conv_w"]) if conv_k > 0 else None
+    cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
+    vl = None if valve is None else dev(np.ascontiguousarray(valve[:, :L]))
+    rt = None if ret is None else dev(np.ascontiguousarray(ret[:, :L]))
+    rb = dev(ret_bias)
+    z_re = torch.empty((B, max(L, 1), J), device=DEV, dtype=torch.bfloat16)
+    z_im = torch.empty((B, max(L, 1), J), device=DEV, dtype=torch.bfloat16)
+    st_in = dev(state_in)
+    ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
+    ws = Workspaces.get(d)
+    K.check(K.cawn_phase_accumulate_bf16_fwd(d, mag, ang, vl, rt, rb, gamma, theta, cw, cb, st_in, z_re, z_im, None, ckpt,
+                                             None, ws))
+    dmag = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
+    dang = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
+    nstate = K.cawn_state_bytes(d) // 4
+    nanv = lambda *shape: torch.full(shape, float("nan"), device=DEV)
+    dgamma = nanv(J) if want_param and ret is None else None
+    dtheta = nanv(J) if want_param else None
+    dcw = nanv(2, J, conv_k) if want_param and conv_k > 0 else None
+    dcb = nanv(2, J) if want_param and conv_k > 0 else None
+    dvalve = nanv(B, max(L, 1), H) if valve is not None else None
+    dret = nanv(B, max(L, 1), H) if ret is not None else None
+    dst_in = nanv(nstate)
+    d.lane_consts_cached = 1
+    K.check(K.cawn_phase_accumulate_bf16_bwd(d, mag, ang, vl, rt, rb, gamma, theta, cw, cb, st_in, ckpt, dz_re, dz_im,
+                                             dev(dstate_out), dmag, dang, dvalve, dret, dgamma, dtheta, dcw, dcb,
+                                             dst_in, ws))
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    out = dict(dmag=host_bf16(dmag[:, :L].contiguous()), dang=host_bf16(dang[:, :L].contiguous()),
+               dstate_in=dst_in.cpu().numpy())
+    for k, v in (("dgamma", dgamma), ("dtheta", dtheta), ("dconv_w", dcw), ("dconv_b", dcb)):
+        if v is not None:
+            out[k] = v.cpu().numpy()
+    if dvalve is not None:
+        out["dvalve"] = dvalve[:, :L].cpu().numpy()
+    if dret is not None:
+        out["dret"] = dret[:, :L].cpu().numpy()
+    return out

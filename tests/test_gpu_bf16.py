@@ -128,3 +128,73 @@ def test_bf16_odd_lane_count_is_refused():
     d = K.make_desc(1, 32, 1, 7)
     assert K.cawn_phase_accumulate_bf16_fwd(d, h, h, None, None, None, x, x, None, None, None, h, h, None, None, None,
                                             K.alloc_workspace(d)) == K.CAWN_EUNSUPPORTED
+
+
+def _check_bwd(B, L, H, F, Kc, d, amp_mode=0, valve=False, ret=False, tau=0.0, state=None, dstate=None, **kw):
+    G = _gpu()
+    J = H * F
+    scan_in = tail_in = blob = dblob = dscan = dtail = None
+    if state is not None:
+        scan_in, tail_in = state
+        blob = G.pack_state(scan_in, tail_in if Kc > 1 else None)
+    if dstate is not None:
+        dscan, dtail = dstate
+        dblob = G.pack_state(dscan, dtail if Kc > 1 else None)
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_mode=1 if valve else 0, gate_tau=tau,
+                ret_mode=1 if ret else 0)
+    ora = O.phase_bwd(cfg, d["mag"][:, :L], d["ang"][:, :L], None if ret else d["gamma"], d["theta"],
+                      d["dz_re"][:, :L], d["dz_im"][:, :L], conv_w=d["conv_w"], conv_b=d["conv_b"],
+                      valve=d["valve"][:, :L] if valve else None, ret=d["ret"][:, :L] if ret else None,
+                      ret_bias=d["ret_bias"] if ret else None,
+                      scan_in=None if scan_in is None else scan_in.astype(np.float64),
+                      tail_in=tail_in if Kc > 1 else None,
+                      dscan_out=None if dscan is None else dscan.astype(np.float64),
+                      dtail_out=None if dtail is None or Kc <= 1 else dtail.astype(np.float64))
+    out = G.run_fwd_bwd_bf16(d, B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, state_in=blob, dstate_out=dblob,
+                             valve=d["valve"] if valve else None, ret=d["ret"] if ret else None,
+                             ret_bias=d["ret_bias"] if ret else None, **kw)
+    for n in ("dmag", "dang"):                       # stored as bf16
+        e = G.bf16_err(out[n], ora[n])
+        assert e <= 1.0, (n, e)
+    for n in ("dgamma", "dtheta", "dconv_w", "dconv_b", "dvalve", "dret"):      # fp32
+        if n in out:
+            e = G.rel_err(out[n], ora[n])
+            assert e <= TOL, (n, e)
+    dsi, dti = G.unpack_state(out["dstate_in"], B, J, Kc)
+    assert G.rel_err(dsi, ora["dscan_in"]) <= TOL
+    if Kc > 1:
+        assert G.rel_err(dti, ora["dtail_in"]) <= TOL
+    return out, ora
+
+
+@pytest.mark.parametrize("H,F", [(3, 64), (2, 32), (4, 16), (1, 128)])
+@pytest.mark.parametrize("Kc", [0, 2, 4])
+def test_bf16_backward_head_widths(H, F, Kc):
+    B, L = 2, 333                      # three backward tiles, ragged tail
+    d = _inputs(B, L, H, F, Kc, 8700 + H * 131 + F + Kc)
+    _check_bwd(B, L, H, F, Kc, d, tau=0.25)
+
+
+@pytest.mark.parametrize("valve,ret", [(True, False), (False, True), (True, True)])
+@pytest.mark.parametrize("Kc", [0, 3])
+def test_bf16_backward_valve_and_retention(valve, ret, Kc):
+    B, L, H, F = 2, 300, 3, 64
+    d = _inputs(B, L, H, F, Kc, 8900 + Kc + 2 * valve + 4 * ret)
+    _check_bwd(B, L, H, F, Kc, d, amp_mode=1, valve=valve, ret=ret)
+
+
+@pytest.mark.parametrize("L", [1, 7, 127, 128, 129, 400])
+def test_bf16_backward_lengths_with_state_and_its_gradients(L):
+    B, H, F, Kc = 3, 2, 64, 4
+    J = H * F
+    d = _inputs(B, 400, H, F, Kc, 9100 + L)
+    r = np.random.Generator(np.random.PCG64(9))
+    state = (r.standard_normal((B, 2, J)).astype(np.float32), r.standard_normal((B, Kc - 1, 2, J)).astype(np.float32))
+    dstate = (r.standard_normal((B, 2, J)).astype(np.float32), r.standard_normal((B, Kc - 1, 2, J)).astype(np.float32))
+    _check_bwd(B, L, H, F, Kc, d, state=state, dstate=dstate)
+
+
+def test_bf16_backward_without_parameter_gradients():
+    B, L, H, F, Kc = 2, 400, 2, 64, 4
+    d = _inputs(B, L, H, F, Kc, 9200)
+    _check_bwd(B, L, H, F, Kc, d, want_param=False)
