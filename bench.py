@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--ret", action="store_true",
                     help="ret_mode 1: the data-dependent retention of Sec. 3.3 item 4 instead of the constant gamma "
                          "(extra line, not the headline; no CPU baseline; with --valve: the paper's literal layer)")
+    ap.add_argument("--bf16", action="store_true",
+                    help="activations (inputs, outputs, upstream and returned gradients) are bfloat16 in memory, "
+                         "arithmetic and state fp32 (extra line, not the headline; no CPU baseline)")
     ap.add_argument("--workload", default="cfg3_train",
                     choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "decode"])
     ap.add_argument("--decode-batch", type=int, default=1)
@@ -171,23 +174,27 @@ def main():
     inp = WL.make_inputs(wl, theta=theta, with_grads=do_bwd, L=L)
     gamma, th = torch.from_numpy(inp["gamma"]).to(dev), torch.from_numpy(inp["theta"]).to(dev)
     cw, cb = torch.from_numpy(inp["conv_w"]).to(dev), torch.from_numpy(inp["conv_b"]).to(dev)
-    per_set = (8 if do_bwd else 4) * B * L * J * 4
-    nsets = max(4, min(16, -(-(600 << 20) // per_set)))     # >= 4 disjoint sets, > 512 MiB in total: the LLC cannot serve them
+    esize = 2 if args.bf16 else 4
+    adt = torch.bfloat16 if args.bf16 else torch.float32
+    per_set = (8 if do_bwd else 4) * B * L * J * esize
+    nsets = max(4, min(16 if not args.bf16 else 32, -(-(600 << 20) // per_set)))     # >= 4 disjoint sets, > 512 MiB in total: the LLC cannot serve them
     names = ["mag", "ang"] + (["dz_re", "dz_im"] if do_bwd else [])
     sets = []
-    base = {k: torch.from_numpy(inp[k]).to(dev) for k in names}
+    base = {k: torch.from_numpy(inp[k]).to(dev).to(adt) for k in names}
     for s in range(nsets):
         cur = {k: (base[k] if s == 0 else torch.roll(base[k], shifts=7 * s, dims=1).contiguous()) for k in names}
-        cur["z_re"] = torch.empty((B, L, J), device=dev)
-        cur["z_im"] = torch.empty((B, L, J), device=dev)
+        cur["z_re"] = torch.empty((B, L, J), device=dev, dtype=adt)
+        cur["z_im"] = torch.empty((B, L, J), device=dev, dtype=adt)
         if do_bwd:
-            cur["dmag"] = torch.empty((B, L, J), device=dev)
-            cur["dang"] = torch.empty((B, L, J), device=dev)
+            cur["dmag"] = torch.empty((B, L, J), device=dev, dtype=adt)
+            cur["dang"] = torch.empty((B, L, J), device=dev, dtype=adt)
         sets.append(cur)
     t_gen = time.time() - t_gen
 
     d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau, gate_mode=1 if args.valve else 0,
                     ret_mode=1 if args.ret else 0)
+    if args.bf16:
+        args.no_cpu_baseline = True
     ret = ret_bias = dret = None
     if args.ret:
         assert not stream_mode, "--ret: cfg2_layer_fwd, cfg3_train or cfg5_wide"
@@ -214,6 +221,9 @@ def main():
 
     # first call builds the lane table; later calls reuse it (parameters do not change in the bench)
     def fwd_call(dd, p, st_in, st_out, ck):
+        if args.bf16:
+            return K.cawn_phase_accumulate_bf16_fwd(dd, p["mag"], p["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
+                                                    st_in, p["z_re"], p["z_im"], st_out, ck, None, ws)
         if ret is not None:
             return K.cawn_phase_accumulate_ret_fwd(dd, p["mag"], p["ang"], valve, ret, ret_bias, th, cw, cb, st_in,
                                                    p["z_re"], p["z_im"], st_out, ck, None, ws)
@@ -238,12 +248,10 @@ def main():
             state.zero_()
             for c in range(nfull):
                 p = sets[c % nsets]
-                K.cawn_phase_accumulate_fwd(d, p["mag"], p["ang"], gamma, th, cw, cb, state, p["z_re"], p["z_im"],
-                                            state, None, None, ws)
+                fwd_call(d, p, state, state, None)
             if d_tail is not None:
                 p = sets[nfull % nsets]
-                K.cawn_phase_accumulate_fwd(d_tail, p["mag"], p["ang"], gamma, th, cw, cb, state, p["z_re"],
-                                            p["z_im"], state, None, None, ws)
+                fwd_call(d_tail, p, state, state, None)
             return
         if rec is not None:
             rec[0].record()
@@ -251,7 +259,12 @@ def main():
         if rec is not None:
             rec[1].record()
         if do_bwd:
-            if ret is not None:
+            if args.bf16:
+                st |= K.cawn_phase_accumulate_bf16_bwd(d, s["mag"], s["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
+                                                       None, ckpt, s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"],
+                                                       dvalve, dret, None if ret is not None else dgamma, dtheta,
+                                                       dcw, dcb, None, ws)
+            elif ret is not None:
                 st |= K.cawn_phase_accumulate_ret_bwd(d, s["mag"], s["ang"], valve, ret, ret_bias, th, cw, cb, None,
                                                       ckpt, s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"],
                                                       dvalve, dret, dtheta, dcw, dcb, None, ws)
@@ -297,17 +310,20 @@ def main():
                                    if args.ret else "constant per lane",
                       "buffer_sets_rotated": nsets}}
     bflag = lambda x: "true" if x else "false"
-    fwd_label = f"fwd_kernel<1,4,{bflag(args.valve)},{bflag(args.ret)}>"
-    bwd_label = f"bwd_kernel<1,4,true,{bflag(args.valve)},{bflag(args.ret)}>"
-    extra = args.valve or args.ret
+    fwd_label = f"fwd_kernel<1,4,{bflag(args.valve)},{bflag(args.ret)},{bflag(args.bf16)}>"
+    bwd_label = f"bwd_kernel<1,4,true,{bflag(args.valve)},{bflag(args.ret)},{bflag(args.bf16)}>"
+    extra = args.valve or args.ret or args.bf16
+    out["config"]["activations"] = "bfloat16 in memory, fp32 arithmetic and state" if args.bf16 else "fp32"
+    fwd_bpl = FWD_BYTES_PER_TOKEN_LANE // (2 if args.bf16 else 1)
+    bwd_bpl = BWD_BYTES_PER_TOKEN_LANE // (2 if args.bf16 else 1)
 
     # ---- roofline of the dominant kernel, from HIP events on the launch stream
     if stream_mode:
         ncalls = nfull + (1 if d_tail is not None else 0)
         per_call_ms = ms_per_step / ncalls
-        alg = FWD_BYTES_PER_TOKEN_LANE * tokens * J / ncalls
+        alg = fwd_bpl * tokens * J / ncalls
         achieved = alg / (per_call_ms * 1e-3) / 1e9
-        out["roofline"] = {"bound": "hbm", "kernel": "fwd_kernel<1,4,false,false> (per 4096-token chunk call, launch gaps included)",
+        out["roofline"] = {"bound": "hbm", "kernel": fwd_label + " (per 4096-token chunk call, launch gaps included)",
                            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                            "traffic": read_traffic(args.workload), "avg_ms": per_call_ms}
         out["stream"] = {"calls": ncalls, "state_bytes": nstate * 4, "device_mem_delta_bytes": int(mem1 - mem0)}
@@ -317,13 +333,13 @@ def main():
         out["fwd_ms"] = fwd_ms
         out["fwd_ms_median_min"] = [float(np.median(fwd_all)), float(np.min(fwd_all))]
         out["fwd_tokens_per_s"] = tokens / (fwd_ms * 1e-3)
-        out["fwd_GBps"] = FWD_BYTES_PER_TOKEN_LANE * tokens * J / (fwd_ms * 1e-3) / 1e9
+        out["fwd_GBps"] = fwd_bpl * tokens * J / (fwd_ms * 1e-3) / 1e9
         if do_bwd:
             bwd_all = [r[1].elapsed_time(r[2]) for r in recs]
             bwd_ms = float(np.mean(bwd_all))
             out["bwd_ms"] = bwd_ms
             out["bwd_ms_median_min"] = [float(np.median(bwd_all)), float(np.min(bwd_all))]
-            alg = BWD_BYTES_PER_TOKEN_LANE * tokens * J
+            alg = bwd_bpl * tokens * J
             achieved = alg / (bwd_ms * 1e-3) / 1e9
             out["roofline"] = {"bound": "hbm", "kernel": bwd_label + " (+ its partial-sum reduction)",
                                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
