@@ -168,7 +168,17 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // Persistent: each workgroup loops over tiles, handed out in chain order by an atomic ticket (a
     // tile only ever waits for tiles that a running workgroup already holds).  The next ticket is
     // asked for at the top of a tile and has long arrived when it is needed.
-    for (int it = 0; ticket < a.total_tiles; ++it) {
+    // The kernel's arguments are read from the kernel-argument segment again in every phase of a tile
+    // (scalar loads next to their use, `ARGS_AGAIN()` makes the compiler forget what it loaded) instead
+    // of living in scalar registers across the loop: kept there they overflow the scalar register file,
+    // and every overflowing value costs vector instructions (lane writes and reads) on each use.
+    const uint32_t total_tiles_ = a.total_tiles;
+    typedef const __attribute__((address_space(4))) BwdArgs *KArgs;
+    for (int it = 0; ticket < total_tiles_; ++it) {
+    KArgs ap = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+#define a (*ap)
+#define ARGS_AGAIN() asm volatile("" : "+s"(ap))
     // (opaque copies: anything computed from them is computed inside the loop and does not occupy
     // registers across it)
     int tid = tid_;
@@ -440,6 +450,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     };
     // The mode switches are uniform over the launch; each combination gets its own straight-line
     // copy of the loop, so that the tokens' dependent chains (exp -> rcp -> sin/cos) interleave.
+    ARGS_AGAIN();
+    const GateSet gs_ = {a.gs.a1, a.gs.b1, a.gs.a2, a.gs.b2};
     auto front_end = [&](auto amp_c, auto small_c) {
         constexpr bool AMP = decltype(amp_c)::value, SMALL = decltype(small_c)::value;
         const int vbase = VALVE ? valve_base() : 0;
@@ -513,7 +525,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     km *= beta;
                     am[i][v] = amp;
                 } else {
-                    agv = in_gate(a.gs, zm) ? amp : 0.0f;
+                    agv = in_gate(gs_, zm) ? amp : 0.0f;
                 }
                 cs[i][v] = LEAN ? rev : c;
                 sn[i][v] = s;
@@ -632,6 +644,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         asm volatile("" ::"v"(psr[v]), "v"(psi[v]), "v"(cth[v]), "v"(sth[v]), "v"(gam[v]));
 
     BWD_STAMP(5);
+    ARGS_AGAIN();
     // ---- chain, second half: look-back (its round trips were hidden behind the recompute above)
     if (head) {
         float cr[V], ci[V], Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
@@ -693,6 +706,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // operations then have one known order).
     const bool fetch_halo = KC > 0 && HALO > 0 && head && chained;
 
+    ARGS_AGAIN();
     // ---- reverse pass: adjoint, returned gradients, parameter terms
     float acc_g[V], acc_t[V];
 #pragma unroll
@@ -771,6 +785,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         BVec<V>::st(a.dstate_in + ((size_t)b * 2 + 1) * a.J + j0, xi);
     }
 
+    ARGS_AGAIN();
     const size_t dbase = ((size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB) * ES;
     float *omag = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dmag) + dbase);
     float *oang = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dang) + dbase);
@@ -987,6 +1002,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
     }
 
+    ARGS_AGAIN();
     // ---- parameter partials: my tokens, then the wave's two segments, then the waves in order
     if (PARAM) {
         float part[ROWS][V];
@@ -1069,6 +1085,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     lds_barrier();
     BWD_STAMP(10);
     ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
+#undef a
+#undef ARGS_AGAIN
     }
 
     // ---- the workgroup that leaves last resets the ticket and advances the epoch for the next call.
