@@ -115,8 +115,10 @@ __device__ __forceinline__ void stage_consts(float *sC, const float *table, int 
 // checkpoints stay fp32 (Sec. 3.5 / Sec. 6.1 of the paper: the network runs in bf16, the accumulator in
 // fp32).  A staged row of JB bf16 lanes is handled as JB/2 four-byte words; outputs are rounded to
 // nearest even by the hardware conversion.
+// (with bf16 rows the staged tile is half as large and a third workgroup fits a CU's LDS; the variants
+// without the per-token retentions also fit its registers)
 template <int V, int KC, bool VALVE, bool RET, bool BF>
-__global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
+__global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVES + 1 : CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
     static_assert(!BF || V == 1, "bf16 activations: one lane per thread");
     constexpr int TILE_T = FwdGeom::TILE_T, NSTEP = FwdGeom::NSTEP, NSEG = FwdGeom::NSEG, LPR = FwdLPR;
@@ -167,6 +169,16 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
     const uint32_t tag = epoch + 1;      // of every word this call publishes (0 is never valid)
 
+    // From here on the kernel's arguments are read from the kernel-argument segment again in every
+    // phase of a tile (scalar loads next to their use; `ARGS_AGAIN()` makes the compiler forget what it
+    // loaded) instead of living in scalar registers across the loop: kept there, they and what the
+    // compiler derives from them overflow the scalar register file, and every overflowing value costs
+    // vector registers and lane moves.
+    typedef const __attribute__((address_space(4))) FwdArgs *KArgs;
+    KArgs ap = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ap));
+#define a (*ap)
+#define ARGS_AGAIN() asm volatile("" : "+s"(ap))
     // Stage a tile's input rows in LDS.  The chain-owning wave stays out of it: a wave's memory
     // operations complete in order, and its polls of other tiles must not queue behind a tile's
     // worth of HBM reads.
@@ -198,6 +210,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
     float rb[V];                                   // RET: static retention bias of my lanes
 
     for (int it = 0; ticket < qtiles; ++it) {
+        ARGS_AGAIN();
+        const GateSet gs_ = {a.gs.a1, a.gs.b1, a.gs.a2, a.gs.b2};
         const uint32_t id = T.id;
         const int b = T.b, tt = T.tt;
         const int j0 = T.lb * JB + lv * V;
@@ -323,7 +337,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
                         g = vl >= a.valve_thr;
                         ag = g ? amp * sigmoid_fast(vl - 3.0f) : 0.0f;
                     } else {
-                        g = in_gate(a.gs, zm);
+                        g = in_gate(gs_, zm);
                         ag = g ? amp : 0.0f;
                     }
                     float s, c;
@@ -366,6 +380,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         }
         CAWN_STAMP(2);
 
+        ARGS_AGAIN();
         // ---- optional gate mask: bit j%32 of word j/32
         if (a.mask) {
             constexpr int TPW = 32 / V;                 // threads per 32-lane word
@@ -400,6 +415,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
             stage_tile(Tn);
         }
 
+        ARGS_AGAIN();
         float Xr[V], Xi[V];   // state entering my segment, from a zero tile input
         float Cs[V];          // RET: product of the retentions of the segments before mine
 #pragma unroll
@@ -504,6 +520,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         lds_barrier_raw();     // the next tile's rows are still on their way
         CAWN_STAMP(6);
 
+        ARGS_AGAIN();
         // ---- true state entering my segment
         float Sr[V], Si[V];
 #pragma unroll
@@ -623,6 +640,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, CAWN_FWD_WAVES) void fwd_ker
         T = Tn;
     }
 
+#undef a
+#undef ARGS_AGAIN
     // ---- the workgroup that leaves last resets the tickets and advances the epoch for the next call.
     //      Workgroups are counted, not tiles: every one of the grid has then drawn its last ticket.
     if (tid == 0) {
