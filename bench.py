@@ -46,7 +46,7 @@ def parse():
                     help="activations (inputs, outputs, upstream and returned gradients) are bfloat16 in memory, "
                          "arithmetic and state fp32 (extra line, not the headline; no CPU baseline)")
     ap.add_argument("--workload", default="cfg3_train",
-                    choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "decode"])
+                    choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "cfg6_paper_heads", "decode"])
     ap.add_argument("--decode-batch", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
@@ -165,7 +165,7 @@ def main():
     wl = WL.CONFIGS[args.workload]
     B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
     theta = K.cawn_theta_init(H, F)
-    do_bwd = args.workload in ("cfg3_train", "cfg5_wide")
+    do_bwd = args.workload in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads")
     stream_mode = args.workload == "cfg4_stream"
     L = wl.chunk if stream_mode else wl.L
 

@@ -57,9 +57,10 @@ typedef struct cawn_desc {
     float out_clamp;      /* 100; +inf disables                                                 */
     float grad_clamp;     /* 100; +inf disables (backward only)                                 */
     int32_t accumulate_param_grads; /* backward: 0 overwrite, 1 add into dgamma/dtheta/dconv_*  */
-    int32_t lane_consts_cached;     /* 1: gamma, theta, conv_w, conv_b are unchanged since the
-                                       last call on this workspace with the same H, F, conv_k
-                                       that had this flag 0 -- skip rebuilding the lane table   */
+    int32_t lane_consts_cached;     /* 1: gamma (ret_mode 1: ret_bias), theta, conv_w, conv_b
+                                       are unchanged since the last call on this workspace with
+                                       the same H, F, conv_k, ret_mode that had this flag 0 --
+                                       skip rebuilding the lane table                           */
     float valve_eps;      /* gate_mode 1: the valve closes below this (paper: 0.001)            */
     int32_t ret_mode;     /* 0 constant per-lane retention gamma[j]; 1 data-dependent retention
                              sigmoid(ret[t][h] + ret_bias[k]) (cawn_phase_accumulate_ret_fwd/_bwd; same

@@ -40,7 +40,7 @@ class Workload:
         return replace(self, **kw)
 
 
-# The five benchmark configurations (index = position in the configuration list).
+# The five benchmark configurations (index = position in the configuration list) and a sixth shape.
 CONFIGS = {
     "cfg1_tiny": Workload("cfg1_tiny", B=1, H=2, F=16, L=256, gate_tau=0.1, gamma_lo=0.90,
                           gamma_hi=0.999, theta_uniform=True, seed=4250),
@@ -49,6 +49,8 @@ CONFIGS = {
     "cfg4_stream": Workload("cfg4_stream", B=1, H=12, F=64, L=2_000_000, gamma_lo=0.999,
                             gamma_hi=0.99999, chunk=4096, seed=4253),
     "cfg5_wide": Workload("cfg5_wide", B=2, H=32, F=128, L=32768, gate_tau=0.25, seed=4254),
+    # the lane shape of the paper's own 150M model (4 heads of 64 harmonics), on the training-step batch
+    "cfg6_paper_heads": Workload("cfg6_paper_heads", B=8, H=4, F=64, L=8192, seed=4255),
 }
 
 

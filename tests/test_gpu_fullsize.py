@@ -116,6 +116,11 @@ def test_cfg5_wide_full_size():
     _run_full("cfg5_wide", do_bwd=True)
 
 
+def test_cfg6_paper_lane_shape_full_size():
+    # 4 heads of 64 harmonics (the paper's own 150M model), the training-step batch
+    _run_full("cfg6_paper_heads", do_bwd=True)
+
+
 def test_cfg5_shape_without_conv_gates_20_percent():
     # threshold 0.25 on raw N(0,1) magnitudes: P(|m| < 0.25) = 19.74 % of lanes gated off
     import torch
