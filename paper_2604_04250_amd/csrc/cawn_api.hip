@@ -684,7 +684,8 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     if (ist < J || ost < J || isb < 0 || osb < 0) return CAWN_EINVAL;
     if (ist > (1ll << 21) || ost > (1ll << 21)) return CAWN_EUNSUPPORTED;   // in-tile offsets are 32-bit
     // bf16 rows are staged as four-byte words: an even number of lanes, even strides, aligned rows
-    if (bf16 && (J % 2 || ist % 2 || isb % 2 || !aligned(mag, 4) || !aligned(ang, 4))) return CAWN_EUNSUPPORTED;
+    if (bf16 && (J % 2 || ist % 2 || isb % 2 || ost % 2 || osb % 2 || !aligned(mag, 4) || !aligned(ang, 4) ||
+                 !aligned(dz_re, 4) || !aligned(dz_im, 4))) return CAWN_EUNSUPPORTED;
 
     BwdArgs a{};
     a.bf16 = bf16 ? 1 : 0;
@@ -739,6 +740,8 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&
                  (!state_in || aligned(state_in, 16))) ? 1 : 0;
     if (bf16) a.stage16 = (J % 8 == 0 && ist % 8 == 0 && isb % 8 == 0 && aligned(mag, 16) && aligned(ang, 16)) ? 1 : 0;
+    const long long zq = bf16 ? 8 : 4;       // elements per 16 bytes
+    a.stage16z = (J % zq == 0 && ost % zq == 0 && osb % zq == 0 && aligned(dz_re, 16) && aligned(dz_im, 16)) ? 1 : 0;
     a.isb = isb; a.ist = ist; a.osb = osb; a.ost = ost;
     a.conv_clamp = d->conv_clamp; a.grad_clamp = d->grad_clamp;
     a.spin_limit = g_spin_limit.load();

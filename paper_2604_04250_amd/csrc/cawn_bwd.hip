@@ -134,11 +134,28 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         if constexpr (BF) return from_bf16(reinterpret_cast<const uint16_t *>(&sU[r][0])[l]);
         else return sU[r][l];
     };
-    __shared__ float sEb[NSEG][2][JB];
-    __shared__ float sEf[PARAM ? NSEG : 1][2][JB];
+    // PF: the upstream gradients of a tile are staged in LDS a tile ahead (direct-to-LDS loads issued
+    // while the previous tile is in its front-end), so that a tile starts its local adjoint, and
+    // publishes its aggregate, without waiting for memory.  The 32 KB this takes fit beside the rest
+    // only because arrays with disjoint lifetimes share storage: the conv-gradient halo rows (written
+    // after the reverse pass) lie over the segment aggregates (dead by then), and the partial-sum
+    // staging lies over the input rows (dead after the last weight-gradient read, one more barrier).
+    constexpr bool PF = !VALVE && !RET;
+    constexpr int NRZ = staged_rows<TILE_T, JBS, 0>();                // staged rows per gradient stream
+    __shared__ __attribute__((aligned(16))) float sDz[PF ? 2 * NRZ : 1][JBS];    // [stream*NRZ + token][lane]
+    // ... and with them the four lane constants the local adjoint needs (lambda, lambda^NSTEP): a wave's
+    // memory operations complete in issue order, so a load issued at the top of a tile returns only after
+    // the previous tile's output stores have been acknowledged
+    __shared__ float sLam[PF ? 4 : 1][JB];
+    constexpr int N_EB = NSEG * 2 * JB, N_EF = (PARAM ? NSEG : 1) * 2 * JB, N_HALO = (NSEG + 1) * HALO1 * 2 * JB;
+    __shared__ float sPool[PF ? (N_EB + N_EF > N_HALO ? N_EB + N_EF : N_HALO) : N_EB + N_EF + N_HALO];
+    float (*sEb)[2][JB] = reinterpret_cast<float (*)[2][JB]>(&sPool[0]);
+    float (*sEf)[2][JB] = reinterpret_cast<float (*)[2][JB]>(&sPool[N_EB]);
+    float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(&sPool[PF ? 0 : N_EB + N_EF]);   // [NSEG]: rows of the next tile
     __shared__ float sCarry[2][JB];
-    __shared__ float sHalo[NSEG + 1][HALO1][2][JB];   // [NSEG]: rows of the next tile
-    __shared__ float sRed[PARAM ? NW : 1][ROWS][JB];
+    __shared__ float sRedOwn[(PARAM && !PF) ? NW : 1][ROWS][JB];
+    static_assert(!PF || (size_t)NW * ROWS * JB <= (size_t)2 * NRTP * JBS, "the partial-sum staging fits over the input rows");
+    float (*sRed)[ROWS][JB] = PF ? reinterpret_cast<float (*)[ROWS][JB]>(&sU[0][0]) : sRedOwn;
     constexpr int GPB_MAX = 4;                    // valve groups per lane block (F >= 8)
     __shared__ float sV[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];      // valve logits, [group][token]
     __shared__ float sVp[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
@@ -146,15 +163,16 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     __shared__ float sPb[RET ? NSEG : 1][JB];                        // product of each segment's retentions
     __shared__ float sPt[RET ? 1 : 1][JB];                           // product of the tile's retentions (head group)
     __shared__ float sRp[RET ? BwdGeom::TILE_T * GPB_MAX : 1];       // retention-logit gradient terms per (group, token)
-    __shared__ uint32_t sTicket[2], sLast, sEpoch;
+    __shared__ uint32_t sTicket[2], sLast, sEpoch;     // tickets of this tile and the next one
 
     const int tid_ = threadIdx.x;
     const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
     const float *dtail_out = a.dstate_out ? a.dstate_out + (size_t)a.B * 2 * a.J : nullptr;
     const uint32_t chain_stride = (uint32_t)a.B * a.nLB;
     const uint32_t ost32 = (uint32_t)a.ost, ist32 = (uint32_t)a.ist;
+    uint32_t ticket_ahead = 0;   // thread 0: the ticket asked for in this tile, until it is parked in LDS
     if (tid_ == 0) {
-        const uint32_t e = flag_load(&a.hdr->epoch);     // both round trips at once
+        const uint32_t e = flag_load(&a.hdr->epoch);     // all three round trips at once
         const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sEpoch = e;
         sTicket[0] = t;
@@ -165,9 +183,14 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
     const uint32_t tag = epoch + 1;      // of every word this call publishes (0 is never valid)
 
-    // Persistent: each workgroup loops over tiles, handed out in chain order by an atomic ticket (a
-    // tile only ever waits for tiles that a running workgroup already holds).  The next ticket is
-    // asked for at the top of a tile and has long arrived when it is needed.
+    // Persistent: each workgroup loops over tiles, handed out in chain order by an atomic ticket.  A
+    // workgroup also holds the ticket of its next tile: it asks for it just before the previous tile's
+    // output stores go out (a wave's memory operations complete in issue order: asked for behind them,
+    // at the top of a tile, the answer would arrive only after they are acknowledged, and the next tile
+    // must be known early, for its staged gradients).  Every workgroup works through its tickets in
+    // increasing order and a tile waits only for lower tickets, so the lowest unfinished ticket is always
+    // some workgroup's current tile: no wait can last.  (Holding tickets two tiles ahead was tried: the
+    // reserved tiles start later and their successors in other workgroups wait for them, +3 % to +30 %.)
     // The kernel's arguments are read from the kernel-argument segment again in every phase of a tile
     // (scalar loads next to their use, `ARGS_AGAIN()` makes the compiler forget what it loaded) instead
     // of living in scalar registers across the loop: kept there they overflow the scalar register file,
@@ -188,10 +211,6 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     const float *table = a.table;      // (the same for the lane table's base and row pitch: the ~30 row
     int Jp = a.Jp;                     // addresses are then formed per tile instead of living in scalar
     asm volatile("" : "+s"(table), "+s"(Jp));   // registers across the loop, which spilled)
-    uint32_t ticket_ahead;   // (only thread 0's copy is ever set or read; no initialiser, so no
-                             // merge of values that would wait for the atomic right here)
-    if (tid == 0)
-        ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     BWD_STAMP(1);
     const int lb = ticket % a.nLB;
     const int rest = ticket / a.nLB;
@@ -212,7 +231,45 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float dzr[NSTEP][V], dzi[NSTEP][V];     // upstream dS, later overwritten by d(pre-activation)
     // a tile that lies wholly inside the tensors loads and stores without per-row checks
     const bool full = (tt + 1) * TILE_T <= a.L && (lb + 1) * JB <= a.J;
-    {
+    // (upstream gradients of tile (b_, tt_, lb_) into sDz: rows of J lanes, or J/2 words with bf16)
+    auto stage_dz = [&](int b_, int tt_, int lb_) {
+        if (wave == NW - 1) {       // rows R_LR, R_LI, then R_PSEGB + 2, + 3 of the lane block: two loads of two rows
+            const int jl = lb_ * JB + (lane & (JB - 1));
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_global_load_lds(table + (size_t)(R_LR + (lane >> 5)) * Jp + jl, &sLam[0][0], 4, 0, 0);
+            __builtin_amdgcn_global_load_lds(table + (size_t)(R_PSEGB + 2 + (lane >> 5)) * Jp + jl, &sLam[2][0], 4, 0, 0);
+#endif
+        }
+        if (a.stage16z)
+            stage_rows<TILE_T, JBS, 0, 16>(&sDz[0][0], a.dz_re, a.dz_im, nullptr, b_, tt_ * TILE_T, lb_, BF ? a.J / 2 : a.J, a.L,
+                                   BF ? a.osb / 2 : a.osb, BF ? (int)a.ost / 2 : (int)a.ost, wave, NW, lane);
+        else
+            stage_rows<TILE_T, JBS, 0, 4>(&sDz[0][0], a.dz_re, a.dz_im, nullptr, b_, tt_ * TILE_T, lb_, BF ? a.J / 2 : a.J, a.L,
+                                  BF ? a.osb / 2 : a.osb, BF ? (int)a.ost / 2 : (int)a.ost, wave, NW, lane);
+    };
+    if (PF) {
+        if (it == 0) {      // a workgroup's first tile: nobody staged its gradients ahead
+            stage_dz(b, tt, lb);
+            wait_vm<0>();
+            lds_barrier();
+        }
+        // (later tiles: staged during the previous tile, complete before its closing barrier)
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+            const int r = seg * NSTEP + i;
+            float vr, vi;
+            if constexpr (BF) {
+                vr = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[r][0])[lv]);
+                vi = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[NRZ + r][0])[lv]);
+            } else {
+                vr = sDz[r][lv];
+                vi = sDz[NRZ + r][lv];
+            }
+            const bool live = full || (active && t0 + i < a.L);     // rows and lanes outside the tensor staged a valid address
+            dzr[i][0] = live ? vr : 0.f;
+            dzi[i][0] = live ? vi : 0.f;
+        }
+    } else {
         const size_t gbase = ((size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB) * ES;
         const float *gre = reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.dz_re) + gbase);
         const float *gim = reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.dz_im) + gbase);
@@ -254,10 +311,17 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // ---- lane constants
     float lr[V], li[V], pnr[V], pni[V];
     float wmf[KC1][V], waf[KC1][V], bm[V], ba[V];   // taps for the front-end
-    ldu<V>(lr, row(R_LR), jb);
-    ldu<V>(li, row(R_LI), jb);
-    ldu<V>(pnr, row(R_PSEGB + 2), jb);                       // lambda^NSTEP
-    ldu<V>(pni, row(R_PSEGB + 3), jb);
+    if (PF) {       // staged with the gradients (lanes beyond J hold table padding: their results are never stored)
+        lr[0] = sLam[0][lv];
+        li[0] = sLam[1][lv];
+        pnr[0] = sLam[2][lv];
+        pni[0] = sLam[3][lv];
+    } else {
+        ldu<V>(lr, row(R_LR), jb);
+        ldu<V>(li, row(R_LI), jb);
+        ldu<V>(pnr, row(R_PSEGB + 2), jb);                       // lambda^NSTEP
+        ldu<V>(pni, row(R_PSEGB + 3), jb);
+    }
     float rb[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) rb[v] = 0.f;
@@ -342,9 +406,12 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         sEb[seg][1][lv * V + v] = Ebi[v];
         if (RET) sPb[seg][lv * V + v] = Pth[v];
     }
-    if (tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
     lds_barrier_raw();     // the staged rows are still on their way
     BWD_STAMP(2);
+    // (PF: the next tile must be known by the time its gradients are staged; asked for here, the answer
+    // arrives with this wave's staged rows, which it waits for below anyway)
+    if (PF && tid == 0)
+        ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
     float Cb[V];            // RET: product of the retentions of the segments after mine
 #pragma unroll
@@ -396,6 +463,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     }
     // the staged rows have landed
     wait_stores_done();
+    if (PF && tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
     lds_barrier();
     BWD_STAMP(3);
 
@@ -422,6 +490,15 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             ldu<V>(cth, row(R_COS), jb);
             ldu<V>(sth, row(R_SIN), jb);
             ldu<V>(gam, row(R_GAMMA), jb);
+        }
+    }
+    // the next tile's upstream gradients start their way into sDz (every thread has read this tile's;
+    // issued behind the loads above, whose wait then leaves these in flight)
+    if (PF) {
+        const uint32_t nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
+        if (nxt < total_tiles_) {
+            const int nlb = nxt % a.nLB, nrest = nxt / a.nLB;
+            stage_dz(nrest % a.B, a.nT - 1 - nrest / a.B, nlb);
         }
     }
 
@@ -786,6 +863,11 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     }
 
     ARGS_AGAIN();
+    // the ticket of the next tile: asked for as late as its answer can still arrive unwaited-for, i.e.
+    // ahead of this tile's output stores (a ticket held in reserve is a tile that has not started:
+    // its successors in other workgroups wait for it)
+    if (!PF && tid == 0)
+        ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const size_t dbase = ((size_t)b * a.isb + (size_t)(tt * TILE_T) * a.ist + (size_t)lb * JB) * ES;
     float *omag = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dmag) + dbase);
     float *oang = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dang) + dbase);
@@ -802,6 +884,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 sto(oang, ooff, dzi[i]);
                 ooff += ist32 * ES;
             }
+            wait_vm<2 * NSTEP>();       // everything older than these stores has completed (the ticket, the next tile's staged gradients)
         } else {
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
@@ -811,6 +894,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 }
                 ooff += ist32 * ES;
             }
+            wait_vm<0>();
         }
     } else {
         // ---- transposed conv: du[t] = sum_k w[k] dz[t + (KC-1) - k]
@@ -1043,6 +1127,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     }
                 }
         }
+        if (PF) lds_barrier();      // the staging below lies over the input rows: everybody has read them
 #pragma unroll
         for (int r = 0; r < ROWS; ++r)
 #pragma unroll
@@ -1081,7 +1166,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
     }
 
-    // ---- LDS is reused by the next tile
+    // ---- LDS is reused by the next tile.  The ticket asked for above is parked where this tile's was
+    //      (everything older than the output stores has completed: no further wait)
+    if (!PF && tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
     lds_barrier();
     BWD_STAMP(10);
     ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);

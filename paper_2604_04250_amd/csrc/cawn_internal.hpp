@@ -165,6 +165,7 @@ struct BwdArgs {
     int B, L, J, Jp, nT, nLB;
     int small_angle;
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
+    int stage16z;                // the same for the upstream-gradient rows
     int amp_mode, want_param;
     long long isb, ist, osb, ost;
     float conv_clamp, grad_clamp;
