@@ -319,3 +319,40 @@ def test_spin_limit_timeout_is_reported_and_every_wave_exits():
     ora = O.phase_fwd(O.Cfg(B, L, 1, 8, conv_k=4, gate_tau=0.1), sub["mag"], sub["ang"], sub["gamma"], sub["theta"],
                       conv_w=sub["conv_w"], conv_b=sub["conv_b"])
     assert G.rel_err(out["z_re"][..., lanes], ora["z_re"]) <= TOL
+
+
+def test_epoch_wrap_clears_published_words():
+    """Published words are valid when their tag equals the call's epoch + 1, and the epoch wraps every
+    2^30 calls: the call that wraps it clears every published word, so that a word of 2^30 calls ago
+    cannot pass for a fresh one.  The host sets the workspace's epoch counter just below the wrap; the
+    calls before, across and after it (forward and backward, each advancing the epoch) must all agree
+    with the oracle."""
+    G = _gpu()
+    from paper_2604_04250_amd import binding as K
+    import torch
+    B, L, H, F, Kc = 2, 700, 2, 64, 4
+    d = _inputs(B, L, H, F, Kc, 1400)
+    r = np.random.Generator(np.random.PCG64(1401))
+    d["dz_re"] = r.standard_normal((B, L, H * F), dtype=np.float32)
+    d["dz_im"] = r.standard_normal((B, L, H * F), dtype=np.float32)
+    desc = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=0.1)
+    ws = torch.empty((K.cawn_workspace_bytes(desc) + 3) // 4, dtype=torch.int32, device=G.DEV)
+    K.check(K.cawn_workspace_init(ws))
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=0.1)
+    of = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"])
+    ob = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], d["dz_re"], d["dz_im"], conv_w=d["conv_w"],
+                     conv_b=d["conv_b"])
+    G.run_fwd_bwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, ws=ws)       # leaves words tagged with small epochs
+    EPOCH_WORD = 64 + 2                 # header: 64 ticket words, finished count, error flag, epoch
+    torch.cuda.synchronize()
+    ws[EPOCH_WORD] = (1 << 30) - 3
+    seen = []
+    for _ in range(4):                  # 8 calls: epochs 2^30 - 3 ... 2^30 - 1, 0, 1, ...
+        out = G.run_fwd_bwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, ws=ws)
+        fw = G.run_fwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, ws=ws, want_mask=False)
+        torch.cuda.synchronize()
+        seen.append(int(ws[EPOCH_WORD].item()))
+        assert G.rel_err(fw["z_re"], of["z_re"]) <= TOL
+        for k in ("dmag", "dang", "dgamma", "dtheta", "dconv_w"):
+            assert G.rel_err(out[k], ob[k]) <= TOL, k
+    assert seen[0] == 0 and seen == sorted(seen) and seen[-1] == 9, seen     # wrapped once, then counts on
