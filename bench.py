@@ -45,6 +45,10 @@ def parse():
     ap.add_argument("--bf16", action="store_true",
                     help="activations (inputs, outputs, upstream and returned gradients) are bfloat16 in memory, "
                          "arithmetic and state fp32 (extra line, not the headline; no CPU baseline)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="cfg2_layer_fwd only: the Temporal Syntax Cache as separate calls (cawn_syntax_conv on each "
+                         "stream, then the scan without conv front-end): 32 instead of 16 bytes per token-lane; "
+                         "a comparison line, not the headline")
     ap.add_argument("--workload", default="cfg3_train",
                     choices=["cfg2_layer_fwd", "cfg3_train", "cfg4_stream", "cfg5_wide", "cfg6_paper_heads", "decode"])
     ap.add_argument("--decode-batch", type=int, default=1)
@@ -220,7 +224,20 @@ def main():
     state = torch.zeros(nstate, device=dev)
 
     # first call builds the lane table; later calls reuse it (parameters do not change in the bench)
+    if args.unfused:
+        assert args.workload == "cfg2_layer_fwd" and not (args.bf16 or args.valve or args.ret), "--unfused: plain cfg2_layer_fwd"
+        args.no_cpu_baseline = True
+        d_plain = K.make_desc(B, L, H, F, conv_k=0, gate_tau=wl.gate_tau)
+        xm, xa = torch.empty((B, L, J), device=dev), torch.empty((B, L, J), device=dev)
+        cwm, cwa = cw[0].contiguous(), cw[1].contiguous()
+        cbm, cba = cb[0].contiguous(), cb[1].contiguous()
+
     def fwd_call(dd, p, st_in, st_out, ck):
+        if args.unfused:
+            st = K.cawn_syntax_conv(d, J, p["mag"], cwm, cbm, None, xm, None)
+            st |= K.cawn_syntax_conv(d, J, p["ang"], cwa, cba, None, xa, None)
+            return st | K.cawn_phase_accumulate_fwd(d_plain, xm, xa, gamma, th, None, None, st_in, p["z_re"], p["z_im"],
+                                                    st_out, ck, None, ws)
         if args.bf16:
             return K.cawn_phase_accumulate_bf16_fwd(dd, p["mag"], p["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
                                                     st_in, p["z_re"], p["z_im"], st_out, ck, None, ws)
@@ -235,6 +252,8 @@ def main():
 
     K.check(fwd_call(d, sets[0], None, None, ckpt))
     d.lane_consts_cached = 1
+    if args.unfused:
+        d_plain.lane_consts_cached = 1
     d_tail = None
     if stream_mode:
         nfull, rem = divmod(wl.L, wl.chunk)
@@ -312,8 +331,12 @@ def main():
     bflag = lambda x: "true" if x else "false"
     fwd_label = f"fwd_kernel<1,4,{bflag(args.valve)},{bflag(args.ret)},{bflag(args.bf16)}>"
     bwd_label = f"bwd_kernel<1,4,true,{bflag(args.valve)},{bflag(args.ret)},{bflag(args.bf16)}>"
-    extra = args.valve or args.ret or args.bf16
+    extra = args.valve or args.ret or args.bf16 or args.unfused
+    if args.unfused:
+        fwd_label = "2 x syntax_conv_kernel<4> + fwd_kernel<1,0,false,false,false> (one event span; the path's own 16 B per token-lane)"
     out["config"]["activations"] = "bfloat16 in memory, fp32 arithmetic and state" if args.bf16 else "fp32"
+    if args.unfused:
+        out["config"]["front_end"] = "conv as separate calls (2 x cawn_syntax_conv + scan): 32 B per token-lane"
     fwd_bpl = FWD_BYTES_PER_TOKEN_LANE // (2 if args.bf16 else 1)
     bwd_bpl = BWD_BYTES_PER_TOKEN_LANE // (2 if args.bf16 else 1)
 
