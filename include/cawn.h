@@ -46,7 +46,10 @@ typedef enum cawn_status {
 } cawn_status;
 
 typedef struct cawn_desc {
-    int32_t B, L, H, F;   /* L = tokens in THIS call (0 allowed: state is passed through)       */
+    int32_t B, L, H, F;   /* L = tokens in THIS call (0 allowed: state is passed through).
+                             One call spans at most 2^18 tiles: B * ceil(L/256) * ceil(H*F/32)
+                             forward, B * ceil(L/128) * ceil(H*F/32) backward; beyond that
+                             CAWN_EUNSUPPORTED (pass the sequence in chunks: state_in/state_out) */
     int32_t conv_k;       /* 0 = no conv front-end; 1..4 taps (paper: 3; benchmark configs: 4)  */
     int32_t amp_mode;     /* 0 amplitude = magnitude stream; 1 = min(softplus(.), 10), Sec. 3.3 */
     int32_t gate_mode;    /* 0 per-lane threshold on |a| (cawn_phase_accumulate_fwd/_bwd);

@@ -536,6 +536,9 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     if (d->ret_mode == 1 ? (!ret || !ret_bias) : !gamma) return CAWN_EINVAL;
     if (d->gate_mode == 1 && !valve) return CAWN_EINVAL;
     if (d->conv_k > 0 && !conv_w) return CAWN_EINVAL;
+    // tile indices and tickets are bounded: B x (tiles per sequence) x (32-lane blocks) <= 2^18 per call
+    if ((unsigned long long)d->B * ((d->L + FwdGeom::TILE_T - 1) / FwdGeom::TILE_T) * ((J + FwdLPR - 1) / FwdLPR) > MAX_TILES)
+        return CAWN_EUNSUPPORTED;
     if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;
@@ -678,6 +681,8 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     if (d->gate_mode == 1 && !valve) return CAWN_EINVAL;
     if (kc > 0 && !conv_w) return CAWN_EINVAL;
     if ((dgamma || dtheta || d->ret_mode == 1) && !ckpt) return CAWN_EINVAL;
+    // tile indices and tickets are bounded: B x (tiles per sequence) x (32-lane blocks) <= 2^18 per call
+    if ((unsigned long long)d->B * w.nT * ((J + BwdLPR - 1) / BwdLPR) > MAX_TILES) return CAWN_EUNSUPPORTED;
     if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
     const long long ist = d->in_stride_t ? d->in_stride_t : J, isb = d->in_stride_b ? d->in_stride_b : (long long)d->L * J;
     const long long ost = d->out_stride_t ? d->out_stride_t : J, osb = d->out_stride_b ? d->out_stride_b : (long long)d->L * J;

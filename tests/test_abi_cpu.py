@@ -84,6 +84,11 @@ def test_host_side_argument_checks_reject_before_any_launch():
     a2 = [fake] * 4 + [fake, fake, null, fake, fake, null, null, null]
     assert L.cawn_phase_accumulate_fwd(C.byref(d), *a2, fake, 16, null) == K.CAWN_EWORKSPACE
     assert L.cawn_phase_accumulate_fwd(C.byref(d), *a2, C.c_void_p(0x1004), 1 << 30, null) == K.CAWN_EWORKSPACE
+    # more tiles than a call may have (2^18): refused whatever the workspace
+    long_fwd = K.make_desc(1, 256 * (1 << 18) + 1, 1, 32)
+    assert L.cawn_phase_accumulate_fwd(C.byref(long_fwd), *a2, fake, 1 << 62, null) == K.CAWN_EUNSUPPORTED
+    ok_fwd = K.make_desc(1, 256 * (1 << 18), 1, 32)                # exactly at the limit: only the fake workspace is short
+    assert L.cawn_phase_accumulate_fwd(C.byref(ok_fwd), *a2, fake, 16, null) == K.CAWN_EWORKSPACE
     strided = K.make_desc(2, 128, 2, 16, in_stride_t=8)           # stride shorter than a row
     assert L.cawn_phase_accumulate_fwd(C.byref(strided), *a2, fake, 1 << 30, null) == K.CAWN_EINVAL
     assert L.cawn_syntax_conv(C.byref(K.make_desc(1, 4, 1, 1, conv_k=0)), 8, *([fake] * 6), null) == K.CAWN_EINVAL

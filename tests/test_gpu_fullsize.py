@@ -259,3 +259,34 @@ def test_cfg3_training_step_full_size_valve_and_retention(valve, ret):
             errs["dgamma"] = G.rel_err(dg.cpu().numpy()[sl], ob["dgamma"])
         bad = {k: v for k, v in errs.items() if not v <= TOL}
         assert not bad, (h, bad, errs)
+
+
+def test_one_call_over_two_million_tokens_forward_and_backward():
+    """A single call of 2^21 tokens on one 32-lane block: one chain of 8192 forward and 16384 backward
+    tiles (1/16 of the most a call may span), retention up to 0.99999 so that the far past still weighs.
+    All 32 lanes against the oracle: outputs, carried state, input and parameter gradients."""
+    import torch
+    import gpu_util as G
+    B, L, H, F, Kc = 1, 1 << 21, 1, 32, 4
+    J = H * F
+    r = np.random.Generator(np.random.PCG64(4250 + 96))
+    d = dict(mag=r.standard_normal((B, L, J), dtype=np.float32), ang=r.standard_normal((B, L, J), dtype=np.float32),
+             gamma=r.uniform(0.999, 0.99999, J).astype(np.float32), theta=O.theta_init(H, F),
+             conv_w=(r.standard_normal((2, J, Kc)) / 2).astype(np.float32), conv_b=np.zeros((2, J), np.float32),
+             dz_re=r.standard_normal((B, L, J), dtype=np.float32), dz_im=r.standard_normal((B, L, J), dtype=np.float32))
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=0.1)
+    of = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"], want_gate=False)
+    ob = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], d["dz_re"], d["dz_im"], conv_w=d["conv_w"],
+                     conv_b=d["conv_b"])
+    fw = G.run_fwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, want_mask=False)
+    assert max(G.rel_err(fw["z_re"], of["z_re"]), G.rel_err(fw["z_im"], of["z_im"])) <= TOL
+    assert G.rel_err(G.unpack_state(fw["state_out"], B, J, Kc)[0], of["scan_out"]) <= TOL
+    # the last stretch on its own terms (the rms floor of the whole tensor must not hide a drift)
+    assert G.rel_err(fw["z_re"][:, -4096:], of["z_re"][:, -4096:]) <= TOL
+    out = G.run_fwd_bwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1)
+    errs = {k: G.rel_err(out[k], ob[k]) for k in ("dmag", "dang", "dgamma", "dtheta", "dconv_w", "dconv_b")}
+    errs["dmag_head"] = G.rel_err(out["dmag"][:, :4096], ob["dmag"][:, :4096])
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, (bad, errs)
+    del fw, out
+    torch.cuda.empty_cache()
