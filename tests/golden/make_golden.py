@@ -1,5 +1,7 @@
 """Writes tests/golden/cfg1_oracle_samples.txt: sampled fp64 oracle outputs for the tiny
-configuration (B=1, H=2, F=16, L=256, seed 4250).  Calls only oracle/ and the seeded input module.
+configuration (B=1, H=2, F=16, L=256, seed 4250), in the threshold mode and with the per-head valve,
+the data-dependent retention and the softplus amplitude together ("paper_" rows).  Calls only oracle/
+and the seeded input module.
 
 The paper prints no worked numeric example for this path (no table or figure gives values of the
 phase state), so there is nothing of the paper's to store here; this file is a regression anchor for
@@ -36,6 +38,26 @@ def samples():
         rows.append(("dtheta", -1, j, g["dtheta"][j]))
         rows.append(("scan_re", -1, j, f["scan_out"][0, 0, j]))
     rows.append(("gate_open_count", -1, -1, float(f["gate"].sum())))
+    # the same inputs through the per-head valve and the data-dependent retention (Sec. 3.3); their
+    # logits are drawn here from a generator of their own, after and apart from the workload's draws
+    r = np.random.Generator(np.random.PCG64(wl.seed + 1000))
+    valve = (-3.9 + 3.0 * r.standard_normal((wl.B, wl.L, wl.H))).astype(np.float32)
+    ret = (-2.0 + 1.5 * r.standard_normal((wl.B, wl.L, wl.H))).astype(np.float32)
+    rbias = np.linspace(3.0, 0.0, wl.F).astype(np.float32)
+    cfg2 = O.Cfg(wl.B, wl.L, wl.H, wl.F, conv_k=wl.conv_k, gate_mode=1, ret_mode=1, amp_mode=1)
+    kw = dict(conv_w=d["conv_w"], conv_b=d["conv_b"], valve=valve, ret=ret, ret_bias=rbias)
+    f2 = O.phase_fwd(cfg2, d["mag"], d["ang"], None, d["theta"], **kw)
+    g2 = O.phase_bwd(cfg2, d["mag"], d["ang"], None, d["theta"], d["dz_re"], d["dz_im"], **kw)
+    for t, j in ((0, 0), (17, 31), (128, 7), (255, 16)):
+        rows.append(("paper_z_re", t, j, f2["z_re"][0, t, j]))
+        rows.append(("paper_z_im", t, j, f2["z_im"][0, t, j]))
+        rows.append(("paper_dmag", t, j, g2["dmag"][0, t, j]))
+        rows.append(("paper_dang", t, j, g2["dang"][0, t, j]))
+    for t, h in ((0, 0), (100, 1), (255, 0)):
+        rows.append(("paper_dvalve", t, h, g2["dvalve"][0, t, h]))
+        rows.append(("paper_dret", t, h, g2["dret"][0, t, h]))
+    rows.append(("paper_dtheta", -1, 13, g2["dtheta"][13]))
+    rows.append(("paper_valves_open", -1, -1, float(f2["gate"].sum())))
     return rows
 
 
