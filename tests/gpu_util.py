@@ -122,7 +122,7 @@ def mask_from_gate(gate):
 def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
                 grad_clamp=100.0, state_in=None, dstate_out=None, want_param=True, want_dstate=True,
                 accumulate=0, preset=None, ws=None, valve=None, valve_eps=0.001, want_dvalve=True,
-                ret=None, ret_bias=None, want_dret=True):
+                ret=None, ret_bias=None, want_dret=True, concat=False):
     """Forward (to get the checkpoints) then backward through the C ABI.  inp additionally holds
     dz_re, dz_im [B,L,J].  Returns dict of numpy arrays: dmag, dang, dgamma, dtheta, dconv_w, dconv_b,
     dstate_in (flat blob)."""
@@ -139,6 +139,16 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
     cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
     z_re = torch.empty((B, max(L, 1), J), device=DEV)
     z_im = torch.empty((B, max(L, 1), J), device=DEV)
+    if concat:
+        # Concat layout (Sec. 3.5): the two planes of every activation pair share rows of 2 J elements,
+        # inputs [mag | ang], outputs [Z_re | Z_im], and their gradients likewise
+        Lr = max(L, 1)
+        xin = torch.cat([mag, ang], dim=2).contiguous()
+        mag, ang = xin[:, :, :J], xin[:, :, J:]
+        zc = torch.empty((B, Lr, 2 * J), device=DEV)
+        z_re, z_im = zc[:, :, :J], zc[:, :, J:]
+        d.in_stride_t, d.in_stride_b = 2 * J, Lr * 2 * J
+        d.out_stride_t, d.out_stride_b = 2 * J, Lr * 2 * J
     st_in = dev(state_in)
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
     ws = ws if ws is not None else Workspaces.get(d)
@@ -153,6 +163,11 @@ def run_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=
     dz_re, dz_im = dev(inp["dz_re"][:, :L]), dev(inp["dz_im"][:, :L])
     dmag = torch.full((B, max(L, 1), J), float("nan"), device=DEV)
     dang = torch.full((B, max(L, 1), J), float("nan"), device=DEV)
+    if concat:
+        dzc = torch.cat([dz_re, dz_im], dim=2).contiguous()
+        dz_re, dz_im = dzc[:, :, :J], dzc[:, :, J:]
+        dxc = torch.full((B, max(L, 1), 2 * J), float("nan"), device=DEV)
+        dmag, dang = dxc[:, :, :J], dxc[:, :, J:]
     nstate = K.cawn_state_bytes(d) // 4
     fill = float("nan") if preset is None else preset
     dgamma = torch.full((J,), fill, device=DEV) if want_param and ret is None else None
@@ -268,7 +283,8 @@ def run_fwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, state_in=N
 
 
 def run_fwd_bwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, grad_clamp=100.0, state_in=None,
-                     dstate_out=None, want_param=True, valve=None, ret=None, ret_bias=None, valve_eps=0.001):
+                     dstate_out=None, want_param=True, valve=None, ret=None, ret_bias=None, valve_eps=0.001,
+                     concat=False):
     """Forward (for the checkpoints) then backward, bfloat16 activations.  dmag, dang come back as float32
     (widened from what the kernel stored); the other gradients are fp32."""
     J = H * F
@@ -284,13 +300,25 @@ def run_fwd_bwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, grad_c
     rb = dev(ret_bias)
     z_re = torch.empty((B, max(L, 1), J), device=DEV, dtype=torch.bfloat16)
     z_im = torch.empty((B, max(L, 1), J), device=DEV, dtype=torch.bfloat16)
+    dmag = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
+    dang = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
+    if concat:      # rows of 2 J elements shared by each activation pair (Sec. 3.5)
+        Lr = max(L, 1)
+        xin = torch.cat([mag, ang], dim=2).contiguous()
+        mag, ang = xin[:, :, :J], xin[:, :, J:]
+        zc = torch.empty((B, Lr, 2 * J), device=DEV, dtype=torch.bfloat16)
+        z_re, z_im = zc[:, :, :J], zc[:, :, J:]
+        dzc = torch.cat([dz_re, dz_im], dim=2).contiguous()
+        dz_re, dz_im = dzc[:, :, :J], dzc[:, :, J:]
+        dxc = torch.full((B, Lr, 2 * J), float("nan"), device=DEV, dtype=torch.bfloat16)
+        dmag, dang = dxc[:, :, :J], dxc[:, :, J:]
+        d.in_stride_t, d.in_stride_b = 2 * J, Lr * 2 * J
+        d.out_stride_t, d.out_stride_b = 2 * J, Lr * 2 * J
     st_in = dev(state_in)
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
     ws = Workspaces.get(d)
     K.check(K.cawn_phase_accumulate_bf16_fwd(d, mag, ang, vl, rt, rb, gamma, theta, cw, cb, st_in, z_re, z_im, None, ckpt,
                                              None, ws))
-    dmag = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
-    dang = torch.full((B, max(L, 1), J), float("nan"), device=DEV, dtype=torch.bfloat16)
     nstate = K.cawn_state_bytes(d) // 4
     nanv = lambda *shape: torch.full(shape, float("nan"), device=DEV)
     dgamma = nanv(J) if want_param and ret is None else None

@@ -198,3 +198,15 @@ def test_bf16_backward_without_parameter_gradients():
     B, L, H, F, Kc = 2, 400, 2, 64, 4
     d = _inputs(B, L, H, F, Kc, 9200)
     _check_bwd(B, L, H, F, Kc, d, want_param=False)
+
+
+@pytest.mark.parametrize("H,F,Kc", [(2, 64, 4), (3, 32, 0), (1, 24, 2)])
+def test_bf16_backward_concat_layout(H, F, Kc):
+    # rows of 2 J bf16 elements shared by each activation pair and its gradients (Sec. 3.5), with state
+    B, L = 2, 333
+    J = H * F
+    d = _inputs(B, L, H, F, Kc, 9300 + H + F + Kc)
+    r = np.random.Generator(np.random.PCG64(10))
+    k1 = max(Kc - 1, 0)
+    state = (r.standard_normal((B, 2, J)).astype(np.float32), r.standard_normal((B, k1, 2, J)).astype(np.float32))
+    _check_bwd(B, L, H, F, Kc, d, state=state, concat=True)

@@ -35,7 +35,7 @@ def _inputs(B, L, H, F, Kc, seed, gamma=(0.9, 0.999), bias=True, dz_scale=1.0):
     return d
 
 
-def _check(B, L, H, F, Kc, d, tau=0.1, amp_mode=0, with_state=False, grad_clamp=100.0, conv_clamp=50.0, seed=1):
+def _check(B, L, H, F, Kc, d, tau=0.1, amp_mode=0, with_state=False, grad_clamp=100.0, conv_clamp=50.0, seed=1, **kw):
     G = _gpu()
     J = H * F
     scan_in = tail_in = blob = dscan = dtail = dblob = None
@@ -53,7 +53,7 @@ def _check(B, L, H, F, Kc, d, tau=0.1, amp_mode=0, with_state=False, grad_clamp=
                       dscan_out=None if dscan is None else dscan.astype(np.float64),
                       dtail_out=None if (dtail is None or Kc <= 1) else dtail.astype(np.float64))
     out = G.run_fwd_bwd(d, B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, grad_clamp=grad_clamp,
-                        conv_clamp=conv_clamp, state_in=blob, dstate_out=dblob)
+                        conv_clamp=conv_clamp, state_in=blob, dstate_out=dblob, **kw)
     errs = {}
     for k in ("dmag", "dang", "dgamma", "dtheta"):
         errs[k] = G.rel_err(out[k], ora[k])
@@ -189,3 +189,13 @@ def test_zero_length_backward_passes_state_gradient_through():
                                         None, None, dg, None, None, None, dsi, None))
     torch.cuda.synchronize()
     assert torch.equal(dsi, dso) and not dg.any()
+
+
+@pytest.mark.parametrize("H,F,Kc", [(2, 64, 4), (3, 32, 0), (1, 24, 3)])
+def test_concat_layout_inputs_outputs_and_their_gradients(H, F, Kc):
+    """Sec. 3.5: Z is the concatenation of the real and the imaginary plane.  Here every activation pair
+    shares rows of 2 J elements ([mag | ang], [Z_re | Z_im], and the gradients likewise): strided rows
+    in the staging of the inputs and of the upstream gradients and in every store, with state."""
+    B, L = 2, 333
+    d = _inputs(B, L, H, F, Kc, 2600 + H + F + Kc)
+    _check(B, L, H, F, Kc, d, with_state=True, concat=True)
