@@ -28,6 +28,8 @@
  *     lane (clamped like every returned per-element gradient), chained through the sigmoid and
  *     summed over the harmonics of a head into d r[t][h].  b_k is static: no gradient.
  *   - Output clamp (Sec. 3.4 clamp equation), Concat layout (Sec. 3.5).
+ *   - Depth-wise harmonic convolution of the output along the harmonics of each head
+ *     (Sec. 3.6), as a function of its own: oracle_harmonic_conv.
  *   - State passing (Sec. 3.7 / Sec. 5 chunked prefill): the phase state plus the last
  *     conv_k-1 pre-conv rows.
  *   - Backward (Sec. 3.4 last paragraph, Sec. 3.5): reverse-time adjoint; clamp passes the
@@ -158,6 +160,45 @@ int oracle_syntax_conv(int B, int L, int C, int Kc, double conv_clamp, const flo
                         v = 0.0f;
                     hist_out[((size_t)b * (Kc - 1) + r) * C + c] = v;
                 }
+    return 0;
+}
+
+/*
+ * Depth-wise harmonic convolution on the path's output (Sec. 3.6, "Convolutional SwiGLU Ear", the
+ * step before the dense projection): the concatenated state of a token is read as 2 H channels
+ * (plane p = real / imaginary, head h) of F positions (the harmonics k of the head), and each
+ * channel is convolved along k with its own Kh taps and bias.
+ *   out[b][t][p][h][k] = bias[p][h] + sum_{i < Kh} w[p][h][i] * Z[b][t][p][h][k + i - (Kh-1)/2],
+ *   positions outside 0 .. F-1 read as zero.
+ * Readings where the paper is silent: Kh is odd and the padding symmetric ("same": every harmonic
+ * keeps a position, harmonics are not a causal axis); taps are applied as deep-learning
+ * libraries apply a conv1d (tap i multiplies position k + i - pad, no flip); one bias per channel.
+ *   z_re, z_im [B][L][H*F] fp64; w [2][H][Kh], bias [2][H] fp32 (bias NULL: zeros);
+ *   o_re, o_im [B][L][H*F] fp64.
+ */
+int oracle_harmonic_conv(int B, int L, int H, int F, int Kh, const double *z_re, const double *z_im,
+                         const float *w, const float *bias, double *o_re, double *o_im)
+{
+    if (B <= 0 || L < 0 || H <= 0 || F <= 0 || Kh < 1 || Kh % 2 == 0) return -1;
+    const int pad = (Kh - 1) / 2;
+    const size_t J = (size_t)H * F;
+    for (int p = 0; p < 2; ++p) {
+        const double *z = p == 0 ? z_re : z_im;
+        double *o = p == 0 ? o_re : o_im;
+        for (int b = 0; b < B; ++b)
+            for (int t = 0; t < L; ++t)
+                for (int h = 0; h < H; ++h)
+                    for (int k = 0; k < F; ++k) {
+                        double acc = bias ? (double)bias[(size_t)p * H + h] : 0.0;
+                        for (int i = 0; i < Kh; ++i) {
+                            const int kk = k + i - pad;
+                            if (kk < 0 || kk >= F) continue;
+                            acc += (double)w[((size_t)p * H + h) * Kh + i] *
+                                   z[((size_t)b * L + t) * J + (size_t)h * F + kk];
+                        }
+                        o[((size_t)b * L + t) * J + (size_t)h * F + k] = acc;
+                    }
+    }
     return 0;
 }
 

@@ -134,6 +134,26 @@ def syntax_conv(x, w, bias=None, hist_in=None, conv_clamp=50.0, want_hist=True):
     return y, hist
 
 
+def harmonic_conv(z_re, z_im, H: int, F: int, w, bias=None):
+    """Depth-wise harmonic convolution (Sec. 3.6): z_re, z_im [B,L,H*F] f64, w [2,H,Kh], bias [2,H]
+    -> (o_re, o_im) f64.  Channel = (plane, head), positions = the head's harmonics, zero padding
+    on both sides, tap i multiplies position k + i - (Kh-1)/2."""
+    z_re = np.ascontiguousarray(z_re, dtype=np.float64)
+    z_im = np.ascontiguousarray(z_im, dtype=np.float64)
+    B, L, J = z_re.shape
+    assert J == H * F and z_im.shape == z_re.shape
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    Kh = w.shape[2]
+    assert w.shape == (2, H, Kh)
+    bias = _f32(bias, (2, H))
+    o_re = np.empty_like(z_re)
+    o_im = np.empty_like(z_im)
+    rc = lib().oracle_harmonic_conv(C.c_int(B), C.c_int(L), C.c_int(H), C.c_int(F), C.c_int(Kh),
+                                    _p(z_re), _p(z_im), _p(w), _p(bias), _p(o_re), _p(o_im))
+    assert rc == 0, rc
+    return o_re, o_im
+
+
 def _ret_args(cfg: Cfg, ret, ret_bias):
     if cfg.ret_mode != 1:
         return None, None

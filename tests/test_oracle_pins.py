@@ -773,6 +773,77 @@ def test_theta_init_endpoints_and_ratio():
     np.testing.assert_allclose(th[-1], 10.0 ** (-8.0 * (J - 1) / J), rtol=1e-7)
 
 
+# ---------------------------------------------------------------- harmonic convolution (Sec. 3.6)
+def test_harmonic_conv_by_hand():
+    """One head of four harmonics, taps (10, 1, 0.1): position k takes 10 x its lower neighbour, itself
+    and 0.1 x its upper neighbour, zeros beyond both ends.  Flipped taps, a shifted window or a
+    dropped bias each change the printed values."""
+    z = np.array([1.0, 2.0, 3.0, 4.0]).reshape(1, 1, 4)
+    w = np.zeros((2, 1, 3), np.float32)
+    w[0, 0] = [10.0, 1.0, 0.125]
+    w[1, 0] = [0.0, 0.0, 1.0]
+    bias = np.array([[0.5], [-1.0]], np.float32)
+    o_re, o_im = O.harmonic_conv(z, 2 * z, 1, 4, w, bias)
+    np.testing.assert_array_equal(o_re[0, 0], [1.75, 12.875, 24.0, 34.5])
+    np.testing.assert_array_equal(o_im[0, 0], [3.0, 5.0, 7.0, -1.0])
+
+
+@pytest.mark.parametrize("Kh", [1, 3, 5])
+def test_harmonic_conv_matches_library_correlation(Kh):
+    """Against scipy's 1-D correlation with zero fill, channel by channel: every (plane, head) uses
+    its own taps and bias, and nothing crosses from one head's harmonics into the next head's."""
+    from scipy.ndimage import correlate1d
+    r = rng_(900 + Kh)
+    B, L, H, F = 2, 5, 3, 8
+    z_re = r.standard_normal((B, L, H * F))
+    z_im = r.standard_normal((B, L, H * F))
+    w = r.standard_normal((2, H, Kh)).astype(np.float32)
+    bias = r.standard_normal((2, H)).astype(np.float32)
+    o_re, o_im = O.harmonic_conv(z_re, z_im, H, F, w, bias)
+    for p_, (z, o) in enumerate(((z_re, o_re), (z_im, o_im))):
+        for h in range(H):
+            ref = correlate1d(z[:, :, h * F:(h + 1) * F], w[p_, h].astype(np.float64), axis=2,
+                              mode="constant", cval=0.0) + float(bias[p_, h])
+            np.testing.assert_allclose(o[:, :, h * F:(h + 1) * F], ref, rtol=0, atol=1e-13)
+
+
+def test_harmonic_conv_is_numpy_convolution_with_flipped_taps():
+    """The textbook convolution flips its kernel: np.convolve(z, taps reversed, 'same') is the same map."""
+    r = rng_(911)
+    F = 16
+    z = r.standard_normal(F)
+    w = r.standard_normal(3).astype(np.float32)
+    o_re, o_im = O.harmonic_conv(z.reshape(1, 1, F), np.zeros((1, 1, F)), 1, F,
+                                 np.stack([w, w]).reshape(2, 1, 3))
+    np.testing.assert_allclose(o_re[0, 0], np.convolve(z, w[::-1].astype(np.float64), mode="same"), atol=1e-14)
+    np.testing.assert_array_equal(o_im, 0.0)
+
+
+def test_harmonic_conv_heads_and_planes_stay_apart():
+    """An impulse on the last harmonic of head 0 (real plane) reaches harmonics F-2 and F-1 of head 0
+    only; the centre tap alone is the identity; the bias shows on every position of its channel."""
+    H, F = 2, 8
+    z_re = np.zeros((1, 1, H * F))
+    z_re[0, 0, F - 1] = 1.0
+    w = np.zeros((2, H, 3), np.float32)
+    w[0, 0] = [2.0, 3.0, 5.0]
+    w[0, 1] = [7.0, 7.0, 7.0]
+    w[1, :] = [9.0, 9.0, 9.0]
+    o_re, o_im = O.harmonic_conv(z_re, np.zeros_like(z_re), H, F, w)
+    want = np.zeros(H * F)
+    want[F - 2], want[F - 1] = 5.0, 3.0       # position k sees the impulse at k+1 through tap 2
+    np.testing.assert_array_equal(o_re[0, 0], want)
+    np.testing.assert_array_equal(o_im, 0.0)
+    ident = np.zeros((2, H, 3), np.float32)
+    ident[:, :, 1] = 1.0
+    bias = np.array([[1.0, 2.0], [3.0, 4.0]], np.float32)
+    r = rng_(912)
+    a, b = r.standard_normal((2, 3, H * F)), r.standard_normal((2, 3, H * F))
+    o_re, o_im = O.harmonic_conv(a, b, H, F, ident, bias)
+    np.testing.assert_array_equal(o_re, a + np.repeat(bias[0].astype(np.float64), F))
+    np.testing.assert_array_equal(o_im, b + np.repeat(bias[1].astype(np.float64), F))
+
+
 # ------------------------------------------------------------------------------- regression anchor
 def test_oracle_matches_its_stored_samples():
     """tests/golden/cfg1_oracle_samples.txt was written by tests/golden/make_golden.py from the oracle
