@@ -68,7 +68,9 @@ typedef struct cawn_desc {
     int32_t ret_mode;     /* 0 constant per-lane retention gamma[j]; 1 data-dependent retention
                              sigmoid(ret[t][h] + ret_bias[k]) (cawn_phase_accumulate_ret_fwd/_bwd; same
                              head widths as gate_mode 1)                                        */
-    int32_t reserved_;    /* 0 */
+    int32_t hconv_k;      /* 0: none; 3: the depth-wise harmonic convolution is applied to the output
+                             before it is stored (cawn_phase_accumulate_hconv_fwd only; every
+                             other call wants 0, CAWN_EINVAL otherwise)                          */
     int64_t in_stride_b, in_stride_t;   /* element strides of mag/ang/dmag/dang; 0 = dense
                                            (t stride J, b stride L*J); lane stride is always 1;
                                            t strides above 2^21 elements: CAWN_EUNSUPPORTED     */
@@ -250,6 +252,35 @@ int cawn_phase_accumulate_bf16_fwd(const cawn_desc *d, const uint16_t *mag, cons
                                    const float *conv_b, const void *state_in, uint16_t *z_re,
                                    uint16_t *z_im, void *state_out, void *ckpt, uint32_t *gate_mask,
                                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Forward with the depth-wise harmonic convolution fused behind the output clamp (the first step of
+ * the paper's "Convolutional SwiGLU Ear", Sec. 3.6; forward only: prefill and decoding).  The
+ * clamped state of a token is read as 2 H channels (plane p = real / imaginary, head h) of F
+ * positions (the harmonics k of the head) and every channel is convolved along k with its own three
+ * taps and bias, zeros beyond both ends of the head:
+ *   zc_p[b][t][h*F + k] = hconv_b[p][h] + sum_{i<3} hconv_w[p][h][i] * z_p[b][t][h*F + k + i - 1].
+ * The paper gives neither the kernel size nor the padding of this convolution; three taps (as in its
+ * temporal convolution), symmetric zero padding and one bias per channel are this library's reading.
+ * d->hconv_k must be 3.  F must divide 32, or be 64, 128 or 256, and be at least 32 with gate_mode 1
+ * or ret_mode 1 (CAWN_EUNSUPPORTED otherwise).
+ *   hconv_w  device [2][H][3] fp32;  hconv_b  device [2][H] fp32 or NULL (zeros)
+ *   zc_re, zc_im  outputs, laid out like z_re, z_im of cawn_phase_accumulate_fwd
+ *   activations_bf16  0: mag, ang, zc_re, zc_im are fp32;  1: bfloat16 with the rules of
+ *                     cawn_phase_accumulate_bf16_fwd (the convolution runs in fp32 on the unrounded
+ *                     clamped state; only its result is rounded)
+ * state_out, ckpt and gate_mask are those of the unconvolved recurrence.  valve / ret / ret_bias /
+ * gamma are selected by d->gate_mode and d->ret_mode as in cawn_phase_accumulate_bf16_fwd.  The lane
+ * constants that d->lane_consts_cached keeps include hconv_w and hconv_b; the workspace size depends
+ * on d->hconv_k.  Everything else as in cawn_phase_accumulate_fwd.
+ */
+int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const void *ang,
+                                    const float *valve, const float *ret, const float *ret_bias,
+                                    const float *gamma, const float *theta, const float *conv_w,
+                                    const float *conv_b, const float *hconv_w, const float *hconv_b,
+                                    const void *state_in, void *zc_re, void *zc_im, void *state_out,
+                                    void *ckpt, uint32_t *gate_mask, void *workspace,
+                                    size_t workspace_bytes, int32_t activations_bf16, void *stream);
 
 /*
  * Backward of cawn_phase_accumulate_bf16_fwd: mag, ang, dz_re, dz_im are read and dmag, dang are

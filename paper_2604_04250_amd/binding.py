@@ -20,7 +20,7 @@ CAWN_OK, CAWN_EINVAL, CAWN_EUNSUPPORTED, CAWN_EWORKSPACE, CAWN_ELAUNCH, CAWN_ETI
 EXPORTS = ["cawn_state_bytes", "cawn_workspace_bytes", "cawn_ckpt_bytes", "cawn_tile_len",
            "cawn_status_string", "cawn_workspace_init", "cawn_workspace_status", "cawn_set_spin_limit",
            "cawn_theta_init", "cawn_syntax_conv", "cawn_phase_accumulate_fwd",
-           "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_bf16_bwd", "cawn_phase_accumulate_bf16_fwd", "cawn_phase_accumulate_ret_bwd", "cawn_phase_accumulate_ret_fwd",
+           "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_bf16_bwd", "cawn_phase_accumulate_bf16_fwd", "cawn_phase_accumulate_hconv_fwd", "cawn_phase_accumulate_ret_bwd", "cawn_phase_accumulate_ret_fwd",
            "cawn_phase_accumulate_valve_fwd",
            "cawn_phase_accumulate_valve_bwd"]
 
@@ -31,7 +31,7 @@ class cawn_desc(C.Structure):
                 ("gate_tau", C.c_float), ("conv_clamp", C.c_float), ("out_clamp", C.c_float),
                 ("grad_clamp", C.c_float), ("accumulate_param_grads", C.c_int32),
                 ("lane_consts_cached", C.c_int32), ("valve_eps", C.c_float),
-                ("ret_mode", C.c_int32), ("reserved_", C.c_int32),
+                ("ret_mode", C.c_int32), ("hconv_k", C.c_int32),
                 ("in_stride_b", C.c_int64), ("in_stride_t", C.c_int64),
                 ("out_stride_b", C.c_int64), ("out_stride_t", C.c_int64)]
 
@@ -43,9 +43,9 @@ class cawn_desc(C.Structure):
 def make_desc(B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
               grad_clamp=100.0, accumulate_param_grads=0, lane_consts_cached=0, in_stride_b=0,
               in_stride_t=0, out_stride_b=0, out_stride_t=0, gate_mode=0, valve_eps=0.001,
-              ret_mode=0) -> cawn_desc:
+              ret_mode=0, hconv_k=0) -> cawn_desc:
     return cawn_desc(B, L, H, F, conv_k, amp_mode, gate_mode, gate_tau, conv_clamp, out_clamp, grad_clamp,
-                     accumulate_param_grads, lane_consts_cached, valve_eps, ret_mode, 0, in_stride_b, in_stride_t,
+                     accumulate_param_grads, lane_consts_cached, valve_eps, ret_mode, hconv_k, in_stride_b, in_stride_t,
                      out_stride_b, out_stride_t)
 
 
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
                                                      [C.c_size_t, C.c_void_p])
         L.cawn_phase_accumulate_bf16_bwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 24 +
                                                      [C.c_size_t, C.c_void_p])
+        L.cawn_phase_accumulate_hconv_fwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 18 +
+                                                      [C.c_size_t, C.c_int32, C.c_void_p])
         _lib = L
     return _lib
 
@@ -224,6 +226,18 @@ def cawn_phase_accumulate_bf16_fwd(d, mag, ang, valve, ret, ret_bias, gamma, the
         _ptr(conv_w), _ptr(conv_b), _ptr(state_in), _ptr(z_re), _ptr(z_im), _ptr(state_out), _ptr(ckpt),
         _ptr(gate_mask), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(stream))
+
+
+def cawn_phase_accumulate_hconv_fwd(d, mag, ang, valve, ret, ret_bias, gamma, theta, conv_w, conv_b, hconv_w,
+                                    hconv_b, state_in, zc_re, zc_im, state_out, ckpt, gate_mask, workspace,
+                                    activations_bf16=0, stream=None) -> int:
+    """mag, ang, zc_re, zc_im: fp32 tensors, or torch.bfloat16 with activations_bf16=1."""
+    return lib().cawn_phase_accumulate_hconv_fwd(
+        C.byref(d), _ptr(mag), _ptr(ang), _ptr(valve), _ptr(ret), _ptr(ret_bias), _ptr(gamma), _ptr(theta),
+        _ptr(conv_w), _ptr(conv_b), _ptr(hconv_w), _ptr(hconv_b), _ptr(state_in), _ptr(zc_re), _ptr(zc_im),
+        _ptr(state_out), _ptr(ckpt), _ptr(gate_mask), _ptr(workspace),
+        workspace.numel() * workspace.element_size() if workspace is not None else 0,
+        C.c_int32(activations_bf16), _stream(stream))
 
 
 def cawn_phase_accumulate_bf16_bwd(d, mag, ang, valve, ret, ret_bias, gamma, theta, conv_w, conv_b, state_in, ckpt,

@@ -20,6 +20,7 @@ static bool desc_ok(const cawn_desc *d)
     if ((int64_t)d->H * d->F > (1 << 24)) return false;
     if (d->conv_k < 0) return false;
     if (d->ret_mode != 0 && d->ret_mode != 1) return false;
+    if (d->hconv_k != 0 && d->hconv_k != 3) return false;
     return true;
 }
 
@@ -34,7 +35,7 @@ static WsLayout make_layout(const cawn_desc *d)
     const size_t tiles_rows = (size_t)d->B * (w.nT > 0 ? w.nT : 1);
     size_t o = sizeof(WsHeader);
     w.off_table = o;
-    o = align_up(o + (size_t)lane_rows(kc) * w.Jp * sizeof(float), 256);
+    o = align_up(o + (size_t)lane_rows(kc, d->hconv_k != 0) * w.Jp * sizeof(float), 256);
     w.off_agg = o;      // published words are 8 bytes each: value + tag
     o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_pre = o;
@@ -227,6 +228,7 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t n)
 __global__ void lane_table_kernel(const float *__restrict__ gamma, const float *__restrict__ theta,
                                   const float *__restrict__ conv_w, const float *__restrict__ conv_b,
                                   const float *__restrict__ ret_bias, int F,
+                                  const float *__restrict__ hconv_w, const float *__restrict__ hconv_b,
                                   float *__restrict__ table, int J, int Jp, int conv_k)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
@@ -278,6 +280,14 @@ __global__ void lane_table_kernel(const float *__restrict__ gamma, const float *
         for (int i = 0; i < conv_k; ++i)
             table[(size_t)(R_W0 + sidx * conv_k + i) * Jp + j] =
                 live ? conv_w[((size_t)sidx * J + j) * conv_k + i] : 0.0f;
+    if (hconv_w) {     // harmonic convolution: the taps [2][H][3] and bias [2][H] of the lane's head, per plane
+        const int H = J / F, h = live ? j / F : 0;
+        for (int p = 0; p < 2; ++p) {
+            for (int i = 0; i < 3; ++i)
+                table[(size_t)(R_W0 + 2 * conv_k + 3 * p + i) * Jp + j] = live ? hconv_w[((size_t)p * H + h) * 3 + i] : 0.0f;
+            table[(size_t)(R_W0 + 2 * conv_k + 6 + p) * Jp + j] = live && hconv_b ? hconv_b[(size_t)p * H + h] : 0.0f;
+        }
+    }
 }
 
 // Stand-alone Temporal Syntax Cache: one thread per (channel, run of NS tokens).
@@ -376,12 +386,13 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
 
 static hipError_t build_table(const cawn_desc *d, const WsLayout &w, char *ws, const float *gamma,
                               const float *theta, const float *conv_w, const float *conv_b,
-                              const float *ret_bias, hipStream_t s)
+                              const float *ret_bias, hipStream_t s, const float *hconv_w = nullptr,
+                              const float *hconv_b = nullptr)
 {
     float *table = reinterpret_cast<float *>(ws + w.off_table);
     const int threads = 128;
     hipLaunchKernelGGL(lane_table_kernel, dim3((w.Jp + threads - 1) / threads), dim3(threads), 0, s,
-                       gamma, theta, conv_w, conv_b, ret_bias, d->F, table, w.J, w.Jp, d->conv_k);
+                       gamma, theta, conv_w, conv_b, ret_bias, d->F, hconv_w, hconv_b, table, w.J, w.Jp, d->conv_k);
     return hipGetLastError();
 }
 
@@ -509,9 +520,16 @@ int cawn_syntax_conv(const cawn_desc *d, int32_t C, const float *x, const float 
 static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, const float *valve,
                     const float *ret, const float *ret_bias, const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                     const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
-                    uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream, bool bf16 = false)
+                    uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream, bool bf16 = false,
+                    const float *hconv_w = nullptr, const float *hconv_b = nullptr)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    // the harmonic convolution belongs to its own entry point (which passes the taps)
+    if ((d->hconv_k != 0) != (hconv_w != nullptr)) return CAWN_EINVAL;
+    // heads are whole inside a 32-lane block, or made of whole blocks (and whole inside the 256 lanes of
+    // a short call's workgroup)
+    if (d->hconv_k != 0 && !(d->F <= 32 ? 32 % d->F == 0 : (d->F % 32 == 0 && 256 % d->F == 0))) return CAWN_EUNSUPPORTED;
+    if (d->hconv_k != 0 && (d->gate_mode == 1 || d->ret_mode == 1) && d->F < 32) return CAWN_EUNSUPPORTED;   // LDS
     if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
     if (d->gate_mode == 1 && d->ret_mode == 1 && d->F < 16) return CAWN_EUNSUPPORTED;   // LDS for both logit tiles
     hipStream_t s = (hipStream_t)stream;
@@ -549,6 +567,8 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
 
     FwdArgs a{};
     a.bf16 = bf16 ? 1 : 0;
+    a.hconv = d->hconv_k != 0 ? 1 : 0;
+    a.hcG = d->hconv_k != 0 && d->F > 32 ? d->F / 32 : 1;
     if (d->gate_mode == 1) {
         const float INF = std::numeric_limits<float>::infinity();
         a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
@@ -576,7 +596,7 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     char *ws = reinterpret_cast<char *>(workspace);
     if (!d->lane_consts_cached) {
         if (build_table(d, w, ws, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
-                        d->ret_mode == 1 ? ret_bias : nullptr, s) != hipSuccess) return CAWN_ELAUNCH;
+                        d->ret_mode == 1 ? ret_bias : nullptr, s, hconv_w, hconv_b) != hipSuccess) return CAWN_ELAUNCH;
     }
     a.mag = mag; a.ang = ang;
     a.table = reinterpret_cast<const float *>(ws + w.off_table);
@@ -648,6 +668,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
                     size_t workspace_bytes, void *stream, bool bf16 = false)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
+    if (d->hconv_k != 0) return CAWN_EINVAL;      // the backward takes gradients of the unconvolved output
     if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
     if (d->gate_mode == 1 && d->ret_mode == 1 && d->F < 16) return CAWN_EUNSUPPORTED;   // as in the forward
     hipStream_t s = (hipStream_t)stream;
@@ -818,6 +839,22 @@ int cawn_phase_accumulate_bf16_fwd(const cawn_desc *d, const uint16_t *mag, cons
                     d->ret_mode == 1 ? ret_bias : nullptr, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
                     state_in, reinterpret_cast<float *>(z_re), reinterpret_cast<float *>(z_im), state_out, ckpt,
                     gate_mask, workspace, workspace_bytes, stream, true);
+}
+
+int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const void *ang, const float *valve,
+                                    const float *ret, const float *ret_bias, const float *gamma, const float *theta,
+                                    const float *conv_w, const float *conv_b, const float *hconv_w,
+                                    const float *hconv_b, const void *state_in, void *zc_re, void *zc_im,
+                                    void *state_out, void *ckpt, uint32_t *gate_mask, void *workspace,
+                                    size_t workspace_bytes, int32_t activations_bf16, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->hconv_k != 3 || !hconv_w) return CAWN_EINVAL;
+    return fwd_impl(d, reinterpret_cast<const float *>(mag), reinterpret_cast<const float *>(ang),
+                    d->gate_mode == 1 ? valve : nullptr, d->ret_mode == 1 ? ret : nullptr,
+                    d->ret_mode == 1 ? ret_bias : nullptr, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
+                    state_in, reinterpret_cast<float *>(zc_re), reinterpret_cast<float *>(zc_im), state_out, ckpt,
+                    gate_mask, workspace, workspace_bytes, stream, activations_bf16 != 0, hconv_w, hconv_b);
 }
 
 int cawn_phase_accumulate_bf16_bwd(const cawn_desc *d, const uint16_t *mag, const uint16_t *ang, const float *valve,

@@ -117,10 +117,17 @@ __device__ __forceinline__ void stage_consts(float *sC, const float *table, int 
 // nearest even by the hardware conversion.
 // (with bf16 rows the staged tile is half as large and a third workgroup fits a CU's LDS; the variants
 // without the per-token retentions also fit its registers)
-template <int V, int KC, bool VALVE, bool RET, bool BF>
-__global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVES + 1 : CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
+// HC: the depth-wise harmonic convolution of Sec. 3.6 applied to the clamped output before it is
+// stored: channel = (plane, head), three taps along the harmonics of the head, zeros beyond its ends.
+// Neighbouring harmonics are neighbouring lanes of a row.  A head wider than a lane block (F = 32 G,
+// G > 1) is handled by one workgroup drawing the G tickets of the head's blocks together and taking
+// them in order: the last lane of a block leaves its value and its unfinished output in LDS, and the
+// first lane of the next block completes and stores that output next to its own.
+template <int V, int KC, bool VALVE, bool RET, bool BF, bool HC>
+__global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_FWD_WAVES + 1 : CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
     static_assert(!BF || V == 1, "bf16 activations: one lane per thread");
+    static_assert(!HC || V == 1, "harmonic convolution: one lane per thread");
     constexpr int TILE_T = FwdGeom::TILE_T, NSTEP = FwdGeom::NSTEP, NSEG = FwdGeom::NSEG, LPR = FwdLPR;
     constexpr int JB = V * LPR;
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
@@ -140,13 +147,17 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVE
     };
     __shared__ float sE[NSEG][2][JB];
     __shared__ float sCarry[2][JB];
-    constexpr int NCR = R_W0 - R_LR + 2 * KC;     // staged lane-constant rows
-    __shared__ __attribute__((aligned(16))) float sC[(NCR + 7) / 8 * 8][JB];
+    constexpr int NCR = R_W0 - R_LR + 2 * KC + (HC ? HC_ROWS : 0);     // staged lane-constant rows
+    // (only rows below NCR are ever staged; HC needs the room of the padding)
+    __shared__ __attribute__((aligned(16))) float sC[HC ? NCR : (NCR + 7) / 8 * 8][JB];
     // valve / retention groups per lane block: F >= 8, or F >= 16 with both (LDS: two workgroups per CU)
-    constexpr int GPB_MAX = (VALVE && RET) ? 2 : 4;
+    // (HC: one group, F >= 32 -- the two rows of unfinished outputs take the room)
+    constexpr int GPB_MAX = HC ? 1 : ((VALVE && RET) ? 2 : 4);
     __shared__ float sV[VALVE ? FwdGeom::TILE_T * GPB_MAX : 1];
     __shared__ float sR[RET ? FwdGeom::TILE_T * GPB_MAX : 1];     // retention logits, laid out like sV
     __shared__ float sP[RET ? NSEG : 1][JB];                      // product of each segment's retentions
+    // HC: value and unfinished output of the block's last lane, per token and plane, for the next block
+    __shared__ float sHZ[2][HC ? FwdGeom::TILE_T : 1], sHP[2][HC ? FwdGeom::TILE_T : 1];
     __shared__ uint32_t sTicket[2], sLast, sEpoch;
 
     const int tid = threadIdx.x;
@@ -159,7 +170,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVE
 
     if (tid == 0) {
         const uint32_t e = flag_load(&a.hdr->epoch);     // both round trips at once
-        const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[0], HC ? (uint32_t)a.hcG : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sEpoch = e;
         sTicket[0] = t;
         sLast = 0;
@@ -208,6 +219,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVE
     float lr[V], li[V], pfr[V], pfi[V], psr[V], psi[V];
     float wm[KC1][V], wa[KC1][V], bm[V], ba[V];
     float rb[V];                                   // RET: static retention bias of my lanes
+    float hw[2][3], hb[2];                         // HC: taps and bias of my lane's two channels
 
     for (int it = 0; ticket < qtiles; ++it) {
         ARGS_AGAIN();
@@ -222,8 +234,14 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVE
         // of the atomic stays off the path to the barrier below)
         uint32_t ticket_ahead;   // (only thread 0's copy is ever set or read; no initialiser, so no
                              // merge of values that would wait for the atomic right here)
-        if (tid == 0)
-            ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // (HC: the tickets of a head's lane blocks are drawn together, a multiple of hcG first)
+        const uint32_t hcG = HC ? (uint32_t)a.hcG : 1u;
+        if (tid == 0) {
+            if (HC && (ticket + 1) % hcG != 0)
+                ticket_ahead = ticket + 1;
+            else
+                ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], hcG, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
 
         // ---- the staged rows have landed (each wave waited for its own loads: before the loop, or
         //      at the end of the previous iteration)
@@ -249,6 +267,14 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVE
                 for (int k = 0; k < KC1; ++k) wm[k][v] = wa[k][v] = 0.f;
             }
             if (RET) cst(rb, R_RBIAS);
+            if (HC) {
+#pragma unroll
+                for (int p = 0; p < 2; ++p) {
+                    hb[p] = sC[R_W0 + 2 * KC + 6 + p - R_LR][lv];
+#pragma unroll
+                    for (int k = 0; k < 3; ++k) hw[p][k] = sC[R_W0 + 2 * KC + 3 * p + k - R_LR][lv];
+                }
+            }
             if (KC > 0) {
                 cst(bm, R_BIAS_M);
                 cst(ba, R_BIAS_A);
@@ -555,6 +581,12 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVE
             uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * ES;   // bytes
             const bool full = (tt + 1) * TILE_T <= a.L && (T.lb + 1) * JB <= a.J;
             const bool plain = full && !(a.state_out && tt == a.nT - 1);   // no per-row checks at all
+            // HC: where my lane sits in its head; which neighbour comes from, or goes to, the next block
+            const int hq = HC ? (int)((uint32_t)T.lb % hcG) : 0;
+            const int hk = HC ? (a.F >= JB ? hq * JB + lv : j0 % a.F) : 0;
+            const bool h_first = hk == 0, h_last = hk == a.F - 1;
+            const bool h_prev = HC && lv == 0 && hq > 0;                    // left neighbour left in LDS
+            const bool h_defer = HC && lv == LPR - 1 && hq + 1 < (int)hcG;  // my output waits for the next block
             auto replay = [&](auto plain_c) {
                 constexpr bool PLAIN = decltype(plain_c)::value;
 #pragma unroll
@@ -578,7 +610,49 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET) ? CAWN_FWD_WAVE
                         zr[v] = clampf(nr, a.out_clamp);
                         zi[v] = clampf(ni, a.out_clamp);
                     }
-                    if (PLAIN || (active && t < a.L)) {
+                    if constexpr (HC) {
+                        const int ix = seg * NSTEP + i;
+                        float lzr = __shfl_up(zr[0], 1, 64), lzi = __shfl_up(zi[0], 1, 64);
+                        float rzr = __shfl_down(zr[0], 1, 64), rzi = __shfl_down(zi[0], 1, 64);
+                        float dpr = 0.f, dpi = 0.f;     // the previous block's unfinished output
+                        if (h_prev) {
+                            lzr = sHZ[0][ix];
+                            lzi = sHZ[1][ix];
+                            dpr = __builtin_fmaf(hw[0][2], zr[0], sHP[0][ix]);     // (same head: same taps)
+                            dpi = __builtin_fmaf(hw[1][2], zi[0], sHP[1][ix]);
+                        }
+                        lzr = h_first ? 0.f : lzr;
+                        lzi = h_first ? 0.f : lzi;
+                        rzr = (h_last || h_defer) ? 0.f : rzr;
+                        rzi = (h_last || h_defer) ? 0.f : rzi;
+                        const float cr_ = __builtin_fmaf(hw[0][2], rzr, __builtin_fmaf(hw[0][1], zr[0], __builtin_fmaf(hw[0][0], lzr, hb[0])));
+                        const float ci_ = __builtin_fmaf(hw[1][2], rzi, __builtin_fmaf(hw[1][1], zi[0], __builtin_fmaf(hw[1][0], lzi, hb[1])));
+                        if (h_defer) {      // (the reads of these slots by lane 0 of this wave come first, above)
+                            sHZ[0][ix] = zr[0];
+                            sHZ[1][ix] = zi[0];
+                            sHP[0][ix] = cr_;
+                            sHP[1][ix] = ci_;
+                        }
+                        const bool row_ok = PLAIN || (active && t < a.L);
+                        if (row_ok && !h_defer) {
+                            if constexpr (BF) {
+                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off) = to_bf16(cr_);
+                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + off) = to_bf16(ci_);
+                            } else {
+                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + off) = cr_;
+                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + off) = ci_;
+                            }
+                        }
+                        if (row_ok && h_prev) {     // the lane before mine in memory: last lane of the previous block
+                            if constexpr (BF) {
+                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + (ptrdiff_t)off - (ptrdiff_t)ES) = to_bf16(dpr);
+                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + (ptrdiff_t)off - (ptrdiff_t)ES) = to_bf16(dpi);
+                            } else {
+                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + (ptrdiff_t)off - (ptrdiff_t)ES) = dpr;
+                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + (ptrdiff_t)off - (ptrdiff_t)ES) = dpi;
+                            }
+                        }
+                    } else if (PLAIN || (active && t < a.L)) {
                         if constexpr (BF) {
                             *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off) = to_bf16(zr[0]);
                             *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + off) = to_bf16(zi[0]);
@@ -663,12 +737,24 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
 {
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
     constexpr int HALO1 = HALO > 0 ? HALO : 1, KC1 = KC > 0 ? KC : 1;
+    // harmonic convolution (Sec. 3.6): the block's 256 lanes hold whole heads; neighbours meet in LDS
+    __shared__ float sZ[2][256 + 2];
     const int j = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
     const bool active = j < a.J;
     const int jc = active ? j : 0;      // lanes beyond J compute on lane 0's data and store nothing
     const float *tb = a.table + jc;
     const float lr = tb[(size_t)R_LR * a.Jp], li = tb[(size_t)R_LI * a.Jp];
     const float rb = tb[(size_t)R_RBIAS * a.Jp];
+    float hw[2][3] = {{0.f, 0.f, 0.f}, {0.f, 0.f, 0.f}}, hb[2] = {0.f, 0.f};
+    if (a.hconv) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            hb[p] = tb[(size_t)(R_W0 + 2 * KC + 6 + p) * a.Jp];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) hw[p][k] = tb[(size_t)(R_W0 + 2 * KC + 3 * p + k) * a.Jp];
+        }
+    }
+    const int hk = jc % a.F;
     float wm[KC1], wa[KC1], bm = 0.f, ba = 0.f;
 #pragma unroll
     for (int k = 0; k < KC1; ++k) wm[k] = wa[k] = 0.f;
@@ -751,14 +837,25 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
         }
         Sr = nr;
         Si = ni;
+        float or_ = clampf(nr, a.out_clamp), oi_ = clampf(ni, a.out_clamp);
+        if (a.hconv) {      // (uniform over the launch: every thread of the block takes the barriers)
+            sZ[0][threadIdx.x + 1] = or_;
+            sZ[1][threadIdx.x + 1] = oi_;
+            __syncthreads();
+            const float lzr = hk > 0 ? sZ[0][threadIdx.x] : 0.f, lzi = hk > 0 ? sZ[1][threadIdx.x] : 0.f;
+            const float rzr = hk < a.F - 1 ? sZ[0][threadIdx.x + 2] : 0.f, rzi = hk < a.F - 1 ? sZ[1][threadIdx.x + 2] : 0.f;
+            or_ = __builtin_fmaf(hw[0][2], rzr, __builtin_fmaf(hw[0][1], or_, __builtin_fmaf(hw[0][0], lzr, hb[0])));
+            oi_ = __builtin_fmaf(hw[1][2], rzi, __builtin_fmaf(hw[1][1], oi_, __builtin_fmaf(hw[1][0], lzi, hb[1])));
+            __syncthreads();
+        }
         if (active) {
             const size_t o = (size_t)b * a.osb + (size_t)t * a.ost + j;
             if (a.bf16) {
-                reinterpret_cast<uint16_t *>(a.z_re)[o] = to_bf16(clampf(nr, a.out_clamp));
-                reinterpret_cast<uint16_t *>(a.z_im)[o] = to_bf16(clampf(ni, a.out_clamp));
+                reinterpret_cast<uint16_t *>(a.z_re)[o] = to_bf16(or_);
+                reinterpret_cast<uint16_t *>(a.z_im)[o] = to_bf16(oi_);
             } else {
-                a.z_re[o] = clampf(nr, a.out_clamp);
-                a.z_im[o] = clampf(ni, a.out_clamp);
+                a.z_re[o] = or_;
+                a.z_im[o] = oi_;
             }
         }
         if (a.mask) {   // bit j%32 of word j/32: one ballot covers two words
@@ -796,8 +893,8 @@ static hipError_t launch_step(const FwdArgs &a, int conv_k, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int V, int KC, bool VALVE, bool RET, bool BF>
-static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
+template <int V, int KC, bool VALVE, bool RET, bool BF, bool HC>
+static hipError_t launch_fwd_vkh(const FwdArgs &a0, hipStream_t s)
 {
     // persistent grid: what fits on the chip (asked once per kernel)
     static int per_cu = 0, cus = 0;
@@ -805,7 +902,7 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC, VALVE, RET, BF>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fwd_kernel<V, KC, VALVE, RET, BF, HC>, FwdGeom::NSEG * FwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
@@ -815,8 +912,17 @@ static hipError_t launch_fwd_vk(const FwdArgs &a0, hipStream_t s)
     const long long tiles = (long long)a.nLB * a.B * a.nT;
     const long long wgs = tiles < resident ? (tiles > 0 ? tiles : 1) : resident;
     dim3 grid((unsigned)wgs), block(FwdGeom::NSEG * FwdLPR);
-    hipLaunchKernelGGL((fwd_kernel<V, KC, VALVE, RET, BF>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((fwd_kernel<V, KC, VALVE, RET, BF, HC>), grid, block, 0, s, a);
     return hipGetLastError();
+}
+
+template <int V, int KC, bool VALVE, bool RET, bool BF>
+static hipError_t launch_fwd_vk(const FwdArgs &a, hipStream_t s)
+{
+    if constexpr (V == 1) {
+        if (a.hconv) return launch_fwd_vkh<1, KC, VALVE, RET, BF, true>(a, s);
+    }
+    return launch_fwd_vkh<V, KC, VALVE, RET, BF, false>(a, s);
 }
 
 template <int V, bool VALVE, bool RET, bool BF>

@@ -79,7 +79,10 @@ enum LaneRow : int {
     R_RBIAS,                   // ret_mode 1: the lane's static retention bias b_k (k = j mod F)
     R_W0                       // R_W0 + s*conv_k + i : tap i of stream s
 };
-inline __host__ __device__ int lane_rows(int conv_k) { return R_W0 + 2 * conv_k; }
+// Harmonic convolution (Sec. 3.6): HC_ROWS more rows behind the temporal conv's taps, per lane the
+// constants of its head's two channels: R_W0 + 2*conv_k + 3*plane + i = tap i, + 6 + plane = bias.
+constexpr int HC_ROWS = 8;
+inline __host__ __device__ int lane_rows(int conv_k, bool hconv = false) { return R_W0 + 2 * conv_k + (hconv ? HC_ROWS : 0); }
 
 // ----------------------------------------------------------------------------------- workspace
 // Workspace: [header 1 KiB][lane table][aggregates][prefixes][backward conv halo][backward parameter
@@ -149,6 +152,9 @@ struct FwdArgs {
     // activations are bfloat16 in memory (mag, ang, z_re, z_im then point to 2-byte elements; strides
     // are in elements); J and the strides are even
     int bf16;
+    // harmonic convolution of the output before it is stored (Sec. 3.6, three taps); hcG: 32-lane blocks
+    // per head (1 when a head fits a block), whose tickets one workgroup draws together
+    int hconv, hcG;
 };
 
 struct BwdArgs {

@@ -59,10 +59,17 @@ class Workspaces:
 
 def run_fwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0, out_clamp=100.0,
             state_in=None, want_mask=True, want_ckpt=False, concat=False, in_place_state=False,
-            cached=0, ws=None, valve=None, valve_eps=0.001, ret=None, ret_bias=None):
+            cached=0, ws=None, valve=None, valve_eps=0.001, ret=None, ret_bias=None, hconv_w=None,
+            hconv_b=None, bf16=False):
     """inp: dict with mag, ang [B,L,J], gamma, theta, conv_w, conv_b (numpy float32).
-    Returns dict(z_re, z_im, state_out (flat blob), mask [B,L,W] uint32, ckpt)."""
+    Returns dict(z_re, z_im, state_out (flat blob), mask [B,L,W] uint32, ckpt).
+    hconv_w [2,H,3] (and hconv_b [2,H]): the harmonic convolution's entry point, z_re / z_im are then
+    the convolved planes; with bf16 the inputs (bf16-exact fp32 arrays) and outputs are bfloat16 in memory."""
     J = H * F
+    if hconv_w is not None:
+        return _run_fwd_hconv(inp, B, L, H, F, conv_k, amp_mode, gate_tau, conv_clamp, out_clamp, state_in, want_mask,
+                              want_ckpt, concat, cached, ws, valve, valve_eps, ret, ret_bias, hconv_w, hconv_b, bf16)
+    assert not bf16
     d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau,
                     conv_clamp=conv_clamp, out_clamp=out_clamp, lane_consts_cached=cached,
                     gate_mode=0 if valve is None else 1, valve_eps=valve_eps, ret_mode=0 if ret is None else 1)
@@ -101,6 +108,50 @@ def run_fwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, conv_clamp=50.0
     torch.cuda.synchronize()
     K.check(K.cawn_workspace_status(ws))
     out = dict(z_re=z_re[:, :L].cpu().numpy(), z_im=z_im[:, :L].cpu().numpy(),
+               state_out=st_out.cpu().numpy())
+    if want_mask:
+        out["mask"] = mask[:, :L].cpu().numpy().view(np.uint32)
+    if want_ckpt:
+        out["ckpt"] = ckpt.cpu().numpy()
+    return out
+
+
+def _run_fwd_hconv(inp, B, L, H, F, conv_k, amp_mode, gate_tau, conv_clamp, out_clamp, state_in, want_mask,
+                   want_ckpt, concat, cached, ws, valve, valve_eps, ret, ret_bias, hconv_w, hconv_b, bf16):
+    J = H * F
+    d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau,
+                    conv_clamp=conv_clamp, out_clamp=out_clamp, lane_consts_cached=cached,
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps, ret_mode=0 if ret is None else 1,
+                    hconv_k=3)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    mag, ang = dev(inp["mag"][:, :L]).to(dt), dev(inp["ang"][:, :L]).to(dt)
+    gamma, theta = dev(inp.get("gamma")), dev(inp["theta"])
+    cw = dev(inp["conv_w"]) if conv_k > 0 else None
+    cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
+    Lr = max(L, 1)
+    if concat:
+        z = torch.full((B, Lr, 2 * J), float("nan"), device=DEV, dtype=dt)
+        z_re, z_im = z[:, :, :J], z[:, :, J:]
+        d.out_stride_t, d.out_stride_b = 2 * J, Lr * 2 * J
+    else:
+        z_re = torch.full((B, Lr, J), float("nan"), device=DEV, dtype=dt)
+        z_im = torch.full((B, Lr, J), float("nan"), device=DEV, dtype=dt)
+    nstate = K.cawn_state_bytes(d) // 4
+    st_in = dev(state_in) if state_in is not None else None
+    st_out = torch.full((nstate,), float("nan"), device=DEV)
+    W = (J + 31) // 32
+    mask = torch.zeros((B, Lr, W), dtype=torch.int32, device=DEV) if want_mask else None
+    ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV) if want_ckpt else None
+    ws = ws if ws is not None else Workspaces.get(d)
+    vl = None if valve is None else dev(np.ascontiguousarray(valve[:, :L]))
+    rt = None if ret is None else dev(np.ascontiguousarray(ret[:, :L]))
+    K.check(K.cawn_phase_accumulate_hconv_fwd(d, mag, ang, vl, rt, dev(ret_bias), gamma, theta, cw, cb,
+                                              dev(np.ascontiguousarray(hconv_w, dtype=np.float32)),
+                                              dev(hconv_b), st_in, z_re, z_im, st_out, ckpt, mask, ws,
+                                              activations_bf16=1 if bf16 else 0))
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    out = dict(z_re=z_re[:, :L].float().cpu().numpy(), z_im=z_im[:, :L].float().cpu().numpy(),
                state_out=st_out.cpu().numpy())
     if want_mask:
         out["mask"] = mask[:, :L].cpu().numpy().view(np.uint32)

@@ -96,6 +96,21 @@ def test_host_side_argument_checks_reject_before_any_launch():
     assert L.cawn_workspace_init(fake, 16, null) == K.CAWN_EWORKSPACE
     args_b = [null] * 19
     assert L.cawn_phase_accumulate_bwd(C.byref(d), *args_b, 0, null) != K.CAWN_OK
+    # harmonic convolution: its own entry point only, three taps only, head widths that tile the lane blocks
+    hc = K.make_desc(2, 128, 2, 64, hconv_k=3)
+    assert L.cawn_phase_accumulate_fwd(C.byref(hc), *a2, fake, 1 << 30, null) == K.CAWN_EINVAL
+    assert L.cawn_phase_accumulate_bwd(C.byref(hc), *([fake] * 19), 1 << 30, null) == K.CAWN_EINVAL
+    a3 = [fake] * 18
+    assert L.cawn_phase_accumulate_hconv_fwd(C.byref(d), *a3, 1 << 30, 0, null) == K.CAWN_EINVAL      # hconv_k = 0
+    assert L.cawn_phase_accumulate_hconv_fwd(C.byref(K.make_desc(2, 128, 2, 64, hconv_k=5)), *a3, 1 << 30, 0, null) == K.CAWN_EINVAL
+    a3[9] = null                                                                                    # no taps
+    assert L.cawn_phase_accumulate_hconv_fwd(C.byref(hc), *a3, 1 << 30, 0, null) == K.CAWN_EINVAL
+    a3[9] = fake
+    for H_, F_, gm in ((2, 96, 0), (2, 24, 0), (1, 512, 0), (4, 16, 1)):
+        bad = K.make_desc(2, 128, H_, F_, hconv_k=3, gate_mode=gm)
+        assert L.cawn_phase_accumulate_hconv_fwd(C.byref(bad), *a3, 1 << 30, 0, null) == K.CAWN_EUNSUPPORTED
+    assert L.cawn_phase_accumulate_hconv_fwd(C.byref(hc), *a3, 16, 0, null) == K.CAWN_EWORKSPACE
+    assert K.cawn_workspace_bytes(hc) > K.cawn_workspace_bytes(K.make_desc(2, 128, 2, 64))
 
 
 def test_header_is_plain_c_and_links(tmp_path):
@@ -155,7 +170,7 @@ def test_kernels_do_not_spill_and_keep_their_occupancy():
                 name = val.strip()
             elif name and ("fwd_kernel" in name or "bwd_kernel" in name or "step_kernel" in name):
                 if key.startswith("ScratchSize"):
-                    # boolean template arguments: forward (VALVE, RET, BF), backward (PARAM, VALVE, RET, BF)
+                    # boolean template arguments: forward (VALVE, RET, BF, HC), backward (PARAM, VALVE, RET, BF)
                     flags = [f == "1" for f in re.findall(r"Lb([01])E", name)]
                     strict = True
                     allowed = 128     # (the compiler sometimes reserves a frame it never touches)
