@@ -45,6 +45,10 @@ def parse():
     ap.add_argument("--bf16", action="store_true",
                     help="activations (inputs, outputs, upstream and returned gradients) are bfloat16 in memory, "
                          "arithmetic and state fp32 (extra line, not the headline; no CPU baseline)")
+    ap.add_argument("--hconv", action="store_true",
+                    help="the depth-wise harmonic convolution of Sec. 3.6 fused behind the output clamp (forward only: "
+                         "a training workload then runs and times its forward pass alone; same bytes per token-lane; "
+                         "extra line, not the headline; no CPU baseline)")
     ap.add_argument("--unfused", action="store_true",
                     help="cfg2_layer_fwd only: the Temporal Syntax Cache as separate calls (cawn_syntax_conv on each "
                          "stream, then the scan without conv front-end): 32 instead of 16 bytes per token-lane; "
@@ -169,7 +173,8 @@ def main():
     wl = WL.CONFIGS[args.workload]
     B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
     theta = K.cawn_theta_init(H, F)
-    do_bwd = args.workload in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads")
+    # (--hconv is a forward-only entry point: on a training workload only its forward pass is run and timed)
+    do_bwd = args.workload in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads") and not args.hconv
     stream_mode = args.workload == "cfg4_stream"
     L = wl.chunk if stream_mode else wl.L
 
@@ -196,7 +201,14 @@ def main():
     t_gen = time.time() - t_gen
 
     d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau, gate_mode=1 if args.valve else 0,
-                    ret_mode=1 if args.ret else 0)
+                    ret_mode=1 if args.ret else 0, hconv_k=3 if args.hconv else 0)
+    hw = hb = None
+    if args.hconv:
+        assert not args.unfused and args.workload != "decode", "--hconv: not with --unfused or the decode workload"
+        args.no_cpu_baseline = True
+        rh = np.random.Generator(np.random.PCG64(4250 + 97))
+        hw = torch.from_numpy((rh.standard_normal((2, H, 3)) / np.sqrt(3.0)).astype(np.float32)).to(dev)
+        hb = torch.from_numpy((0.1 * rh.standard_normal((2, H))).astype(np.float32)).to(dev)
     if args.bf16:
         args.no_cpu_baseline = True
     ret = ret_bias = dret = None
@@ -238,6 +250,10 @@ def main():
             st |= K.cawn_syntax_conv(d, J, p["ang"], cwa, cba, None, xa, None)
             return st | K.cawn_phase_accumulate_fwd(d_plain, xm, xa, gamma, th, None, None, st_in, p["z_re"], p["z_im"],
                                                     st_out, ck, None, ws)
+        if args.hconv:
+            return K.cawn_phase_accumulate_hconv_fwd(dd, p["mag"], p["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
+                                                     hw, hb, st_in, p["z_re"], p["z_im"], st_out, ck, None, ws,
+                                                     activations_bf16=1 if args.bf16 else 0)
         if args.bf16:
             return K.cawn_phase_accumulate_bf16_fwd(dd, p["mag"], p["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
                                                     st_in, p["z_re"], p["z_im"], st_out, ck, None, ws)
@@ -257,7 +273,8 @@ def main():
     d_tail = None
     if stream_mode:
         nfull, rem = divmod(wl.L, wl.chunk)
-        d_tail = K.make_desc(B, rem, H, F, conv_k=Kc, gate_tau=wl.gate_tau, lane_consts_cached=1) if rem else None
+        d_tail = K.make_desc(B, rem, H, F, conv_k=Kc, gate_tau=wl.gate_tau, lane_consts_cached=1,
+                             hconv_k=3 if args.hconv else 0) if rem else None
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
@@ -329,12 +346,14 @@ def main():
                                    if args.ret else "constant per lane",
                       "buffer_sets_rotated": nsets}}
     bflag = lambda x: "true" if x else "false"
-    fwd_label = f"fwd_kernel<1,4,{bflag(args.valve)},{bflag(args.ret)},{bflag(args.bf16)}>"
+    fwd_label = f"fwd_kernel<1,4,{bflag(args.valve)},{bflag(args.ret)},{bflag(args.bf16)},{bflag(args.hconv)}>"
     bwd_label = f"bwd_kernel<1,4,true,{bflag(args.valve)},{bflag(args.ret)},{bflag(args.bf16)}>"
-    extra = args.valve or args.ret or args.bf16 or args.unfused
+    extra = args.valve or args.ret or args.bf16 or args.unfused or args.hconv
     if args.unfused:
-        fwd_label = "2 x syntax_conv_kernel<4> + fwd_kernel<1,0,false,false,false> (one event span; the path's own 16 B per token-lane)"
+        fwd_label = "2 x syntax_conv_kernel<4> + fwd_kernel<1,0,false,false,false,false> (one event span; the path's own 16 B per token-lane)"
     out["config"]["activations"] = "bfloat16 in memory, fp32 arithmetic and state" if args.bf16 else "fp32"
+    if args.hconv:
+        out["config"]["epilogue"] = "depth-wise harmonic convolution (3 taps per (plane, head) channel) fused behind the clamp"
     if args.unfused:
         out["config"]["front_end"] = "conv as separate calls (2 x cawn_syntax_conv + scan): 32 B per token-lane"
     fwd_bpl = FWD_BYTES_PER_TOKEN_LANE // (2 if args.bf16 else 1)

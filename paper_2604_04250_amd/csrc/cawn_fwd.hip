@@ -208,9 +208,20 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                                      BF ? a.J / 2 : a.J, a.L, BF ? a.isb / 2 : a.isb, BF ? ist32 / 2 : ist32, wave, NW - 1, lane);
     };
 
+    // HC, heads of G > 1 lane blocks: a group of G tickets is one head's blocks; groups with an odd index
+    // take them from the last block down, so that at any time the workgroups of the grid are spread over
+    // all positions in a head (in step on one position they would all read and write one 128-byte
+    // address class of the rows at a time, i.e. a part of the memory channels)
+    auto tile_of = [&](uint32_t tk) {
+        if (HC) {
+            const uint32_t G = (uint32_t)a.hcG, g = tk / G, p_ = tk - g * G;
+            tk = g * G + ((g & 1u) ? G - 1u - p_ : p_);
+        }
+        return decode_tile(tk, a.nLB, a.B, a.nT);
+    };
     TileId T{};
     if (ticket < qtiles) {
-        T = decode_tile(ticket, a.nLB, a.B, a.nT);
+        T = tile_of(ticket);
         stage_tile(T);
     }
 
@@ -437,7 +448,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
         const uint32_t next_ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
         TileId Tn{};
         if (next_ticket < qtiles) {
-            Tn = decode_tile(next_ticket, a.nLB, a.B, a.nT);
+            Tn = tile_of(next_ticket);
             stage_tile(Tn);
         }
 
@@ -585,10 +596,113 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
             const int hq = HC ? (int)((uint32_t)T.lb % hcG) : 0;
             const int hk = HC ? (a.F >= JB ? hq * JB + lv : j0 % a.F) : 0;
             const bool h_first = hk == 0, h_last = hk == a.F - 1;
-            const bool h_prev = HC && lv == 0 && hq > 0;                    // left neighbour left in LDS
-            const bool h_defer = HC && lv == LPR - 1 && hq + 1 < (int)hcG;  // my output waits for the next block
-            auto replay = [&](auto plain_c) {
+            // (h_dn: this group goes down the head; the roles of the block's first and last lane swap)
+            const bool h_dn = HC && ((ticket / hcG) & 1u);
+            const bool h_lo = HC && lv == 0 && hq > 0, h_hi = HC && lv == LPR - 1 && hq + 1 < (int)hcG;
+            const bool h_prev = h_dn ? h_hi : h_lo;     // my outer neighbour was left in LDS by the previous tile
+            const bool h_defer = h_dn ? h_lo : h_hi;    // my output waits for the next tile
+            const bool h_zl = h_first || (h_defer && h_dn), h_zr = h_last || (h_defer && !h_dn);
+            const float h_wr = h_dn ? hw[0][0] : hw[0][2], h_wi = h_dn ? hw[1][0] : hw[1][2];   // tap that completes it
+            const bool h_tl = h_prev && !h_dn, h_tr = h_prev && h_dn;        // which neighbour comes from LDS
+            // where the completed output is stored (0: this lane has none to complete, its second store repeats its first)
+            const ptrdiff_t h_back = h_prev ? (h_dn ? (ptrdiff_t)ES : -(ptrdiff_t)ES) : 0;
+            auto replay = [&](auto plain_c, auto multi_c) {
                 constexpr bool PLAIN = decltype(plain_c)::value;
+                // heads of several lane blocks (1, 2); this tile completes outputs of the previous one (2)
+                constexpr bool MULTI = HC && decltype(multi_c)::value > 0, RECV = HC && decltype(multi_c)::value == 2;
+                if constexpr (HC) {
+                    // The harmonic convolution, four tokens at a time: the recurrence of the four, then all
+                    // their lane exchanges and LDS reads (one wait instead of one per token), then outputs.
+                    // No branch in here, so the steps stay one block of code.  MULTI (a head spans several
+                    // blocks): every lane reads the slot of its row (a broadcast) and selects; every lane
+                    // writes -- the deferring lane into the slot, the others into words of sE that only they
+                    // write and nobody reads before the next tile rewrites them; the deferring lane stores
+                    // its unfinished output like any other lane and the receiving lane of the next tile (same
+                    // wave, so later at the same address) overwrites it; the receiving lane's second store
+                    // goes to the neighbouring element, every other lane's second store repeats its first.
+                    constexpr int CH = 4;
+                    static_assert(NSTEP % CH == 0, "whole chunks");
+#pragma unroll
+                    for (int c0 = 0; c0 < NSTEP; c0 += CH) {
+                        float z_r[CH], z_i[CH], lzr[CH], lzi[CH], rzr[CH], rzi[CH], dpr[CH], dpi[CH];
+#pragma unroll
+                        for (int k = 0; k < CH; ++k) {
+                            const int i = c0 + k;
+                            float nr, ni;
+                            if (RET) {
+                                const float rr = __builtin_fmaf(lr[0], Sr[0], -li[0] * Si[0]);
+                                const float ri = __builtin_fmaf(li[0], Sr[0], lr[0] * Si[0]);
+                                nr = __builtin_fmaf(gm[i][0], rr, pr[i][0]);
+                                ni = __builtin_fmaf(gm[i][0], ri, pi[i][0]);
+                            } else {
+                                nr = __builtin_fmaf(lr[0], Sr[0], __builtin_fmaf(-li[0], Si[0], pr[i][0]));
+                                ni = __builtin_fmaf(li[0], Sr[0], __builtin_fmaf(lr[0], Si[0], pi[i][0]));
+                            }
+                            Sr[0] = nr;
+                            Si[0] = ni;
+                            z_r[k] = clampf(nr, a.out_clamp);
+                            z_i[k] = clampf(ni, a.out_clamp);
+                            if (!PLAIN && t0 + i == a.L - 1 && a.state_out && active) {
+                                a.state_out[((size_t)b * 2 + 0) * a.J + j0] = nr;
+                                a.state_out[((size_t)b * 2 + 1) * a.J + j0] = ni;
+                            }
+                        }
+#pragma unroll
+                        for (int k = 0; k < CH; ++k) {
+                            const int ix = seg * NSTEP + c0 + k;
+                            lzr[k] = __shfl_up(z_r[k], 1, 64);
+                            lzi[k] = __shfl_up(z_i[k], 1, 64);
+                            rzr[k] = __shfl_down(z_r[k], 1, 64);
+                            rzi[k] = __shfl_down(z_i[k], 1, 64);
+                            dpr[k] = dpi[k] = 0.f;     // the neighbouring block's unfinished output, completed
+                            if constexpr (RECV) {
+                                const float nzr = sHZ[0][ix], nzi = sHZ[1][ix];
+                                lzr[k] = h_tl ? nzr : lzr[k];
+                                lzi[k] = h_tl ? nzi : lzi[k];
+                                rzr[k] = h_tr ? nzr : rzr[k];
+                                rzi[k] = h_tr ? nzi : rzi[k];
+                                dpr[k] = __builtin_fmaf(h_wr, z_r[k], sHP[0][ix]);     // (same head: same taps)
+                                dpi[k] = __builtin_fmaf(h_wi, z_i[k], sHP[1][ix]);
+                            }
+                        }
+#pragma unroll
+                        for (int k = 0; k < CH; ++k) {
+                            const int ix = seg * NSTEP + c0 + k;
+                            const float l_r = h_zl ? 0.f : lzr[k], l_i = h_zl ? 0.f : lzi[k];
+                            const float r_r = h_zr ? 0.f : rzr[k], r_i = h_zr ? 0.f : rzi[k];
+                            const float cr_ = __builtin_fmaf(hw[0][2], r_r, __builtin_fmaf(hw[0][1], z_r[k], __builtin_fmaf(hw[0][0], l_r, hb[0])));
+                            const float ci_ = __builtin_fmaf(hw[1][2], r_i, __builtin_fmaf(hw[1][1], z_i[k], __builtin_fmaf(hw[1][0], l_i, hb[1])));
+                            if constexpr (MULTI) {      // (the reads of these slots, above, come first in this wave)
+                                float *wz = h_defer ? &sHZ[0][ix] : &sE[seg][0][lv];
+                                float *wp = h_defer ? &sHP[0][ix] : &sE[seg][1][lv];
+                                constexpr int PL = FwdGeom::TILE_T;      // from plane 0 to plane 1 of a slot
+                                wz[0] = z_r[k];
+                                wz[h_defer ? PL : 0] = z_i[k];
+                                wp[0] = cr_;
+                                wp[h_defer ? PL : 0] = ci_;
+                            }
+                            if (PLAIN || (active && t0 + c0 + k < a.L)) {
+                                char *pr_ = reinterpret_cast<char *>(zre) + off, *pi_ = reinterpret_cast<char *>(zim) + off;
+                                if constexpr (BF) {
+                                    *reinterpret_cast<uint16_t *>(pr_) = to_bf16(cr_);
+                                    *reinterpret_cast<uint16_t *>(pi_) = to_bf16(ci_);
+                                    if constexpr (RECV) {
+                                        *reinterpret_cast<uint16_t *>(pr_ + h_back) = to_bf16(h_prev ? dpr[k] : cr_);
+                                        *reinterpret_cast<uint16_t *>(pi_ + h_back) = to_bf16(h_prev ? dpi[k] : ci_);
+                                    }
+                                } else {
+                                    *reinterpret_cast<float *>(pr_) = cr_;
+                                    *reinterpret_cast<float *>(pi_) = ci_;
+                                    if constexpr (RECV) {
+                                        *reinterpret_cast<float *>(pr_ + h_back) = h_prev ? dpr[k] : cr_;
+                                        *reinterpret_cast<float *>(pi_ + h_back) = h_prev ? dpi[k] : ci_;
+                                    }
+                                }
+                            }
+                            off += ost32 * ES;
+                        }
+                    }
+                } else {
 #pragma unroll
                 for (int i = 0; i < NSTEP; ++i) {
                     const int t = t0 + i;
@@ -610,49 +724,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                         zr[v] = clampf(nr, a.out_clamp);
                         zi[v] = clampf(ni, a.out_clamp);
                     }
-                    if constexpr (HC) {
-                        const int ix = seg * NSTEP + i;
-                        float lzr = __shfl_up(zr[0], 1, 64), lzi = __shfl_up(zi[0], 1, 64);
-                        float rzr = __shfl_down(zr[0], 1, 64), rzi = __shfl_down(zi[0], 1, 64);
-                        float dpr = 0.f, dpi = 0.f;     // the previous block's unfinished output
-                        if (h_prev) {
-                            lzr = sHZ[0][ix];
-                            lzi = sHZ[1][ix];
-                            dpr = __builtin_fmaf(hw[0][2], zr[0], sHP[0][ix]);     // (same head: same taps)
-                            dpi = __builtin_fmaf(hw[1][2], zi[0], sHP[1][ix]);
-                        }
-                        lzr = h_first ? 0.f : lzr;
-                        lzi = h_first ? 0.f : lzi;
-                        rzr = (h_last || h_defer) ? 0.f : rzr;
-                        rzi = (h_last || h_defer) ? 0.f : rzi;
-                        const float cr_ = __builtin_fmaf(hw[0][2], rzr, __builtin_fmaf(hw[0][1], zr[0], __builtin_fmaf(hw[0][0], lzr, hb[0])));
-                        const float ci_ = __builtin_fmaf(hw[1][2], rzi, __builtin_fmaf(hw[1][1], zi[0], __builtin_fmaf(hw[1][0], lzi, hb[1])));
-                        if (h_defer) {      // (the reads of these slots by lane 0 of this wave come first, above)
-                            sHZ[0][ix] = zr[0];
-                            sHZ[1][ix] = zi[0];
-                            sHP[0][ix] = cr_;
-                            sHP[1][ix] = ci_;
-                        }
-                        const bool row_ok = PLAIN || (active && t < a.L);
-                        if (row_ok && !h_defer) {
-                            if constexpr (BF) {
-                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off) = to_bf16(cr_);
-                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + off) = to_bf16(ci_);
-                            } else {
-                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + off) = cr_;
-                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + off) = ci_;
-                            }
-                        }
-                        if (row_ok && h_prev) {     // the lane before mine in memory: last lane of the previous block
-                            if constexpr (BF) {
-                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + (ptrdiff_t)off - (ptrdiff_t)ES) = to_bf16(dpr);
-                                *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + (ptrdiff_t)off - (ptrdiff_t)ES) = to_bf16(dpi);
-                            } else {
-                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + (ptrdiff_t)off - (ptrdiff_t)ES) = dpr;
-                                *reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + (ptrdiff_t)off - (ptrdiff_t)ES) = dpi;
-                            }
-                        }
-                    } else if (PLAIN || (active && t < a.L)) {
+                    if (PLAIN || (active && t < a.L)) {
                         if constexpr (BF) {
                             *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off) = to_bf16(zr[0]);
                             *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + off) = to_bf16(zi[0]);
@@ -667,15 +739,27 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                     }
                     off += ost32 * ES;
                 }
+                }
             };
             // What is still in flight ahead of this tile's output stores must be complete now: the next
             // tile's staged rows (needed after the next barrier).  The output stores themselves (the
             // 2 * NSTEP youngest operations when no row needed a check) are left in flight.
+            // (a tile that completes its predecessor's outputs issues twice the stores, more than the 63 a
+            // wave can leave in flight behind its wait: the wait below then covers half of the tile's own
+            // stores, about 4 us in a tile of 12; the first tile of a group does not)
+            const bool recv_tile = HC && (h_dn ? hq + 1 < (int)hcG : hq > 0);
+            using M0 = std::integral_constant<int, 0>;
+            using M1 = std::integral_constant<int, 1>;
+            using M2 = std::integral_constant<int, 2>;
             if (plain) {
-                replay(std::true_type{});
+                if (recv_tile) replay(std::true_type{}, M2{});
+                else if (HC && hcG > 1) replay(std::true_type{}, M1{});
+                else replay(std::true_type{}, M0{});
                 wait_vm<(2 * NSTEP < 63 ? 2 * NSTEP : 63)>();
             } else {
-                replay(std::false_type{});
+                if (recv_tile) replay(std::false_type{}, M2{});
+                else if (HC && hcG > 1) replay(std::false_type{}, M1{});
+                else replay(std::false_type{}, M0{});
                 wait_vm<0>();
             }
         }

@@ -200,3 +200,48 @@ def test_hconv_unsupported_shapes_are_refused():
         st = K.cawn_phase_accumulate_hconv_fwd(dsc, x, x, v, None, None, p, p, None, None, w, None, None,
                                                torch.empty_like(x), torch.empty_like(x), None, None, None, ws)
         assert st == want, (H, F, st)
+
+
+@pytest.mark.parametrize("name,bf16", [("cfg2_layer_fwd", False), ("cfg2_layer_fwd", True), ("cfg6_paper_heads", False)])
+def test_hconv_full_size_sampled_heads(name, bf16):
+    """A benchmark configuration at full size, launched as bench.py --hconv launches it; whole heads are
+    sampled (the convolution needs every harmonic of a head) and compared with the oracle on those heads."""
+    import torch
+    from paper_2604_04250_amd import binding as K
+    from paper_2604_04250_amd import workloads as WL
+    G = _gpu()
+    wl = WL.CONFIGS[name]
+    B, L, H, F, J, Kc = wl.B, wl.L, wl.H, wl.F, wl.J, wl.conv_k
+    inp = WL.make_inputs(wl, theta=K.cawn_theta_init(H, F), with_grads=False)
+    if bf16:
+        inp = dict(inp, mag=G.bf16_exact(inp["mag"]), ang=G.bf16_exact(inp["ang"]))
+    r = np.random.Generator(np.random.PCG64(6100))
+    hw = (r.standard_normal((2, H, 3)) / np.sqrt(3.0)).astype(np.float32)
+    hb = (0.1 * r.standard_normal((2, H))).astype(np.float32)
+    heads = sorted({0, H - 1, int(r.integers(0, H))})
+    lanes = np.concatenate([np.arange(h * F, (h + 1) * F) for h in heads])
+    n = len(heads)
+    cfg = O.Cfg(B, L, n, F, conv_k=Kc, gate_tau=wl.gate_tau)
+    of = O.phase_fwd(cfg, np.ascontiguousarray(inp["mag"][..., lanes]), np.ascontiguousarray(inp["ang"][..., lanes]),
+                     inp["gamma"][lanes], inp["theta"][lanes], conv_w=np.ascontiguousarray(inp["conv_w"][:, lanes]),
+                     conv_b=np.ascontiguousarray(inp["conv_b"][:, lanes]))
+    c_re, c_im = O.harmonic_conv(of["z_re"], of["z_im"], n, F, hw[:, heads], hb[:, heads])
+    d = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau, hconv_k=3)
+    dev = G.DEV
+    adt = torch.bfloat16 if bf16 else torch.float32
+    t = {k: torch.from_numpy(inp[k]).to(dev) for k in inp}
+    mag, ang = t["mag"].to(adt), t["ang"].to(adt)
+    z_re, z_im = torch.empty((B, L, J), device=dev, dtype=adt), torch.empty((B, L, J), device=dev, dtype=adt)
+    ws = K.alloc_workspace(d, dev)
+    K.check(K.cawn_phase_accumulate_hconv_fwd(d, mag, ang, None, None, None, t["gamma"], t["theta"], t["conv_w"],
+                                              t["conv_b"], torch.from_numpy(hw).to(dev), torch.from_numpy(hb).to(dev),
+                                              None, z_re, z_im, None, None, None, ws,
+                                              activations_bf16=1 if bf16 else 0))
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    li = torch.from_numpy(lanes).to(dev)
+    g_re, g_im = z_re[..., li].float().cpu().numpy(), z_im[..., li].float().cpu().numpy()
+    if bf16:
+        assert max(G.bf16_err(g_re, c_re), G.bf16_err(g_im, c_im)) <= 1.0
+    else:
+        assert max(G.rel_err(g_re, c_re), G.rel_err(g_im, c_im)) <= TOL
