@@ -367,7 +367,7 @@ def main():
         achieved = alg / (per_call_ms * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "kernel": fwd_label + " (per 4096-token chunk call, launch gaps included)",
                            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                           "traffic": read_traffic(args.workload), "avg_ms": per_call_ms}
+                           "traffic": None if extra else read_traffic(args.workload), "avg_ms": per_call_ms}
         out["stream"] = {"calls": ncalls, "state_bytes": nstate * 4, "device_mem_delta_bytes": int(mem1 - mem0)}
     else:
         fwd_all = [r[0].elapsed_time(r[1]) for r in recs]
