@@ -121,8 +121,9 @@ __device__ __forceinline__ void stage_consts(float *sC, const float *table, int 
 // stored: channel = (plane, head), three taps along the harmonics of the head, zeros beyond its ends.
 // Neighbouring harmonics are neighbouring lanes of a row.  A head wider than a lane block (F = 32 G,
 // G > 1) is handled by one workgroup drawing the G tickets of the head's blocks together and taking
-// them in order: the last lane of a block leaves its value and its unfinished output in LDS, and the
-// first lane of the next block completes and stores that output next to its own.
+// them in order (every other group from the top block down): the lane of a block that borders the
+// next block to come leaves its value and its unfinished output in LDS, and the bordering lane of
+// that next block completes the output and stores it next to its own.
 template <int V, int KC, bool VALVE, bool RET, bool BF, bool HC>
 __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_FWD_WAVES + 1 : CAWN_FWD_WAVES) void fwd_kernel(const FwdArgs a)
 {
