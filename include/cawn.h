@@ -54,7 +54,9 @@ typedef struct cawn_desc {
     int32_t amp_mode;     /* 0 amplitude = magnitude stream; 1 = min(softplus(.), 10), Sec. 3.3 */
     int32_t gate_mode;    /* 0 per-lane threshold on |a| (cawn_phase_accumulate_fwd/_bwd);
                              1 per-head input valve (cawn_phase_accumulate_valve_fwd/_bwd; needs
-                             F % 32 == 0, F == 16 or F == 8); else CAWN_EUNSUPPORTED            */
+                             F % 32 == 0, F == 16 or F == 8, CAWN_EUNSUPPORTED otherwise); any other
+                             value, or a mode passed to an entry point that is not its own:
+                             CAWN_EINVAL                                                         */
     float gate_tau;       /* gate_mode 0: keep when |a| >= gate_tau; 0 = gate open              */
     float conv_clamp;     /* 50 in the paper; +inf disables                                     */
     float out_clamp;      /* 100; +inf disables                                                 */
@@ -77,18 +79,26 @@ typedef struct cawn_desc {
     int64_t out_stride_b, out_stride_t; /* element strides of z_re/z_im/dz_re/dz_im; 0 = dense  */
 } cawn_desc;
 
-/* State blob: [B][2][J] scan state (re, im of S at the last token, unclamped) followed by
+/* State blob (Sec. 3.7 and Sec. 5.1: the fixed-size phase state that chunked prefill and decoding
+ * carry; Sec. 5.2: the two-step history of the Temporal Syntax Cache beside it):
+ * [B][2][J] scan state (re, im of S at the last token, unclamped) followed by
  * [B][conv_k-1][2][J] conv history (last conv_k-1 PRE-conv rows, oldest first, mag then ang).
- * J = H*F.  The same layout is used for the gradient blobs dstate_out / dstate_in. */
+ * J = H*F.  The same layout is used for the gradient blobs dstate_out / dstate_in.
+ * Returns 0 for an invalid descriptor. */
 size_t cawn_state_bytes(const cawn_desc *d);
 
-/* Scratch the kernels need: carry descriptors of the tile chain, the lane table, reduction
- * partials.  Must be 256-byte aligned and must have been passed ONCE to cawn_workspace_init
- * before its first use; calls leave it ready for the next call. */
+/* Scratch the kernels need to evaluate the recurrence of Sec. 3.4 tile-parallel: the carries that
+ * the time tiles of one lane publish to each other, the per-lane constants (powers of
+ * gamma e^{i theta}, conv taps), and the per-tile partial sums of the parameter gradients (Sec. 3.5).
+ * Must be 256-byte aligned and must have been passed ONCE to cawn_workspace_init before its first
+ * use; calls leave it ready for the next call, with any descriptor.  Returns 0 for an invalid
+ * descriptor. */
 size_t cawn_workspace_bytes(const cawn_desc *d);
 
-/* Forward checkpoints the backward consumes: the unclamped scan state before every
- * cawn_tile_len()-th token, [B][ceil(L / cawn_tile_len())][2][J]. */
+/* Forward checkpoints the backward consumes (the gradients of the retention and of the rotation
+ * angle, Sec. 3.5, need the state S[t-1] of Sec. 3.4; it is rebuilt from these instead of being
+ * stored per token): the unclamped scan state before every cawn_tile_len()-th token,
+ * [B][ceil(L / cawn_tile_len())][2][J].  Returns 0 for an invalid descriptor. */
 size_t cawn_ckpt_bytes(const cawn_desc *d);
 
 /* Tokens between checkpoints (the backward kernel's time tile). */
@@ -299,6 +309,16 @@ int cawn_phase_accumulate_bf16_bwd(const cawn_desc *d, const uint16_t *mag, cons
                                    float *dvalve, float *dret, float *dgamma, float *dtheta,
                                    float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
                                    size_t workspace_bytes, void *stream);
+
+/*
+ * Measurement aid, not part of the layer: a plain streaming copy with the forward's traffic shape
+ * (two fp32 streams of n elements read, two written: 8 bytes in and 8 bytes out per element, every
+ * byte touched once).  What it reaches on the device at hand is the practical ceiling against which
+ * the HBM roofline fractions of the scan kernels are read.  n must be a multiple of 4 and the four
+ * device pointers 16-byte aligned (CAWN_EUNSUPPORTED otherwise); inputs must not alias outputs.
+ */
+int cawn_stream_copy(const float *in0, const float *in1, float *out0, float *out1, size_t n,
+                     void *stream);
 
 #ifdef __cplusplus
 }

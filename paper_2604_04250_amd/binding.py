@@ -22,7 +22,7 @@ EXPORTS = ["cawn_state_bytes", "cawn_workspace_bytes", "cawn_ckpt_bytes", "cawn_
            "cawn_theta_init", "cawn_syntax_conv", "cawn_phase_accumulate_fwd",
            "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_bf16_bwd", "cawn_phase_accumulate_bf16_fwd", "cawn_phase_accumulate_hconv_fwd", "cawn_phase_accumulate_ret_bwd", "cawn_phase_accumulate_ret_fwd",
            "cawn_phase_accumulate_valve_fwd",
-           "cawn_phase_accumulate_valve_bwd"]
+           "cawn_phase_accumulate_valve_bwd", "cawn_stream_copy"]
 
 
 class cawn_desc(C.Structure):
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
                                                      [C.c_size_t, C.c_void_p])
         L.cawn_phase_accumulate_hconv_fwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 18 +
                                                       [C.c_size_t, C.c_int32, C.c_void_p])
+        L.cawn_stream_copy.argtypes = [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
         _lib = L
     return _lib
 
@@ -250,6 +251,11 @@ def cawn_phase_accumulate_bf16_bwd(d, mag, ang, valve, ret, ret_bias, gamma, the
         _ptr(dmag), _ptr(dang), _ptr(dvalve), _ptr(dret), _ptr(dgamma), _ptr(dtheta), _ptr(dconv_w),
         _ptr(dconv_b), _ptr(dstate_in), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(stream))
+
+
+def cawn_stream_copy(in0, in1, out0, out1, stream=None) -> int:
+    """Plain copy of two fp32 streams (the bandwidth ceiling the scan kernels are read against)."""
+    return lib().cawn_stream_copy(_ptr(in0), _ptr(in1), _ptr(out0), _ptr(out1), in0.numel(), _stream(stream))
 
 
 def alloc_workspace(d: cawn_desc, device="cuda:0") -> torch.Tensor:

@@ -19,12 +19,15 @@ static bool desc_ok(const cawn_desc *d)
     if (d->B <= 0 || d->L < 0 || d->H <= 0 || d->F <= 0) return false;
     if ((int64_t)d->H * d->F > (1 << 24)) return false;
     if (d->conv_k < 0) return false;
+    if (d->gate_mode != 0 && d->gate_mode != 1) return false;
     if (d->ret_mode != 0 && d->ret_mode != 1) return false;
     if (d->hconv_k != 0 && d->hconv_k != 3) return false;
     return true;
 }
 
-static WsLayout make_layout(const cawn_desc *d)
+// fwd_only: the layout of a workspace that only forward calls use (the allocation-free entry point):
+// published words for the forward's tiles, no backward halo, no partial sums.
+static WsLayout make_layout(const cawn_desc *d, bool fwd_only = false)
 {
     WsLayout w{};
     w.J = d->H * d->F;
@@ -32,7 +35,8 @@ static WsLayout make_layout(const cawn_desc *d)
     w.Jp128 = (int)align_up(w.J, 256);   // covers the widest lane block of any kernel variant
     w.nT = (d->L + CKPT_T - 1) / CKPT_T;      // backward tiles = checkpoint intervals (the finer of the two tilings)
     const int kc = d->conv_k > MAX_KC ? MAX_KC : d->conv_k;
-    const size_t tiles_rows = (size_t)d->B * (w.nT > 0 ? w.nT : 1);
+    const int nT_pub = fwd_only ? (d->L + FwdGeom::TILE_T - 1) / FwdGeom::TILE_T : w.nT;
+    const size_t tiles_rows = (size_t)d->B * (nT_pub > 0 ? nT_pub : 1);
     size_t o = sizeof(WsHeader);
     w.off_table = o;
     o = align_up(o + (size_t)lane_rows(kc, d->hconv_k != 0) * w.Jp * sizeof(float), 256);
@@ -41,16 +45,16 @@ static WsLayout make_layout(const cawn_desc *d)
     w.off_pre = o;
     o = align_up(o + tiles_rows * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_halo = o;
-    o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(tagged_t), 256);
+    if (!fwd_only) o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_part = o;
-    o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
+    if (!fwd_only) o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
     w.off_vpart = o;    // gate_mode 1: per-group sums of the valve's gradient terms, [B][groups][L]
-    if (d->gate_mode == 1)
+    if (d->gate_mode == 1 && !fwd_only)
         o = align_up(o + (size_t)d->B * (size_t)(d->H * (d->F >= 32 ? d->F / 32 : 1)) * (size_t)(d->L > 0 ? d->L : 1) * sizeof(float), 256);
     w.off_aggp = o;     // ret_mode 1: third chained word of a tile's aggregate (product of its retentions)
     if (d->ret_mode == 1) o = align_up(o + tiles_rows * w.Jp128 * sizeof(tagged_t), 256);
     w.off_rpart = o;    // ret_mode 1: per-group sums of the retention logits' gradient terms, [B][groups][L]
-    if (d->ret_mode == 1)
+    if (d->ret_mode == 1 && !fwd_only)
         o = align_up(o + (size_t)d->B * (size_t)(d->H * (d->F >= 32 ? d->F / 32 : 1)) * (size_t)(d->L > 0 ? d->L : 1) * sizeof(float), 256);
     w.off_dbg = o;
 #ifdef CAWN_TIMING
@@ -384,6 +388,28 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
     }
 }
 
+// Plain streaming copy with the forward's traffic shape: two fp32 streams in, two out, 8 bytes read and
+// 8 bytes written per element, 16-byte accesses, every byte touched once.  What this kernel reaches
+// is the practical ceiling of the HBM roofline on the chip at hand; it computes nothing.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const float4 *__restrict__ a0, const float4 *__restrict__ a1,
+                                                          float4 *__restrict__ o0, float4 *__restrict__ o1, size_t n4)
+{
+    constexpr int U = 4;     // independent 16-byte loads in flight per stream and thread
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + (U - 1) * stride < n4; i += U * stride) {
+        float4 x[U], y[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { x[u] = a0[i + u * stride]; y[u] = a1[i + u * stride]; }
+#pragma unroll
+        for (int u = 0; u < U; ++u) { o0[i + u * stride] = x[u]; o1[i + u * stride] = y[u]; }
+    }
+    for (; i < n4; i += stride) {
+        o0[i] = a0[i];
+        o1[i] = a1[i];
+    }
+}
+
 static hipError_t build_table(const cawn_desc *d, const WsLayout &w, char *ws, const float *gamma,
                               const float *theta, const float *conv_w, const float *conv_b,
                               const float *ret_bias, hipStream_t s, const float *hconv_w = nullptr,
@@ -521,7 +547,7 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
                     const float *ret, const float *ret_bias, const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
                     const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
                     uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream, bool bf16 = false,
-                    const float *hconv_w = nullptr, const float *hconv_b = nullptr)
+                    const float *hconv_w = nullptr, const float *hconv_b = nullptr, bool fwd_only_ws = false)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
     // the harmonic convolution belongs to its own entry point (which passes the taps)
@@ -533,7 +559,7 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
     if (d->gate_mode == 1 && d->ret_mode == 1 && d->F < 16) return CAWN_EUNSUPPORTED;   // LDS for both logit tiles
     hipStream_t s = (hipStream_t)stream;
-    const WsLayout w = make_layout(d);
+    const WsLayout w = make_layout(d, fwd_only_ws);
     const long long J = w.J;
     if (d->L == 0) {   // nothing to scan: the state passes through
         if (state_out && state_out != state_in) {
@@ -630,7 +656,7 @@ int cawn_phase_accumulate_fwd(const cawn_desc *d, const float *mag, const float 
                               uint32_t *gate_mask, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 0 || d->ret_mode != 0) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode != 0 || d->ret_mode != 0) return CAWN_EINVAL;      // those modes have entry points of their own
     return fwd_impl(d, mag, ang, nullptr, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, z_re, z_im, state_out, ckpt,
                     gate_mask, workspace, workspace_bytes, stream);
 }
@@ -806,7 +832,7 @@ int cawn_phase_accumulate_bwd(const cawn_desc *d, const float *mag, const float 
                               size_t workspace_bytes, void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
-    if (d->gate_mode != 0 || d->ret_mode != 0) return CAWN_EUNSUPPORTED;
+    if (d->gate_mode != 0 || d->ret_mode != 0) return CAWN_EINVAL;      // those modes have entry points of their own
     return bwd_impl(d, mag, ang, nullptr, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, ckpt, dz_re, dz_im, dstate_out,
                     dmag, dang, nullptr, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace, workspace_bytes,
                     stream);
@@ -890,6 +916,28 @@ int cawn_phase_accumulate_ret_bwd(const cawn_desc *d, const float *mag, const fl
     return bwd_impl(d, mag, ang, valved ? valve : nullptr, ret, ret_bias, nullptr, theta, conv_w, conv_b, state_in,
                     ckpt, dz_re, dz_im, dstate_out, dmag, dang, valved ? dvalve : nullptr, dret, nullptr, dtheta,
                     dconv_w, dconv_b, dstate_in, workspace, workspace_bytes, stream);
+}
+
+int cawn_stream_copy(const float *in0, const float *in1, float *out0, float *out1, size_t n, void *stream)
+{
+    if (!in0 || !in1 || !out0 || !out1) return CAWN_EINVAL;
+    if (n % 4 || !aligned(in0, 16) || !aligned(in1, 16) || !aligned(out0, 16) || !aligned(out1, 16)) return CAWN_EUNSUPPORTED;
+    if (n == 0) return CAWN_OK;
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return CAWN_ELAUNCH;
+        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    }
+    const size_t n4 = n / 4;
+    size_t blocks = (n4 + 255) / 256;
+    const size_t resident = (size_t)cus * 8;       // 8 workgroups of 4 waves per CU
+    if (blocks > resident) blocks = resident;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       reinterpret_cast<const float4 *>(in0), reinterpret_cast<const float4 *>(in1),
+                       reinterpret_cast<float4 *>(out0), reinterpret_cast<float4 *>(out1), n4);
+    return hipGetLastError() == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
 }
 
 }  // extern "C"

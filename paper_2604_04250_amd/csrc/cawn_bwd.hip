@@ -181,7 +181,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     __syncthreads();
     uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
     const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
-    const uint32_t tag = epoch + 1;      // of every word this call publishes (0 is never valid)
+    const uint32_t tag = make_tag(epoch);      // of every word this call publishes
 
     // Persistent: each workgroup loops over tiles, handed out in chain order by an atomic ticket.  A
     // workgroup also holds the ticket of its next tile: it asks for it just before the previous tile's
@@ -1213,15 +1213,25 @@ static hipError_t launch_bwd_vp(const BwdArgs &a, int conv_k, hipStream_t s)
 {
     return a.bf16 ? launch_bwd_vpb<V, PARAM, VALVE, RET, true>(a, conv_k, s) : launch_bwd_vpb<V, PARAM, VALVE, RET, false>(a, conv_k, s);
 }
+// Tuning aid: -DCAWN_DEV_KC=<k> compiles only the conv_k = k kernels and -DCAWN_DEV_PLAIN only the
+// threshold-mode fp32 ones (a build for timing one variant in seconds; every other variant then
+// fails to launch with hipErrorInvalidValue).  The library is always built without them.
 template <int V, bool PARAM, bool VALVE, bool RET, bool BF>
 static hipError_t launch_bwd_vpb(const BwdArgs &a, int conv_k, hipStream_t s)
 {
+#ifdef CAWN_DEV_PLAIN
+    if constexpr (VALVE || RET || BF) return hipErrorInvalidValue; else
+#endif
     switch (conv_k) {
+#ifdef CAWN_DEV_KC
+    case CAWN_DEV_KC: return launch_bwd_vkp<V, CAWN_DEV_KC, PARAM, VALVE, RET, BF>(a, s);
+#else
     case 0: return launch_bwd_vkp<V, 0, PARAM, VALVE, RET, BF>(a, s);
     case 1: return launch_bwd_vkp<V, 1, PARAM, VALVE, RET, BF>(a, s);
     case 2: return launch_bwd_vkp<V, 2, PARAM, VALVE, RET, BF>(a, s);
     case 3: return launch_bwd_vkp<V, 3, PARAM, VALVE, RET, BF>(a, s);
     case 4: return launch_bwd_vkp<V, 4, PARAM, VALVE, RET, BF>(a, s);
+#endif
     default: return hipErrorInvalidValue;
     }
 }

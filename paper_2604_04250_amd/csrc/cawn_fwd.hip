@@ -179,7 +179,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
     __syncthreads();
     uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
     const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
-    const uint32_t tag = epoch + 1;      // of every word this call publishes (0 is never valid)
+    const uint32_t tag = make_tag(epoch);      // of every word this call publishes
 
     // From here on the kernel's arguments are read from the kernel-argument segment again in every
     // phase of a tile (scalar loads next to their use; `ARGS_AGAIN()` makes the compiler forget what it
@@ -617,10 +617,10 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                     // No branch in here, so the steps stay one block of code.  MULTI (a head spans several
                     // blocks): every lane reads the slot of its row (a broadcast) and selects; every lane
                     // writes -- the deferring lane into the slot, the others into words of sE that only they
-                    // write and nobody reads before the next tile rewrites them; the deferring lane stores
-                    // its unfinished output like any other lane and the receiving lane of the next tile (same
-                    // wave, so later at the same address) overwrites it; the receiving lane's second store
-                    // goes to the neighbouring element, every other lane's second store repeats its first.
+                    // write and nobody reads before the next tile rewrites them; the deferring lane's global
+                    // stores are masked off and the receiving lane of the next tile stores the completed
+                    // element; the receiving lane's second store goes to that neighbouring element, every
+                    // other lane's second store repeats its first.
                     constexpr int CH = 4;
                     static_assert(NSTEP % CH == 0, "whole chunks");
 #pragma unroll
@@ -682,7 +682,9 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                                 wp[0] = cr_;
                                 wp[h_defer ? PL : 0] = ci_;
                             }
-                            if (PLAIN || (active && t0 + c0 + k < a.L)) {
+                            // (the deferring lane stores nothing: the receiving lane of the head's next block
+                            // stores the completed element, so exactly one store reaches that address)
+                            if ((PLAIN || (active && t0 + c0 + k < a.L)) && !(MULTI && h_defer)) {
                                 char *pr_ = reinterpret_cast<char *>(zre) + off, *pi_ = reinterpret_cast<char *>(zim) + off;
                                 if constexpr (BF) {
                                     *reinterpret_cast<uint16_t *>(pr_) = to_bf16(cr_);
@@ -1004,21 +1006,34 @@ static hipError_t launch_fwd_vkh(const FwdArgs &a0, hipStream_t s)
 template <int V, int KC, bool VALVE, bool RET, bool BF>
 static hipError_t launch_fwd_vk(const FwdArgs &a, hipStream_t s)
 {
+#ifndef CAWN_DEV_PLAIN
     if constexpr (V == 1) {
         if (a.hconv) return launch_fwd_vkh<1, KC, VALVE, RET, BF, true>(a, s);
     }
+#endif
     return launch_fwd_vkh<V, KC, VALVE, RET, BF, false>(a, s);
 }
 
+// Tuning aid: -DCAWN_DEV_KC=<k> compiles only the conv_k = k kernels and -DCAWN_DEV_PLAIN only the
+// threshold-mode fp32 ones without the harmonic convolution (a build for timing one variant in
+// seconds; every other variant then fails to launch with hipErrorInvalidValue).  The library is
+// always built without them.
 template <int V, bool VALVE, bool RET, bool BF>
 static hipError_t launch_fwd_vmb(const FwdArgs &a, int conv_k, hipStream_t s)
 {
+#ifdef CAWN_DEV_PLAIN
+    if constexpr (VALVE || RET || BF) return hipErrorInvalidValue; else
+#endif
     switch (conv_k) {
+#ifdef CAWN_DEV_KC
+    case CAWN_DEV_KC: return launch_fwd_vk<V, CAWN_DEV_KC, VALVE, RET, BF>(a, s);
+#else
     case 0: return launch_fwd_vk<V, 0, VALVE, RET, BF>(a, s);
     case 1: return launch_fwd_vk<V, 1, VALVE, RET, BF>(a, s);
     case 2: return launch_fwd_vk<V, 2, VALVE, RET, BF>(a, s);
     case 3: return launch_fwd_vk<V, 3, VALVE, RET, BF>(a, s);
     case 4: return launch_fwd_vk<V, 4, VALVE, RET, BF>(a, s);
+#endif
     default: return hipErrorInvalidValue;
     }
 }

@@ -87,10 +87,14 @@ inline __host__ __device__ int lane_rows(int conv_k, bool hconv = false) { retur
 // ----------------------------------------------------------------------------------- workspace
 // Workspace: [header 1 KiB][lane table][aggregates][prefixes][backward conv halo][backward parameter
 // partials].  Everything tiles publish to each other (aggregates, prefixes, halo rows) is stored as
-// 8-byte words {value, tag}: the tag is the epoch of the call plus one, so a word is valid exactly
+// 8-byte words {value, tag}: the tag is make_tag(epoch of the call), so a word is valid exactly
 // when its tag matches -- no separate status words, no ordering between stores, one memory round trip
 // from publication to use.  Words left by earlier calls (whatever their descriptor) carry other tags
-// and read as "not published"; cawn_workspace_init zeroes the whole buffer (tag 0 is never valid).
+// and read as "not published"; cawn_workspace_init zeroes the whole buffer (a zero word is never a tag).
+// Region offsets depend on the descriptor, so a call may find fp32 data of an earlier call with another
+// descriptor (lane-table rows, partial sums) where it expects published words.  Tags are therefore the
+// bit patterns of negative NaNs with a non-zero payload (0xFF800001 .. 0xFFFFFFFF): no finite value,
+// infinity or hardware-made NaN (0x7FC00000) an fp32 computation leaves behind equals one.
 // Nothing is cleared per tile or per call: the workgroup that leaves last resets the tickets and
 // advances the epoch.
 constexpr int MAX_QUEUES = 64;
@@ -98,7 +102,7 @@ struct WsHeader {
     uint32_t ticket[MAX_QUEUES];   // ticket[0]: next tile to hand out (the other words are spare)
     uint32_t done;                 // tiles finished
     uint32_t error;                // sticky: a tile gave up waiting
-    uint32_t epoch;                // calls completed on this workspace (mod 2^30): tag of published words - 1
+    uint32_t epoch;                // calls completed on this workspace (mod EPOCH_MOD): make_tag() of it marks published words
     uint32_t bytes_lo, bytes_hi;   // size given to cawn_workspace_init (what an epoch wrap has to clear)
     uint32_t pad[256 - MAX_QUEUES - 5];
 };
@@ -109,8 +113,9 @@ struct WsLayout {
     size_t off_table, off_agg, off_pre, off_halo, off_part, off_vpart, off_aggp, off_rpart, off_dbg, total;
 };
 
-constexpr uint32_t EPOCH_MOD = 1u << 30;
+constexpr uint32_t EPOCH_MOD = (1u << 23) - 1u;     // epochs 0 .. 2^23 - 2
 typedef unsigned long long tagged_t;     // {fp32 value (low half), tag (high half)}
+inline __host__ __device__ uint32_t make_tag(uint32_t epoch) { return 0xFF800001u + epoch; }
 
 // Gate as a union of two closed fp32 intervals on the quantity the decision is taken on (the
 // fp32 conv pre-activation, or the raw magnitude input when there is no conv).
@@ -423,7 +428,7 @@ __device__ __forceinline__ float tagged_value(tagged_t w) { return __uint_as_flo
 
 // End of a call, run by thread `tid` of the `nthreads` of the workgroup that left last: tickets and
 // the finished-workgroup count return to zero and the epoch advances.  When the epoch wraps, words of
-// 2^30 calls ago would become valid again: everything behind the lane table is cleared then
+// EPOCH_MOD calls ago would become valid again: everything behind the lane table is cleared then
 // (`clear_from`: byte offset of this call's first published word).
 __device__ __forceinline__ void finish_call(WsHeader *hdr, size_t clear_from, uint32_t epoch, uint32_t tid,
                                             uint32_t nthreads)

@@ -76,8 +76,18 @@ def test_host_side_argument_checks_reject_before_any_launch():
     bad = K.make_desc(2, 128, 2, 16, conv_k=9)
     assert L.cawn_phase_accumulate_fwd(C.byref(bad), *args, 0, null) == K.CAWN_EUNSUPPORTED
     bad = K.make_desc(2, 128, 2, 16)
-    bad.gate_mode = 1
-    assert L.cawn_phase_accumulate_fwd(C.byref(bad), *args, 0, null) == K.CAWN_EUNSUPPORTED
+    bad.gate_mode = 1       # a valid mode at the wrong entry point, and values that are no mode at all
+    assert L.cawn_phase_accumulate_fwd(C.byref(bad), *args, 0, null) == K.CAWN_EINVAL
+    assert L.cawn_phase_accumulate_bwd(C.byref(bad), *([null] * 19), 0, null) == K.CAWN_EINVAL
+    assert L.cawn_phase_accumulate_valve_fwd(C.byref(K.make_desc(2, 128, 2, 16)), *([null] * 14), 0, null) == K.CAWN_EINVAL
+    for gm in (2, -1, 77):
+        bad.gate_mode = gm
+        assert K.cawn_workspace_bytes(bad) == 0 and K.cawn_state_bytes(bad) == 0
+        assert L.cawn_phase_accumulate_fwd(C.byref(bad), *args, 0, null) == K.CAWN_EINVAL
+        assert L.cawn_phase_accumulate_valve_fwd(C.byref(bad), *([null] * 14), 0, null) == K.CAWN_EINVAL
+        assert L.cawn_phase_accumulate_ret_fwd(C.byref(bad), *([null] * 15), 0, null) == K.CAWN_EINVAL
+        assert L.cawn_phase_accumulate_bf16_fwd(C.byref(bad), *([null] * 16), 0, null) == K.CAWN_EINVAL
+        assert L.cawn_phase_accumulate_bf16_bwd(C.byref(bad), *([null] * 24), 0, null) == K.CAWN_EINVAL
     assert L.cawn_phase_accumulate_fwd(C.byref(K.make_desc(-1, 1, 1, 1)), *args, 0, null) == K.CAWN_EINVAL
     # workspace too small / misaligned: fake non-null pointers are never dereferenced on the host
     fake = C.c_void_p(0x1000)

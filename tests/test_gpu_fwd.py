@@ -322,9 +322,9 @@ def test_spin_limit_timeout_is_reported_and_every_wave_exits():
 
 
 def test_epoch_wrap_clears_published_words():
-    """Published words are valid when their tag equals the call's epoch + 1, and the epoch wraps every
-    2^30 calls: the call that wraps it clears every published word, so that a word of 2^30 calls ago
-    cannot pass for a fresh one.  The host sets the workspace's epoch counter just below the wrap; the
+    """Published words are valid when their tag is the one made from the call's epoch, and the epoch wraps
+    every 2^23 - 1 calls: the call that wraps it clears every published word, so that a word of that many
+    calls ago cannot pass for a fresh one.  The host sets the workspace's epoch counter just below the wrap; the
     calls before, across and after it (forward and backward, each advancing the epoch) must all agree
     with the oracle."""
     G = _gpu()
@@ -345,9 +345,10 @@ def test_epoch_wrap_clears_published_words():
     G.run_fwd_bwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, ws=ws)       # leaves words tagged with small epochs
     EPOCH_WORD = 64 + 2                 # header: 64 ticket words, finished count, error flag, epoch
     torch.cuda.synchronize()
-    ws[EPOCH_WORD] = (1 << 30) - 3
+    EPOCH_MOD = (1 << 23) - 1
+    ws[EPOCH_WORD] = EPOCH_MOD - 3
     seen = []
-    for _ in range(4):                  # 8 calls: epochs 2^30 - 3 ... 2^30 - 1, 0, 1, ...
+    for _ in range(4):                  # 8 calls: epochs EPOCH_MOD - 3 ... EPOCH_MOD - 1, 0, 1, ...
         out = G.run_fwd_bwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, ws=ws)
         fw = G.run_fwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, ws=ws, want_mask=False)
         torch.cuda.synchronize()

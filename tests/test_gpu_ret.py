@@ -143,7 +143,7 @@ def test_retention_errors():
     d = K.make_desc(1, 8, 2, 32, ret_mode=0)
     assert K.cawn_phase_accumulate_ret_fwd(d, x, x, None, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL
     d = K.make_desc(1, 8, 2, 32, ret_mode=1)
-    assert K.cawn_phase_accumulate_fwd(d, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EUNSUPPORTED
+    assert K.cawn_phase_accumulate_fwd(d, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL        # a mode at an entry point that is not its own
     assert K.cawn_phase_accumulate_ret_fwd(d, x, x, None, None, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL
 
 

@@ -97,7 +97,7 @@ def test_valve_unsupported_head_width_and_wrong_entry_point():
     d = K.make_desc(1, 8, 2, 32, gate_mode=0)
     assert K.cawn_phase_accumulate_valve_fwd(d, x, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL
     d = K.make_desc(1, 8, 2, 32, gate_mode=1)
-    assert K.cawn_phase_accumulate_fwd(d, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EUNSUPPORTED
+    assert K.cawn_phase_accumulate_fwd(d, x, x, x, x, None, None, None, x, x, None, None, None, x) == K.CAWN_EINVAL      # a mode at an entry point that is not its own
 
 
 def _check_bwd(B, L, H, F, Kc, d, amp_mode=0, eps=0.001, state=None, dstate=None, tol=TOL, **kw):
