@@ -311,6 +311,26 @@ int cawn_phase_accumulate_bf16_bwd(const cawn_desc *d, const uint16_t *mag, cons
                                    size_t workspace_bytes, void *stream);
 
 /*
+ * cawn_phase_accumulate_fwd for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace
+ * is a static device array inside the library, CAWN_STATIC_WS_BYTES = 8 MiB per GPU, held until the
+ * process ends; the call allocates and frees nothing.  Arguments, results and errors are those of
+ * cawn_phase_accumulate_fwd (d->gate_mode, d->ret_mode and d->hconv_k must be 0) without `workspace`
+ * and `workspace_bytes`.  A descriptor whose forward-only scratch
+ *   1 KiB + lane table (~66 rows of H*F floats) + 32 bytes * B * ceil(L/256) * roundup(H*F, 256)
+ * exceeds 8 MiB is refused with CAWN_EWORKSPACE before anything is enqueued (B=8, H*F=768, L=8192
+ * fits; pass longer sequences in chunks).  Every call on one GPU shares that GPU's array: calls
+ * that overlap in time on one GPU race (order them on one stream), and d->lane_consts_cached refers
+ * to the previous call of THIS entry point on that GPU.  The first call on a device also writes the
+ * array's header; make that call outside graph capture.
+ */
+int cawn_phase_accumulate_fwd_static(const cawn_desc *d, const float *mag, const float *ang,
+                                     const float *gamma, const float *theta, const float *conv_w,
+                                     const float *conv_b, const void *state_in, float *z_re,
+                                     float *z_im, void *state_out, void *ckpt, uint32_t *gate_mask,
+                                     void *stream);
+
+/*
  * Measurement aid, not part of the layer: a plain streaming copy with the forward's traffic shape
  * (two fp32 streams of n elements read, two written: 8 bytes in and 8 bytes out per element, every
  * byte touched once).  What it reaches on the device at hand is the practical ceiling against which

@@ -22,7 +22,7 @@ EXPORTS = ["cawn_state_bytes", "cawn_workspace_bytes", "cawn_ckpt_bytes", "cawn_
            "cawn_theta_init", "cawn_syntax_conv", "cawn_phase_accumulate_fwd",
            "cawn_phase_accumulate_bwd", "cawn_phase_accumulate_bf16_bwd", "cawn_phase_accumulate_bf16_fwd", "cawn_phase_accumulate_hconv_fwd", "cawn_phase_accumulate_ret_bwd", "cawn_phase_accumulate_ret_fwd",
            "cawn_phase_accumulate_valve_fwd",
-           "cawn_phase_accumulate_valve_bwd", "cawn_stream_copy"]
+           "cawn_phase_accumulate_valve_bwd", "cawn_stream_copy", "cawn_phase_accumulate_fwd_static"]
 
 
 class cawn_desc(C.Structure):
@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
         L.cawn_phase_accumulate_hconv_fwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 18 +
                                                       [C.c_size_t, C.c_int32, C.c_void_p])
         L.cawn_stream_copy.argtypes = [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+        L.cawn_phase_accumulate_fwd_static.argtypes = [C.POINTER(cawn_desc)] + [C.c_void_p] * 13
         _lib = L
     return _lib
 
@@ -251,6 +252,14 @@ def cawn_phase_accumulate_bf16_bwd(d, mag, ang, valve, ret, ret_bias, gamma, the
         _ptr(dmag), _ptr(dang), _ptr(dvalve), _ptr(dret), _ptr(dgamma), _ptr(dtheta), _ptr(dconv_w),
         _ptr(dconv_b), _ptr(dstate_in), _ptr(workspace),
         workspace.numel() * workspace.element_size() if workspace is not None else 0, _stream(stream))
+
+
+def cawn_phase_accumulate_fwd_static(d, mag, ang, gamma, theta, conv_w, conv_b, state_in, z_re, z_im,
+                                     state_out, ckpt, gate_mask, stream=None) -> int:
+    """cawn_phase_accumulate_fwd on the library's static scratch array: allocates nothing."""
+    return lib().cawn_phase_accumulate_fwd_static(
+        C.byref(d), _ptr(mag), _ptr(ang), _ptr(gamma), _ptr(theta), _ptr(conv_w), _ptr(conv_b),
+        _ptr(state_in), _ptr(z_re), _ptr(z_im), _ptr(state_out), _ptr(ckpt), _ptr(gate_mask), _stream(stream))
 
 
 def cawn_stream_copy(in0, in1, out0, out1, stream=None) -> int:

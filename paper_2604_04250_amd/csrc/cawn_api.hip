@@ -389,20 +389,29 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
 }
 
 // Plain streaming copy with the forward's traffic shape: two fp32 streams in, two out, 8 bytes read and
-// 8 bytes written per element, 16-byte accesses, every byte touched once.  What this kernel reaches
-// is the practical ceiling of the HBM roofline on the chip at hand; it computes nothing.
-__global__ __launch_bounds__(256) void stream_copy_kernel(const float4 *__restrict__ a0, const float4 *__restrict__ a1,
-                                                          float4 *__restrict__ o0, float4 *__restrict__ o1, size_t n4)
+// 8 bytes written per element, 16-byte non-temporal accesses, every byte touched once.  What this
+// kernel reaches is the practical ceiling of the HBM roofline on the chip at hand; it computes nothing.
+// (Of the shapes tried at 50 MB .. 1.2 GB -- grid-stride and slab-per-workgroup, 1/2/4 loads in flight,
+// 2 .. 32 workgroups per CU, one element per thread -- this one was at or within 3 % of the best.)
+typedef float v4f __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_copy_kernel(const v4f *__restrict__ a0, const v4f *__restrict__ a1,
+                                                          v4f *__restrict__ o0, v4f *__restrict__ o1, size_t n4)
 {
     constexpr int U = 4;     // independent 16-byte loads in flight per stream and thread
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (; i + (U - 1) * stride < n4; i += U * stride) {
-        float4 x[U], y[U];
+        v4f x[U], y[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) { x[u] = a0[i + u * stride]; y[u] = a1[i + u * stride]; }
+        for (int u = 0; u < U; ++u) {
+            x[u] = __builtin_nontemporal_load(a0 + i + u * stride);
+            y[u] = __builtin_nontemporal_load(a1 + i + u * stride);
+        }
 #pragma unroll
-        for (int u = 0; u < U; ++u) { o0[i + u * stride] = x[u]; o1[i + u * stride] = y[u]; }
+        for (int u = 0; u < U; ++u) {
+            __builtin_nontemporal_store(x[u], o0 + i + u * stride);
+            __builtin_nontemporal_store(y[u], o1 + i + u * stride);
+        }
     }
     for (; i < n4; i += stride) {
         o0[i] = a0[i];
@@ -932,12 +941,55 @@ int cawn_stream_copy(const float *in0, const float *in1, float *out0, float *out
     }
     const size_t n4 = n / 4;
     size_t blocks = (n4 + 255) / 256;
-    const size_t resident = (size_t)cus * 8;       // 8 workgroups of 4 waves per CU
+    const size_t resident = (size_t)cus * 2;       // two workgroups of 4 waves per CU
     if (blocks > resident) blocks = resident;
     hipLaunchKernelGGL(stream_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                       reinterpret_cast<const float4 *>(in0), reinterpret_cast<const float4 *>(in1),
-                       reinterpret_cast<float4 *>(out0), reinterpret_cast<float4 *>(out1), n4);
+                       reinterpret_cast<const v4f *>(in0), reinterpret_cast<const v4f *>(in1),
+                       reinterpret_cast<v4f *>(out0), reinterpret_cast<v4f *>(out1), n4);
     return hipGetLastError() == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
+}
+
+// ---------------------------------------------------------------------- allocation-free forward
+// The workspace of this entry point is a static device array instead of caller memory.  `scratch`
+// names the array for device code only: on the host it is a stand-in, never an address.  The device
+// address is asked for once per device (hipGetSymbolAddress, with that device current) and kept;
+// every launch and fill below takes that pointer.
+#ifndef CAWN_STATIC_WS_BYTES
+#define CAWN_STATIC_WS_BYTES (8u << 20)
+#endif
+static __device__ __align__(256) unsigned char scratch[CAWN_STATIC_WS_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];      // per device: the array's address there, once known
+}
+
+int cawn_phase_accumulate_fwd_static(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
+                                     const float *theta, const float *conv_w, const float *conv_b,
+                                     const void *state_in, float *z_re, float *z_im, void *state_out, void *ckpt,
+                                     uint32_t *gate_mask, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->gate_mode != 0 || d->ret_mode != 0 || d->hconv_k != 0) return CAWN_EINVAL;
+    // sizes beyond the static array are refused before anything touches the device
+    if (make_layout(d, true).total > (size_t)CAWN_STATIC_WS_BYTES) return CAWN_EWORKSPACE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return CAWN_ELAUNCH;
+    void *ws = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ws) {
+        // first call on this device.  The array is zero when the module is loaded (no word carries a
+        // tag); only the header's size field, read when the epoch wraps, has to be written.  Two
+        // threads racing here find the same address and enqueue the same idempotent store.
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CAWN_ELAUNCH;
+        hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream,
+                           reinterpret_cast<WsHeader *>(p), (unsigned long long)CAWN_STATIC_WS_BYTES);
+        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+        ws = p;
+    }
+    return fwd_impl(d, mag, ang, nullptr, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, z_re, z_im,
+                    state_out, ckpt, gate_mask, ws, (size_t)CAWN_STATIC_WS_BYTES, stream, false, nullptr, nullptr, true);
 }
 
 }  // extern "C"
