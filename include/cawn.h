@@ -101,7 +101,7 @@ size_t cawn_workspace_bytes(const cawn_desc *d);
  * [B][ceil(L / cawn_tile_len())][2][J].  Returns 0 for an invalid descriptor. */
 size_t cawn_ckpt_bytes(const cawn_desc *d);
 
-/* Tokens between checkpoints (the backward kernel's time tile). */
+/* Tokens between checkpoints (the run of tokens one backward thread owns). */
 int32_t cawn_tile_len(void);
 
 const char *cawn_status_string(int status);

@@ -33,7 +33,8 @@ static WsLayout make_layout(const cawn_desc *d, bool fwd_only = false)
     w.J = d->H * d->F;
     w.Jp = (int)align_up(w.J, 64);
     w.Jp128 = (int)align_up(w.J, 256);   // covers the widest lane block of any kernel variant
-    w.nT = (d->L + CKPT_T - 1) / CKPT_T;      // backward tiles = checkpoint intervals (the finer of the two tilings)
+    w.nT = (d->L + BwdGeom::TILE_T - 1) / BwdGeom::TILE_T;      // backward tiles (the finer of the two tilings)
+    w.nTc = (d->L + CKPT_T - 1) / CKPT_T;
     const int kc = d->conv_k > MAX_KC ? MAX_KC : d->conv_k;
     const int nT_pub = fwd_only ? (d->L + FwdGeom::TILE_T - 1) / FwdGeom::TILE_T : w.nT;
     const size_t tiles_rows = (size_t)d->B * (nT_pub > 0 ? nT_pub : 1);
@@ -644,7 +645,7 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.agg = reinterpret_cast<tagged_t *>(ws + w.off_agg);
     a.pre = reinterpret_cast<tagged_t *>(ws + w.off_pre);
     a.clear_from = w.off_agg;
-    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = nTf; a.nTc = w.nT; a.nLB = nLB;
+    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = nTf; a.nTc = w.nTc; a.nLB = nLB;
     a.amp_mode = d->amp_mode;
     a.small_angle = (d->conv_k > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;   // |angle| <= SiLU(clamp) <= 41 revolutions
     a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&
@@ -795,7 +796,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.clear_from = w.off_agg;
     a.halo = reinterpret_cast<tagged_t *>(ws + w.off_halo);
     a.part = reinterpret_cast<float *>(ws + w.off_part);
-    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nLB = nLB;
+    a.B = d->B; a.L = d->L; a.J = (int)J; a.Jp = w.Jp; a.nT = w.nT; a.nTc = w.nTc; a.nLB = nLB;
     a.amp_mode = d->amp_mode; a.want_param = want_param ? 1 : 0;
     a.small_angle = (kc > 0 && d->conv_clamp <= 256.0f) ? 1 : 0;
     a.stage16 = (J % 4 == 0 && ist % 4 == 0 && isb % 4 == 0 && aligned(mag, 16) && aligned(ang, 16) &&

@@ -11,8 +11,8 @@
 //     BEFORE the expensive front-end recompute, which then hides the chain's memory round trips;
 //   * the pre-conv input rows are staged once per tile in LDS (direct global->LDS loads): the
 //     conv, its halo and the weight gradient all read them from there, not from registers;
-//   * parameter gradients need the forward state S[t-1]; it is rebuilt inside the tile from the
-//     checkpoint the forward stored for the tile's first token;
+//   * parameter gradients need the forward state S[t-1]; every thread rebuilds it for its own tokens
+//     from the checkpoint the forward stored for the first of them;
 //   * the transposed conv needs the conv pre-activation gradients of the next conv_k-1 tokens.
 //     Inside a tile they cross segments through LDS; across tiles the later tile (earlier in the
 //     chain) publishes its first conv_k-1 rows through the workspace.
@@ -147,11 +147,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // memory operations complete in issue order, so a load issued at the top of a tile returns only after
     // the previous tile's output stores have been acknowledged
     __shared__ float sLam[PF ? 4 : 1][JB];
-    constexpr int N_EB = NSEG * 2 * JB, N_EF = (PARAM ? NSEG : 1) * 2 * JB, N_HALO = (NSEG + 1) * HALO1 * 2 * JB;
-    __shared__ float sPool[PF ? (N_EB + N_EF > N_HALO ? N_EB + N_EF : N_HALO) : N_EB + N_EF + N_HALO];
+    constexpr int N_EB = NSEG * 2 * JB, N_HALO = (NSEG + 1) * HALO1 * 2 * JB;
+    __shared__ float sPool[PF ? (N_EB > N_HALO ? N_EB : N_HALO) : N_EB + N_HALO];
     float (*sEb)[2][JB] = reinterpret_cast<float (*)[2][JB]>(&sPool[0]);
-    float (*sEf)[2][JB] = reinterpret_cast<float (*)[2][JB]>(&sPool[N_EB]);
-    float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(&sPool[PF ? 0 : N_EB + N_EF]);   // [NSEG]: rows of the next tile
+    float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(&sPool[PF ? 0 : N_EB]);   // [NSEG]: rows of the next tile
     __shared__ float sCarry[2][JB];
     __shared__ float sRedOwn[(PARAM && !PF) ? NW : 1][ROWS][JB];
     static_assert(!PF || (size_t)NW * ROWS * JB <= (size_t)2 * NRTP * JBS, "the partial-sum staging fits over the input rows");
@@ -254,21 +253,27 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             lds_barrier();
         }
         // (later tiles: staged during the previous tile, complete before its closing barrier)
+        auto dz_from_lds = [&](auto full_c) {
+            constexpr bool FULL = decltype(full_c)::value;
 #pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-            const int r = seg * NSTEP + i;
-            float vr, vi;
-            if constexpr (BF) {
-                vr = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[r][0])[lv]);
-                vi = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[NRZ + r][0])[lv]);
-            } else {
-                vr = sDz[r][lv];
-                vi = sDz[NRZ + r][lv];
+            for (int i = 0; i < NSTEP; ++i) {
+                const int r = seg * NSTEP + i;
+                float vr, vi;
+                if constexpr (BF) {
+                    vr = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[r][0])[lv]);
+                    vi = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[NRZ + r][0])[lv]);
+                } else {
+                    vr = sDz[r][lv];
+                    vi = sDz[NRZ + r][lv];
+                }
+                const bool live = FULL || (active && t0 + i < a.L);     // rows and lanes outside the tensor staged a valid address
+                dzr[i][0] = live ? vr : 0.f;
+                dzi[i][0] = live ? vi : 0.f;
             }
-            const bool live = full || (active && t0 + i < a.L);     // rows and lanes outside the tensor staged a valid address
-            dzr[i][0] = live ? vr : 0.f;
-            dzi[i][0] = live ? vi : 0.f;
-        }
+        };
+        // (a tile that lies wholly inside the tensors takes the rows as they are: no per-row selects)
+        if (full) dz_from_lds(std::true_type{});
+        else dz_from_lds(std::false_type{});
     } else {
         const size_t gbase = ((size_t)b * a.osb + (size_t)(tt * TILE_T) * a.ost + (size_t)lb * JB) * ES;
         const float *gre = reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.dz_re) + gbase);
@@ -322,6 +327,20 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         ldu<V>(pnr, row(R_PSEGB + 2), jb);                       // lambda^NSTEP
         ldu<V>(pni, row(R_PSEGB + 3), jb);
     }
+    // the forward state before my first token: the checkpoint of my segment (PF: fetched here, so that it
+    // has arrived with the staged rows; the other kernels fetch it behind that wait, next to the
+    // constants of the reverse pass)
+    float kr[V], ki[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) kr[v] = ki[v] = 0.f;
+    auto load_ckpt = [&]() {
+        if (PARAM && active && a.ckpt && t0 < a.L) {
+            const float *ck = a.ckpt + (((size_t)b * a.nTc + t0 / CKPT_T) * 2) * a.J + j0;
+            BVec<V>::ld(kr, ck);
+            BVec<V>::ld(ki, ck + a.J);
+        }
+    };
+    if (PF) load_ckpt();
     float rb[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) rb[v] = 0.f;
@@ -467,23 +486,15 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     lds_barrier();
     BWD_STAMP(3);
 
-    // the forward state entering the tile (checkpoint) and the constants of the reverse pass, fetched
-    // now so that they arrive during the front-end (the valve kernels, at their register budget in
-    // the front-end, fetch them after it)
+    // the constants of the reverse pass, fetched now so that they arrive during the front-end (the
+    // valve kernels, at their register budget in the front-end, fetch them after it)
     // (written out twice rather than as a lambda called from two places: with the lambda the
     // compiler allocates scalar registers differently over the whole loop and spills 2.7x as many)
-    float kr[V], ki[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) kr[v] = ki[v] = 0.f;
     float psr[V], psi[V], cth[V], sth[V], gam[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) { sth[v] = gam[v] = 0.f; cth[v] = 1.f; }
+    if (!PF) load_ckpt();
     if (!LEAN) {
-        if (PARAM && active && a.ckpt) {
-            const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
-            BVec<V>::ld(kr, ck);
-            BVec<V>::ld(ki, ck + a.J);
-        }
         ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);    // adjoint: segments after mine
         ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
         if (PARAM) {
@@ -551,7 +562,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             wait_vm<0>();
         }
 #pragma unroll
-        for (int v = 0; v < V; ++v) Efr[v] = Efi[v] = 0.f;
+        for (int v = 0; v < V; ++v) { Efr[v] = kr[v]; Efi[v] = ki[v]; }      // the true state before my first token
 #pragma unroll
         for (int i = 0; i < NSTEP; ++i) {
 #pragma unroll
@@ -574,9 +585,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     const float sgm = sigmoid_fast(cm), sga = sigmoid_fast(ca);
                     xm = cm * sgm;
                     phi = ca * sga;
-                    // SiLU'(z) = sig (1 + z (1 - sig)); the clamp passes gradient only inside its range
-                    km = __builtin_fabsf(zm) <= a.conv_clamp ? sgm * __builtin_fmaf(cm, 1.0f - sgm, 1.0f) : 0.0f;
-                    ka = __builtin_fabsf(za) <= a.conv_clamp ? sga * __builtin_fmaf(ca, 1.0f - sga, 1.0f) : 0.0f;
+                    // SiLU'(z) = sig (1 + z (1 - sig)) = sig + SiLU(z) (1 - sig); the clamp passes gradient only
+                    // inside its range
+                    km = __builtin_fabsf(zm) <= a.conv_clamp ? __builtin_fmaf(xm, 1.0f - sgm, sgm) : 0.0f;
+                    ka = __builtin_fabsf(za) <= a.conv_clamp ? __builtin_fmaf(phi, 1.0f - sga, sga) : 0.0f;
                 } else {
                     zm = wnm[i % KC1][v];
                     xm = zm;
@@ -608,7 +620,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 sn[i][v] = s;
                 dsm[i][v] = km;
                 ag[i][v] = agv * ka;
-                if (PARAM) {   // forward scan from zero; the state before token i is kept
+                if (PARAM) {   // forward scan from the checkpoint; the state before token i is kept
                     Spr[i][v] = Efr[v];
                     Spi[i][v] = Efi[v];
                     const float pr = agv * c, pi = agv * s;
@@ -637,79 +649,12 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
     }
     if (LEAN) {
-        if (PARAM && active && a.ckpt) {
-            const float *ck = a.ckpt + (((size_t)b * a.nT + tt) * 2) * a.J + j0;
-            BVec<V>::ld(kr, ck);
-            BVec<V>::ld(ki, ck + a.J);
-        }
         ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);
         ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
         if (PARAM && !RET) {      // (retention kernels: the table's lambda is e^{i theta} itself, and gamma is per token)
             ldu<V>(cth, row(R_COS), jb);
             ldu<V>(sth, row(R_SIN), jb);
             ldu<V>(gam, row(R_GAMMA), jb);
-        }
-    }
-
-    // ---- forward state entering my segment (checkpoint + earlier segments), then S[t-1] per token
-    if (PARAM) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            sEf[seg][0][lv * V + v] = Efr[v];
-            sEf[seg][1][lv * V + v] = Efi[v];
-        }
-        lds_barrier();
-    BWD_STAMP(4);
-        float Fr[V], Fi[V], pfr[V], pfi[V];   // lambda^(NSTEP*seg): the segments before mine
-        float Cf[V];        // RET: product of the retentions of the segments before mine
-#pragma unroll
-        for (int v = 0; v < V; ++v) { Fr[v] = Fi[v] = 0.f; Cf[v] = 1.f; }
-        ldu<V>(pfr, row(R_PSEGB + 2 * seg), jb);
-        ldu<V>(pfi, row(R_PSEGB + 2 * seg + 1), jb);
-        for (int qq = 0; qq < seg; ++qq) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const float er = sEf[qq][0][lv * V + v], ei = sEf[qq][1][lv * V + v];
-                float nr, ni;
-                if (RET) {
-                    const float pq = sPb[qq][lv * V + v];
-                    nr = __builtin_fmaf(pq, __builtin_fmaf(pnr[v], Fr[v], -pni[v] * Fi[v]), er);
-                    ni = __builtin_fmaf(pq, __builtin_fmaf(pni[v], Fr[v], pnr[v] * Fi[v]), ei);
-                    Cf[v] *= pq;
-                } else {
-                    nr = __builtin_fmaf(pnr[v], Fr[v], __builtin_fmaf(-pni[v], Fi[v], er));
-                    ni = __builtin_fmaf(pni[v], Fr[v], __builtin_fmaf(pnr[v], Fi[v], ei));
-                }
-                Fr[v] = nr;
-                Fi[v] = ni;
-            }
-        }
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            float nr, ni;
-            if (RET) {
-                nr = __builtin_fmaf(Cf[v], __builtin_fmaf(pfr[v], kr[v], -pfi[v] * ki[v]), Fr[v]);
-                ni = __builtin_fmaf(Cf[v], __builtin_fmaf(pfi[v], kr[v], pfr[v] * ki[v]), Fi[v]);
-            } else {
-                nr = __builtin_fmaf(pfr[v], kr[v], __builtin_fmaf(-pfi[v], ki[v], Fr[v]));
-                ni = __builtin_fmaf(pfi[v], kr[v], __builtin_fmaf(pfr[v], ki[v], Fi[v]));
-            }
-            Fr[v] = nr;
-            Fi[v] = ni;
-        }
-        // S[t-1] = (scan from zero) + lambda^i * (true state entering the segment)
-#pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                Spr[i][v] += Fr[v];
-                Spi[i][v] += Fi[v];
-                float nr = __builtin_fmaf(lr[v], Fr[v], -li[v] * Fi[v]);
-                float ni = __builtin_fmaf(li[v], Fr[v], lr[v] * Fi[v]);
-                if (RET) { nr *= gm[i][v]; ni *= gm[i][v]; }
-                Fr[v] = nr;
-                Fi[v] = ni;
-            }
         }
     }
 

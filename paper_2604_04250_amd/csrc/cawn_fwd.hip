@@ -575,11 +575,13 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
             }
         }
 
-        // ---- checkpoints for the backward pass: the state before every CKPT_T-th token
-        if (a.ckpt && (seg * NSTEP) % CKPT_T == 0 && active && t0 < a.L) {
-            float *ck = a.ckpt + (((size_t)b * a.nTc + t0 / CKPT_T) * 2) * a.J + j0;
-            Vec<V>::st(ck, Sr);
-            Vec<V>::st(ck + a.J, Si);
+        // ---- checkpoints for the backward pass: the state before every CKPT_T-th token.  The one at
+        //      the start of my segment goes out here, the others from inside the replay.
+        float *ckp = a.ckpt ? a.ckpt + (((size_t)b * a.nTc + t0 / CKPT_T) * 2) * a.J + (active ? j0 : 0) : nullptr;
+        const uint32_t ck_step = (uint32_t)a.J * 2u * 4u;       // bytes from one checkpoint of a lane to the next
+        if (ckp && active && t0 < a.L) {
+            Vec<V>::st(ckp, Sr);
+            Vec<V>::st(ckp + a.J, Si);
         }
 
         // ---- replay from the true state, clamp, store.  Addresses are a wave-uniform base plus a
@@ -607,8 +609,9 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
             const bool h_tl = h_prev && !h_dn, h_tr = h_prev && h_dn;        // which neighbour comes from LDS
             // where the completed output is stored (0: this lane has none to complete, its second store repeats its first)
             const ptrdiff_t h_back = h_prev ? (h_dn ? (ptrdiff_t)ES : -(ptrdiff_t)ES) : 0;
-            auto replay = [&](auto plain_c, auto multi_c) {
+            auto replay = [&](auto plain_c, auto multi_c, auto ck_c) {
                 constexpr bool PLAIN = decltype(plain_c)::value;
+                constexpr bool CK = decltype(ck_c)::value;       // checkpoints wanted (uniform over the launch)
                 // heads of several lane blocks (1, 2); this tile completes outputs of the previous one (2)
                 constexpr bool MULTI = HC && decltype(multi_c)::value > 0, RECV = HC && decltype(multi_c)::value == 2;
                 if constexpr (HC) {
@@ -641,6 +644,11 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                             }
                             Sr[0] = nr;
                             Si[0] = ni;
+                            if (CK && (i + 1) % CKPT_T == 0 && i + 1 < NSTEP && (PLAIN || (active && t0 + i + 1 < a.L))) {
+                                float *cq = reinterpret_cast<float *>(reinterpret_cast<char *>(ckp) + (uint32_t)((i + 1) / CKPT_T) * ck_step);
+                                cq[0] = nr;
+                                cq[a.J] = ni;
+                            }
                             z_r[k] = clampf(nr, a.out_clamp);
                             z_i[k] = clampf(ni, a.out_clamp);
                             if (!PLAIN && t0 + i == a.L - 1 && a.state_out && active) {
@@ -727,6 +735,11 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                         zr[v] = clampf(nr, a.out_clamp);
                         zi[v] = clampf(ni, a.out_clamp);
                     }
+                    if (CK && (i + 1) % CKPT_T == 0 && i + 1 < NSTEP && (PLAIN || (active && t + 1 < a.L))) {
+                        float *cq = reinterpret_cast<float *>(reinterpret_cast<char *>(ckp) + (uint32_t)((i + 1) / CKPT_T) * ck_step);
+                        Vec<V>::st(cq, Sr);       // the state before token t + 1
+                        Vec<V>::st(cq + a.J, Si);
+                    }
                     if (PLAIN || (active && t < a.L)) {
                         if constexpr (BF) {
                             *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off) = to_bf16(zr[0]);
@@ -754,15 +767,21 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
             using M0 = std::integral_constant<int, 0>;
             using M1 = std::integral_constant<int, 1>;
             using M2 = std::integral_constant<int, 2>;
+            using T_ = std::true_type;
+            using F_ = std::false_type;
+            auto replay_ck = [&](auto plain_c, auto multi_c) {
+                if (ckp) replay(plain_c, multi_c, T_{});
+                else replay(plain_c, multi_c, F_{});
+            };
             if (plain) {
-                if (recv_tile) replay(std::true_type{}, M2{});
-                else if (HC && hcG > 1) replay(std::true_type{}, M1{});
-                else replay(std::true_type{}, M0{});
+                if (recv_tile) replay_ck(T_{}, M2{});
+                else if (HC && hcG > 1) replay_ck(T_{}, M1{});
+                else replay_ck(T_{}, M0{});
                 wait_vm<(2 * NSTEP < 63 ? 2 * NSTEP : 63)>();
             } else {
-                if (recv_tile) replay(std::false_type{}, M2{});
-                else if (HC && hcG > 1) replay(std::false_type{}, M1{});
-                else replay(std::false_type{}, M0{});
+                if (recv_tile) replay_ck(F_{}, M2{});
+                else if (HC && hcG > 1) replay_ck(F_{}, M1{});
+                else replay_ck(F_{}, M0{});
                 wait_vm<0>();
             }
         }
@@ -868,12 +887,12 @@ __global__ __launch_bounds__(256) void step_kernel(const FwdArgs a)
             ha[r] = tail_in[((size_t)(b * HALO + r) * 2 + 1) * a.J + jc];
         }
     }
-    if (a.ckpt && active) {     // the call lies inside the first checkpoint interval
-        a.ckpt[((size_t)b * a.nTc * 2 + 0) * a.J + j] = Sr;
-        a.ckpt[((size_t)b * a.nTc * 2 + 1) * a.J + j] = Si;
-    }
     const int W = (a.J + 31) >> 5;
     for (int t = 0; t < a.L; ++t) {
+        if (a.ckpt && active && t % CKPT_T == 0) {     // the state before every CKPT_T-th token
+            a.ckpt[(((size_t)b * a.nTc + t / CKPT_T) * 2 + 0) * a.J + j] = Sr;
+            a.ckpt[(((size_t)b * a.nTc + t / CKPT_T) * 2 + 1) * a.J + j] = Si;
+        }
         const size_t off = (size_t)b * a.isb + (size_t)t * a.ist + jc;
         const float um = a.bf16 ? from_bf16(reinterpret_cast<const uint16_t *>(a.mag)[off]) : a.mag[off];
         const float ua = a.bf16 ? from_bf16(reinterpret_cast<const uint16_t *>(a.ang)[off]) : a.ang[off];

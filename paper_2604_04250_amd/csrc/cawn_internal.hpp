@@ -16,7 +16,9 @@ namespace cawn {
 //             which allows 32 tokens per thread.
 //   backward: keeps ~10 values per token-lane, hence 8 tokens per thread and one lane per thread
 //             (4 waves per SIMD).
-// Checkpoints of the scan state are kept every CKPT_T tokens = one backward tile.
+// Checkpoints of the scan state are kept every CKPT_T tokens = one backward segment: a backward
+// thread starts the forward state of its tokens from the checkpoint of its own segment (one more
+// byte per token-lane each way; without it every tile had to join its segments' states in LDS).
 #ifndef CAWN_FWD_TILE_T
 #define CAWN_FWD_TILE_T 256
 #endif
@@ -53,9 +55,9 @@ struct FwdGeom {
 struct BwdGeom {
     static constexpr int TILE_T = CAWN_BWD_TILE_T, NSTEP = CAWN_BWD_NSTEP, NSEG = TILE_T / NSTEP;
 };
-constexpr int CKPT_T = BwdGeom::TILE_T;
-static_assert(FwdGeom::TILE_T % CKPT_T == 0, "a forward tile spans whole checkpoint intervals");
-static_assert(CKPT_T % FwdGeom::NSTEP == 0, "checkpoints fall on forward segment boundaries");
+constexpr int CKPT_T = BwdGeom::NSTEP;
+static_assert(FwdGeom::NSTEP % CKPT_T == 0, "a forward segment spans whole checkpoint intervals");
+static_assert(BwdGeom::TILE_T % CKPT_T == 0, "backward tiles start on checkpoints");
 constexpr int FwdV = CAWN_FWD_V, FwdLPR = CAWN_FWD_LPR;  // lanes per thread, threads per row
 constexpr int BwdV = CAWN_BWD_V, BwdLPR = CAWN_BWD_LPR;
 constexpr int MAX_KC = 4;
@@ -109,7 +111,7 @@ struct WsHeader {
 static_assert(sizeof(WsHeader) == 1024, "header size");
 
 struct WsLayout {
-    int J, Jp, Jp128, nT;
+    int J, Jp, Jp128, nT, nTc;     // nT: backward tiles per sequence, nTc: checkpoint intervals
     size_t off_table, off_agg, off_pre, off_halo, off_part, off_vpart, off_aggp, off_rpart, off_dbg, total;
 };
 
@@ -174,6 +176,7 @@ struct BwdArgs {
     tagged_t *agg, *pre, *halo;
     float *part;
     int B, L, J, Jp, nT, nLB;
+    int nTc;                     // checkpoint intervals per sequence
     int small_angle;
     int stage16;                 // input rows may be staged with 16-byte loads (alignment, J % 4 == 0)
     int stage16z;                // the same for the upstream-gradient rows
