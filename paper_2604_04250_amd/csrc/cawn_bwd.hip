@@ -159,7 +159,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     __shared__ float sV[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];      // valve logits, [group][token]
     __shared__ float sVp[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
     __shared__ float sTaps[LEAN ? 2 * KC1 : 1][JB];                 // conv taps of the lane block (valve kernels)
-    __shared__ float sPb[RET ? NSEG : 1][JB];                        // product of each segment's retentions
+    __shared__ float sPb[RET ? NSEG : 1][JB];                        // product of each wave's retentions
     __shared__ float sPt[RET ? 1 : 1][JB];                           // product of the tile's retentions (head group)
     __shared__ float sRp[RET ? BwdGeom::TILE_T * GPB_MAX : 1];       // retention-logit gradient terms per (group, token)
     __shared__ uint32_t sTicket[2], sLast, sEpoch;     // tickets of this tile and the next one
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // a tile that lies wholly inside the tensors loads and stores without per-row checks
     const bool full = (tt + 1) * TILE_T <= a.L && (lb + 1) * JB <= a.J;
     // (upstream gradients of tile (b_, tt_, lb_) into sDz: rows of J lanes, or J/2 words with bf16)
-    auto stage_dz = [&](int b_, int tt_, int lb_) {
+    auto stage_dz = [&](int b_, int tt_, int lb_, int wv, int nwv) {
         if (wave == NW - 1) {       // rows R_LR, R_LI, then R_PSEGB + 2, + 3 of the lane block: two loads of two rows
             const int jl = lb_ * JB + (lane & (JB - 1));
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -241,14 +241,14 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         }
         if (a.stage16z)
             stage_rows<TILE_T, JBS, 0, 16>(&sDz[0][0], a.dz_re, a.dz_im, nullptr, b_, tt_ * TILE_T, lb_, BF ? a.J / 2 : a.J, a.L,
-                                   BF ? a.osb / 2 : a.osb, BF ? (int)a.ost / 2 : (int)a.ost, wave, NW, lane);
+                                   BF ? a.osb / 2 : a.osb, BF ? (int)a.ost / 2 : (int)a.ost, wv, nwv, lane);
         else
             stage_rows<TILE_T, JBS, 0, 4>(&sDz[0][0], a.dz_re, a.dz_im, nullptr, b_, tt_ * TILE_T, lb_, BF ? a.J / 2 : a.J, a.L,
-                                  BF ? a.osb / 2 : a.osb, BF ? (int)a.ost / 2 : (int)a.ost, wave, NW, lane);
+                                  BF ? a.osb / 2 : a.osb, BF ? (int)a.ost / 2 : (int)a.ost, wv, nwv, lane);
     };
     if (PF) {
         if (it == 0) {      // a workgroup's first tile: nobody staged its gradients ahead
-            stage_dz(b, tt, lb);
+            stage_dz(b, tt, lb, wave, NW);
             wait_vm<0>();
             lds_barrier();
         }
@@ -419,11 +419,32 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             }
         }
     }
+    // ---- the segments join in two levels: the two segments of a wave by a lane exchange, the waves
+    //      through LDS (a run of tokens acts on what enters it from later tokens as X -> E + conj(lambda^n) X,
+    //      RET: X -> E + (product of its retentions) conj(e^{i n theta}) X)
+    const bool lower = !(seg & 1);          // my segment is the earlier one of my wave
+    float Eor[V], Eoi[V], Po[V];            // aggregate (RET: and product) of my wave's other segment
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        sEb[seg][0][lv * V + v] = Ebr[v];
-        sEb[seg][1][lv * V + v] = Ebi[v];
-        if (RET) sPb[seg][lv * V + v] = Pth[v];
+        Eor[v] = __shfl_xor(Ebr[v], 32, 64);
+        Eoi[v] = __shfl_xor(Ebi[v], 32, 64);
+        Po[v] = RET ? __shfl_xor(Pth[v], 32, 64) : 1.f;
+    }
+    if (lower) {        // the wave's aggregate: my segment after the later one
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            float ar_, ai_;
+            if (RET) {
+                ar_ = __builtin_fmaf(Pth[v], __builtin_fmaf(pnr[v], Eor[v], pni[v] * Eoi[v]), Ebr[v]);
+                ai_ = __builtin_fmaf(Pth[v], __builtin_fmaf(pnr[v], Eoi[v], -pni[v] * Eor[v]), Ebi[v]);
+                sPb[wave][lv * V + v] = Pth[v] * Po[v];
+            } else {
+                ar_ = __builtin_fmaf(pnr[v], Eor[v], __builtin_fmaf(pni[v], Eoi[v], Ebr[v]));
+                ai_ = __builtin_fmaf(pnr[v], Eoi[v], __builtin_fmaf(-pni[v], Eor[v], Ebi[v]));
+            }
+            sEb[wave][0][lv * V + v] = ar_;
+            sEb[wave][1][lv * V + v] = ai_;
+        }
     }
     lds_barrier_raw();     // the staged rows are still on their way
     BWD_STAMP(2);
@@ -433,24 +454,46 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     float Xr[V], Xi[V];     // adjoint entering my segment (from later segments), zero tile input
     float Cb[V];            // RET: product of the retentions of the segments after mine
-#pragma unroll
-    for (int v = 0; v < V; ++v) { Xr[v] = Xi[v] = 0.f; Cb[v] = 1.f; }
-    for (int qq = NSEG - 1; qq > seg; --qq) {
+    {
+        float Yr[V], Yi[V], Cy[V], p2r[V], p2i[V];      // what enters my wave from the later waves; lambda^(2 NSTEP)
 #pragma unroll
         for (int v = 0; v < V; ++v) {
-            const float er = sEb[qq][0][lv * V + v], ei = sEb[qq][1][lv * V + v];
-            float nr, ni;
-            if (RET) {
-                const float pq = sPb[qq][lv * V + v];
-                nr = __builtin_fmaf(pq, __builtin_fmaf(pnr[v], Xr[v], pni[v] * Xi[v]), er);
-                ni = __builtin_fmaf(pq, __builtin_fmaf(pnr[v], Xi[v], -pni[v] * Xr[v]), ei);
-                Cb[v] *= pq;
-            } else {
-                nr = __builtin_fmaf(pnr[v], Xr[v], __builtin_fmaf(pni[v], Xi[v], er));
-                ni = __builtin_fmaf(pnr[v], Xi[v], __builtin_fmaf(-pni[v], Xr[v], ei));
+            Yr[v] = Yi[v] = 0.f;
+            Cy[v] = 1.f;
+            p2r[v] = __builtin_fmaf(pnr[v], pnr[v], -pni[v] * pni[v]);
+            p2i[v] = 2.0f * pnr[v] * pni[v];
+        }
+        for (int w = NW - 1; w > wave; --w) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const float er = sEb[w][0][lv * V + v], ei = sEb[w][1][lv * V + v];
+                float nr, ni;
+                if (RET) {
+                    const float pq = sPb[w][lv * V + v];
+                    nr = __builtin_fmaf(pq, __builtin_fmaf(p2r[v], Yr[v], p2i[v] * Yi[v]), er);
+                    ni = __builtin_fmaf(pq, __builtin_fmaf(p2r[v], Yi[v], -p2i[v] * Yr[v]), ei);
+                    Cy[v] *= pq;
+                } else {
+                    nr = __builtin_fmaf(p2r[v], Yr[v], __builtin_fmaf(p2i[v], Yi[v], er));
+                    ni = __builtin_fmaf(p2r[v], Yi[v], __builtin_fmaf(-p2i[v], Yr[v], ei));
+                }
+                Yr[v] = nr;
+                Yi[v] = ni;
             }
-            Xr[v] = nr;
-            Xi[v] = ni;
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) {       // the later segment of my wave stands between the earlier one and that
+            float lr_, li_;
+            if (RET) {
+                lr_ = __builtin_fmaf(Po[v], __builtin_fmaf(pnr[v], Yr[v], pni[v] * Yi[v]), Eor[v]);
+                li_ = __builtin_fmaf(Po[v], __builtin_fmaf(pnr[v], Yi[v], -pni[v] * Yr[v]), Eoi[v]);
+            } else {
+                lr_ = __builtin_fmaf(pnr[v], Yr[v], __builtin_fmaf(pni[v], Yi[v], Eor[v]));
+                li_ = __builtin_fmaf(pnr[v], Yi[v], __builtin_fmaf(-pni[v], Yr[v], Eoi[v]));
+            }
+            Xr[v] = lower ? lr_ : Yr[v];
+            Xi[v] = lower ? li_ : Yi[v];
+            Cb[v] = lower ? Po[v] * Cy[v] : Cy[v];
         }
     }
 
@@ -480,8 +523,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             }
         }
     }
-    // the staged rows have landed
-    wait_stores_done();
+    // the staged rows have landed (the head wave leaves the stores of its aggregate, its youngest
+    // operations, in flight: their round trip is nobody's business here)
+    if (wave == 0 && chained && feeds) wait_vm<(RET ? 3 : 2) * V>();
+    else wait_stores_done();
     if (PF && tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
     lds_barrier();
     BWD_STAMP(3);
@@ -503,16 +548,6 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             ldu<V>(gam, row(R_GAMMA), jb);
         }
     }
-    // the next tile's upstream gradients start their way into sDz (every thread has read this tile's;
-    // issued behind the loads above, whose wait then leaves these in flight)
-    if (PF) {
-        const uint32_t nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
-        if (nxt < total_tiles_) {
-            const int nlb = nxt % a.nLB, nrest = nxt / a.nLB;
-            stage_dz(nrest % a.B, a.nT - 1 - nrest / a.B, nlb);
-        }
-    }
-
     // ---- front-end recompute, rows from LDS as a sliding window
     float cs[NSTEP][V], sn[NSTEP][V], ag[NSTEP][V], dsm[NSTEP][V];   // ag: a*g*SiLU'(z_ang)
     float am[VALVE ? NSTEP : 1][V];                                  // the amplitude itself (valve gradient)
@@ -667,6 +702,16 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 
     BWD_STAMP(5);
     ARGS_AGAIN();
+    // ---- the next tile's upstream gradients start their way into sDz, issued by the waves that would
+    //      otherwise only wait for the head wave's look-back.  From here to the end of the tile direct-to-LDS
+    //      loads are in flight: every barrier is the raw one (the compiler makes a fence wait for such loads).
+    if (PF && wave != 0) {
+        const uint32_t nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
+        if (nxt < total_tiles_) {
+            const int nlb = nxt % a.nLB, nrest = nxt / a.nLB;
+            stage_dz(nrest % a.B, a.nT - 1 - nrest / a.B, nlb, wave - 1, NW - 1);
+        }
+    }
     // ---- chain, second half: look-back (its round trips were hidden behind the recompute above)
     if (head) {
         float cr[V], ci[V], Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
@@ -706,7 +751,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             }
         }
     }
-    lds_barrier();
+    if (PF) lds_barrier_raw(); else lds_barrier();
     BWD_STAMP(6);
 
     // ---- true adjoint entering my segment
@@ -722,11 +767,6 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             Gi[v] = __builtin_fmaf(psr[v], ci, __builtin_fmaf(-psi[v], cr, Xi[v]));
         }
     }
-
-    // The tile's last segment needs the conv pre-activation gradients of the next tile's first HALO
-    // tokens.  The head group fetches them (all chain traffic stays in one wave, whose memory
-    // operations then have one known order).
-    const bool fetch_halo = KC > 0 && HALO > 0 && head && chained;
 
     ARGS_AGAIN();
     // ---- reverse pass: adjoint, returned gradients, parameter terms
@@ -853,6 +893,11 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 wm[k][v] = LEAN ? sTaps[k][lv * V + v] : wmf[k][v];
                 wa[k][v] = LEAN ? sTaps[KC + k][lv * V + v] : waf[k][v];
             }
+        // The transposed conv needs the conv pre-activation gradients of the HALO tokens after each
+        // segment.  Inside the tile they cross segments through LDS.  The tile's own first rows go to the
+        // tile before it in time through the workspace (published by the head group, which holds them);
+        // the tile's last segment takes the rows of the tile after it in time from there itself: only its
+        // wave waits for them, and only in front of the segment's last HALO tokens.
         if (HALO > 0) {
 #pragma unroll
             for (int r = 0; r < HALO; ++r)
@@ -861,28 +906,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     sHalo[seg][r][0][lv * V + v] = dzr[r][v];
                     sHalo[seg][r][1][lv * V + v] = dzi[r][v];
                 }
-        }
-        if (head) {
-            // The rows of the later tile come in, the rows the earlier tile needs go out.  The loads
-            // are issued first: a wave's memory operations complete in order, so waiting for them
-            // then does not wait for the stores' round trip as well.
-            const tagged_t *hin = a.halo + (size_t)(ticket - (chained ? chain_stride : 0u)) * HALO * 2 * JB + lv * V;
-            tagged_t xw[HALO1][2][V];
-#pragma unroll
-            for (int r = 0; r < HALO1; ++r)
-#pragma unroll
-                for (int v = 0; v < V; ++v) xw[r][0][v] = xw[r][1][v] = 0;
-            auto fetch = [&]() {
-#pragma unroll
-                for (int r = 0; r < HALO; ++r)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        xw[r][0][v] = tagged_load(hin + (r * 2 + 0) * JB + v);
-                        xw[r][1][v] = tagged_load(hin + (r * 2 + 1) * JB + v);
-                    }
-            };
-            if (fetch_halo) fetch();
-            if (feeds && HALO > 0) {
+            if (head && feeds) {
                 tagged_t *hp = a.halo + (size_t)ticket * HALO * 2 * JB + lv * V;
 #pragma unroll
                 for (int r = 0; r < HALO; ++r)
@@ -891,69 +915,42 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                         tagged_store(hp + (r * 2 + 0) * JB + v, dzr[r][v], tag);
                         tagged_store(hp + (r * 2 + 1) * JB + v, dzi[r][v], tag);
                     }
-                wait_vm<2 * HALO1 * V>();     // everything but those stores
-            } else {
-                wait_vm<0>();
-            }
-            float xm[HALO1][V], xa[HALO1][V];
-#pragma unroll
-            for (int r = 0; r < HALO1; ++r)
-#pragma unroll
-                for (int v = 0; v < V; ++v) xm[r][v] = xa[r][v] = 0.f;
-            if (fetch_halo) {
-                const int gshift = (int)(threadIdx.x & 63) - lv;
-                const unsigned long long gmask = (1ull << LPR) - 1ull;
-                uint32_t spins = 0;
-                bool ok;
-                while (true) {       // valid when every lane of the group found all its tags
-                    bool mine = true;
-#pragma unroll
-                    for (int r = 0; r < HALO; ++r)
-#pragma unroll
-                        for (int v = 0; v < V; ++v) mine = mine && tagged_ok(xw[r][0][v], tag) && tagged_ok(xw[r][1][v], tag);
-                    ok = ((__ballot(mine) >> gshift) & gmask) == gmask;
-                    if (ok || spins >= a.spin_limit) break;
-                    ++spins;
-                    __builtin_amdgcn_s_sleep(1);
-                    fetch();
-                    wait_vm<0>();
-                }
-                if (ok) {
-#pragma unroll
-                    for (int r = 0; r < HALO; ++r)
-#pragma unroll
-                        for (int v = 0; v < V; ++v) {
-                            xm[r][v] = tagged_value(xw[r][0][v]);
-                            xa[r][v] = tagged_value(xw[r][1][v]);
-                        }
-                } else if (lv == 0) {
-                    __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-            if (HALO > 0) {
-#pragma unroll
-                for (int r = 0; r < HALO; ++r)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        sHalo[NSEG][r][0][lv * V + v] = xm[r][v];
-                        sHalo[NSEG][r][1][lv * V + v] = xa[r][v];
-                    }
             }
         }
-        lds_barrier();
+        const bool plain = full && !dtail_out;     // no per-row checks, no loads in the transposed conv
+        const bool last_wave = wave == NW - 1;
+        const bool want_rows = HALO > 0 && seg == NSEG - 1 && chained;
+        const tagged_t *hin = a.halo + (size_t)(ticket - (chained ? chain_stride : 0u)) * HALO * 2 * JB + lv * V;
+        tagged_t xw[HALO1][2][V];
+#pragma unroll
+        for (int r = 0; r < HALO1; ++r)
+#pragma unroll
+            for (int v = 0; v < V; ++v) xw[r][0][v] = xw[r][1][v] = 0;
+        auto ask_rows = [&]() {
+#pragma unroll
+            for (int r = 0; r < HALO; ++r)
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    xw[r][0][v] = tagged_load(hin + (r * 2 + 0) * JB + v);
+                    xw[r][1][v] = tagged_load(hin + (r * 2 + 1) * JB + v);
+                }
+        };
+        if (want_rows) ask_rows();
+        if (PF) lds_barrier_raw(); else lds_barrier();
     BWD_STAMP(8);
         float hm[HALO1][V], ha[HALO1][V];       // dz of the HALO tokens after my segment
 #pragma unroll
         for (int r = 0; r < HALO1; ++r)
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                hm[r][v] = HALO > 0 ? sHalo[seg + 1][r][0][lv * V + v] : 0.f;
-                ha[r][v] = HALO > 0 ? sHalo[seg + 1][r][1][lv * V + v] : 0.f;
+                hm[r][v] = (HALO > 0 && seg < NSEG - 1) ? sHalo[seg + 1][r][0][lv * V + v] : 0.f;
+                ha[r][v] = (HALO > 0 && seg < NSEG - 1) ? sHalo[seg + 1][r][1][lv * V + v] : 0.f;
             }
-        auto conv_t = [&](auto plain_c) {
+        auto conv_t = [&](auto plain_c, auto lo_c, auto hi_c) {
             constexpr bool PLAIN = decltype(plain_c)::value;     // no per-row checks
+            constexpr int I0 = decltype(lo_c)::value, I1 = decltype(hi_c)::value;
 #pragma unroll
-            for (int i = 0; i < NSTEP; ++i) {
+            for (int i = I0; i < I1; ++i) {
                 const int t = t0 + i;
                 float dm[V], da[V];
 #pragma unroll
@@ -989,13 +986,62 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 ooff += ist32 * ES;
             }
         };
-        // Both paths end with every load complete, so that no wait for one of them can land behind
-        // the output stores (where it would drain them); the stores themselves stay in flight.
-        if (full && !dtail_out) {
-            conv_t(std::true_type{});
+        using I_0 = std::integral_constant<int, 0>;
+        using I_A = std::integral_constant<int, NSTEP - HALO>;
+        using I_N = std::integral_constant<int, NSTEP>;
+        // The rows asked for above, taken when they are needed.  The first look stands outside the polling
+        // loop, and the whole of it inside each of the two paths below: the compiler places its own waits
+        // for those loads from what it knows of a path, and where paths meet it knows the least.
+        auto take_rows = [&]() {
+            const int gshift = (int)(threadIdx.x & 63) - lv;
+            const unsigned long long gmask = (1ull << LPR) - 1ull;
+            auto all_tagged = [&]() {      // valid when every lane of the group found all its tags
+                bool mine = true;
+#pragma unroll
+                for (int r = 0; r < HALO; ++r)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) mine = mine && tagged_ok(xw[r][0][v], tag) && tagged_ok(xw[r][1][v], tag);
+                return ((__ballot(mine) >> gshift) & gmask) == gmask;
+            };
+            bool ok = all_tagged();
+            for (uint32_t spins = 0; !ok && spins < a.spin_limit; ++spins) {
+                __builtin_amdgcn_s_sleep(1);
+                ask_rows();
+                wait_vm<0>();
+                ok = all_tagged();
+            }
+            if (ok) {
+#pragma unroll
+                for (int r = 0; r < HALO; ++r)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        hm[r][v] = tagged_value(xw[r][0][v]);
+                        ha[r][v] = tagged_value(xw[r][1][v]);
+                    }
+            } else if (lv == 0) {
+                __hip_atomic_store(&a.hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        };
+        // The tokens that need no row beyond my segment come first; by then the rows asked for have arrived
+        // (their round trip ran beside the barrier and those tokens).  Only the last wave waits, for
+        // everything but the stores it has issued since.  Both paths end with every load complete, so that
+        // no wait for one of them can land behind the output stores (where it would drain them); the stores
+        // themselves stay in flight.
+        if (plain) {
+            conv_t(std::true_type{}, I_0{}, I_A{});
+            if (HALO > 0 && last_wave && chained) {
+                wait_vm<2 * (NSTEP - HALO) * V>();
+                if (want_rows) take_rows();
+            }
+            conv_t(std::true_type{}, I_A{}, I_N{});
             wait_vm<(2 * NSTEP < 63 ? 2 * NSTEP : 63)>();
         } else {
-            conv_t(std::false_type{});
+            conv_t(std::false_type{}, I_0{}, I_A{});
+            if (HALO > 0 && last_wave && chained) {
+                wait_vm<0>();
+                if (want_rows) take_rows();
+            }
+            conv_t(std::false_type{}, I_A{}, I_N{});
             wait_vm<0>();
         }
         // gradient of the incoming conv history: rows r <-> time r - HALO
@@ -1072,7 +1118,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     }
                 }
         }
-        if (PF) lds_barrier();      // the staging below lies over the input rows: everybody has read them
+        if (PF) lds_barrier_raw();      // the staging below lies over the input rows: everybody has read them
 #pragma unroll
         for (int r = 0; r < ROWS; ++r)
 #pragma unroll
@@ -1081,7 +1127,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 const float s = (seg & 1) ? other + part[r][v] : part[r][v] + other;
                 if (!(seg & 1)) sRed[wave][r][lv * V + v] = s;
             }
-        lds_barrier();
+        if (PF) lds_barrier_raw(); else lds_barrier();
     BWD_STAMP(9);
         for (int e = tid; e < ROWS * JB; e += NT) {
             const int row = e / JB, c = e % JB;
@@ -1114,7 +1160,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // ---- LDS is reused by the next tile.  The ticket asked for above is parked where this tile's was
     //      (everything older than the output stores has completed: no further wait)
     if (!PF && tid == 0) sTicket[(it + 1) & 1] = ticket_ahead;
-    lds_barrier();
+    if (PF) lds_barrier_raw(); else lds_barrier();
     BWD_STAMP(10);
     ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
 #undef a
