@@ -29,7 +29,8 @@
  *     summed over the harmonics of a head into d r[t][h].  b_k is static: no gradient.
  *   - Output clamp (Sec. 3.4 clamp equation), Concat layout (Sec. 3.5).
  *   - Depth-wise harmonic convolution of the output along the harmonics of each head
- *     (Sec. 3.6), as a function of its own: oracle_harmonic_conv.
+ *     (Sec. 3.6), as functions of their own: oracle_harmonic_conv and its adjoint
+ *     oracle_harmonic_conv_bwd.
  *   - State passing (Sec. 3.7 / Sec. 5 chunked prefill): the phase state plus the last
  *     conv_k-1 pre-conv rows.
  *   - Backward (Sec. 3.4 last paragraph, Sec. 3.5): reverse-time adjoint; clamp passes the
@@ -71,6 +72,8 @@ typedef struct {
     float gate_tau;          /* threshold, same fp32 value the GPU gets; 0 = open           */
     float valve_eps;         /* gate_mode 1: the valve closes below this (paper: 0.001)     */
     int32_t ret_mode;        /* 0: constant gamma[j];  1: sigmoid(ret[t][h] + ret_bias[k])  */
+    int32_t dz_f64;          /* backward: dz_re / dz_im point at doubles (an upstream gradient that another
+                                oracle function produced, e.g. oracle_harmonic_conv_bwd) instead of floats */
     double conv_clamp;       /* 50 in the paper; +inf disables                              */
     double out_clamp;        /* 100; +inf disables                                          */
     double grad_clamp;       /* 100; +inf disables                                          */
@@ -197,6 +200,47 @@ int oracle_harmonic_conv(int B, int L, int H, int F, int Kh, const double *z_re,
                                    z[((size_t)b * L + t) * J + (size_t)h * F + kk];
                         }
                         o[((size_t)b * L + t) * J + (size_t)h * F + k] = acc;
+                    }
+    }
+    return 0;
+}
+
+/*
+ * Backward of the depth-wise harmonic convolution (Sec. 3.6; the paper trains through it like through
+ * any layer of the block, Sec. 4): the adjoint of oracle_harmonic_conv, term by term.  Every product
+ * w[p][h][i] * Z[..][kk] that the forward adds into out[..][k] hands do[..][k] * w[p][h][i] back to
+ * dZ[..][kk] and do[..][k] * Z[..][kk] to dw[p][h][i]; the bias receives the sum of do over its channel.
+ *   z_re, z_im  [B][L][H*F] fp64: what the forward convolved (the path's clamped output);
+ *   do_re, do_im [B][L][H*F] fp64: upstream gradient of the convolution's output;
+ *   dz_re, dz_im [B][L][H*F] fp64 (written); dw [2][H][Kh], dbias [2][H] fp64 (written; either may be NULL).
+ */
+int oracle_harmonic_conv_bwd(int B, int L, int H, int F, int Kh, const double *z_re, const double *z_im,
+                             const float *w, const double *do_re, const double *do_im, double *dz_re,
+                             double *dz_im, double *dw, double *dbias)
+{
+    if (B <= 0 || L < 0 || H <= 0 || F <= 0 || Kh < 1 || Kh % 2 == 0) return -1;
+    const int pad = (Kh - 1) / 2;
+    const size_t J = (size_t)H * F;
+    if (dw) memset(dw, 0, sizeof(double) * 2 * H * Kh);
+    if (dbias) memset(dbias, 0, sizeof(double) * 2 * H);
+    for (int p = 0; p < 2; ++p) {
+        const double *z = p == 0 ? z_re : z_im;
+        const double *up = p == 0 ? do_re : do_im;
+        double *dz = p == 0 ? dz_re : dz_im;
+        memset(dz, 0, sizeof(double) * (size_t)B * L * J);
+        for (int b = 0; b < B; ++b)
+            for (int t = 0; t < L; ++t)
+                for (int h = 0; h < H; ++h)
+                    for (int k = 0; k < F; ++k) {
+                        const size_t row = ((size_t)b * L + t) * J + (size_t)h * F;
+                        const double g = up[row + k];
+                        if (dbias) dbias[(size_t)p * H + h] += g;
+                        for (int i = 0; i < Kh; ++i) {
+                            const int kk = k + i - pad;
+                            if (kk < 0 || kk >= F) continue;
+                            dz[row + kk] += (double)w[((size_t)p * H + h) * Kh + i] * g;
+                            if (dw) dw[((size_t)p * H + h) * Kh + i] += g * z[row + kk];
+                        }
                     }
     }
     return 0;
@@ -333,7 +377,8 @@ int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, co
 
 /*
  * Backward of oracle_phase_fwd (clamp_feedback must be 0).
- *   dz_re, dz_im [B][L][J] fp32 upstream gradients of the emitted (clamped) outputs
+ *   dz_re, dz_im [B][L][J] upstream gradients of the emitted (clamped) outputs: fp32, or fp64 when
+ *              cfg.dz_f64 is set
  *   dscan_out    [B][2][J] fp64 or NULL     gradient w.r.t. scan_out
  *   dtail_out    [B][Kc-1][2][J] fp64 or NULL gradient w.r.t. tail_out
  * Outputs (fp64, any may be NULL except dmag, dang):
@@ -346,8 +391,8 @@ int oracle_phase_fwd(const oracle_cfg *c, const float *mag, const float *ang, co
 int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, const float *valve,
                      const float *ret, const float *ret_bias,
                      const float *gamma, const float *theta, const float *conv_w, const float *conv_b,
-                     const double *scan_in, const float *tail_in, const float *dz_re,
-                     const float *dz_im, const double *dscan_out, const double *dtail_out,
+                     const double *scan_in, const float *tail_in, const void *dz_re,
+                     const void *dz_im, const double *dscan_out, const double *dtail_out,
                      double *dmag, double *dang, double *dgamma, double *dtheta, double *dconv_w,
                      double *dconv_b, double *dscan_in, double *dtail_in, double *dvalve,
                      double *valve_term, double *dret, double *ret_term)
@@ -392,7 +437,9 @@ int oracle_phase_bwd(const oracle_cfg *c, const float *mag, const float *ang, co
             for (int t = L - 1; t >= 0; --t) {
                 const double ga = retention(c, ret, ret_bias, gamma, b, t, j);
                 size_t o = ((size_t)b * L + t) * J + j;
-                double dSr = (double)dz_re[o], dSi = (double)dz_im[o]; /* clamp passes gradient */
+                /* the output clamp passes the gradient */
+                double dSr = c->dz_f64 ? ((const double *)dz_re)[o] : (double)((const float *)dz_re)[o];
+                double dSi = c->dz_f64 ? ((const double *)dz_im)[o] : (double)((const float *)dz_im)[o];
                 if (t == L - 1 && dscan_out) {
                     dSr += dscan_out[((size_t)b * 2 + 0) * J + j];
                     dSi += dscan_out[((size_t)b * 2 + 1) * J + j];

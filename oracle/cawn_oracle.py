@@ -41,7 +41,7 @@ class _Cfg(C.Structure):
     _fields_ = [("B", C.c_int32), ("L", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
                 ("conv_k", C.c_int32), ("amp_mode", C.c_int32), ("clamp_feedback", C.c_int32),
                 ("nthreads", C.c_int32), ("gate_mode", C.c_int32), ("gate_tau", C.c_float),
-                ("valve_eps", C.c_float), ("ret_mode", C.c_int32),
+                ("valve_eps", C.c_float), ("ret_mode", C.c_int32), ("dz_f64", C.c_int32),
                 ("conv_clamp", C.c_double), ("out_clamp", C.c_double), ("grad_clamp", C.c_double)]
 
 
@@ -77,6 +77,7 @@ class Cfg:
     gate_mode: int = 0          # 1: per-head valve (valve logits [B, L, H]), Sec. 3.3
     valve_eps: float = 0.001
     ret_mode: int = 0           # 1: retention sigmoid(ret[B,L,H] + ret_bias[F]), Sec. 3.3 item 4
+    dz_f64: int = 0             # phase_bwd: dz_re / dz_im are taken as fp64 (e.g. from harmonic_conv_bwd)
 
     @property
     def J(self) -> int:
@@ -85,7 +86,7 @@ class Cfg:
     def c(self) -> _Cfg:
         return _Cfg(self.B, self.L, self.H, self.F, self.conv_k, self.amp_mode, self.clamp_feedback,
                     self.nthreads, self.gate_mode, np.float32(self.gate_tau),
-                    np.float32(self.valve_eps), self.ret_mode, self.conv_clamp, self.out_clamp, self.grad_clamp)
+                    np.float32(self.valve_eps), self.ret_mode, self.dz_f64, self.conv_clamp, self.out_clamp, self.grad_clamp)
 
 
 def _p(a):
@@ -154,6 +155,27 @@ def harmonic_conv(z_re, z_im, H: int, F: int, w, bias=None):
     return o_re, o_im
 
 
+def harmonic_conv_bwd(z_re, z_im, H: int, F: int, w, do_re, do_im):
+    """Adjoint of harmonic_conv (Sec. 3.6): z_re, z_im [B,L,H*F] (what the forward convolved), w [2,H,Kh],
+    do_re, do_im [B,L,H*F] (upstream of the convolution's output) -> dict(dz_re, dz_im [B,L,H*F],
+    dw [2,H,Kh], dbias [2,H]) in f64."""
+    z_re = np.ascontiguousarray(z_re, dtype=np.float64)
+    z_im = np.ascontiguousarray(z_im, dtype=np.float64)
+    B, L, J = z_re.shape
+    assert J == H * F and z_im.shape == z_re.shape
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    Kh = w.shape[2]
+    assert w.shape == (2, H, Kh)
+    do_re = _f64(do_re, (B, L, J))
+    do_im = _f64(do_im, (B, L, J))
+    out = dict(dz_re=np.empty((B, L, J)), dz_im=np.empty((B, L, J)), dw=np.empty((2, H, Kh)), dbias=np.empty((2, H)))
+    rc = lib().oracle_harmonic_conv_bwd(C.c_int(B), C.c_int(L), C.c_int(H), C.c_int(F), C.c_int(Kh), _p(z_re), _p(z_im),
+                                        _p(w), _p(do_re), _p(do_im), _p(out["dz_re"]), _p(out["dz_im"]), _p(out["dw"]),
+                                        _p(out["dbias"]))
+    assert rc == 0, rc
+    return out
+
+
 def _ret_args(cfg: Cfg, ret, ret_bias):
     if cfg.ret_mode != 1:
         return None, None
@@ -202,8 +224,8 @@ def phase_bwd(cfg: Cfg, mag, ang, gamma, theta, dz_re, dz_im, conv_w=None, conv_
     ang = _f32(ang, (B, L, J))
     gamma = _f32(gamma, (J,))
     theta = _f32(theta, (J,))
-    dz_re = _f32(dz_re, (B, L, J))
-    dz_im = _f32(dz_im, (B, L, J))
+    dz_re = (_f64 if cfg.dz_f64 else _f32)(dz_re, (B, L, J))
+    dz_im = (_f64 if cfg.dz_f64 else _f32)(dz_im, (B, L, J))
     if Kc > 0:
         conv_w = _f32(conv_w, (2, J, Kc))
         conv_b = _f32(conv_b, (2, J))

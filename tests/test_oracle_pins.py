@@ -396,9 +396,11 @@ def test_ste_gradient_ignores_gate_for_amplitude_and_masks_phase():
     assert not np.array_equal(g1["dgamma"], g0["dgamma"])      # the state itself did change
 
 
-@pytest.mark.parametrize("tau", [0.0, 0.15])
-def test_fused_backward_equals_numpy_chain(tau):
-    # conv backward + STE with the gate active: rebuild every gradient from brute-force pieces
+@pytest.mark.parametrize("tau,amp_mode", [(0.0, 0), (0.15, 0), (0.0, 1), (0.75, 1)])
+def test_fused_backward_equals_numpy_chain(tau, amp_mode):
+    # conv backward + STE with the gate active: rebuild every gradient from brute-force pieces.
+    # amp_mode 1 (Sec. 3.3 item 1): a = min(softplus(x), 10) on the conv's output x, the threshold is taken
+    # on that amplitude, and the chain to x carries sigmoid(x) below the cap
     B, L, H, F, Kc = 2, 14, 1, 3, 4
     J = H * F
     d = small(18, B, L, H, F, Kc)
@@ -406,7 +408,7 @@ def test_fused_backward_equals_numpy_chain(tau):
     tail = r.standard_normal((B, Kc - 1, 2, J)).astype(np.float32)
     dz_re = r.standard_normal((B, L, J)).astype(np.float32)
     dz_im = r.standard_normal((B, L, J)).astype(np.float32)
-    cfg = O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=tau, out_clamp=INF, grad_clamp=INF)
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=tau, out_clamp=INF, grad_clamp=INF)
     fwd = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d["conv_w"],
                       conv_b=d["conv_b"], tail_in=tail)
     g = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], dz_re, dz_im,
@@ -418,12 +420,19 @@ def test_fused_backward_equals_numpy_chain(tau):
             for s in range(2)]                                         # [B, Kc-1+L, J]
     z = [sum(w[s][None, None, :, i] * useq[s][:, i:i + L] for i in range(Kc)) + d["conv_b"][s]
          for s in range(2)]
-    a, phi = np_silu(z[0]), np_silu(z[1])
+    x, phi = np_silu(z[0]), np_silu(z[1])
+    a = np.minimum(np.logaddexp(0.0, x), 10.0) if amp_mode == 1 else x
+    dadx = np.where(np.logaddexp(0.0, x) < 10.0, np_sigmoid(x), 0.0) if amp_mode == 1 else 1.0
     gate = fwd["gate"].astype(np.float64)
+    clear = np.abs(np.abs(a) - tau) > 1e-5         # away from ties the fp32 decision is the fp64 one
+    assert np.array_equal(gate[clear], (np.abs(a) >= tau)[clear].astype(np.float64))
+    if tau > 0:
+        assert 0.1 < gate.mean() < 0.9
     e = np.exp(1j * phi)
+    np.testing.assert_allclose(fwd["z_re"] + 1j * fwd["z_im"], brute_scan(gate * a * e, lmb), atol=1e-12)
     da = (np.conj(G) * e).real
     dphi = gate * a * (np.conj(G) * 1j * e).real
-    dzc = [da * np_dsilu(z[0]), dphi * np_dsilu(z[1])]
+    dzc = [da * dadx * np_dsilu(z[0]), dphi * np_dsilu(z[1])]
     S = brute_scan(gate * a * e, lmb)
     Sprev = np.concatenate([np.zeros((B, 1, J)), S[:, :-1]], axis=1)
     np.testing.assert_allclose(g["dgamma"], (np.conj(G) * np.exp(1j * d["theta"].astype(np.float64)) * Sprev).real.sum((0, 1)), atol=1e-11)
@@ -504,6 +513,217 @@ def test_conv_clamp_blocks_gradient_outside_range():
 
 
 # -------------------------------------------------------------------------------------- theta_j
+def test_softplus_cap_blocks_the_amplitude_gradient():
+    """amp_mode 1 (Sec. 3.3 item 1): a = min(softplus(m), 10).  d a / d m = sigmoid(m) while softplus(m) < 10
+    and 0 once the cap holds (m = 10 already gives softplus = 10.0000454).  One token, phi = 0, dz = 1: the
+    returned dmag is that derivative itself."""
+    ms = np.array([0.0, -2.0, 9.0, 9.99, 10.0, 20.0], np.float32)
+    want = [0.5, 1 / (1 + math.exp(2.0)), 1 / (1 + math.exp(-9.0)), 1 / (1 + math.exp(-float(np.float32(9.99)))), 0.0, 0.0]
+    for m, w in zip(ms, want):
+        one = np.full((1, 1, 1), m, np.float32)
+        g = O.phase_bwd(O.Cfg(1, 1, 1, 1, amp_mode=1), one, np.zeros_like(one), np.zeros(1, np.float32),
+                        np.zeros(1, np.float32), np.ones_like(one), np.zeros_like(one))
+        assert g["dmag"][0, 0, 0] == pytest.approx(w, rel=1e-14, abs=0)
+    # the phase keeps its gradient at the cap: d/dphi of a sin(phi) . dz_im = a cos(phi) = 10 at phi = 0
+    one = np.full((1, 1, 1), 20.0, np.float32)
+    g = O.phase_bwd(O.Cfg(1, 1, 1, 1, amp_mode=1), one, np.zeros_like(one), np.zeros(1, np.float32),
+                    np.zeros(1, np.float32), np.zeros_like(one), np.ones_like(one))
+    assert g["dang"][0, 0, 0] == 10.0 and g["dmag"][0, 0, 0] == 0.0
+
+
+def test_paper_layer_all_gradients_against_finite_differences():
+    """The layer with everything the paper states switched on at once: conv kernel 3 (Sec. 3.2), softplus
+    amplitude, per-head valve and data-dependent retention (Sec. 3.3).  With eps = 0 the valve's forward is its
+    sigmoid, so the straight-through gradient is the exact derivative and central differences apply to every
+    input, parameter and carried state."""
+    B, L, H, F, Kc = 2, 8, 2, 3, 3
+    J = H * F
+    d = small(301, B, L, H, F, Kc)
+    q = lambda a: (np.round(np.asarray(a, np.float64) * 1024) / 1024).astype(np.float32)
+    for k in d:
+        d[k] = q(d[k])
+    r = rng_(302)
+    valve = q(3.0 + 2.0 * r.standard_normal((B, L, H)))
+    ret = q(0.5 + 1.5 * r.standard_normal((B, L, H)))
+    bias = np.linspace(3.0, 0.0, F).astype(np.float32)
+    scan_in = np.round(r.standard_normal((B, 2, J)) * 1024) / 1024
+    tail_in = q(r.standard_normal((B, Kc - 1, 2, J)))
+    up = dict(dz_re=r.standard_normal((B, L, J)).astype(np.float32), dz_im=r.standard_normal((B, L, J)).astype(np.float32),
+              dscan_out=r.standard_normal((B, 2, J)), dtail_out=r.standard_normal((B, Kc - 1, 2, J)))
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, amp_mode=1, gate_mode=1, valve_eps=0.0, ret_mode=1, conv_clamp=INF,
+                out_clamp=INF, grad_clamp=INF)
+    arrs = dict(mag=d["mag"], ang=d["ang"], theta=d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"], valve=valve,
+                ret=ret, scan_in=scan_in, tail_in=tail_in)
+
+    def loss(a):
+        f = O.phase_fwd(cfg, a["mag"], a["ang"], None, a["theta"], conv_w=a["conv_w"], conv_b=a["conv_b"],
+                        scan_in=a["scan_in"], tail_in=a["tail_in"], valve=a["valve"], ret=a["ret"], ret_bias=bias,
+                        want_gate=False)
+        return float((up["dz_re"] * f["z_re"]).sum() + (up["dz_im"] * f["z_im"]).sum()
+                     + (up["dscan_out"] * f["scan_out"]).sum() + (up["dtail_out"] * f["tail_out"]).sum())
+
+    g = O.phase_bwd(cfg, d["mag"], d["ang"], None, d["theta"], up["dz_re"], up["dz_im"], conv_w=d["conv_w"],
+                    conv_b=d["conv_b"], scan_in=scan_in, tail_in=tail_in, dscan_out=up["dscan_out"],
+                    dtail_out=up["dtail_out"], valve=valve, ret=ret, ret_bias=bias)
+    assert "dgamma" not in g
+    names = dict(mag="dmag", ang="dang", theta="dtheta", conv_w="dconv_w", conv_b="dconv_b", valve="dvalve", ret="dret",
+                 scan_in="dscan_in", tail_in="dtail_in")
+    r2 = rng_(303)
+    for name, gname in names.items():
+        arr, grad = arrs[name], g[gname]
+        assert grad.shape == arr.shape, name
+        for f in r2.permutation(arr.size)[:8]:
+            idx = np.unravel_index(f, arr.shape)
+
+            def at(h):
+                a2 = dict(arrs)
+                a2[name] = arr.copy()
+                a2[name][idx] += h
+                return loss(a2)
+            h = 2.0 ** -7
+            d1 = (at(h) - at(-h)) / (2 * h)
+            d2 = (at(h / 2) - at(-h / 2)) / h
+            num = (4 * d2 - d1) / 3
+            assert abs(num - grad[idx]) <= 3e-7 * max(1.0, abs(num)), (name, idx, num, grad[idx])
+
+
+# ------------------------------------------------------- harmonic convolution, backward (Sec. 3.6)
+def test_harmonic_conv_bwd_by_hand():
+    """One head of four harmonics, taps (10, 1, 0.125) on the real plane, upstream (1, 0, 0, 2): position 0
+    fed outputs 0 (centre) and 1 (lower tap), position 3 fed outputs 3 (centre) and 2 (upper tap), so
+    dZ = (1, 0.125, 20, 2); d tap_i = sum_k up[k] Z[k + i - 1]; the bias receives the sum of its channel."""
+    z = np.array([1.0, 2.0, 3.0, 4.0]).reshape(1, 1, 4)
+    w = np.zeros((2, 1, 3), np.float32)
+    w[0, 0] = [10.0, 1.0, 0.125]
+    w[1, 0] = [0.0, 0.0, 1.0]
+    up_re = np.array([1.0, 0.0, 0.0, 2.0]).reshape(1, 1, 4)
+    up_im = np.array([0.0, 1.0, 0.0, 0.5]).reshape(1, 1, 4)
+    g = O.harmonic_conv_bwd(z, 2 * z, 1, 4, w, up_re, up_im)
+    np.testing.assert_array_equal(g["dz_re"][0, 0], [1.0, 0.125, 20.0, 2.0])
+    np.testing.assert_array_equal(g["dz_im"][0, 0], [0.0, 0.0, 1.0, 0.0])      # output 1 read position 2; output 3 read nothing
+    np.testing.assert_array_equal(g["dw"][0, 0], [2.0 * 3.0, 1.0 * 1.0 + 2.0 * 4.0, 1.0 * 2.0])
+    np.testing.assert_array_equal(g["dw"][1, 0], [1.0 * 2.0 + 0.5 * 6.0, 1.0 * 4.0 + 0.5 * 8.0, 1.0 * 6.0])
+    np.testing.assert_array_equal(g["dbias"], [[3.0], [1.5]])
+
+
+@pytest.mark.parametrize("Kh", [1, 3, 5])
+def test_harmonic_conv_bwd_is_the_adjoint_and_matches_library_routines(Kh):
+    """<up, conv(Z) - bias> = <dZ, Z> for any up and Z (the transposed map); dZ is the correlation of up with the
+    reversed taps (scipy, zero fill); the tap gradient is numpy's full cross-correlation of up and Z read at lags
+    -pad .. pad; heads and planes stay apart."""
+    from scipy.ndimage import correlate1d
+    r = rng_(950 + Kh)
+    B, L, H, F = 2, 4, 3, 8
+    pad = (Kh - 1) // 2
+    z = r.standard_normal((2, B, L, H * F))
+    up = r.standard_normal((2, B, L, H * F))
+    w = r.standard_normal((2, H, Kh)).astype(np.float32)
+    bias = r.standard_normal((2, H)).astype(np.float32)
+    o = O.harmonic_conv(z[0], z[1], H, F, w, bias)
+    o0 = O.harmonic_conv(np.zeros_like(z[0]), np.zeros_like(z[1]), H, F, w, bias)
+    g = O.harmonic_conv_bwd(z[0], z[1], H, F, w, up[0], up[1])
+    for p_ in range(2):
+        lhs = (up[p_] * (o[p_] - o0[p_])).sum()
+        rhs = (g[("dz_re", "dz_im")[p_]] * z[p_]).sum()
+        assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+        for h in range(H):
+            sl = slice(h * F, (h + 1) * F)
+            ref = correlate1d(up[p_][:, :, sl], w[p_, h, ::-1].astype(np.float64), axis=2, mode="constant", cval=0.0)
+            np.testing.assert_allclose(g[("dz_re", "dz_im")[p_]][:, :, sl], ref, rtol=0, atol=1e-13)
+            dw = np.zeros(Kh)
+            for b in range(B):
+                for t in range(L):
+                    full = np.correlate(z[p_][b, t, sl], up[p_][b, t, sl], mode="full")   # lag s at index s + F - 1
+                    dw += full[F - 1 - pad:F + pad]
+            np.testing.assert_allclose(g["dw"][p_, h], dw, rtol=0, atol=1e-12)
+            np.testing.assert_allclose(g["dbias"][p_, h], up[p_][:, :, sl].sum(), rtol=0, atol=1e-12)
+
+
+def test_harmonic_conv_bwd_against_finite_differences():
+    """The map is linear in Z and in (taps, bias): central differences are exact up to rounding."""
+    r = rng_(960)
+    B, L, H, F = 1, 3, 2, 5
+    z = r.standard_normal((2, B, L, H * F))
+    up = r.standard_normal((2, B, L, H * F))
+    w = (np.round(r.standard_normal((2, H, 3)) * 256) / 256).astype(np.float32)
+    bias = (np.round(r.standard_normal((2, H)) * 256) / 256).astype(np.float32)
+    g = O.harmonic_conv_bwd(z[0], z[1], H, F, w, up[0], up[1])
+
+    def loss(z_=z, w_=w, b_=bias):
+        o = O.harmonic_conv(z_[0], z_[1], H, F, w_, b_)
+        return float((o[0] * up[0]).sum() + (o[1] * up[1]).sum())
+
+    for idx in [(0, 0, 0, 0), (1, 0, 2, 9), (0, 0, 1, 4), (1, 0, 1, 5)]:
+        zp, zm = z.copy(), z.copy()
+        zp[idx] += 0.25
+        zm[idx] -= 0.25
+        assert g[("dz_re", "dz_im")[idx[0]]][idx[1:]] == pytest.approx((loss(z_=zp) - loss(z_=zm)) / 0.5, rel=1e-12, abs=1e-12)
+    for idx in [(0, 0, 0), (0, 1, 2), (1, 0, 1), (1, 1, 0)]:
+        wp, wm = w.copy(), w.copy()
+        wp[idx] += np.float32(0.25)
+        wm[idx] -= np.float32(0.25)
+        assert g["dw"][idx] == pytest.approx((loss(w_=wp) - loss(w_=wm)) / 0.5, rel=1e-12, abs=1e-12)
+    for idx in [(0, 1), (1, 0)]:
+        bp, bm = bias.copy(), bias.copy()
+        bp[idx] += np.float32(0.25)
+        bm[idx] -= np.float32(0.25)
+        assert g["dbias"][idx] == pytest.approx((loss(b_=bp) - loss(b_=bm)) / 0.5, rel=1e-12, abs=1e-12)
+
+
+def test_training_step_through_the_harmonic_conv_against_finite_differences():
+    """The whole step: conv front-end, scan, clamp (inactive here), harmonic convolution, loss = <up, C>.  Backward
+    = harmonic_conv_bwd, then phase_bwd on its fp64 dZ (cfg.dz_f64).  Central differences through the composed
+    forward check the hand-over between the two (a dZ rounded to fp32 on the way would still pass this bar, a
+    swapped plane, a transposed tap window or a missing term would not)."""
+    B, L, H, F, Kc = 2, 7, 2, 4, 3
+    J = H * F
+    d = small(970, B, L, H, F, Kc)
+    q = lambda a: (np.round(np.asarray(a, np.float64) * 1024) / 1024).astype(np.float32)
+    for k in d:
+        d[k] = q(d[k])
+    r = rng_(971)
+    hw = q(r.standard_normal((2, H, 3)))
+    hb = q(r.standard_normal((2, H)))
+    up = r.standard_normal((2, B, L, J))
+    cfg = O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=0.0, conv_clamp=INF, out_clamp=INF, grad_clamp=INF)
+
+    def loss(dd, hw_=hw, hb_=hb):
+        f = O.phase_fwd(cfg, dd["mag"], dd["ang"], dd["gamma"], dd["theta"], conv_w=dd["conv_w"], conv_b=dd["conv_b"],
+                        want_gate=False)
+        c = O.harmonic_conv(f["z_re"], f["z_im"], H, F, hw_, hb_)
+        return float((c[0] * up[0]).sum() + (c[1] * up[1]).sum())
+
+    f = O.phase_fwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"])
+    gh = O.harmonic_conv_bwd(f["z_re"], f["z_im"], H, F, hw, up[0], up[1])
+    cfg64 = O.Cfg(B, L, H, F, conv_k=Kc, gate_tau=0.0, conv_clamp=INF, out_clamp=INF, grad_clamp=INF, dz_f64=1)
+    g = O.phase_bwd(cfg64, d["mag"], d["ang"], d["gamma"], d["theta"], gh["dz_re"], gh["dz_im"], conv_w=d["conv_w"],
+                    conv_b=d["conv_b"])
+    # the fp64 hand-over differs from the fp32 one by rounding only
+    g32 = O.phase_bwd(cfg, d["mag"], d["ang"], d["gamma"], d["theta"], gh["dz_re"].astype(np.float32),
+                      gh["dz_im"].astype(np.float32), conv_w=d["conv_w"], conv_b=d["conv_b"])
+    np.testing.assert_allclose(g["dmag"], g32["dmag"], rtol=0, atol=1e-5)
+    assert not np.array_equal(g["dmag"], g32["dmag"])
+    r2 = rng_(972)
+    for name, gname in (("mag", "dmag"), ("ang", "dang"), ("gamma", "dgamma"), ("theta", "dtheta"),
+                        ("conv_w", "dconv_w"), ("conv_b", "dconv_b")):
+        arr, grad = d[name], g[gname]
+        for fl in r2.permutation(arr.size)[:6]:
+            idx = np.unravel_index(fl, arr.shape)
+
+            def at(h):
+                dd = dict(d)
+                dd[name] = arr.copy()
+                dd[name][idx] += h
+                return loss(dd)
+            h = 2.0 ** -7
+            num = (4 * (at(h / 2) - at(-h / 2)) / h - (at(h) - at(-h)) / (2 * h)) / 3
+            assert abs(num - grad[idx]) <= 3e-7 * max(1.0, abs(num)), (name, idx, num, grad[idx])
+    hp, hm = hw.copy(), hw.copy()
+    hp[1, 0, 2] += np.float32(0.125)
+    hm[1, 0, 2] -= np.float32(0.125)
+    assert gh["dw"][1, 0, 2] == pytest.approx((loss(d, hw_=hp) - loss(d, hw_=hm)) / 0.25, rel=1e-11)
+
+
 # ------------------------------------------------------------------------- per-head valve (mode 1)
 def np_sigmoid(v):
     return 1.0 / (1.0 + np.exp(-v))
