@@ -71,8 +71,8 @@ typedef struct cawn_desc {
                              sigmoid(ret[t][h] + ret_bias[k]) (cawn_phase_accumulate_ret_fwd/_bwd; same
                              head widths as gate_mode 1)                                        */
     int32_t hconv_k;      /* 0: none; 3: the depth-wise harmonic convolution is applied to the output
-                             before it is stored (cawn_phase_accumulate_hconv_fwd only; every
-                             other call wants 0, CAWN_EINVAL otherwise)                          */
+                             before it is stored (cawn_phase_accumulate_hconv_fwd / _hconv_bwd only;
+                             every other call wants 0, CAWN_EINVAL otherwise)                    */
     int64_t in_stride_b, in_stride_t;   /* element strides of mag/ang/dmag/dang; 0 = dense
                                            (t stride J, b stride L*J); lane stride is always 1;
                                            t strides above 2^21 elements: CAWN_EUNSUPPORTED     */
@@ -265,7 +265,7 @@ int cawn_phase_accumulate_bf16_fwd(const cawn_desc *d, const uint16_t *mag, cons
 
 /*
  * Forward with the depth-wise harmonic convolution fused behind the output clamp (the first step of
- * the paper's "Convolutional SwiGLU Ear", Sec. 3.6; forward only: prefill and decoding).  The
+ * the paper's "Convolutional SwiGLU Ear", Sec. 3.6; its backward is cawn_phase_accumulate_hconv_bwd).  The
  * clamped state of a token is read as 2 H channels (plane p = real / imaginary, head h) of F
  * positions (the harmonics k of the head) and every channel is convolved along k with its own three
  * taps and bias, zeros beyond both ends of the head:
@@ -291,6 +291,30 @@ int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const v
                                     const void *state_in, void *zc_re, void *zc_im, void *state_out,
                                     void *ckpt, uint32_t *gate_mask, void *workspace,
                                     size_t workspace_bytes, int32_t activations_bf16, void *stream);
+
+/*
+ * Backward of cawn_phase_accumulate_hconv_fwd (Sec. 3.6 trained end to end with the layer, Sec. 4): the
+ * upstream gradients dc_re, dc_im are those of the CONVOLVED output.  The kernel applies the transposed
+ * harmonic convolution while it reads them,
+ *   dz_p[k] = w_p[h][0] dc_p[k+1] + w_p[h][1] dc_p[k] + w_p[h][2] dc_p[k-1]   (inside the head only),
+ * runs the backward of cawn_phase_accumulate_bwd on dz, and returns beside its gradients
+ *   dhconv_w [2][H][3]:  d w_p[h][i] = sum over b, t, k of dc_p[k] * z_p[k + i - 1]
+ *   dhconv_b [2][H]:     d b_p[h]    = sum over b, t, k of dc_p[k]
+ * where z is the clamped state of the forward (rebuilt from ckpt, never read from memory; the output
+ * clamp passes the gradient).  Neither is clamped by grad_clamp; both follow accumulate_param_grads and
+ * may be NULL.  Threshold gate, constant retention and fp32 activations only: gate_mode 0, ret_mode 0
+ * (CAWN_EUNSUPPORTED otherwise); d->hconv_k must be 3, head widths as in the forward; ckpt is required.
+ * dc_re, dc_im use the out strides.  The lane constants that d->lane_consts_cached keeps include hconv_w
+ * and hconv_b.  Everything else (arguments, layouts, ownership, errors) as in cawn_phase_accumulate_bwd.
+ */
+int cawn_phase_accumulate_hconv_bwd(const cawn_desc *d, const float *mag, const float *ang,
+                                    const float *gamma, const float *theta, const float *conv_w,
+                                    const float *conv_b, const float *hconv_w, const float *hconv_b,
+                                    const void *state_in, const void *ckpt, const float *dc_re,
+                                    const float *dc_im, const void *dstate_out, float *dmag, float *dang,
+                                    float *dgamma, float *dtheta, float *dconv_w, float *dconv_b,
+                                    float *dhconv_w, float *dhconv_b, void *dstate_in, void *workspace,
+                                    size_t workspace_bytes, void *stream);
 
 /*
  * Backward of cawn_phase_accumulate_bf16_fwd: mag, ang, dz_re, dz_im are read and dmag, dang are

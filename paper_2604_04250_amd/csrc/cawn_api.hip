@@ -6,6 +6,7 @@
 #include <limits>
 
 #include "cawn_internal.hpp"
+#include "cawn_gate_host.hpp"
 
 namespace cawn {
 
@@ -48,7 +49,7 @@ static WsLayout make_layout(const cawn_desc *d, bool fwd_only = false)
     w.off_halo = o;
     if (!fwd_only) o = align_up(o + tiles_rows * (kc > 1 ? kc - 1 : 0) * 2 * w.Jp128 * sizeof(tagged_t), 256);
     w.off_part = o;
-    if (!fwd_only) o = align_up(o + tiles_rows * part_rows(kc) * w.Jp128 * sizeof(float), 256);
+    if (!fwd_only) o = align_up(o + tiles_rows * part_rows(kc, d->hconv_k != 0) * w.Jp128 * sizeof(float), 256);
     w.off_vpart = o;    // gate_mode 1: per-group sums of the valve's gradient terms, [B][groups][L]
     if (d->gate_mode == 1 && !fwd_only)
         o = align_up(o + (size_t)d->B * (size_t)(d->H * (d->F >= 32 ? d->F / 32 : 1)) * (size_t)(d->L > 0 ? d->L : 1) * sizeof(float), 256);
@@ -57,6 +58,8 @@ static WsLayout make_layout(const cawn_desc *d, bool fwd_only = false)
     w.off_rpart = o;    // ret_mode 1: per-group sums of the retention logits' gradient terms, [B][groups][L]
     if (d->ret_mode == 1 && !fwd_only)
         o = align_up(o + (size_t)d->B * (size_t)(d->H * (d->F >= 32 ? d->F / 32 : 1)) * (size_t)(d->L > 0 ? d->L : 1) * sizeof(float), 256);
+    w.off_hpart = o;    // harmonic convolution: per-lane sums of its taps' and biases' gradient terms, [8][Jp]
+    if (d->hconv_k != 0 && !fwd_only) o = align_up(o + (size_t)HC_PART_ROWS * w.Jp * sizeof(float), 256);
     w.off_dbg = o;
 #ifdef CAWN_TIMING
     o += (size_t)MAX_TILES * 16 * sizeof(unsigned long long);
@@ -65,133 +68,6 @@ static WsLayout make_layout(const cawn_desc *d, bool fwd_only = false)
     return w;
 }
 
-// ------------------------------------------------------------------------------------------ gate
-// The gate decision |A(X(x))| >= tau is defined on an fp32 quantity x (the conv pre-activation, or
-// the raw magnitude when there is no conv), evaluated in fp64.  It is piecewise monotone in x, so
-// the open set is a union of at most two closed fp32 intervals, found by bisection over the
-// ordered fp32 values.
-namespace {
-struct GateFn {
-    bool fused;
-    int amp_mode;
-    double cc;   // conv clamp
-    double tau;
-    double f(float x) const
-    {
-        double v = (double)x;
-        if (fused) {
-            v = v < -cc ? -cc : (v > cc ? cc : v);
-            v = v / (1.0 + std::exp(-v));   // SiLU
-        }
-        if (amp_mode == 1) {
-            double sp = v > 30.0 ? v + std::log1p(std::exp(-v)) : std::log1p(std::exp(v));
-            v = sp < 10.0 ? sp : 10.0;
-        }
-        return std::fabs(v);
-    }
-    bool open(float x) const { return f(x) >= tau; }
-};
-
-int64_t ord(float x)
-{
-    int32_t b;
-    std::memcpy(&b, &x, 4);
-    return b >= 0 ? (int64_t)b : -(int64_t)(b & 0x7fffffff);
-}
-float unord(int64_t o)
-{
-    int32_t b = o >= 0 ? (int32_t)o : (int32_t)((uint32_t)(-o) | 0x80000000u);
-    float x;
-    std::memcpy(&x, &b, 4);
-    return x;
-}
-
-struct Interval { float lo, hi; bool empty; };
-
-// Open sub-interval of the monotone piece [l, r].
-Interval piece(const GateFn &g, float l, float r, bool increasing)
-{
-    int64_t lo = ord(l), hi = ord(r);
-    if (increasing) {
-        if (!g.open(r)) return {0, 0, true};
-        while (lo < hi) {   // smallest open value
-            int64_t mid = lo + (hi - lo) / 2;
-            if (g.open(unord(mid))) hi = mid; else lo = mid + 1;
-        }
-        return {unord(lo), r, false};
-    }
-    if (!g.open(l)) return {0, 0, true};
-    while (lo < hi) {       // largest open value
-        int64_t mid = lo + (hi - lo + 1) / 2;
-        if (g.open(unord(mid))) lo = mid; else hi = mid - 1;
-    }
-    return {l, unord(lo), false};
-}
-}  // namespace
-
-static bool make_gate_set(const cawn_desc *d, GateSet *out)
-{
-    const float INF = std::numeric_limits<float>::infinity();
-    const float FMAX = std::numeric_limits<float>::max();
-    GateSet gs{INF, -INF, INF, -INF};
-    const double tau = (double)d->gate_tau;
-    if (std::isnan(tau)) { *out = gs; return true; }
-    if (tau <= 0.0) { gs.a1 = -INF; gs.b1 = INF; *out = gs; return true; }
-    GateFn g{d->conv_k > 0, d->amp_mode, (double)d->conv_clamp, tau};
-    const float ZSTAR = -1.2784645f;   // argmin of SiLU
-    Interval iv[3];
-    int n = 0;
-    if (g.fused && g.amp_mode == 0) {
-        iv[n++] = piece(g, -FMAX, ZSTAR, true);
-        iv[n++] = piece(g, ZSTAR, 0.0f, false);
-        iv[n++] = piece(g, 0.0f, FMAX, true);
-    } else if (g.fused) {
-        iv[n++] = piece(g, -FMAX, ZSTAR, false);
-        iv[n++] = piece(g, ZSTAR, FMAX, true);
-    } else if (g.amp_mode == 0) {
-        iv[n++] = piece(g, -FMAX, 0.0f, false);
-        iv[n++] = piece(g, 0.0f, FMAX, true);
-    } else {
-        iv[n++] = piece(g, -FMAX, FMAX, true);
-    }
-    // merge pieces that meet, widen the outer ends to infinity
-    Interval m[3];
-    int k = 0;
-    for (int i = 0; i < n; ++i) {
-        if (iv[i].empty) continue;
-        if (k > 0 && ord(iv[i].lo) <= ord(m[k - 1].hi) + 1) m[k - 1].hi = iv[i].hi;
-        else m[k++] = iv[i];
-    }
-    if (k > 2) return false;
-    for (int i = 0; i < k; ++i) {
-        if (m[i].lo == -FMAX) m[i].lo = -INF;
-        if (m[i].hi == FMAX) m[i].hi = INF;
-    }
-    if (k > 0) { gs.a1 = m[0].lo; gs.b1 = m[0].hi; }
-    if (k > 1) { gs.a2 = m[1].lo; gs.b2 = m[1].hi; }
-    *out = gs;
-    return true;
-}
-
-// gate_mode 1: the valve of Sec. 3.3 is open when sigmoid(v - 3) >= eps, a decision defined on the
-// fp32 logit v and evaluated in fp64.  sigmoid is increasing, so the open set is [thr, +inf): thr is
-// found by bisection over the ordered fp32 values.  +inf: never open; -inf: always open.
-static float valve_threshold(float eps)
-{
-    const float INF = std::numeric_limits<float>::infinity();
-    const float FMAX = std::numeric_limits<float>::max();
-    const double e = (double)eps;
-    auto open = [&](float v) { return 1.0 / (1.0 + std::exp(-((double)v - 3.0))) >= e; };
-    if (std::isnan(e)) return INF;
-    if (open(-FMAX)) return -INF;
-    if (!open(FMAX)) return INF;
-    int64_t lo = ord(-FMAX), hi = ord(FMAX);
-    while (lo < hi) {
-        const int64_t mid = lo + (hi - lo) / 2;
-        if (open(unord(mid))) hi = mid; else lo = mid + 1;
-    }
-    return unord(lo);
-}
 // lanes of a 32-lane block that share a valve: heads of F >= 32 lanes span whole blocks
 static bool valve_shape_ok(const cawn_desc *d) { return d->F % 32 == 0 || d->F == 16 || d->F == 8; }
 static int valve_groups(const cawn_desc *d) { return d->H * (d->F >= 32 ? d->F / 32 : 1); }   // per token
@@ -353,8 +229,9 @@ __global__ __launch_bounds__(256) void syntax_conv_kernel(const float *__restric
 // and are added in index order -- the association is fixed, so results are bitwise repeatable.
 __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, float *__restrict__ out0,
                                                                float *__restrict__ out1, float *__restrict__ out2,
-                                                               float *__restrict__ out3, int rows, int conv_k, int J,
-                                                               int JB, int nLB, int chains, int accumulate)
+                                                               float *__restrict__ out3, float *__restrict__ out4,
+                                                               int rows, int conv_k, int hc_row0, int J, int JB,
+                                                               int nLB, int chains, int accumulate)
 {
     // grid: (ceil(J/32), rows)
     constexpr int G = 32;
@@ -376,8 +253,13 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
         float s = 0.0f;
 #pragma unroll
         for (int qq = 0; qq < G; ++qq) s += sm[qq][lane];
-        // rows: 0 dgamma, 1 dtheta, 2 dbias_m, 3 dbias_a, 4 + s*conv_k + i: dw[s][j][i]
+        // rows: 0 dgamma, 1 dtheta, 2 dbias_m, 3 dbias_a, 4 + s*conv_k + i: dw[s][j][i]; from hc_row0 on (when
+        // >= 0): the harmonic convolution's per-lane terms, kept per lane in out4 [8][J] for their own reduction
         float *dst = nullptr;
+        if (hc_row0 >= 0 && row >= hc_row0) {
+            out4[(size_t)(row - hc_row0) * J + j] = s;
+            return;
+        }
         if (row == 0) dst = out0 ? out0 + j : nullptr;
         else if (row == 1) dst = out1 ? out1 + j : nullptr;
         else if (row < 4) dst = out3 ? out3 + (size_t)(row - 2) * J + j : nullptr;
@@ -385,6 +267,23 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
             const int sidx = (row - 4) / conv_k, i = (row - 4) % conv_k;
             dst = out2 ? out2 + ((size_t)sidx * J + j) * conv_k + i : nullptr;
         }
+        if (dst) *dst = accumulate ? *dst + s : s;
+    }
+}
+
+// Harmonic convolution (Sec. 3.6): its taps and biases belong to a (plane, head) channel, so the per-lane sums
+// hpart [8][J] (rows: plane-0 taps 0..2, plane-1 taps 0..2, plane-0 bias, plane-1 bias) are summed over the F
+// lanes of each head, in lane order (one thread per output: the association is fixed).
+__global__ void hconv_grad_reduce_kernel(const float *__restrict__ hpart, float *__restrict__ dw, float *__restrict__ db,
+                                         int H, int F, int J, int accumulate)
+{
+    const int n = HC_PART_ROWS * H;
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < n; e += gridDim.x * blockDim.x) {
+        const int q = e / H, h = e % H;
+        float s = 0.0f;
+        for (int k = 0; k < F; ++k) s += hpart[(size_t)q * J + (size_t)h * F + k];
+        float *dst = q < 6 ? (dw ? dw + ((size_t)(q / 3) * H + h) * 3 + q % 3 : nullptr)
+                           : (db ? db + (size_t)(q - 6) * H + h : nullptr);
         if (dst) *dst = accumulate ? *dst + s : s;
     }
 }
@@ -610,7 +509,7 @@ static int fwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
         a.gs = GateSet{-INF, INF, INF, -INF};        // no per-lane threshold in this mode
         a.valve = valve;
         a.valve_thr = valve_threshold(d->valve_eps);
-    } else if (!make_gate_set(d, &a.gs)) {
+    } else if (!make_gate_set(d->conv_k > 0, d->amp_mode, (double)d->conv_clamp, d->gate_tau, &a.gs)) {
         return CAWN_EUNSUPPORTED;
     }
     a.H = d->H; a.F = d->F;
@@ -701,10 +600,15 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
                     const void *state_in, const void *ckpt, const float *dz_re, const float *dz_im,
                     const void *dstate_out, float *dmag, float *dang, float *dvalve, float *dret, float *dgamma,
                     float *dtheta, float *dconv_w, float *dconv_b, void *dstate_in, void *workspace,
-                    size_t workspace_bytes, void *stream, bool bf16 = false)
+                    size_t workspace_bytes, void *stream, bool bf16 = false, const float *hconv_w = nullptr,
+                    const float *hconv_b = nullptr, float *dhconv_w = nullptr, float *dhconv_b = nullptr)
 {
     if (d->conv_k > MAX_KC || (d->amp_mode != 0 && d->amp_mode != 1)) return CAWN_EUNSUPPORTED;
-    if (d->hconv_k != 0) return CAWN_EINVAL;      // the backward takes gradients of the unconvolved output
+    // gradients of the convolved output: the harmonic convolution's own entry point only
+    const bool hc = d->hconv_k != 0;
+    if (hc != (hconv_w != nullptr)) return CAWN_EINVAL;
+    if (hc && (d->gate_mode != 0 || d->ret_mode != 0 || bf16)) return CAWN_EUNSUPPORTED;
+    if (hc && !(d->F <= 32 ? 32 % d->F == 0 : (d->F % 32 == 0 && 256 % d->F == 0))) return CAWN_EUNSUPPORTED;   // as in the forward
     if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
     if (d->gate_mode == 1 && d->ret_mode == 1 && d->F < 16) return CAWN_EUNSUPPORTED;   // as in the forward
     hipStream_t s = (hipStream_t)stream;
@@ -713,7 +617,8 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     const int kc = d->conv_k;
     const bool want_w = kc > 0 && (dconv_w || dconv_b);
     // (the retention kernels rebuild the forward state in any case and always emit their partials)
-    const bool want_param = dgamma || dtheta || want_w || d->ret_mode == 1;
+    // (the harmonic convolution's tap gradients need the clamped state: state rebuilt, partials always emitted)
+    const bool want_param = dgamma || dtheta || want_w || d->ret_mode == 1 || hc;
     if (d->L == 0) {   // no tokens: the state gradient passes through, parameter gradients are zero
         auto zero = [&](void *p, size_t nfloat) {
             if (!p || !nfloat) return hipSuccess;
@@ -730,6 +635,8 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
             if (e == hipSuccess) e = zero(dtheta, J);
             if (e == hipSuccess && kc > 0) e = zero(dconv_w, 2 * J * kc);
             if (e == hipSuccess && kc > 0) e = zero(dconv_b, 2 * J);
+            if (e == hipSuccess && hc) e = zero(dhconv_w, (size_t)2 * d->H * 3);
+            if (e == hipSuccess && hc) e = zero(dhconv_b, (size_t)2 * d->H);
         }
         return e == hipSuccess ? CAWN_OK : CAWN_ELAUNCH;
     }
@@ -737,7 +644,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     if (d->ret_mode == 1 ? (!ret || !ret_bias || dgamma) : !gamma) return CAWN_EINVAL;
     if (d->gate_mode == 1 && !valve) return CAWN_EINVAL;
     if (kc > 0 && !conv_w) return CAWN_EINVAL;
-    if ((dgamma || dtheta || d->ret_mode == 1) && !ckpt) return CAWN_EINVAL;
+    if ((dgamma || dtheta || d->ret_mode == 1 || hc) && !ckpt) return CAWN_EINVAL;
     // tile indices and tickets are bounded: B x (tiles per sequence) x (32-lane blocks) <= 2^18 per call
     if ((unsigned long long)d->B * w.nT * ((J + BwdLPR - 1) / BwdLPR) > MAX_TILES) return CAWN_EUNSUPPORTED;
     if (workspace_bytes < w.total || !aligned(workspace, 256)) return CAWN_EWORKSPACE;
@@ -757,7 +664,7 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
         a.valve = valve;
         a.valve_thr = valve_threshold(d->valve_eps);
         a.vpart = dvalve ? reinterpret_cast<float *>(reinterpret_cast<char *>(workspace) + w.off_vpart) : nullptr;
-    } else if (!make_gate_set(d, &a.gs)) {
+    } else if (!make_gate_set(d->conv_k > 0, d->amp_mode, (double)d->conv_clamp, d->gate_tau, &a.gs)) {
         return CAWN_EUNSUPPORTED;
     }
     a.H = d->H; a.F = d->F;
@@ -781,8 +688,10 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     char *ws = reinterpret_cast<char *>(workspace);
     if (!d->lane_consts_cached) {
         if (build_table(d, w, ws, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
-                        d->ret_mode == 1 ? ret_bias : nullptr, s) != hipSuccess) return CAWN_ELAUNCH;
+                        d->ret_mode == 1 ? ret_bias : nullptr, s, hconv_w, hconv_b) != hipSuccess) return CAWN_ELAUNCH;
     }
+    a.hconv = hc ? 1 : 0;
+    a.out_clamp = d->out_clamp;
     a.mag = mag; a.ang = ang; a.dz_re = dz_re; a.dz_im = dz_im;
     a.table = reinterpret_cast<const float *>(ws + w.off_table);
     a.state_in = reinterpret_cast<const float *>(state_in);
@@ -810,12 +719,19 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.total_tiles = (uint32_t)tiles;
     a.dbg = reinterpret_cast<unsigned long long *>(ws + w.off_dbg);
     if (launch_bwd(a, kc, vec, s) != hipSuccess) return CAWN_ELAUNCH;
-    if (dgamma || dtheta || want_w) {
-        const int rows = part_rows(kc);
+    if (dgamma || dtheta || want_w || hc) {
+        const int rows = part_rows(kc, hc);
+        float *hpart = reinterpret_cast<float *>(ws + w.off_hpart);
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((J + 31) / 32), rows), dim3(1024), 0, s, a.part,
-                           dgamma, dtheta, dconv_w, dconv_b, rows, kc > 0 ? kc : 1, (int)J, JB, nLB,
-                           d->B * w.nT, d->accumulate_param_grads);
+                           dgamma, dtheta, dconv_w, dconv_b, hpart, rows, kc > 0 ? kc : 1, hc ? 4 + 2 * kc : -1, (int)J,
+                           JB, nLB, d->B * w.nT, d->accumulate_param_grads);
         if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+        if (hc && (dhconv_w || dhconv_b)) {
+            const int n = HC_PART_ROWS * d->H;
+            hipLaunchKernelGGL(hconv_grad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, hpart, dhconv_w,
+                               dhconv_b, d->H, d->F, (int)J, d->accumulate_param_grads);
+            if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+        }
     }
     if (a.vpart) {
         const long long n = (long long)d->B * d->H * d->L;
@@ -891,6 +807,21 @@ int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const v
                     d->ret_mode == 1 ? ret_bias : nullptr, d->ret_mode == 1 ? nullptr : gamma, theta, conv_w, conv_b,
                     state_in, reinterpret_cast<float *>(zc_re), reinterpret_cast<float *>(zc_im), state_out, ckpt,
                     gate_mask, workspace, workspace_bytes, stream, activations_bf16 != 0, hconv_w, hconv_b);
+}
+
+int cawn_phase_accumulate_hconv_bwd(const cawn_desc *d, const float *mag, const float *ang, const float *gamma,
+                                    const float *theta, const float *conv_w, const float *conv_b,
+                                    const float *hconv_w, const float *hconv_b, const void *state_in, const void *ckpt,
+                                    const float *dc_re, const float *dc_im, const void *dstate_out, float *dmag,
+                                    float *dang, float *dgamma, float *dtheta, float *dconv_w, float *dconv_b,
+                                    float *dhconv_w, float *dhconv_b, void *dstate_in, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (!desc_ok(d)) return CAWN_EINVAL;
+    if (d->hconv_k != 3 || !hconv_w) return CAWN_EINVAL;
+    return bwd_impl(d, mag, ang, nullptr, nullptr, nullptr, gamma, theta, conv_w, conv_b, state_in, ckpt, dc_re, dc_im,
+                    dstate_out, dmag, dang, nullptr, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace,
+                    workspace_bytes, stream, false, hconv_w, hconv_b, dhconv_w, dhconv_b);
 }
 
 int cawn_phase_accumulate_bf16_bwd(const cawn_desc *d, const uint16_t *mag, const uint16_t *ang, const float *valve,

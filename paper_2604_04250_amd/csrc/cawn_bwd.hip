@@ -104,9 +104,17 @@ __device__ __forceinline__ bool head_sum_lane(int lv, int vwidth)
 // lane table holds pure rotations.  The logit's gradient needs S[t-1], so these kernels always rebuild
 // the forward state (PARAM).
 // BF: activations (mag, ang, dz_re, dz_im in; dmag, dang out) are bfloat16 in memory, as in the forward.
-template <int V, int KC, bool PARAM, bool VALVE, bool RET, bool BF>
+// HC: the forward ended in the depth-wise harmonic convolution of Sec. 3.6 (three taps along the harmonics of
+// each head, per plane), so dz_re / dz_im are gradients of the CONVOLVED output C.  The transposed convolution
+//   dZ[k] = w0 dC[k+1] + w1 dC[k] + w2 dC[k-1]      (positions outside the head contribute nothing)
+// is applied as the staged gradients are read; a lane block's neighbours (lanes -1 and 32) are staged beside
+// the rows.  The tap gradients d w_i = sum dC[k] Z[k+i-1] = sum_k' Z[k'] dC[k'-i+1] pair a thread's own
+// clamped state Z (rebuilt in the front-end) with the same three gradients, read again from LDS there; they
+// leave the tile as 8 more rows of per-lane partial sums.
+template <int V, int KC, bool PARAM, bool VALVE, bool RET, bool BF, bool HC = false>
 __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
+    static_assert(!HC || (PARAM && !VALVE && !RET && !BF && V == 1), "harmonic convolution: threshold mode, fp32, with the state rebuild");
     static_assert(!BF || V == 1, "bf16 activations: one lane per thread");
     static_assert(!RET || (PARAM && V == 1), "retention kernels rebuild the forward state; one lane per thread");
     // The valve and retention kernels sit at the register budget.  They keep the reduced angle instead
@@ -118,7 +126,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     constexpr int HALO = KC > 0 ? KC - 1 : 0;
     constexpr int HALO1 = HALO > 0 ? HALO : 1;
     constexpr int KC1 = KC > 0 ? KC : 1;
-    constexpr int ROWS = 4 + 2 * KC;
+    constexpr int ROWS = 4 + 2 * KC + (HC ? HC_PART_ROWS : 0);
     constexpr int NT = NSEG * LPR, NW = NT / 64;
     constexpr int JBS = BF ? JB / 2 : JB;          // four-byte words per staged row
     constexpr uint32_t ES = BF ? 2u : 4u;          // bytes per activation element
@@ -146,11 +154,14 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // ... and with them the four lane constants the local adjoint needs (lambda, lambda^NSTEP): a wave's
     // memory operations complete in issue order, so a load issued at the top of a tile returns only after
     // the previous tile's output stores have been acknowledged
-    __shared__ float sLam[PF ? 4 : 1][JB];
-    constexpr int N_EB = NSEG * 2 * JB, N_HALO = (NSEG + 1) * HALO1 * 2 * JB;
+    // HC: ... and the lane block's harmonic-convolution taps (table rows R_W0 + 2 KC + 0 .. 7)
+    __shared__ float sLam[PF ? (HC ? 4 + HC_ROWS : 4) : 1][JB];
+    // HC: the gradients of the two lanes beside the lane block, [plane][side: lane -1, lane JB][token]
+    __shared__ float sEdge[HC ? 4 * NRZ : 1];
+    constexpr int N_EB = NSEG * 2 * JB, N_HALO = NW * HALO1 * 2 * JB;
     __shared__ float sPool[PF ? (N_EB > N_HALO ? N_EB : N_HALO) : N_EB + N_HALO];
     float (*sEb)[2][JB] = reinterpret_cast<float (*)[2][JB]>(&sPool[0]);
-    float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(&sPool[PF ? 0 : N_EB]);   // [NSEG]: rows of the next tile
+    float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(&sPool[PF ? 0 : N_EB]);   // [NW]: first rows of each wave's earlier segment
     __shared__ float sCarry[2][JB];
     __shared__ float sRedOwn[(PARAM && !PF) ? NW : 1][ROWS][JB];
     static_assert(!PF || (size_t)NW * ROWS * JB <= (size_t)2 * NRTP * JBS, "the partial-sum staging fits over the input rows");
@@ -237,7 +248,30 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 #if defined(__HIP_DEVICE_COMPILE__)
             __builtin_amdgcn_global_load_lds(table + (size_t)(R_LR + (lane >> 5)) * Jp + jl, &sLam[0][0], 4, 0, 0);
             __builtin_amdgcn_global_load_lds(table + (size_t)(R_PSEGB + 2 + (lane >> 5)) * Jp + jl, &sLam[2][0], 4, 0, 0);
+            if constexpr (HC) {
+#pragma unroll
+                for (int q = 0; q < HC_ROWS / 2; ++q)
+                    __builtin_amdgcn_global_load_lds(table + (size_t)(R_W0 + 2 * KC + 2 * q + (lane >> 5)) * Jp + jl,
+                                                     &sLam[4 + 2 * q][0], 4, 0, 0);
+            }
 #endif
+        }
+        if constexpr (HC) {
+            // the two neighbour lanes of the block, 64 tokens per instruction; rows past the end and lanes
+            // outside the tensor read a valid address (their values are masked where they are used)
+            for (int e = wv; e < 8; e += nwv) {
+                const int plane = e >> 2, side = (e >> 1) & 1, half = e & 1;
+                int t = tt_ * TILE_T + half * 64 + lane;
+                t = t < a.L ? t : a.L - 1;
+                int j = side ? lb_ * JB + JB : lb_ * JB - 1;
+                j = j < 0 ? 0 : (j >= a.J ? a.J - 1 : j);
+                const float *src = (plane ? a.dz_im : a.dz_re) + (size_t)b_ * a.osb + (size_t)t * a.ost + j;
+#if defined(__HIP_DEVICE_COMPILE__)
+                __builtin_amdgcn_global_load_lds(src, &sEdge[(plane * 2 + side) * NRZ + half * 64], 4, 0, 0);
+#else
+                (void)src;
+#endif
+            }
         }
         if (a.stage16z)
             stage_rows<TILE_T, JBS, 0, 16>(&sDz[0][0], a.dz_re, a.dz_im, nullptr, b_, tt_ * TILE_T, lb_, BF ? a.J / 2 : a.J, a.L,
@@ -245,6 +279,47 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         else
             stage_rows<TILE_T, JBS, 0, 4>(&sDz[0][0], a.dz_re, a.dz_im, nullptr, b_, tt_ * TILE_T, lb_, BF ? a.J / 2 : a.J, a.L,
                                   BF ? a.osb / 2 : a.osb, BF ? (int)a.ost / 2 : (int)a.ost, wv, nwv, lane);
+    };
+    // HC: the gradients of convolved-output positions k-1, k, k+1 of token i of my segment ([0], [1], [2]), zero
+    // where the position lies outside my head or the token outside the tensor.  Head widths are powers of two.
+    // My own position comes from LDS, the neighbours' by a lane exchange of it (lanes 0 and 31 of the block take
+    // the staged edge instead).  What depends on the lane alone is set up once per pass from an opaque copy of
+    // the thread index, not carried across the tile; every read is unconditional and pinned, so that the
+    // choices below are selects on loaded values (a read inside one arm of a choice becomes a branch around it).
+    struct HcLane { int own, edge, nlive; bool is_lo, is_hi, first, last; };
+    auto hc_setup = [&]() {
+        int t_ = tid_;
+        asm volatile("" : "+v"(t_));
+        const int lv_ = t_ % LPR, sg_ = t_ / LPR;
+        const int kh = (lb * JB + lv_) & (a.F - 1);
+        HcLane k;
+        k.own = sg_ * NSTEP * JBS + lv_;                         // word offset of (my first token, my lane) in a plane of sDz
+        k.edge = (lv_ == 0 ? 0 : NRZ) + sg_ * NSTEP;             // word offset of my first token in my side of sEdge
+        const int left = a.L - (tt * TILE_T + sg_ * NSTEP);
+        k.nlive = full ? NSTEP : ((lb * JB + lv_ < a.J) ? (left < 0 ? 0 : (left > NSTEP ? NSTEP : left)) : 0);
+        k.is_lo = lv_ == 0;
+        k.is_hi = lv_ == LPR - 1;
+        k.first = kh == 0;
+        k.last = kh == a.F - 1;
+        return k;
+    };
+    auto hc_read = [&](int i, const HcLane &k, float (&cr)[3], float (&ci)[3]) {
+        float c0r = (&sDz[0][0])[k.own + i * JBS], c0i = (&sDz[NRZ][0])[k.own + i * JBS];
+        float er = sEdge[k.edge + i], ei = sEdge[2 * NRZ + k.edge + i];
+        asm volatile("" : "+v"(c0r), "+v"(c0i), "+v"(er), "+v"(ei));
+        const bool live = i < k.nlive;
+        c0r = live ? c0r : 0.f;
+        c0i = live ? c0i : 0.f;
+        // (the exchange crosses the two segments of a wave at lanes 31 | 32: exactly the lanes that take the edge)
+        const float mr = __shfl_up(c0r, 1, 64), mi = __shfl_up(c0i, 1, 64);
+        const float pr = __shfl_down(c0r, 1, 64), pi = __shfl_down(c0i, 1, 64);
+        const bool keep_m = live & !k.first, keep_p = live & !k.last;
+        cr[0] = keep_m ? (k.is_lo ? er : mr) : 0.f;
+        ci[0] = keep_m ? (k.is_lo ? ei : mi) : 0.f;
+        cr[2] = keep_p ? (k.is_hi ? er : pr) : 0.f;
+        ci[2] = keep_p ? (k.is_hi ? ei : pi) : 0.f;
+        cr[1] = c0r;
+        ci[1] = c0i;
     };
     if (PF) {
         if (it == 0) {      // a workgroup's first tile: nobody staged its gradients ahead
@@ -255,6 +330,23 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         // (later tiles: staged during the previous tile, complete before its closing barrier)
         auto dz_from_lds = [&](auto full_c) {
             constexpr bool FULL = decltype(full_c)::value;
+            if constexpr (HC) {     // transposed harmonic convolution of the staged gradients
+                float w_[2][3];
+#pragma unroll
+                for (int p_ = 0; p_ < 2; ++p_)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q) w_[p_][q] = sLam[4 + 3 * p_ + q][lv];
+                const HcLane hk = hc_setup();
+#pragma unroll
+                for (int i = 0; i < NSTEP; ++i) {
+                    float cr[3], ci[3];
+                    hc_read(i, hk, cr, ci);
+                    dzr[i][0] = __builtin_fmaf(w_[0][0], cr[2], __builtin_fmaf(w_[0][1], cr[1], w_[0][2] * cr[0]));
+                    dzi[i][0] = __builtin_fmaf(w_[1][0], ci[2], __builtin_fmaf(w_[1][1], ci[1], w_[1][2] * ci[0]));
+                    if (i & 1) __builtin_amdgcn_sched_barrier(0);     // (two tokens' reads in flight, not all eight)
+                }
+                return;
+            }
 #pragma unroll
             for (int i = 0; i < NSTEP; ++i) {
                 const int r = seg * NSTEP + i;
@@ -564,6 +656,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     };
     float Spr[PARAM ? NSTEP : 1][V], Spi[PARAM ? NSTEP : 1][V];      // forward state before each token
     float Efr[V], Efi[V];
+
     const bool zero_hist = HALO > 0 && !tail_in && tt == 0 && seg == 0;   // rows before a sequence start
     // bf16: the carried conv history is fp32 and is not staged; the one segment that needs it reads it
     // where it uses it (and waits for it there, so that no wait for it lands in the common path)
@@ -683,6 +776,36 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         default: front_end(T_{}, T_{}); break;
         }
     }
+    float hacc[HC ? HC_PART_ROWS : 1];      // HC: tap gradient terms [plane][tap], then the biases' [plane]
+#pragma unroll
+    for (int q = 0; q < (HC ? HC_PART_ROWS : 1); ++q) hacc[q] = 0.f;
+    if constexpr (HC) {
+        // ---- the harmonic convolution's tap and bias terms, in a pass of its own (inside the front-end its
+        //      temporaries came on top of the kernel's register peak): the state after token i is the state
+        //      before token i+1; Z[t] = clamp(S[t]) meets the gradients at k+1, k, k-1 (taps 0, 1, 2)
+        __builtin_amdgcn_sched_barrier(0);
+        const HcLane hk = hc_setup();
+#pragma unroll
+        for (int i = 0; i < NSTEP; ++i) {
+            const float sr_ = i + 1 < NSTEP ? Spr[i + 1 < NSTEP ? i + 1 : 0][0] : Efr[0];
+            const float si_ = i + 1 < NSTEP ? Spi[i + 1 < NSTEP ? i + 1 : 0][0] : Efi[0];
+            const float zr_ = clampf(sr_, a.out_clamp), zi_ = clampf(si_, a.out_clamp);
+            float cr[3], ci[3];
+            hc_read(i, hk, cr, ci);
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                hacc[q] = __builtin_fmaf(zr_, cr[2 - q], hacc[q]);
+                hacc[3 + q] = __builtin_fmaf(zi_, ci[2 - q], hacc[3 + q]);
+            }
+            hacc[6] += cr[1];
+            hacc[7] += ci[1];
+            // (the sums are used at the end of the tile only; left alone, the compiler moves the whole chain
+            // down there and keeps all 48 gradients alive until then)
+#pragma unroll
+            for (int q = 0; q < HC_PART_ROWS; ++q) asm volatile("" : "+v"(hacc[q]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
     if (LEAN) {
         ldu<V>(psr, row(R_PSEGB + 2 * (NSEG - 1 - seg)), jb);
         ldu<V>(psi, row(R_PSEGB + 2 * (NSEG - 1 - seg) + 1), jb);
@@ -705,13 +828,16 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // ---- the next tile's upstream gradients start their way into sDz, issued by the waves that would
     //      otherwise only wait for the head wave's look-back.  From here to the end of the tile direct-to-LDS
     //      loads are in flight: every barrier is the raw one (the compiler makes a fence wait for such loads).
-    if (PF && wave != 0) {
+    //      (HC: the front-end reads this tile's staged gradients, so the next tile's start behind the barrier
+    //      that closes it, below)
+    auto stage_next = [&]() {
         const uint32_t nxt = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[(it + 1) & 1]);
         if (nxt < total_tiles_) {
             const int nlb = nxt % a.nLB, nrest = nxt / a.nLB;
             stage_dz(nrest % a.B, a.nT - 1 - nrest / a.B, nlb, wave - 1, NW - 1);
         }
-    }
+    };
+    if (PF && !HC && wave != 0) stage_next();
     // ---- chain, second half: look-back (its round trips were hidden behind the recompute above)
     if (head) {
         float cr[V], ci[V], Tr[V], Ti[V], hr[V], hi[V], qr[V], qi[V];
@@ -753,6 +879,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     }
     if (PF) lds_barrier_raw(); else lds_barrier();
     BWD_STAMP(6);
+    if (PF && HC && wave != 0) stage_next();
 
     // ---- true adjoint entering my segment
     float Gr[V], Gi[V];
@@ -894,18 +1021,21 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 wa[k][v] = LEAN ? sTaps[KC + k][lv * V + v] : waf[k][v];
             }
         // The transposed conv needs the conv pre-activation gradients of the HALO tokens after each
-        // segment.  Inside the tile they cross segments through LDS.  The tile's own first rows go to the
+        // segment.  Inside the tile the earlier segment of a wave takes them from the later one by a lane
+        // exchange, the later one from the next wave through LDS.  The tile's own first rows go to the
         // tile before it in time through the workspace (published by the head group, which holds them);
         // the tile's last segment takes the rows of the tile after it in time from there itself: only its
         // wave waits for them, and only in front of the segment's last HALO tokens.
         if (HALO > 0) {
+            if (lower && wave > 0) {
 #pragma unroll
-            for (int r = 0; r < HALO; ++r)
+                for (int r = 0; r < HALO; ++r)
 #pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    sHalo[seg][r][0][lv * V + v] = dzr[r][v];
-                    sHalo[seg][r][1][lv * V + v] = dzi[r][v];
-                }
+                    for (int v = 0; v < V; ++v) {
+                        sHalo[wave][r][0][lv * V + v] = dzr[r][v];
+                        sHalo[wave][r][1][lv * V + v] = dzi[r][v];
+                    }
+            }
             if (head && feeds) {
                 tagged_t *hp = a.halo + (size_t)ticket * HALO * 2 * JB + lv * V;
 #pragma unroll
@@ -943,8 +1073,12 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         for (int r = 0; r < HALO1; ++r)
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                hm[r][v] = (HALO > 0 && seg < NSEG - 1) ? sHalo[seg + 1][r][0][lv * V + v] : 0.f;
-                ha[r][v] = (HALO > 0 && seg < NSEG - 1) ? sHalo[seg + 1][r][1][lv * V + v] : 0.f;
+                // (the exchange runs in every lane: the later segment's lanes receive rows they do not use)
+                const float xm_ = HALO > 0 ? __shfl_xor(dzr[r < HALO ? r : 0][v], 32, 64) : 0.f;
+                const float xa_ = HALO > 0 ? __shfl_xor(dzi[r < HALO ? r : 0][v], 32, 64) : 0.f;
+                const bool nextw = HALO > 0 && !lower && wave < NW - 1;
+                hm[r][v] = lower ? xm_ : (nextw ? sHalo[nextw ? wave + 1 : 0][r][0][lv * V + v] : 0.f);
+                ha[r][v] = lower ? xa_ : (nextw ? sHalo[nextw ? wave + 1 : 0][r][1][lv * V + v] : 0.f);
             }
         auto conv_t = [&](auto plain_c, auto lo_c, auto hi_c) {
             constexpr bool PLAIN = decltype(plain_c)::value;     // no per-row checks
@@ -1118,6 +1252,10 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     }
                 }
         }
+        if constexpr (HC) {
+#pragma unroll
+            for (int q = 0; q < HC_PART_ROWS; ++q) part[4 + 2 * KC + q][0] = hacc[q];
+        }
         if (PF) lds_barrier_raw();      // the staging below lies over the input rows: everybody has read them
 #pragma unroll
         for (int r = 0; r < ROWS; ++r)
@@ -1178,7 +1316,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
 }
 
 // Persistent grid: what fits on the chip at once (asked once per kernel), never more than tiles.
-template <int V, int KC, bool PARAM, bool VALVE, bool RET, bool BF>
+template <int V, int KC, bool PARAM, bool VALVE, bool RET, bool BF, bool HC = false>
 static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
 {
     static int per_cu = 0, cus = 0;
@@ -1186,14 +1324,14 @@ static hipError_t launch_bwd_vkp(const BwdArgs &a, hipStream_t s)
         int dev = 0, n = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM, VALVE, RET, BF>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, bwd_kernel<V, KC, PARAM, VALVE, RET, BF, HC>, BwdGeom::NSEG * BwdLPR, 0) != hipSuccess)
             return hipErrorUnknown;
         cus = prop.multiProcessorCount;
         per_cu = n > 0 ? n : 1;
     }
     long long g = (long long)per_cu * cus;
     if (g > (long long)a.total_tiles) g = a.total_tiles;
-    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM, VALVE, RET, BF>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
+    hipLaunchKernelGGL((bwd_kernel<V, KC, PARAM, VALVE, RET, BF, HC>), dim3((unsigned)g), dim3(BwdGeom::NSEG * BwdLPR), 0, s, a);
     return hipGetLastError();
 }
 
@@ -1213,6 +1351,23 @@ static hipError_t launch_bwd_vpb(const BwdArgs &a, int conv_k, hipStream_t s)
 #ifdef CAWN_DEV_PLAIN
     if constexpr (VALVE || RET || BF) return hipErrorInvalidValue; else
 #endif
+    if constexpr (PARAM && !VALVE && !RET && !BF) {
+        if (a.hconv) {
+            switch (conv_k) {
+#ifdef CAWN_DEV_KC
+            case CAWN_DEV_KC: return launch_bwd_vkp<V, CAWN_DEV_KC, true, false, false, false, true>(a, s);
+#else
+            case 0: return launch_bwd_vkp<V, 0, true, false, false, false, true>(a, s);
+            case 1: return launch_bwd_vkp<V, 1, true, false, false, false, true>(a, s);
+            case 2: return launch_bwd_vkp<V, 2, true, false, false, false, true>(a, s);
+            case 3: return launch_bwd_vkp<V, 3, true, false, false, false, true>(a, s);
+            case 4: return launch_bwd_vkp<V, 4, true, false, false, false, true>(a, s);
+#endif
+            default: return hipErrorInvalidValue;
+            }
+        }
+    }
+    if (a.hconv) return hipErrorInvalidValue;       // the harmonic convolution: threshold mode, fp32, state rebuilt
     switch (conv_k) {
 #ifdef CAWN_DEV_KC
     case CAWN_DEV_KC: return launch_bwd_vkp<V, CAWN_DEV_KC, PARAM, VALVE, RET, BF>(a, s);

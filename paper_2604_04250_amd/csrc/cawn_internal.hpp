@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "cawn.h"
+#include "cawn_gate_host.hpp"
 
 namespace cawn {
 
@@ -112,16 +113,14 @@ static_assert(sizeof(WsHeader) == 1024, "header size");
 
 struct WsLayout {
     int J, Jp, Jp128, nT, nTc;     // nT: backward tiles per sequence, nTc: checkpoint intervals
-    size_t off_table, off_agg, off_pre, off_halo, off_part, off_vpart, off_aggp, off_rpart, off_dbg, total;
+    size_t off_table, off_agg, off_pre, off_halo, off_part, off_vpart, off_aggp, off_rpart, off_hpart, off_dbg, total;
 };
 
 constexpr uint32_t EPOCH_MOD = (1u << 23) - 1u;     // epochs 0 .. 2^23 - 2
 typedef unsigned long long tagged_t;     // {fp32 value (low half), tag (high half)}
 inline __host__ __device__ uint32_t make_tag(uint32_t epoch) { return 0xFF800001u + epoch; }
 
-// Gate as a union of two closed fp32 intervals on the quantity the decision is taken on (the
-// fp32 conv pre-activation, or the raw magnitude input when there is no conv).
-struct GateSet { float a1, b1, a2, b2; };
+// (GateSet, the gate as a union of two closed fp32 intervals, comes from cawn_gate_host.hpp)
 
 struct FwdArgs {
     const float *mag, *ang;
@@ -201,10 +200,17 @@ struct BwdArgs {
     float *rpart;                // null: no gradient of the retention logits wanted
     tagged_t *aggp;
     int bf16;                    // activations (mag, ang, dz_*, dmag, dang) are bfloat16 in memory: see FwdArgs
+    // harmonic convolution behind the output clamp (Sec. 3.6): dz_re / dz_im are then the gradients of the
+    // CONVOLVED output; the kernel applies the transposed convolution as it reads them and emits, per lane,
+    // the terms of the tap and bias gradients (rows behind the conv front-end's in `part`)
+    int hconv;
+    float out_clamp;
 };
 
-// Number of per-lane partial sums a backward tile emits: dgamma, dtheta, dbias[2], dw[2][conv_k].
-inline __host__ __device__ int part_rows(int conv_k) { return 4 + 2 * conv_k; }
+// Number of per-lane partial sums a backward tile emits: dgamma, dtheta, dbias[2], dw[2][conv_k]; with the
+// harmonic convolution 8 more: its taps' terms [2 planes][3], then its biases' [2 planes].
+constexpr int HC_PART_ROWS = 8;
+inline __host__ __device__ int part_rows(int conv_k, bool hconv = false) { return 4 + 2 * conv_k + (hconv ? HC_PART_ROWS : 0); }
 
 hipError_t launch_fwd(const FwdArgs &a, int conv_k, bool vec4, hipStream_t s);
 hipError_t launch_bwd(const BwdArgs &a, int conv_k, bool vec, hipStream_t s);

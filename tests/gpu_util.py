@@ -333,6 +333,62 @@ def run_fwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, state_in=N
     return out
 
 
+def run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, out_clamp=100.0, grad_clamp=100.0,
+                      state_in=None, dstate_out=None, accumulate=0, preset=None, concat=False, want_hgrads=True):
+    """Forward with the harmonic convolution (for the checkpoints and the convolved output), then its backward,
+    through the C ABI.  inp holds hconv_w [2,H,3], hconv_b [2,H] and dc_re, dc_im [B,L,J] (gradients of the
+    convolved output).  Returns numpy arrays: c_re, c_im, dmag, dang, dgamma, dtheta, dconv_w, dconv_b, dhconv_w,
+    dhconv_b, dstate_in (flat blob)."""
+    J = H * F
+    d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau, out_clamp=out_clamp,
+                    grad_clamp=grad_clamp, accumulate_param_grads=accumulate, hconv_k=3)
+    mag, ang = dev(inp["mag"][:, :L]), dev(inp["ang"][:, :L])
+    gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
+    cw = dev(inp["conv_w"]) if conv_k > 0 else None
+    cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
+    hw, hb = dev(inp["hconv_w"]), dev(inp.get("hconv_b"))
+    Lr = max(L, 1)
+    c_re, c_im = torch.empty((B, Lr, J), device=DEV), torch.empty((B, Lr, J), device=DEV)
+    dc_re, dc_im = dev(inp["dc_re"][:, :L]), dev(inp["dc_im"][:, :L])
+    nanv = lambda *shape: torch.full(shape, float("nan") if preset is None else preset, device=DEV)
+    dmag, dang = torch.full((B, Lr, J), float("nan"), device=DEV), torch.full((B, Lr, J), float("nan"), device=DEV)
+    if concat:      # rows of 2 J elements shared by each activation pair (Sec. 3.5)
+        xin = torch.cat([mag, ang], dim=2).contiguous()
+        mag, ang = xin[:, :, :J], xin[:, :, J:]
+        cc = torch.empty((B, Lr, 2 * J), device=DEV)
+        c_re, c_im = cc[:, :, :J], cc[:, :, J:]
+        dcc = torch.cat([dc_re, dc_im], dim=2).contiguous()
+        dc_re, dc_im = dcc[:, :, :J], dcc[:, :, J:]
+        dxc = torch.full((B, Lr, 2 * J), float("nan"), device=DEV)
+        dmag, dang = dxc[:, :, :J], dxc[:, :, J:]
+        d.in_stride_t, d.in_stride_b = 2 * J, Lr * 2 * J
+        d.out_stride_t, d.out_stride_b = 2 * J, Lr * 2 * J
+    st_in = dev(state_in)
+    ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
+    ws = Workspaces.get(d)
+    K.check(K.cawn_phase_accumulate_hconv_fwd(d, mag, ang, None, None, None, gamma, theta, cw, cb, hw, hb, st_in, c_re, c_im,
+                                              None, ckpt, None, ws))
+    nstate = K.cawn_state_bytes(d) // 4
+    dgamma, dtheta = nanv(J), nanv(J)
+    dcw = nanv(2, J, conv_k) if conv_k > 0 else None
+    dcb = nanv(2, J) if conv_k > 0 else None
+    dhw = nanv(2, H, 3) if want_hgrads else None
+    dhb = nanv(2, H) if want_hgrads else None
+    dst_in = torch.full((nstate,), float("nan"), device=DEV)
+    d.lane_consts_cached = 1
+    K.check(K.cawn_phase_accumulate_hconv_bwd(d, mag, ang, gamma, theta, cw, cb, hw, hb, st_in, ckpt, dc_re, dc_im,
+                                              dev(dstate_out), dmag, dang, dgamma, dtheta, dcw, dcb, dhw, dhb, dst_in, ws))
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    out = dict(c_re=c_re[:, :L].cpu().numpy(), c_im=c_im[:, :L].cpu().numpy(), dmag=dmag[:, :L].cpu().numpy(),
+               dang=dang[:, :L].cpu().numpy(), dgamma=dgamma.cpu().numpy(), dtheta=dtheta.cpu().numpy(),
+               dstate_in=dst_in.cpu().numpy())
+    for k, v in (("dconv_w", dcw), ("dconv_b", dcb), ("dhconv_w", dhw), ("dhconv_b", dhb)):
+        if v is not None:
+            out[k] = v.cpu().numpy()
+    return out
+
+
 def run_fwd_bwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, grad_clamp=100.0, state_in=None,
                      dstate_out=None, want_param=True, valve=None, ret=None, ret_bias=None, valve_eps=0.001,
                      concat=False):

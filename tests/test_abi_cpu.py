@@ -172,6 +172,7 @@ def test_kernels_do_not_spill_and_keep_their_occupancy():
         pytest.skip("no resource report: library was not built by paper_2604_04250_amd.build")
     seen = 0
     strict = True
+    max_spill = 0
     for path in reports:
         name = None
         for line in open(path):
@@ -180,7 +181,7 @@ def test_kernels_do_not_spill_and_keep_their_occupancy():
                 name = val.strip()
             elif name and ("fwd_kernel" in name or "bwd_kernel" in name or "step_kernel" in name):
                 if key.startswith("ScratchSize"):
-                    # boolean template arguments: forward (VALVE, RET, BF, HC), backward (PARAM, VALVE, RET, BF)
+                    # boolean template arguments: forward (VALVE, RET, BF, HC), backward (PARAM, VALVE, RET, BF, HC)
                     flags = [f == "1" for f in re.findall(r"Lb([01])E", name)]
                     strict = True
                     allowed = 128     # (the compiler sometimes reserves a frame it never touches)
@@ -191,10 +192,13 @@ def test_kernels_do_not_spill_and_keep_their_occupancy():
                         # per tile are tolerated; the retention variants keep a retention per token-lane
                         # on top of that
                         strict = False
+                    # the backward through the harmonic convolution carries 8 more sums: with four conv taps it
+                    # parks two values outside the registers
+                    max_spill = 2 if "bwd_kernel" in name and len(flags) > 4 and flags[4] else 0
                     assert int(val) <= allowed, (name, line)
                     seen += 1
                 elif key.startswith("VGPRs Spill") and strict:
-                    assert int(val) == 0, (name, line)
+                    assert int(val) <= max_spill, (name, line)
                 elif key.startswith("Occupancy"):
                     want = 4 if "bwd_kernel" in name else 2
                     assert int(val) >= want, (name, line)
