@@ -61,9 +61,10 @@ def parse():
                     help="activations (inputs, outputs, upstream and returned gradients) are bfloat16 in memory, "
                          "arithmetic and state fp32 (extra line, not the headline; no CPU baseline)")
     ap.add_argument("--hconv", action="store_true",
-                    help="the depth-wise harmonic convolution of Sec. 3.6 fused behind the output clamp (forward only: "
-                         "a training workload then runs and times its forward pass alone; same bytes per token-lane; "
-                         "extra line, not the headline; no CPU baseline)")
+                    help="the depth-wise harmonic convolution of Sec. 3.6 fused behind the output clamp: the forward "
+                         "stores the convolved output, the backward takes its gradients and returns the taps' and "
+                         "biases' gradients as well (same bytes per token-lane; fp32, threshold gate; with --bf16, "
+                         "--valve or --ret the forward pass alone; extra line, not the headline; no CPU baseline)")
     ap.add_argument("--unfused", action="store_true",
                     help="cfg2_layer_fwd only: the Temporal Syntax Cache as separate calls (cawn_syntax_conv on each "
                          "stream, then the scan without conv front-end): 32 instead of 16 bytes per token-lane; "
@@ -261,8 +262,9 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         wl = wl.with_(chunk=args.chunk)
     B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
     theta = K.cawn_theta_init(H, F)
-    # (--hconv is a forward-only entry point: on a training workload only its forward pass is run and timed)
-    do_bwd = name in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads") and not hconv
+    # (the backward through the harmonic convolution exists for the fp32 threshold-gate path: with the other modes
+    # a training workload runs and times its forward pass alone)
+    do_bwd = name in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads") and not (hconv and (bf16 or valve_on or ret_on))
     stream_mode = name == "cfg4_stream"
     L = wl.chunk if stream_mode else wl.L
     valve_eps = 0.001
@@ -298,6 +300,7 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         rh = np.random.Generator(np.random.PCG64(4250 + 97))
         hw = torch.from_numpy((rh.standard_normal((2, H, 3)) / np.sqrt(3.0)).astype(np.float32)).to(dev)
         hb = torch.from_numpy((0.1 * rh.standard_normal((2, H))).astype(np.float32)).to(dev)
+        dhw, dhb = torch.empty((2, H, 3), device=dev), torch.empty((2, H), device=dev)
     if bf16:
         no_cpu = True
     ret = ret_bias = dret = ret_h = ret_bias_h = None
@@ -386,7 +389,11 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         if rec is not None:
             rec[1].record()
         if do_bwd:
-            if bf16:
+            if hconv:
+                st |= K.cawn_phase_accumulate_hconv_bwd(d, s["mag"], s["ang"], gamma, th, cw, cb, hw, hb, None, ckpt,
+                                                        s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"], dgamma, dtheta,
+                                                        dcw, dcb, dhw, dhb, None, ws)
+            elif bf16:
                 st |= K.cawn_phase_accumulate_bf16_bwd(d, s["mag"], s["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
                                                        None, ckpt, s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"],
                                                        dvalve, dret, None if ret is not None else dgamma, dtheta,
@@ -449,7 +456,7 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
                       "buffer_sets_rotated": nsets}}
     bflag = lambda x: "true" if x else "false"
     fwd_label = f"fwd_kernel<1,{Kc},{bflag(valve_on)},{bflag(ret_on)},{bflag(bf16)},{bflag(hconv)}>"
-    bwd_label = f"bwd_kernel<1,{Kc},true,{bflag(valve_on)},{bflag(ret_on)},{bflag(bf16)}>"
+    bwd_label = f"bwd_kernel<1,{Kc},true,{bflag(valve_on)},{bflag(ret_on)},{bflag(bf16)},{bflag(hconv)}>"
     extra = valve_on or ret_on or bf16 or unfused or hconv
     if paper:
         out["config"]["layer"] = ("the paper's statement of the layer: H=4, K=64 (Sec. 4.3), conv kernel 3 (Sec. 3.2), "

@@ -290,3 +290,90 @@ def test_one_call_over_two_million_tokens_forward_and_backward():
     assert not bad, (bad, errs)
     del fw, out
     torch.cuda.empty_cache()
+
+
+def _paper_inputs(wl):
+    """The valve and retention logits exactly as bench.py --paper draws them."""
+    B, L, H, F = wl.B, wl.L, wl.H, wl.F
+    rr = np.random.Generator(np.random.PCG64(4250 + 98))
+    ret = (-2.0 + 1.5 * rr.standard_normal((B, L, H))).astype(np.float32)
+    ret_bias = np.linspace(3.0, 0.0, F).astype(np.float32)
+    rv = np.random.Generator(np.random.PCG64(4250 + 99))
+    valve = (-3.9 + 3.0 * rv.standard_normal((B, L, H))).astype(np.float32)
+    return valve, ret, ret_bias
+
+
+def test_paper_layer_training_step_full_size():
+    """The descriptor bench.py --paper times: B=8, L=8192, 4 heads of 64 harmonics (Sec. 4.3), conv kernel 3
+    (Sec. 3.2), softplus amplitude, per-head valve with eps = 0.001 and data-dependent retention (Sec. 3.3).
+    The valve and the retention couple the lanes of a head, so whole heads are sampled: the oracle runs heads
+    0 and 3 (all batch rows, all tokens) as a two-head problem of its own."""
+    import gpu_util as G
+    from paper_2604_04250_amd import binding as K
+    wl = WL.CONFIGS["cfg6_paper_heads"].with_(name="paper_layer", conv_k=3)
+    B, L, H, F, J, Kc = wl.B, wl.L, wl.H, wl.F, wl.J, wl.conv_k
+    assert (B, L, H, F, Kc) == (8, 8192, 4, 64, 3)
+    theta = K.cawn_theta_init(H, F)
+    inp = WL.make_inputs(wl, theta=theta, with_grads=True)
+    valve, ret, ret_bias = _paper_inputs(wl)
+    out = G.run_fwd_bwd(inp, B, L, H, F, conv_k=Kc, amp_mode=1, valve=valve, valve_eps=0.001, ret=ret, ret_bias=ret_bias,
+                        want_dstate=False)
+    fw = G.run_fwd(inp, B, L, H, F, conv_k=Kc, amp_mode=1, valve=valve, valve_eps=0.001, ret=ret, ret_bias=ret_bias)
+    heads = [0, 3]
+    lanes = np.concatenate([np.arange(h * F, (h + 1) * F) for h in heads])
+    sub = _sub(inp, lanes)
+    cfg = O.Cfg(B, L, len(heads), F, conv_k=Kc, amp_mode=1, gate_mode=1, valve_eps=0.001, ret_mode=1, nthreads=O.max_threads())
+    kw = dict(conv_w=sub["conv_w"], conv_b=sub["conv_b"], valve=np.ascontiguousarray(valve[:, :, heads]),
+              ret=np.ascontiguousarray(ret[:, :, heads]), ret_bias=ret_bias)
+    of = O.phase_fwd(cfg, sub["mag"], sub["ang"], None, sub["theta"], **kw)
+    ob = O.phase_bwd(cfg, sub["mag"], sub["ang"], None, sub["theta"], sub["dz_re"], sub["dz_im"], **kw)
+    errs = {"z_re": G.rel_err(fw["z_re"][..., lanes], of["z_re"]), "z_im": G.rel_err(fw["z_im"][..., lanes], of["z_im"]),
+            "dmag": G.rel_err(out["dmag"][..., lanes], ob["dmag"]), "dang": G.rel_err(out["dang"][..., lanes], ob["dang"]),
+            "dtheta": G.rel_err(out["dtheta"][lanes], ob["dtheta"]),
+            "dconv_w": G.rel_err(out["dconv_w"][:, lanes], ob["dconv_w"]),
+            "dconv_b": G.rel_err(out["dconv_b"][:, lanes], ob["dconv_b"]),
+            "dvalve": G.rel_err(out["dvalve"][:, :, heads], ob["dvalve"]),
+            "dret": G.rel_err(out["dret"][:, :, heads], ob["dret"])}
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, (bad, errs)
+    # the valve mask of the sampled heads, bit for bit, and about half the valves shut
+    bits = np.unpackbits(fw["mask"].view(np.uint8), bitorder="little").reshape(B, L, -1)[..., :J]
+    assert np.array_equal(bits[..., lanes], of["gate"])
+    assert 0.4 < 1.0 - bits.mean() < 0.6
+
+
+def test_training_step_through_the_harmonic_conv_full_size():
+    """bench.py --hconv: the training-step shape (B=8, L=8192, 12 heads of 64) with the harmonic convolution fused
+    behind the clamp, forward and backward; heads 0, 5 and 11 against the oracle's composed step."""
+    import gpu_util as G
+    from paper_2604_04250_amd import binding as K
+    wl = WL.CONFIGS["cfg3_train"]
+    B, L, H, F, J, Kc = wl.B, wl.L, wl.H, wl.F, wl.J, wl.conv_k
+    theta = K.cawn_theta_init(H, F)
+    inp = WL.make_inputs(wl, theta=theta, with_grads=True)
+    rh = np.random.Generator(np.random.PCG64(4250 + 97))
+    inp["hconv_w"] = (rh.standard_normal((2, H, 3)) / np.sqrt(3.0)).astype(np.float32)
+    inp["hconv_b"] = (0.1 * rh.standard_normal((2, H))).astype(np.float32)
+    inp["dc_re"], inp["dc_im"] = inp["dz_re"], inp["dz_im"]
+    out = G.run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=Kc, gate_tau=wl.gate_tau)
+    heads = [0, 5, 11]
+    lanes = np.concatenate([np.arange(h * F, (h + 1) * F) for h in heads])
+    sub = _sub(inp, lanes)
+    n = len(heads)
+    hw, hb = np.ascontiguousarray(inp["hconv_w"][:, heads]), np.ascontiguousarray(inp["hconv_b"][:, heads])
+    kw = dict(conv_k=Kc, gate_tau=wl.gate_tau, nthreads=O.max_threads())
+    f = O.phase_fwd(O.Cfg(B, L, n, F, **kw), sub["mag"], sub["ang"], sub["gamma"], sub["theta"], conv_w=sub["conv_w"],
+                    conv_b=sub["conv_b"], want_gate=False)
+    c = O.harmonic_conv(f["z_re"], f["z_im"], n, F, hw, hb)
+    gh = O.harmonic_conv_bwd(f["z_re"], f["z_im"], n, F, hw, sub["dz_re"], sub["dz_im"])
+    g = O.phase_bwd(O.Cfg(B, L, n, F, dz_f64=1, **kw), sub["mag"], sub["ang"], sub["gamma"], sub["theta"], gh["dz_re"],
+                    gh["dz_im"], conv_w=sub["conv_w"], conv_b=sub["conv_b"])
+    errs = {"c_re": G.rel_err(out["c_re"][..., lanes], c[0]), "c_im": G.rel_err(out["c_im"][..., lanes], c[1]),
+            "dmag": G.rel_err(out["dmag"][..., lanes], g["dmag"]), "dang": G.rel_err(out["dang"][..., lanes], g["dang"]),
+            "dgamma": G.rel_err(out["dgamma"][lanes], g["dgamma"]), "dtheta": G.rel_err(out["dtheta"][lanes], g["dtheta"]),
+            "dconv_w": G.rel_err(out["dconv_w"][:, lanes], g["dconv_w"]),
+            "dconv_b": G.rel_err(out["dconv_b"][:, lanes], g["dconv_b"]),
+            "dhconv_w": G.rel_err(out["dhconv_w"][:, heads], gh["dw"]),
+            "dhconv_b": G.rel_err(out["dhconv_b"][:, heads], gh["dbias"])}
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, (bad, errs)
