@@ -242,10 +242,18 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
     float acc = 0.0f;
     if (j < J) {
         const int lb = j / JB, jj = j % JB;
-        for (int c = g; c < chains; c += G) {
-            const size_t tile = (size_t)c * nLB + lb;
-            acc += part[(tile * rows + row) * JB + jj];
+        // (eight independent reads in flight per thread; the sum keeps its order)
+        const float *src = part + ((size_t)lb * rows + row) * JB + jj;
+        const size_t step = (size_t)nLB * rows * JB;      // floats between the same slot of consecutive chains
+        int c = g;
+        for (; c + 7 * G < chains; c += 8 * G) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(c + u * G) * step];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
         }
+        for (; c < chains; c += G) acc += src[(size_t)c * step];
     }
     sm[g][lane] = acc;
     __syncthreads();

@@ -42,6 +42,17 @@ __device__ __forceinline__ float dpp_add_bcast15(float x)
     return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x142, 0xA, 0xF, false));
 }
 
+// Whole-wave shifts by one lane (DPP wave_shr:1 / wave_shl:1): lane i takes lane i-1's (i+1's) value, the
+// first (last) lane keeps its own.
+__device__ __forceinline__ float wave_shift_up(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x138, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float wave_shift_down(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x130, 0xF, 0xF, false));
+}
+
 template <int V> struct BVec;
 template <> struct BVec<1> {
     static __device__ __forceinline__ void ld(float (&d)[1], const float *p) { d[0] = *p; }
@@ -259,8 +270,12 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         if constexpr (HC) {
             // the two neighbour lanes of the block, 64 tokens per instruction; rows past the end and lanes
             // outside the tensor read a valid address (their values are masked where they are used)
+            // (a side whose neighbour lies in another head is never used: not fetched.  Heads of 32 lanes or
+            // fewer need none, heads of 64 one side per block)
+            const bool need_lo = ((lb_ * JB) & (a.F - 1)) != 0, need_hi = ((lb_ * JB + JB) & (a.F - 1)) != 0;
             for (int e = wv; e < 8; e += nwv) {
                 const int plane = e >> 2, side = (e >> 1) & 1, half = e & 1;
+                if (side ? !need_hi : !need_lo) continue;
                 int t = tt_ * TILE_T + half * 64 + lane;
                 t = t < a.L ? t : a.L - 1;
                 int j = side ? lb_ * JB + JB : lb_ * JB - 1;
@@ -304,22 +319,25 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         return k;
     };
     auto hc_read = [&](int i, const HcLane &k, float (&cr)[3], float (&ci)[3]) {
-        float c0r = (&sDz[0][0])[k.own + i * JBS], c0i = (&sDz[NRZ][0])[k.own + i * JBS];
-        float er = sEdge[k.edge + i], ei = sEdge[2 * NRZ + k.edge + i];
-        asm volatile("" : "+v"(c0r), "+v"(c0i), "+v"(er), "+v"(ei));
-        const bool live = i < k.nlive;
-        c0r = live ? c0r : 0.f;
-        c0i = live ? c0i : 0.f;
-        // (the exchange crosses the two segments of a wave at lanes 31 | 32: exactly the lanes that take the edge)
-        const float mr = __shfl_up(c0r, 1, 64), mi = __shfl_up(c0i, 1, 64);
-        const float pr = __shfl_down(c0r, 1, 64), pi = __shfl_down(c0i, 1, 64);
-        const bool keep_m = live & !k.first, keep_p = live & !k.last;
-        cr[0] = keep_m ? (k.is_lo ? er : mr) : 0.f;
-        ci[0] = keep_m ? (k.is_lo ? ei : mi) : 0.f;
-        cr[2] = keep_p ? (k.is_hi ? er : pr) : 0.f;
-        ci[2] = keep_p ? (k.is_hi ? ei : pi) : 0.f;
-        cr[1] = c0r;
-        ci[1] = c0i;
+        if constexpr (HC) {
+            float c0r = (&sDz[0][0])[k.own + i * JBS], c0i = (&sDz[NRZ][0])[k.own + i * JBS];
+            float er = sEdge[k.edge + i], ei = sEdge[2 * NRZ + k.edge + i];
+            asm volatile("" : "+v"(c0r), "+v"(c0i), "+v"(er), "+v"(ei));
+            const bool live = i < k.nlive;
+            c0r = live ? c0r : 0.f;
+            c0i = live ? c0i : 0.f;
+            // (whole-wave shifts by one lane, in the vector ALU: they cross the two segments of a wave at lanes
+            // 31 | 32, exactly the lanes that take the staged edge instead)
+            const float mr = wave_shift_up(c0r), mi = wave_shift_up(c0i);
+            const float pr = wave_shift_down(c0r), pi = wave_shift_down(c0i);
+            const bool keep_m = live & !k.first, keep_p = live & !k.last;
+            cr[0] = keep_m ? (k.is_lo ? er : mr) : 0.f;
+            ci[0] = keep_m ? (k.is_lo ? ei : mi) : 0.f;
+            cr[2] = keep_p ? (k.is_hi ? er : pr) : 0.f;
+            ci[2] = keep_p ? (k.is_hi ? ei : pi) : 0.f;
+            cr[1] = c0r;
+            ci[1] = c0i;
+        }
     };
     if (PF) {
         if (it == 0) {      // a workgroup's first tile: nobody staged its gradients ahead
