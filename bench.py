@@ -210,7 +210,7 @@ class CopyCeiling:
 
 
 def lane_sample_parity(np, G, O, wl, inp, got, mode, Kc, amp_mode=0, valve=None, valve_eps=0.001, ret=None, ret_bias=None,
-                       max_tokens=None):
+                       max_tokens=None, hconv=None):
     """Parity of the timed configuration itself on sampled lanes: the harmonics of head 0, every batch row,
     every token (lanes are independent, so the oracle runs on those lanes alone).  `got` holds the timed
     run's outputs (torch tensors).  Returns the worst relative error (rms-floored, as in the tests)."""
@@ -230,9 +230,21 @@ def lane_sample_parity(np, G, O, wl, inp, got, mode, Kc, amp_mode=0, valve=None,
     gam = None if ret is not None else inp["gamma"][sl]
     of = O.phase_fwd(cfg, sub(inp["mag"]), sub(inp["ang"]), gam, inp["theta"][sl], want_gate=False, **kw)
     host = lambda t: t[:, :L, sl].float().cpu().numpy()
-    err = {"z": max(G.rel_err(host(got["z_re"]), of["z_re"]), G.rel_err(host(got["z_im"]), of["z_im"]))}
+    zo = (of["z_re"], of["z_im"])
+    if hconv is not None:       # (hw [2,H,3], hb [2,H]): the stored planes are the convolved ones; head 0 stands alone
+        hw0, hb0 = np.ascontiguousarray(hconv[0][:, :1]), np.ascontiguousarray(hconv[1][:, :1])
+        zo = O.harmonic_conv(of["z_re"], of["z_im"], 1, F, hw0, hb0)
+    err = {"z": max(G.rel_err(host(got["z_re"]), zo[0]), G.rel_err(host(got["z_im"]), zo[1]))}
     if "dmag" in got and L == wl.L:
-        ob = O.phase_bwd(cfg, sub(inp["mag"]), sub(inp["ang"]), gam, inp["theta"][sl], sub(inp["dz_re"]), sub(inp["dz_im"]), **kw)
+        up_re, up_im = sub(inp["dz_re"]), sub(inp["dz_im"])
+        bcfg = cfg
+        if hconv is not None:   # the upstream gradients are those of the convolved planes
+            gh = O.harmonic_conv_bwd(of["z_re"], of["z_im"], 1, F, hw0, up_re, up_im)
+            up_re, up_im = gh["dz_re"], gh["dz_im"]
+            bcfg = O.Cfg(B, L, 1, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=wl.gate_tau, dz_f64=1, nthreads=O.max_threads())
+            err["dhconv_w"] = G.rel_err(got["dhconv_w"][:, :1].cpu().numpy(), gh["dw"])
+            err["dhconv_b"] = G.rel_err(got["dhconv_b"][:, :1].cpu().numpy(), gh["dbias"])
+        ob = O.phase_bwd(bcfg, sub(inp["mag"]), sub(inp["ang"]), gam, inp["theta"][sl], up_re, up_im, **kw)
         err["dmag"] = G.rel_err(host(got["dmag"]), ob["dmag"])
         err["dang"] = G.rel_err(host(got["dang"]), ob["dang"])
         for k in ("dgamma", "dtheta"):
@@ -528,7 +540,7 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         out["gate_closed_fraction"] = float(1.0 - bits.mean())
 
     # ---- parity of the timed configuration itself on sampled lanes (head 0: lanes are independent)
-    if not (bf16 or hconv or unfused):
+    if not (bf16 or unfused or (hconv and (valve_on or ret_on))):
         from oracle import cawn_oracle as O
         import gpu_util as G
         if stream_mode:                  # the first chunk of a stream: zero state in, state carried out in place
@@ -541,9 +553,12 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         if do_bwd:
             got.update(dgamma=None if ret_on else dgamma, dtheta=dtheta, dconv_w=dcw if Kc else None, dconv_b=dcb if Kc else None,
                        dvalve=dvalve, dret=dret)
+            if hconv:
+                got.update(dhconv_w=dhw, dhconv_b=dhb)
         t_par = time.perf_counter()
         errs = lane_sample_parity(np, G, O, wl, inp, got, "stream" if stream_mode else "batch", Kc, amp_mode=amp_mode,
-                                  valve=valve_h, valve_eps=valve_eps, ret=ret_h, ret_bias=ret_bias_h)
+                                  valve=valve_h, valve_eps=valve_eps, ret=ret_h, ret_bias=ret_bias_h,
+                                  hconv=(hw.cpu().numpy(), hb.cpu().numpy()) if hconv else None)
         out["parity_sample"] = {"lanes": f"head 0 ({F} lanes), all {B} batch rows, all tokens of one call",
                                 "max_rel_err": max(errs.values()), "per_tensor": errs,
                                 "oracle_seconds": round(time.perf_counter() - t_par, 2)}

@@ -248,6 +248,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     const bool chained = ttr > 0;                     // has a predecessor in the chain
     const bool feeds = tt > 0;                        // has a successor in the chain
 
+    // (the wave that owns the chain runs at raised priority until the tile's prefix is out: what it does in
+    // that span -- aggregate, look-back, prefix -- is what other tiles wait for; 0.5 % on the whole kernel)
+    if (wave == 0) __builtin_amdgcn_s_setprio(2);
     // ---- upstream gradients of my tokens (registers), then the tile's input rows (LDS)
     float dzr[NSTEP][V], dzi[NSTEP][V];     // upstream dS, later overwritten by d(pre-activation)
     // a tile that lies wholly inside the tensors loads and stores without per-row checks
@@ -895,6 +898,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
             }
         }
     }
+    if (wave == 0) __builtin_amdgcn_s_setprio(0);
     if (PF) lds_barrier_raw(); else lds_barrier();
     BWD_STAMP(6);
     if (PF && HC && wave != 0) stage_next();
