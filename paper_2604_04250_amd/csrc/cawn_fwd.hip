@@ -169,20 +169,17 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
     const bool owner_wave = wave == NW - 1;        // the wave holding the last segment owns the chain
     const float *tail_in = a.state_in ? a.state_in + (size_t)a.B * 2 * a.J : nullptr;
 
-    // A workgroup's first tile is the one with its own index; further tiles are drawn from the atomic
-    // counter, which starts behind the grid's first tiles.  (Drawn from the counter, the first tickets of a
-    // 384-workgroup call arrived over 5.7 us: atomics on one address are served one after the other.  Tile
-    // order and progress argument are unchanged: workgroups are dispatched in index order and the grid never
-    // exceeds what is resident at once, so every tile a workgroup can wait for -- one with a lower ticket --
-    // belongs to a workgroup that is running or has finished.)
-    const uint32_t hcG0 = HC ? (uint32_t)a.hcG : 1u;
-    const uint32_t first_base = gridDim.x * hcG0;
-    uint32_t ticket = (uint32_t)blockIdx.x * hcG0;
-    uint32_t epoch_early = 0;     // (thread 0: the call's epoch, on its way while the first rows are staged)
     if (tid == 0) {
-        epoch_early = flag_load(&a.hdr->epoch);
+        const uint32_t e = flag_load(&a.hdr->epoch);     // both round trips at once
+        const uint32_t t = __hip_atomic_fetch_add(&a.hdr->ticket[0], HC ? (uint32_t)a.hcG : 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sEpoch = e;
+        sTicket[0] = t;
         sLast = 0;
     }
+    __syncthreads();
+    uint32_t ticket = (uint32_t)__builtin_amdgcn_readfirstlane((int)sTicket[0]);   // wave-uniform: index math stays scalar
+    const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
+    const uint32_t tag = make_tag(epoch);      // of every word this call publishes
 
     // From here on the kernel's arguments are read from the kernel-argument segment again in every
     // phase of a tile (scalar loads next to their use; `ARGS_AGAIN()` makes the compiler forget what it
@@ -229,11 +226,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
         stage_tile(T);
     }
 
-    wait_vm<0>();     // the first tile's staged rows (and the epoch)
-    if (tid == 0) sEpoch = epoch_early;
-    __syncthreads();
-    const uint32_t epoch = (uint32_t)__builtin_amdgcn_readfirstlane((int)sEpoch);
-    const uint32_t tag = make_tag(epoch);      // of every word this call publishes
+    wait_vm<0>();     // the first tile's staged rows
 
     float lr[V], li[V], pfr[V], pfi[V], psr[V], psi[V];
     float wm[KC1][V], wa[KC1][V], bm[V], ba[V];
@@ -259,7 +252,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
             if (HC && (ticket + 1) % hcG != 0)
                 ticket_ahead = ticket + 1;
             else
-                ticket_ahead = first_base + __hip_atomic_fetch_add(&a.hdr->ticket[0], hcG, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ticket_ahead = __hip_atomic_fetch_add(&a.hdr->ticket[0], hcG, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 
         // ---- the staged rows have landed (each wave waited for its own loads: before the loop, or
