@@ -357,3 +357,54 @@ def test_epoch_wrap_clears_published_words():
         for k in ("dmag", "dang", "dgamma", "dtheta", "dconv_w"):
             assert G.rel_err(out[k], ob[k]) <= TOL, k
     assert seen[0] == 0 and seen == sorted(seen) and seen[-1] == 9, seen     # wrapped once, then counts on
+
+
+def test_two_calls_on_two_streams_share_the_gpu_without_blocking_each_other():
+    """Two forward + backward calls run at the same time on two streams with a workspace each.  Each has more
+    tiles than the GPU holds workgroups, so neither grid is resident as a whole while the other runs: a tile
+    must never wait for a tile that no running workgroup holds (tickets are drawn by running workgroups only).
+    Results equal those of the same calls run one after the other, bit for bit, and no wait gave up."""
+    G = _gpu()
+    from paper_2604_04250_amd import binding as K
+    import torch
+    B, L, H, F, Kc = 4, 4096, 12, 64, 4
+    J = H * F
+    jobs = []
+    for s in range(2):
+        d = _inputs(B, L, H, F, Kc, 1500 + s)
+        g = torch.Generator(device=G.DEV)
+        g.manual_seed(77 + s)
+        t = {k: G.dev(v) for k, v in d.items() if k in ("mag", "ang", "gamma", "theta", "conv_w", "conv_b")}
+        t["dz"] = torch.randn((2, B, L, J), device=G.DEV, generator=g)
+        desc = K.make_desc(B, L, H, F, conv_k=Kc, gate_tau=0.1)
+        ws = torch.empty((K.cawn_workspace_bytes(desc) + 3) // 4, dtype=torch.int32, device=G.DEV)
+        K.check(K.cawn_workspace_init(ws))
+        ck = torch.empty(K.cawn_ckpt_bytes(desc) // 4, device=G.DEV)
+        jobs.append((t, desc, ws, ck))
+
+    def run(job, stream):
+        t, desc, ws, ck = job
+        z = torch.empty((2, B, L, J), device=G.DEV)
+        dx = torch.empty((2, B, L, J), device=G.DEV)
+        par = [torch.empty(J, device=G.DEV), torch.empty(J, device=G.DEV), torch.empty((2, J, Kc), device=G.DEV),
+               torch.empty((2, J), device=G.DEV)]
+        K.check(K.cawn_phase_accumulate_fwd(desc, t["mag"], t["ang"], t["gamma"], t["theta"], t["conv_w"], t["conv_b"], None,
+                                            z[0], z[1], None, ck, None, ws, stream=stream))
+        K.check(K.cawn_phase_accumulate_bwd(desc, t["mag"], t["ang"], t["gamma"], t["theta"], t["conv_w"], t["conv_b"], None,
+                                            ck, t["dz"][0], t["dz"][1], None, dx[0], dx[1], *par, None, ws, stream=stream))
+        return [z, dx] + par
+
+    torch.cuda.synchronize()
+    ref = [run(j, None) for j in jobs]                      # one after the other
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]    # (default priority)
+    for rounds in range(3):
+        got = []
+        for j, s in zip(jobs, streams):
+            with torch.cuda.stream(s):                      # allocations of run() belong to the stream
+                got.append(run(j, s))
+        torch.cuda.synchronize()
+        for j, r_, g_ in zip(jobs, ref, got):
+            K.check(K.cawn_workspace_status(j[2]))
+            for a_, b_ in zip(r_, g_):
+                assert torch.equal(a_, b_)
