@@ -304,7 +304,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // the staged edge instead).  What depends on the lane alone is set up once per pass from an opaque copy of
     // the thread index, not carried across the tile; every read is unconditional and pinned, so that the
     // choices below are selects on loaded values (a read inside one arm of a choice becomes a branch around it).
-    struct HcLane { int own, edge, nlive; bool is_lo, is_hi, first, last; };
+    struct HcLane { int own, edge, nlive; bool use_lo, use_hi, first, last; };
     auto hc_setup = [&]() {
         int t_ = tid_;
         asm volatile("" : "+v"(t_));
@@ -315,29 +315,38 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         k.edge = (lv_ == 0 ? 0 : NRZ) + sg_ * NSTEP;             // word offset of my first token in my side of sEdge
         const int left = a.L - (tt * TILE_T + sg_ * NSTEP);
         k.nlive = full ? NSTEP : ((lb * JB + lv_ < a.J) ? (left < 0 ? 0 : (left > NSTEP ? NSTEP : left)) : 0);
-        k.is_lo = lv_ == 0;
-        k.is_hi = lv_ == LPR - 1;
         k.first = kh == 0;
         k.last = kh == a.F - 1;
+        // (the staged edge is taken only where it was fetched: a block edge inside a head.  At a head's end the
+        // shifted value stands in -- finite data that the callers' zero tap or final select discards)
+        k.use_lo = lv_ == 0 && !k.first;
+        k.use_hi = lv_ == LPR - 1 && !k.last;
         return k;
     };
-    auto hc_read = [&](int i, const HcLane &k, float (&cr)[3], float (&ci)[3]) {
+    auto hc_read = [&](auto full_c, int i, const HcLane &k, float (&cr)[3], float (&ci)[3]) {
+        constexpr bool FULL = decltype(full_c)::value;
         if constexpr (HC) {
             float c0r = (&sDz[0][0])[k.own + i * JBS], c0i = (&sDz[NRZ][0])[k.own + i * JBS];
             float er = sEdge[k.edge + i], ei = sEdge[2 * NRZ + k.edge + i];
             asm volatile("" : "+v"(c0r), "+v"(c0i), "+v"(er), "+v"(ei));
-            const bool live = i < k.nlive;
-            c0r = live ? c0r : 0.f;
-            c0i = live ? c0i : 0.f;
+            if constexpr (!FULL) {      // rows and lanes outside the tensor staged a valid address: their values count as zero
+                const bool live = i < k.nlive;
+                c0r = live ? c0r : 0.f;
+                c0i = live ? c0i : 0.f;
+                er = live ? er : 0.f;
+                ei = live ? ei : 0.f;
+            }
             // (whole-wave shifts by one lane, in the vector ALU: they cross the two segments of a wave at lanes
-            // 31 | 32, exactly the lanes that take the staged edge instead)
-            const float mr = wave_shift_up(c0r), mi = wave_shift_up(c0i);
-            const float pr = wave_shift_down(c0r), pi = wave_shift_down(c0i);
-            const bool keep_m = live & !k.first, keep_p = live & !k.last;
-            cr[0] = keep_m ? (k.is_lo ? er : mr) : 0.f;
-            ci[0] = keep_m ? (k.is_lo ? ei : mi) : 0.f;
-            cr[2] = keep_p ? (k.is_hi ? er : pr) : 0.f;
-            ci[2] = keep_p ? (k.is_hi ? ei : pi) : 0.f;
+            // 31 | 32, exactly the lanes that take the staged edge instead.  Positions outside the head are NOT
+            // zeroed here: the callers fold that into the taps, or into the finished sums, once per tile.)
+            // The shifts are statements of their own, in front of every choice: written inside one arm of a `?:` a
+            // shift runs under that arm's narrowed EXEC mask, and a lane whose source lane is switched off keeps its
+            // own value.  (Cross-lane operations are convergent: the compiler does not move them under a condition.)
+            const float mr = wave_shift_up(c0r), mi = wave_shift_up(c0i), pr = wave_shift_down(c0r), pi = wave_shift_down(c0i);
+            cr[0] = k.use_lo ? er : mr;
+            ci[0] = k.use_lo ? ei : mi;
+            cr[2] = k.use_hi ? er : pr;
+            ci[2] = k.use_hi ? ei : pi;
             cr[1] = c0r;
             ci[1] = c0i;
         }
@@ -359,9 +368,14 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                     for (int q = 0; q < 3; ++q) w_[p_][q] = sLam[4 + 3 * p_ + q][lv];
                 const HcLane hk = hc_setup();
 #pragma unroll
+                for (int p_ = 0; p_ < 2; ++p_) {     // a neighbour outside my head contributes nothing
+                    w_[p_][0] = hk.last ? 0.f : w_[p_][0];      // tap 0 meets the gradient at k+1
+                    w_[p_][2] = hk.first ? 0.f : w_[p_][2];     // tap 2 the one at k-1
+                }
+#pragma unroll
                 for (int i = 0; i < NSTEP; ++i) {
                     float cr[3], ci[3];
-                    hc_read(i, hk, cr, ci);
+                    hc_read(full_c, i, hk, cr, ci);
                     dzr[i][0] = __builtin_fmaf(w_[0][0], cr[2], __builtin_fmaf(w_[0][1], cr[1], w_[0][2] * cr[0]));
                     dzi[i][0] = __builtin_fmaf(w_[1][0], ci[2], __builtin_fmaf(w_[1][1], ci[1], w_[1][2] * ci[0]));
                     if (i & 1) __builtin_amdgcn_sched_barrier(0);     // (two tokens' reads in flight, not all eight)
@@ -806,25 +820,33 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         //      before token i+1; Z[t] = clamp(S[t]) meets the gradients at k+1, k, k-1 (taps 0, 1, 2)
         __builtin_amdgcn_sched_barrier(0);
         const HcLane hk = hc_setup();
+        auto tap_pass = [&](auto full_c) {
 #pragma unroll
-        for (int i = 0; i < NSTEP; ++i) {
-            const float sr_ = i + 1 < NSTEP ? Spr[i + 1 < NSTEP ? i + 1 : 0][0] : Efr[0];
-            const float si_ = i + 1 < NSTEP ? Spi[i + 1 < NSTEP ? i + 1 : 0][0] : Efi[0];
-            const float zr_ = clampf(sr_, a.out_clamp), zi_ = clampf(si_, a.out_clamp);
-            float cr[3], ci[3];
-            hc_read(i, hk, cr, ci);
+            for (int i = 0; i < NSTEP; ++i) {
+                const float sr_ = i + 1 < NSTEP ? Spr[i + 1 < NSTEP ? i + 1 : 0][0] : Efr[0];
+                const float si_ = i + 1 < NSTEP ? Spi[i + 1 < NSTEP ? i + 1 : 0][0] : Efi[0];
+                const float zr_ = clampf(sr_, a.out_clamp), zi_ = clampf(si_, a.out_clamp);
+                float cr[3], ci[3];
+                hc_read(full_c, i, hk, cr, ci);
 #pragma unroll
-            for (int q = 0; q < 3; ++q) {
-                hacc[q] = __builtin_fmaf(zr_, cr[2 - q], hacc[q]);
-                hacc[3 + q] = __builtin_fmaf(zi_, ci[2 - q], hacc[3 + q]);
+                for (int q = 0; q < 3; ++q) {
+                    hacc[q] = __builtin_fmaf(zr_, cr[2 - q], hacc[q]);
+                    hacc[3 + q] = __builtin_fmaf(zi_, ci[2 - q], hacc[3 + q]);
+                }
+                hacc[6] += cr[1];
+                hacc[7] += ci[1];
+                // (the sums are used at the end of the tile only; left alone, the compiler moves the whole chain
+                // down there and keeps all 48 gradients alive until then)
+#pragma unroll
+                for (int q = 0; q < HC_PART_ROWS; ++q) asm volatile("" : "+v"(hacc[q]));
             }
-            hacc[6] += cr[1];
-            hacc[7] += ci[1];
-            // (the sums are used at the end of the tile only; left alone, the compiler moves the whole chain
-            // down there and keeps all 48 gradients alive until then)
-#pragma unroll
-            for (int q = 0; q < HC_PART_ROWS; ++q) asm volatile("" : "+v"(hacc[q]));
-        }
+        };
+        tap_pass(std::false_type{});      // (one copy of the pass: a second one for whole tiles costs more registers than its four selects per token)
+        // a neighbour outside my head contributes nothing: tap 0 met the gradient at k+1, tap 2 the one at k-1
+        hacc[0] = hk.last ? 0.f : hacc[0];
+        hacc[3] = hk.last ? 0.f : hacc[3];
+        hacc[2] = hk.first ? 0.f : hacc[2];
+        hacc[5] = hk.first ? 0.f : hacc[5];
         __builtin_amdgcn_sched_barrier(0);
     }
     if (LEAN) {
@@ -1007,8 +1029,8 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float *oang = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dang) + dbase);
     uint32_t ooff = ((uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V)) * ES;      // bytes
     auto sto = [&](float *ub, uint32_t bo, const float (&x)[V]) {
-        if constexpr (BF) *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(ub) + bo) = to_bf16(x[0]);
-        else stu<V>(ub, bo, x);
+        if constexpr (BF) st_stream(reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(ub) + bo), to_bf16(x[0]));
+        else st_stream(reinterpret_cast<float *>(reinterpret_cast<char *>(ub) + bo), x[0]);
     };
     if (KC == 0) {
         if (full) {

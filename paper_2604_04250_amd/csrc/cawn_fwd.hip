@@ -607,7 +607,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
             const bool h_zl = h_first || (h_defer && h_dn), h_zr = h_last || (h_defer && !h_dn);
             const float h_wr = h_dn ? hw[0][0] : hw[0][2], h_wi = h_dn ? hw[1][0] : hw[1][2];   // tap that completes it
             const bool h_tl = h_prev && !h_dn, h_tr = h_prev && h_dn;        // which neighbour comes from LDS
-            // where the completed output is stored (0: this lane has none to complete, its second store repeats its first)
+            // where the completed output is stored (0: this lane has none to complete)
             const ptrdiff_t h_back = h_prev ? (h_dn ? (ptrdiff_t)ES : -(ptrdiff_t)ES) : 0;
             auto replay = [&](auto plain_c, auto multi_c, auto ck_c) {
                 constexpr bool PLAIN = decltype(plain_c)::value;
@@ -622,8 +622,8 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                     // writes -- the deferring lane into the slot, the others into words of sE that only they
                     // write and nobody reads before the next tile rewrites them; the deferring lane's global
                     // stores are masked off and the receiving lane of the next tile stores the completed
-                    // element; the receiving lane's second store goes to that neighbouring element, every
-                    // other lane's second store repeats its first.
+                    // element: a second store that only the receiving lane executes (streamed stores are not merged
+                    // in a cache: a second store from every lane, repeating its first, doubled the tile's writes).
                     constexpr int CH = 4;
                     static_assert(NSTEP % CH == 0, "whole chunks");
 #pragma unroll
@@ -646,7 +646,7 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                             Si[0] = ni;
                             if (CK && (i + 1) % CKPT_T == 0 && i + 1 < NSTEP && (PLAIN || (active && t0 + i + 1 < a.L))) {
                                 float *cq = reinterpret_cast<float *>(reinterpret_cast<char *>(ckp) + (uint32_t)((i + 1) / CKPT_T) * ck_step);
-                                cq[0] = nr;
+                                cq[0] = nr;       // (checkpoints are read back by the backward of the same step: cached stores)
                                 cq[a.J] = ni;
                             }
                             z_r[k] = clampf(nr, a.out_clamp);
@@ -695,18 +695,22 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                             if ((PLAIN || (active && t0 + c0 + k < a.L)) && !(MULTI && h_defer)) {
                                 char *pr_ = reinterpret_cast<char *>(zre) + off, *pi_ = reinterpret_cast<char *>(zim) + off;
                                 if constexpr (BF) {
-                                    *reinterpret_cast<uint16_t *>(pr_) = to_bf16(cr_);
-                                    *reinterpret_cast<uint16_t *>(pi_) = to_bf16(ci_);
+                                    st_stream(reinterpret_cast<uint16_t *>(pr_), to_bf16(cr_));
+                                    st_stream(reinterpret_cast<uint16_t *>(pi_), to_bf16(ci_));
                                     if constexpr (RECV) {
-                                        *reinterpret_cast<uint16_t *>(pr_ + h_back) = to_bf16(h_prev ? dpr[k] : cr_);
-                                        *reinterpret_cast<uint16_t *>(pi_ + h_back) = to_bf16(h_prev ? dpi[k] : ci_);
+                                        if (h_prev) {       // (one lane per segment: a store under its own EXEC mask)
+                                            st_stream(reinterpret_cast<uint16_t *>(pr_ + h_back), to_bf16(dpr[k]));
+                                            st_stream(reinterpret_cast<uint16_t *>(pi_ + h_back), to_bf16(dpi[k]));
+                                        }
                                     }
                                 } else {
-                                    *reinterpret_cast<float *>(pr_) = cr_;
-                                    *reinterpret_cast<float *>(pi_) = ci_;
+                                    st_stream(reinterpret_cast<float *>(pr_), cr_);
+                                    st_stream(reinterpret_cast<float *>(pi_), ci_);
                                     if constexpr (RECV) {
-                                        *reinterpret_cast<float *>(pr_ + h_back) = h_prev ? dpr[k] : cr_;
-                                        *reinterpret_cast<float *>(pi_ + h_back) = h_prev ? dpi[k] : ci_;
+                                        if (h_prev) {       // (one lane per segment: a store under its own EXEC mask)
+                                            st_stream(reinterpret_cast<float *>(pr_ + h_back), dpr[k]);
+                                            st_stream(reinterpret_cast<float *>(pi_ + h_back), dpi[k]);
+                                        }
                                     }
                                 }
                             }
@@ -742,11 +746,12 @@ __global__ __launch_bounds__(FwdGeom::NSEG *FwdLPR, (BF && !RET && !HC) ? CAWN_F
                     }
                     if (PLAIN || (active && t < a.L)) {
                         if constexpr (BF) {
-                            *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off) = to_bf16(zr[0]);
-                            *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + off) = to_bf16(zi[0]);
+                            st_stream(reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zre) + off), to_bf16(zr[0]));
+                            st_stream(reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(zim) + off), to_bf16(zi[0]));
                         } else {
-                            Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + off), zr);
-                            Vec<V>::st(reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + off), zi);
+                            static_assert(V == 1, "streamed output stores: one lane per thread");
+                            st_stream(reinterpret_cast<float *>(reinterpret_cast<char *>(zre) + off), zr[0]);
+                            st_stream(reinterpret_cast<float *>(reinterpret_cast<char *>(zim) + off), zi[0]);
                         }
                     }
                     if (!PLAIN && t == a.L - 1 && a.state_out && active) {
