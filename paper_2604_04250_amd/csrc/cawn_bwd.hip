@@ -1029,7 +1029,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float *oang = reinterpret_cast<float *>(reinterpret_cast<char *>(a.dang) + dbase);
     uint32_t ooff = ((uint32_t)(seg * NSTEP) * ist32 + (uint32_t)(lv * V)) * ES;      // bytes
     auto sto = [&](float *ub, uint32_t bo, const float (&x)[V]) {
-        if constexpr (BF) st_stream(reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(ub) + bo), to_bf16(x[0]));
+        if constexpr (BF) *reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(ub) + bo) = to_bf16(x[0]);     // (half lines: default policy)
         else st_stream(reinterpret_cast<float *>(reinterpret_cast<char *>(ub) + bo), x[0]);
     };
     if (KC == 0) {

@@ -224,7 +224,6 @@ __device__ __forceinline__ float clampf(float v, float c) { return __builtin_amd
 // and the checkpoints, which the backward of the same step reads back: those keep the default policy).
 // Measured on the training-step shape: backward 275 -> 258 us, a 4096-token chunk 25.3 -> 23.5 us.
 __device__ __forceinline__ void st_stream(float *p, float v) { __builtin_nontemporal_store(v, p); }
-__device__ __forceinline__ void st_stream(uint16_t *p, uint16_t v) { __builtin_nontemporal_store(v, p); }
 constexpr int DMA_STREAM = 2;      // cache-policy operand of the direct-to-LDS loads of staged rows: nt
 
 // bfloat16 in memory: the upper half of an fp32; to bf16 with the hardware's round-to-nearest-even.
@@ -350,6 +349,9 @@ __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const fl
                                            int wave, int nwaves, int lane)
 {
     constexpr int NRT = TT + HALO;
+    // rows whose segment fills a 128-byte line are streamed; half lines (bf16) keep the default policy, so that
+    // the cache can serve the neighbouring lane block's half of the line
+    constexpr int POL = JB * 4 >= 128 ? DMA_STREAM : 0;
     constexpr int NRTP = staged_rows<TT, JB, HALO>();
     constexpr int LR = JB * 4 / LB;                // lanes per row
     if constexpr (LR <= 64) {
@@ -370,8 +372,8 @@ __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const fl
                 const float *src = reinterpret_cast<const float *>(reinterpret_cast<const char *>(ub) + loff);
                 if (ii * RPI + r_in >= NRT) continue;      // padding rows of a stream's last instruction: not fetched
 #if defined(__HIP_DEVICE_COMPILE__)
-                if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 16, 0, DMA_STREAM);
-                else __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 4, 0, DMA_STREAM);
+                if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 16, 0, POL);
+                else __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 4, 0, POL);
 #else
                 (void)src;
 #endif
@@ -390,8 +392,8 @@ __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const fl
             const float *src = (sidx ? base_a : base_m) + ((tc - t_first) * ist + j);
             if (hist && t < 0) src = tail_in + ((size_t)(b * HALO + rr) * 2 + sidx) * J + j;
 #if defined(__HIP_DEVICE_COMPILE__)
-            if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 16, 0, DMA_STREAM);
-            else __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 4, 0, DMA_STREAM);
+            if constexpr (LB == 16) __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 16, 0, POL);
+            else __builtin_amdgcn_global_load_lds(src, sU + (size_t)(sidx * NRTP + ii * RPI) * JB, 4, 0, POL);
 #else
             (void)src;
 #endif
