@@ -407,8 +407,9 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         const float *gim = reinterpret_cast<const float *>(reinterpret_cast<const char *>(a.dz_im) + gbase);
         uint32_t off = ((uint32_t)(seg * NSTEP) * ost32 + (uint32_t)(lv * V)) * ES;      // bytes
         auto ldg = [&](float (&d)[V], const float *ub, uint32_t bo) {
+            // (read once: streamed, like the staged rows; bf16 rows are half lines and keep the default policy)
             if constexpr (BF) d[0] = from_bf16(*reinterpret_cast<const uint16_t *>(reinterpret_cast<const char *>(ub) + bo));
-            else ldu<V>(d, ub, bo);
+            else d[0] = __builtin_nontemporal_load(reinterpret_cast<const float *>(reinterpret_cast<const char *>(ub) + bo));
         };
         if (full) {
 #pragma unroll
