@@ -599,8 +599,8 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
 def main():
     args = parse()
     if args.gpus != 1:
-        print(f"bench.py: this build runs on ONE GPU (lanes and batch rows shard with no traffic; see "
-              f"DESIGN.md); --gpus {args.gpus} is not available", file=sys.stderr)
+        print(f"bench.py: this build runs on ONE GPU (lanes and batch rows are independent and would shard "
+              f"with no traffic between GPUs); --gpus {args.gpus} is not available", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
