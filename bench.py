@@ -63,7 +63,7 @@ def parse():
     ap.add_argument("--hconv", action="store_true",
                     help="the depth-wise harmonic convolution of Sec. 3.6 fused behind the output clamp: the forward "
                          "stores the convolved output, the backward takes its gradients and returns the taps' and "
-                         "biases' gradients as well (same bytes per token-lane; fp32, threshold gate; with --bf16, "
+                         "biases' gradients as well (same bytes per token-lane; threshold gate, fp32 or --bf16; with "
                          "--valve or --ret the forward pass alone; extra line, not the headline; no CPU baseline)")
     ap.add_argument("--unfused", action="store_true",
                     help="cfg2_layer_fwd only: the Temporal Syntax Cache as separate calls (cawn_syntax_conv on each "
@@ -274,9 +274,9 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         wl = wl.with_(chunk=args.chunk)
     B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
     theta = K.cawn_theta_init(H, F)
-    # (the backward through the harmonic convolution exists for the fp32 threshold-gate path: with the other modes
-    # a training workload runs and times its forward pass alone)
-    do_bwd = name in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads") and not (hconv and (bf16 or valve_on or ret_on))
+    # (the backward through the harmonic convolution exists for the threshold gate with constant retention: with the
+    # valve or data-dependent retention a training workload runs and times its forward pass alone)
+    do_bwd = name in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads") and not (hconv and (valve_on or ret_on))
     stream_mode = name == "cfg4_stream"
     L = wl.chunk if stream_mode else wl.L
     valve_eps = 0.001
@@ -404,7 +404,7 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
             if hconv:
                 st |= K.cawn_phase_accumulate_hconv_bwd(d, s["mag"], s["ang"], gamma, th, cw, cb, hw, hb, None, ckpt,
                                                         s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"], dgamma, dtheta,
-                                                        dcw, dcb, dhw, dhb, None, ws)
+                                                        dcw, dcb, dhw, dhb, None, ws, activations_bf16=1 if bf16 else 0)
             elif bf16:
                 st |= K.cawn_phase_accumulate_bf16_bwd(d, s["mag"], s["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
                                                        None, ckpt, s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"],

@@ -302,19 +302,21 @@ int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const v
  *   dhconv_b [2][H]:     d b_p[h]    = sum over b, t, k of dc_p[k]
  * where z is the clamped state of the forward (rebuilt from ckpt, never read from memory; the output
  * clamp passes the gradient).  Neither is clamped by grad_clamp; both follow accumulate_param_grads and
- * may be NULL.  Threshold gate, constant retention and fp32 activations only: gate_mode 0, ret_mode 0
- * (CAWN_EUNSUPPORTED otherwise); d->hconv_k must be 3, head widths as in the forward; ckpt is required.
+ * may be NULL.  Threshold gate and constant retention only: gate_mode 0, ret_mode 0 (CAWN_EUNSUPPORTED
+ * otherwise); d->hconv_k must be 3, head widths as in the forward; ckpt is required.
+ *   activations_bf16  0: mag, ang, dc_re, dc_im, dmag, dang are fp32;  1: bfloat16 with the rules of
+ *                     cawn_phase_accumulate_bf16_bwd (every other gradient stays fp32)
  * dc_re, dc_im use the out strides.  The lane constants that d->lane_consts_cached keeps include hconv_w
  * and hconv_b.  Everything else (arguments, layouts, ownership, errors) as in cawn_phase_accumulate_bwd.
  */
-int cawn_phase_accumulate_hconv_bwd(const cawn_desc *d, const float *mag, const float *ang,
+int cawn_phase_accumulate_hconv_bwd(const cawn_desc *d, const void *mag, const void *ang,
                                     const float *gamma, const float *theta, const float *conv_w,
                                     const float *conv_b, const float *hconv_w, const float *hconv_b,
-                                    const void *state_in, const void *ckpt, const float *dc_re,
-                                    const float *dc_im, const void *dstate_out, float *dmag, float *dang,
+                                    const void *state_in, const void *ckpt, const void *dc_re,
+                                    const void *dc_im, const void *dstate_out, void *dmag, void *dang,
                                     float *dgamma, float *dtheta, float *dconv_w, float *dconv_b,
                                     float *dhconv_w, float *dhconv_b, void *dstate_in, void *workspace,
-                                    size_t workspace_bytes, void *stream);
+                                    size_t workspace_bytes, int32_t activations_bf16, void *stream);
 
 /*
  * Backward of cawn_phase_accumulate_bf16_fwd: mag, ang, dz_re, dz_im are read and dmag, dang are

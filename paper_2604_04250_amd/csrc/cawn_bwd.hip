@@ -125,7 +125,7 @@ __device__ __forceinline__ bool head_sum_lane(int lv, int vwidth)
 template <int V, int KC, bool PARAM, bool VALVE, bool RET, bool BF, bool HC = false>
 __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_kernel(const BwdArgs a)
 {
-    static_assert(!HC || (PARAM && !VALVE && !RET && !BF && V == 1), "harmonic convolution: threshold mode, fp32, with the state rebuild");
+    static_assert(!HC || (PARAM && !VALVE && !RET && V == 1), "harmonic convolution: threshold mode, with the state rebuild");
     static_assert(!BF || V == 1, "bf16 activations: one lane per thread");
     static_assert(!RET || (PARAM && V == 1), "retention kernels rebuild the forward state; one lane per thread");
     // The valve and retention kernels sit at the register budget.  They keep the reduced angle instead
@@ -174,9 +174,12 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     float (*sEb)[2][JB] = reinterpret_cast<float (*)[2][JB]>(&sPool[0]);
     float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(&sPool[PF ? 0 : N_EB]);   // [NW]: first rows of each wave's earlier segment
     __shared__ float sCarry[2][JB];
-    __shared__ float sRedOwn[(PARAM && !PF) ? NW : 1][ROWS][JB];
-    static_assert(!PF || (size_t)NW * ROWS * JB <= (size_t)2 * NRTP * JBS, "the partial-sum staging fits over the input rows");
-    float (*sRed)[ROWS][JB] = PF ? reinterpret_cast<float (*)[ROWS][JB]>(&sU[0][0]) : sRedOwn;
+    // (bf16 rows are half as large and the harmonic convolution adds 8 partial rows: that combination has LDS to
+    // spare and keeps the staging in an array of its own)
+    constexpr bool RED_OVER_ROWS = PF && !(BF && HC);
+    __shared__ float sRedOwn[(PARAM && !RED_OVER_ROWS) ? NW : 1][ROWS][JB];
+    static_assert(!RED_OVER_ROWS || (size_t)NW * ROWS * JB <= (size_t)2 * NRTP * JBS, "the partial-sum staging fits over the input rows");
+    float (*sRed)[ROWS][JB] = RED_OVER_ROWS ? reinterpret_cast<float (*)[ROWS][JB]>(&sU[0][0]) : sRedOwn;
     constexpr int GPB_MAX = 4;                    // valve groups per lane block (F >= 8)
     __shared__ float sV[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];      // valve logits, [group][token]
     __shared__ float sVp[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
@@ -283,7 +286,11 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
                 t = t < a.L ? t : a.L - 1;
                 int j = side ? lb_ * JB + JB : lb_ * JB - 1;
                 j = j < 0 ? 0 : (j >= a.J ? a.J - 1 : j);
-                const float *src = (plane ? a.dz_im : a.dz_re) + (size_t)b_ * a.osb + (size_t)t * a.ost + j;
+                // (bf16: the four-byte word that holds the element -- strides and the block's first lane are even, so
+                // lane -1 is the upper half of its word and lane JB the lower half of its own)
+                const size_t e_ = (size_t)b_ * a.osb + (size_t)t * a.ost + j;
+                const float *src = BF ? reinterpret_cast<const float *>(reinterpret_cast<const uint16_t *>(plane ? a.dz_im : a.dz_re) + (e_ & ~(size_t)1))
+                                      : (plane ? a.dz_im : a.dz_re) + e_;
 #if defined(__HIP_DEVICE_COMPILE__)
                 __builtin_amdgcn_global_load_lds(src, &sEdge[(plane * 2 + side) * NRZ + half * 64], 4, 0, 0);
 #else
@@ -311,7 +318,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
         const int lv_ = t_ % LPR, sg_ = t_ / LPR;
         const int kh = (lb * JB + lv_) & (a.F - 1);
         HcLane k;
-        k.own = sg_ * NSTEP * JBS + lv_;                         // word offset of (my first token, my lane) in a plane of sDz
+        k.own = sg_ * NSTEP * (BF ? 2 * JBS : JBS) + lv_;         // element offset of (my first token, my lane) in a plane of sDz
         k.edge = (lv_ == 0 ? 0 : NRZ) + sg_ * NSTEP;             // word offset of my first token in my side of sEdge
         const int left = a.L - (tt * TILE_T + sg_ * NSTEP);
         k.nlive = full ? NSTEP : ((lb * JB + lv_ < a.J) ? (left < 0 ? 0 : (left > NSTEP ? NSTEP : left)) : 0);
@@ -326,8 +333,18 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     auto hc_read = [&](auto full_c, int i, const HcLane &k, float (&cr)[3], float (&ci)[3]) {
         constexpr bool FULL = decltype(full_c)::value;
         if constexpr (HC) {
-            float c0r = (&sDz[0][0])[k.own + i * JBS], c0i = (&sDz[NRZ][0])[k.own + i * JBS];
-            float er = sEdge[k.edge + i], ei = sEdge[2 * NRZ + k.edge + i];
+            float c0r, c0i, er = sEdge[k.edge + i], ei = sEdge[2 * NRZ + k.edge + i];
+            if constexpr (BF) {
+                c0r = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[0][0])[k.own + i * 2 * JBS]);
+                c0i = from_bf16(reinterpret_cast<const uint16_t *>(&sDz[NRZ][0])[k.own + i * 2 * JBS]);
+                // the staged word's half that is my neighbour: upper for lane -1, lower for lane JB
+                const uint32_t wr = __float_as_uint(er), wi = __float_as_uint(ei);
+                er = __uint_as_float(k.use_lo ? (wr & 0xffff0000u) : (wr << 16));
+                ei = __uint_as_float(k.use_lo ? (wi & 0xffff0000u) : (wi << 16));
+            } else {
+                c0r = (&sDz[0][0])[k.own + i * JBS];
+                c0i = (&sDz[NRZ][0])[k.own + i * JBS];
+            }
             asm volatile("" : "+v"(c0r), "+v"(c0i), "+v"(er), "+v"(ei));
             if constexpr (!FULL) {      // rows and lanes outside the tensor staged a valid address: their values count as zero
                 const bool live = i < k.nlive;
@@ -1396,23 +1413,23 @@ static hipError_t launch_bwd_vpb(const BwdArgs &a, int conv_k, hipStream_t s)
 #ifdef CAWN_DEV_PLAIN
     if constexpr (VALVE || RET || BF) return hipErrorInvalidValue; else
 #endif
-    if constexpr (PARAM && !VALVE && !RET && !BF) {
+    if constexpr (PARAM && !VALVE && !RET) {
         if (a.hconv) {
             switch (conv_k) {
 #ifdef CAWN_DEV_KC
-            case CAWN_DEV_KC: return launch_bwd_vkp<V, CAWN_DEV_KC, true, false, false, false, true>(a, s);
+            case CAWN_DEV_KC: return launch_bwd_vkp<V, CAWN_DEV_KC, true, false, false, BF, true>(a, s);
 #else
-            case 0: return launch_bwd_vkp<V, 0, true, false, false, false, true>(a, s);
-            case 1: return launch_bwd_vkp<V, 1, true, false, false, false, true>(a, s);
-            case 2: return launch_bwd_vkp<V, 2, true, false, false, false, true>(a, s);
-            case 3: return launch_bwd_vkp<V, 3, true, false, false, false, true>(a, s);
-            case 4: return launch_bwd_vkp<V, 4, true, false, false, false, true>(a, s);
+            case 0: return launch_bwd_vkp<V, 0, true, false, false, BF, true>(a, s);
+            case 1: return launch_bwd_vkp<V, 1, true, false, false, BF, true>(a, s);
+            case 2: return launch_bwd_vkp<V, 2, true, false, false, BF, true>(a, s);
+            case 3: return launch_bwd_vkp<V, 3, true, false, false, BF, true>(a, s);
+            case 4: return launch_bwd_vkp<V, 4, true, false, false, BF, true>(a, s);
 #endif
             default: return hipErrorInvalidValue;
             }
         }
     }
-    if (a.hconv) return hipErrorInvalidValue;       // the harmonic convolution: threshold mode, fp32, state rebuilt
+    if (a.hconv) return hipErrorInvalidValue;       // the harmonic convolution: threshold mode, state rebuilt
     switch (conv_k) {
 #ifdef CAWN_DEV_KC
     case CAWN_DEV_KC: return launch_bwd_vkp<V, CAWN_DEV_KC, PARAM, VALVE, RET, BF>(a, s);

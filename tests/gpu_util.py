@@ -334,32 +334,37 @@ def run_fwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, state_in=N
 
 
 def run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, out_clamp=100.0, grad_clamp=100.0,
-                      state_in=None, dstate_out=None, accumulate=0, preset=None, concat=False, want_hgrads=True):
+                      state_in=None, dstate_out=None, accumulate=0, preset=None, concat=False, want_hgrads=True,
+                      bf16=False):
     """Forward with the harmonic convolution (for the checkpoints and the convolved output), then its backward,
     through the C ABI.  inp holds hconv_w [2,H,3], hconv_b [2,H] and dc_re, dc_im [B,L,J] (gradients of the
     convolved output).  Returns numpy arrays: c_re, c_im, dmag, dang, dgamma, dtheta, dconv_w, dconv_b, dhconv_w,
-    dhconv_b, dstate_in (flat blob)."""
+    dhconv_b, dstate_in (flat blob).  bf16: mag, ang, dc_re, dc_im (bf16-exact fp32 arrays) go in as bfloat16, c_re,
+    c_im, dmag, dang come back widened from what the kernels stored."""
     J = H * F
     d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau, out_clamp=out_clamp,
                     grad_clamp=grad_clamp, accumulate_param_grads=accumulate, hconv_k=3)
-    mag, ang = dev(inp["mag"][:, :L]), dev(inp["ang"][:, :L])
+    up = dev_bf16 if bf16 else dev
+    adt = torch.bfloat16 if bf16 else torch.float32
+    mag, ang = up(inp["mag"][:, :L]), up(inp["ang"][:, :L])
     gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
     cw = dev(inp["conv_w"]) if conv_k > 0 else None
     cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
     hw, hb = dev(inp["hconv_w"]), dev(inp.get("hconv_b"))
     Lr = max(L, 1)
-    c_re, c_im = torch.empty((B, Lr, J), device=DEV), torch.empty((B, Lr, J), device=DEV)
-    dc_re, dc_im = dev(inp["dc_re"][:, :L]), dev(inp["dc_im"][:, :L])
+    c_re, c_im = torch.empty((B, Lr, J), device=DEV, dtype=adt), torch.empty((B, Lr, J), device=DEV, dtype=adt)
+    dc_re, dc_im = up(inp["dc_re"][:, :L]), up(inp["dc_im"][:, :L])
     nanv = lambda *shape: torch.full(shape, float("nan") if preset is None else preset, device=DEV)
-    dmag, dang = torch.full((B, Lr, J), float("nan"), device=DEV), torch.full((B, Lr, J), float("nan"), device=DEV)
+    dmag = torch.full((B, Lr, J), float("nan"), device=DEV, dtype=adt)
+    dang = torch.full((B, Lr, J), float("nan"), device=DEV, dtype=adt)
     if concat:      # rows of 2 J elements shared by each activation pair (Sec. 3.5)
         xin = torch.cat([mag, ang], dim=2).contiguous()
         mag, ang = xin[:, :, :J], xin[:, :, J:]
-        cc = torch.empty((B, Lr, 2 * J), device=DEV)
+        cc = torch.empty((B, Lr, 2 * J), device=DEV, dtype=adt)
         c_re, c_im = cc[:, :, :J], cc[:, :, J:]
         dcc = torch.cat([dc_re, dc_im], dim=2).contiguous()
         dc_re, dc_im = dcc[:, :, :J], dcc[:, :, J:]
-        dxc = torch.full((B, Lr, 2 * J), float("nan"), device=DEV)
+        dxc = torch.full((B, Lr, 2 * J), float("nan"), device=DEV, dtype=adt)
         dmag, dang = dxc[:, :, :J], dxc[:, :, J:]
         d.in_stride_t, d.in_stride_b = 2 * J, Lr * 2 * J
         d.out_stride_t, d.out_stride_b = 2 * J, Lr * 2 * J
@@ -367,7 +372,7 @@ def run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, out_c
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
     ws = Workspaces.get(d)
     K.check(K.cawn_phase_accumulate_hconv_fwd(d, mag, ang, None, None, None, gamma, theta, cw, cb, hw, hb, st_in, c_re, c_im,
-                                              None, ckpt, None, ws))
+                                              None, ckpt, None, ws, activations_bf16=1 if bf16 else 0))
     nstate = K.cawn_state_bytes(d) // 4
     dgamma, dtheta = nanv(J), nanv(J)
     dcw = nanv(2, J, conv_k) if conv_k > 0 else None
@@ -377,12 +382,13 @@ def run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, out_c
     dst_in = torch.full((nstate,), float("nan"), device=DEV)
     d.lane_consts_cached = 1
     K.check(K.cawn_phase_accumulate_hconv_bwd(d, mag, ang, gamma, theta, cw, cb, hw, hb, st_in, ckpt, dc_re, dc_im,
-                                              dev(dstate_out), dmag, dang, dgamma, dtheta, dcw, dcb, dhw, dhb, dst_in, ws))
+                                              dev(dstate_out), dmag, dang, dgamma, dtheta, dcw, dcb, dhw, dhb, dst_in, ws,
+                                              activations_bf16=1 if bf16 else 0))
     torch.cuda.synchronize()
     K.check(K.cawn_workspace_status(ws))
-    out = dict(c_re=c_re[:, :L].cpu().numpy(), c_im=c_im[:, :L].cpu().numpy(), dmag=dmag[:, :L].cpu().numpy(),
-               dang=dang[:, :L].cpu().numpy(), dgamma=dgamma.cpu().numpy(), dtheta=dtheta.cpu().numpy(),
-               dstate_in=dst_in.cpu().numpy())
+    host = (lambda t: host_bf16(t[:, :L].contiguous())) if bf16 else (lambda t: t[:, :L].cpu().numpy())
+    out = dict(c_re=host(c_re), c_im=host(c_im), dmag=host(dmag), dang=host(dang), dgamma=dgamma.cpu().numpy(),
+               dtheta=dtheta.cpu().numpy(), dstate_in=dst_in.cpu().numpy())
     for k, v in (("dconv_w", dcw), ("dconv_b", dcb), ("dhconv_w", dhw), ("dhconv_b", dhb)):
         if v is not None:
             out[k] = v.cpu().numpy()

@@ -126,6 +126,38 @@ def test_hconv_backward_concat_layout_and_accumulation():
         assert G.rel_err(acc[k] - 2.0, ora[k]) <= 2 * TOL, k
 
 
+@pytest.mark.parametrize("H,F", [(4, 64), (2, 32), (4, 16), (1, 128), (1, 256)])
+@pytest.mark.parametrize("Kc", [0, 3, 4])
+def test_hconv_backward_bf16(H, F, Kc):
+    """bfloat16 activations: inputs and the gradients of the convolved output are bf16-exact, what the kernels store
+    as bf16 (convolved output, input gradients) may differ from the oracle by 1e-4 and is then rounded; every other
+    gradient stays fp32 and keeps the plain bar."""
+    G = _gpu()
+    B, L = 2, 300
+    d = _inputs(B, L, H, F, Kc, 6700 + H * 131 + F + Kc)
+    for k in ("mag", "ang", "dc_re", "dc_im"):
+        d[k] = G.bf16_exact(d[k])
+    out = G.run_hconv_fwd_bwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.25, bf16=True)
+    ora = _oracle(B, L, H, F, Kc, d, tau=0.25)
+    for k in ("c_re", "c_im", "dmag", "dang"):
+        assert G.bf16_err(out[k], ora[k]) <= 1.0, k
+    _compare(out, ora, Kc, names=["dgamma", "dtheta", "dhconv_w", "dhconv_b"] + (["dconv_w", "dconv_b"] if Kc > 0 else []))
+
+
+def test_hconv_backward_bf16_ragged_and_concat():
+    G = _gpu()
+    B, L, H, F, Kc = 3, 257, 2, 64, 3
+    d = _inputs(B, L, H, F, Kc, 6800)
+    for k in ("mag", "ang", "dc_re", "dc_im"):
+        d[k] = G.bf16_exact(d[k])
+    ora = _oracle(B, L, H, F, Kc, d, tau=0.1)
+    for concat in (False, True):
+        out = G.run_hconv_fwd_bwd(d, B, L, H, F, conv_k=Kc, gate_tau=0.1, bf16=True, concat=concat)
+        for k in ("c_re", "c_im", "dmag", "dang"):
+            assert G.bf16_err(out[k], ora[k]) <= 1.0, (k, concat)
+        _compare(out, ora, Kc, names=["dgamma", "dtheta", "dhconv_w", "dhconv_b", "dconv_w", "dconv_b"])
+
+
 def test_hconv_backward_refusals():
     import torch
     from paper_2604_04250_amd import binding as K
