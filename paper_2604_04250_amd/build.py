@@ -10,11 +10,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libcawn.so")
-SOURCES = ["cawn_api.hip", "cawn_fwd.hip", "cawn_bwd.hip"]
+# (the scan kernels' families are translation units of their own: they compile side by side)
+SOURCES = ["cawn_fwd_plain.hip", "cawn_fwd_valve.hip", "cawn_fwd_ret.hip", "cawn_fwd_valve_ret.hip",
+           "cawn_api.hip", "cawn_fwd.hip", "cawn_bwd.hip", "cawn_bwd_plain.hip", "cawn_bwd_valve.hip",
+           "cawn_bwd_ret.hip", "cawn_bwd_hconv.hip", "cawn_bwd_hconv_valve.hip", "cawn_bwd_hconv_ret.hip"]
 # The backward kernel is a persistent loop whose body fills its register budget (4 waves per SIMD).
 # Hoisting loop-invariant copies of uniform values and addresses out of that loop costs ~10 VGPRs
 # and a wave of occupancy; they are a few ALU ops per tile when left inside.
-FILE_FLAGS = {"cawn_bwd.hip": ["-mllvm", "-disable-machine-licm"]}
+BWD_FLAGS = ["-mllvm", "-disable-machine-licm"]
+FILE_FLAGS = {src: BWD_FLAGS for src in SOURCES if src.startswith("cawn_bwd_")}
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-ffp-contract=off", "-Wall", "-Wno-unused-function",
@@ -61,7 +65,7 @@ def build(verbose: bool = False, defines=(), out: str = OUT, objdir: str = CSRC)
                 f.write(line.split("remark: ", 1)[-1].replace(" [-Rpass-analysis=kernel-resource-usage]", "").strip() + "\n")
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 4)) as ex:
         objs = list(ex.map(cc, SOURCES))
     cmd = [hipcc, "-shared", "--offload-arch=gfx950", "-fno-gpu-rdc", "-o", out, *objs]
     if verbose:
