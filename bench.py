@@ -241,7 +241,8 @@ def lane_sample_parity(np, G, O, wl, inp, got, mode, Kc, amp_mode=0, valve=None,
         if hconv is not None:   # the upstream gradients are those of the convolved planes
             gh = O.harmonic_conv_bwd(of["z_re"], of["z_im"], 1, F, hw0, up_re, up_im)
             up_re, up_im = gh["dz_re"], gh["dz_im"]
-            bcfg = O.Cfg(B, L, 1, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=wl.gate_tau, dz_f64=1, nthreads=O.max_threads())
+            bcfg = O.Cfg(B, L, 1, F, conv_k=Kc, amp_mode=amp_mode, gate_tau=wl.gate_tau, gate_mode=0 if valve is None else 1,
+                         valve_eps=valve_eps, ret_mode=0 if ret is None else 1, dz_f64=1, nthreads=O.max_threads())
             err["dhconv_w"] = G.rel_err(got["dhconv_w"][:, :1].cpu().numpy(), gh["dw"])
             err["dhconv_b"] = G.rel_err(got["dhconv_b"][:, :1].cpu().numpy(), gh["dbias"])
         ob = O.phase_bwd(bcfg, sub(inp["mag"]), sub(inp["ang"]), gam, inp["theta"][sl], up_re, up_im, **kw)
@@ -276,7 +277,7 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
     theta = K.cawn_theta_init(H, F)
     # (the backward through the harmonic convolution exists for the threshold gate with constant retention: with the
     # valve or data-dependent retention a training workload runs and times its forward pass alone)
-    do_bwd = name in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads") and not (hconv and (valve_on or ret_on))
+    do_bwd = name in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads")
     stream_mode = name == "cfg4_stream"
     L = wl.chunk if stream_mode else wl.L
     valve_eps = 0.001
@@ -402,9 +403,10 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
             rec[1].record()
         if do_bwd:
             if hconv:
-                st |= K.cawn_phase_accumulate_hconv_bwd(d, s["mag"], s["ang"], gamma, th, cw, cb, hw, hb, None, ckpt,
-                                                        s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"], dgamma, dtheta,
-                                                        dcw, dcb, dhw, dhb, None, ws, activations_bf16=1 if bf16 else 0)
+                st |= K.cawn_phase_accumulate_hconv_bwd(d, s["mag"], s["ang"], valve, ret, ret_bias, gamma, th, cw, cb, hw,
+                                                        hb, None, ckpt, s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"],
+                                                        dvalve, dret, None if ret is not None else dgamma, dtheta, dcw, dcb,
+                                                        dhw, dhb, None, ws, activations_bf16=1 if bf16 else 0)
             elif bf16:
                 st |= K.cawn_phase_accumulate_bf16_bwd(d, s["mag"], s["ang"], valve, ret, ret_bias, gamma, th, cw, cb,
                                                        None, ckpt, s["dz_re"], s["dz_im"], None, s["dmag"], s["dang"],
@@ -540,7 +542,7 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         out["gate_closed_fraction"] = float(1.0 - bits.mean())
 
     # ---- parity of the timed configuration itself on sampled lanes (head 0: lanes are independent)
-    if not (bf16 or unfused or (hconv and (valve_on or ret_on))):
+    if not (bf16 or unfused):
         from oracle import cawn_oracle as O
         import gpu_util as G
         if stream_mode:                  # the first chunk of a stream: zero state in, state carried out in place
@@ -619,7 +621,7 @@ def main():
     if args.workload == "decode":
         return decode_bench(args, np, torch, K, WL, dev)
     if args.paper:
-        assert args.workload == "cfg3_train" and not (args.bf16 or args.hconv or args.unfused), "--paper stands alone"
+        assert args.workload == "cfg3_train" and not (args.bf16 or args.unfused), "--paper: alone or with --hconv"
     ceiling = CopyCeiling(np, torch, K, dev)
     out = run_workload(args, args.workload, np, torch, K, WL, dev, ceiling, args.steps, args.warmup, True)
     plain_default = args.workload == "cfg3_train" and not (args.valve or args.ret or args.bf16 or args.hconv or

@@ -302,21 +302,27 @@ int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const v
  *   dhconv_b [2][H]:     d b_p[h]    = sum over b, t, k of dc_p[k]
  * where z is the clamped state of the forward (rebuilt from ckpt, never read from memory; the output
  * clamp passes the gradient).  Neither is clamped by grad_clamp; both follow accumulate_param_grads and
- * may be NULL.  Threshold gate and constant retention only: gate_mode 0, ret_mode 0 (CAWN_EUNSUPPORTED
- * otherwise); d->hconv_k must be 3, head widths as in the forward; ckpt is required.
+ * may be NULL.  d->hconv_k must be 3, head widths as in the forward; ckpt is required.
+ * d->gate_mode and d->ret_mode select the variant as in the forward: valve is read and dvalve written when
+ * gate_mode == 1; ret, ret_bias are read and dret written when ret_mode == 1 (gamma is then ignored and dgamma
+ * must be NULL), gamma otherwise; unused ones may be NULL.  Those variants are the backward of
+ * cawn_phase_accumulate_valve_bwd / _ret_bwd behind the same transposed convolution; with fp32 activations they
+ * stage the gradients in so much LDS that one workgroup runs per compute unit.
  *   activations_bf16  0: mag, ang, dc_re, dc_im, dmag, dang are fp32;  1: bfloat16 with the rules of
  *                     cawn_phase_accumulate_bf16_bwd (every other gradient stays fp32)
  * dc_re, dc_im use the out strides.  The lane constants that d->lane_consts_cached keeps include hconv_w
  * and hconv_b.  Everything else (arguments, layouts, ownership, errors) as in cawn_phase_accumulate_bwd.
  */
 int cawn_phase_accumulate_hconv_bwd(const cawn_desc *d, const void *mag, const void *ang,
+                                    const float *valve, const float *ret, const float *ret_bias,
                                     const float *gamma, const float *theta, const float *conv_w,
                                     const float *conv_b, const float *hconv_w, const float *hconv_b,
                                     const void *state_in, const void *ckpt, const void *dc_re,
                                     const void *dc_im, const void *dstate_out, void *dmag, void *dang,
-                                    float *dgamma, float *dtheta, float *dconv_w, float *dconv_b,
-                                    float *dhconv_w, float *dhconv_b, void *dstate_in, void *workspace,
-                                    size_t workspace_bytes, int32_t activations_bf16, void *stream);
+                                    float *dvalve, float *dret, float *dgamma, float *dtheta,
+                                    float *dconv_w, float *dconv_b, float *dhconv_w, float *dhconv_b,
+                                    void *dstate_in, void *workspace, size_t workspace_bytes,
+                                    int32_t activations_bf16, void *stream);
 
 /*
  * Backward of cawn_phase_accumulate_bf16_fwd: mag, ang, dz_re, dz_im are read and dmag, dang are

@@ -90,7 +90,7 @@ def lib() -> C.CDLL:
                                                      [C.c_size_t, C.c_void_p])
         L.cawn_phase_accumulate_hconv_fwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 18 +
                                                       [C.c_size_t, C.c_int32, C.c_void_p])
-        L.cawn_phase_accumulate_hconv_bwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 23 +
+        L.cawn_phase_accumulate_hconv_bwd.argtypes = ([C.POINTER(cawn_desc)] + [C.c_void_p] * 28 +
                                                       [C.c_size_t, C.c_int32, C.c_void_p])
         L.cawn_stream_copy.argtypes = [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
         L.cawn_phase_accumulate_fwd_static.argtypes = [C.POINTER(cawn_desc)] + [C.c_void_p] * 13
@@ -244,15 +244,17 @@ def cawn_phase_accumulate_hconv_fwd(d, mag, ang, valve, ret, ret_bias, gamma, th
         C.c_int32(activations_bf16), _stream(stream))
 
 
-def cawn_phase_accumulate_hconv_bwd(d, mag, ang, gamma, theta, conv_w, conv_b, hconv_w, hconv_b, state_in, ckpt, dc_re,
-                                    dc_im, dstate_out, dmag, dang, dgamma, dtheta, dconv_w, dconv_b, dhconv_w,
-                                    dhconv_b, dstate_in, workspace, activations_bf16=0, stream=None) -> int:
+def cawn_phase_accumulate_hconv_bwd(d, mag, ang, valve, ret, ret_bias, gamma, theta, conv_w, conv_b, hconv_w, hconv_b,
+                                    state_in, ckpt, dc_re, dc_im, dstate_out, dmag, dang, dvalve, dret, dgamma, dtheta,
+                                    dconv_w, dconv_b, dhconv_w, dhconv_b, dstate_in, workspace, activations_bf16=0,
+                                    stream=None) -> int:
     """dc_re, dc_im: gradients of the convolved output; dhconv_w [2,H,3], dhconv_b [2,H] beside the usual gradients.
     mag, ang, dc_re, dc_im, dmag, dang: fp32 tensors, or torch.bfloat16 with activations_bf16=1."""
     return lib().cawn_phase_accumulate_hconv_bwd(
-        C.byref(d), _ptr(mag), _ptr(ang), _ptr(gamma), _ptr(theta), _ptr(conv_w), _ptr(conv_b), _ptr(hconv_w),
-        _ptr(hconv_b), _ptr(state_in), _ptr(ckpt), _ptr(dc_re), _ptr(dc_im), _ptr(dstate_out), _ptr(dmag), _ptr(dang),
-        _ptr(dgamma), _ptr(dtheta), _ptr(dconv_w), _ptr(dconv_b), _ptr(dhconv_w), _ptr(dhconv_b), _ptr(dstate_in),
+        C.byref(d), _ptr(mag), _ptr(ang), _ptr(valve), _ptr(ret), _ptr(ret_bias), _ptr(gamma), _ptr(theta), _ptr(conv_w),
+        _ptr(conv_b), _ptr(hconv_w), _ptr(hconv_b), _ptr(state_in), _ptr(ckpt), _ptr(dc_re), _ptr(dc_im), _ptr(dstate_out),
+        _ptr(dmag), _ptr(dang), _ptr(dvalve), _ptr(dret), _ptr(dgamma), _ptr(dtheta), _ptr(dconv_w), _ptr(dconv_b),
+        _ptr(dhconv_w), _ptr(dhconv_b), _ptr(dstate_in),
         _ptr(workspace), workspace.numel() * workspace.element_size() if workspace is not None else 0,
         C.c_int32(activations_bf16), _stream(stream))
 

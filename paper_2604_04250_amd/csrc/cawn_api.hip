@@ -615,8 +615,8 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     // gradients of the convolved output: the harmonic convolution's own entry point only
     const bool hc = d->hconv_k != 0;
     if (hc != (hconv_w != nullptr)) return CAWN_EINVAL;
-    if (hc && (d->gate_mode != 0 || d->ret_mode != 0)) return CAWN_EUNSUPPORTED;
     if (hc && !(d->F <= 32 ? 32 % d->F == 0 : (d->F % 32 == 0 && 256 % d->F == 0))) return CAWN_EUNSUPPORTED;   // as in the forward
+    if (hc && (d->gate_mode == 1 || d->ret_mode == 1) && d->F < 32) return CAWN_EUNSUPPORTED;                   // as in the forward
     if ((d->gate_mode == 1 || d->ret_mode == 1) && !valve_shape_ok(d)) return CAWN_EUNSUPPORTED;
     if (d->gate_mode == 1 && d->ret_mode == 1 && d->F < 16) return CAWN_EUNSUPPORTED;   // as in the forward
     hipStream_t s = (hipStream_t)stream;
@@ -817,21 +817,25 @@ int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const v
                     gate_mask, workspace, workspace_bytes, stream, activations_bf16 != 0, hconv_w, hconv_b);
 }
 
-int cawn_phase_accumulate_hconv_bwd(const cawn_desc *d, const void *mag, const void *ang, const float *gamma,
-                                    const float *theta, const float *conv_w, const float *conv_b,
-                                    const float *hconv_w, const float *hconv_b, const void *state_in, const void *ckpt,
-                                    const void *dc_re, const void *dc_im, const void *dstate_out, void *dmag,
-                                    void *dang, float *dgamma, float *dtheta, float *dconv_w, float *dconv_b,
-                                    float *dhconv_w, float *dhconv_b, void *dstate_in, void *workspace,
-                                    size_t workspace_bytes, int32_t activations_bf16, void *stream)
+int cawn_phase_accumulate_hconv_bwd(const cawn_desc *d, const void *mag, const void *ang, const float *valve,
+                                    const float *ret, const float *ret_bias, const float *gamma, const float *theta,
+                                    const float *conv_w, const float *conv_b, const float *hconv_w, const float *hconv_b,
+                                    const void *state_in, const void *ckpt, const void *dc_re, const void *dc_im,
+                                    const void *dstate_out, void *dmag, void *dang, float *dvalve, float *dret,
+                                    float *dgamma, float *dtheta, float *dconv_w, float *dconv_b, float *dhconv_w,
+                                    float *dhconv_b, void *dstate_in, void *workspace, size_t workspace_bytes,
+                                    int32_t activations_bf16, void *stream)
 {
     if (!desc_ok(d)) return CAWN_EINVAL;
     if (d->hconv_k != 3 || !hconv_w) return CAWN_EINVAL;
-    return bwd_impl(d, reinterpret_cast<const float *>(mag), reinterpret_cast<const float *>(ang), nullptr, nullptr, nullptr,
-                    gamma, theta, conv_w, conv_b, state_in, ckpt, reinterpret_cast<const float *>(dc_re),
+    const bool valved = d->gate_mode == 1, rmode = d->ret_mode == 1;
+    return bwd_impl(d, reinterpret_cast<const float *>(mag), reinterpret_cast<const float *>(ang),
+                    valved ? valve : nullptr, rmode ? ret : nullptr, rmode ? ret_bias : nullptr, rmode ? nullptr : gamma,
+                    theta, conv_w, conv_b, state_in, ckpt, reinterpret_cast<const float *>(dc_re),
                     reinterpret_cast<const float *>(dc_im), dstate_out, reinterpret_cast<float *>(dmag),
-                    reinterpret_cast<float *>(dang), nullptr, nullptr, dgamma, dtheta, dconv_w, dconv_b, dstate_in, workspace,
-                    workspace_bytes, stream, activations_bf16 != 0, hconv_w, hconv_b, dhconv_w, dhconv_b);
+                    reinterpret_cast<float *>(dang), valved ? dvalve : nullptr, rmode ? dret : nullptr, dgamma, dtheta,
+                    dconv_w, dconv_b, dstate_in, workspace, workspace_bytes, stream, activations_bf16 != 0, hconv_w,
+                    hconv_b, dhconv_w, dhconv_b);
 }
 
 int cawn_phase_accumulate_bf16_bwd(const cawn_desc *d, const uint16_t *mag, const uint16_t *ang, const float *valve,

@@ -335,19 +335,24 @@ def run_fwd_bf16(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, state_in=N
 
 def run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, out_clamp=100.0, grad_clamp=100.0,
                       state_in=None, dstate_out=None, accumulate=0, preset=None, concat=False, want_hgrads=True,
-                      bf16=False):
+                      bf16=False, valve=None, ret=None, ret_bias=None, valve_eps=0.001):
     """Forward with the harmonic convolution (for the checkpoints and the convolved output), then its backward,
     through the C ABI.  inp holds hconv_w [2,H,3], hconv_b [2,H] and dc_re, dc_im [B,L,J] (gradients of the
     convolved output).  Returns numpy arrays: c_re, c_im, dmag, dang, dgamma, dtheta, dconv_w, dconv_b, dhconv_w,
     dhconv_b, dstate_in (flat blob).  bf16: mag, ang, dc_re, dc_im (bf16-exact fp32 arrays) go in as bfloat16, c_re,
-    c_im, dmag, dang come back widened from what the kernels stored."""
+    c_im, dmag, dang come back widened from what the kernels stored.  valve [B,L,H] selects gate_mode 1 (dvalve
+    comes back), ret [B,L,H] with ret_bias [H,F] ret_mode 1 (dret comes back, no dgamma)."""
     J = H * F
     d = K.make_desc(B, L, H, F, conv_k=conv_k, amp_mode=amp_mode, gate_tau=gate_tau, out_clamp=out_clamp,
-                    grad_clamp=grad_clamp, accumulate_param_grads=accumulate, hconv_k=3)
+                    grad_clamp=grad_clamp, accumulate_param_grads=accumulate, hconv_k=3,
+                    gate_mode=0 if valve is None else 1, valve_eps=valve_eps, ret_mode=0 if ret is None else 1)
+    vl = None if valve is None else dev(np.ascontiguousarray(valve[:, :L]))
+    rt = None if ret is None else dev(np.ascontiguousarray(ret[:, :L]))
+    rb = dev(ret_bias)
     up = dev_bf16 if bf16 else dev
     adt = torch.bfloat16 if bf16 else torch.float32
     mag, ang = up(inp["mag"][:, :L]), up(inp["ang"][:, :L])
-    gamma, theta = dev(inp["gamma"]), dev(inp["theta"])
+    gamma, theta = dev(inp.get("gamma")), dev(inp["theta"])
     cw = dev(inp["conv_w"]) if conv_k > 0 else None
     cb = dev(inp["conv_b"]) if conv_k > 0 and inp.get("conv_b") is not None else None
     hw, hb = dev(inp["hconv_w"]), dev(inp.get("hconv_b"))
@@ -371,27 +376,32 @@ def run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=0, amp_mode=0, gate_tau=0.0, out_c
     st_in = dev(state_in)
     ckpt = torch.full((max(K.cawn_ckpt_bytes(d) // 4, 1),), float("nan"), device=DEV)
     ws = Workspaces.get(d)
-    K.check(K.cawn_phase_accumulate_hconv_fwd(d, mag, ang, None, None, None, gamma, theta, cw, cb, hw, hb, st_in, c_re, c_im,
+    K.check(K.cawn_phase_accumulate_hconv_fwd(d, mag, ang, vl, rt, rb, gamma, theta, cw, cb, hw, hb, st_in, c_re, c_im,
                                               None, ckpt, None, ws, activations_bf16=1 if bf16 else 0))
     nstate = K.cawn_state_bytes(d) // 4
-    dgamma, dtheta = nanv(J), nanv(J)
+    dgamma, dtheta = (nanv(J) if ret is None else None), nanv(J)
+    dvl = None if valve is None else torch.full((B, Lr, H), float("nan"), device=DEV)
+    drt = None if ret is None else torch.full((B, Lr, H), float("nan"), device=DEV)
     dcw = nanv(2, J, conv_k) if conv_k > 0 else None
     dcb = nanv(2, J) if conv_k > 0 else None
     dhw = nanv(2, H, 3) if want_hgrads else None
     dhb = nanv(2, H) if want_hgrads else None
     dst_in = torch.full((nstate,), float("nan"), device=DEV)
     d.lane_consts_cached = 1
-    K.check(K.cawn_phase_accumulate_hconv_bwd(d, mag, ang, gamma, theta, cw, cb, hw, hb, st_in, ckpt, dc_re, dc_im,
-                                              dev(dstate_out), dmag, dang, dgamma, dtheta, dcw, dcb, dhw, dhb, dst_in, ws,
-                                              activations_bf16=1 if bf16 else 0))
+    K.check(K.cawn_phase_accumulate_hconv_bwd(d, mag, ang, vl, rt, rb, gamma, theta, cw, cb, hw, hb, st_in, ckpt, dc_re,
+                                              dc_im, dev(dstate_out), dmag, dang, dvl, drt, dgamma, dtheta, dcw, dcb, dhw,
+                                              dhb, dst_in, ws, activations_bf16=1 if bf16 else 0))
     torch.cuda.synchronize()
     K.check(K.cawn_workspace_status(ws))
     host = (lambda t: host_bf16(t[:, :L].contiguous())) if bf16 else (lambda t: t[:, :L].cpu().numpy())
-    out = dict(c_re=host(c_re), c_im=host(c_im), dmag=host(dmag), dang=host(dang), dgamma=dgamma.cpu().numpy(),
+    out = dict(c_re=host(c_re), c_im=host(c_im), dmag=host(dmag), dang=host(dang),
                dtheta=dtheta.cpu().numpy(), dstate_in=dst_in.cpu().numpy())
-    for k, v in (("dconv_w", dcw), ("dconv_b", dcb), ("dhconv_w", dhw), ("dhconv_b", dhb)):
+    for k, v in (("dgamma", dgamma), ("dconv_w", dcw), ("dconv_b", dcb), ("dhconv_w", dhw), ("dhconv_b", dhb)):
         if v is not None:
             out[k] = v.cpu().numpy()
+    for k, v in (("dvalve", dvl), ("dret", drt)):
+        if v is not None:
+            out[k] = v[:, :L].cpu().numpy()
     return out
 
 

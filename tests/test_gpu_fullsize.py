@@ -377,3 +377,46 @@ def test_training_step_through_the_harmonic_conv_full_size():
             "dhconv_b": G.rel_err(out["dhconv_b"][:, heads], gh["dbias"])}
     bad = {k: v for k, v in errs.items() if not v <= TOL}
     assert not bad, (bad, errs)
+
+
+def test_paper_layer_through_the_harmonic_conv_full_size():
+    """bench.py --paper --hconv: the layer as the paper states it (B=8, L=8192, 4 heads of 64 harmonics, conv kernel 3,
+    softplus amplitude, per-head valve, data-dependent retention: Sec. 3.2-3.4, Sec. 4.3) ending in the depth-wise
+    harmonic convolution of Sec. 3.6, forward and backward; heads 0 and 3 against the oracle's composed step."""
+    import gpu_util as G
+    from paper_2604_04250_amd import binding as K
+    wl = WL.CONFIGS["cfg6_paper_heads"].with_(name="paper_layer", conv_k=3)
+    B, L, H, F, J, Kc = wl.B, wl.L, wl.H, wl.F, wl.J, wl.conv_k
+    theta = K.cawn_theta_init(H, F)
+    inp = WL.make_inputs(wl, theta=theta, with_grads=True)
+    valve, ret, ret_bias = _paper_inputs(wl)
+    rh = np.random.Generator(np.random.PCG64(4250 + 98))
+    inp["hconv_w"] = (rh.standard_normal((2, H, 3)) / np.sqrt(3.0)).astype(np.float32)
+    inp["hconv_b"] = (0.1 * rh.standard_normal((2, H))).astype(np.float32)
+    inp["dc_re"], inp["dc_im"] = inp["dz_re"], inp["dz_im"]
+    out = G.run_hconv_fwd_bwd(inp, B, L, H, F, conv_k=Kc, amp_mode=1, valve=valve, valve_eps=0.001, ret=ret,
+                              ret_bias=ret_bias)
+    heads = [0, 3]
+    lanes = np.concatenate([np.arange(h * F, (h + 1) * F) for h in heads])
+    sub = _sub(inp, lanes)
+    n = len(heads)
+    hw, hb = np.ascontiguousarray(inp["hconv_w"][:, heads]), np.ascontiguousarray(inp["hconv_b"][:, heads])
+    kw = dict(conv_k=Kc, amp_mode=1, gate_mode=1, valve_eps=0.001, ret_mode=1, nthreads=O.max_threads())
+    streams = dict(conv_w=sub["conv_w"], conv_b=sub["conv_b"], valve=np.ascontiguousarray(valve[:, :, heads]),
+                   ret=np.ascontiguousarray(ret[:, :, heads]), ret_bias=ret_bias)
+    f = O.phase_fwd(O.Cfg(B, L, n, F, **kw), sub["mag"], sub["ang"], None, sub["theta"], want_gate=False, **streams)
+    c = O.harmonic_conv(f["z_re"], f["z_im"], n, F, hw, hb)
+    gh = O.harmonic_conv_bwd(f["z_re"], f["z_im"], n, F, hw, sub["dz_re"], sub["dz_im"])
+    g = O.phase_bwd(O.Cfg(B, L, n, F, dz_f64=1, **kw), sub["mag"], sub["ang"], None, sub["theta"], gh["dz_re"], gh["dz_im"],
+                    **streams)
+    errs = {"c_re": G.rel_err(out["c_re"][..., lanes], c[0]), "c_im": G.rel_err(out["c_im"][..., lanes], c[1]),
+            "dmag": G.rel_err(out["dmag"][..., lanes], g["dmag"]), "dang": G.rel_err(out["dang"][..., lanes], g["dang"]),
+            "dtheta": G.rel_err(out["dtheta"][lanes], g["dtheta"]),
+            "dconv_w": G.rel_err(out["dconv_w"][:, lanes], g["dconv_w"]),
+            "dconv_b": G.rel_err(out["dconv_b"][:, lanes], g["dconv_b"]),
+            "dvalve": G.rel_err(out["dvalve"][:, :, heads], g["dvalve"]),
+            "dret": G.rel_err(out["dret"][:, :, heads], g["dret"]),
+            "dhconv_w": G.rel_err(out["dhconv_w"][:, heads], gh["dw"]),
+            "dhconv_b": G.rel_err(out["dhconv_b"][:, heads], gh["dbias"])}
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, (bad, errs)
