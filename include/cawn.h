@@ -306,8 +306,7 @@ int cawn_phase_accumulate_hconv_fwd(const cawn_desc *d, const void *mag, const v
  * d->gate_mode and d->ret_mode select the variant as in the forward: valve is read and dvalve written when
  * gate_mode == 1; ret, ret_bias are read and dret written when ret_mode == 1 (gamma is then ignored and dgamma
  * must be NULL), gamma otherwise; unused ones may be NULL.  Those variants are the backward of
- * cawn_phase_accumulate_valve_bwd / _ret_bwd behind the same transposed convolution; with fp32 activations they
- * stage the gradients in so much LDS that one workgroup runs per compute unit.
+ * cawn_phase_accumulate_valve_bwd / _ret_bwd behind the same transposed convolution.
  *   activations_bf16  0: mag, ang, dc_re, dc_im, dmag, dang are fp32;  1: bfloat16 with the rules of
  *                     cawn_phase_accumulate_bf16_bwd (every other gradient stays fp32)
  * dc_re, dc_im use the out strides.  The lane constants that d->lane_consts_cached keeps include hconv_w

@@ -164,8 +164,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // SDZ: the upstream gradients pass through LDS at all.  The valve and retention kernels load them into
     // registers, except behind the harmonic convolution: its transposed form and its tap gradients read three
     // neighbouring lanes of every gradient, twice in a tile, so there the tile's gradients are staged too -- at
-    // the top of the tile itself, not a tile ahead.  Those kernels then hold more LDS than half a compute
-    // unit's: one workgroup per compute unit.
+    // the top of the tile itself, not a tile ahead (see OVL below for where the 32 KB come from).
     constexpr bool SDZ = PF || HC;
     constexpr int NRZ = staged_rows<TILE_T, JBS, 0>();                // staged rows per gradient stream
     __shared__ __attribute__((aligned(16))) float sDz[SDZ ? 2 * NRZ : 1][JBS];    // [stream*NRZ + token][lane]
@@ -177,23 +176,35 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // HC: the gradients of the two lanes beside the lane block, [plane][side: lane -1, lane JB][token]
     __shared__ float sEdge[HC ? 4 * NRZ : 1];
     constexpr int N_EB = NSEG * 2 * JB, N_HALO = NW * HALO1 * 2 * JB;
-    __shared__ float sPool[PF ? (N_EB > N_HALO ? N_EB : N_HALO) : N_EB + N_HALO];
+    // OVL: the valve and retention kernels behind the harmonic convolution (fp32 rows) stage a tile's gradients at
+    // its top and read them for the last time in the tap pass, in the middle of the tile: what is written only
+    // after the barrier that follows that pass -- the conv-gradient halo rows, the valve's and the retention
+    // logits' gradient terms, the partial-sum staging -- lies over them.  With that the kernel fits twice on a
+    // compute unit.
+    constexpr bool OVL = HC && !PF && !BF;
+    constexpr int N_RED = NW * ROWS * JB, N_VT = BwdGeom::TILE_T * 4;
+    static_assert(!OVL || N_RED + N_HALO + 2 * N_VT <= 2 * NRZ * JBS, "what lies over the staged gradients fits there");
+    __shared__ float sPool[PF ? (N_EB > N_HALO ? N_EB : N_HALO) : (OVL ? N_EB : N_EB + N_HALO)];
     float (*sEb)[2][JB] = reinterpret_cast<float (*)[2][JB]>(&sPool[0]);
-    float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(&sPool[PF ? 0 : N_EB]);   // [NW]: first rows of each wave's earlier segment
+    float (*sHalo)[HALO1][2][JB] = reinterpret_cast<float (*)[HALO1][2][JB]>(OVL ? &sDz[0][0] + N_RED : &sPool[PF ? 0 : N_EB]);   // [NW]: first rows of each wave's earlier segment
     __shared__ float sCarry[2][JB];
     // (bf16 rows are half as large and the harmonic convolution adds 8 partial rows: that combination has LDS to
     // spare and keeps the staging in an array of its own)
     constexpr bool RED_OVER_ROWS = PF && !(BF && HC);
-    __shared__ float sRedOwn[(PARAM && !RED_OVER_ROWS) ? NW : 1][ROWS][JB];
+    __shared__ float sRedOwn[(PARAM && !RED_OVER_ROWS && !OVL) ? NW : 1][ROWS][JB];
     static_assert(!RED_OVER_ROWS || (size_t)NW * ROWS * JB <= (size_t)2 * NRTP * JBS, "the partial-sum staging fits over the input rows");
-    float (*sRed)[ROWS][JB] = RED_OVER_ROWS ? reinterpret_cast<float (*)[ROWS][JB]>(&sU[0][0]) : sRedOwn;
+    float (*sRed)[ROWS][JB] = RED_OVER_ROWS ? reinterpret_cast<float (*)[ROWS][JB]>(&sU[0][0])
+                                            : (OVL ? reinterpret_cast<float (*)[ROWS][JB]>(&sDz[0][0]) : sRedOwn);
     constexpr int GPB_MAX = 4;                    // valve groups per lane block (F >= 8)
+    static_assert(N_VT == BwdGeom::TILE_T * GPB_MAX, "");
     __shared__ float sV[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];      // valve logits, [group][token]
-    __shared__ float sVp[VALVE ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
+    __shared__ float sVpOwn[VALVE && !OVL ? BwdGeom::TILE_T * GPB_MAX : 1];     // valve gradient terms summed over a group's lanes
+    float *sVp = OVL ? &sDz[0][0] + N_RED + N_HALO : sVpOwn;
     __shared__ float sTaps[LEAN ? 2 * KC1 : 1][JB];                 // conv taps of the lane block (valve kernels)
     __shared__ float sPb[RET ? NSEG : 1][JB];                        // product of each wave's retentions
     __shared__ float sPt[RET ? 1 : 1][JB];                           // product of the tile's retentions (head group)
-    __shared__ float sRp[RET ? BwdGeom::TILE_T * GPB_MAX : 1];       // retention-logit gradient terms per (group, token)
+    __shared__ float sRpOwn[RET && !OVL ? BwdGeom::TILE_T * GPB_MAX : 1];       // retention-logit gradient terms per (group, token)
+    float *sRp = OVL ? &sDz[0][0] + N_RED + N_HALO + N_VT : sRpOwn;
     __shared__ uint32_t sTicket[2], sLast, sEpoch;     // tickets of this tile and the next one
 
     const int tid_ = threadIdx.x;
