@@ -63,8 +63,8 @@ def parse():
     ap.add_argument("--hconv", action="store_true",
                     help="the depth-wise harmonic convolution of Sec. 3.6 fused behind the output clamp: the forward "
                          "stores the convolved output, the backward takes its gradients and returns the taps' and "
-                         "biases' gradients as well (same bytes per token-lane; threshold gate, fp32 or --bf16; with "
-                         "--valve or --ret the forward pass alone; extra line, not the headline; no CPU baseline)")
+                         "biases' gradients as well (same bytes per token-lane; fp32 or --bf16, alone or with --valve, --ret "
+                         "or --paper; extra line, not the headline; no CPU baseline)")
     ap.add_argument("--unfused", action="store_true",
                     help="cfg2_layer_fwd only: the Temporal Syntax Cache as separate calls (cawn_syntax_conv on each "
                          "stream, then the scan without conv front-end): 32 instead of 16 bytes per token-lane; "
