@@ -724,6 +724,71 @@ def test_training_step_through_the_harmonic_conv_against_finite_differences():
     assert gh["dw"][1, 0, 2] == pytest.approx((loss(d, hw_=hp) - loss(d, hw_=hm)) / 0.25, rel=1e-11)
 
 
+def test_paper_layer_through_the_harmonic_conv_against_finite_differences():
+    """Everything at once: conv kernel 3, softplus amplitude, per-head valve (eps = 0: the straight-through
+    gradient is then the exact derivative), data-dependent retention (Sec. 3.2-3.4), the carried state, and the
+    harmonic convolution of Sec. 3.6 behind it; loss = <up, C> + <dstate, state>.  Backward = harmonic_conv_bwd, then
+    phase_bwd in the same modes on its fp64 dZ.  Central differences through the composed forward, on every input,
+    parameter, logit and state."""
+    B, L, H, F, Kc = 2, 7, 2, 4, 3
+    J = H * F
+    d = small(980, B, L, H, F, Kc)
+    q = lambda a: (np.round(np.asarray(a, np.float64) * 1024) / 1024).astype(np.float32)
+    for k in d:
+        d[k] = q(d[k])
+    r = rng_(981)
+    valve = q(3.0 + 2.0 * r.standard_normal((B, L, H)))
+    ret = q(0.5 + 1.5 * r.standard_normal((B, L, H)))
+    bias = np.linspace(3.0, 0.0, F).astype(np.float32)
+    scan_in = np.round(r.standard_normal((B, 2, J)) * 1024) / 1024
+    tail_in = q(r.standard_normal((B, Kc - 1, 2, J)))
+    hw = q(r.standard_normal((2, H, 3)))
+    hb = q(r.standard_normal((2, H)))
+    up = r.standard_normal((2, B, L, J))
+    dscan_out, dtail_out = r.standard_normal((B, 2, J)), r.standard_normal((B, Kc - 1, 2, J))
+    kw = dict(conv_k=Kc, amp_mode=1, gate_mode=1, valve_eps=0.0, ret_mode=1, conv_clamp=INF, out_clamp=INF, grad_clamp=INF)
+    cfg = O.Cfg(B, L, H, F, **kw)
+    arrs = dict(mag=d["mag"], ang=d["ang"], theta=d["theta"], conv_w=d["conv_w"], conv_b=d["conv_b"], valve=valve,
+                ret=ret, scan_in=scan_in, tail_in=tail_in, hconv_w=hw)
+
+    def fwd(a):
+        return O.phase_fwd(cfg, a["mag"], a["ang"], None, a["theta"], conv_w=a["conv_w"], conv_b=a["conv_b"],
+                           scan_in=a["scan_in"], tail_in=a["tail_in"], valve=a["valve"], ret=a["ret"], ret_bias=bias,
+                           want_gate=False)
+
+    def loss(a):
+        f = fwd(a)
+        c = O.harmonic_conv(f["z_re"], f["z_im"], H, F, a["hconv_w"], hb)
+        return float((c[0] * up[0]).sum() + (c[1] * up[1]).sum() + (dscan_out * f["scan_out"]).sum()
+                     + (dtail_out * f["tail_out"]).sum())
+
+    f = fwd(arrs)
+    gh = O.harmonic_conv_bwd(f["z_re"], f["z_im"], H, F, hw, up[0], up[1])
+    g = O.phase_bwd(O.Cfg(B, L, H, F, dz_f64=1, **kw), d["mag"], d["ang"], None, d["theta"], gh["dz_re"], gh["dz_im"],
+                    conv_w=d["conv_w"], conv_b=d["conv_b"], scan_in=scan_in, tail_in=tail_in, dscan_out=dscan_out,
+                    dtail_out=dtail_out, valve=valve, ret=ret, ret_bias=bias)
+    g["dhconv_w"] = gh["dw"]
+    names = dict(mag="dmag", ang="dang", theta="dtheta", conv_w="dconv_w", conv_b="dconv_b", valve="dvalve", ret="dret",
+                 scan_in="dscan_in", tail_in="dtail_in", hconv_w="dhconv_w")
+    r2 = rng_(982)
+    for name, gname in names.items():
+        arr, grad = arrs[name], g[gname]
+        assert grad.shape == arr.shape, name
+        for fl in r2.permutation(arr.size)[:6]:
+            idx = np.unravel_index(fl, arr.shape)
+
+            def at(h):
+                a2 = dict(arrs)
+                a2[name] = arr.copy()
+                a2[name][idx] += h
+                return loss(a2)
+            h = 2.0 ** -7
+            num = (4 * (at(h / 2) - at(-h / 2)) / h - (at(h) - at(-h)) / (2 * h)) / 3
+            assert abs(num - grad[idx]) <= 3e-7 * max(1.0, abs(num)), (name, idx, num, grad[idx])
+    # the biases' gradient is the sum of their channel's upstream gradients
+    np.testing.assert_allclose(gh["dbias"], up.reshape(2, B, L, H, F).sum(axis=(1, 2, 4)), rtol=1e-12)
+
+
 # ------------------------------------------------------------------------- per-head valve (mode 1)
 def np_sigmoid(v):
     return 1.0 / (1.0 + np.exp(-v))
