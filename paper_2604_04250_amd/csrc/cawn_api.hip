@@ -76,10 +76,18 @@ static int valve_groups(const cawn_desc *d) { return d->H * (d->F >= 32 ? d->F /
 // gate_mode 1: dvalve[b][t][h] = sig (1 - sig) * (sum over the head's groups of vpart[b][g][t]),
 // sig = sigmoid(valve - 3): the straight-through gradient of Sec. 3.3.  One thread per (b, h, t),
 // t fastest; the groups of a head are summed in index order.  valve == nullptr: the plain sum (the
-// retention logits' gradient, whose terms already carry their sigmoid factor per lane).
+// retention logits' gradient, whose terms already carry their sigmoid factor per lane).  One launch serves
+// both logit gradients of a call: blockIdx.y = 1 works on the second set of arguments.
 __global__ void valve_reduce_kernel(const float *__restrict__ vpart, const float *__restrict__ valve,
-                                    float *__restrict__ dvalve, int B, int L, int H, int G)
+                                    float *__restrict__ dvalve, const float *__restrict__ vpart1,
+                                    const float *__restrict__ valve1, float *__restrict__ dvalve1, int B, int L, int H,
+                                    int G)
 {
+    if (blockIdx.y == 1) {
+        vpart = vpart1;
+        valve = valve1;
+        dvalve = dvalve1;
+    }
     const long long n = (long long)B * H * L;
     const int gph = G / H;       // groups per head
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long long)gridDim.x * blockDim.x) {
@@ -281,15 +289,20 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
 
 // Harmonic convolution (Sec. 3.6): its taps and biases belong to a (plane, head) channel, so the per-lane sums
 // hpart [8][J] (rows: plane-0 taps 0..2, plane-1 taps 0..2, plane-0 bias, plane-1 bias) are summed over the F
-// lanes of each head, in lane order (one thread per output: the association is fixed).
-__global__ void hconv_grad_reduce_kernel(const float *__restrict__ hpart, float *__restrict__ dw, float *__restrict__ db,
-                                         int H, int F, int J, int accumulate)
+// lanes of each head by one wave per output: lane l adds the head's lanes l, l + 64, ... in ascending order, then
+// the 64 sums meet in a butterfly of lane exchanges (both partners of an exchange add the same two values, so
+// every lane ends with the same bits): the association is fixed, the result repeatable.
+__global__ __launch_bounds__(64) void hconv_grad_reduce_kernel(const float *__restrict__ hpart, float *__restrict__ dw,
+                                                               float *__restrict__ db, int H, int F, int J, int accumulate)
 {
-    const int n = HC_PART_ROWS * H;
-    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < n; e += gridDim.x * blockDim.x) {
-        const int q = e / H, h = e % H;
-        float s = 0.0f;
-        for (int k = 0; k < F; ++k) s += hpart[(size_t)q * J + (size_t)h * F + k];
+    const int e = blockIdx.x;        // (row, head)
+    const int q = e / H, h = e % H;
+    const float *src = hpart + (size_t)q * J + (size_t)h * F;
+    float s = 0.0f;
+    for (int k = threadIdx.x; k < F; k += 64) s += src[k];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (threadIdx.x == 0) {
         float *dst = q < 6 ? (dw ? dw + ((size_t)(q / 3) * H + h) * 3 + q % 3 : nullptr)
                            : (db ? db + (size_t)(q - 6) * H + h : nullptr);
         if (dst) *dst = accumulate ? *dst + s : s;
@@ -736,23 +749,19 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
         if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
         if (hc && (dhconv_w || dhconv_b)) {
             const int n = HC_PART_ROWS * d->H;
-            hipLaunchKernelGGL(hconv_grad_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, hpart, dhconv_w,
+            hipLaunchKernelGGL(hconv_grad_reduce_kernel, dim3((unsigned)n), dim3(64), 0, s, hpart, dhconv_w,
                                dhconv_b, d->H, d->F, (int)J, d->accumulate_param_grads);
             if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
         }
     }
-    if (a.vpart) {
+    if (a.vpart || a.rpart) {       // the logit gradients: one launch for both
         const long long n = (long long)d->B * d->H * d->L;
         const long long nb = (n + 255) / 256;
-        hipLaunchKernelGGL(valve_reduce_kernel, dim3((unsigned)(nb < 4096 ? nb : 4096)), dim3(256), 0, s, a.vpart,
-                           valve, dvalve, d->B, d->L, d->H, a.G);
-        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
-    }
-    if (a.rpart) {
-        const long long n = (long long)d->B * d->H * d->L;
-        const long long nb = (n + 255) / 256;
-        hipLaunchKernelGGL(valve_reduce_kernel, dim3((unsigned)(nb < 4096 ? nb : 4096)), dim3(256), 0, s, a.rpart,
-                           static_cast<const float *>(nullptr), dret, d->B, d->L, d->H, a.G);
+        const float *none = nullptr;
+        const bool both = a.vpart && a.rpart;
+        hipLaunchKernelGGL(valve_reduce_kernel, dim3((unsigned)(nb < 4096 ? nb : 4096), both ? 2u : 1u), dim3(256), 0, s,
+                           a.vpart ? a.vpart : a.rpart, a.vpart ? valve : none, a.vpart ? dvalve : dret, a.rpart, none, dret,
+                           d->B, d->L, d->H, a.G);
         if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
     }
     return CAWN_OK;
