@@ -76,21 +76,15 @@ static int valve_groups(const cawn_desc *d) { return d->H * (d->F >= 32 ? d->F /
 // gate_mode 1: dvalve[b][t][h] = sig (1 - sig) * (sum over the head's groups of vpart[b][g][t]),
 // sig = sigmoid(valve - 3): the straight-through gradient of Sec. 3.3.  One thread per (b, h, t),
 // t fastest; the groups of a head are summed in index order.  valve == nullptr: the plain sum (the
-// retention logits' gradient, whose terms already carry their sigmoid factor per lane).  One launch serves
-// both logit gradients of a call: blockIdx.y = 1 works on the second set of arguments.
-__global__ void valve_reduce_kernel(const float *__restrict__ vpart, const float *__restrict__ valve,
-                                    float *__restrict__ dvalve, const float *__restrict__ vpart1,
-                                    const float *__restrict__ valve1, float *__restrict__ dvalve1, int B, int L, int H,
-                                    int G)
+// retention logits' gradient, whose terms already carry their sigmoid factor per lane).  The calling
+// threads share the elements: thread `first` of `stride`.
+__device__ __forceinline__ void logit_reduce(const float *__restrict__ vpart, const float *__restrict__ valve,
+                                             float *__restrict__ dvalve, int B, int L, int H, int G, long long first,
+                                             long long stride)
 {
-    if (blockIdx.y == 1) {
-        vpart = vpart1;
-        valve = valve1;
-        dvalve = dvalve1;
-    }
     const long long n = (long long)B * H * L;
     const int gph = G / H;       // groups per head
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (long long)gridDim.x * blockDim.x) {
+    for (long long e = first; e < n; e += stride) {
         const int t = (int)(e % L);
         const long long r = e / L;
         const int h = (int)(r % H), b = (int)(r / H);
@@ -235,18 +229,17 @@ __global__ __launch_bounds__(256) void syntax_conv_kernel(const float *__restric
 // tile = chain * nLB + lb (chain = position-in-time * B + b).  Block = 32 lanes x 32 groups: group g
 // sums chains g, g+32, ... of its lane's block in increasing order, then the 32 sub-sums meet in LDS
 // and are added in index order -- the association is fixed, so results are bitwise repeatable.
-__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__restrict__ part, float *__restrict__ out0,
-                                                               float *__restrict__ out1, float *__restrict__ out2,
-                                                               float *__restrict__ out3, float *__restrict__ out4,
-                                                               int rows, int conv_k, int hc_row0, int J, int JB,
-                                                               int nLB, int chains, int accumulate)
+__device__ __forceinline__ void reduce_partials(const float *__restrict__ part, float *__restrict__ out0,
+                                                float *__restrict__ out1, float *__restrict__ out2,
+                                                float *__restrict__ out3, float *__restrict__ out4, int rows, int conv_k,
+                                                int hc_row0, int J, int JB, int nLB, int chains, int accumulate, int bx,
+                                                int row)
 {
-    // grid: (ceil(J/32), rows)
+    // one block per (32 lanes, row): bx, row
     constexpr int G = 32;
     __shared__ float sm[G][33];
     const int lane = threadIdx.x % 32, g = threadIdx.x / 32;
-    const int j = blockIdx.x * 32 + lane;
-    const int row = blockIdx.y;
+    const int j = bx * 32 + lane;
     float acc = 0.0f;
     if (j < J) {
         const int lb = j / JB, jj = j % JB;
@@ -285,6 +278,30 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float *__re
         }
         if (dst) *dst = accumulate ? *dst + s : s;
     }
+}
+
+// What follows the backward kernel, in one launch (each small launch costs 4-5 us on this chip whatever it
+// does): blocks [0, nbx * rows) sum the parameter partials, the blocks behind them share the logit gradients of
+// the valve and of the retention (nsets of them, nb blocks each).
+struct EpilogueArgs {
+    const float *part;
+    float *out0, *out1, *out2, *out3, *out4;
+    int rows, conv_k, hc_row0, J, JB, nLB, chains, accumulate, nbx;
+    const float *lpart[2], *logit[2];
+    float *lout[2];
+    int nsets, nb, B, L, H, G;
+};
+__global__ __launch_bounds__(1024) void bwd_epilogue_kernel(const EpilogueArgs p)
+{
+    const int nA = p.nbx * p.rows;
+    if ((int)blockIdx.x < nA) {
+        reduce_partials(p.part, p.out0, p.out1, p.out2, p.out3, p.out4, p.rows, p.conv_k, p.hc_row0, p.J, p.JB, p.nLB,
+                        p.chains, p.accumulate, (int)blockIdx.x % p.nbx, (int)blockIdx.x / p.nbx);
+        return;
+    }
+    const int bid = (int)blockIdx.x - nA, set = bid / p.nb, blk = bid % p.nb;
+    logit_reduce(p.lpart[set], p.logit[set], p.lout[set], p.B, p.L, p.H, p.G, (long long)blk * blockDim.x + threadIdx.x,
+                 (long long)p.nb * blockDim.x);
 }
 
 // Harmonic convolution (Sec. 3.6): its taps and biases belong to a (plane, head) channel, so the per-lane sums
@@ -740,29 +757,35 @@ static int bwd_impl(const cawn_desc *d, const float *mag, const float *ang, cons
     a.total_tiles = (uint32_t)tiles;
     a.dbg = reinterpret_cast<unsigned long long *>(ws + w.off_dbg);
     if (launch_bwd(a, kc, vec, s) != hipSuccess) return CAWN_ELAUNCH;
-    if (dgamma || dtheta || want_w || hc) {
-        const int rows = part_rows(kc, hc);
+    {
+        EpilogueArgs p{};
         float *hpart = reinterpret_cast<float *>(ws + w.off_hpart);
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((J + 31) / 32), rows), dim3(1024), 0, s, a.part,
-                           dgamma, dtheta, dconv_w, dconv_b, hpart, rows, kc > 0 ? kc : 1, hc ? 4 + 2 * kc : -1, (int)J,
-                           JB, nLB, d->B * w.nT, d->accumulate_param_grads);
-        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+        if (dgamma || dtheta || want_w || hc) {
+            p.rows = part_rows(kc, hc);
+            p.nbx = (int)((J + 31) / 32);
+        }
+        p.part = a.part;
+        p.out0 = dgamma; p.out1 = dtheta; p.out2 = dconv_w; p.out3 = dconv_b; p.out4 = hpart;
+        p.conv_k = kc > 0 ? kc : 1;
+        p.hc_row0 = hc ? 4 + 2 * kc : -1;
+        p.J = (int)J; p.JB = JB; p.nLB = nLB; p.chains = d->B * w.nT; p.accumulate = d->accumulate_param_grads;
+        if (a.vpart) { p.lpart[p.nsets] = a.vpart; p.logit[p.nsets] = valve; p.lout[p.nsets] = dvalve; ++p.nsets; }
+        if (a.rpart) { p.lpart[p.nsets] = a.rpart; p.logit[p.nsets] = nullptr; p.lout[p.nsets] = dret; ++p.nsets; }
+        const long long n = (long long)d->B * d->H * d->L;
+        const long long nb = (n + 1023) / 1024;
+        p.nb = p.nsets ? (int)(nb < 1024 ? nb : 1024) : 0;
+        p.B = d->B; p.L = d->L; p.H = d->H; p.G = a.G;
+        const unsigned blocks = (unsigned)(p.nbx * p.rows + p.nb * p.nsets);
+        if (blocks) {
+            hipLaunchKernelGGL(bwd_epilogue_kernel, dim3(blocks), dim3(1024), 0, s, p);
+            if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
+        }
         if (hc && (dhconv_w || dhconv_b)) {
-            const int n = HC_PART_ROWS * d->H;
-            hipLaunchKernelGGL(hconv_grad_reduce_kernel, dim3((unsigned)n), dim3(64), 0, s, hpart, dhconv_w,
+            const int nh = HC_PART_ROWS * d->H;
+            hipLaunchKernelGGL(hconv_grad_reduce_kernel, dim3((unsigned)nh), dim3(64), 0, s, hpart, dhconv_w,
                                dhconv_b, d->H, d->F, (int)J, d->accumulate_param_grads);
             if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
         }
-    }
-    if (a.vpart || a.rpart) {       // the logit gradients: one launch for both
-        const long long n = (long long)d->B * d->H * d->L;
-        const long long nb = (n + 255) / 256;
-        const float *none = nullptr;
-        const bool both = a.vpart && a.rpart;
-        hipLaunchKernelGGL(valve_reduce_kernel, dim3((unsigned)(nb < 4096 ? nb : 4096), both ? 2u : 1u), dim3(256), 0, s,
-                           a.vpart ? a.vpart : a.rpart, a.vpart ? valve : none, a.vpart ? dvalve : dret, a.rpart, none, dret,
-                           d->B, d->L, d->H, a.G);
-        if (hipGetLastError() != hipSuccess) return CAWN_ELAUNCH;
     }
     return CAWN_OK;
 }

@@ -279,7 +279,7 @@ __global__ __launch_bounds__(BwdGeom::NSEG *BwdLPR, CAWN_BWD_WAVES) void bwd_ker
     // (upstream gradients of tile (b_, tt_, lb_) into sDz: rows of J lanes, or J/2 words with bf16)
     auto stage_dz = [&](int b_, int tt_, int lb_, int wv, int nwv) {
         if (wave == NW - 1) {       // rows R_LR, R_LI, then R_PSEGB + 2, + 3 of the lane block: two loads of two rows
-            const int jl = lb_ * JB + (lane & (JB - 1));
+            [[maybe_unused]] const int jl = lb_ * JB + (lane & (JB - 1));
 #if defined(__HIP_DEVICE_COMPILE__)
             __builtin_amdgcn_global_load_lds(table + (size_t)(R_LR + (lane >> 5)) * Jp + jl, &sLam[0][0], 4, 0, 0);
             __builtin_amdgcn_global_load_lds(table + (size_t)(R_PSEGB + 2 + (lane >> 5)) * Jp + jl, &sLam[2][0], 4, 0, 0);

@@ -351,7 +351,7 @@ __device__ __forceinline__ void stage_rows(float *sU, const float *mag, const fl
     constexpr int NRT = TT + HALO;
     // rows whose segment fills a 128-byte line are streamed; half lines (bf16) keep the default policy, so that
     // the cache can serve the neighbouring lane block's half of the line
-    constexpr int POL = JB * 4 >= 128 ? DMA_STREAM : 0;
+    [[maybe_unused]] constexpr int POL = JB * 4 >= 128 ? DMA_STREAM : 0;
     constexpr int NRTP = staged_rows<TT, JB, HALO>();
     constexpr int LR = JB * 4 / LB;                // lanes per row
     if constexpr (LR <= 64) {
