@@ -199,3 +199,67 @@ def test_concat_layout_inputs_outputs_and_their_gradients(H, F, Kc):
     B, L = 2, 333
     d = _inputs(B, L, H, F, Kc, 2600 + H + F + Kc)
     _check(B, L, H, F, Kc, d, with_state=True, concat=True)
+
+
+@pytest.mark.parametrize("paper_modes", [False, True])
+def test_training_step_replayed_from_a_hip_graph_matches_eager(paper_modes):
+    """Forward (with checkpoints) and backward (every gradient) of one step captured in a HIP graph -- with the valve
+    and the retention: their kernels and the epilogue's logit sums as well; three replays with eager work and
+    synchronisation in between, each compared with the eager step bit for bit (same kernels, fixed summation
+    orders).  The eager step itself is held to the oracle by the parity tests."""
+    G = _gpu()
+    import torch
+    K = G.K
+    B, L, H, F, Kc = 2, 700, 2, 64, 3
+    J = H * F
+    d = _inputs(B, L, H, F, Kc, 990)
+    r = np.random.Generator(np.random.PCG64(991))
+    dev = G.dev
+    mag, ang, theta, cw, cb = (dev(d[k]) for k in ("mag", "ang", "theta", "conv_w", "conv_b"))
+    gamma = None if paper_modes else dev(d["gamma"])
+    valve = dev((-3.9 + 3.0 * r.standard_normal((B, L, H))).astype(np.float32)) if paper_modes else None
+    ret = dev((-2.0 + 1.5 * r.standard_normal((B, L, H))).astype(np.float32)) if paper_modes else None
+    rb = dev(np.linspace(3.0, 0.0, F).astype(np.float32)) if paper_modes else None
+    dz_re, dz_im = dev(d["dz_re"]), dev(d["dz_im"])
+    desc = K.make_desc(B, L, H, F, conv_k=Kc, amp_mode=1 if paper_modes else 0, gate_tau=0.1,
+                       gate_mode=1 if paper_modes else 0, ret_mode=1 if paper_modes else 0)
+    ws = G.Workspaces.get(desc)
+    new = lambda *s: torch.full(s, float("nan"), device=G.DEV)
+    z_re, z_im, dmag, dang = new(B, L, J), new(B, L, J), new(B, L, J), new(B, L, J)
+    ckpt = new(max(K.cawn_ckpt_bytes(desc) // 4, 1))
+    dgamma = None if paper_modes else new(J)
+    dtheta, dcw, dcb = new(J), new(2, J, Kc), new(2, J)
+    dvalve = new(B, L, H) if paper_modes else None
+    dret = new(B, L, H) if paper_modes else None
+    outs = [t for t in (z_re, z_im, dmag, dang, dgamma, dtheta, dcw, dcb, dvalve, dret) if t is not None]
+
+    def step():
+        if paper_modes:
+            K.check(K.cawn_phase_accumulate_ret_fwd(desc, mag, ang, valve, ret, rb, theta, cw, cb, None, z_re, z_im, None,
+                                                    ckpt, None, ws))
+            K.check(K.cawn_phase_accumulate_ret_bwd(desc, mag, ang, valve, ret, rb, theta, cw, cb, None, ckpt, dz_re, dz_im,
+                                                    None, dmag, dang, dvalve, dret, dtheta, dcw, dcb, None, ws))
+        else:
+            K.check(K.cawn_phase_accumulate_fwd(desc, mag, ang, gamma, theta, cw, cb, None, z_re, z_im, None, ckpt, None,
+                                                ws))
+            K.check(K.cawn_phase_accumulate_bwd(desc, mag, ang, gamma, theta, cw, cb, None, ckpt, dz_re, dz_im, None, dmag,
+                                                dang, dgamma, dtheta, dcw, dcb, None, ws))
+
+    step()                                  # (the first call of a kernel asks the runtime how many workgroups fit)
+    torch.cuda.synchronize()
+    K.check(K.cawn_workspace_status(ws))
+    ref = [t.clone() for t in outs]
+    assert all(bool(torch.isfinite(t).all()) for t in ref)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(g, stream=side):
+        step()
+    for rep in range(3):
+        for t in outs:
+            t.fill_(float("nan"))           # eager work between the replays
+        ckpt.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(x, y) for x, y in zip(outs, ref)), f"replay {rep} differs from eager"
+    K.check(K.cawn_workspace_status(ws))
