@@ -203,3 +203,13 @@ def test_kernels_do_not_spill_and_keep_their_occupancy():
                     want = 4 if "bwd_kernel" in name else 2
                     assert int(val) >= want, (name, line)
     assert seen >= 35       # 5 tap counts x (forward, backward with/without parameters) x gate modes, short-call forward
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
