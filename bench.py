@@ -275,8 +275,7 @@ def run_workload(args, name, np, torch, K, WL, dev, ceiling, steps, warmup, head
         wl = wl.with_(chunk=args.chunk)
     B, H, F, J, Kc = wl.B, wl.H, wl.F, wl.J, wl.conv_k
     theta = K.cawn_theta_init(H, F)
-    # (the backward through the harmonic convolution exists for the threshold gate with constant retention: with the
-    # valve or data-dependent retention a training workload runs and times its forward pass alone)
+    # (the training workloads run forward + backward in every mode; the others time the forward)
     do_bwd = name in ("cfg3_train", "cfg5_wide", "cfg6_paper_heads")
     stream_mode = name == "cfg4_stream"
     L = wl.chunk if stream_mode else wl.L
