@@ -105,9 +105,12 @@ __global__ void fill_zero_kernel(uint32_t *p, size_t n)
         p[i] = 0u;
 }
 
-// One thread per lane: every per-lane constant the scan kernels need, formed in fp64.
+// Every per-lane constant the scan kernels need, formed in fp64.  One thread per (lane, slot): slot 0 writes the
+// lane's plain constants and taps, every other slot one power of lambda (an fp64 pow, sine and cosine each: one
+// thread per lane, working through all 26 of them in turn, took 24 us).
 // gamma == nullptr (data-dependent retention): the table is built with gamma = 1, i.e. its powers
 // are pure rotations, and row R_RBIAS receives the static retention bias b_k of the lane's harmonic.
+constexpr int LANE_TABLE_SLOTS = 3 + FwdGeom::NSEG + BwdGeom::NSEG;
 __global__ void lane_table_kernel(const float *__restrict__ gamma, const float *__restrict__ theta,
                                   const float *__restrict__ conv_w, const float *__restrict__ conv_b,
                                   const float *__restrict__ ret_bias, int F,
@@ -115,47 +118,41 @@ __global__ void lane_table_kernel(const float *__restrict__ gamma, const float *
                                   float *__restrict__ table, int J, int Jp, int conv_k)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int slot = blockIdx.y;
     if (j >= Jp) return;
     auto put = [&](int row, double v) { table[(size_t)row * Jp + j] = (float)v; };
     const bool live = j < J;
     const double g = live ? (gamma ? (double)gamma[j] : 1.0) : 0.0, th = live ? (double)theta[j] : 0.0;
+    auto power = [&](int n, double &re, double &im) {
+        const double m = n == 0 ? 1.0 : pow(g, (double)n);
+        re = m * cos(n * th);
+        im = m * sin(n * th);
+    };
+    if (slot == 1 || slot == 2) {       // lambda^(tile length) as a double-float: forward, backward
+        double tr, ti;
+        power(slot == 1 ? FwdGeom::TILE_T : BwdGeom::TILE_T, tr, ti);
+        const float hr = (float)tr, hi = (float)ti;
+        put(slot == 1 ? R_PT_HR : R_PTB_HR, hr);
+        put(slot == 1 ? R_PT_HI : R_PTB_HI, hi);
+        put(slot == 1 ? R_PT_LR : R_PTB_LR, tr - (double)hr);
+        put(slot == 1 ? R_PT_LI : R_PTB_LI, ti - (double)hi);
+        return;
+    }
+    if (slot >= 3) {                    // lambda^(segment start): forward segments, then backward segments
+        const bool fwd = slot - 3 < FwdGeom::NSEG;
+        const int sgi = fwd ? slot - 3 : slot - 3 - FwdGeom::NSEG;
+        double re, im;
+        power(sgi * (fwd ? FwdGeom::NSTEP : BwdGeom::NSTEP), re, im);
+        put((fwd ? R_PSEG : R_PSEGB) + 2 * sgi, re);
+        put((fwd ? R_PSEG : R_PSEGB) + 2 * sgi + 1, im);
+        return;
+    }
     const double c = cos(th), s = sin(th);
     put(R_LR, g * c);
     put(R_LI, g * s);
     put(R_COS, c);
     put(R_SIN, s);
     put(R_GAMMA, g);
-    auto power = [&](int n, double &re, double &im) {
-        const double m = n == 0 ? 1.0 : pow(g, (double)n);
-        re = m * cos(n * th);
-        im = m * sin(n * th);
-    };
-    double tr, ti;
-    float hr, hi;
-    power(FwdGeom::TILE_T, tr, ti);
-    hr = (float)tr; hi = (float)ti;
-    put(R_PT_HR, hr);
-    put(R_PT_HI, hi);
-    put(R_PT_LR, tr - (double)hr);
-    put(R_PT_LI, ti - (double)hi);
-    power(BwdGeom::TILE_T, tr, ti);
-    hr = (float)tr; hi = (float)ti;
-    put(R_PTB_HR, hr);
-    put(R_PTB_HI, hi);
-    put(R_PTB_LR, tr - (double)hr);
-    put(R_PTB_LI, ti - (double)hi);
-    for (int sgi = 0; sgi < FwdGeom::NSEG; ++sgi) {
-        double re, im;
-        power(sgi * FwdGeom::NSTEP, re, im);
-        put(R_PSEG + 2 * sgi, re);
-        put(R_PSEG + 2 * sgi + 1, im);
-    }
-    for (int sgi = 0; sgi < BwdGeom::NSEG; ++sgi) {
-        double re, im;
-        power(sgi * BwdGeom::NSTEP, re, im);
-        put(R_PSEGB + 2 * sgi, re);
-        put(R_PSEGB + 2 * sgi + 1, im);
-    }
     put(R_RBIAS, live && ret_bias ? (double)ret_bias[j % F] : 0.0);
     put(R_BIAS_M, live && conv_b && conv_k > 0 ? (double)conv_b[j] : 0.0);
     put(R_BIAS_A, live && conv_b && conv_k > 0 ? (double)conv_b[(size_t)J + j] : 0.0);
@@ -364,7 +361,7 @@ static hipError_t build_table(const cawn_desc *d, const WsLayout &w, char *ws, c
 {
     float *table = reinterpret_cast<float *>(ws + w.off_table);
     const int threads = 128;
-    hipLaunchKernelGGL(lane_table_kernel, dim3((w.Jp + threads - 1) / threads), dim3(threads), 0, s,
+    hipLaunchKernelGGL(lane_table_kernel, dim3((w.Jp + threads - 1) / threads, LANE_TABLE_SLOTS), dim3(threads), 0, s,
                        gamma, theta, conv_w, conv_b, ret_bias, d->F, hconv_w, hconv_b, table, w.J, w.Jp, d->conv_k);
     return hipGetLastError();
 }
