@@ -45,12 +45,19 @@ def build(verbose: bool = False, defines=(), out: str = OUT, objdir: str = CSRC)
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
-        report, rest, in_remark = [], [], False
+        report, rest, in_remark, held = [], [], False, []
         for line in r.stderr.splitlines():
+            if line.startswith("In file included from"):
+                held.append(line)       # the include chain in front of a diagnostic: kept only if that is no remark
+                continue
             if "[-Rpass-analysis=kernel-resource-usage]" in line:
                 report.append(line)
                 in_remark = True
-            elif in_remark and line.lstrip()[:1].isdigit() is False and "|" in line[:12] or \
+                held = []
+                continue
+            rest += held
+            held = []
+            if in_remark and line.lstrip()[:1].isdigit() is False and "|" in line[:12] or \
                     in_remark and line.lstrip().split(" ", 1)[0].isdigit() and "|" in line[:12]:
                 pass            # the source excerpt and caret under a remark
             else:
